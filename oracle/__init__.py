@@ -1,0 +1,153 @@
+"""TEST INFRASTRUCTURE: ctypes front end of the float64 CPU oracle (oracle/s2v_oracle.c).
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this package.
+It is independent of the HIP library: it shares no code with it and neither imports
+the other.  Inputs are numpy arrays; float inputs of any precision are widened to
+float64 before the C code sees them.
+
+Functions mirror the C entry points: embed (Eq. 1 / Alg. 1), q_scores (Eq. 2 / Alg. 2),
+select (Alg. 3's argmax and the top-d selection of Sec. 4.5.1), loss_grad (the Train
+step of Alg. 4) and sgd (plain gradient descent, repeated as in Sec. 4.5.2).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "s2v_oracle.c")
+_LIB = os.path.join(_HERE, "libs2v_oracle.so")
+
+THETA_NAMES = ("theta1", "theta2", "theta3", "theta4", "theta5", "theta6", "theta7")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2 + OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"], cwd=_HERE
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+    return _lib
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _th(theta: dict):
+    return [_f64(theta[k]) for k in THETA_NAMES]
+
+
+def embed(rowptr, colidx, w, theta: dict, x, T: int, history: bool = False):
+    """mu^T as [n][p] float64 (and mu^1..mu^T as [T][n][p] when history is set)."""
+    lib = _load()
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    n = rowptr.shape[0] - 1
+    th = _th(theta)
+    p = th[0].shape[0]
+    wd = None if w is None else _f64(w)
+    xd = _f64(x).reshape(-1)
+    assert xd.shape[0] == n
+    mu = np.zeros((n, p), dtype=np.float64)
+    hist = np.zeros((T, n, p), dtype=np.float64) if history else None
+    rc = lib.oracle_embed(
+        ctypes.c_int32(n), _ptr(rowptr), _ptr(colidx), _ptr(wd), ctypes.c_int32(p), ctypes.c_int32(T),
+        _ptr(th[0]), _ptr(th[1]), _ptr(th[2]), _ptr(th[3]), _ptr(xd), _ptr(mu), _ptr(hist),
+    )
+    assert rc == 0
+    return (mu, hist) if history else mu
+
+
+def q_scores(graph_off, theta: dict, mu):
+    """(gsum [G][p], q [n]) for a block-diagonal batch; graph_off None means one graph."""
+    lib = _load()
+    mu = _f64(mu)
+    n, p = mu.shape
+    th = _th(theta)
+    go = None if graph_off is None else _i32(graph_off)
+    G = 1 if go is None else go.shape[0] - 1
+    gsum = np.zeros((G, p), dtype=np.float64)
+    q = np.zeros(n, dtype=np.float64)
+    rc = lib.oracle_q(ctypes.c_int32(n), ctypes.c_int32(G), _ptr(go), ctypes.c_int32(p),
+                      _ptr(th[4]), _ptr(th[5]), _ptr(th[6]), _ptr(mu), _ptr(gsum), _ptr(q))
+    assert rc == 0
+    return gsum, q
+
+
+def select(graph_off, q, x, cand, k: int):
+    """(idx [G][k] int32, val [G][k] float64, count [G] int32)."""
+    lib = _load()
+    q = _f64(q)
+    n = q.shape[0]
+    xd = _f64(x).reshape(-1)
+    go = None if graph_off is None else _i32(graph_off)
+    G = 1 if go is None else go.shape[0] - 1
+    cd = None if cand is None else np.ascontiguousarray(cand, dtype=np.uint8)
+    idx = np.zeros((G, k), dtype=np.int32)
+    val = np.zeros((G, k), dtype=np.float64)
+    cnt = np.zeros(G, dtype=np.int32)
+    rc = lib.oracle_select(ctypes.c_int32(n), ctypes.c_int32(G), _ptr(go), _ptr(q), _ptr(xd), _ptr(cd),
+                           ctypes.c_int32(k), _ptr(idx), _ptr(val), _ptr(cnt))
+    assert rc == 0
+    return idx, val, cnt
+
+
+def loss_grad(rowptr, colidx, w, graph_off, theta: dict, x, T: int, action, target):
+    """(loss, q_pred [S], grads dict) for the squared loss averaged over the S states."""
+    lib = _load()
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    n = rowptr.shape[0] - 1
+    th = _th(theta)
+    p = th[0].shape[0]
+    wd = None if w is None else _f64(w)
+    xd = _f64(x).reshape(-1, n)
+    S = xd.shape[0]
+    go = None if graph_off is None else _i32(graph_off)
+    G = 1 if go is None else go.shape[0] - 1
+    act = _i32(action)
+    tgt = _f64(target)
+    assert act.shape[0] == S and tgt.shape[0] == S
+    loss = np.zeros(1, dtype=np.float64)
+    qp = np.zeros(S, dtype=np.float64)
+    grads = [np.zeros_like(t) for t in th]
+    rc = lib.oracle_loss_grad(
+        ctypes.c_int32(n), _ptr(rowptr), _ptr(colidx), _ptr(wd), ctypes.c_int32(G), _ptr(go),
+        ctypes.c_int32(p), ctypes.c_int32(T), *[_ptr(t) for t in th], ctypes.c_int32(S), _ptr(xd),
+        _ptr(act), _ptr(tgt), _ptr(loss), _ptr(qp), *[_ptr(g) for g in grads],
+    )
+    assert rc == 0, rc
+    return float(loss[0]), qp, dict(zip(THETA_NAMES, grads))
+
+
+def sgd(theta: dict, grads: dict, lr: float) -> dict:
+    """theta - lr * grad for every parameter, in float64."""
+    lib = _load()
+    out = {}
+    for k in THETA_NAMES:
+        t = _f64(theta[k]).copy()
+        g = _f64(grads[k])
+        lib.oracle_sgd(ctypes.c_int64(t.size), _ptr(t), _ptr(g), ctypes.c_double(lr))
+        out[k] = t
+    return out
