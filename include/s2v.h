@@ -1,0 +1,194 @@
+/*
+ * s2v.h -- C interface of the MI355X (gfx950) structure2vec / deep-Q hot-path library.
+ *
+ * The library evaluates the policy model of OpenGraphGym-MG (arXiv 2105.08764) on one
+ * GPU: the structure2vec graph embedding (Eq. 1 / Alg. 1), the action-evaluation
+ * scores (Eq. 2 / Alg. 2), node selection (Alg. 3's argmax and the top-d rule of
+ * Sec. 4.5.1), and the training step's backward pass and parameter update (the Train
+ * function of Alg. 4, repeated as in Sec. 4.5.2).
+ *
+ * Parameter numbering.  This interface uses the structure2vec numbering; the paper
+ * renumbers the same seven tensors:
+ *     here    role                                   shape   paper's name
+ *     theta1  weight of the node feature x_v         [p]     theta1
+ *     theta2  weight of the neighbour-embedding sum  [p][p]  theta4
+ *     theta3  outer weight of the edge term          [p][p]  theta3
+ *     theta4  lift of the edge weight (inside relu)  [p]     theta2
+ *     theta5  output vector of the score             [2p]    theta7
+ *     theta6  weight of the graph sum in the score   [p][p]  theta5
+ *     theta7  weight of the node's own embedding     [p][p]  theta6
+ * 4p^2 + 4p values in total (Sec. 5.1 item 3).  Matrices are row-major [out][in] and
+ * act on column vectors, y = theta * v, as Eq. 1 and Eq. 2 are written.
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller (allocated and freed by
+ *     the caller) unless the comment says "host".  The structs themselves are host
+ *     memory.  The library allocates no device memory: scratch space comes from the
+ *     caller's workspace `ws`, sized by s2v_workspace_bytes.
+ *   - Work is enqueued on the HIP stream given to s2v_create and the call returns
+ *     without waiting for it (s2v_graph_prepare is the exception: it waits).  Scalar
+ *     results (loss, counts) are written to device memory.
+ *   - Every call returns an int32 status: S2V_OK or a negative S2V_ERR_* code.  Nothing
+ *     throws, prints or exits.  A call that returns an error has enqueued nothing.
+ *   - Layouts: x is [S][N]; embeddings are [N][S][p] (S states of one graph batch;
+ *     S == 1 gives [N][p]); saved activations [T][N][S][p]; scores [S][N];
+ *     graph sums [S][G][p].  N * S must be below 2^31.
+ *   - Supported embedding sizes: p = 32 or 64.
+ *   - Calls on one context must not overlap in time on different host threads, and two
+ *     calls that share a workspace must run on the same stream.
+ */
+#ifndef S2V_H
+#define S2V_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define S2V_OK 0
+#define S2V_ERR_INVALID_ARG (-1)         /* null pointer, negative size, inconsistent shapes */
+#define S2V_ERR_UNSUPPORTED (-2)         /* p not in {32, 64}; (G > 1 and k > 1) in selection */
+#define S2V_ERR_WORKSPACE_TOO_SMALL (-3) /* ws_bytes below what s2v_workspace_bytes reports */
+#define S2V_ERR_HIP (-4)                 /* a HIP call failed; see s2v_last_hip_error */
+#define S2V_ERR_NO_DEVICE (-5)           /* no usable GPU in this process */
+#define S2V_ERR_NOT_PREPARED (-6)        /* s2v_graph_prepare has not run for this graph + workspace */
+
+typedef struct s2v_ctx s2v_ctx;
+
+/*
+ * A graph, or a block-diagonal batch of G independent graphs (the paper stacks B graphs,
+ * Sec. 4.1; here they need not have equal size).  The adjacency matrix A of Sec. 4.1 is
+ * held as a symmetric CSR pattern: every undirected edge {u,v} appears in row u and in
+ * row v.  The neighbourhood N(v) of Eq. 1 is exactly the stored entries of row v.
+ * Symmetry, sortedness and the absence of duplicates are the caller's promise; they are
+ * not checked.  Column indices must lie in [0, n_nodes).
+ */
+typedef struct {
+    int32_t n_nodes;          /* N >= 0 */
+    int64_t nnz;              /* stored entries = 2 * undirected edges */
+    const int32_t *rowptr;    /* device [N+1], rowptr[0] == 0, rowptr[N] == nnz */
+    const int32_t *colidx;    /* device [nnz] */
+    const float *w;           /* device [nnz] edge weights W(v,u) of Eq. 1, or NULL = all 1.0 */
+    int32_t n_graphs;         /* G >= 1 */
+    const int32_t *graph_off; /* device [G+1] ascending node offsets (0 .. N), or NULL when G == 1 */
+} s2v_graph;
+
+/* The seven parameter tensors (device pointers), also used for their gradients. */
+typedef struct {
+    int32_t p;
+    float *theta1; /* [p]    */
+    float *theta2; /* [p][p] */
+    float *theta3; /* [p][p] */
+    float *theta4; /* [p]    */
+    float *theta5; /* [2p]: [0:p] pairs with the graph term, [p:2p] with the node term */
+    float *theta6; /* [p][p] */
+    float *theta7; /* [p][p] */
+} s2v_params;
+
+/* Text for a status code (host string, never NULL). */
+const char *s2v_status_str(int32_t status);
+
+/*
+ * Create a context bound to a HIP stream (`hip_stream` is a hipStream_t passed as void*;
+ * NULL is the default stream) on the current device.  Host memory only.
+ * Errors: S2V_ERR_INVALID_ARG (out == NULL), S2V_ERR_NO_DEVICE.
+ */
+int32_t s2v_create(void *hip_stream, s2v_ctx **out);
+int32_t s2v_destroy(s2v_ctx *ctx);
+/* hipError_t value of the last failed HIP call seen by this context (0 if none). */
+int32_t s2v_last_hip_error(const s2v_ctx *ctx);
+
+/*
+ * Bytes of workspace that every call below needs for this graph shape (only n_nodes,
+ * nnz and n_graphs of `g` are read) with embedding size p, T rounds, S states and at
+ * most k_max selected nodes per call.  `training` non-zero includes the scratch of
+ * s2v_embed_bwd (two [N][S][p] buffers and the partial-gradient tables); leave it zero
+ * for inference.  `out` is a host pointer.
+ */
+int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t T, int32_t S,
+                            int32_t k_max, int32_t training, size_t *out);
+
+/*
+ * One-time pass over a graph: the round-invariant part of Eq. 1's third term (Alg. 1
+ * computes it once, before the layer loop).  Because relu(theta4_k * w) equals
+ * relu(theta4_k) * max(w,0) + relu(-theta4_k) * max(-w,0), the sum over a row needs only
+ * the two per-node scalars  s+_v = sum_u max(W(v,u),0)  and  s-_v = sum_u max(-W(v,u),0),
+ * which are stored at the head of `ws` together with the reduction chunk table.  The head
+ * of `ws` must stay untouched for as long as the graph is used with that workspace; the
+ * other calls use the rest as scratch.  Reads graph_off back to the host, so this call
+ * waits for the stream.  Call again if the graph's arrays change.
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, HIP.
+ */
+int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_bytes);
+
+/*
+ * Graph embedding, Eq. 1 / Alg. 1, for S states x[s][.] of the same graph batch:
+ *   mu^0 = 0;  mu^{t+1}_v = relu(theta1 x_v + theta2 sum_{u in N(v)} mu^t_u
+ *                                + theta3 sum_{u in N(v)} relu(theta4 W(v,u))),  t = 0..T-1.
+ * The neighbour sum is unweighted, as Eq. 1 writes it.
+ *   x        [S][N]  node feature (the partial-solution indicator S of Sec. 4.1; any float)
+ *   mu_out   [N][S][p]  mu^T; may be NULL when mu_saved is given
+ *   mu_saved [T][N][S][p] receives mu^1..mu^T (needed by s2v_embed_bwd), or NULL
+ *   gsum     [S][G][p]  per-graph sum of mu^T over ALL nodes of the graph (Alg. 2 line 4),
+ *                       or NULL to skip it
+ * T >= 1, S >= 1.  Errors: INVALID_ARG, UNSUPPORTED, NOT_PREPARED, WORKSPACE_TOO_SMALL, HIP.
+ */
+int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                      int32_t S, float *mu_out, float *mu_saved, float *gsum, void *ws, size_t ws_bytes);
+
+/*
+ * Action-evaluation scores, Eq. 2 / Alg. 2, for EVERY node (candidates are filtered at
+ * selection, not here):
+ *   Q_v = theta5[0:p] . relu(theta6 g_b) + theta5[p:2p] . relu(theta7 mu_v),  b = graph of v.
+ *   mu [N][S][p], gsum [S][G][p] (from s2v_embed_fwd), q [S][N] (output).
+ */
+int32_t s2v_q_score(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *mu,
+                    const float *gsum, int32_t S, float *q, void *ws, size_t ws_bytes);
+
+/*
+ * Node selection for one state: per graph, the k candidates with the highest scores,
+ * ordered by score descending and node index ascending among equal scores (k == 1 is
+ * the argmax of Alg. 3 line 7; k > 1 is the top-d selection of Sec. 4.5.1).
+ *   q     [N] scores;  x [N] node feature
+ *   cand  [N] bytes, non-zero = candidate (the set C of Sec. 4.1), or NULL = nodes with x == 0
+ *   idx   [G][k] selected node ids (global numbering), -1 in unused slots
+ *   val   [G][k] their scores, -inf in unused slots
+ *   count [G]    min(k, number of candidates of the graph)
+ * Scores must not be NaN; -0.0 and +0.0 compare equal.
+ * Supported: (G >= 1, k == 1) and (G == 1, k >= 1); otherwise S2V_ERR_UNSUPPORTED.
+ */
+int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const float *x, const uint8_t *cand,
+                        int32_t k, int32_t *idx, float *val, int32_t *count, void *ws, size_t ws_bytes);
+
+/*
+ * Backward pass of the training step (Train of Alg. 4: forward = Alg. 1 then Alg. 2, then
+ * back-propagation) for the squared loss averaged over the S states,
+ *   L = (1/S) sum_b (Q^{(b)}(action_b) - target_b)^2,
+ * through Eq. 2 at the action nodes and all T rounds of Eq. 1 (the adjoint of the
+ * neighbour sum is the same sum because the pattern is symmetric).  relu'(0) = 0.
+ *   mu_saved [T][N][S][p] and gsum [S][G][p] from s2v_embed_fwd with the same x, T, S
+ *   action [S] node ids, target [S]
+ *   loss   [1] output;  q_pred [S] output (Q of each action node), may be NULL
+ *   grads  gradient of L w.r.t. theta1..theta7 (overwritten; grads->p must equal params->p)
+ */
+int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                      int32_t S, const float *mu_saved, const float *gsum, const int32_t *action,
+                      const float *target, float *loss, float *q_pred, s2v_params *grads, void *ws,
+                      size_t ws_bytes);
+
+/* Plain gradient descent on all seven tensors: theta <- theta - lr * grad (Sec. 4.5.2 repeats
+ * forward, backward and this update several times on one minibatch). */
+int32_t s2v_sgd_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, float lr);
+
+/*
+ * Host helper: the adaptive number of nodes to select per policy evaluation (Sec. 4.5.1):
+ * 8 if |C| > N/2, 4 if N/4 < |C| <= N/2, 2 if N/8 < |C| <= N/4, else 1.  Returns d >= 1.
+ */
+int32_t s2v_adaptive_d(int64_t n_candidates, int64_t n_nodes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S2V_H */

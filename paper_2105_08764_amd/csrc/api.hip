@@ -1,0 +1,485 @@
+// C interface of libs2v.so: argument checks, workspace layout and the order of kernel launches.
+// See include/s2v.h for the contract of every entry point.
+#include <new>
+#include <vector>
+
+#include "../../include/s2v.h"
+#include "internal.h"
+
+using namespace s2v;
+
+namespace {
+
+struct Prepared {
+    const void *ws;
+    const int32_t *rowptr;
+    const int32_t *colidx;
+    int32_t N;
+    int64_t nnz;
+    int32_t G;
+    int32_t n_chunks;
+};
+
+// Carves consecutive 256-byte aligned pieces out of a byte range.
+struct Carver {
+    size_t off;
+    explicit Carver(size_t start) : off(align_up(start)) {}
+    size_t take(size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes);
+        return at;
+    }
+};
+
+struct HeadLayout {
+    size_t s_pos, s_neg, chunk_begin, chunk_end, chunk_graph, graph_chunk_off, end;
+    int max_chunks;
+};
+
+HeadLayout head_layout(int64_t N, int64_t G) {
+    HeadLayout h;
+    h.max_chunks = (int)((N + kChunkNodes - 1) / kChunkNodes + G);
+    Carver c(0);
+    h.s_pos = c.take(sizeof(float) * N);
+    h.s_neg = c.take(sizeof(float) * N);
+    h.chunk_begin = c.take(sizeof(int32_t) * h.max_chunks);
+    h.chunk_end = c.take(sizeof(int32_t) * h.max_chunks);
+    h.chunk_graph = c.take(sizeof(int32_t) * h.max_chunks);
+    h.graph_chunk_off = c.take(sizeof(int32_t) * (G + 1));
+    h.end = c.off;
+    return h;
+}
+
+struct FwdLayout { size_t qvec, tmp, gpart, end; };
+FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp) {
+    FwdLayout f;
+    Carver c(h.end);
+    f.qvec = c.take(sizeof(float) * 2 * p);
+    f.gpart = c.take(sizeof(float) * (size_t)h.max_chunks * S * p);
+    f.tmp = c.take(need_tmp ? sizeof(float) * (size_t)N * S * p : 0);
+    f.end = c.off;
+    return f;
+}
+
+struct QLayout { size_t qa, end; };
+QLayout q_layout(const HeadLayout &h, int S, int G) {
+    QLayout q;
+    Carver c(h.end);
+    q.qa = c.take(sizeof(float) * (size_t)S * G);
+    q.end = c.off;
+    return q;
+}
+
+struct SelLayout { size_t part_val, part_idx, hist, state, blk, keys0, keys1, ids0, ids1, sort_cnt, end; };
+SelLayout sel_layout(const HeadLayout &h, int64_t N, int64_t k) {
+    SelLayout s;
+    Carver c(h.end);
+    const size_t n_scan_blk = (size_t)((N + kScanBlock - 1) / kScanBlock);
+    const size_t n_sort_blk = (size_t)((k + kSortTile - 1) / kSortTile);
+    s.part_val = c.take(sizeof(float) * h.max_chunks);
+    s.part_idx = c.take(sizeof(int32_t) * h.max_chunks);
+    s.hist = c.take(sizeof(uint32_t) * 4 * 256);
+    s.state = c.take(sizeof(uint32_t) * 16);
+    s.blk = c.take(sizeof(uint32_t) * 4 * n_scan_blk);
+    s.keys0 = c.take(sizeof(uint32_t) * k);
+    s.keys1 = c.take(sizeof(uint32_t) * k);
+    s.ids0 = c.take(sizeof(int32_t) * k);
+    s.ids1 = c.take(sizeof(int32_t) * k);
+    s.sort_cnt = c.take(sizeof(uint32_t) * 256 * n_sort_blk);
+    s.end = c.off;
+    return s;
+}
+
+struct BwdLayout {
+    size_t dg, da, glo, ghi, head_part, dz0, dz1, dc_part, d2_part, dvec, red_tmp, end;
+    int dc_rows, d2_rows;
+};
+BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
+    BwdLayout b;
+    Carver c(h.end);
+    b.dc_rows = kBwdHeadGrid + (T - 1) * kBwdGrid;
+    b.d2_rows = (T - 1) * kBwdGrid;
+    const size_t width = (size_t)(3 * p > p * p ? 3 * p : p * p);
+    const size_t segs = (size_t)(b.dc_rows + 63) / 64;
+    b.dg = c.take(sizeof(float) * (size_t)S * p);
+    b.da = c.take(sizeof(float) * (size_t)S * p);
+    b.glo = c.take(sizeof(int32_t) * S);
+    b.ghi = c.take(sizeof(int32_t) * S);
+    b.head_part = c.take(sizeof(float) * (size_t)S * (2 * p + 2 * p * p + 1));
+    b.dz0 = c.take(sizeof(float) * (size_t)N * S * p);
+    b.dz1 = c.take(T >= 2 ? sizeof(float) * (size_t)N * S * p : 0);
+    b.dc_part = c.take(sizeof(float) * (size_t)b.dc_rows * 3 * p);
+    b.d2_part = c.take(sizeof(float) * (size_t)b.d2_rows * p * p);
+    b.dvec = c.take(sizeof(float) * 3 * p);
+    b.red_tmp = c.take(sizeof(float) * segs * width);
+    b.end = c.off;
+    return b;
+}
+
+template <class T>
+T *at(void *ws, size_t off) {
+    return reinterpret_cast<T *>(static_cast<char *>(ws) + off);
+}
+
+bool p_supported(int p) { return p == 32 || p == 64; }
+
+}  // namespace
+
+struct s2v_ctx {
+    hipStream_t stream;
+    int32_t last_hip;
+    std::vector<Prepared> prepared;
+};
+
+namespace {
+
+int32_t hip_fail(s2v_ctx *ctx, hipError_t e) {
+    ctx->last_hip = (int32_t)e;
+    return S2V_ERR_HIP;
+}
+
+#define S2V_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_); \
+    } while (0)
+
+int32_t check_graph(const s2v_graph *g) {
+    if (!g) return S2V_ERR_INVALID_ARG;
+    if (g->n_nodes < 0 || g->nnz < 0 || g->n_graphs < 1) return S2V_ERR_INVALID_ARG;
+    if (g->nnz >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
+    if (!g->rowptr) return S2V_ERR_INVALID_ARG;
+    if (g->nnz > 0 && !g->colidx) return S2V_ERR_INVALID_ARG;
+    if (g->n_graphs > 1 && !g->graph_off) return S2V_ERR_INVALID_ARG;
+    return S2V_OK;
+}
+
+int32_t check_params(const s2v_params *t) {
+    if (!t) return S2V_ERR_INVALID_ARG;
+    if (!p_supported(t->p)) return S2V_ERR_UNSUPPORTED;
+    if (!t->theta1 || !t->theta2 || !t->theta3 || !t->theta4 || !t->theta5 || !t->theta6 || !t->theta7)
+        return S2V_ERR_INVALID_ARG;
+    return S2V_OK;
+}
+
+int32_t check_ws(const void *ws) {
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return S2V_ERR_INVALID_ARG;
+    return S2V_OK;
+}
+
+const Prepared *find_prepared(const s2v_ctx *ctx, const s2v_graph *g, const void *ws) {
+    for (const Prepared &pr : ctx->prepared)
+        if (pr.ws == ws && pr.rowptr == g->rowptr && pr.colidx == g->colidx && pr.N == g->n_nodes &&
+            pr.nnz == g->nnz && pr.G == g->n_graphs)
+            return &pr;
+    return nullptr;
+}
+
+ChunkTable chunk_table(void *ws, const HeadLayout &h, const Prepared &pr) {
+    ChunkTable ct;
+    ct.n_chunks = pr.n_chunks;
+    ct.chunk_begin = at<int32_t>(ws, h.chunk_begin);
+    ct.chunk_end = at<int32_t>(ws, h.chunk_end);
+    ct.chunk_graph = at<int32_t>(ws, h.chunk_graph);
+    ct.graph_chunk_off = at<int32_t>(ws, h.graph_chunk_off);
+    return ct;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *s2v_status_str(int32_t status) {
+    switch (status) {
+        case S2V_OK: return "ok";
+        case S2V_ERR_INVALID_ARG: return "invalid argument";
+        case S2V_ERR_UNSUPPORTED: return "unsupported configuration";
+        case S2V_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case S2V_ERR_HIP: return "HIP runtime error";
+        case S2V_ERR_NO_DEVICE: return "no usable GPU";
+        case S2V_ERR_NOT_PREPARED: return "graph not prepared with this workspace";
+        default: return "unknown status";
+    }
+}
+
+int32_t s2v_create(void *hip_stream, s2v_ctx **out) {
+    if (!out) return S2V_ERR_INVALID_ARG;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        return S2V_ERR_NO_DEVICE;
+    }
+    s2v_ctx *ctx = new (std::nothrow) s2v_ctx;
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->last_hip = 0;
+    *out = ctx;
+    return S2V_OK;
+}
+
+int32_t s2v_destroy(s2v_ctx *ctx) {
+    delete ctx;
+    return S2V_OK;
+}
+
+int32_t s2v_last_hip_error(const s2v_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t T, int32_t S, int32_t k_max,
+                            int32_t training, size_t *out) {
+    (void)ctx;
+    if (!g || !out || g->n_nodes < 0 || g->n_graphs < 1 || T < 1 || S < 1 || k_max < 0) return S2V_ERR_INVALID_ARG;
+    if (!p_supported(p)) return S2V_ERR_UNSUPPORTED;
+    if ((int64_t)g->n_nodes * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
+    const HeadLayout h = head_layout(g->n_nodes, g->n_graphs);
+    size_t need = fwd_layout(h, g->n_nodes, p, S, true).end;
+    const size_t q_end = q_layout(h, S, g->n_graphs).end;
+    const size_t s_end = sel_layout(h, g->n_nodes, k_max > 0 ? k_max : 1).end;
+    if (q_end > need) need = q_end;
+    if (s_end > need) need = s_end;
+    if (training) {
+        const size_t b_end = bwd_layout(h, g->n_nodes, p, T, S).end;
+        if (b_end > need) need = b_end;
+    }
+    *out = need;
+    return S2V_OK;
+}
+
+int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_bytes) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    int32_t rc = check_graph(g);
+    if (rc != S2V_OK) return rc;
+    rc = check_ws(ws);
+    if (rc != S2V_OK) return rc;
+    const int32_t N = g->n_nodes, G = g->n_graphs;
+    const HeadLayout h = head_layout(N, G);
+    if (ws_bytes < h.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
+
+    // graph offsets to the host: the chunk table is built here, once per graph
+    std::vector<int32_t> off(G + 1);
+    if (G > 1) {
+        S2V_TRY(hipMemcpyAsync(off.data(), g->graph_off, sizeof(int32_t) * (G + 1), hipMemcpyDeviceToHost, ctx->stream));
+        S2V_TRY(hipStreamSynchronize(ctx->stream));
+        if (off[0] != 0 || off[G] != N) return S2V_ERR_INVALID_ARG;
+        for (int b = 0; b < G; ++b)
+            if (off[b + 1] < off[b]) return S2V_ERR_INVALID_ARG;
+    } else {
+        off[0] = 0;
+        off[1] = N;
+    }
+    std::vector<int32_t> cb, ce, cg, gco(G + 1);
+    for (int b = 0; b < G; ++b) {
+        gco[b] = (int32_t)cb.size();
+        for (int32_t v = off[b]; v < off[b + 1]; v += kChunkNodes) {
+            cb.push_back(v);
+            ce.push_back(v + kChunkNodes < off[b + 1] ? v + kChunkNodes : off[b + 1]);
+            cg.push_back(b);
+        }
+    }
+    gco[G] = (int32_t)cb.size();
+    const int n_chunks = (int)cb.size();
+    if (n_chunks > h.max_chunks) return S2V_ERR_INVALID_ARG;
+    if (n_chunks > 0) {
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_begin), cb.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_end), ce.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_graph), cg.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
+    }
+    S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.graph_chunk_off), gco.data(), sizeof(int32_t) * (G + 1), hipMemcpyHostToDevice, ctx->stream));
+    S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg)));
+    S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
+
+    Prepared pr{ws, g->rowptr, g->colidx, N, g->nnz, G, n_chunks};
+    for (Prepared &old : ctx->prepared)
+        if (old.ws == ws) { old = pr; return S2V_OK; }
+    ctx->prepared.push_back(pr);
+    return S2V_OK;
+}
+
+int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                      int32_t S, float *mu_out, float *mu_saved, float *gsum, void *ws, size_t ws_bytes) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    int32_t rc = check_graph(g);
+    if (rc != S2V_OK) return rc;
+    rc = check_params(params);
+    if (rc != S2V_OK) return rc;
+    rc = check_ws(ws);
+    if (rc != S2V_OK) return rc;
+    if (T < 1 || S < 1 || (!mu_out && !mu_saved)) return S2V_ERR_INVALID_ARG;
+    const int32_t N = g->n_nodes, G = g->n_graphs, p = params->p;
+    if (N > 0 && !x) return S2V_ERR_INVALID_ARG;
+    if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(N, G);
+    const bool need_tmp = !mu_saved && T >= 2;
+    const FwdLayout f = fwd_layout(h, N, p, S, need_tmp);
+    if (ws_bytes < f.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t st = ctx->stream;
+    const float *s_pos = at<float>(ws, h.s_pos), *s_neg = at<float>(ws, h.s_neg);
+    float *qvec = at<float>(ws, f.qvec);
+    float *tmp = at<float>(ws, f.tmp);
+    const size_t nsp = (size_t)N * S * p;
+    S2V_TRY(launch_qvec(st, p, params->theta3, params->theta4, qvec));
+    // destination of round t (1-based): the saved slot, or ping-pong so that round T lands in mu_out
+    auto dest = [&](int t) -> float * {
+        if (mu_saved) return mu_saved + (size_t)(t - 1) * nsp;
+        return ((T - t) % 2 == 0) ? mu_out : tmp;
+    };
+    S2V_TRY(launch_round1(st, p, N, S, x, s_pos, s_neg, params->theta1, qvec, dest(1)));
+    for (int t = 2; t <= T; ++t)
+        S2V_TRY(launch_round(st, p, N, S, g->rowptr, g->colidx, dest(t - 1), dest(t), x, s_pos, s_neg,
+                             params->theta1, params->theta2, qvec));
+    float *muT = dest(T);
+    if (mu_saved && mu_out && mu_out != muT && nsp > 0)
+        S2V_TRY(hipMemcpyAsync(mu_out, muT, sizeof(float) * nsp, hipMemcpyDeviceToDevice, st));
+    if (gsum) {
+        const ChunkTable ct = chunk_table(ws, h, *pr);
+        S2V_TRY(launch_gsum(st, p, N, S, G, ct, muT, at<float>(ws, f.gpart), gsum));
+    }
+    return S2V_OK;
+}
+
+int32_t s2v_q_score(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *mu,
+                    const float *gsum, int32_t S, float *q, void *ws, size_t ws_bytes) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    int32_t rc = check_graph(g);
+    if (rc != S2V_OK) return rc;
+    rc = check_params(params);
+    if (rc != S2V_OK) return rc;
+    rc = check_ws(ws);
+    if (rc != S2V_OK) return rc;
+    if (S < 1 || !gsum) return S2V_ERR_INVALID_ARG;
+    const int32_t N = g->n_nodes, G = g->n_graphs, p = params->p;
+    if (N > 0 && (!mu || !q)) return S2V_ERR_INVALID_ARG;
+    if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
+    const HeadLayout h = head_layout(N, G);
+    const QLayout ql = q_layout(h, S, G);
+    if (ws_bytes < ql.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = ctx->stream;
+    float *qa = at<float>(ws, ql.qa);
+    S2V_TRY(launch_qa(st, p, S, G, params->theta5, params->theta6, gsum, qa));
+    S2V_TRY(launch_qnode(st, p, N, S, G, g->graph_off, params->theta5, params->theta7, mu, qa, q));
+    return S2V_OK;
+}
+
+int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const float *x, const uint8_t *cand,
+                        int32_t k, int32_t *idx, float *val, int32_t *count, void *ws, size_t ws_bytes) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    int32_t rc = check_graph(g);
+    if (rc != S2V_OK) return rc;
+    rc = check_ws(ws);
+    if (rc != S2V_OK) return rc;
+    if (k < 1 || !idx || !val || !count) return S2V_ERR_INVALID_ARG;
+    const int32_t N = g->n_nodes, G = g->n_graphs;
+    if (N > 0 && (!q || (!x && !cand))) return S2V_ERR_INVALID_ARG;
+    if (G > 1 && k > 1) return S2V_ERR_UNSUPPORTED;
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(N, G);
+    const SelLayout sl = sel_layout(h, N, k);
+    if (ws_bytes < sl.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
+    SelectScratch sc;
+    sc.part_val = at<float>(ws, sl.part_val);
+    sc.part_idx = at<int32_t>(ws, sl.part_idx);
+    sc.hist = at<uint32_t>(ws, sl.hist);
+    sc.state = at<uint32_t>(ws, sl.state);
+    sc.blk = at<uint32_t>(ws, sl.blk);
+    sc.keys[0] = at<uint32_t>(ws, sl.keys0);
+    sc.keys[1] = at<uint32_t>(ws, sl.keys1);
+    sc.ids[0] = at<int32_t>(ws, sl.ids0);
+    sc.ids[1] = at<int32_t>(ws, sl.ids1);
+    sc.sort_cnt = at<uint32_t>(ws, sl.sort_cnt);
+    if (k == 1) {
+        const ChunkTable ct = chunk_table(ws, h, *pr);
+        S2V_TRY(launch_argmax(ctx->stream, N, G, ct, q, x, cand, sc, idx, val, count));
+    } else {
+        S2V_TRY(launch_topk(ctx->stream, N, q, x, cand, k, sc, idx, val, count));
+    }
+    return S2V_OK;
+}
+
+int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                      int32_t S, const float *mu_saved, const float *gsum, const int32_t *action,
+                      const float *target, float *loss, float *q_pred, s2v_params *grads, void *ws,
+                      size_t ws_bytes) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    int32_t rc = check_graph(g);
+    if (rc != S2V_OK) return rc;
+    rc = check_params(params);
+    if (rc != S2V_OK) return rc;
+    rc = check_params(grads);
+    if (rc != S2V_OK) return rc;
+    rc = check_ws(ws);
+    if (rc != S2V_OK) return rc;
+    if (grads->p != params->p || T < 1 || S < 1) return S2V_ERR_INVALID_ARG;
+    if (!x || !mu_saved || !gsum || !action || !target || !loss) return S2V_ERR_INVALID_ARG;
+    const int32_t N = g->n_nodes, G = g->n_graphs, p = params->p;
+    if (N < 1) return S2V_ERR_INVALID_ARG;  // an action node must exist
+    if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(N, G);
+    const BwdLayout bl = bwd_layout(h, N, p, T, S);
+    if (ws_bytes < bl.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t st = ctx->stream;
+    const float *s_pos = at<float>(ws, h.s_pos), *s_neg = at<float>(ws, h.s_neg);
+    BwdScratch sc;
+    sc.dg = at<float>(ws, bl.dg);
+    sc.da = at<float>(ws, bl.da);
+    sc.glo = at<int32_t>(ws, bl.glo);
+    sc.ghi = at<int32_t>(ws, bl.ghi);
+    sc.head_part = at<float>(ws, bl.head_part);
+    sc.dz[0] = at<float>(ws, bl.dz0);
+    sc.dz[1] = at<float>(ws, bl.dz1);
+    sc.dc_part = at<float>(ws, bl.dc_part);
+    sc.d2_part = at<float>(ws, bl.d2_part);
+    sc.dvec = at<float>(ws, bl.dvec);
+    sc.red_tmp = at<float>(ws, bl.red_tmp);
+
+    const size_t nsp = (size_t)N * S * p;
+    const float *muT = mu_saved + (size_t)(T - 1) * nsp;
+    S2V_TRY(launch_bwd_head(st, p, N, S, G, g->graph_off, params->theta5, params->theta6, params->theta7, muT, gsum,
+                            action, target, sc, q_pred));
+    S2V_TRY(launch_bwd_head_reduce(st, p, S, sc, loss, grads->theta5, grads->theta6, grads->theta7));
+    S2V_TRY(launch_bwd_dzT(st, p, N, S, muT, x, s_pos, s_neg, action, sc, sc.dz[0], sc.dc_part));
+    int cur = 0;
+    for (int t = T; t >= 2; --t) {
+        const int slot = T - t;  // 0 for the first reversed round
+        float *dc_part = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)slot * kBwdGrid) * 3 * p;
+        float *d2_part = sc.d2_part + (size_t)slot * kBwdGrid * p * p;
+        const float *mu_prev = mu_saved + (size_t)(t - 2) * nsp;
+        S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, g->colidx, sc.dz[cur], mu_prev, sc.dz[cur ^ 1], x, s_pos,
+                                 s_neg, params->theta2, dc_part, d2_part));
+        cur ^= 1;
+    }
+    S2V_TRY(launch_bwd_finish(st, p, bl.dc_rows, bl.d2_rows, sc, params->theta3, params->theta4, grads->theta1,
+                              grads->theta2, grads->theta3, grads->theta4));
+    return S2V_OK;
+}
+
+int32_t s2v_sgd_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, float lr) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    int32_t rc = check_params(params);
+    if (rc != S2V_OK) return rc;
+    rc = check_params(grads);
+    if (rc != S2V_OK) return rc;
+    if (grads->p != params->p) return S2V_ERR_INVALID_ARG;
+    float *const th[7] = {params->theta1, params->theta2, params->theta3, params->theta4,
+                          params->theta5, params->theta6, params->theta7};
+    const float *const gr[7] = {grads->theta1, grads->theta2, grads->theta3, grads->theta4,
+                                grads->theta5, grads->theta6, grads->theta7};
+    S2V_TRY(launch_sgd(ctx->stream, params->p, th, gr, lr));
+    return S2V_OK;
+}
+
+int32_t s2v_adaptive_d(int64_t n_candidates, int64_t n_nodes) {
+    // compare 2|C| > N, 4|C| > N, 8|C| > N to avoid fractions
+    if (2 * n_candidates > n_nodes) return 8;
+    if (4 * n_candidates > n_nodes) return 4;
+    if (8 * n_candidates > n_nodes) return 2;
+    return 1;
+}
+
+}  // extern "C"

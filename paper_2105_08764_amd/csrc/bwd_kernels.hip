@@ -1,0 +1,465 @@
+// Backward pass of the training step (Train of Alg. 4): reverse-mode differentiation of the
+// squared loss through Eq. 2 at the action nodes and through all T rounds of Eq. 1, and the
+// plain gradient-descent update (repeated per minibatch as in Sec. 4.5.2).
+//
+// Notation (state b, node v, round t):  z^t_v = c_v + theta2 a^{t-1}_v,  a^{t-1}_v = sum_{u in N(v)} mu^{t-1}_u,
+// mu^t = relu(z^t),  c_v = theta1 x_v + s+_v q+ + s-_v q-,  q+- = theta3 relu(+-theta4).
+//   dz^t     = dmu^t (.) [mu^t > 0]
+//   G_u      = sum_{v in N(u)} dz^t_v             (adjoint of the neighbour sum; the pattern is symmetric)
+//   dtheta2 += sum_u G_u mu^{t-1}_u^T
+//   dmu^{t-1}_u = theta2^T G_u
+//   dtheta1 = sum_t sum_v x_v dz^t_v,  dq+- = sum_t sum_v s+-_v dz^t_v
+//   dtheta3 = dq+ relu(theta4)^T + dq- relu(-theta4)^T
+//   dtheta4 = [theta4 > 0] (.) theta3^T dq+  -  [theta4 < 0] (.) theta3^T dq-
+// Every reduction is a fixed tree over a fixed grid: results do not vary from run to run.
+#include "device_util.h"
+#include "internal.h"
+
+namespace s2v {
+
+// ------------------------------------------------------------------------------------------
+// Head: Eq. 2 at the action node of each state, the loss, and the gradients that do not need
+// the graph: per-state partials of dtheta5/6/7 and the two vectors that seed dmu^T:
+//   dg = theta6^T dh1 (goes to every node of the action's graph), da = theta7^T dh2 (action node only).
+// One workgroup of 128 threads per state.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void k_bwd_head(int p, int N, int S, int G, const int32_t *__restrict__ graph_off,
+                                                  const float *__restrict__ theta5, const float *__restrict__ theta6,
+                                                  const float *__restrict__ theta7, const float *__restrict__ muT,
+                                                  const float *__restrict__ gsum, const int32_t *__restrict__ action,
+                                                  const float *__restrict__ target, float *__restrict__ dg,
+                                                  float *__restrict__ da, int32_t *__restrict__ glo,
+                                                  int32_t *__restrict__ ghi, float *__restrict__ head_part,
+                                                  float *__restrict__ q_pred) {
+    __shared__ float g[128], m[128], dh1[128], dh2[128], red[128];
+    const int b = blockIdx.x, i = threadIdx.x;
+    const int a = action[b];
+    int gi = 0, lo = 0, hi = N;
+    if (G > 1) {
+        int l = 0, h = G;
+        while (h - l > 1) {
+            const int mid = (l + h) >> 1;
+            if (graph_off[mid] <= a) l = mid; else h = mid;
+        }
+        gi = l; lo = graph_off[gi]; hi = graph_off[gi + 1];
+    }
+    if (i < p) {
+        g[i] = gsum[((size_t)b * G + gi) * p + i];
+        m[i] = muT[((size_t)a * S + b) * p + i];
+    }
+    __syncthreads();
+    float h1 = 0.f, h2 = 0.f, r1 = 0.f, r2 = 0.f, term = 0.f;
+    if (i < p) {
+        for (int j = 0; j < p; ++j) {
+            h1 += theta6[i * p + j] * g[j];
+            h2 += theta7[i * p + j] * m[j];
+        }
+        r1 = fmaxf(h1, 0.f);
+        r2 = fmaxf(h2, 0.f);
+        term = theta5[i] * r1 + theta5[p + i] * r2;
+    }
+    red[i] = term;
+    __syncthreads();
+    for (int w = 64; w >= 1; w >>= 1) {
+        if (i < w) red[i] += red[i + w];
+        __syncthreads();
+    }
+    const float q = red[0];
+    const float diff = q - target[b];
+    const float dq = 2.f * diff / (float)S;
+    float *part = head_part + (size_t)b * (2 * p + 2 * p * p + 1);
+    if (i < p) {
+        part[i] = dq * r1;
+        part[p + i] = dq * r2;
+        dh1[i] = h1 > 0.f ? dq * theta5[i] : 0.f;
+        dh2[i] = h2 > 0.f ? dq * theta5[p + i] : 0.f;
+    }
+    if (i == 0) {
+        part[2 * p + 2 * p * p] = diff * diff / (float)S;
+        glo[b] = lo; ghi[b] = hi;
+        if (q_pred) q_pred[b] = q;
+    }
+    __syncthreads();
+    float *p6 = part + 2 * p, *p7 = p6 + p * p;
+    for (int e = i; e < p * p; e += 128) {
+        const int r = e / p, c = e - r * p;
+        p6[e] = dh1[r] * g[c];
+        p7[e] = dh2[r] * m[c];
+    }
+    if (i < p) {
+        float s6 = 0.f, s7 = 0.f;
+        for (int r = 0; r < p; ++r) {
+            s6 += theta6[r * p + i] * dh1[r];
+            s7 += theta7[r * p + i] * dh2[r];
+        }
+        dg[(size_t)b * p + i] = s6;
+        da[(size_t)b * p + i] = s7;
+    }
+}
+
+hipError_t launch_bwd_head(hipStream_t st, int p, int N, int S, int G, const int32_t *graph_off, const float *theta5,
+                           const float *theta6, const float *theta7, const float *muT, const float *gsum,
+                           const int32_t *action, const float *target, const BwdScratch &sc, float *q_pred) {
+    k_bwd_head<<<S, 128, 0, st>>>(p, N, S, G, graph_off, theta5, theta6, theta7, muT, gsum, action, target, sc.dg, sc.da,
+                                  sc.glo, sc.ghi, sc.head_part, q_pred);
+    return hipGetLastError();
+}
+
+// Sum the per-state partials over the S states in state order: dtheta5, dtheta6, dtheta7, loss.
+__global__ __launch_bounds__(256) void k_bwd_head_reduce(int p, int S, const float *__restrict__ head_part,
+                                                         float *__restrict__ loss, float *__restrict__ d5,
+                                                         float *__restrict__ d6, float *__restrict__ d7) {
+    const int width = 2 * p + 2 * p * p + 1;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= width) return;
+    double acc = 0.0;
+    for (int b = 0; b < S; ++b) acc += (double)head_part[(size_t)b * width + e];
+    const float out = (float)acc;
+    if (e < 2 * p) d5[e] = out;
+    else if (e < 2 * p + p * p) d6[e - 2 * p] = out;
+    else if (e < 2 * p + 2 * p * p) d7[e - 2 * p - p * p] = out;
+    else loss[0] = out;
+}
+
+hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch &sc, float *loss, float *d5, float *d6,
+                                  float *d7) {
+    const int width = 2 * p + 2 * p * p + 1;
+    k_bwd_head_reduce<<<(width + 255) / 256, 256, 0, st>>>(p, S, sc.head_part, loss, d5, d6, d7);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// dz^T[v][s] = (dg[s] if v is in the action's graph, + da[s] if v is the action node) (.) [mu^T > 0],
+// plus this kernel's share of sum x dz, sum s+ dz, sum s- dz.  Streaming; fixed grid, each
+// workgroup owns a contiguous block of rows; thread = (row slot, float4 column).
+// ------------------------------------------------------------------------------------------
+template <int P>
+__global__ __launch_bounds__(256) void k_bwd_dzT(long n_vrows, int N, int S, const float *__restrict__ muT,
+                                                 const float *__restrict__ x, const float *__restrict__ s_pos,
+                                                 const float *__restrict__ s_neg, const int32_t *__restrict__ action,
+                                                 const float *__restrict__ dg, const float *__restrict__ da,
+                                                 const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi,
+                                                 float *__restrict__ dz_out, float *__restrict__ dc_part) {
+    constexpr int LPR = P / 4, SLOTS = 256 / LPR;
+    __shared__ float red[3][SLOTS][P];
+    const int c4 = threadIdx.x % LPR, slot = threadIdx.x / LPR;
+    const long per = (n_vrows + gridDim.x - 1) / gridDim.x;
+    const long r_begin = (long)blockIdx.x * per, r_end = min(n_vrows, r_begin + per);
+    float4 ax = make_float4(0.f, 0.f, 0.f, 0.f), ap = ax, an = ax;
+    for (long r = r_begin + slot; r < r_end; r += SLOTS) {
+        const int v = (int)(r / S), s = (int)(r - (long)v * S);
+        const float4 mu = ld4(muT + (size_t)r * P + 4 * c4);
+        float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * c4);
+        if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * c4));
+        d.x = mu.x > 0.f ? d.x : 0.f;
+        d.y = mu.y > 0.f ? d.y : 0.f;
+        d.z = mu.z > 0.f ? d.z : 0.f;
+        d.w = mu.w > 0.f ? d.w : 0.f;
+        st4(dz_out + (size_t)r * P + 4 * c4, d);
+        const float xs = x[(size_t)s * N + v], sp = s_pos[v], sn = s_neg[v];
+        ax.x += xs * d.x; ax.y += xs * d.y; ax.z += xs * d.z; ax.w += xs * d.w;
+        ap.x += sp * d.x; ap.y += sp * d.y; ap.z += sp * d.z; ap.w += sp * d.w;
+        an.x += sn * d.x; an.y += sn * d.y; an.z += sn * d.z; an.w += sn * d.w;
+    }
+    st4(&red[0][slot][4 * c4], ax);
+    st4(&red[1][slot][4 * c4], ap);
+    st4(&red[2][slot][4 * c4], an);
+    __syncthreads();
+    for (int e = threadIdx.x; e < 3 * P; e += 256) {
+        const int c = e / P, j = e - c * P;
+        float s = 0.f;
+        for (int k = 0; k < SLOTS; ++k) s += red[c][k][j];
+        dc_part[(size_t)blockIdx.x * 3 * P + e] = s;
+    }
+}
+
+hipError_t launch_bwd_dzT(hipStream_t st, int p, int N, int S, const float *muT, const float *x, const float *s_pos,
+                          const float *s_neg, const int32_t *action, const BwdScratch &sc, float *dz_out,
+                          float *dc_part) {
+    const long n_vrows = (long)N * S;
+    if (p == 32)
+        k_bwd_dzT<32><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, x, s_pos, s_neg, action, sc.dg, sc.da, sc.glo,
+                                                    sc.ghi, dz_out, dc_part);
+    else
+        k_bwd_dzT<64><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, x, s_pos, s_neg, action, sc.dg, sc.da, sc.glo,
+                                                    sc.ghi, dz_out, dc_part);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// One reversed round t (T >= t >= 2), fused: G = A dz^t (same gather as the forward round),
+// dtheta2 partial += G^T mu^{t-1}, dz^{t-1} = (G theta2) (.) [mu^{t-1} > 0], and this round's share
+// of sum x dz^{t-1}, sum s+- dz^{t-1}.  Wave tiles of 16 rows of the [N*S][p] matrices; the
+// p x p accumulator of dtheta2 stays in registers over all tiles of the wave.
+// ------------------------------------------------------------------------------------------
+template <int P>
+__global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int S, const int32_t *__restrict__ rowptr,
+                                                        const int32_t *__restrict__ colidx,
+                                                        const float *__restrict__ dz_in,
+                                                        const float *__restrict__ mu_prev, float *__restrict__ dz_out,
+                                                        const float *__restrict__ x, const float *__restrict__ s_pos,
+                                                        const float *__restrict__ s_neg,
+                                                        const float *__restrict__ theta2, float *__restrict__ dc_part,
+                                                        float *__restrict__ d2_part) {
+    using Ge = Geo<P>;
+    constexpr int CB = Ge::CB, STRIDE = Ge::STRIDE;
+    constexpr int TILE_F = kTileRows * STRIDE;
+    // per wave: tile of G and tile of mu^{t-1}; reused at the end for the cross-wave reductions
+    constexpr int LDS_F = (2 * kWaves * TILE_F > kWaves * P * 16) ? 2 * kWaves * TILE_F : kWaves * P * 16;
+    __shared__ __attribute__((aligned(16))) float lds[LDS_F];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float *tile_g = lds + (2 * wave) * TILE_F;
+    float *tile_m = tile_g + TILE_F;
+    const int li = lane % Ge::LPR;
+    const int jl = lane & 15, gl = lane >> 4;
+
+    Frag<P> bfrag[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) bfrag[cb] = load_b_frag_cols<P>(theta2, cb, lane);
+
+    f32x4 d2acc[CB][CB];
+#pragma unroll
+    for (int ib = 0; ib < CB; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < CB; ++jb) d2acc[ib][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float cx[CB], cp[CB], cn[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) cx[cb] = cp[cb] = cn[cb] = 0.f;
+
+    const size_t row_stride = (size_t)S * P;
+    const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int r0 = t * kWgRows + wave * kTileRows;
+        const int r = r0 + jl;
+        const bool valid = r < n_vrows;
+        const int v = valid ? r / S : 0;
+        const int s = valid ? r - v * S : 0;
+        const int rb = valid ? rowptr[v] : 0;
+        const int re = valid ? rowptr[v + 1] : 0;
+        const float xs = valid ? x[(size_t)s * N + v] : 0.f;
+        const float sp = valid ? s_pos[v] : 0.f;
+        const float sn = valid ? s_neg[v] : 0.f;
+
+        // mu^{t-1} rows of this tile (16 contiguous rows): issue the loads now, park them in LDS after the gather
+        constexpr int MV = (kTileRows * Ge::LPR) / 64;
+        float4 mv[MV];
+#pragma unroll
+        for (int c = 0; c < MV; ++c) {
+            const int f = c * 64 + lane;            // float4 index inside the tile
+            const int row = f / Ge::LPR, col4 = f % Ge::LPR;
+            mv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r0 + row < n_vrows) mv[c] = ld4(mu_prev + (size_t)(r0 + row) * P + 4 * col4);
+        }
+
+        int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
+        int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+#pragma unroll 1
+        for (int i = 0; i < kTileRows; ++i) {
+            const int b = b_next, e = e_next;
+            const int cols = cols_next;
+            const int si = __shfl(s, i);
+            if (i + 1 < kTileRows) {
+                b_next = __shfl(rb, i + 1);
+                e_next = __shfl(re, i + 1);
+                cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+            }
+            const float4 a = gather_row_sum<P>(dz_in, row_stride, (size_t)si * P + 4 * li, colidx, b, e, cols, lane);
+            if (lane < Ge::LPR) st4(tile_g + i * STRIDE + 4 * lane, a);
+        }
+#pragma unroll
+        for (int c = 0; c < MV; ++c) {
+            const int f = c * 64 + lane;
+            st4(tile_m + (f / Ge::LPR) * STRIDE + 4 * (f % Ge::LPR), mv[c]);
+        }
+        __builtin_amdgcn_wave_barrier();
+
+        // dmu^{t-1} = G theta2, masked by mu^{t-1} > 0
+        const Frag<P> afrag = load_a_frag_lds<P>(tile_g, lane);
+        f32x4 acc[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            acc[cb] = mfma_tile<P>(afrag, bfrag[cb], acc[cb]);
+        }
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const int i = 4 * gl + rr;
+            const float xi = __shfl(xs, i), spi = __shfl(sp, i), sni = __shfl(sn, i);
+            const int ro = r0 + i;
+            if (ro < n_vrows) {
+                float *out = dz_out + (size_t)ro * P + jl;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    const float mprev = tile_m[i * STRIDE + 16 * cb + jl];
+                    const float d = mprev > 0.f ? acc[cb][rr] : 0.f;
+                    out[16 * cb] = d;
+                    cx[cb] += xi * d; cp[cb] += spi * d; cn[cb] += sni * d;
+                }
+            }
+        }
+
+        // dtheta2[i][j] += sum_r G[r][i] mu^{t-1}[r][j]: 16x16 blocks, k runs over the 16 tile rows
+        // (lane group gl takes rows 4*gl + ks at k-step ks); rows past the end hold zeros in both tiles.
+        float a2[CB][4], b2[CB][4];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                a2[cb][ks] = tile_g[(4 * gl + ks) * STRIDE + 16 * cb + jl];
+                b2[cb][ks] = tile_m[(4 * gl + ks) * STRIDE + 16 * cb + jl];
+            }
+#pragma unroll
+        for (int ib = 0; ib < CB; ++ib)
+#pragma unroll
+            for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    d2acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[ib][ks], b2[jb][ks], d2acc[ib][jb], 0, 0, 0);
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- workgroup reductions, fixed order over the four waves ----
+    __syncthreads();
+    // dtheta2: in 16-row slabs of the p x p matrix (one ib at a time) to bound LDS use
+#pragma unroll
+    for (int ib = 0; ib < CB; ++ib) {
+        float *slab = lds + wave * (16 * P);
+#pragma unroll
+        for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) slab[(4 * gl + rr) * P + 16 * jb + jl] = d2acc[ib][jb][rr];
+        __syncthreads();
+        for (int e = threadIdx.x; e < 16 * P; e += kThreads) {
+            const float sum = (lds[e] + lds[16 * P + e]) + (lds[2 * 16 * P + e] + lds[3 * 16 * P + e]);
+            d2_part[(size_t)blockIdx.x * P * P + (size_t)ib * 16 * P + e] = sum;
+        }
+        __syncthreads();
+    }
+    // sum x dz, sum s+ dz, sum s- dz: lanes with equal jl first, then waves
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        cx[cb] += __shfl_xor(cx[cb], 16); cx[cb] += __shfl_xor(cx[cb], 32);
+        cp[cb] += __shfl_xor(cp[cb], 16); cp[cb] += __shfl_xor(cp[cb], 32);
+        cn[cb] += __shfl_xor(cn[cb], 16); cn[cb] += __shfl_xor(cn[cb], 32);
+    }
+    if (gl == 0) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            lds[(wave * 3 + 0) * P + 16 * cb + jl] = cx[cb];
+            lds[(wave * 3 + 1) * P + 16 * cb + jl] = cp[cb];
+            lds[(wave * 3 + 2) * P + 16 * cb + jl] = cn[cb];
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < 3 * P; e += kThreads) {
+        const float sum = (lds[e] + lds[3 * P + e]) + (lds[2 * 3 * P + e] + lds[3 * 3 * P + e]);
+        dc_part[(size_t)blockIdx.x * 3 * P + e] = sum;
+    }
+}
+
+hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+                            const float *dz_in, const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
+                            const float *s_neg, const float *theta2, float *dc_part, float *d2_part) {
+    const long n_vrows = (long)N * S;
+    if (p == 32)
+        k_bwd_round<32><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, mu_prev, dz_out, x,
+                                                       s_pos, s_neg, theta2, dc_part, d2_part);
+    else
+        k_bwd_round<64><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, mu_prev, dz_out, x,
+                                                       s_pos, s_neg, theta2, dc_part, d2_part);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Final reductions.  k_colsum adds `rows` rows of width `width` in segments of rows_per_seg rows
+// (double accumulator per segment, float out); called twice it gives a fixed two-level tree.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_colsum(int rows, int width, int rows_per_seg, const float *__restrict__ in,
+                                                float *__restrict__ out) {
+    const int col = blockIdx.x * 256 + threadIdx.x;
+    if (col >= width) return;
+    const int r0 = blockIdx.y * rows_per_seg, r1 = min(rows, r0 + rows_per_seg);
+    double a0 = 0.0, a1 = 0.0;
+    int r = r0;
+    for (; r + 2 <= r1; r += 2) {
+        a0 += (double)in[(size_t)r * width + col];
+        a1 += (double)in[(size_t)(r + 1) * width + col];
+    }
+    if (r < r1) a0 += (double)in[(size_t)r * width + col];
+    out[(size_t)blockIdx.y * width + col] = (float)(a0 + a1);
+}
+
+__global__ __launch_bounds__(128) void k_bwd_finish_vec(int p, const float *__restrict__ dvec,
+                                                        const float *__restrict__ theta3,
+                                                        const float *__restrict__ theta4, float *__restrict__ d1,
+                                                        float *__restrict__ d3, float *__restrict__ d4) {
+    const int j = threadIdx.x;
+    const float *dqp = dvec + p, *dqn = dvec + 2 * p;
+    if (j < p) {
+        d1[j] = dvec[j];
+        const float t4 = theta4[j];
+        float up = 0.f, un = 0.f;
+        for (int i = 0; i < p; ++i) {
+            up += theta3[i * p + j] * dqp[i];
+            un += theta3[i * p + j] * dqn[i];
+        }
+        d4[j] = (t4 > 0.f ? up : 0.f) - (t4 < 0.f ? un : 0.f);
+    }
+    for (int e = j; e < p * p; e += 128) {
+        const int r = e / p, c = e - r * p;
+        const float t4 = theta4[c];
+        d3[e] = dqp[r] * fmaxf(t4, 0.f) + dqn[r] * fmaxf(-t4, 0.f);
+    }
+}
+
+static hipError_t colsum_two_level(hipStream_t st, int rows, int width, const float *in, float *tmp, float *out) {
+    constexpr int kSeg = 64;
+    const int segs = (rows + kSeg - 1) / kSeg;
+    const dim3 g1((width + 255) / 256, segs > 0 ? segs : 1);
+    if (segs <= 1) {
+        k_colsum<<<g1, 256, 0, st>>>(rows, width, kSeg, in, out);
+        return hipGetLastError();
+    }
+    k_colsum<<<g1, 256, 0, st>>>(rows, width, kSeg, in, tmp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 g2((width + 255) / 256, 1);
+    k_colsum<<<g2, 256, 0, st>>>(segs, width, segs, tmp, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_finish(hipStream_t st, int p, int dc_rows, int d2_rows, const BwdScratch &sc, const float *theta3,
+                             const float *theta4, float *d1, float *d2, float *d3, float *d4) {
+    hipError_t e = colsum_two_level(st, dc_rows, 3 * p, sc.dc_part, sc.red_tmp, sc.dvec);
+    if (e != hipSuccess) return e;
+    e = colsum_two_level(st, d2_rows, p * p, sc.d2_part, sc.red_tmp, d2);
+    if (e != hipSuccess) return e;
+    k_bwd_finish_vec<<<1, 128, 0, st>>>(p, sc.dvec, theta3, theta4, d1, d3, d4);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// theta <- theta - lr * grad over the seven tensors (4p^2 + 4p values).
+// ------------------------------------------------------------------------------------------
+struct SgdArgs {
+    float *theta[7];
+    const float *grad[7];
+    int len[7];
+};
+
+__global__ __launch_bounds__(256) void k_sgd(SgdArgs a, float lr) {
+    const int t = blockIdx.y;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < a.len[t]; i += gridDim.x * 256)
+        a.theta[t][i] = a.theta[t][i] - lr * a.grad[t][i];
+}
+
+hipError_t launch_sgd(hipStream_t st, int p, float *const theta[7], const float *const grad[7], float lr) {
+    SgdArgs a;
+    const int len[7] = {p, p * p, p * p, p, 2 * p, p * p, p * p};
+    for (int i = 0; i < 7; ++i) { a.theta[i] = theta[i]; a.grad[i] = grad[i]; a.len[i] = len[i]; }
+    k_sgd<<<dim3((p * p + 255) / 256, 7), 256, 0, st>>>(a, lr);
+    return hipGetLastError();
+}
+
+}  // namespace s2v

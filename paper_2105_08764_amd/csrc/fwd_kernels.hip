@@ -1,0 +1,378 @@
+// Forward kernels: graph preparation, the embedding rounds of Eq. 1 / Alg. 1, the per-graph
+// embedding sum (Alg. 2 lines 4-5) and the scores of Eq. 2 / Alg. 2.
+#include "device_util.h"
+#include "internal.h"
+
+namespace s2v {
+
+// ------------------------------------------------------------------------------------------
+// Graph preparation: s+_v = sum_u max(W(v,u), 0), s-_v = sum_u max(-W(v,u), 0).
+// With these, the third term of Eq. 1 is  s+_v * theta3 relu(theta4) + s-_v * theta3 relu(-theta4),
+// the same for every round (Alg. 1 computes it before the layer loop).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_prepare_s(int N, const int32_t *__restrict__ rowptr,
+                                                   const float *__restrict__ w, float *__restrict__ s_pos,
+                                                   float *__restrict__ s_neg) {
+    for (int v = blockIdx.x * blockDim.x + threadIdx.x; v < N; v += gridDim.x * blockDim.x) {
+        const int b = rowptr[v], e = rowptr[v + 1];
+        double sp = 0.0, sn = 0.0;
+        if (w) {
+            for (int j = b; j < e; ++j) {
+                const float wj = w[j];
+                sp += (double)fmaxf(wj, 0.f);
+                sn += (double)fmaxf(-wj, 0.f);
+            }
+        } else {
+            sp = (double)(e - b);
+        }
+        s_pos[v] = (float)sp;
+        s_neg[v] = (float)sn;
+    }
+}
+
+hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const float *w, float *s_pos, float *s_neg) {
+    if (N == 0) return hipSuccess;
+    const int grid = min((N + 255) / 256, 65536);
+    k_prepare_s<<<grid, 256, 0, st>>>(N, rowptr, w, s_pos, s_neg);
+    return hipGetLastError();
+}
+
+// q+ = theta3 relu(theta4), q- = theta3 relu(-theta4)   (two p-vectors, qvec = [q+ ; q-])
+__global__ void k_qvec(int p, const float *__restrict__ theta3, const float *__restrict__ theta4,
+                       float *__restrict__ qvec) {
+    const int i = threadIdx.x;
+    if (i >= p) return;
+    float qp = 0.f, qn = 0.f;
+    for (int j = 0; j < p; ++j) {
+        const float t4 = theta4[j], t3 = theta3[i * p + j];
+        qp += t3 * fmaxf(t4, 0.f);
+        qn += t3 * fmaxf(-t4, 0.f);
+    }
+    qvec[i] = qp;
+    qvec[p + i] = qn;
+}
+
+hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec) {
+    k_qvec<<<1, 128, 0, st>>>(p, theta3, theta4, qvec);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Round 1: mu^0 = 0 (Alg. 1), so mu^1_v = relu(theta1 x_v + s+_v q+ + s-_v q-): no neighbour sum.
+// One thread per float4 of the [N][S][p] output.
+// ------------------------------------------------------------------------------------------
+template <int P>
+__global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, const float *__restrict__ x,
+                                                const float *__restrict__ s_pos, const float *__restrict__ s_neg,
+                                                const float *__restrict__ theta1, const float *__restrict__ qvec,
+                                                float *__restrict__ mu_out) {
+    constexpr int LPR = P / 4;
+    const long total = n_vrows * LPR;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const long r = i / LPR;
+        const int c = (int)(i - r * LPR) * 4;
+        const int v = (int)(r / S), s = (int)(r - (long)v * S);
+        const float xs = x[(size_t)s * N + v], sp = s_pos[v], sn = s_neg[v];
+        const float4 t1 = ld4(theta1 + c), qp = ld4(qvec + c), qn = ld4(qvec + P + c);
+        float4 o;
+        o.x = fmaxf(xs * t1.x + sp * qp.x + sn * qn.x, 0.f);
+        o.y = fmaxf(xs * t1.y + sp * qp.y + sn * qn.y, 0.f);
+        o.z = fmaxf(xs * t1.z + sp * qp.z + sn * qn.z, 0.f);
+        o.w = fmaxf(xs * t1.w + sp * qp.w + sn * qn.w, 0.f);
+        st4(mu_out + (size_t)r * P + c, o);
+    }
+}
+
+hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *x, const float *s_pos, const float *s_neg,
+                         const float *theta1, const float *qvec, float *mu_out) {
+    const long n_vrows = (long)N * S;
+    if (n_vrows == 0) return hipSuccess;
+    const long total = n_vrows * (p / 4);
+    const int grid = (int)min((total + 255) / 256, (long)(256 * 32));
+    if (p == 32) k_round1<32><<<grid, 256, 0, st>>>(n_vrows, N, S, x, s_pos, s_neg, theta1, qvec, mu_out);
+    else k_round1<64><<<grid, 256, 0, st>>>(n_vrows, N, S, x, s_pos, s_neg, theta1, qvec, mu_out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Rounds 2..T of Eq. 1, fused: neighbour sum (CSR gather of p-float rows), theta2 product on
+// the matrix cores, the round-invariant terms, relu.  The matrix being updated is viewed as
+// [N*S][p]: row r = (node v = r / S, state s = r % S); the neighbours of row r are the rows
+// (u, s) for u in N(v).  A wave owns 16 consecutive rows at a time: it gathers their sums into
+// its own LDS tile, multiplies the tile by theta2 and writes the 16 output rows.
+// ------------------------------------------------------------------------------------------
+template <int P>
+__global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int N, int S, const int32_t *__restrict__ rowptr,
+                                                    const int32_t *__restrict__ colidx,
+                                                    const float *__restrict__ mu_in, float *__restrict__ mu_out,
+                                                    const float *__restrict__ x, const float *__restrict__ s_pos,
+                                                    const float *__restrict__ s_neg,
+                                                    const float *__restrict__ theta1,
+                                                    const float *__restrict__ theta2,
+                                                    const float *__restrict__ qvec) {
+    using G = Geo<P>;
+    __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float *tile = lds[wave];
+    const int li = lane % G::LPR;
+    const int jl = lane & 15, gl = lane >> 4;
+
+    Frag<P> bfrag[G::CB];
+    float t1[G::CB], qp[G::CB], qn[G::CB];
+#pragma unroll
+    for (int cb = 0; cb < G::CB; ++cb) {
+        bfrag[cb] = load_b_frag_rows<P>(theta2, cb, lane);
+        t1[cb] = theta1[16 * cb + jl];
+        qp[cb] = qvec[16 * cb + jl];
+        qn[cb] = qvec[P + 16 * cb + jl];
+    }
+
+    const size_t row_stride = (size_t)S * P;
+    const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int r0 = t * kWgRows + wave * kTileRows;
+        // lane i (mod 16) carries the metadata of tile row i
+        const int r = r0 + jl;
+        const bool valid = r < n_vrows;
+        const int v = valid ? r / S : 0;
+        const int s = valid ? r - v * S : 0;
+        const int rb = valid ? rowptr[v] : 0;
+        const int re = valid ? rowptr[v + 1] : 0;
+        const float xs = valid ? x[(size_t)s * N + v] : 0.f;
+        const float sp = valid ? s_pos[v] : 0.f;
+        const float sn = valid ? s_neg[v] : 0.f;
+
+        int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
+        int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+#pragma unroll 1
+        for (int i = 0; i < kTileRows; ++i) {
+            const int b = b_next, e = e_next;
+            const int cols = cols_next;
+            const int si = __shfl(s, i);
+            if (i + 1 < kTileRows) {
+                b_next = __shfl(rb, i + 1);
+                e_next = __shfl(re, i + 1);
+                cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+            }
+            const float4 a = gather_row_sum<P>(mu_in, row_stride, (size_t)si * P + 4 * li, colidx, b, e, cols, lane);
+            if (lane < G::LPR) st4(tile + i * G::STRIDE + 4 * lane, a);
+        }
+        __builtin_amdgcn_wave_barrier();
+        const Frag<P> afrag = load_a_frag_lds<P>(tile, lane);
+        __builtin_amdgcn_wave_barrier();
+        f32x4 acc[G::CB];
+#pragma unroll
+        for (int cb = 0; cb < G::CB; ++cb) {
+            acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            acc[cb] = mfma_tile<P>(afrag, bfrag[cb], acc[cb]);
+        }
+        // lane (jl, gl) holds rows 4*gl + rr, columns 16*cb + jl
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const int i = 4 * gl + rr;
+            const float xi = __shfl(xs, i), spi = __shfl(sp, i), sni = __shfl(sn, i);
+            const int ro = r0 + i;
+            if (ro < n_vrows) {
+                float *out = mu_out + (size_t)ro * P + jl;
+#pragma unroll
+                for (int cb = 0; cb < G::CB; ++cb)
+                    out[16 * cb] = fmaxf(acc[cb][rr] + xi * t1[cb] + spi * qp[cb] + sni * qn[cb], 0.f);
+            }
+        }
+    }
+}
+
+hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+                        const float *mu_in, float *mu_out, const float *x, const float *s_pos, const float *s_neg,
+                        const float *theta1, const float *theta2, const float *qvec) {
+    const long n_vrows = (long)N * S;
+    if (n_vrows == 0) return hipSuccess;
+    const long n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    const int grid = (int)min(n_tiles, (long)(256 * 16));
+    if (p == 32)
+        k_round<32><<<grid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, mu_in, mu_out, x, s_pos, s_neg,
+                                               theta1, theta2, qvec);
+    else
+        k_round<64><<<grid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, mu_in, mu_out, x, s_pos, s_neg,
+                                               theta1, theta2, qvec);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Per-graph sum of the final embedding (Alg. 2 lines 4-5), deterministic two stages:
+// stage 1 sums each chunk of <= kChunkNodes nodes (a chunk lies inside one graph) column by
+// column; stage 2 adds the chunk partials of each graph in chunk order, in double.
+// The matrix is [N][L] with L = S*p columns.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_gsum_stage1(int L, const int32_t *__restrict__ chunk_begin,
+                                                     const int32_t *__restrict__ chunk_end,
+                                                     const float *__restrict__ mu, float *__restrict__ partial) {
+    __shared__ float red[256];
+    const int c = blockIdx.x;
+    const int vb = chunk_begin[c], ve = chunk_end[c];
+    const int tid = threadIdx.x;
+    if (L >= 256) {
+        for (int col = tid; col < L; col += 256) {
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+            int v = vb;
+            for (; v + 4 <= ve; v += 4) {
+                a0 += mu[(size_t)v * L + col];
+                a1 += mu[(size_t)(v + 1) * L + col];
+                a2 += mu[(size_t)(v + 2) * L + col];
+                a3 += mu[(size_t)(v + 3) * L + col];
+            }
+            for (; v < ve; ++v) a0 += mu[(size_t)v * L + col];
+            partial[(size_t)c * L + col] = (a0 + a1) + (a2 + a3);
+        }
+    } else {
+        // L in {32, 64, 128}: 256 / L row groups, combined through LDS in group order
+        const int groups = 256 / L;
+        const int col = tid % L, grp = tid / L;
+        float a0 = 0.f, a1 = 0.f;
+        if (grp < groups) {
+            int v = vb + grp;
+            for (; v + groups < ve; v += 2 * groups) {
+                a0 += mu[(size_t)v * L + col];
+                a1 += mu[(size_t)(v + groups) * L + col];
+            }
+            if (v < ve) a0 += mu[(size_t)v * L + col];
+        }
+        red[tid] = a0 + a1;
+        __syncthreads();
+        if (grp == 0) {
+            float s = red[col];
+            for (int g = 1; g < groups; ++g) s += red[g * L + col];
+            partial[(size_t)c * L + col] = s;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_gsum_stage2(int p, int S, int G, const int32_t *__restrict__ graph_chunk_off,
+                                                     const float *__restrict__ partial, float *__restrict__ gsum) {
+    const int L = S * p;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= G * L) return;
+    const int g = i / L, col = i - g * L;
+    double acc = 0.0;
+    for (int c = graph_chunk_off[g]; c < graph_chunk_off[g + 1]; ++c) acc += (double)partial[(size_t)c * L + col];
+    const int s = col / p, j = col - s * p;
+    gsum[((size_t)s * G + g) * p + j] = (float)acc;
+}
+
+hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu, float *partial,
+                       float *gsum) {
+    (void)N;
+    const int L = S * p;
+    if (ct.n_chunks > 0) {
+        k_gsum_stage1<<<ct.n_chunks, 256, 0, st>>>(L, ct.chunk_begin, ct.chunk_end, mu, partial);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const int total = G * L;
+    k_gsum_stage2<<<(total + 255) / 256, 256, 0, st>>>(p, S, G, ct.graph_chunk_off, partial, gsum);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 2, graph term: qa[s][g] = theta5[0:p] . relu(theta6 gsum[s][g])   (one block per (s, g))
+// ------------------------------------------------------------------------------------------
+__global__ void k_qa(int p, const float *__restrict__ theta5, const float *__restrict__ theta6,
+                     const float *__restrict__ gsum, float *__restrict__ qa) {
+    __shared__ float gs[128];
+    __shared__ float red[128];
+    const int b = blockIdx.x, i = threadIdx.x;
+    if (i < p) gs[i] = gsum[(size_t)b * p + i];
+    __syncthreads();
+    float term = 0.f;
+    if (i < p) {
+        float h = 0.f;
+        for (int j = 0; j < p; ++j) h += theta6[i * p + j] * gs[j];
+        term = theta5[i] * fmaxf(h, 0.f);
+    }
+    red[i] = term;
+    __syncthreads();
+    for (int w = 64; w >= 1; w >>= 1) {
+        if (i < w) red[i] += red[i + w];
+        __syncthreads();
+    }
+    if (i == 0) qa[b] = red[0];
+}
+
+hipError_t launch_qa(hipStream_t st, int p, int S, int G, const float *theta5, const float *theta6, const float *gsum,
+                     float *qa) {
+    k_qa<<<S * G, 128, 0, st>>>(p, theta5, theta6, gsum, qa);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 2, node term + sum: q[s][v] = qa[s][graph(v)] + theta5[p:2p] . relu(theta7 mu[v][s])
+// Same 16-row wave tiles as the embedding round; the A operand comes straight from mu.
+// ------------------------------------------------------------------------------------------
+template <int P>
+__global__ __launch_bounds__(kThreads) void k_qnode(int n_vrows, int N, int S, int G,
+                                                    const int32_t *__restrict__ graph_off,
+                                                    const float *__restrict__ theta5,
+                                                    const float *__restrict__ theta7, const float *__restrict__ mu,
+                                                    const float *__restrict__ qa, float *__restrict__ q) {
+    using Ge = Geo<P>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int jl = lane & 15, gl = lane >> 4;
+    Frag<P> bfrag[Ge::CB];
+    float t5[Ge::CB];
+#pragma unroll
+    for (int cb = 0; cb < Ge::CB; ++cb) {
+        bfrag[cb] = load_b_frag_rows<P>(theta7, cb, lane);
+        t5[cb] = theta5[P + 16 * cb + jl];
+    }
+    const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int r0 = t * kWgRows + wave * kTileRows;
+        if (r0 >= n_vrows) continue;
+        const Frag<P> afrag = load_a_frag_global<P>(mu, r0, n_vrows, lane);
+        float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cb = 0; cb < Ge::CB; ++cb) {
+            f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+            acc = mfma_tile<P>(afrag, bfrag[cb], acc);
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) part[rr] += t5[cb] * fmaxf(acc[rr], 0.f);
+        }
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+#pragma unroll
+            for (int m = 1; m < 16; m <<= 1) part[rr] += __shfl_xor(part[rr], m);
+        }
+        if (jl == 0) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = r0 + 4 * gl + rr;
+                if (r < n_vrows) {
+                    const int v = r / S, s = r - v * S;
+                    int g = 0;
+                    if (G > 1) {  // last graph whose offset is <= v
+                        int lo = 0, hi = G;
+                        while (hi - lo > 1) {
+                            const int mid = (lo + hi) >> 1;
+                            if (graph_off[mid] <= v) lo = mid; else hi = mid;
+                        }
+                        g = lo;
+                    }
+                    q[(size_t)s * N + v] = qa[(size_t)s * G + g] + part[rr];
+                }
+            }
+        }
+    }
+}
+
+hipError_t launch_qnode(hipStream_t st, int p, int N, int S, int G, const int32_t *graph_off, const float *theta5,
+                        const float *theta7, const float *mu, const float *qa, float *q) {
+    const long n_vrows = (long)N * S;
+    if (n_vrows == 0) return hipSuccess;
+    const long n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    const int grid = (int)min(n_tiles, (long)(256 * 16));
+    if (p == 32) k_qnode<32><<<grid, kThreads, 0, st>>>((int)n_vrows, N, S, G, graph_off, theta5, theta7, mu, qa, q);
+    else k_qnode<64><<<grid, kThreads, 0, st>>>((int)n_vrows, N, S, G, graph_off, theta5, theta7, mu, qa, q);
+    return hipGetLastError();
+}
+
+}  // namespace s2v

@@ -1,0 +1,90 @@
+// Internal declarations shared by the translation units of libs2v.so.
+// Host-side launchers only; every kernel lives in the .hip file that defines its launcher.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace s2v {
+
+// Nodes per reduction chunk (graph sums, argmax partials).  A chunk never straddles two graphs.
+constexpr int kChunkNodes = 1024;
+// Workgroups of the backward round kernel: a fixed grid, so that the order in which
+// per-workgroup partial gradients are summed does not depend on the device.
+constexpr int kBwdGrid = 1024;
+constexpr int kBwdHeadGrid = 1024;
+// Elements per block of the selection scan / sort passes.
+constexpr int kScanBlock = 2048;
+constexpr int kSortTile = 1024;
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct ChunkTable {            // device pointers into the prepared head of the workspace
+    int n_chunks;
+    const int32_t *chunk_begin;      // [n_chunks] first node
+    const int32_t *chunk_end;        // [n_chunks] one past the last node
+    const int32_t *chunk_graph;      // [n_chunks] graph of the chunk
+    const int32_t *graph_chunk_off;  // [G+1] chunks of graph g are [off[g], off[g+1])
+};
+
+// ---- forward (fwd_kernels.hip) ----
+hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const float *w, float *s_pos, float *s_neg);
+hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec);
+hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *x, const float *s_pos, const float *s_neg,
+                         const float *theta1, const float *qvec, float *mu_out);
+hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+                        const float *mu_in, float *mu_out, const float *x, const float *s_pos, const float *s_neg,
+                        const float *theta1, const float *theta2, const float *qvec);
+hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu,
+                       float *partial /*[n_chunks][S*p]*/, float *gsum /*[S][G][p]*/);
+hipError_t launch_qa(hipStream_t st, int p, int S, int G, const float *theta5, const float *theta6, const float *gsum,
+                     float *qa /*[S][G]*/);
+hipError_t launch_qnode(hipStream_t st, int p, int N, int S, int G, const int32_t *graph_off, const float *theta5,
+                        const float *theta7, const float *mu, const float *qa, float *q /*[S][N]*/);
+
+// ---- selection (select_kernels.hip) ----
+struct SelectScratch {
+    float *part_val;    // [n_chunks]
+    int32_t *part_idx;  // [n_chunks]
+    uint32_t *hist;     // [4][256]
+    uint32_t *state;    // [16]
+    uint32_t *blk;      // [2][n_scan_blocks][2]
+    uint32_t *keys[2];  // [k] each
+    int32_t *ids[2];    // [k] each
+    uint32_t *sort_cnt; // [256][n_sort_blocks]
+};
+hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, const float *q, const float *x,
+                         const uint8_t *cand, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
+hipError_t launch_topk(hipStream_t st, int N, const float *q, const float *x, const uint8_t *cand, int k,
+                       const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
+
+// ---- backward (bwd_kernels.hip) ----
+struct BwdScratch {
+    float *dg;          // [S][p]   theta6^T dh1 : gradient w.r.t. the graph sum
+    float *da;          // [S][p]   theta7^T dh2 : extra gradient at the action node
+    int32_t *glo;       // [S] first node of the action's graph
+    int32_t *ghi;       // [S] one past its last node
+    float *head_part;   // [S][2p + 2*p*p + 1]  per-state partials of dtheta5, dtheta6, dtheta7, loss
+    float *dz[2];       // [N][S][p] each
+    float *dc_part;     // [dc_rows][3][p]   partial sums of x*dz, s+ * dz, s- * dz
+    float *d2_part;     // [d2_rows][p][p]   partial sums of G (x) mu
+    float *dvec;        // [3][p] reduced dtheta1, dq+, dq-
+    float *red_tmp;     // [ceil(max rows / 64)][max(3p, p*p)] second level of the final reductions
+};
+hipError_t launch_bwd_head(hipStream_t st, int p, int N, int S, int G, const int32_t *graph_off, const float *theta5,
+                           const float *theta6, const float *theta7, const float *muT, const float *gsum,
+                           const int32_t *action, const float *target, const BwdScratch &sc, float *q_pred);
+hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch &sc, float *loss, float *d5, float *d6,
+                                  float *d7);
+hipError_t launch_bwd_dzT(hipStream_t st, int p, int N, int S, const float *muT, const float *x, const float *s_pos,
+                          const float *s_neg, const int32_t *action, const BwdScratch &sc, float *dz_out,
+                          float *dc_part /*[kBwdHeadGrid][3][p]*/);
+hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+                            const float *dz_in, const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
+                            const float *s_neg, const float *theta2, float *dc_part /*[kBwdGrid][3][p]*/,
+                            float *d2_part /*[kBwdGrid][p][p]*/);
+hipError_t launch_bwd_finish(hipStream_t st, int p, int dc_rows, int d2_rows, const BwdScratch &sc, const float *theta3,
+                             const float *theta4, float *d1, float *d2, float *d3, float *d4);
+hipError_t launch_sgd(hipStream_t st, int p, float *const theta[7], const float *const grad[7], float lr);
+
+}  // namespace s2v

@@ -1,0 +1,383 @@
+// Node selection: masked per-graph argmax (Alg. 3 line 7) and top-k of one graph
+// (the top-d selection of Sec. 4.5.1).  Order: score descending, node index ascending on
+// equal scores.  All results are exact functions of the float32 scores: no atomics on floats,
+// integer atomics only for histogram counts.
+#include <limits.h>
+
+#include "internal.h"
+
+namespace s2v {
+
+__device__ __forceinline__ bool is_candidate(const float *__restrict__ x, const uint8_t *__restrict__ cand, int v) {
+    return cand ? (cand[v] != 0) : (x[v] == 0.f);
+}
+
+// Order-preserving map float -> uint32 (larger score = larger key); -0.0 is folded onto +0.0.
+__device__ __forceinline__ uint32_t score_key(float q) {
+    const uint32_t b = __float_as_uint(q + 0.0f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_score(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// (val, idx) beats (val2, idx2) if the score is higher, or equal with a lower node index.
+__device__ __forceinline__ void take_better(float &val, int &idx, float val2, int idx2) {
+    if (val2 > val || (val2 == val && idx2 < idx)) { val = val2; idx = idx2; }
+}
+
+__device__ __forceinline__ void block_best(float &val, int &idx, float *sval, int *sidx) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        const float v2 = __shfl_xor(val, m);
+        const int i2 = __shfl_xor(idx, m);
+        take_better(val, idx, v2, i2);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sval[wave] = val; sidx[wave] = idx; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) take_better(val, idx, sval[w], sidx[w]);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_argmax_stage1(const int32_t *__restrict__ chunk_begin,
+                                                       const int32_t *__restrict__ chunk_end,
+                                                       const float *__restrict__ q, const float *__restrict__ x,
+                                                       const uint8_t *__restrict__ cand,
+                                                       float *__restrict__ part_val, int32_t *__restrict__ part_idx) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    const int c = blockIdx.x;
+    const int vb = chunk_begin[c], ve = chunk_end[c];
+    float val = -INFINITY;
+    int idx = INT_MAX;
+    for (int v = vb + threadIdx.x; v < ve; v += 256)
+        if (is_candidate(x, cand, v)) take_better(val, idx, q[v], v);
+    block_best(val, idx, sval, sidx);
+    if (threadIdx.x == 0) { part_val[c] = val; part_idx[c] = idx; }
+}
+
+__global__ __launch_bounds__(256) void k_argmax_stage2(const int32_t *__restrict__ graph_chunk_off,
+                                                       const float *__restrict__ part_val,
+                                                       const int32_t *__restrict__ part_idx,
+                                                       int32_t *__restrict__ idx_out, float *__restrict__ val_out,
+                                                       int32_t *__restrict__ count) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    const int g = blockIdx.x;
+    float val = -INFINITY;
+    int idx = INT_MAX;
+    for (int c = graph_chunk_off[g] + threadIdx.x; c < graph_chunk_off[g + 1]; c += 256)
+        take_better(val, idx, part_val[c], part_idx[c]);
+    block_best(val, idx, sval, sidx);
+    if (threadIdx.x == 0) {
+        const bool any = idx != INT_MAX;
+        idx_out[g] = any ? idx : -1;
+        val_out[g] = any ? val : -INFINITY;
+        count[g] = any ? 1 : 0;
+    }
+}
+
+hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, const float *q, const float *x,
+                         const uint8_t *cand, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count) {
+    (void)N;
+    if (ct.n_chunks > 0) {
+        k_argmax_stage1<<<ct.n_chunks, 256, 0, st>>>(ct.chunk_begin, ct.chunk_end, q, x, cand, sc.part_val, sc.part_idx);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    k_argmax_stage2<<<G, 256, 0, st>>>(ct.graph_chunk_off, sc.part_val, sc.part_idx, idx, val, count);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Top-k of one graph.
+//  1. radix select: four 8-bit histogram passes from the top byte find the k-th largest key tau
+//     and how many keys equal to tau are still needed (`need`);
+//  2. index-ordered compaction of {key > tau} and the first `need` nodes with key == tau;
+//  3. stable LSD radix sort of the selected (<= k) entries by key descending; stability keeps
+//     equal scores in ascending node index.
+// state: [0] prefix (tau after pass 3), [1] k still to find, [2] number of candidates,
+//        [3] 1 if candidates < k (take all), [4] count = min(k, candidates)
+// ------------------------------------------------------------------------------------------
+__global__ void k_topk_init(uint32_t *__restrict__ hist, uint32_t *__restrict__ state, int k) {
+    for (int i = threadIdx.x; i < 4 * 256; i += blockDim.x) hist[i] = 0;
+    if (threadIdx.x < 16) state[threadIdx.x] = (threadIdx.x == 1) ? (uint32_t)k : 0u;
+}
+
+__global__ __launch_bounds__(256) void k_topk_hist(int N, int pass, const float *__restrict__ q,
+                                                   const float *__restrict__ x, const uint8_t *__restrict__ cand,
+                                                   uint32_t *__restrict__ hist, const uint32_t *__restrict__ state) {
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    if (state[3] == 0) {
+        const int shift = 24 - 8 * pass;
+        const uint32_t mask_hi = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+        const uint32_t prefix = state[0];
+        for (int v = blockIdx.x * 256 + threadIdx.x; v < N; v += gridDim.x * 256) {
+            if (!is_candidate(x, cand, v)) continue;
+            const uint32_t key = score_key(q[v]);
+            if ((key & mask_hi) == prefix) atomicAdd(&h[(key >> shift) & 255u], 1u);
+        }
+    }
+    __syncthreads();
+    if (h[threadIdx.x]) atomicAdd(&hist[pass * 256 + threadIdx.x], h[threadIdx.x]);
+}
+
+__global__ void k_topk_pick(int pass, const uint32_t *__restrict__ hist, uint32_t *__restrict__ state) {
+    if (threadIdx.x != 0 || state[3] != 0) return;
+    const uint32_t *h = hist + pass * 256;
+    uint32_t k_rem = state[1];
+    if (pass == 0) {
+        uint32_t total = 0;
+        for (int d = 0; d < 256; ++d) total += h[d];
+        state[2] = total;
+        if (total < k_rem) { state[3] = 1; state[4] = total; return; }
+        state[4] = k_rem;
+    }
+    uint32_t cum = 0;
+    int d = 255;
+    for (; d > 0; --d) {
+        if (cum + h[d] >= k_rem) break;
+        cum += h[d];
+    }
+    state[0] |= (uint32_t)d << (24 - 8 * pass);
+    state[1] = k_rem - cum;
+}
+
+// flags of one node: bit 0 = key > tau (or any candidate when taking all), bit 1 = key == tau
+__device__ __forceinline__ uint32_t sel_flags(const float *__restrict__ q, const float *__restrict__ x,
+                                              const uint8_t *__restrict__ cand, int v, uint32_t tau, bool take_all,
+                                              uint32_t &key) {
+    if (!is_candidate(x, cand, v)) return 0;
+    key = score_key(q[v]);
+    if (take_all || key > tau) return 1u;
+    return key == tau ? 2u : 0u;
+}
+
+__global__ __launch_bounds__(256) void k_topk_scan1(int N, const float *__restrict__ q, const float *__restrict__ x,
+                                                    const uint8_t *__restrict__ cand,
+                                                    const uint32_t *__restrict__ state, uint32_t *__restrict__ blk) {
+    __shared__ uint32_t sg[4], se[4];
+    const uint32_t tau = state[0];
+    const bool take_all = state[3] != 0;
+    const int base = blockIdx.x * kScanBlock + threadIdx.x * 8;
+    uint32_t gt = 0, eq = 0, key;
+    for (int i = 0; i < 8; ++i) {
+        const int v = base + i;
+        if (v < N) {
+            const uint32_t f = sel_flags(q, x, cand, v, tau, take_all, key);
+            gt += f & 1u;
+            eq += f >> 1;
+        }
+    }
+    for (int m = 1; m < 64; m <<= 1) { gt += __shfl_xor(gt, m); eq += __shfl_xor(eq, m); }
+    if ((threadIdx.x & 63) == 0) { sg[threadIdx.x >> 6] = gt; se[threadIdx.x >> 6] = eq; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        blk[2 * blockIdx.x] = sg[0] + sg[1] + sg[2] + sg[3];
+        blk[2 * blockIdx.x + 1] = se[0] + se[1] + se[2] + se[3];
+    }
+}
+
+// exclusive scan of the per-block (gt, eq) pairs, single workgroup
+__global__ __launch_bounds__(256) void k_topk_scan2(int n_blk, const uint32_t *__restrict__ blk,
+                                                    uint32_t *__restrict__ blk_scan,
+                                                    const uint32_t *__restrict__ state, int32_t *__restrict__ count) {
+    __shared__ uint32_t sg[256], se[256];
+    const int tid = threadIdx.x;
+    const int per = (n_blk + 255) / 256;
+    const int b0 = tid * per, b1 = min(n_blk, b0 + per);
+    uint32_t gt = 0, eq = 0;
+    for (int b = b0; b < b1; ++b) { gt += blk[2 * b]; eq += blk[2 * b + 1]; }
+    sg[tid] = gt; se[tid] = eq;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t cg = 0, ce = 0;
+        for (int i = 0; i < 256; ++i) {
+            const uint32_t tg = sg[i], te = se[i];
+            sg[i] = cg; se[i] = ce;
+            cg += tg; ce += te;
+        }
+        count[0] = (int32_t)state[4];
+    }
+    __syncthreads();
+    gt = sg[tid]; eq = se[tid];
+    for (int b = b0; b < b1; ++b) {
+        blk_scan[2 * b] = gt; blk_scan[2 * b + 1] = eq;
+        gt += blk[2 * b]; eq += blk[2 * b + 1];
+    }
+}
+
+__global__ __launch_bounds__(256) void k_topk_scan3(int N, const float *__restrict__ q, const float *__restrict__ x,
+                                                    const uint8_t *__restrict__ cand,
+                                                    const uint32_t *__restrict__ state,
+                                                    const uint32_t *__restrict__ blk_scan,
+                                                    uint32_t *__restrict__ keys, int32_t *__restrict__ ids) {
+    __shared__ uint32_t sg[4], se[4];
+    const uint32_t tau = state[0];
+    const bool take_all = state[3] != 0;
+    const uint32_t need = take_all ? 0u : state[1];
+    const int base = blockIdx.x * kScanBlock + threadIdx.x * 8;
+    uint32_t f[8], key[8];
+    uint32_t gt = 0, eq = 0;
+    for (int i = 0; i < 8; ++i) {
+        const int v = base + i;
+        key[i] = 0;
+        f[i] = v < N ? sel_flags(q, x, cand, v, tau, take_all, key[i]) : 0u;
+        gt += f[i] & 1u;
+        eq += f[i] >> 1;
+    }
+    // exclusive prefix over the threads of the block: inclusive wave scan, then wave bases
+    uint32_t ig = gt, ie = eq;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int m = 1; m < 64; m <<= 1) {
+        const uint32_t tg = __shfl_up(ig, m), te = __shfl_up(ie, m);
+        if (lane >= m) { ig += tg; ie += te; }
+    }
+    if (lane == 63) { sg[wave] = ig; se[wave] = ie; }
+    __syncthreads();
+    uint32_t pg = blk_scan[2 * blockIdx.x] + ig - gt, pe = blk_scan[2 * blockIdx.x + 1] + ie - eq;
+    for (int w = 0; w < wave; ++w) { pg += sg[w]; pe += se[w]; }
+    for (int i = 0; i < 8; ++i) {
+        if (f[i] & 1u) {
+            const uint32_t pos = pg + min(pe, need);
+            keys[pos] = key[i]; ids[pos] = base + i;
+            ++pg;
+        } else if (f[i] & 2u) {
+            if (pe < need) {
+                const uint32_t pos = pg + pe;
+                keys[pos] = key[i]; ids[pos] = base + i;
+            }
+            ++pe;
+        }
+    }
+}
+
+// ---- stable LSD radix sort of n = state[4] (key, id) pairs by key descending, 8 bits per pass ----
+__global__ __launch_bounds__(64) void k_sort_hist(int pass, int n_blk, const uint32_t *__restrict__ state,
+                                                  const uint32_t *__restrict__ keys, uint32_t *__restrict__ cnt) {
+    __shared__ uint32_t h[256];
+    const int n = (int)state[4];
+    for (int i = threadIdx.x; i < 256; i += 64) h[i] = 0;
+    __syncthreads();
+    const int b = blockIdx.x * kSortTile, e = min(n, b + kSortTile);
+    for (int i = b + threadIdx.x; i < e; i += 64) atomicAdd(&h[((~keys[i]) >> (8 * pass)) & 255u], 1u);
+    __syncthreads();
+    for (int d = threadIdx.x; d < 256; d += 64) cnt[(size_t)d * n_blk + blockIdx.x] = h[d];
+}
+
+__global__ __launch_bounds__(256) void k_sort_scan(int n_blk, uint32_t *__restrict__ cnt) {
+    __shared__ uint32_t tot[256];
+    const int d = threadIdx.x;
+    uint32_t s = 0;
+    for (int b = 0; b < n_blk; ++b) s += cnt[(size_t)d * n_blk + b];
+    tot[d] = s;
+    __syncthreads();
+    if (d == 0) {
+        uint32_t c = 0;
+        for (int i = 0; i < 256; ++i) { const uint32_t t = tot[i]; tot[i] = c; c += t; }
+    }
+    __syncthreads();
+    s = tot[d];
+    for (int b = 0; b < n_blk; ++b) {
+        const uint32_t t = cnt[(size_t)d * n_blk + b];
+        cnt[(size_t)d * n_blk + b] = s;
+        s += t;
+    }
+}
+
+__global__ __launch_bounds__(64) void k_sort_scatter(int pass, int n_blk, const uint32_t *__restrict__ state,
+                                                     const uint32_t *__restrict__ keys_in,
+                                                     const int32_t *__restrict__ ids_in,
+                                                     const uint32_t *__restrict__ cnt, uint32_t *__restrict__ keys_out,
+                                                     int32_t *__restrict__ ids_out) {
+    __shared__ uint32_t base[256];
+    const int n = (int)state[4];
+    const int lane = threadIdx.x;
+    for (int d = lane; d < 256; d += 64) base[d] = cnt[(size_t)d * n_blk + blockIdx.x];
+    __syncthreads();
+    const int b = blockIdx.x * kSortTile, e = min(n, b + kSortTile);
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    for (int i0 = b; i0 < e; i0 += 64) {
+        const int i = i0 + lane;
+        const bool valid = i < e;
+        const uint32_t key = valid ? keys_in[i] : 0u;
+        const int32_t id = valid ? ids_in[i] : 0;
+        const uint32_t digit = ((~key) >> (8 * pass)) & 255u;
+        uint64_t m = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const bool on = (digit >> bit) & 1u;
+            const uint64_t bm = __ballot(on);
+            m &= on ? bm : ~bm;
+        }
+        uint32_t pos = 0;
+        if (valid) pos = base[digit] + (uint32_t)__popcll(m & lt_mask);
+        __syncthreads();
+        if (valid) {
+            keys_out[pos] = key;
+            ids_out[pos] = id;
+            if ((m >> lane) == 1ull) base[digit] += (uint32_t)__popcll(m);  // highest lane of its digit group
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void k_topk_write(int k, const uint32_t *__restrict__ state,
+                                                    const uint32_t *__restrict__ keys, const int32_t *__restrict__ ids,
+                                                    int32_t *__restrict__ idx, float *__restrict__ val) {
+    const int n = (int)state[4];
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < k; i += gridDim.x * 256) {
+        idx[i] = i < n ? ids[i] : -1;
+        val[i] = i < n ? key_score(keys[i]) : -INFINITY;
+    }
+}
+
+#define S2V_CHECK_LAUNCH()                         \
+    do {                                           \
+        hipError_t e_ = hipGetLastError();         \
+        if (e_ != hipSuccess) return e_;           \
+    } while (0)
+
+hipError_t launch_topk(hipStream_t st, int N, const float *q, const float *x, const uint8_t *cand, int k,
+                       const SelectScratch &sc, int32_t *idx, float *val, int32_t *count) {
+    k_topk_init<<<1, 256, 0, st>>>(sc.hist, sc.state, k);
+    S2V_CHECK_LAUNCH();
+    const int n_scan_blk = (N + kScanBlock - 1) / kScanBlock;
+    uint32_t *blk = sc.blk, *blk_scan = sc.blk + 2 * (size_t)n_scan_blk;
+    if (N > 0) {
+        const int hist_grid = min((N + 255) / 256, 256 * 8);
+        for (int pass = 0; pass < 4; ++pass) {
+            k_topk_hist<<<hist_grid, 256, 0, st>>>(N, pass, q, x, cand, sc.hist, sc.state);
+            S2V_CHECK_LAUNCH();
+            k_topk_pick<<<1, 64, 0, st>>>(pass, sc.hist, sc.state);
+            S2V_CHECK_LAUNCH();
+        }
+        k_topk_scan1<<<n_scan_blk, 256, 0, st>>>(N, q, x, cand, sc.state, blk);
+        S2V_CHECK_LAUNCH();
+    }
+    k_topk_scan2<<<1, 256, 0, st>>>(n_scan_blk, blk, blk_scan, sc.state, count);
+    S2V_CHECK_LAUNCH();
+    if (N > 0) {
+        k_topk_scan3<<<n_scan_blk, 256, 0, st>>>(N, q, x, cand, sc.state, blk_scan, sc.keys[0], sc.ids[0]);
+        S2V_CHECK_LAUNCH();
+        const int n_sort_blk = (k + kSortTile - 1) / kSortTile;
+        for (int pass = 0; pass < 4; ++pass) {
+            const int a = pass & 1, b = a ^ 1;
+            k_sort_hist<<<n_sort_blk, 64, 0, st>>>(pass, n_sort_blk, sc.state, sc.keys[a], sc.sort_cnt);
+            S2V_CHECK_LAUNCH();
+            k_sort_scan<<<1, 256, 0, st>>>(n_sort_blk, sc.sort_cnt);
+            S2V_CHECK_LAUNCH();
+            k_sort_scatter<<<n_sort_blk, 64, 0, st>>>(pass, n_sort_blk, sc.state, sc.keys[a], sc.ids[a], sc.sort_cnt,
+                                                      sc.keys[b], sc.ids[b]);
+            S2V_CHECK_LAUNCH();
+        }
+    }
+    k_topk_write<<<min((k + 255) / 256, 1024), 256, 0, st>>>(k, sc.state, sc.keys[0], sc.ids[0], idx, val);
+    return hipGetLastError();
+}
+
+}  // namespace s2v

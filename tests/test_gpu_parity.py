@@ -1,0 +1,208 @@
+"""GPU parity: the HIP path, called through the C interface, against the float64 CPU oracle
+on the same seeded inputs.  Bars: embeddings, graph sums and scores within 1e-4 relative
+error (entries below 1e-2 of their row's largest entry are measured against that floor, see
+gpu_util.rel_err); selection bit-exact given the same float32 scores, and consistent with
+the oracle's float64 scores outside a 1e-4 relative band."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _graph(kind, seed):
+    if kind == "er_small":
+        return si.erdos_renyi_gnp(300, 0.05, seed)          # ragged: 300 = 4 tiles + 44 rows
+    if kind == "er_dense":
+        return si.erdos_renyi_gnp(257, 0.4, seed)           # rows longer than one 64-entry chunk
+    if kind == "ba":
+        return si.barabasi_albert(1000, 4, seed)
+    if kind == "star":
+        return si.star_graph(5000)                          # one row of 5000 entries
+    if kind == "edgeless":
+        return si.edgeless(100)
+    if kind == "tiny":
+        return si.erdos_renyi_gnp(5, 0.8, seed)
+    if kind == "batch":
+        parts = [si.barabasi_albert(n, 2, seed + i) if n > 2 else si.edgeless(n)
+                 for i, n in enumerate((40, 1, 77, 3, 1500, 2, 64))]
+        return si.block_diagonal(parts)
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("kind", ["er_small", "er_dense", "ba", "star", "edgeless", "tiny", "batch"])
+@pytest.mark.parametrize("p,T", [(32, 3), (64, 4), (64, 1), (32, 2)])
+def test_forward_and_scores_match_oracle(oracle_mod, kind, p, T):
+    print(f"case kind={kind} p={p} T={T}", flush=True)
+    g = _graph(kind, 7)
+    if kind in ("er_small", "batch"):
+        g.w = si.symmetric_edge_weights(g, 11, 0.5, 1.5)
+    if kind == "er_dense":
+        g.w = si.signed_edge_weights(g, 12, 1.0)            # both signs: exercises s- and theta4's two branches
+    std = 0.1 if kind not in ("star", "er_dense") else 0.02
+    theta = si.thetas(p, 100 + p + T, std)
+    x = si.node_flags(g.n, 0.2, 5)
+    dev = gu.Device(g, p, T)
+    out = dev.forward(theta, x, save=True)
+    mu, hist = oracle_mod.embed(g.rowptr, g.colidx, g.w, theta, x[0], T, history=True)
+    gsum, q = oracle_mod.q_scores(g.graph_off, theta, mu)
+    for t in range(T):
+        assert gu.rel_err(out["saved"][t, :, 0, :], hist[t]) <= TOL, f"round {t + 1}"
+    assert gu.rel_err(out["mu"][:, 0, :], mu) <= TOL
+    assert gu.rel_err(out["gsum"][0], gsum) <= TOL
+    assert gu.rel_err(out["q"][0], q) <= TOL
+
+
+@pytest.mark.parametrize("S", [2, 5, 16])
+def test_forward_many_states(oracle_mod, S):
+    print(f"case states S={S}", flush=True)
+    p, T = 64, 3
+    g = si.barabasi_albert(700, 3, 3)
+    g.w = si.symmetric_edge_weights(g, 1, 0.5, 1.5)
+    theta = si.thetas(p, 42)
+    x = si.node_flags(g.n, 0.1, 9, n_states=S)
+    dev = gu.Device(g, p, T, S=S)
+    out = dev.forward(theta, x)
+    for s in range(S):
+        mu, gsum, q = gu.oracle_forward(oracle_mod, g, theta, x[s], T)
+        assert gu.rel_err(out["mu"][:, s, :], mu) <= TOL
+        assert gu.rel_err(out["gsum"][s], gsum) <= TOL
+        assert gu.rel_err(out["q"][s], q) <= TOL
+
+
+def test_forward_without_saved_buffers_matches_saved(oracle_mod):
+    # ping-pong path (mu_saved == NULL) must give the same bits as the saved path
+    p, T = 64, 4
+    g = si.erdos_renyi_gnp(500, 0.03, 2)
+    theta = si.thetas(p, 1)
+    x = si.node_flags(g.n, 0.1, 1)
+    dev = gu.Device(g, p, T)
+    a = dev.forward(theta, x, save=True)
+    b = dev.forward(theta, x, save=False)
+    assert np.array_equal(a["mu"], b["mu"]) and np.array_equal(a["q"], b["q"])
+    assert np.array_equal(a["mu"][:, 0, :], a["saved"][T - 1, :, 0, :])
+
+
+def test_permutation_equivariance_on_gpu():
+    p, T = 64, 3
+    g = si.barabasi_albert(900, 5, 4)
+    theta = si.thetas(p, 3)
+    rng = np.random.default_rng(0)
+    x = si.node_flags(g.n, 0.2, 2)
+    perm = rng.permutation(g.n)
+    g2 = si.relabel(g, perm)
+    x2 = np.empty_like(x)
+    x2[0, perm] = x[0]
+    a = gu.Device(g, p, T).forward(theta, x)
+    b = gu.Device(g2, p, T).forward(theta, x2)
+    # neighbour order changes with the labels, so sums agree to rounding, not bitwise
+    assert gu.rel_err(b["mu"][perm, 0, :], a["mu"][:, 0, :]) <= 1e-5
+    assert gu.rel_err(b["q"][0, perm], a["q"][0]) <= 1e-5
+
+
+# ---- selection ------------------------------------------------------------------------------
+
+def _select_cases():
+    rng = np.random.default_rng(5)
+    n = 10000
+    q_ties = np.round(rng.normal(size=n), 1).astype(np.float32)        # heavy ties
+    q_cont = rng.normal(size=n).astype(np.float32)
+    q_neg0 = q_cont.copy()
+    q_neg0[::3] = -0.0
+    q_neg0[1::3] = 0.0
+    x = (rng.random(n) < 0.3).astype(np.float32)
+    return n, {"ties": q_ties, "cont": q_cont, "zeros": q_neg0, "const": np.full(n, 2.5, np.float32)}, x
+
+
+@pytest.mark.parametrize("k", [1, 2, 8, 100, 1024, 1025, 6999, 20000])
+@pytest.mark.parametrize("name", ["ties", "cont", "zeros", "const"])
+def test_topk_bit_exact_on_same_scores(oracle_mod, name, k):
+    print(f"case topk {name} k={k}", flush=True)
+    n, qs, x = _select_cases()
+    q = qs[name]
+    g = si.edgeless(n)
+    dev = gu.Device(g, 32, 1, k_max=k)
+    idx, val, cnt = dev.select(q, x[None][0], None, k)
+    oi, ov, oc = oracle_mod.select(None, q, x, None, k)
+    assert cnt[0] == oc[0]
+    assert np.array_equal(idx, oi)
+    take = oc[0]
+    assert np.array_equal(val[0, :take].astype(np.float64), ov[0, :take])
+    assert np.isneginf(val[0, take:]).all()
+
+
+def test_topk_candidate_mask_and_empty(oracle_mod):
+    n, qs, x = _select_cases()
+    q = qs["ties"]
+    g = si.edgeless(n)
+    dev = gu.Device(g, 32, 1, k_max=64)
+    cand = (np.random.default_rng(1).random(n) < 0.01).astype(np.uint8)
+    for k in (1, 64):
+        idx, val, cnt = dev.select(q, x, cand, k)
+        oi, ov, oc = oracle_mod.select(None, q, x, cand, k)
+        assert np.array_equal(idx, oi) and cnt[0] == oc[0]
+    for k in (1, 5):
+        idx, val, cnt = dev.select(q, np.ones(n, np.float32), None, k)   # no candidates at all
+        assert cnt[0] == 0 and (idx == -1).all() and np.isneginf(val).all()
+
+
+def test_segmented_argmax_bit_exact(oracle_mod):
+    parts = [si.edgeless(n) for n in (5, 1, 3000, 1024, 1025, 2, 700)]
+    g = si.block_diagonal(parts)
+    rng = np.random.default_rng(3)
+    q = np.round(rng.normal(size=g.n), 1).astype(np.float32)
+    x = (rng.random(g.n) < 0.4).astype(np.float32)
+    x[g.graph_off[1]:g.graph_off[2]] = 1.0                                   # a graph with no candidate
+    dev = gu.Device(g, 32, 1)
+    idx, val, cnt = dev.select(q, x, None, 1)
+    oi, ov, oc = oracle_mod.select(g.graph_off, q, x, None, 1)
+    assert np.array_equal(idx, oi) and np.array_equal(cnt, oc)
+    ok = oc > 0
+    assert np.array_equal(val[ok, 0].astype(np.float64), ov[ok, 0])
+
+
+# ---- benchmark configurations ---------------------------------------------------------------
+
+def _run_config(oracle_mod, c, scale):
+    w = si.config(c, scale)
+    g = w.graph
+    print(f"config {c} scale {scale}: n={g.n} nnz={g.nnz} k={w.k}", flush=True)
+    dev = gu.Device(g, w.p, w.T, k_max=w.k)
+    out = dev.forward(w.theta, w.x)
+    mu, gsum, q = gu.oracle_forward(oracle_mod, g, w.theta, w.x[0], w.T)
+    errs = (gu.rel_err(out["mu"][:, 0, :], mu), gu.rel_err(out["gsum"][0], gsum), gu.rel_err(out["q"][0], q))
+    print("rel errors mu/gsum/q:", errs, flush=True)
+    assert max(errs) <= TOL
+    # selection on the GPU's own float32 scores: bit-exact against the oracle's rule
+    idx, val, cnt = dev.select(out["q"][0], w.x[0], None, w.k)
+    oi, ov, oc = oracle_mod.select(g.graph_off, out["q"][0], w.x[0], None, w.k)
+    assert np.array_equal(idx, oi) and np.array_equal(cnt, oc)
+    # and end to end against the oracle's float64 scores, outside the 1e-4 band
+    offs = g.offsets()
+    exact = 0
+    for b in range(g.n_graphs):
+        lo, hi = offs[b], offs[b + 1]
+        mask = np.zeros(g.n, dtype=bool)
+        mask[lo:hi] = w.x[0, lo:hi] == 0
+        exact += gu.check_selection_with_margin(idx[b], cnt[b], q, mask, w.k)
+    print("positions compared exactly:", exact, flush=True)
+
+
+def test_config1_full(oracle_mod):
+    _run_config(oracle_mod, 1, 1.0)
+
+
+def test_config2_full(oracle_mod):
+    _run_config(oracle_mod, 2, 1.0)
+
+
+def test_config3_scaled(oracle_mod):
+    _run_config(oracle_mod, 3, 0.05)
+
+
+def test_config4_scaled(oracle_mod):
+    _run_config(oracle_mod, 4, 0.02)
