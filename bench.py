@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the structure2vec / deep-Q hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-train] [--no-cpu-baseline]
+
+A "step" is one RL inference step on the 30M-edge workload (benchmark configuration 4:
+Erdos-Renyi n = 2e6, average degree 30, p = 64, T = 4): embedding (s2v_embed_fwd), scores
+(s2v_q_score) and top-k selection with k = 1 % of the candidates (s2v_select_topk), with all
+inputs resident in HBM.  The one-time graph preparation is timed separately.  Also reported:
+the training step of configuration 5 (Barabasi-Albert n = 1e6, 16 states, 4 SGD iterations),
+the live HIP-event time of the fused embedding-round kernel against the HBM roofline, and the
+float64 CPU oracle timed on the host cores as a baseline.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def round_algorithmic_bytes(n, nnz, p, S=1):
+    """Bytes one fused embedding round must move when no gathered row is reused:
+    rowptr + colidx + one p-float row per stored entry + x, s+, s- + the output rows."""
+    return 4 * (n + 1) + 4 * nnz + 4 * p * nnz * S + 12 * n * S + 4 * p * n * S
+
+
+def read_traffic(path):
+    """HBM bytes per launch of the embedding-round kernel from a committed rocprofv3 counter
+    summary (FETCH_SIZE + WRITE_SIZE, scaled); None if the summary is not there."""
+    try:
+        for line in open(path):
+            if line.startswith("HBM_BYTES_PER_LAUNCH="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def upload(s2v, torch, g):
+    return s2v.Graph(
+        torch.from_numpy(g.rowptr).cuda(), torch.from_numpy(g.colidx).cuda(),
+        None if g.w is None else torch.from_numpy(g.w).cuda(),
+        None if g.graph_off is None else torch.from_numpy(g.graph_off).cuda())
+
+
+def bench_inference(args, s2v, torch):
+    t0 = time.time()
+    w = si.config(4, args.scale)
+    g = w.graph
+    log(f"[bench] config 4 generated: n={g.n} nnz={g.nnz} k={w.k} ({time.time() - t0:.1f}s)")
+    ctx = s2v.Context()
+    torch.cuda.reset_peak_memory_stats()
+    graph = upload(s2v, torch, g)
+    prm = s2v.Params.from_numpy(w.theta)
+    N, p, T, k = g.n, w.p, w.T, w.k
+    ws = torch.empty(ctx.s2v_workspace_bytes(graph, p, T, 1, k), dtype=torch.uint8, device="cuda")
+    x = torch.from_numpy(w.x).cuda()
+    mu = torch.empty((N, 1, p), device="cuda")
+    gsum = torch.empty((1, 1, p), device="cuda")
+    q = torch.empty((1, N), device="cuda")
+    idx = torch.empty((1, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((1, k), device="cuda")
+    cnt = torch.empty((1,), dtype=torch.int32, device="cuda")
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.s2v_graph_prepare(graph, ws)
+    torch.cuda.synchronize()
+    prepare_ms = (time.perf_counter() - t0) * 1e3
+
+    def step():
+        ctx.s2v_embed_fwd(graph, prm, x, T, 1, mu, None, gsum, ws)
+        ctx.s2v_q_score(graph, prm, mu, gsum, 1, q, ws)
+        ctx.s2v_select_topk(graph, q[0], x[0], None, k, idx, val, cnt, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.s2v_profile_begin(args.steps * (T - 1) + 4)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    (n_round, ms_round), _ = ctx.s2v_profile_end()
+    peak_mb = torch.cuda.max_memory_allocated() / 2**20
+    round_ms = ms_round / max(n_round, 1)
+    alg = round_algorithmic_bytes(N, g.nnz, p)
+    achieved = alg / (round_ms * 1e-3) / 1e9
+    log(f"[bench] inference {ms:.3f} ms/step; embedding round {round_ms:.3f} ms x {n_round}; "
+        f"{achieved:.0f} GB/s algorithmic; prepare {prepare_ms:.1f} ms; peak {peak_mb:.0f} MiB")
+    out = dict(
+        ms=ms, prepare_ms=prepare_ms, peak_device_mib=peak_mb, n=N, nnz=g.nnz, k=k, p=p, T=T,
+        round_ms=round_ms, round_launches=n_round, alg_bytes=alg, achieved_gbs=achieved,
+        selected_count=int(cnt.item()), first_selected=int(idx[0, 0].item()),
+    )
+    return out, w
+
+
+def bench_training(args, s2v, torch):
+    t0 = time.time()
+    w = si.config(5, args.scale)
+    g = w.graph
+    S = w.x.shape[0]
+    log(f"[bench] config 5 generated: n={g.n} nnz={g.nnz} S={S} ({time.time() - t0:.1f}s)")
+    ctx = s2v.Context()
+    graph = upload(s2v, torch, g)
+    N, p, T = g.n, w.p, w.T
+    ws = torch.empty(ctx.s2v_workspace_bytes(graph, p, T, S, 1, True), dtype=torch.uint8, device="cuda")
+    ctx.s2v_graph_prepare(graph, ws)
+    x = torch.from_numpy(w.x).cuda()
+    saved = torch.empty((T, N, S, p), device="cuda")
+    gsum = torch.empty((S, 1, p), device="cuda")
+    action = torch.from_numpy(w.action).cuda()
+    target = torch.from_numpy(w.target).cuda()
+    loss = torch.empty((1,), device="cuda")
+    qp = torch.empty((S,), device="cuda")
+    theta0 = s2v.Params.from_numpy(w.theta)
+    prm = s2v.Params.from_numpy(w.theta)
+    grads = s2v.Params.zeros_like(prm)
+
+    def step():
+        # every step starts from the same parameters, then takes w.iters SGD iterations (Sec. 4.5.2)
+        for k_ in si.THETA_NAMES:
+            prm.t[k_].copy_(theta0.t[k_])
+        for _ in range(w.iters):
+            ctx.s2v_embed_fwd(graph, prm, x, T, S, None, saved, gsum, ws)
+            ctx.s2v_embed_bwd(graph, prm, x, T, S, saved, gsum, action, target, loss, qp, grads, ws)
+            ctx.s2v_sgd_step(prm, grads, w.lr)
+
+    steps = max(1, min(args.steps, args.train_steps))
+    for _ in range(1):
+        step()
+    torch.cuda.synchronize()
+    ctx.s2v_profile_begin(steps * w.iters * 2 * (T - 1) + 4)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    (n_f, ms_f), (n_b, ms_b) = ctx.s2v_profile_end()
+    alg = round_algorithmic_bytes(N, g.nnz, p, S)
+    out = dict(ms_per_step=ms, ms_per_iteration=ms / w.iters, steps=steps, iterations=w.iters, S=S, n=N, nnz=g.nnz,
+               fwd_round_ms=ms_f / max(n_f, 1), bwd_round_ms=ms_b / max(n_b, 1),
+               fwd_round_gbs=alg / (ms_f / max(n_f, 1) * 1e-3) / 1e9 if n_f else None,
+               bwd_round_gbs=(alg + 4 * p * N * S) / (ms_b / max(n_b, 1) * 1e-3) / 1e9 if n_b else None)
+    log(f"[bench] training {ms:.1f} ms/step ({w.iters} iterations); fwd round {out['fwd_round_ms']:.2f} ms, "
+        f"bwd round {out['bwd_round_ms']:.2f} ms")
+    return out
+
+
+def cpu_baseline(w):
+    """The float64 oracle, as it stands, on the same inference step (embed + scores + top-k)."""
+    import oracle
+
+    oracle.build()
+    g = w.graph
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    t0 = time.perf_counter()
+    mu = oracle.embed(g.rowptr, g.colidx, g.w, w.theta, w.x[0], w.T)
+    _, q = oracle.q_scores(g.graph_off, w.theta, mu)
+    oracle.select(g.graph_off, q, w.x[0], None, w.k)
+    ms = (time.perf_counter() - t0) * 1e3
+    log(f"[bench] cpu oracle: {ms:.0f} ms on {threads} threads")
+    return dict(value=ms, unit="ms", cores=threads, kind="oracle",
+                sample=f"the whole configuration-4 inference step (n={g.n}, nnz={g.nnz}), one repetition")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--train-steps", type=int, default=3)
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the graphs (debugging only; invalid as a result)")
+    ap.add_argument("--no-train", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+
+    import paper_2105_08764_amd as s2v
+
+    s2v.load_library()  # fails loudly when the HIP library has not been built
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    inf, w4 = bench_inference(args, s2v, torch)
+    train = None
+    if not args.no_train:
+        torch.cuda.empty_cache()
+        train = bench_training(args, s2v, torch)
+    cpu = None if args.no_cpu_baseline else cpu_baseline(w4)
+
+    traffic = read_traffic(os.path.join(ROOT, "profiles", "k_round_cfg4_pmc.txt"))
+    line = {
+        "metric": "ms per RL inference step at 30M edges (embed + Q + top-k)",
+        "value": round(inf["ms"], 4),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(inf["ms"], 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "cfg4_er2m: Erdos-Renyi n=2e6, avg degree 30 (60M stored entries), w~U(0.5,1.5), "
+                        "x~Bern(0.05), p=64, T=4, top-k with k = 1% of candidates",
+            "n_nodes": inf["n"], "nnz": inf["nnz"], "p": inf["p"], "T": inf["T"], "k": inf["k"],
+            "scale": args.scale,
+        },
+        "roofline": {
+            "kernel": "k_round<64> (fused CSR gather + theta2 product + relu, rounds 2..T)",
+            "bound": "hbm",
+            "achieved": round(inf["achieved_gbs"], 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(inf["achieved_gbs"] / HBM_PEAK_GBS, 4),
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": inf["alg_bytes"],
+            "avg_launch_ms": round(inf["round_ms"], 4),
+            "launches_timed": inf["round_launches"],
+        },
+        "cpu_baseline": cpu,
+        "prepare_ms": round(inf["prepare_ms"], 2),
+        "peak_device_mib": round(inf["peak_device_mib"], 1),
+        "training": train,
+        "paper_context": {"inference_step_s_1xV100": 23.8, "training_step_s_1xV100": 316.4,
+                          "note": "Summit, ER N=21000 (~33M edges), K=32, L=2; another machine and graph shape"},
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

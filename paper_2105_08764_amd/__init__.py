@@ -27,7 +27,7 @@ THETA_NAMES = ("theta1", "theta2", "theta3", "theta4", "theta5", "theta6", "thet
 EXPORTS = (
     "s2v_status_str", "s2v_create", "s2v_destroy", "s2v_last_hip_error", "s2v_workspace_bytes",
     "s2v_graph_prepare", "s2v_embed_fwd", "s2v_q_score", "s2v_select_topk", "s2v_embed_bwd",
-    "s2v_sgd_step", "s2v_adaptive_d",
+    "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end",
 )
 
 
@@ -218,6 +218,16 @@ class Context:
                                       ctypes.c_void_p(_dp(target)), ctypes.c_void_p(_dp(loss)),
                                       ctypes.c_void_p(_dp(q_pred)), ctypes.byref(grads.c), ctypes.c_void_p(_dp(ws)),
                                       ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_embed_bwd")
+
+    def s2v_profile_begin(self, max_launches: int) -> None:
+        _check(self.lib.s2v_profile_begin(self.handle, ctypes.c_int32(max_launches)), "s2v_profile_begin")
+
+    def s2v_profile_end(self):
+        """((n_fwd_round, ms_fwd_round), (n_bwd_round, ms_bwd_round))"""
+        n = (ctypes.c_int32 * 2)()
+        ms = (ctypes.c_float * 2)()
+        _check(self.lib.s2v_profile_end(self.handle, n, ms), "s2v_profile_end")
+        return (int(n[0]), float(ms[0])), (int(n[1]), float(ms[1]))
 
     def s2v_sgd_step(self, params: Params, grads: Params, lr: float) -> None:
         _check(self.lib.s2v_sgd_step(self.handle, ctypes.byref(params.c), ctypes.byref(grads.c), ctypes.c_float(lr)),

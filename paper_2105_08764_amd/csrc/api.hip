@@ -125,10 +125,19 @@ bool p_supported(int p) { return p == 32 || p == 64; }
 
 }  // namespace
 
+struct ProfSpan {
+    hipEvent_t start, stop;
+    int kind;
+};
+
 struct s2v_ctx {
     hipStream_t stream;
     int32_t last_hip;
     std::vector<Prepared> prepared;
+    // optional timing of the two gather kernels (s2v_profile_begin / s2v_profile_end)
+    bool profiling = false;
+    std::vector<ProfSpan> spans;   // pre-created event pairs
+    size_t spans_used = 0;
 };
 
 namespace {
@@ -143,6 +152,22 @@ int32_t hip_fail(s2v_ctx *ctx, hipError_t e) {
         hipError_t e_ = (expr);                        \
         if (e_ != hipSuccess) return hip_fail(ctx, e_); \
     } while (0)
+
+// Brackets one kernel launch with events on the context's stream while profiling is on.
+struct SpanGuard {
+    s2v_ctx *ctx;
+    ProfSpan *span = nullptr;
+    SpanGuard(s2v_ctx *c, int kind) : ctx(c) {
+        if (c->profiling && c->spans_used < c->spans.size()) {
+            span = &c->spans[c->spans_used++];
+            span->kind = kind;
+            (void)hipEventRecord(span->start, c->stream);
+        }
+    }
+    ~SpanGuard() {
+        if (span) (void)hipEventRecord(span->stop, ctx->stream);
+    }
+};
 
 int32_t check_graph(const s2v_graph *g) {
     if (!g) return S2V_ERR_INVALID_ARG;
@@ -218,8 +243,55 @@ int32_t s2v_create(void *hip_stream, s2v_ctx **out) {
     return S2V_OK;
 }
 
+static void drop_spans(s2v_ctx *ctx) {
+    for (ProfSpan &sp : ctx->spans) {
+        (void)hipEventDestroy(sp.start);
+        (void)hipEventDestroy(sp.stop);
+    }
+    ctx->spans.clear();
+    ctx->spans_used = 0;
+    ctx->profiling = false;
+}
+
 int32_t s2v_destroy(s2v_ctx *ctx) {
+    if (ctx) drop_spans(ctx);
     delete ctx;
+    return S2V_OK;
+}
+
+int32_t s2v_profile_begin(s2v_ctx *ctx, int32_t max_launches) {
+    if (!ctx || max_launches < 1) return S2V_ERR_INVALID_ARG;
+    drop_spans(ctx);
+    ctx->spans.reserve(max_launches);
+    for (int i = 0; i < max_launches; ++i) {
+        ProfSpan sp;
+        sp.kind = 0;
+        S2V_TRY(hipEventCreate(&sp.start));
+        hipError_t e = hipEventCreate(&sp.stop);
+        if (e != hipSuccess) {
+            (void)hipEventDestroy(sp.start);
+            return hip_fail(ctx, e);
+        }
+        ctx->spans.push_back(sp);
+    }
+    ctx->profiling = true;
+    return S2V_OK;
+}
+
+int32_t s2v_profile_end(s2v_ctx *ctx, int32_t *n_launches, float *total_ms) {
+    if (!ctx || !n_launches || !total_ms) return S2V_ERR_INVALID_ARG;
+    n_launches[0] = n_launches[1] = 0;
+    total_ms[0] = total_ms[1] = 0.f;
+    ctx->profiling = false;
+    S2V_TRY(hipStreamSynchronize(ctx->stream));
+    for (size_t i = 0; i < ctx->spans_used; ++i) {
+        float ms = 0.f;
+        S2V_TRY(hipEventElapsedTime(&ms, ctx->spans[i].start, ctx->spans[i].stop));
+        const int k = ctx->spans[i].kind == S2V_PROFILE_BWD_ROUND ? 1 : 0;
+        n_launches[k] += 1;
+        total_ms[k] += ms;
+    }
+    drop_spans(ctx);
     return S2V_OK;
 }
 
@@ -327,9 +399,11 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         return ((T - t) % 2 == 0) ? mu_out : tmp;
     };
     S2V_TRY(launch_round1(st, p, N, S, x, s_pos, s_neg, params->theta1, qvec, dest(1)));
-    for (int t = 2; t <= T; ++t)
+    for (int t = 2; t <= T; ++t) {
+        SpanGuard span(ctx, S2V_PROFILE_FWD_ROUND);
         S2V_TRY(launch_round(st, p, N, S, g->rowptr, g->colidx, dest(t - 1), dest(t), x, s_pos, s_neg,
                              params->theta1, params->theta2, qvec));
+    }
     float *muT = dest(T);
     if (mu_saved && mu_out && mu_out != muT && nsp > 0)
         S2V_TRY(hipMemcpyAsync(mu_out, muT, sizeof(float) * nsp, hipMemcpyDeviceToDevice, st));
@@ -450,6 +524,7 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         float *dc_part = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)slot * kBwdGrid) * 3 * p;
         float *d2_part = sc.d2_part + (size_t)slot * kBwdGrid * p * p;
         const float *mu_prev = mu_saved + (size_t)(t - 2) * nsp;
+        SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
         S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, g->colidx, sc.dz[cur], mu_prev, sc.dz[cur ^ 1], x, s_pos,
                                  s_neg, params->theta2, dc_part, d2_part));
         cur ^= 1;
