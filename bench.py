@@ -97,16 +97,17 @@ def bench_inference(args, s2v, torch):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    (n_round, ms_round), _ = ctx.s2v_profile_end()
+    (n_round, ms_round), _, (n_r2, ms_r2) = ctx.s2v_profile_end()
     peak_mb = torch.cuda.max_memory_allocated() / 2**20
     round_ms = ms_round / max(n_round, 1)
     alg = round_algorithmic_bytes(N, g.nnz, p)
     achieved = alg / (round_ms * 1e-3) / 1e9
-    log(f"[bench] inference {ms:.3f} ms/step; embedding round {round_ms:.3f} ms x {n_round}; "
+    log(f"[bench] inference {ms:.3f} ms/step; round 2 (from scalars) {ms_r2 / max(n_r2, 1):.3f} ms; "
+        f"gather round {round_ms:.3f} ms x {n_round}; "
         f"{achieved:.0f} GB/s algorithmic; prepare {prepare_ms:.1f} ms; peak {peak_mb:.0f} MiB")
     out = dict(
         ms=ms, prepare_ms=prepare_ms, peak_device_mib=peak_mb, n=N, nnz=g.nnz, k=k, p=p, T=T,
-        round_ms=round_ms, round_launches=n_round, alg_bytes=alg, achieved_gbs=achieved,
+        round_ms=round_ms, round_launches=n_round, round2_ms=ms_r2 / max(n_r2, 1), alg_bytes=alg, achieved_gbs=achieved,
         selected_count=int(cnt.item()), first_selected=int(idx[0, 0].item()),
     )
     return out, w
@@ -153,10 +154,10 @@ def bench_training(args, s2v, torch):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    (n_f, ms_f), (n_b, ms_b) = ctx.s2v_profile_end()
+    (n_f, ms_f), (n_b, ms_b), (n_f2, ms_f2) = ctx.s2v_profile_end()
     alg = round_algorithmic_bytes(N, g.nnz, p, S)
     out = dict(ms_per_step=ms, ms_per_iteration=ms / w.iters, steps=steps, iterations=w.iters, S=S, n=N, nnz=g.nnz,
-               fwd_round_ms=ms_f / max(n_f, 1), bwd_round_ms=ms_b / max(n_b, 1),
+               fwd_round_ms=ms_f / max(n_f, 1), bwd_round_ms=ms_b / max(n_b, 1), fwd_round2_ms=ms_f2 / max(n_f2, 1),
                fwd_round_gbs=alg / (ms_f / max(n_f, 1) * 1e-3) / 1e9 if n_f else None,
                bwd_round_gbs=(alg + 4 * p * N * S) / (ms_b / max(n_b, 1) * 1e-3) / 1e9 if n_b else None)
     log(f"[bench] training {ms:.1f} ms/step ({w.iters} iterations); fwd round {out['fwd_round_ms']:.2f} ms, "
@@ -230,7 +231,7 @@ def main():
             "scale": args.scale,
         },
         "roofline": {
-            "kernel": "k_round<64> (fused CSR gather + theta2 product + relu, rounds 2..T)",
+            "kernel": "k_round<64,false,false,*> (fused CSR gather + theta2 product + relu, rounds 3..T)",
             "bound": "hbm",
             "achieved": round(inf["achieved_gbs"], 1),
             "peak": HBM_PEAK_GBS,
@@ -242,6 +243,7 @@ def main():
             "launches_timed": inf["round_launches"],
         },
         "cpu_baseline": cpu,
+        "round2_from_scalars_ms": round(inf["round2_ms"], 4),
         "prepare_ms": round(inf["prepare_ms"], 2),
         "peak_device_mib": round(inf["peak_device_mib"], 1),
         "training": train,

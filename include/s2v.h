@@ -183,16 +183,20 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
 int32_t s2v_sgd_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, float lr);
 
 /*
- * Optional live timing of the two gather kernels (for benchmarks; not part of the method).
+ * Optional live timing of the gather kernels (for benchmarks; not part of the method).
  * Between s2v_profile_begin and s2v_profile_end every launch of the fused embedding-round
- * kernel (kind 0: rounds 2..T of Eq. 1 inside s2v_embed_fwd) and of the fused backward-round
- * kernel (kind 1, inside s2v_embed_bwd) is bracketed by HIP events on the context's stream,
- * up to max_launches launches in total.  s2v_profile_end waits for the stream and returns,
- * per kind, the number of bracketed launches and the sum of their durations in milliseconds
- * (host arrays of two elements each).
+ * kernel and of the fused backward-round kernel is bracketed by HIP events on the context's
+ * stream, up to max_launches launches in total.  Kinds:
+ *   S2V_PROFILE_FWD_ROUND   rounds 3..T of Eq. 1 inside s2v_embed_fwd (neighbour rows read from memory)
+ *   S2V_PROFILE_BWD_ROUND   the reversed rounds inside s2v_embed_bwd
+ *   S2V_PROFILE_FWD_ROUND2  round 2 of Eq. 1 (neighbour rows recomputed from per-node scalars)
+ * s2v_profile_end waits for the stream and returns, per kind, the number of bracketed launches
+ * and the sum of their durations in milliseconds (host arrays of S2V_PROFILE_KINDS elements).
  */
 #define S2V_PROFILE_FWD_ROUND 0
 #define S2V_PROFILE_BWD_ROUND 1
+#define S2V_PROFILE_FWD_ROUND2 2
+#define S2V_PROFILE_KINDS 3
 int32_t s2v_profile_begin(s2v_ctx *ctx, int32_t max_launches);
 int32_t s2v_profile_end(s2v_ctx *ctx, int32_t *n_launches, float *total_ms);
 

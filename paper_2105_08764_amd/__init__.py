@@ -223,11 +223,11 @@ class Context:
         _check(self.lib.s2v_profile_begin(self.handle, ctypes.c_int32(max_launches)), "s2v_profile_begin")
 
     def s2v_profile_end(self):
-        """((n_fwd_round, ms_fwd_round), (n_bwd_round, ms_bwd_round))"""
-        n = (ctypes.c_int32 * 2)()
-        ms = (ctypes.c_float * 2)()
+        """[(launches, total ms)] for the kinds fwd round (from memory), bwd round, fwd round 2."""
+        n = (ctypes.c_int32 * 3)()
+        ms = (ctypes.c_float * 3)()
         _check(self.lib.s2v_profile_end(self.handle, n, ms), "s2v_profile_end")
-        return (int(n[0]), float(ms[0])), (int(n[1]), float(ms[1]))
+        return [(int(n[i]), float(ms[i])) for i in range(3)]
 
     def s2v_sgd_step(self, params: Params, grads: Params, lr: float) -> None:
         _check(self.lib.s2v_sgd_step(self.handle, ctypes.byref(params.c), ctypes.byref(grads.c), ctypes.c_float(lr)),

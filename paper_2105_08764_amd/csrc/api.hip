@@ -50,12 +50,15 @@ HeadLayout head_layout(int64_t N, int64_t G) {
     return h;
 }
 
-struct FwdLayout { size_t qvec, tmp, gpart, end; };
+struct FwdLayout { size_t qvec, info, tmp, gpart, end; };
 FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp) {
     FwdLayout f;
     Carver c(h.end);
     f.qvec = c.take(sizeof(float) * 2 * p);
-    f.gpart = c.take(sizeof(float) * (size_t)h.max_chunks * S * p);
+    f.info = c.take(sizeof(float) * (size_t)N * nodeinfo_stride(S));
+    size_t part_rows = (size_t)h.max_chunks * S;
+    if (part_rows < (size_t)kRoundGridMax) part_rows = kRoundGridMax;
+    f.gpart = c.take(sizeof(float) * part_rows * p);
     f.tmp = c.take(need_tmp ? sizeof(float) * (size_t)N * S * p : 0);
     f.end = c.off;
     return f;
@@ -280,14 +283,16 @@ int32_t s2v_profile_begin(s2v_ctx *ctx, int32_t max_launches) {
 
 int32_t s2v_profile_end(s2v_ctx *ctx, int32_t *n_launches, float *total_ms) {
     if (!ctx || !n_launches || !total_ms) return S2V_ERR_INVALID_ARG;
-    n_launches[0] = n_launches[1] = 0;
-    total_ms[0] = total_ms[1] = 0.f;
+    for (int k = 0; k < S2V_PROFILE_KINDS; ++k) {
+        n_launches[k] = 0;
+        total_ms[k] = 0.f;
+    }
     ctx->profiling = false;
     S2V_TRY(hipStreamSynchronize(ctx->stream));
     for (size_t i = 0; i < ctx->spans_used; ++i) {
         float ms = 0.f;
         S2V_TRY(hipEventElapsedTime(&ms, ctx->spans[i].start, ctx->spans[i].stop));
-        const int k = ctx->spans[i].kind == S2V_PROFILE_BWD_ROUND ? 1 : 0;
+        const int k = ctx->spans[i].kind;
         n_launches[k] += 1;
         total_ms[k] += ms;
     }
@@ -383,7 +388,7 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
     const HeadLayout h = head_layout(N, G);
-    const bool need_tmp = !mu_saved && T >= 2;
+    const bool need_tmp = !mu_saved && T >= 3;  // round 2 reads no embedding from memory
     const FwdLayout f = fwd_layout(h, N, p, S, need_tmp);
     if (ws_bytes < f.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
 
@@ -398,18 +403,29 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         if (mu_saved) return mu_saved + (size_t)(t - 1) * nsp;
         return ((T - t) % 2 == 0) ? mu_out : tmp;
     };
-    S2V_TRY(launch_round1(st, p, N, S, x, s_pos, s_neg, params->theta1, qvec, dest(1)));
+    // Round 1 has no neighbour term (mu^0 = 0).  Its result is written out only when somebody reads
+    // it from memory: the caller (mu_saved) or, when T == 1, the output itself.  Round 2 recomputes
+    // the neighbours' round-1 rows from the per-node scalars instead of gathering them.
+    float *info = at<float>(ws, f.info);
+    float *gpart = at<float>(ws, f.gpart);
+    if (T >= 2) S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info));
+    if (mu_saved || T == 1) S2V_TRY(launch_round1(st, p, N, S, x, s_pos, s_neg, params->theta1, qvec, dest(1)));
+    const bool fuse_gsum = gsum && S == 1 && G == 1 && T >= 2 && N > 0;
     for (int t = 2; t <= T; ++t) {
-        SpanGuard span(ctx, S2V_PROFILE_FWD_ROUND);
-        S2V_TRY(launch_round(st, p, N, S, g->rowptr, g->colidx, dest(t - 1), dest(t), x, s_pos, s_neg,
-                             params->theta1, params->theta2, qvec));
+        SpanGuard span(ctx, t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND);
+        S2V_TRY(launch_round(st, p, N, S, g->rowptr, g->colidx, t == 2 ? nullptr : dest(t - 1), dest(t), info,
+                             params->theta1, params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr));
     }
     float *muT = dest(T);
     if (mu_saved && mu_out && mu_out != muT && nsp > 0)
         S2V_TRY(hipMemcpyAsync(mu_out, muT, sizeof(float) * nsp, hipMemcpyDeviceToDevice, st));
     if (gsum) {
-        const ChunkTable ct = chunk_table(ws, h, *pr);
-        S2V_TRY(launch_gsum(st, p, N, S, G, ct, muT, at<float>(ws, f.gpart), gsum));
+        if (fuse_gsum) {
+            S2V_TRY(launch_gsum_from_round(st, p, round_grid((long)N * S), gpart, gsum));
+        } else {
+            const ChunkTable ct = chunk_table(ws, h, *pr);
+            S2V_TRY(launch_gsum(st, p, N, S, G, ct, muT, gpart, gsum));
+        }
     }
     return S2V_OK;
 }

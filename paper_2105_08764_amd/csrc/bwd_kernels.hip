@@ -193,7 +193,7 @@ hipError_t launch_bwd_dzT(hipStream_t st, int p, int N, int S, const float *muT,
 // of sum x dz^{t-1}, sum s+- dz^{t-1}.  Wave tiles of 16 rows of the [N*S][p] matrices; the
 // p x p accumulator of dtheta2 stays in registers over all tiles of the wave.
 // ------------------------------------------------------------------------------------------
-template <int P>
+template <int P, bool NODE>
 __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int S, const int32_t *__restrict__ rowptr,
                                                         const int32_t *__restrict__ colidx,
                                                         const float *__restrict__ dz_in,
@@ -252,20 +252,28 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
             if (r0 + row < n_vrows) mv[c] = ld4(mu_prev + (size_t)(r0 + row) * P + 4 * col4);
         }
 
-        int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
-        int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+        if (NODE) {
+            const int b = __builtin_amdgcn_readfirstlane(rb), e = __builtin_amdgcn_readfirstlane(re);
+            const int s0 = __builtin_amdgcn_readfirstlane(s);
+            const NodeAcc<P> ga = gather_node_block<P>(dz_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+            store_node_block<P>(tile_g, ga, lane);
+        } else {
+            int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
+            int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
 #pragma unroll 1
-        for (int i = 0; i < kTileRows; ++i) {
-            const int b = b_next, e = e_next;
-            const int cols = cols_next;
-            const int si = __shfl(s, i);
-            if (i + 1 < kTileRows) {
-                b_next = __shfl(rb, i + 1);
-                e_next = __shfl(re, i + 1);
-                cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+            for (int i = 0; i < kTileRows; ++i) {
+                const int b = b_next, e = e_next;
+                const int cols = cols_next;
+                const int si = __shfl(s, i);
+                if (i + 1 < kTileRows) {
+                    b_next = __shfl(rb, i + 1);
+                    e_next = __shfl(re, i + 1);
+                    cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+                }
+                const MemRow mem{dz_in, row_stride, (size_t)si * P + 4 * li};
+                const float4 a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
+                if (lane < Ge::LPR) st4(tile_g + i * STRIDE + 4 * lane, a);
             }
-            const float4 a = gather_row_sum<P>(dz_in, row_stride, (size_t)si * P + 4 * li, colidx, b, e, cols, lane);
-            if (lane < Ge::LPR) st4(tile_g + i * STRIDE + 4 * lane, a);
         }
 #pragma unroll
         for (int c = 0; c < MV; ++c) {
@@ -362,12 +370,16 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
                             const float *dz_in, const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
                             const float *s_neg, const float *theta2, float *dc_part, float *d2_part) {
     const long n_vrows = (long)N * S;
-    if (p == 32)
-        k_bwd_round<32><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, mu_prev, dz_out, x,
-                                                       s_pos, s_neg, theta2, dc_part, d2_part);
-    else
-        k_bwd_round<64><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, mu_prev, dz_out, x,
-                                                       s_pos, s_neg, theta2, dc_part, d2_part);
+    const bool node = (S % 16) == 0;
+#define S2V_LAUNCH_BWD(PP, NODE)                                                                                  \
+    k_bwd_round<PP, NODE><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, mu_prev, dz_out, x, \
+                                                         s_pos, s_neg, theta2, dc_part, d2_part)
+    if (p == 32) {
+        if (node) S2V_LAUNCH_BWD(32, true); else S2V_LAUNCH_BWD(32, false);
+    } else {
+        if (node) S2V_LAUNCH_BWD(64, true); else S2V_LAUNCH_BWD(64, false);
+    }
+#undef S2V_LAUNCH_BWD
     return hipGetLastError();
 }
 

@@ -27,20 +27,53 @@ __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast
 __device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
 __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
-// Sum over the stored entries [b, e) of one CSR row of the P-float rows src[col * row_stride + col_off ..].
-// All 64 lanes take part: lane = (group gq, lane-in-row li); col_off already includes 4 * li.
-// `cols` holds colidx[b + lane] for the first (up to) 64 entries, loaded by the caller ahead of time.
-// Returns the full row sum in every group (lanes with equal li hold equal values).
-template <int P>
-__device__ __forceinline__ float4 gather_row_sum(const float *__restrict__ src, size_t row_stride, size_t col_off,
-                                                 const int *__restrict__ colidx, int b, int e, int cols, int lane) {
+// ---- row loaders: the float4 (columns 4*li .. 4*li+3) of neighbour u's row -------------------
+
+// Row (u, s) of a [N][S][P] matrix in memory.
+struct MemRow {
+    const float *__restrict__ src;
+    size_t row_stride;  // S * P
+    size_t col_off;     // s * P + 4 * li
+    __device__ __forceinline__ float4 operator()(int u) const { return ld4(src + (size_t)u * row_stride + col_off); }
+};
+
+// Row (u, s) of the round-1 embedding, recomputed instead of read: mu^0 = 0 makes
+// mu^1_u = relu(theta1 x_u + s+_u q+ + s-_u q-) a function of three scalars per (node, state),
+// kept as info[u] = {s+, s-, x_0 .. x_{S-1}} (row length ni floats).
+struct Mu1Row {
+    const float *__restrict__ info;
+    int ni;
+    int s;
+    float4 t1, qp, qn;  // theta1, q+, q- at this lane's four columns
+    __device__ __forceinline__ float4 operator()(int u) const {
+        const float *r = info + (size_t)u * ni;
+        const float2 spn = *reinterpret_cast<const float2 *>(r);
+        const float xs = r[2 + s];
+        float4 o;
+        o.x = fmaxf(xs * t1.x + spn.x * qp.x + spn.y * qn.x, 0.f);
+        o.y = fmaxf(xs * t1.y + spn.x * qp.y + spn.y * qn.y, 0.f);
+        o.z = fmaxf(xs * t1.z + spn.x * qp.z + spn.y * qn.z, 0.f);
+        o.w = fmaxf(xs * t1.w + spn.x * qp.w + spn.y * qn.w, 0.f);
+        return o;
+    }
+};
+
+// Sum over the stored entries [b, e) of one CSR row of the neighbours' P-float rows (row mode:
+// any S).  All 64 lanes take part: lane = (group gq, lane-in-row li); one wave-wide load fetches
+// NPL neighbour rows.  `cols` holds colidx[b + lane] for the first (up to) 64 entries, loaded by
+// the caller ahead of time.  Returns the full row sum in every group.
+template <int P, class Loader>
+__device__ __forceinline__ float4 gather_row_sum(const Loader &row, const int *__restrict__ colidx, int b, int e,
+                                                 int cols, int lane) {
     constexpr int NPL = Geo<P>::NPL, LPR = Geo<P>::LPR;
     const int gq = lane / LPR;
-    float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0, a2 = a0, a3 = a0;
+    float4 total = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         if (base != b) cols = (lane < cnt) ? colidx[base + lane] : 0;
         const int last = cnt - 1;
+        // per-chunk accumulators folded into the running total: bounds the terms added into one float
+        float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0, a2 = a0, a3 = a0;
         for (int s0 = 0; s0 < cnt; s0 += 4 * NPL) {
             // Four independent loads per lane; slots past the end re-read the last valid row
             // (same cache line as a live lane, so no extra traffic) and are dropped below.
@@ -49,17 +82,18 @@ __device__ __forceinline__ float4 gather_row_sum(const float *__restrict__ src, 
             const int u1 = __shfl(cols, min(sl1, last));
             const int u2 = __shfl(cols, min(sl2, last));
             const int u3 = __shfl(cols, min(sl3, last));
-            const float4 v0 = ld4(src + (size_t)u0 * row_stride + col_off);
-            const float4 v1 = ld4(src + (size_t)u1 * row_stride + col_off);
-            const float4 v2 = ld4(src + (size_t)u2 * row_stride + col_off);
-            const float4 v3 = ld4(src + (size_t)u3 * row_stride + col_off);
+            const float4 v0 = row(u0);
+            const float4 v1 = row(u1);
+            const float4 v2 = row(u2);
+            const float4 v3 = row(u3);
             if (sl0 < cnt) a0 = add4(a0, v0);
             if (sl1 < cnt) a1 = add4(a1, v1);
             if (sl2 < cnt) a2 = add4(a2, v2);
             if (sl3 < cnt) a3 = add4(a3, v3);
         }
+        total = add4(total, add4(add4(a0, a1), add4(a2, a3)));
     }
-    a0 = add4(add4(a0, a1), add4(a2, a3));
+    float4 a0 = total;
 #pragma unroll
     for (int m = LPR; m < 64; m <<= 1) {
         a0.x += __shfl_xor(a0.x, m);
@@ -68,6 +102,109 @@ __device__ __forceinline__ float4 gather_row_sum(const float *__restrict__ src, 
         a0.w += __shfl_xor(a0.w, m);
     }
     return a0;
+}
+
+// Node mode (S a multiple of 16): the 16 rows of a wave tile are 16 consecutive states
+// s0 .. s0+15 of ONE node v, so every neighbour u contributes one contiguous block of 16 * P
+// floats, mu[u][s0 .. s0+15][:].  A wave-wide float4 load covers RPI = 64 / LPR of those rows
+// (1 KB, fully coalesced); NC = 16 / RPI loads cover the block.  Lane l, register c owns tile
+// row c * RPI + l / LPR, columns 4 * (l % LPR) ..: no cross-lane reduction is needed, and the
+// neighbour index is wave-uniform.
+template <int P>
+struct NodeAcc {
+    float4 a[16 / Geo<P>::NPL];
+};
+
+template <int P>
+__device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict__ src, size_t node_stride /*S*P*/,
+                                                        size_t blk_off /*s0*P*/, const int *__restrict__ colidx, int b,
+                                                        int e, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI;
+    // Two accumulators per 64-entry chunk, folded into the running total after each chunk, so a
+    // row of d entries adds at most about 32 + d / 64 terms into any one float.
+    NodeAcc<P> total, acc, acc2;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) total.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const size_t lane_off = blk_off + 4 * (size_t)lane;
+    for (int base = b; base < e; base += 64) {
+        const int cnt = min(64, e - base);
+        const int cols = (lane < cnt) ? colidx[base + lane] : 0;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc.a[c] = acc2.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        int j = 0;
+        for (; j + 2 <= cnt; j += 2) {
+            const int u0 = __builtin_amdgcn_readlane(cols, j);
+            const int u1 = __builtin_amdgcn_readlane(cols, j + 1);
+            const float *p0 = src + (size_t)u0 * node_stride + lane_off;
+            const float *p1 = src + (size_t)u1 * node_stride + lane_off;
+            float4 v0[NC], v1[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) v0[c] = ld4(p0 + c * RPI * P);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) v1[c] = ld4(p1 + c * RPI * P);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                acc.a[c] = add4(acc.a[c], v0[c]);
+                acc2.a[c] = add4(acc2.a[c], v1[c]);
+            }
+        }
+        if (j < cnt) {
+            const int u0 = __builtin_amdgcn_readlane(cols, j);
+            const float *p0 = src + (size_t)u0 * node_stride + lane_off;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) acc.a[c] = add4(acc.a[c], ld4(p0 + c * RPI * P));
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], add4(acc.a[c], acc2.a[c]));
+    }
+    return total;
+}
+
+// Node mode with the round-1 rows recomputed from info[u] = {s+, s-, x_0 ..} (see Mu1Row).
+template <int P>
+__device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restrict__ info, int ni, int s0,
+                                                            const float *__restrict__ theta1,
+                                                            const float *__restrict__ qvec,
+                                                            const int *__restrict__ colidx, int b, int e, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+    NodeAcc<P> total, acc;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) total.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int col = 4 * (lane % LPR);
+    const float4 t1 = ld4(theta1 + col), qp = ld4(qvec + col), qn = ld4(qvec + P + col);
+    const int srow = 2 + s0 + lane / LPR;
+    for (int base = b; base < e; base += 64) {
+        const int cnt = min(64, e - base);
+        const int cols = (lane < cnt) ? colidx[base + lane] : 0;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < cnt; ++j) {
+            const int u = __builtin_amdgcn_readlane(cols, j);
+            const float *r = info + (size_t)u * ni;
+            const float sp = r[0], sn = r[1];
+            const float bx = sp * qp.x + sn * qn.x, by = sp * qp.y + sn * qn.y;
+            const float bz = sp * qp.z + sn * qn.z, bw = sp * qp.w + sn * qn.w;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const float xs = r[srow + c * RPI];
+                acc.a[c].x += fmaxf(xs * t1.x + bx, 0.f);
+                acc.a[c].y += fmaxf(xs * t1.y + by, 0.f);
+                acc.a[c].z += fmaxf(xs * t1.z + bz, 0.f);
+                acc.a[c].w += fmaxf(xs * t1.w + bw, 0.f);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], acc.a[c]);
+    }
+    return total;
+}
+
+// Park a node-mode accumulator in the wave's LDS tile (row stride Geo<P>::STRIDE).
+template <int P>
+__device__ __forceinline__ void store_node_block(float *tile, const NodeAcc<P> &acc, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) st4(tile + (c * RPI + lane / LPR) * Geo<P>::STRIDE + 4 * (lane % LPR), acc.a[c]);
 }
 
 // The matrix-core product used everywhere:  D[i][j] = sum_k A[i][k] * B[j][k]  for a 16 x P

@@ -95,21 +95,52 @@ hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *x, co
 }
 
 // ------------------------------------------------------------------------------------------
+// Per-node scalars gathered in one place: info[v] = {s+_v, s-_v, x_0[v], .., x_{S-1}[v], pad}
+// (ni floats per node, ni a multiple of 4).  One 16-byte line per neighbour is all the second
+// round needs (see Mu1Row), and the epilogue of every round reads its own row's scalars here.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const float *__restrict__ x,
+                                                  const float *__restrict__ s_pos, const float *__restrict__ s_neg,
+                                                  float *__restrict__ info) {
+    const long total = (long)N * ni;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int v = (int)(i / ni), c = (int)(i - (long)v * ni);
+        float o = 0.f;
+        if (c == 0) o = s_pos[v];
+        else if (c == 1) o = s_neg[v];
+        else if (c - 2 < S) o = x[(size_t)(c - 2) * N + v];
+        info[i] = o;
+    }
+}
+
+hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
+                           float *info) {
+    if (N == 0) return hipSuccess;
+    const int ni = nodeinfo_stride(S);
+    const long total = (long)N * ni;
+    k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // Rounds 2..T of Eq. 1, fused: neighbour sum (CSR gather of p-float rows), theta2 product on
 // the matrix cores, the round-invariant terms, relu.  The matrix being updated is viewed as
 // [N*S][p]: row r = (node v = r / S, state s = r % S); the neighbours of row r are the rows
 // (u, s) for u in N(v).  A wave owns 16 consecutive rows at a time: it gathers their sums into
 // its own LDS tile, multiplies the tile by theta2 and writes the 16 output rows.
+//   NODE: S is a multiple of 16, so a tile is 16 states of one node (contiguous 1 KB loads).
+//   MU1 : this is round 2; the neighbours' round-1 rows are recomputed from info[] instead of read.
+//   GSUM: also emit this workgroup's column sums of the output (S == 1, one graph) to
+//         gpart[blockIdx.x][P]: the first stage of the graph sum of Alg. 2 line 4.
 // ------------------------------------------------------------------------------------------
-template <int P>
-__global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int N, int S, const int32_t *__restrict__ rowptr,
+template <int P, bool NODE, bool MU1, bool GSUM>
+__global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int S, int ni, const int32_t *__restrict__ rowptr,
                                                     const int32_t *__restrict__ colidx,
                                                     const float *__restrict__ mu_in, float *__restrict__ mu_out,
-                                                    const float *__restrict__ x, const float *__restrict__ s_pos,
-                                                    const float *__restrict__ s_neg,
+                                                    const float *__restrict__ info,
                                                     const float *__restrict__ theta1,
                                                     const float *__restrict__ theta2,
-                                                    const float *__restrict__ qvec) {
+                                                    const float *__restrict__ qvec, float *__restrict__ gpart) {
     using G = Geo<P>;
     __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -118,13 +149,23 @@ __global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int N, int S, c
     const int jl = lane & 15, gl = lane >> 4;
 
     Frag<P> bfrag[G::CB];
-    float t1[G::CB], qp[G::CB], qn[G::CB];
+    float t1[G::CB], qp[G::CB], qn[G::CB], csum[G::CB];
 #pragma unroll
     for (int cb = 0; cb < G::CB; ++cb) {
         bfrag[cb] = load_b_frag_rows<P>(theta2, cb, lane);
         t1[cb] = theta1[16 * cb + jl];
         qp[cb] = qvec[16 * cb + jl];
         qn[cb] = qvec[P + 16 * cb + jl];
+        csum[cb] = 0.f;
+    }
+    Mu1Row mu1;
+    if (MU1) {
+        mu1.info = info;
+        mu1.ni = ni;
+        mu1.s = 0;
+        mu1.t1 = ld4(theta1 + 4 * li);
+        mu1.qp = ld4(qvec + 4 * li);
+        mu1.qn = ld4(qvec + P + 4 * li);
     }
 
     const size_t row_stride = (size_t)S * P;
@@ -138,24 +179,41 @@ __global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int N, int S, c
         const int s = valid ? r - v * S : 0;
         const int rb = valid ? rowptr[v] : 0;
         const int re = valid ? rowptr[v + 1] : 0;
-        const float xs = valid ? x[(size_t)s * N + v] : 0.f;
-        const float sp = valid ? s_pos[v] : 0.f;
-        const float sn = valid ? s_neg[v] : 0.f;
+        const float *myinfo = info + (size_t)v * ni;
+        const float sp = valid ? myinfo[0] : 0.f;
+        const float sn = valid ? myinfo[1] : 0.f;
+        const float xs = valid ? myinfo[2 + s] : 0.f;
 
-        int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
-        int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+        if (NODE) {
+            // one node, 16 states: s0 = state of tile row 0
+            const int b = __builtin_amdgcn_readfirstlane(rb), e = __builtin_amdgcn_readfirstlane(re);
+            const int s0 = __builtin_amdgcn_readfirstlane(s);
+            NodeAcc<P> acc = MU1 ? gather_node_block_mu1<P>(info, ni, s0, theta1, qvec, colidx, b, e, lane)
+                                 : gather_node_block<P>(mu_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+            store_node_block<P>(tile, acc, lane);
+        } else {
+            int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
+            int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
 #pragma unroll 1
-        for (int i = 0; i < kTileRows; ++i) {
-            const int b = b_next, e = e_next;
-            const int cols = cols_next;
-            const int si = __shfl(s, i);
-            if (i + 1 < kTileRows) {
-                b_next = __shfl(rb, i + 1);
-                e_next = __shfl(re, i + 1);
-                cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+            for (int i = 0; i < kTileRows; ++i) {
+                const int b = b_next, e = e_next;
+                const int cols = cols_next;
+                const int si = __shfl(s, i);
+                if (i + 1 < kTileRows) {
+                    b_next = __shfl(rb, i + 1);
+                    e_next = __shfl(re, i + 1);
+                    cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+                }
+                float4 a;
+                if (MU1) {
+                    mu1.s = si;
+                    a = gather_row_sum<P>(mu1, colidx, b, e, cols, lane);
+                } else {
+                    const MemRow mem{mu_in, row_stride, (size_t)si * P + 4 * li};
+                    a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
+                }
+                if (lane < G::LPR) st4(tile + i * G::STRIDE + 4 * lane, a);
             }
-            const float4 a = gather_row_sum<P>(mu_in, row_stride, (size_t)si * P + 4 * li, colidx, b, e, cols, lane);
-            if (lane < G::LPR) st4(tile + i * G::STRIDE + 4 * lane, a);
         }
         __builtin_amdgcn_wave_barrier();
         const Frag<P> afrag = load_a_frag_lds<P>(tile, lane);
@@ -175,27 +233,70 @@ __global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int N, int S, c
             if (ro < n_vrows) {
                 float *out = mu_out + (size_t)ro * P + jl;
 #pragma unroll
-                for (int cb = 0; cb < G::CB; ++cb)
-                    out[16 * cb] = fmaxf(acc[cb][rr] + xi * t1[cb] + spi * qp[cb] + sni * qn[cb], 0.f);
+                for (int cb = 0; cb < G::CB; ++cb) {
+                    const float o = fmaxf(acc[cb][rr] + xi * t1[cb] + spi * qp[cb] + sni * qn[cb], 0.f);
+                    out[16 * cb] = o;
+                    if (GSUM) csum[cb] += o;
+                }
             }
         }
     }
+    if (GSUM) {
+        // column sums of everything this workgroup wrote: lanes with equal jl, then the four waves
+        __syncthreads();
+        float *red = &lds[0][0];
+#pragma unroll
+        for (int cb = 0; cb < G::CB; ++cb) {
+            csum[cb] += __shfl_xor(csum[cb], 16);
+            csum[cb] += __shfl_xor(csum[cb], 32);
+            if (gl == 0) red[wave * P + 16 * cb + jl] = csum[cb];
+        }
+        __syncthreads();
+        if (threadIdx.x < P)
+            gpart[(size_t)blockIdx.x * P + threadIdx.x] =
+                (red[threadIdx.x] + red[P + threadIdx.x]) + (red[2 * P + threadIdx.x] + red[3 * P + threadIdx.x]);
+    }
 }
 
-hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
-                        const float *mu_in, float *mu_out, const float *x, const float *s_pos, const float *s_neg,
-                        const float *theta1, const float *theta2, const float *qvec) {
-    const long n_vrows = (long)N * S;
-    if (n_vrows == 0) return hipSuccess;
+int round_grid(long n_vrows) {
     const long n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
-    const int grid = (int)min(n_tiles, (long)(256 * 16));
-    if (p == 32)
-        k_round<32><<<grid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, mu_in, mu_out, x, s_pos, s_neg,
-                                               theta1, theta2, qvec);
-    else
-        k_round<64><<<grid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, mu_in, mu_out, x, s_pos, s_neg,
-                                               theta1, theta2, qvec);
+    return (int)min(n_tiles, (long)kRoundGridMax);
+}
+
+template <int P>
+static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+                                 const float *mu_in, float *mu_out, const float *info, const float *theta1,
+                                 const float *theta2, const float *qvec, bool from_scalars, float *gpart) {
+    const long n_vrows = (long)N * S;
+    const int grid = round_grid(n_vrows);
+    const int ni = nodeinfo_stride(S);
+    const bool node = (S % 16) == 0;
+#define S2V_LAUNCH_ROUND(NODE, MU1, GSUM)                                                                         \
+    k_round<P, NODE, MU1, GSUM><<<grid, kThreads, 0, st>>>((int)n_vrows, S, ni, rowptr, colidx, mu_in, mu_out, info, \
+                                                           theta1, theta2, qvec, gpart)
+    if (node) {
+        if (from_scalars) S2V_LAUNCH_ROUND(true, true, false);
+        else S2V_LAUNCH_ROUND(true, false, false);
+    } else if (gpart) {
+        if (from_scalars) S2V_LAUNCH_ROUND(false, true, true);
+        else S2V_LAUNCH_ROUND(false, false, true);
+    } else {
+        if (from_scalars) S2V_LAUNCH_ROUND(false, true, false);
+        else S2V_LAUNCH_ROUND(false, false, false);
+    }
+#undef S2V_LAUNCH_ROUND
     return hipGetLastError();
+}
+
+// gpart != NULL asks for the fused column sums (only legal for S == 1 and a single graph).
+hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+                        const float *mu_in, float *mu_out, const float *info, const float *theta1,
+                        const float *theta2, const float *qvec, bool from_scalars, float *gpart) {
+    if ((long)N * S == 0) return hipSuccess;
+    if (p == 32)
+        return launch_round_p<32>(st, N, S, rowptr, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
+                                  gpart);
+    return launch_round_p<64>(st, N, S, rowptr, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -247,16 +348,35 @@ __global__ __launch_bounds__(256) void k_gsum_stage1(int L, const int32_t *__res
     }
 }
 
-__global__ __launch_bounds__(256) void k_gsum_stage2(int p, int S, int G, const int32_t *__restrict__ graph_chunk_off,
-                                                     const float *__restrict__ partial, float *__restrict__ gsum) {
+// Stage 2: per (graph, column) add the partial rows [row_begin, row_end) of that graph.  A block
+// owns 16 columns; its 16 row lanes take rows round-robin (double accumulators) and are combined
+// through LDS in lane order, so the result does not depend on timing.
+__global__ __launch_bounds__(256) void k_gsum_stage2(int p, int S, int G, const int32_t *__restrict__ graph_row_off,
+                                                     int rows_if_single, const float *__restrict__ partial,
+                                                     float *__restrict__ gsum) {
+    __shared__ double red[16][17];
     const int L = S * p;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= G * L) return;
-    const int g = i / L, col = i - g * L;
-    double acc = 0.0;
-    for (int c = graph_chunk_off[g]; c < graph_chunk_off[g + 1]; ++c) acc += (double)partial[(size_t)c * L + col];
-    const int s = col / p, j = col - s * p;
-    gsum[((size_t)s * G + g) * p + j] = (float)acc;
+    const int blocks_per_graph = L / 16;
+    const int g = blockIdx.x / blocks_per_graph;
+    const int col = (blockIdx.x - g * blocks_per_graph) * 16 + (threadIdx.x & 15);
+    const int rl = threadIdx.x >> 4;
+    const int rb = graph_row_off ? graph_row_off[g] : 0;
+    const int re = graph_row_off ? graph_row_off[g + 1] : rows_if_single;
+    double a0 = 0.0, a1 = 0.0;
+    int c = rb + rl;
+    for (; c + 16 < re; c += 32) {
+        a0 += (double)partial[(size_t)c * L + col];
+        a1 += (double)partial[(size_t)(c + 16) * L + col];
+    }
+    if (c < re) a0 += (double)partial[(size_t)c * L + col];
+    red[rl][threadIdx.x & 15] = a0 + a1;
+    __syncthreads();
+    if (rl == 0) {
+        double acc = 0.0;
+        for (int k = 0; k < 16; ++k) acc += red[k][threadIdx.x];
+        const int s = col / p, j = col - s * p;
+        gsum[((size_t)s * G + g) * p + j] = (float)acc;
+    }
 }
 
 hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu, float *partial,
@@ -268,8 +388,13 @@ hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTa
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    const int total = G * L;
-    k_gsum_stage2<<<(total + 255) / 256, 256, 0, st>>>(p, S, G, ct.graph_chunk_off, partial, gsum);
+    k_gsum_stage2<<<G * (L / 16), 256, 0, st>>>(p, S, G, ct.graph_chunk_off, 0, partial, gsum);
+    return hipGetLastError();
+}
+
+// Second stage alone, over `rows` partial rows written by the last embedding round (S == 1, G == 1).
+hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum) {
+    k_gsum_stage2<<<p / 16, 256, 0, st>>>(p, 1, 1, nullptr, rows, partial, gsum);
     return hipGetLastError();
 }
 

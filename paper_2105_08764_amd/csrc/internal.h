@@ -32,9 +32,17 @@ hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const 
 hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec);
 hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *x, const float *s_pos, const float *s_neg,
                          const float *theta1, const float *qvec, float *mu_out);
+// floats per node of the scalar table {s+, s-, x_0 .. x_{S-1}}, padded to a multiple of 4
+inline int nodeinfo_stride(int S) { return (S + 2 + 3) / 4 * 4; }
+// upper bound of the embedding-round grid (also the number of partial rows of its fused graph sum)
+constexpr int kRoundGridMax = 256 * 16;
+int round_grid(long n_vrows);
+hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
+                           float *info);
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
-                        const float *mu_in, float *mu_out, const float *x, const float *s_pos, const float *s_neg,
-                        const float *theta1, const float *theta2, const float *qvec);
+                        const float *mu_in, float *mu_out, const float *info, const float *theta1,
+                        const float *theta2, const float *qvec, bool from_scalars, float *gpart);
+hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum);
 hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu,
                        float *partial /*[n_chunks][S*p]*/, float *gsum /*[S][G][p]*/);
 hipError_t launch_qa(hipStream_t st, int p, int S, int G, const float *theta5, const float *theta6, const float *gsum,
