@@ -74,22 +74,39 @@ __device__ __forceinline__ float4 gather_row_sum(const Loader &row, const int *_
         const int last = cnt - 1;
         // per-chunk accumulators folded into the running total: bounds the terms added into one float
         float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0, a2 = a0, a3 = a0;
-        for (int s0 = 0; s0 < cnt; s0 += 4 * NPL) {
-            // Four independent loads per lane; slots past the end re-read the last valid row
-            // (same cache line as a live lane, so no extra traffic) and are dropped below.
-            const int sl0 = s0 + gq, sl1 = sl0 + NPL, sl2 = sl1 + NPL, sl3 = sl2 + NPL;
-            const int u0 = __shfl(cols, min(sl0, last));
-            const int u1 = __shfl(cols, min(sl1, last));
-            const int u2 = __shfl(cols, min(sl2, last));
-            const int u3 = __shfl(cols, min(sl3, last));
-            const float4 v0 = row(u0);
-            const float4 v1 = row(u1);
-            const float4 v2 = row(u2);
-            const float4 v3 = row(u3);
-            if (sl0 < cnt) a0 = add4(a0, v0);
-            if (sl1 < cnt) a1 = add4(a1, v1);
-            if (sl2 < cnt) a2 = add4(a2, v2);
-            if (sl3 < cnt) a3 = add4(a3, v3);
+        int s0 = 0;
+        // Eight independent loads per lane while at least 4*NPL + 1 entries remain, else four.
+        // Slots past the end re-read the last valid row (same cache line as a live lane, so no
+        // extra memory traffic) and are dropped when accumulating.
+        for (; cnt - s0 > 4 * NPL; s0 += 8 * NPL) {
+            int sl[8];
+            float4 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                sl[k] = s0 + gq + k * NPL;
+                v[k] = row(__shfl(cols, min(sl[k], last)));
+            }
+            if (sl[0] < cnt) a0 = add4(a0, v[0]);
+            if (sl[1] < cnt) a1 = add4(a1, v[1]);
+            if (sl[2] < cnt) a2 = add4(a2, v[2]);
+            if (sl[3] < cnt) a3 = add4(a3, v[3]);
+            if (sl[4] < cnt) a0 = add4(a0, v[4]);
+            if (sl[5] < cnt) a1 = add4(a1, v[5]);
+            if (sl[6] < cnt) a2 = add4(a2, v[6]);
+            if (sl[7] < cnt) a3 = add4(a3, v[7]);
+        }
+        if (s0 < cnt) {
+            int sl[4];
+            float4 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                sl[k] = s0 + gq + k * NPL;
+                v[k] = row(__shfl(cols, min(sl[k], last)));
+            }
+            if (sl[0] < cnt) a0 = add4(a0, v[0]);
+            if (sl[1] < cnt) a1 = add4(a1, v[1]);
+            if (sl[2] < cnt) a2 = add4(a2, v[2]);
+            if (sl[3] < cnt) a3 = add4(a3, v[3]);
         }
         total = add4(total, add4(add4(a0, a1), add4(a2, a3)));
     }
@@ -274,6 +291,39 @@ __device__ __forceinline__ Frag<P> load_b_frag_cols(const float *__restrict__ m,
     const float *col = m + (size_t)((lane >> 4) * KS) * P + 16 * cb + (lane & 15);
 #pragma unroll
     for (int c = 0; c < KS; ++c) f.v[c] = col[(size_t)c * P];
+    return f;
+}
+
+// The P x P matrix M staged in LDS (row stride Geo<P>::STRIDE) by the whole workgroup; call
+// __syncthreads() afterwards.  transpose = false keeps M[j][k]; true stores M[k][j] at [j][k], so
+// that in both cases B-fragments are contiguous float4 reads of "row j".
+template <int P>
+__device__ __forceinline__ void stage_matrix_lds(float *dst, const float *__restrict__ m, bool transpose) {
+    constexpr int STRIDE = Geo<P>::STRIDE;
+    if (!transpose) {
+        for (int f = threadIdx.x; f < P * P / 4; f += blockDim.x) {
+            const int r = f / (P / 4), c4 = f % (P / 4);
+            st4(dst + r * STRIDE + 4 * c4, ld4(m + r * P + 4 * c4));
+        }
+    } else {
+        for (int f = threadIdx.x; f < P * P; f += blockDim.x) {
+            const int k = f / P, j = f % P;
+            dst[j * STRIDE + k] = m[f];
+        }
+    }
+}
+
+// B-fragment of column block cb from a matrix staged by stage_matrix_lds.
+template <int P>
+__device__ __forceinline__ Frag<P> load_b_frag_lds(const float *mat, int cb, int lane) {
+    constexpr int KS = Geo<P>::KS;
+    Frag<P> f;
+    const float *row = mat + (16 * cb + (lane & 15)) * Geo<P>::STRIDE + (lane >> 4) * KS;
+#pragma unroll
+    for (int c = 0; c < KS / 4; ++c) {
+        const float4 t = ld4(row + 4 * c);
+        f.v[4 * c] = t.x; f.v[4 * c + 1] = t.y; f.v[4 * c + 2] = t.z; f.v[4 * c + 3] = t.w;
+    }
     return f;
 }
 

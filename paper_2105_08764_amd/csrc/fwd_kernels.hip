@@ -134,7 +134,7 @@ hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const f
 //         gpart[blockIdx.x][P]: the first stage of the graph sum of Alg. 2 line 4.
 // ------------------------------------------------------------------------------------------
 template <int P, bool NODE, bool MU1, bool GSUM>
-__global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int S, int ni, const int32_t *__restrict__ rowptr,
+__global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int ni, const int32_t *__restrict__ rowptr,
                                                     const int32_t *__restrict__ colidx,
                                                     const float *__restrict__ mu_in, float *__restrict__ mu_out,
                                                     const float *__restrict__ info,
@@ -143,16 +143,17 @@ __global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int S, int ni, 
                                                     const float *__restrict__ qvec, float *__restrict__ gpart) {
     using G = Geo<P>;
     __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
+    __shared__ __attribute__((aligned(16))) float lds_b[P * G::STRIDE];   // theta2, the B operand
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float *tile = lds[wave];
     const int li = lane % G::LPR;
     const int jl = lane & 15, gl = lane >> 4;
 
-    Frag<P> bfrag[G::CB];
+    stage_matrix_lds<P>(lds_b, theta2, false);
+    __syncthreads();
     float t1[G::CB], qp[G::CB], qn[G::CB], csum[G::CB];
 #pragma unroll
     for (int cb = 0; cb < G::CB; ++cb) {
-        bfrag[cb] = load_b_frag_rows<P>(theta2, cb, lane);
         t1[cb] = theta1[16 * cb + jl];
         qp[cb] = qvec[16 * cb + jl];
         qn[cb] = qvec[P + 16 * cb + jl];
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void k_round(int n_vrows, int S, int ni, 
 #pragma unroll
         for (int cb = 0; cb < G::CB; ++cb) {
             acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            acc[cb] = mfma_tile<P>(afrag, bfrag[cb], acc[cb]);
+            acc[cb] = mfma_tile<P>(afrag, load_b_frag_lds<P>(lds_b, cb, lane), acc[cb]);
         }
         // lane (jl, gl) holds rows 4*gl + rr, columns 16*cb + jl
 #pragma unroll
