@@ -190,6 +190,8 @@ def main():
     ap.add_argument("--train-steps", type=int, default=3)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graphs (debugging only; invalid as a result)")
     ap.add_argument("--no-train", action="store_true")
+    ap.add_argument("--counters", action="store_true",
+                    help="short run for rocprofv3 --pmc: a 1 GiB device copy (calibration) and 3 inference steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -202,6 +204,16 @@ def main():
     s2v.load_library()  # fails loudly when the HIP library has not been built
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+
+    if args.counters:
+        # calibration for byte counters: a plain copy kernel of known size (1 GiB read + 1 GiB written)
+        src = torch.empty(1 << 28, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        args.steps, args.warmup, args.no_train, args.no_cpu_baseline = 3, 1, True, True
 
     inf, w4 = bench_inference(args, s2v, torch)
     train = None

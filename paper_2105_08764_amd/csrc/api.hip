@@ -18,6 +18,8 @@ struct Prepared {
     int64_t nnz;
     int32_t G;
     int32_t n_chunks;
+    int32_t n_hubs;
+    int32_t n_segs;
 };
 
 // Carves consecutive 256-byte aligned pieces out of a byte range.
@@ -32,13 +34,18 @@ struct Carver {
 };
 
 struct HeadLayout {
-    size_t s_pos, s_neg, chunk_begin, chunk_end, chunk_graph, graph_chunk_off, end;
-    int max_chunks;
+    size_t s_pos, s_neg, chunk_begin, chunk_end, chunk_graph, graph_chunk_off;
+    size_t hub_rows, hub_seg_off, seg_begin, seg_end, end;
+    int max_chunks, max_hubs, max_segs;
 };
 
-HeadLayout head_layout(int64_t N, int64_t G) {
+// Upper bounds from the shape alone: a hub has more than kHubDegree entries, and a hub of d
+// entries has ceil(d / kHubDegree) <= d / kHubDegree + 1 segments.
+HeadLayout head_layout(int64_t N, int64_t G, int64_t nnz) {
     HeadLayout h;
     h.max_chunks = (int)((N + kChunkNodes - 1) / kChunkNodes + G);
+    h.max_hubs = (int)(nnz / (kHubDegree + 1));
+    h.max_segs = (int)(nnz / kHubDegree) + h.max_hubs;
     Carver c(0);
     h.s_pos = c.take(sizeof(float) * N);
     h.s_neg = c.take(sizeof(float) * N);
@@ -46,11 +53,15 @@ HeadLayout head_layout(int64_t N, int64_t G) {
     h.chunk_end = c.take(sizeof(int32_t) * h.max_chunks);
     h.chunk_graph = c.take(sizeof(int32_t) * h.max_chunks);
     h.graph_chunk_off = c.take(sizeof(int32_t) * (G + 1));
+    h.hub_rows = c.take(sizeof(int32_t) * h.max_hubs);
+    h.hub_seg_off = c.take(sizeof(int32_t) * (h.max_hubs + 1));
+    h.seg_begin = c.take(sizeof(int32_t) * h.max_segs);
+    h.seg_end = c.take(sizeof(int32_t) * h.max_segs);
     h.end = c.off;
     return h;
 }
 
-struct FwdLayout { size_t qvec, info, tmp, gpart, end; };
+struct FwdLayout { size_t qvec, info, tmp, gpart, hub_part, hub_sum, end; };
 FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp) {
     FwdLayout f;
     Carver c(h.end);
@@ -60,6 +71,8 @@ FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp
     if (part_rows < (size_t)kRoundGridMax) part_rows = kRoundGridMax;
     f.gpart = c.take(sizeof(float) * part_rows * p);
     f.tmp = c.take(need_tmp ? sizeof(float) * (size_t)N * S * p : 0);
+    f.hub_part = c.take(sizeof(float) * (size_t)h.max_segs * S * p);
+    f.hub_sum = c.take(sizeof(float) * (size_t)h.max_hubs * S * p);
     f.end = c.off;
     return f;
 }
@@ -94,7 +107,7 @@ SelLayout sel_layout(const HeadLayout &h, int64_t N, int64_t k) {
 }
 
 struct BwdLayout {
-    size_t dg, da, glo, ghi, head_part, dz0, dz1, dc_part, d2_part, dvec, red_tmp, end;
+    size_t dg, da, glo, ghi, head_part, dz0, dz1, dc_part, d2_part, dvec, red_tmp, hub_part, hub_sum, end;
     int dc_rows, d2_rows;
 };
 BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
@@ -115,6 +128,8 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.d2_part = c.take(sizeof(float) * (size_t)b.d2_rows * p * p);
     b.dvec = c.take(sizeof(float) * 3 * p);
     b.red_tmp = c.take(sizeof(float) * segs * width);
+    b.hub_part = c.take(sizeof(float) * (size_t)h.max_segs * S * p);
+    b.hub_sum = c.take(sizeof(float) * (size_t)h.max_hubs * S * p);
     b.end = c.off;
     return b;
 }
@@ -201,6 +216,17 @@ const Prepared *find_prepared(const s2v_ctx *ctx, const s2v_graph *g, const void
             pr.nnz == g->nnz && pr.G == g->n_graphs)
             return &pr;
     return nullptr;
+}
+
+HubTable hub_table(void *ws, const HeadLayout &h, const Prepared &pr) {
+    HubTable ht;
+    ht.n_hubs = pr.n_hubs;
+    ht.n_segs = pr.n_segs;
+    ht.hub_rows = at<int32_t>(ws, h.hub_rows);
+    ht.hub_seg_off = at<int32_t>(ws, h.hub_seg_off);
+    ht.seg_begin = at<int32_t>(ws, h.seg_begin);
+    ht.seg_end = at<int32_t>(ws, h.seg_end);
+    return ht;
 }
 
 ChunkTable chunk_table(void *ws, const HeadLayout &h, const Prepared &pr) {
@@ -308,7 +334,7 @@ int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t
     if (!g || !out || g->n_nodes < 0 || g->n_graphs < 1 || T < 1 || S < 1 || k_max < 0) return S2V_ERR_INVALID_ARG;
     if (!p_supported(p)) return S2V_ERR_UNSUPPORTED;
     if ((int64_t)g->n_nodes * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
-    const HeadLayout h = head_layout(g->n_nodes, g->n_graphs);
+    const HeadLayout h = head_layout(g->n_nodes, g->n_graphs, g->nnz);
     size_t need = fwd_layout(h, g->n_nodes, p, S, true).end;
     const size_t q_end = q_layout(h, S, g->n_graphs).end;
     const size_t s_end = sel_layout(h, g->n_nodes, k_max > 0 ? k_max : 1).end;
@@ -329,7 +355,7 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     rc = check_ws(ws);
     if (rc != S2V_OK) return rc;
     const int32_t N = g->n_nodes, G = g->n_graphs;
-    const HeadLayout h = head_layout(N, G);
+    const HeadLayout h = head_layout(N, G, g->nnz);
     if (ws_bytes < h.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
 
     // graph offsets to the host: the chunk table is built here, once per graph
@@ -362,10 +388,36 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_graph), cg.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
     }
     S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.graph_chunk_off), gco.data(), sizeof(int32_t) * (G + 1), hipMemcpyHostToDevice, ctx->stream));
+    // hub rows and their segments, from a host copy of rowptr
+    std::vector<int32_t> rp((size_t)N + 1);
+    S2V_TRY(hipMemcpyAsync(rp.data(), g->rowptr, sizeof(int32_t) * ((size_t)N + 1), hipMemcpyDeviceToHost, ctx->stream));
+    S2V_TRY(hipStreamSynchronize(ctx->stream));
+    if (rp[0] != 0 || (int64_t)rp[N] != g->nnz) return S2V_ERR_INVALID_ARG;
+    std::vector<int32_t> hub_rows, hub_seg_off, seg_begin, seg_end;
+    for (int32_t v = 0; v < N; ++v) {
+        if (rp[v + 1] < rp[v]) return S2V_ERR_INVALID_ARG;
+        if (rp[v + 1] - rp[v] > kHubDegree) {
+            hub_rows.push_back(v);
+            hub_seg_off.push_back((int32_t)seg_begin.size());
+            for (int32_t b = rp[v]; b < rp[v + 1]; b += kHubDegree) {
+                seg_begin.push_back(b);
+                seg_end.push_back(b + kHubDegree < rp[v + 1] ? b + kHubDegree : rp[v + 1]);
+            }
+        }
+    }
+    hub_seg_off.push_back((int32_t)seg_begin.size());
+    const int n_hubs = (int)hub_rows.size(), n_segs = (int)seg_begin.size();
+    if (n_hubs > h.max_hubs || n_segs > h.max_segs) return S2V_ERR_INVALID_ARG;
+    if (n_hubs > 0) {
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.hub_rows), hub_rows.data(), sizeof(int32_t) * n_hubs, hipMemcpyHostToDevice, ctx->stream));
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.hub_seg_off), hub_seg_off.data(), sizeof(int32_t) * (n_hubs + 1), hipMemcpyHostToDevice, ctx->stream));
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_begin), seg_begin.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_end), seg_end.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
+    }
     S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg)));
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
 
-    Prepared pr{ws, g->rowptr, g->colidx, N, g->nnz, G, n_chunks};
+    Prepared pr{ws, g->rowptr, g->colidx, N, g->nnz, G, n_chunks, n_hubs, n_segs};
     for (Prepared &old : ctx->prepared)
         if (old.ws == ws) { old = pr; return S2V_OK; }
     ctx->prepared.push_back(pr);
@@ -387,7 +439,7 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
-    const HeadLayout h = head_layout(N, G);
+    const HeadLayout h = head_layout(N, G, g->nnz);
     const bool need_tmp = !mu_saved && T >= 3;  // round 2 reads no embedding from memory
     const FwdLayout f = fwd_layout(h, N, p, S, need_tmp);
     if (ws_bytes < f.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
@@ -411,10 +463,14 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     if (T >= 2) S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info));
     if (mu_saved || T == 1) S2V_TRY(launch_round1(st, p, N, S, x, s_pos, s_neg, params->theta1, qvec, dest(1)));
     const bool fuse_gsum = gsum && S == 1 && G == 1 && T >= 2 && N > 0;
+    const HubTable ht = hub_table(ws, h, *pr);
+    float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     for (int t = 2; t <= T; ++t) {
+        const float *src = t == 2 ? nullptr : dest(t - 1);
+        S2V_TRY(launch_hub_sums(st, p, S, ht, g->colidx, src, info, params->theta1, qvec, hub_part, hub_sum));
         SpanGuard span(ctx, t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND);
-        S2V_TRY(launch_round(st, p, N, S, g->rowptr, g->colidx, t == 2 ? nullptr : dest(t - 1), dest(t), info,
-                             params->theta1, params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr));
+        S2V_TRY(launch_round(st, p, N, S, g->rowptr, g->colidx, src, dest(t), info, params->theta1, params->theta2,
+                             qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum));
     }
     float *muT = dest(T);
     if (mu_saved && mu_out && mu_out != muT && nsp > 0)
@@ -443,7 +499,7 @@ int32_t s2v_q_score(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, 
     const int32_t N = g->n_nodes, G = g->n_graphs, p = params->p;
     if (N > 0 && (!mu || !q)) return S2V_ERR_INVALID_ARG;
     if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
-    const HeadLayout h = head_layout(N, G);
+    const HeadLayout h = head_layout(N, G, g->nnz);
     const QLayout ql = q_layout(h, S, G);
     if (ws_bytes < ql.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = ctx->stream;
@@ -466,7 +522,7 @@ int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const 
     if (G > 1 && k > 1) return S2V_ERR_UNSUPPORTED;
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
-    const HeadLayout h = head_layout(N, G);
+    const HeadLayout h = head_layout(N, G, g->nnz);
     const SelLayout sl = sel_layout(h, N, k);
     if (ws_bytes < sl.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
     SelectScratch sc;
@@ -509,7 +565,7 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
-    const HeadLayout h = head_layout(N, G);
+    const HeadLayout h = head_layout(N, G, g->nnz);
     const BwdLayout bl = bwd_layout(h, N, p, T, S);
     if (ws_bytes < bl.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
 
@@ -534,15 +590,18 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
                             action, target, sc, q_pred));
     S2V_TRY(launch_bwd_head_reduce(st, p, S, sc, loss, grads->theta5, grads->theta6, grads->theta7));
     S2V_TRY(launch_bwd_dzT(st, p, N, S, muT, x, s_pos, s_neg, action, sc, sc.dz[0], sc.dc_part));
+    const HubTable ht = hub_table(ws, h, *pr);
+    float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);
     int cur = 0;
     for (int t = T; t >= 2; --t) {
         const int slot = T - t;  // 0 for the first reversed round
         float *dc_part = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)slot * kBwdGrid) * 3 * p;
         float *d2_part = sc.d2_part + (size_t)slot * kBwdGrid * p * p;
         const float *mu_prev = mu_saved + (size_t)(t - 2) * nsp;
+        S2V_TRY(launch_hub_sums(st, p, S, ht, g->colidx, sc.dz[cur], nullptr, nullptr, nullptr, hub_part, hub_sum));
         SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
         S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, g->colidx, sc.dz[cur], mu_prev, sc.dz[cur ^ 1], x, s_pos,
-                                 s_neg, params->theta2, dc_part, d2_part));
+                                 s_neg, params->theta2, dc_part, d2_part, ht, hub_sum));
         cur ^= 1;
     }
     S2V_TRY(launch_bwd_finish(st, p, bl.dc_rows, bl.d2_rows, sc, params->theta3, params->theta4, grads->theta1,

@@ -201,7 +201,8 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
                                                         const float *__restrict__ x, const float *__restrict__ s_pos,
                                                         const float *__restrict__ s_neg,
                                                         const float *__restrict__ theta2, float *__restrict__ dc_part,
-                                                        float *__restrict__ d2_part) {
+                                                        float *__restrict__ d2_part, HubTable ht,
+                                                        const float *__restrict__ hub_sum) {
     using Ge = Geo<P>;
     constexpr int CB = Ge::CB, STRIDE = Ge::STRIDE;
     constexpr int TILE_F = kTileRows * STRIDE;
@@ -255,7 +256,13 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
         if (NODE) {
             const int b = __builtin_amdgcn_readfirstlane(rb), e = __builtin_amdgcn_readfirstlane(re);
             const int s0 = __builtin_amdgcn_readfirstlane(s);
-            const NodeAcc<P> ga = gather_node_block<P>(dz_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+            NodeAcc<P> ga;
+            if (e - b > kHubDegree) {
+                const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
+                ga = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
+            } else {
+                ga = gather_node_block<P>(dz_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+            }
             store_node_block<P>(tile_g, ga, lane);
         } else {
             int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
@@ -270,8 +277,14 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
                     e_next = __shfl(re, i + 1);
                     cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
                 }
-                const MemRow mem{dz_in, row_stride, (size_t)si * P + 4 * li};
-                const float4 a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
+                float4 a;
+                if (e - b > kHubDegree) {
+                    const int h = hub_index(ht.hub_rows, ht.n_hubs, __shfl(v, i));
+                    a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
+                } else {
+                    const MemRow mem{dz_in, row_stride, (size_t)si * P + 4 * li};
+                    a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
+                }
                 if (lane < Ge::LPR) st4(tile_g + i * STRIDE + 4 * lane, a);
             }
         }
@@ -368,12 +381,13 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
 
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
                             const float *dz_in, const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
-                            const float *s_neg, const float *theta2, float *dc_part, float *d2_part) {
+                            const float *s_neg, const float *theta2, float *dc_part, float *d2_part,
+                            const HubTable &ht, const float *hub_sum) {
     const long n_vrows = (long)N * S;
     const bool node = (S % 16) == 0;
 #define S2V_LAUNCH_BWD(PP, NODE)                                                                                  \
     k_bwd_round<PP, NODE><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, mu_prev, dz_out, x, \
-                                                         s_pos, s_neg, theta2, dc_part, d2_part)
+                                                         s_pos, s_neg, theta2, dc_part, d2_part, ht, hub_sum)
     if (p == 32) {
         if (node) S2V_LAUNCH_BWD(32, true); else S2V_LAUNCH_BWD(32, false);
     } else {

@@ -2,6 +2,7 @@
 // the wave-level neighbour gather and the 16 x P by P x P product on the matrix cores.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace s2v {
 
@@ -214,6 +215,26 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
         for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], acc.a[c]);
     }
     return total;
+}
+
+// Index of node v in the ascending list of hub rows (v is known to be a hub).
+__device__ __forceinline__ int hub_index(const int32_t *__restrict__ hub_rows, int n_hubs, int v) {
+    int lo = 0, hi = n_hubs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (hub_rows[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// A node-mode block read back from the hub sums instead of gathered.
+template <int P>
+__device__ __forceinline__ NodeAcc<P> load_node_block(const float *__restrict__ blk, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI;
+    NodeAcc<P> acc;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc.a[c] = ld4(blk + c * RPI * P + 4 * lane);
+    return acc;
 }
 
 // Park a node-mode accumulator in the wave's LDS tile (row stride Geo<P>::STRIDE).

@@ -140,7 +140,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
                                                     const float *__restrict__ info,
                                                     const float *__restrict__ theta1,
                                                     const float *__restrict__ theta2,
-                                                    const float *__restrict__ qvec, float *__restrict__ gpart) {
+                                                    const float *__restrict__ qvec, float *__restrict__ gpart,
+                                                    HubTable ht, const float *__restrict__ hub_sum) {
     using G = Geo<P>;
     __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
     __shared__ __attribute__((aligned(16))) float lds_b[P * G::STRIDE];   // theta2, the B operand
@@ -189,8 +190,14 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
             // one node, 16 states: s0 = state of tile row 0
             const int b = __builtin_amdgcn_readfirstlane(rb), e = __builtin_amdgcn_readfirstlane(re);
             const int s0 = __builtin_amdgcn_readfirstlane(s);
-            NodeAcc<P> acc = MU1 ? gather_node_block_mu1<P>(info, ni, s0, theta1, qvec, colidx, b, e, lane)
-                                 : gather_node_block<P>(mu_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+            NodeAcc<P> acc;
+            if (e - b > kHubDegree) {
+                const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
+                acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
+            } else {
+                acc = MU1 ? gather_node_block_mu1<P>(info, ni, s0, theta1, qvec, colidx, b, e, lane)
+                          : gather_node_block<P>(mu_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+            }
             store_node_block<P>(tile, acc, lane);
         } else {
             int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
@@ -206,7 +213,10 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
                     cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
                 }
                 float4 a;
-                if (MU1) {
+                if (e - b > kHubDegree) {
+                    const int h = hub_index(ht.hub_rows, ht.n_hubs, __shfl(v, i));
+                    a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
+                } else if (MU1) {
                     mu1.s = si;
                     a = gather_row_sum<P>(mu1, colidx, b, e, cols, lane);
                 } else {
@@ -267,14 +277,15 @@ int round_grid(long n_vrows) {
 template <int P>
 static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *rowptr, const int32_t *colidx,
                                  const float *mu_in, float *mu_out, const float *info, const float *theta1,
-                                 const float *theta2, const float *qvec, bool from_scalars, float *gpart) {
+                                 const float *theta2, const float *qvec, bool from_scalars, float *gpart,
+                                 const HubTable &ht, const float *hub_sum) {
     const long n_vrows = (long)N * S;
     const int grid = round_grid(n_vrows);
     const int ni = nodeinfo_stride(S);
     const bool node = (S % 16) == 0;
 #define S2V_LAUNCH_ROUND(NODE, MU1, GSUM)                                                                         \
     k_round<P, NODE, MU1, GSUM><<<grid, kThreads, 0, st>>>((int)n_vrows, S, ni, rowptr, colidx, mu_in, mu_out, info, \
-                                                           theta1, theta2, qvec, gpart)
+                                                           theta1, theta2, qvec, gpart, ht, hub_sum)
     if (node) {
         if (from_scalars) S2V_LAUNCH_ROUND(true, true, false);
         else S2V_LAUNCH_ROUND(true, false, false);
@@ -292,12 +303,93 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
 // gpart != NULL asks for the fused column sums (only legal for S == 1 and a single graph).
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
                         const float *mu_in, float *mu_out, const float *info, const float *theta1,
-                        const float *theta2, const float *qvec, bool from_scalars, float *gpart) {
+                        const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
+                        const float *hub_sum) {
     if ((long)N * S == 0) return hipSuccess;
     if (p == 32)
         return launch_round_p<32>(st, N, S, rowptr, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
-                                  gpart);
-    return launch_round_p<64>(st, N, S, rowptr, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart);
+                                  gpart, ht, hub_sum);
+    return launch_round_p<64>(st, N, S, rowptr, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
+                              ht, hub_sum);
+}
+
+// ------------------------------------------------------------------------------------------
+// Hub pre-pass.  Stage A: one wave per (segment, block of rows of that node) sums at most
+// kHubDegree neighbour rows with the same gather code as the round kernel.  Stage B adds the
+// segment partials of each hub in segment order.
+// ------------------------------------------------------------------------------------------
+template <int P, bool NODE, bool MU1>
+__global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTable ht,
+                                                          const int32_t *__restrict__ colidx,
+                                                          const float *__restrict__ src,
+                                                          const float *__restrict__ info,
+                                                          const float *__restrict__ theta1,
+                                                          const float *__restrict__ qvec, float *__restrict__ partial) {
+    using G = Geo<P>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane % G::LPR;
+    const int bpn = NODE ? S / 16 : S;  // blocks per node
+    const long items = (long)ht.n_segs * bpn;
+    for (long item = (long)blockIdx.x * kWaves + wave; item < items; item += (long)gridDim.x * kWaves) {
+        const int seg = (int)(item / bpn), blk = (int)(item - (long)seg * bpn);
+        const int b = ht.seg_begin[seg], e = ht.seg_end[seg];
+        if (NODE) {
+            const int s0 = blk * 16;
+            const NodeAcc<P> acc = MU1 ? gather_node_block_mu1<P>(info, ni, s0, theta1, qvec, colidx, b, e, lane)
+                                       : gather_node_block<P>(src, (size_t)S * P, (size_t)s0 * P, colidx, b, e, lane);
+            float *out = partial + ((size_t)seg * S + s0) * P;
+#pragma unroll
+            for (int c = 0; c < 16 / G::NPL; ++c) st4(out + c * G::NPL * P + 4 * lane, acc.a[c]);
+        } else {
+            const int s = blk;
+            const int cols = (lane < min(64, e - b)) ? colidx[b + lane] : 0;
+            float4 a;
+            if (MU1) {
+                Mu1Row mu1{info, ni, s, ld4(theta1 + 4 * li), ld4(qvec + 4 * li), ld4(qvec + P + 4 * li)};
+                a = gather_row_sum<P>(mu1, colidx, b, e, cols, lane);
+            } else {
+                const MemRow mem{src, (size_t)S * P, (size_t)s * P + 4 * li};
+                a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
+            }
+            if (lane < G::LPR) st4(partial + ((size_t)seg * S + s) * P + 4 * lane, a);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_hub_combine(int L, HubTable ht, const float *__restrict__ partial,
+                                                     float *__restrict__ hub_sum) {
+    const long total = (long)ht.n_hubs * L;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int h = (int)(i / L), c = (int)(i - (long)h * L);
+        float acc = 0.f;
+        for (int seg = ht.hub_seg_off[h]; seg < ht.hub_seg_off[h + 1]; ++seg) acc += partial[(size_t)seg * L + c];
+        hub_sum[i] = acc;
+    }
+}
+
+hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *colidx, const float *src,
+                           const float *info, const float *theta1, const float *qvec, float *partial, float *hub_sum) {
+    if (ht.n_hubs == 0) return hipSuccess;
+    const bool node = (S % 16) == 0, mu1 = src == nullptr;
+    const int ni = nodeinfo_stride(S);
+    const long items = (long)ht.n_segs * (node ? S / 16 : S);
+    const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
+#define S2V_LAUNCH_HUB(PP, NODE, MU1) \
+    k_hub_partial<PP, NODE, MU1><<<grid, kThreads, 0, st>>>(S, ni, ht, colidx, src, info, theta1, qvec, partial)
+    if (p == 32) {
+        if (node) { if (mu1) S2V_LAUNCH_HUB(32, true, true); else S2V_LAUNCH_HUB(32, true, false); }
+        else { if (mu1) S2V_LAUNCH_HUB(32, false, true); else S2V_LAUNCH_HUB(32, false, false); }
+    } else {
+        if (node) { if (mu1) S2V_LAUNCH_HUB(64, true, true); else S2V_LAUNCH_HUB(64, true, false); }
+        else { if (mu1) S2V_LAUNCH_HUB(64, false, true); else S2V_LAUNCH_HUB(64, false, false); }
+    }
+#undef S2V_LAUNCH_HUB
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const int L = S * p;
+    const long total = (long)ht.n_hubs * L;
+    k_hub_combine<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(L, ht, partial, hub_sum);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------

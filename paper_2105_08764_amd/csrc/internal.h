@@ -19,6 +19,19 @@ constexpr int kSortTile = 1024;
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
+// Rows with more stored entries than this are "hubs": their neighbour sums are formed ahead of
+// the round kernel by many waves, each summing one segment of at most kHubDegree entries, so
+// that no single wave ever walks a long row.
+constexpr int kHubDegree = 256;
+
+struct HubTable {              // device pointers into the prepared head of the workspace
+    int n_hubs, n_segs;
+    const int32_t *hub_rows;     // [n_hubs] node ids, ascending
+    const int32_t *hub_seg_off;  // [n_hubs+1] segments of hub h are [off[h], off[h+1])
+    const int32_t *seg_begin;    // [n_segs] first CSR entry of the segment
+    const int32_t *seg_end;      // [n_segs] one past its last entry
+};
+
 struct ChunkTable {            // device pointers into the prepared head of the workspace
     int n_chunks;
     const int32_t *chunk_begin;      // [n_chunks] first node
@@ -39,9 +52,14 @@ constexpr int kRoundGridMax = 256 * 16;
 int round_grid(long n_vrows);
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
                            float *info);
+// Neighbour sums of the hub rows: hub_sum[h][S][p] = sum over the row of hub h of src[u][s][:]
+// (src == NULL: the round-1 rows recomputed from info).  partial is [n_segs][S][p] scratch.
+hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *colidx, const float *src,
+                           const float *info, const float *theta1, const float *qvec, float *partial, float *hub_sum);
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
                         const float *mu_in, float *mu_out, const float *info, const float *theta1,
-                        const float *theta2, const float *qvec, bool from_scalars, float *gpart);
+                        const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
+                        const float *hub_sum);
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum);
 hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu,
                        float *partial /*[n_chunks][S*p]*/, float *gsum /*[S][G][p]*/);
@@ -90,7 +108,7 @@ hipError_t launch_bwd_dzT(hipStream_t st, int p, int N, int S, const float *muT,
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
                             const float *dz_in, const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
                             const float *s_neg, const float *theta2, float *dc_part /*[kBwdGrid][3][p]*/,
-                            float *d2_part /*[kBwdGrid][p][p]*/);
+                            float *d2_part /*[kBwdGrid][p][p]*/, const HubTable &ht, const float *hub_sum);
 hipError_t launch_bwd_finish(hipStream_t st, int p, int dc_rows, int d2_rows, const BwdScratch &sc, const float *theta3,
                              const float *theta4, float *d1, float *d2, float *d3, float *d4);
 hipError_t launch_sgd(hipStream_t st, int p, float *const theta[7], const float *const grad[7], float lr);
