@@ -133,47 +133,56 @@ struct NodeAcc {
     float4 a[16 / Geo<P>::NPL];
 };
 
+#ifndef S2V_NODE_UNROLL
+#define S2V_NODE_UNROLL 2
+#endif
+
 template <int P>
 __device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict__ src, size_t node_stride /*S*P*/,
                                                         size_t blk_off /*s0*P*/, const int *__restrict__ colidx, int b,
                                                         int e, int lane) {
-    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI;
-    // Two accumulators per 64-entry chunk, folded into the running total after each chunk, so a
-    // row of d entries adds at most about 32 + d / 64 terms into any one float.
-    NodeAcc<P> total, acc, acc2;
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, U = S2V_NODE_UNROLL;
+    // U accumulators per 64-entry chunk, folded into the running total after each chunk, so a
+    // row of d entries adds at most about 64 / U + d / 64 terms into any one float.
+    NodeAcc<P> total, acc[U];
 #pragma unroll
     for (int c = 0; c < NC; ++c) total.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-    const size_t lane_off = blk_off + 4 * (size_t)lane;
+    const float *lane_src = src + blk_off + 4 * (size_t)lane;
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         const int cols = (lane < cnt) ? colidx[base + lane] : 0;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) acc.a[c] = acc2.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < U; ++k)
+#pragma unroll
+            for (int c = 0; c < NC; ++c) acc[k].a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
         int j = 0;
-        for (; j + 2 <= cnt; j += 2) {
-            const int u0 = __builtin_amdgcn_readlane(cols, j);
-            const int u1 = __builtin_amdgcn_readlane(cols, j + 1);
-            const float *p0 = src + (size_t)u0 * node_stride + lane_off;
-            const float *p1 = src + (size_t)u1 * node_stride + lane_off;
-            float4 v0[NC], v1[NC];
+        for (; j + U <= cnt; j += U) {
+            float4 v[U][NC];
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                const float *pk = lane_src + (size_t)__builtin_amdgcn_readlane(cols, j + k) * node_stride;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) v[k][c] = ld4(pk + c * RPI * P);
+            }
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+#pragma unroll
+                for (int c = 0; c < NC; ++c) acc[k].a[c] = add4(acc[k].a[c], v[k][c]);
+        }
+        for (; j < cnt; ++j) {
+            const float *p0 = lane_src + (size_t)__builtin_amdgcn_readlane(cols, j) * node_stride;
+            float4 v0[NC];
 #pragma unroll
             for (int c = 0; c < NC; ++c) v0[c] = ld4(p0 + c * RPI * P);
 #pragma unroll
-            for (int c = 0; c < NC; ++c) v1[c] = ld4(p1 + c * RPI * P);
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                acc.a[c] = add4(acc.a[c], v0[c]);
-                acc2.a[c] = add4(acc2.a[c], v1[c]);
-            }
-        }
-        if (j < cnt) {
-            const int u0 = __builtin_amdgcn_readlane(cols, j);
-            const float *p0 = src + (size_t)u0 * node_stride + lane_off;
-#pragma unroll
-            for (int c = 0; c < NC; ++c) acc.a[c] = add4(acc.a[c], ld4(p0 + c * RPI * P));
+            for (int c = 0; c < NC; ++c) acc[0].a[c] = add4(acc[0].a[c], v0[c]);
         }
 #pragma unroll
-        for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], add4(acc.a[c], acc2.a[c]));
+        for (int k = 1; k < U; ++k)
+#pragma unroll
+            for (int c = 0; c < NC; ++c) acc[0].a[c] = add4(acc[0].a[c], acc[k].a[c]);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], acc[0].a[c]);
     }
     return total;
 }

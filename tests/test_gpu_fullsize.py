@@ -1,0 +1,84 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+Configurations 3 and 4 (inference): the whole float64 oracle is run on the host (tens of seconds)
+and every embedding entry, graph sum and score is compared; selection is checked bit-exactly on
+the GPU's scores and, against the oracle's scores, outside the 1e-4 band.
+Configuration 5 (training, 16 states): predicted Q and loss against the oracle's forward pass of
+every state would take minutes, so two sampled states are checked against the oracle, the
+two-state minibatch gradient is checked against the oracle at full graph size, and the 16-state
+gradient (the timed launch shape) is checked through the identity grad(mean of losses) = mean of
+the single-state gradients, each of which takes the separately verified one-state path.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from tests import gpu_util as gu
+from tests.test_gpu_parity import _run_config
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.mark.timeout(900)
+def test_config3_full(oracle_mod):
+    _run_config(oracle_mod, 3, 1.0)
+
+
+@pytest.mark.timeout(900)
+def test_config4_full(oracle_mod):
+    _run_config(oracle_mod, 4, 1.0)
+
+
+@pytest.mark.timeout(1200)
+def test_config5_full_training(oracle_mod):
+    import torch
+
+    w = si.config(5, 1.0)
+    g = w.graph
+    S = w.x.shape[0]
+    print(f"config 5 full: n={g.n} nnz={g.nnz} S={S}", flush=True)
+
+    # (1) the timed shape: 16 states, one iteration
+    dev = gu.Device(g, w.p, w.T, S=S, training=True)
+    loss16, qp16, grads16 = dev.train_iter(dev.params(w.theta), w.x, w.action, w.target)
+    del dev
+    torch.cuda.empty_cache()
+    print(f"S=16 loss {loss16:.6g}", flush=True)
+
+    # (2) predicted Q of two sampled states against the oracle's forward pass
+    for b in (3, 12):
+        mu = oracle_mod.embed(g.rowptr, g.colidx, g.w, w.theta, w.x[b], w.T)
+        _, q = oracle_mod.q_scores(None, w.theta, mu)
+        rel = abs(qp16[b] - q[w.action[b]]) / abs(q[w.action[b]])
+        print(f"state {b}: Q gpu {qp16[b]:.8g} oracle {q[w.action[b]]:.8g} rel {rel:.2e}", flush=True)
+        assert rel <= TOL
+    del mu, q
+
+    # (3) gradient of the mean = mean of single-state gradients (one-state path, row-mode gathers)
+    dev1 = gu.Device(g, w.p, w.T, S=1, training=True)
+    acc = {k: np.zeros_like(v, dtype=np.float64) for k, v in grads16.items()}
+    loss_sum = 0.0
+    singles = {}
+    for b in range(S):
+        l1, q1, g1 = dev1.train_iter(dev1.params(w.theta), w.x[b:b + 1], w.action[b:b + 1], w.target[b:b + 1])
+        assert abs(q1[0] - qp16[b]) <= 1e-5 * abs(qp16[b])
+        loss_sum += l1 / S
+        for k in acc:
+            acc[k] += g1[k].astype(np.float64) / S
+        if b in (0, 1):
+            singles[b] = (l1, q1, g1)
+    assert abs(loss_sum - loss16) <= 1e-5 * abs(loss16)
+    errs = {k: gu.rel_err(grads16[k], acc[k], whole=True) for k in acc}
+    print("S=16 vs mean of S=1 gradients:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert max(errs.values()) <= TOL
+
+    # (4) the one-state gradient itself against the oracle at full graph size
+    oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, None, w.theta, w.x[0:1], w.T,
+                                              w.action[0:1], w.target[0:1])
+    l1, q1, g1 = singles[0]
+    assert abs(l1 - oloss) <= TOL * abs(oloss) and abs(q1[0] - oqp[0]) <= TOL * abs(oqp[0])
+    errs = {k: gu.rel_err(g1[k], ograds[k], whole=True) for k in g1}
+    print("S=1 gradient vs oracle:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert max(errs.values()) <= TOL
