@@ -107,14 +107,15 @@ SelLayout sel_layout(const HeadLayout &h, int64_t N, int64_t k) {
 }
 
 struct BwdLayout {
-    size_t dg, da, glo, ghi, head_part, dz0, dz1, dc_part, d2_part, dvec, red_tmp, hub_part, hub_sum, end;
+    size_t dg, da, glo, ghi, head_part, dz0, dz1, maskT, dc_part, d2_part, dvec, red_tmp, hub_part, hub_sum, end;
     int dc_rows, d2_rows;
 };
 BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     BwdLayout b;
     Carver c(h.end);
-    b.dc_rows = kBwdHeadGrid + (T - 1) * kBwdGrid;
-    b.d2_rows = (T - 1) * kBwdGrid;
+    // partial rows: the mask/seed kernel, every reversed round, and the action-node fix-up
+    b.dc_rows = kBwdHeadGrid + (T - 1) * kBwdGrid + (T >= 2 ? S * kFixSplit : 0);
+    b.d2_rows = (T - 1) * kBwdGrid + (T >= 2 ? S * kFixSplit : 0);
     const size_t width = (size_t)(3 * p > p * p ? 3 * p : p * p);
     const size_t segs = (size_t)(b.dc_rows + 63) / 64;
     b.dg = c.take(sizeof(float) * (size_t)S * p);
@@ -122,8 +123,9 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.glo = c.take(sizeof(int32_t) * S);
     b.ghi = c.take(sizeof(int32_t) * S);
     b.head_part = c.take(sizeof(float) * (size_t)S * (2 * p + 2 * p * p + 1));
-    b.dz0 = c.take(sizeof(float) * (size_t)N * S * p);
-    b.dz1 = c.take(T >= 2 ? sizeof(float) * (size_t)N * S * p : 0);
+    b.dz0 = c.take(T >= 3 ? sizeof(float) * (size_t)N * S * p : 0);
+    b.dz1 = c.take(T >= 4 ? sizeof(float) * (size_t)N * S * p : 0);
+    b.maskT = c.take(T >= 2 ? sizeof(unsigned long long) * (size_t)N * S : 0);
     b.dc_part = c.take(sizeof(float) * (size_t)b.dc_rows * 3 * p);
     b.d2_part = c.take(sizeof(float) * (size_t)b.d2_rows * p * p);
     b.dvec = c.take(sizeof(float) * 3 * p);
@@ -467,7 +469,7 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     for (int t = 2; t <= T; ++t) {
         const float *src = t == 2 ? nullptr : dest(t - 1);
-        S2V_TRY(launch_hub_sums(st, p, S, ht, g->colidx, src, info, params->theta1, qvec, hub_part, hub_sum));
+        S2V_TRY(launch_hub_sums(st, p, S, ht, g->colidx, src, info, params->theta1, qvec, nullptr, hub_part, hub_sum));
         SpanGuard span(ctx, t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND);
         S2V_TRY(launch_round(st, p, N, S, g->rowptr, g->colidx, src, dest(t), info, params->theta1, params->theta2,
                              qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum));
@@ -579,6 +581,7 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     sc.head_part = at<float>(ws, bl.head_part);
     sc.dz[0] = at<float>(ws, bl.dz0);
     sc.dz[1] = at<float>(ws, bl.dz1);
+    sc.maskT = at<unsigned long long>(ws, bl.maskT);
     sc.dc_part = at<float>(ws, bl.dc_part);
     sc.d2_part = at<float>(ws, bl.d2_part);
     sc.dvec = at<float>(ws, bl.dvec);
@@ -589,19 +592,32 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     S2V_TRY(launch_bwd_head(st, p, N, S, G, g->graph_off, params->theta5, params->theta6, params->theta7, muT, gsum,
                             action, target, sc, q_pred));
     S2V_TRY(launch_bwd_head_reduce(st, p, S, sc, loss, grads->theta5, grads->theta6, grads->theta7));
-    S2V_TRY(launch_bwd_dzT(st, p, N, S, muT, x, s_pos, s_neg, action, sc, sc.dz[0], sc.dc_part));
+    // dz^T is never materialised: its relu mask and its share of the sums come from one pass over mu^T
+    S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, x, s_pos, s_neg, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part));
     const HubTable ht = hub_table(ws, h, *pr);
     float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);
-    int cur = 0;
+    int cur = 1;  // the round t = T writes dz[0]
     for (int t = T; t >= 2; --t) {
         const int slot = T - t;  // 0 for the first reversed round
         float *dc_part = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)slot * kBwdGrid) * 3 * p;
         float *d2_part = sc.d2_part + (size_t)slot * kBwdGrid * p * p;
         const float *mu_prev = mu_saved + (size_t)(t - 2) * nsp;
-        S2V_TRY(launch_hub_sums(st, p, S, ht, g->colidx, sc.dz[cur], nullptr, nullptr, nullptr, hub_part, hub_sum));
-        SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
-        S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, g->colidx, sc.dz[cur], mu_prev, sc.dz[cur ^ 1], x, s_pos,
-                                 s_neg, params->theta2, dc_part, d2_part, ht, hub_sum));
+        const bool first = t == T;
+        const float *dz_in = first ? nullptr : sc.dz[cur];
+        float *dz_out = t == 2 ? nullptr : sc.dz[cur ^ 1];  // dz^1 only feeds the sums
+        S2V_TRY(launch_hub_sums(st, p, S, ht, g->colidx, dz_in, nullptr, nullptr, nullptr, first ? sc.maskT : nullptr,
+                                hub_part, hub_sum));
+        {
+            SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
+            S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, g->colidx, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
+                                     dz_out, x, s_pos, s_neg, params->theta2, dc_part, d2_part, ht, hub_sum));
+        }
+        if (first) {
+            float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;
+            float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdGrid * p * p;
+            S2V_TRY(launch_bwd_action_fix(st, p, N, S, g->rowptr, g->colidx, action, sc.maskT, sc, params->theta2,
+                                          mu_prev, dz_out, x, s_pos, s_neg, dc_fix, d2_fix));
+        }
         cur ^= 1;
     }
     S2V_TRY(launch_bwd_finish(st, p, bl.dc_rows, bl.d2_rows, sc, params->theta3, params->theta4, grads->theta1,

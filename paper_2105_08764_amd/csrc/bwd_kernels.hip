@@ -129,38 +129,55 @@ hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch
 }
 
 // ------------------------------------------------------------------------------------------
-// dz^T[v][s] = (dg[s] if v is in the action's graph, + da[s] if v is the action node) (.) [mu^T > 0],
-// plus this kernel's share of sum x dz, sum s+ dz, sum s- dz.  Streaming; fixed grid, each
-// workgroup owns a contiguous block of rows; thread = (row slot, float4 column).
+// Last-round seed.  dz^T[v][s] = (dg[s] if v is in the action's graph, + da[s] if v is the action
+// node) (.) [mu^T[v][s] > 0] is never written out: this kernel streams mu^T once, stores only the
+// relu mask (one 64-bit word per (node, state), bit j = entry j positive; skipped when T == 1) and
+// adds dz^T's share of sum x dz, sum s+ dz, sum s- dz.  Fixed grid, each workgroup owns a
+// contiguous block of rows; thread = (row slot, float4 column).
 // ------------------------------------------------------------------------------------------
 template <int P>
-__global__ __launch_bounds__(256) void k_bwd_dzT(long n_vrows, int N, int S, const float *__restrict__ muT,
-                                                 const float *__restrict__ x, const float *__restrict__ s_pos,
-                                                 const float *__restrict__ s_neg, const int32_t *__restrict__ action,
-                                                 const float *__restrict__ dg, const float *__restrict__ da,
-                                                 const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi,
-                                                 float *__restrict__ dz_out, float *__restrict__ dc_part) {
+__global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, const float *__restrict__ muT,
+                                                   const float *__restrict__ x, const float *__restrict__ s_pos,
+                                                   const float *__restrict__ s_neg, const int32_t *__restrict__ action,
+                                                   const float *__restrict__ dg, const float *__restrict__ da,
+                                                   const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi,
+                                                   unsigned long long *__restrict__ mask,
+                                                   float *__restrict__ dc_part) {
     constexpr int LPR = P / 4, SLOTS = 256 / LPR;
     __shared__ float red[3][SLOTS][P];
     const int c4 = threadIdx.x % LPR, slot = threadIdx.x / LPR;
     const long per = (n_vrows + gridDim.x - 1) / gridDim.x;
     const long r_begin = (long)blockIdx.x * per, r_end = min(n_vrows, r_begin + per);
     float4 ax = make_float4(0.f, 0.f, 0.f, 0.f), ap = ax, an = ax;
-    for (long r = r_begin + slot; r < r_end; r += SLOTS) {
-        const int v = (int)(r / S), s = (int)(r - (long)v * S);
-        const float4 mu = ld4(muT + (size_t)r * P + 4 * c4);
-        float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * c4);
-        if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * c4));
-        d.x = mu.x > 0.f ? d.x : 0.f;
-        d.y = mu.y > 0.f ? d.y : 0.f;
-        d.z = mu.z > 0.f ? d.z : 0.f;
-        d.w = mu.w > 0.f ? d.w : 0.f;
-        st4(dz_out + (size_t)r * P + 4 * c4, d);
-        const float xs = x[(size_t)s * N + v], sp = s_pos[v], sn = s_neg[v];
-        ax.x += xs * d.x; ax.y += xs * d.y; ax.z += xs * d.z; ax.w += xs * d.w;
-        ap.x += sp * d.x; ap.y += sp * d.y; ap.z += sp * d.z; ap.w += sp * d.w;
-        an.x += sn * d.x; an.y += sn * d.y; an.z += sn * d.z; an.w += sn * d.w;
+    // all lanes of a wave run the same number of iterations (the shuffles below need that)
+    for (long rbase = r_begin; rbase < r_end; rbase += SLOTS) {
+        const long r = rbase + slot;
+        const bool valid = r < r_end;
+        unsigned long long word = 0ull;
+        if (valid) {
+            const int v = (int)(r / S), s = (int)(r - (long)v * S);
+            const float4 mu = ld4(muT + (size_t)r * P + 4 * c4);
+            float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * c4);
+            if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * c4));
+            d.x = mu.x > 0.f ? d.x : 0.f;
+            d.y = mu.y > 0.f ? d.y : 0.f;
+            d.z = mu.z > 0.f ? d.z : 0.f;
+            d.w = mu.w > 0.f ? d.w : 0.f;
+            const unsigned nib = (mu.x > 0.f ? 1u : 0u) | (mu.y > 0.f ? 2u : 0u) | (mu.z > 0.f ? 4u : 0u) |
+                                 (mu.w > 0.f ? 8u : 0u);
+            word = (unsigned long long)nib << (4 * c4);
+            const float xs = x[(size_t)s * N + v], sp = s_pos[v], sn = s_neg[v];
+            ax.x += xs * d.x; ax.y += xs * d.y; ax.z += xs * d.z; ax.w += xs * d.w;
+            ap.x += sp * d.x; ap.y += sp * d.y; ap.z += sp * d.z; ap.w += sp * d.w;
+            an.x += sn * d.x; an.y += sn * d.y; an.z += sn * d.z; an.w += sn * d.w;
+        }
+        if (mask) {
+            // OR the nibbles of the LPR lanes that share a row
+#pragma unroll
+            for (int m = 1; m < LPR; m <<= 1) word |= __shfl_xor(word, m);
+            if (valid && c4 == 0) mask[r] = word;
+        }
     }
     st4(&red[0][slot][4 * c4], ax);
     st4(&red[1][slot][4 * c4], ap);
@@ -174,50 +191,52 @@ __global__ __launch_bounds__(256) void k_bwd_dzT(long n_vrows, int N, int S, con
     }
 }
 
-hipError_t launch_bwd_dzT(hipStream_t st, int p, int N, int S, const float *muT, const float *x, const float *s_pos,
-                          const float *s_neg, const int32_t *action, const BwdScratch &sc, float *dz_out,
-                          float *dc_part) {
+hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const float *x, const float *s_pos,
+                            const float *s_neg, const int32_t *action, const BwdScratch &sc,
+                            unsigned long long *mask, float *dc_part) {
     const long n_vrows = (long)N * S;
     if (p == 32)
-        k_bwd_dzT<32><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, x, s_pos, s_neg, action, sc.dg, sc.da, sc.glo,
-                                                    sc.ghi, dz_out, dc_part);
+        k_bwd_maskT<32><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, x, s_pos, s_neg, action, sc.dg, sc.da, sc.glo,
+                                                      sc.ghi, mask, dc_part);
     else
-        k_bwd_dzT<64><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, x, s_pos, s_neg, action, sc.dg, sc.da, sc.glo,
-                                                    sc.ghi, dz_out, dc_part);
+        k_bwd_maskT<64><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, x, s_pos, s_neg, action, sc.dg, sc.da, sc.glo,
+                                                      sc.ghi, mask, dc_part);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
-// One reversed round t (T >= t >= 2), fused: G = A dz^t (same gather as the forward round),
+// One reversed round t (T >= t >= 2), fused: G = A dz^t (same gathers as the forward round),
 // dtheta2 partial += G^T mu^{t-1}, dz^{t-1} = (G theta2) (.) [mu^{t-1} > 0], and this round's share
 // of sum x dz^{t-1}, sum s+- dz^{t-1}.  Wave tiles of 16 rows of the [N*S][p] matrices; the
 // p x p accumulator of dtheta2 stays in registers over all tiles of the wave.
+//   NODE: S is a multiple of 16 (a tile is 16 states of one node).
+//   MASK: this is round t = T.  dz^T is not in memory; apart from the action node's own term
+//         (added afterwards by k_bwd_action_fix, the round being linear in dz^T) it equals
+//         dg[s] (.) [mu^T > 0] on the nodes of the action's graph, so G_u = dg[s] (.) (number of
+//         neighbours of u whose mask bit is set): the gather reads 8-byte mask words, not rows.
+//   dz_out may be NULL (t == 2: dz^1 is needed for the sums only).
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE>
-__global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int S, const int32_t *__restrict__ rowptr,
-                                                        const int32_t *__restrict__ colidx,
-                                                        const float *__restrict__ dz_in,
-                                                        const float *__restrict__ mu_prev, float *__restrict__ dz_out,
-                                                        const float *__restrict__ x, const float *__restrict__ s_pos,
-                                                        const float *__restrict__ s_neg,
-                                                        const float *__restrict__ theta2, float *__restrict__ dc_part,
-                                                        float *__restrict__ d2_part, HubTable ht,
-                                                        const float *__restrict__ hub_sum) {
+template <int P, bool NODE, bool MASK>
+__global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
+    int n_vrows, int N, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
+    const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
+    float *__restrict__ dz_out, const float *__restrict__ x, const float *__restrict__ s_pos,
+    const float *__restrict__ s_neg, const float *__restrict__ theta2, float *__restrict__ dc_part,
+    float *__restrict__ d2_part, HubTable ht, const float *__restrict__ hub_sum) {
     using Ge = Geo<P>;
     constexpr int CB = Ge::CB, STRIDE = Ge::STRIDE;
     constexpr int TILE_F = kTileRows * STRIDE;
-    // per wave: tile of G and tile of mu^{t-1}; reused at the end for the cross-wave reductions
-    constexpr int LDS_F = (2 * kWaves * TILE_F > kWaves * P * 16) ? 2 * kWaves * TILE_F : kWaves * P * 16;
-    __shared__ __attribute__((aligned(16))) float lds[LDS_F];
+    static_assert(kWaves * TILE_F >= kWaves * 16 * P, "tile area is reused for the final reductions");
+    __shared__ __attribute__((aligned(16))) float lds[kWaves * TILE_F];
+    __shared__ __attribute__((aligned(16))) float lds_b[P * STRIDE];   // theta2^T: B operand of G theta2
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float *tile_g = lds + (2 * wave) * TILE_F;
-    float *tile_m = tile_g + TILE_F;
+    float *tile_g = lds + wave * TILE_F;
     const int li = lane % Ge::LPR;
     const int jl = lane & 15, gl = lane >> 4;
 
-    Frag<P> bfrag[CB];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) bfrag[cb] = load_b_frag_cols<P>(theta2, cb, lane);
+    stage_matrix_lds<P>(lds_b, theta2, true);
+    __syncthreads();
 
     f32x4 d2acc[CB][CB];
 #pragma unroll
@@ -241,16 +260,18 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
         const float xs = valid ? x[(size_t)s * N + v] : 0.f;
         const float sp = valid ? s_pos[v] : 0.f;
         const float sn = valid ? s_neg[v] : 0.f;
+        // MASK: rows outside the action's graph receive nothing from the broadcast part of dz^T
+        const bool in_graph = MASK ? (valid && v >= glo[s] && v < ghi[s]) : true;
 
-        // mu^{t-1} rows of this tile (16 contiguous rows): issue the loads now, park them in LDS after the gather
-        constexpr int MV = (kTileRows * Ge::LPR) / 64;
-        float4 mv[MV];
+        // mu^{t-1} in the layout of the matrix-core result (row 4*gl + k, column 16*cb + jl): it is the
+        // relu mask of this tile's output AND the B operand of the dtheta2 update.  Rows past the end: 0.
+        float mp[CB][4];
 #pragma unroll
-        for (int c = 0; c < MV; ++c) {
-            const int f = c * 64 + lane;            // float4 index inside the tile
-            const int row = f / Ge::LPR, col4 = f % Ge::LPR;
-            mv[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r0 + row < n_vrows) mv[c] = ld4(mu_prev + (size_t)(r0 + row) * P + 4 * col4);
+        for (int k = 0; k < 4; ++k) {
+            const int ro = r0 + 4 * gl + k;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+                mp[cb][k] = ro < n_vrows ? mu_prev[(size_t)ro * P + 16 * cb + jl] : 0.f;
         }
 
         if (NODE) {
@@ -260,8 +281,25 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
             if (e - b > kHubDegree) {
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
                 ga = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
+            } else if (MASK) {
+                ga = gather_node_block_bits<P>(maskT, S, s0, colidx, b, e, lane);
             } else {
                 ga = gather_node_block<P>(dz_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+            }
+            if (MASK) {
+                // counts -> G: times dg of this lane's state and columns (the node is wave-uniform)
+                constexpr int RPI = Ge::NPL, NC = 16 / RPI;
+                const int vn = __builtin_amdgcn_readfirstlane(v);
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const int sl = s0 + c * RPI + lane / Ge::LPR;      // this lane's state for block c
+                    const bool ing = vn >= glo[sl] && vn < ghi[sl];
+                    const float4 d = ld4(dg + (size_t)sl * P + 4 * li);
+                    ga.a[c].x = ing ? ga.a[c].x * d.x : 0.f;
+                    ga.a[c].y = ing ? ga.a[c].y * d.y : 0.f;
+                    ga.a[c].z = ing ? ga.a[c].z * d.z : 0.f;
+                    ga.a[c].w = ing ? ga.a[c].w * d.w : 0.f;
+                }
             }
             store_node_block<P>(tile_g, ga, lane);
         } else {
@@ -281,17 +319,23 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
                 if (e - b > kHubDegree) {
                     const int h = hub_index(ht.hub_rows, ht.n_hubs, __shfl(v, i));
                     a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
+                } else if (MASK) {
+                    const BitsRow bits{maskT, S, si, 4 * li};
+                    a = gather_row_sum<P>(bits, colidx, b, e, cols, lane);
                 } else {
                     const MemRow mem{dz_in, row_stride, (size_t)si * P + 4 * li};
                     a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
                 }
+                if (MASK) {
+                    const bool ing = __shfl((int)in_graph, i) != 0;
+                    const float4 d = ld4(dg + (size_t)si * P + 4 * li);
+                    a.x = ing ? a.x * d.x : 0.f;
+                    a.y = ing ? a.y * d.y : 0.f;
+                    a.z = ing ? a.z * d.z : 0.f;
+                    a.w = ing ? a.w * d.w : 0.f;
+                }
                 if (lane < Ge::LPR) st4(tile_g + i * STRIDE + 4 * lane, a);
             }
-        }
-#pragma unroll
-        for (int c = 0; c < MV; ++c) {
-            const int f = c * 64 + lane;
-            st4(tile_m + (f / Ge::LPR) * STRIDE + 4 * (f % Ge::LPR), mv[c]);
         }
         __builtin_amdgcn_wave_barrier();
 
@@ -301,7 +345,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            acc[cb] = mfma_tile<P>(afrag, bfrag[cb], acc[cb]);
+            acc[cb] = mfma_tile<P>(afrag, load_b_frag_lds<P>(lds_b, cb, lane), acc[cb]);
         }
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
@@ -309,34 +353,28 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
             const float xi = __shfl(xs, i), spi = __shfl(sp, i), sni = __shfl(sn, i);
             const int ro = r0 + i;
             if (ro < n_vrows) {
-                float *out = dz_out + (size_t)ro * P + jl;
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
-                    const float mprev = tile_m[i * STRIDE + 16 * cb + jl];
-                    const float d = mprev > 0.f ? acc[cb][rr] : 0.f;
-                    out[16 * cb] = d;
+                    const float d = mp[cb][rr] > 0.f ? acc[cb][rr] : 0.f;
+                    if (dz_out) dz_out[(size_t)ro * P + 16 * cb + jl] = d;
                     cx[cb] += xi * d; cp[cb] += spi * d; cn[cb] += sni * d;
                 }
             }
         }
 
         // dtheta2[i][j] += sum_r G[r][i] mu^{t-1}[r][j]: 16x16 blocks, k runs over the 16 tile rows
-        // (lane group gl takes rows 4*gl + ks at k-step ks); rows past the end hold zeros in both tiles.
-        float a2[CB][4], b2[CB][4];
+        // (lane group gl takes row 4*gl + ks at k-step ks); rows past the end are zero in both operands.
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
+        for (int ib = 0; ib < CB; ++ib) {
+            float a2[4];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                a2[cb][ks] = tile_g[(4 * gl + ks) * STRIDE + 16 * cb + jl];
-                b2[cb][ks] = tile_m[(4 * gl + ks) * STRIDE + 16 * cb + jl];
-            }
-#pragma unroll
-        for (int ib = 0; ib < CB; ++ib)
+            for (int ks = 0; ks < 4; ++ks) a2[ks] = tile_g[(4 * gl + ks) * STRIDE + 16 * ib + jl];
 #pragma unroll
             for (int jb = 0; jb < CB; ++jb)
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
-                    d2acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[ib][ks], b2[jb][ks], d2acc[ib][jb], 0, 0, 0);
+                    d2acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[ks], mp[jb][ks], d2acc[ib][jb], 0, 0, 0);
+        }
         __builtin_amdgcn_wave_barrier();
     }
 
@@ -380,20 +418,109 @@ __global__ __launch_bounds__(kThreads) void k_bwd_round(int n_vrows, int N, int 
 }
 
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
-                            const float *dz_in, const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
+                            const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
+                            const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
                             const float *s_neg, const float *theta2, float *dc_part, float *d2_part,
                             const HubTable &ht, const float *hub_sum) {
     const long n_vrows = (long)N * S;
-    const bool node = (S % 16) == 0;
-#define S2V_LAUNCH_BWD(PP, NODE)                                                                                  \
-    k_bwd_round<PP, NODE><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, mu_prev, dz_out, x, \
-                                                         s_pos, s_neg, theta2, dc_part, d2_part, ht, hub_sum)
-    if (p == 32) {
-        if (node) S2V_LAUNCH_BWD(32, true); else S2V_LAUNCH_BWD(32, false);
-    } else {
-        if (node) S2V_LAUNCH_BWD(64, true); else S2V_LAUNCH_BWD(64, false);
-    }
+    const bool node = (S % 16) == 0, mask = maskT != nullptr;
+#define S2V_LAUNCH_BWD(PP, NODE, MASK)                                                                              \
+    k_bwd_round<PP, NODE, MASK><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, maskT, sc.dg, \
+                                                               sc.glo, sc.ghi, mu_prev, dz_out, x, s_pos, s_neg, theta2, \
+                                                               dc_part, d2_part, ht, hub_sum)
+#define S2V_LAUNCH_BWD_P(PP)                                                                          \
+    do {                                                                                              \
+        if (node) { if (mask) S2V_LAUNCH_BWD(PP, true, true); else S2V_LAUNCH_BWD(PP, true, false); }  \
+        else { if (mask) S2V_LAUNCH_BWD(PP, false, true); else S2V_LAUNCH_BWD(PP, false, false); }     \
+    } while (0)
+    if (p == 32) S2V_LAUNCH_BWD_P(32); else S2V_LAUNCH_BWD_P(64);
+#undef S2V_LAUNCH_BWD_P
 #undef S2V_LAUNCH_BWD
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// The action node's own term of dz^T, which the MASK round leaves out:
+//   dz^T[a_s][s] += da[s] (.) [mu^T[a_s][s] > 0] =: g_s.
+// The round is linear in dz^T, so its effect is added here.  Only the rows u in N(a_s) see it:
+//   G_u += g_s  =>  dz^{T-1}_u += (theta2^T g_s) (.) [mu^{T-1}_u > 0],  dtheta2 += g_s (sum_u mu^{T-1}_u)^T,
+// plus the matching share of the sum x dz, sum s+- dz partials.  Grid = (kFixSplit, S): block
+// (k, s) takes the entries of row a_s congruent to k modulo kFixSplit; thread = (slot, column).
+// ------------------------------------------------------------------------------------------
+template <int P>
+__global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int32_t *__restrict__ rowptr,
+                                                        const int32_t *__restrict__ colidx,
+                                                        const int32_t *__restrict__ action,
+                                                        const unsigned long long *__restrict__ maskT,
+                                                        const float *__restrict__ da,
+                                                        const float *__restrict__ theta2,
+                                                        const float *__restrict__ mu_prev, float *__restrict__ dz_out,
+                                                        const float *__restrict__ x, const float *__restrict__ s_pos,
+                                                        const float *__restrict__ s_neg, float *__restrict__ dc_part,
+                                                        float *__restrict__ d2_part) {
+    constexpr int SLOTS = 256 / P;
+    __shared__ float g[P], w[P];
+    __shared__ float red[4][SLOTS][P];
+    const int s = blockIdx.y, split = blockIdx.x;
+    const int j = threadIdx.x % P, slot = threadIdx.x / P;
+    const int a = action[s];
+    if (threadIdx.x < P) {
+        const unsigned long long word = maskT[(size_t)a * S + s];
+        g[threadIdx.x] = ((word >> threadIdx.x) & 1ull) ? da[(size_t)s * P + threadIdx.x] : 0.f;
+    }
+    __syncthreads();
+    if (threadIdx.x < P) {
+        float acc = 0.f;
+        for (int k = 0; k < P; ++k) acc += theta2[k * P + threadIdx.x] * g[k];
+        w[threadIdx.x] = acc;
+    }
+    __syncthreads();
+    float cx = 0.f, cp = 0.f, cn = 0.f, msum = 0.f;
+    const int b = rowptr[a], e = rowptr[a + 1];
+    for (int idx = b + split + slot * kFixSplit; idx < e; idx += SLOTS * kFixSplit) {
+        const int u = colidx[idx];
+        const size_t off = ((size_t)u * S + s) * P + j;
+        const float mprev = mu_prev[off];
+        const float d = mprev > 0.f ? w[j] : 0.f;
+        if (dz_out) dz_out[off] += d;
+        cx += x[(size_t)s * N + u] * d;
+        cp += s_pos[u] * d;
+        cn += s_neg[u] * d;
+        msum += mprev;
+    }
+    red[0][slot][j] = cx; red[1][slot][j] = cp; red[2][slot][j] = cn; red[3][slot][j] = msum;
+    __syncthreads();
+    const size_t row = (size_t)s * kFixSplit + split;
+    if (threadIdx.x < P) {
+        float t[4];
+        for (int c = 0; c < 4; ++c) {
+            float acc = 0.f;
+            for (int k = 0; k < SLOTS; ++k) acc += red[c][k][threadIdx.x];
+            t[c] = acc;
+        }
+        dc_part[row * 3 * P + threadIdx.x] = t[0];
+        dc_part[row * 3 * P + P + threadIdx.x] = t[1];
+        dc_part[row * 3 * P + 2 * P + threadIdx.x] = t[2];
+        red[3][0][threadIdx.x] = t[3];
+    }
+    __syncthreads();
+    for (int el = threadIdx.x; el < P * P; el += 256) {
+        const int i = el / P, jj = el - i * P;
+        d2_part[row * P * P + el] = g[i] * red[3][0][jj];
+    }
+}
+
+hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+                                 const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
+                                 const float *theta2, const float *mu_prev, float *dz_out, const float *x,
+                                 const float *s_pos, const float *s_neg, float *dc_part, float *d2_part) {
+    const dim3 grid(kFixSplit, S);
+    if (p == 32)
+        k_bwd_action_fix<32><<<grid, 256, 0, st>>>(N, S, rowptr, colidx, action, maskT, sc.da, theta2, mu_prev, dz_out, x,
+                                                   s_pos, s_neg, dc_part, d2_part);
+    else
+        k_bwd_action_fix<64><<<grid, 256, 0, st>>>(N, S, rowptr, colidx, action, maskT, sc.da, theta2, mu_prev, dz_out, x,
+                                                   s_pos, s_neg, dc_part, d2_part);
     return hipGetLastError();
 }
 

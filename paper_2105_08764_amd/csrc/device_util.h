@@ -59,6 +59,21 @@ struct Mu1Row {
     }
 };
 
+// Row (u, s) of the relu mask of an embedding, one 64-bit word per (node, state) with bit j set
+// when entry j is positive, expanded to 0.0 / 1.0 floats: summing these rows counts, per column,
+// the neighbours whose entry is positive (exact in float up to 2^24 neighbours).
+struct BitsRow {
+    const unsigned long long *__restrict__ mask;
+    int S;
+    int s;
+    int shift;  // 4 * li
+    __device__ __forceinline__ float4 operator()(int u) const {
+        const unsigned nib = (unsigned)(mask[(size_t)u * S + s] >> shift);
+        return make_float4((float)(nib & 1u), (float)((nib >> 1) & 1u), (float)((nib >> 2) & 1u),
+                           (float)((nib >> 3) & 1u));
+    }
+};
+
 // Sum over the stored entries [b, e) of one CSR row of the neighbours' P-float rows (row mode:
 // any S).  All 64 lanes take part: lane = (group gq, lane-in-row li); one wave-wide load fetches
 // NPL neighbour rows.  `cols` holds colidx[b + lane] for the first (up to) 64 entries, loaded by
@@ -224,6 +239,41 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
         for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], acc.a[c]);
     }
     return total;
+}
+
+// Node mode over relu-mask words (see BitsRow): per column, the number of neighbours of the node
+// whose entry is positive, for the 16 states s0 .. s0+15.
+template <int P>
+__device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long long *__restrict__ mask, int S, int s0,
+                                                             const int *__restrict__ colidx, int b, int e, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+    int4 cnt[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) cnt[c] = make_int4(0, 0, 0, 0);
+    const int shift = 4 * (lane % LPR);
+    const int srow = s0 + lane / LPR;
+    for (int base = b; base < e; base += 64) {
+        const int n = min(64, e - base);
+        const int cols = (lane < n) ? colidx[base + lane] : 0;
+        for (int j = 0; j < n; ++j) {
+            const unsigned long long *w = mask + (size_t)__builtin_amdgcn_readlane(cols, j) * S + srow;
+            unsigned nib[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) nib[c] = (unsigned)(w[c * RPI] >> shift);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                cnt[c].x += (int)(nib[c] & 1u);
+                cnt[c].y += (int)((nib[c] >> 1) & 1u);
+                cnt[c].z += (int)((nib[c] >> 2) & 1u);
+                cnt[c].w += (int)((nib[c] >> 3) & 1u);
+            }
+        }
+    }
+    NodeAcc<P> acc;
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+        acc.a[c] = make_float4((float)cnt[c].x, (float)cnt[c].y, (float)cnt[c].z, (float)cnt[c].w);
+    return acc;
 }
 
 // Index of node v in the ascending list of hub rows (v is known to be a hub).

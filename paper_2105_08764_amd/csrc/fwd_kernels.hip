@@ -318,13 +318,15 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
 // kHubDegree neighbour rows with the same gather code as the round kernel.  Stage B adds the
 // segment partials of each hub in segment order.
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE, bool MU1>
+template <int P, bool NODE, int SRC>   // SRC: 0 rows in memory, 1 round-1 rows from scalars, 2 relu-mask bits
 __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTable ht,
                                                           const int32_t *__restrict__ colidx,
                                                           const float *__restrict__ src,
                                                           const float *__restrict__ info,
                                                           const float *__restrict__ theta1,
-                                                          const float *__restrict__ qvec, float *__restrict__ partial) {
+                                                          const float *__restrict__ qvec,
+                                                          const unsigned long long *__restrict__ mask,
+                                                          float *__restrict__ partial) {
     using G = Geo<P>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane % G::LPR;
@@ -335,8 +337,10 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTabl
         const int b = ht.seg_begin[seg], e = ht.seg_end[seg];
         if (NODE) {
             const int s0 = blk * 16;
-            const NodeAcc<P> acc = MU1 ? gather_node_block_mu1<P>(info, ni, s0, theta1, qvec, colidx, b, e, lane)
-                                       : gather_node_block<P>(src, (size_t)S * P, (size_t)s0 * P, colidx, b, e, lane);
+            NodeAcc<P> acc;
+            if (SRC == 1) acc = gather_node_block_mu1<P>(info, ni, s0, theta1, qvec, colidx, b, e, lane);
+            else if (SRC == 2) acc = gather_node_block_bits<P>(mask, S, s0, colidx, b, e, lane);
+            else acc = gather_node_block<P>(src, (size_t)S * P, (size_t)s0 * P, colidx, b, e, lane);
             float *out = partial + ((size_t)seg * S + s0) * P;
 #pragma unroll
             for (int c = 0; c < 16 / G::NPL; ++c) st4(out + c * G::NPL * P + 4 * lane, acc.a[c]);
@@ -344,9 +348,12 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTabl
             const int s = blk;
             const int cols = (lane < min(64, e - b)) ? colidx[b + lane] : 0;
             float4 a;
-            if (MU1) {
+            if (SRC == 1) {
                 Mu1Row mu1{info, ni, s, ld4(theta1 + 4 * li), ld4(qvec + 4 * li), ld4(qvec + P + 4 * li)};
                 a = gather_row_sum<P>(mu1, colidx, b, e, cols, lane);
+            } else if (SRC == 2) {
+                const BitsRow bits{mask, S, s, 4 * li};
+                a = gather_row_sum<P>(bits, colidx, b, e, cols, lane);
             } else {
                 const MemRow mem{src, (size_t)S * P, (size_t)s * P + 4 * li};
                 a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
@@ -368,21 +375,28 @@ __global__ __launch_bounds__(256) void k_hub_combine(int L, HubTable ht, const f
 }
 
 hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *colidx, const float *src,
-                           const float *info, const float *theta1, const float *qvec, float *partial, float *hub_sum) {
+                           const float *info, const float *theta1, const float *qvec,
+                           const unsigned long long *mask, float *partial, float *hub_sum) {
     if (ht.n_hubs == 0) return hipSuccess;
-    const bool node = (S % 16) == 0, mu1 = src == nullptr;
+    const bool node = (S % 16) == 0;
+    const int kind = mask ? 2 : (src ? 0 : 1);
     const int ni = nodeinfo_stride(S);
     const long items = (long)ht.n_segs * (node ? S / 16 : S);
     const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
-#define S2V_LAUNCH_HUB(PP, NODE, MU1) \
-    k_hub_partial<PP, NODE, MU1><<<grid, kThreads, 0, st>>>(S, ni, ht, colidx, src, info, theta1, qvec, partial)
-    if (p == 32) {
-        if (node) { if (mu1) S2V_LAUNCH_HUB(32, true, true); else S2V_LAUNCH_HUB(32, true, false); }
-        else { if (mu1) S2V_LAUNCH_HUB(32, false, true); else S2V_LAUNCH_HUB(32, false, false); }
-    } else {
-        if (node) { if (mu1) S2V_LAUNCH_HUB(64, true, true); else S2V_LAUNCH_HUB(64, true, false); }
-        else { if (mu1) S2V_LAUNCH_HUB(64, false, true); else S2V_LAUNCH_HUB(64, false, false); }
-    }
+#define S2V_LAUNCH_HUB(PP, NODE, SRC) \
+    k_hub_partial<PP, NODE, SRC><<<grid, kThreads, 0, st>>>(S, ni, ht, colidx, src, info, theta1, qvec, mask, partial)
+#define S2V_LAUNCH_HUB_P(PP)                                                                           \
+    do {                                                                                               \
+        if (node) {                                                                                    \
+            if (kind == 0) S2V_LAUNCH_HUB(PP, true, 0); else if (kind == 1) S2V_LAUNCH_HUB(PP, true, 1);   \
+            else S2V_LAUNCH_HUB(PP, true, 2);                                                          \
+        } else {                                                                                       \
+            if (kind == 0) S2V_LAUNCH_HUB(PP, false, 0); else if (kind == 1) S2V_LAUNCH_HUB(PP, false, 1); \
+            else S2V_LAUNCH_HUB(PP, false, 2);                                                         \
+        }                                                                                              \
+    } while (0)
+    if (p == 32) S2V_LAUNCH_HUB_P(32); else S2V_LAUNCH_HUB_P(64);
+#undef S2V_LAUNCH_HUB_P
 #undef S2V_LAUNCH_HUB
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;

@@ -13,6 +13,8 @@ constexpr int kChunkNodes = 1024;
 // per-workgroup partial gradients are summed does not depend on the device.
 constexpr int kBwdGrid = 1024;
 constexpr int kBwdHeadGrid = 1024;
+// Blocks per state of the action-node fix-up of the backward pass (each adds one partial row).
+constexpr int kFixSplit = 16;
 // Elements per block of the selection scan / sort passes.
 constexpr int kScanBlock = 2048;
 constexpr int kSortTile = 1024;
@@ -53,9 +55,11 @@ int round_grid(long n_vrows);
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
                            float *info);
 // Neighbour sums of the hub rows: hub_sum[h][S][p] = sum over the row of hub h of src[u][s][:]
-// (src == NULL: the round-1 rows recomputed from info).  partial is [n_segs][S][p] scratch.
+// (mask != NULL: counts of set relu-mask bits instead; else src == NULL: the round-1 rows
+// recomputed from info).  partial is [n_segs][S][p] scratch.
 hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *colidx, const float *src,
-                           const float *info, const float *theta1, const float *qvec, float *partial, float *hub_sum);
+                           const float *info, const float *theta1, const float *qvec,
+                           const unsigned long long *mask, float *partial, float *hub_sum);
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
                         const float *mu_in, float *mu_out, const float *info, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
@@ -92,6 +96,7 @@ struct BwdScratch {
     int32_t *ghi;       // [S] one past its last node
     float *head_part;   // [S][2p + 2*p*p + 1]  per-state partials of dtheta5, dtheta6, dtheta7, loss
     float *dz[2];       // [N][S][p] each
+    unsigned long long *maskT;  // [N][S] relu mask of mu^T
     float *dc_part;     // [dc_rows][3][p]   partial sums of x*dz, s+ * dz, s- * dz
     float *d2_part;     // [d2_rows][p][p]   partial sums of G (x) mu
     float *dvec;        // [3][p] reduced dtheta1, dq+, dq-
@@ -102,13 +107,20 @@ hipError_t launch_bwd_head(hipStream_t st, int p, int N, int S, int G, const int
                            const int32_t *action, const float *target, const BwdScratch &sc, float *q_pred);
 hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch &sc, float *loss, float *d5, float *d6,
                                   float *d7);
-hipError_t launch_bwd_dzT(hipStream_t st, int p, int N, int S, const float *muT, const float *x, const float *s_pos,
-                          const float *s_neg, const int32_t *action, const BwdScratch &sc, float *dz_out,
-                          float *dc_part /*[kBwdHeadGrid][3][p]*/);
+hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const float *x, const float *s_pos,
+                            const float *s_neg, const int32_t *action, const BwdScratch &sc,
+                            unsigned long long *mask /*[N][S] or NULL*/, float *dc_part /*[kBwdHeadGrid][3][p]*/);
+// maskT != NULL selects the first reversed round (t = T), which reads relu-mask words instead of dz_in.
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
-                            const float *dz_in, const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
+                            const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
+                            const float *mu_prev, float *dz_out /*may be NULL*/, const float *x, const float *s_pos,
                             const float *s_neg, const float *theta2, float *dc_part /*[kBwdGrid][3][p]*/,
                             float *d2_part /*[kBwdGrid][p][p]*/, const HubTable &ht, const float *hub_sum);
+hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+                                 const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
+                                 const float *theta2, const float *mu_prev, float *dz_out /*may be NULL*/,
+                                 const float *x, const float *s_pos, const float *s_neg,
+                                 float *dc_part /*[S*kFixSplit][3][p]*/, float *d2_part /*[S*kFixSplit][p][p]*/);
 hipError_t launch_bwd_finish(hipStream_t st, int p, int dc_rows, int d2_rows, const BwdScratch &sc, const float *theta3,
                              const float *theta4, float *d1, float *d2, float *d3, float *d4);
 hipError_t launch_sgd(hipStream_t st, int p, float *const theta[7], const float *const grad[7], float lr);
