@@ -220,19 +220,31 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
         const int cols = (lane < cnt) ? colidx[base + lane] : 0;
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int j = 0; j < cnt; ++j) {
-            const int u = __builtin_amdgcn_readlane(cols, j);
-            const float *r = info + (size_t)u * ni;
-            const float sp = r[0], sn = r[1];
-            const float bx = sp * qp.x + sn * qn.x, by = sp * qp.y + sn * qn.y;
-            const float bz = sp * qp.z + sn * qn.z, bw = sp * qp.w + sn * qn.w;
+        // four neighbours per step: their scalar loads are issued together
+        for (int j = 0; j < cnt; j += 4) {
+            float sp[4], sn[4], xs[4][NC];
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const float xs = r[srow + c * RPI];
-                acc.a[c].x += fmaxf(xs * t1.x + bx, 0.f);
-                acc.a[c].y += fmaxf(xs * t1.y + by, 0.f);
-                acc.a[c].z += fmaxf(xs * t1.z + bz, 0.f);
-                acc.a[c].w += fmaxf(xs * t1.w + bw, 0.f);
+            for (int k = 0; k < 4; ++k) {
+                const int jj = min(j + k, cnt - 1);   // past the end: re-read the last record, dropped below
+                const float *r = info + (size_t)__builtin_amdgcn_readlane(cols, jj) * ni;
+                sp[k] = r[0];
+                sn[k] = r[1];
+#pragma unroll
+                for (int c = 0; c < NC; ++c) xs[k][c] = r[srow + c * RPI];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (j + k < cnt) {
+                    const float bx = sp[k] * qp.x + sn[k] * qn.x, by = sp[k] * qp.y + sn[k] * qn.y;
+                    const float bz = sp[k] * qp.z + sn[k] * qn.z, bw = sp[k] * qp.w + sn[k] * qn.w;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        acc.a[c].x += fmaxf(xs[k][c] * t1.x + bx, 0.f);
+                        acc.a[c].y += fmaxf(xs[k][c] * t1.y + by, 0.f);
+                        acc.a[c].z += fmaxf(xs[k][c] * t1.z + bz, 0.f);
+                        acc.a[c].w += fmaxf(xs[k][c] * t1.w + bw, 0.f);
+                    }
+                }
             }
         }
 #pragma unroll
@@ -255,17 +267,27 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long
     for (int base = b; base < e; base += 64) {
         const int n = min(64, e - base);
         const int cols = (lane < n) ? colidx[base + lane] : 0;
-        for (int j = 0; j < n; ++j) {
-            const unsigned long long *w = mask + (size_t)__builtin_amdgcn_readlane(cols, j) * S + srow;
-            unsigned nib[NC];
+        // four neighbours per step keeps 4 * NC independent loads in flight
+        for (int j = 0; j < n; j += 4) {
+            unsigned nib[4][NC];
 #pragma unroll
-            for (int c = 0; c < NC; ++c) nib[c] = (unsigned)(w[c * RPI] >> shift);
+            for (int k = 0; k < 4; ++k) {
+                const int jj = min(j + k, n - 1);   // past the end: re-read the last word, masked below
+                const unsigned long long *w = mask + (size_t)__builtin_amdgcn_readlane(cols, jj) * S + srow;
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                cnt[c].x += (int)(nib[c] & 1u);
-                cnt[c].y += (int)((nib[c] >> 1) & 1u);
-                cnt[c].z += (int)((nib[c] >> 2) & 1u);
-                cnt[c].w += (int)((nib[c] >> 3) & 1u);
+                for (int c = 0; c < NC; ++c) nib[k][c] = (unsigned)(w[c * RPI] >> shift);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const unsigned live = (j + k < n) ? 0xFu : 0u;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const unsigned b4 = nib[k][c] & live;
+                    cnt[c].x += (int)(b4 & 1u);
+                    cnt[c].y += (int)((b4 >> 1) & 1u);
+                    cnt[c].z += (int)((b4 >> 2) & 1u);
+                    cnt[c].w += (int)((b4 >> 3) & 1u);
+                }
             }
         }
     }
