@@ -435,8 +435,9 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     if (rc != S2V_OK) return rc;
     rc = check_ws(ws);
     if (rc != S2V_OK) return rc;
-    if (T < 1 || S < 1 || (!mu_out && !mu_saved)) return S2V_ERR_INVALID_ARG;
+    if (T < 1 || S < 1) return S2V_ERR_INVALID_ARG;
     const int32_t N = g->n_nodes, G = g->n_graphs, p = params->p;
+    if (N > 0 && !mu_out && !mu_saved) return S2V_ERR_INVALID_ARG;
     if (N > 0 && !x) return S2V_ERR_INVALID_ARG;
     if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
     const Prepared *pr = find_prepared(ctx, g, ws);

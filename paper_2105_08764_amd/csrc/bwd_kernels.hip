@@ -149,34 +149,44 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
     const long per = (n_vrows + gridDim.x - 1) / gridDim.x;
     const long r_begin = (long)blockIdx.x * per, r_end = min(n_vrows, r_begin + per);
     float4 ax = make_float4(0.f, 0.f, 0.f, 0.f), ap = ax, an = ax;
-    // all lanes of a wave run the same number of iterations (the shuffles below need that)
-    for (long rbase = r_begin; rbase < r_end; rbase += SLOTS) {
-        const long r = rbase + slot;
-        const bool valid = r < r_end;
-        unsigned long long word = 0ull;
-        if (valid) {
-            const int v = (int)(r / S), s = (int)(r - (long)v * S);
-            const float4 mu = ld4(muT + (size_t)r * P + 4 * c4);
-            float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * c4);
-            if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * c4));
-            d.x = mu.x > 0.f ? d.x : 0.f;
-            d.y = mu.y > 0.f ? d.y : 0.f;
-            d.z = mu.z > 0.f ? d.z : 0.f;
-            d.w = mu.w > 0.f ? d.w : 0.f;
-            const unsigned nib = (mu.x > 0.f ? 1u : 0u) | (mu.y > 0.f ? 2u : 0u) | (mu.z > 0.f ? 4u : 0u) |
-                                 (mu.w > 0.f ? 8u : 0u);
-            word = (unsigned long long)nib << (4 * c4);
-            const float xs = x[(size_t)s * N + v], sp = s_pos[v], sn = s_neg[v];
-            ax.x += xs * d.x; ax.y += xs * d.y; ax.z += xs * d.z; ax.w += xs * d.w;
-            ap.x += sp * d.x; ap.y += sp * d.y; ap.z += sp * d.z; ap.w += sp * d.w;
-            an.x += sn * d.x; an.y += sn * d.y; an.z += sn * d.z; an.w += sn * d.w;
-        }
-        if (mask) {
-            // OR the nibbles of the LPR lanes that share a row
+    // All lanes of a wave run the same number of iterations (the shuffles below need that); four
+    // rows per thread and step keep four independent loads in flight.
+    constexpr int U = 4;
+    for (long rbase = r_begin; rbase < r_end; rbase += U * SLOTS) {
+        float4 mu[U];
 #pragma unroll
-            for (int m = 1; m < LPR; m <<= 1) word |= __shfl_xor(word, m);
-            if (valid && c4 == 0) mask[r] = word;
+        for (int k = 0; k < U; ++k) {
+            const long r = rbase + k * SLOTS + slot;
+            mu[k] = r < r_end ? ld4(muT + (size_t)r * P + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const long r = rbase + k * SLOTS + slot;
+            const bool valid = r < r_end;
+            unsigned long long word = 0ull;
+            if (valid) {
+                const int v = (int)(r / S), s = (int)(r - (long)v * S);
+                float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * c4);
+                if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * c4));
+                d.x = mu[k].x > 0.f ? d.x : 0.f;
+                d.y = mu[k].y > 0.f ? d.y : 0.f;
+                d.z = mu[k].z > 0.f ? d.z : 0.f;
+                d.w = mu[k].w > 0.f ? d.w : 0.f;
+                const unsigned nib = (mu[k].x > 0.f ? 1u : 0u) | (mu[k].y > 0.f ? 2u : 0u) |
+                                     (mu[k].z > 0.f ? 4u : 0u) | (mu[k].w > 0.f ? 8u : 0u);
+                word = (unsigned long long)nib << (4 * c4);
+                const float xs = x[(size_t)s * N + v], sp = s_pos[v], sn = s_neg[v];
+                ax.x += xs * d.x; ax.y += xs * d.y; ax.z += xs * d.z; ax.w += xs * d.w;
+                ap.x += sp * d.x; ap.y += sp * d.y; ap.z += sp * d.z; ap.w += sp * d.w;
+                an.x += sn * d.x; an.y += sn * d.y; an.z += sn * d.z; an.w += sn * d.w;
+            }
+            if (mask) {
+                // OR the nibbles of the LPR lanes that share a row
+#pragma unroll
+                for (int m = 1; m < LPR; m <<= 1) word |= __shfl_xor(word, m);
+                if (valid && c4 == 0) mask[r] = word;
+            }
         }
     }
     st4(&red[0][slot][4 * c4], ax);

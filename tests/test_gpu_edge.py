@@ -1,0 +1,158 @@
+"""GPU edge cases of the C interface: error codes (nothing is enqueued on an error), empty
+inputs, run-to-run determinism.  Every kernel launched here exits normally."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _status(exc):
+    return exc.value.status
+
+
+def test_error_codes():
+    import torch
+
+    import paper_2105_08764_amd as s2v
+
+    g = si.erdos_renyi_gnp(200, 0.05, 1)
+    dev = gu.Device(g, 32, 3, k_max=4)
+    ctx, graph, ws = dev.ctx, dev.graph, dev.ws
+    prm = dev.params(si.thetas(32, 1))
+    x = torch.zeros((1, g.n), device="cuda")
+    mu = torch.zeros((g.n, 1, 32), device="cuda")
+    gsum = torch.zeros((1, 1, 32), device="cuda")
+    q = torch.zeros((1, g.n), device="cuda")
+    idx = torch.zeros((1, 4), dtype=torch.int32, device="cuda")
+    val = torch.zeros((1, 4), device="cuda")
+    cnt = torch.zeros((1,), dtype=torch.int32, device="cuda")
+
+    # unsupported embedding size
+    bad = s2v.Params(48, {k: torch.zeros(1, device="cuda") for k in s2v.THETA_NAMES})
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_embed_fwd(graph, bad, x, 3, 1, mu, None, gsum, ws)
+    assert _status(e) == s2v.S2V_ERR_UNSUPPORTED
+    # T < 1, S < 1
+    for T, S in ((0, 1), (3, 0)):
+        with pytest.raises(s2v.S2VError) as e:
+            ctx.s2v_embed_fwd(graph, prm, x, T, S, mu, None, gsum, ws)
+        assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    # no output buffer at all
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_embed_fwd(graph, prm, x, 3, 1, None, None, gsum, ws)
+    assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    # workspace too small
+    small = ws[: 4096]
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_embed_fwd(graph, prm, x, 3, 1, mu, None, gsum, small)
+    assert _status(e) in (s2v.S2V_ERR_WORKSPACE_TOO_SMALL, s2v.S2V_ERR_NOT_PREPARED)
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_graph_prepare(graph, small[:256])
+    assert _status(e) == s2v.S2V_ERR_WORKSPACE_TOO_SMALL
+    # a workspace that was never prepared
+    other = torch.empty(dev.ws_bytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_embed_fwd(graph, prm, x, 3, 1, mu, None, gsum, other)
+    assert _status(e) == s2v.S2V_ERR_NOT_PREPARED
+    # misaligned workspace
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_embed_fwd(graph, prm, x, 3, 1, mu, None, gsum, ws[8:])
+    assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    # selection: k < 1; batch with k > 1
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_select_topk(graph, q[0], x[0], None, 0, idx, val, cnt, ws)
+    assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    gb = si.block_diagonal([si.edgeless(5), si.edgeless(7)])
+    devb = gu.Device(gb, 32, 1, k_max=4)
+    with pytest.raises(s2v.S2VError) as e:
+        devb.ctx.s2v_select_topk(devb.graph, torch.zeros(12, device="cuda"), torch.zeros(12, device="cuda"), None, 2,
+                                 torch.zeros((2, 2), dtype=torch.int32, device="cuda"),
+                                 torch.zeros((2, 2), device="cuda"), torch.zeros(2, dtype=torch.int32, device="cuda"),
+                                 devb.ws)
+    assert _status(e) == s2v.S2V_ERR_UNSUPPORTED
+    # gradient struct with another p
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_sgd_step(prm, s2v.Params.from_numpy(si.thetas(64, 1)), 0.1)
+    assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    # bad graph offsets are caught by prepare (first offset must be 0, last must be N)
+    off = torch.tensor([0, 3, 11], dtype=torch.int32, device="cuda")
+    gbad = s2v.Graph(devb.graph.rowptr, devb.graph.colidx, None, off)
+    with pytest.raises(s2v.S2VError) as e:
+        devb.ctx.s2v_graph_prepare(gbad, devb.ws)
+    assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    # after all those refusals the context still works
+    ctx.s2v_embed_fwd(graph, prm, x, 3, 1, mu, None, gsum, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(mu).all()
+
+
+def test_empty_graph():
+    import torch
+
+    g = si.edgeless(0)
+    dev = gu.Device(g, 32, 3, k_max=3)
+    out = dev.forward(si.thetas(32, 1), np.zeros((1, 0), np.float32))
+    assert out["mu"].shape == (0, 1, 32) and (out["gsum"] == 0).all()
+    for k in (1, 3):
+        idx, val, cnt = dev.select(np.zeros(0, np.float32), np.zeros(0, np.float32), None, k)
+        assert cnt[0] == 0 and (idx == -1).all() and np.isneginf(val).all()
+
+
+def test_single_node_and_single_round(oracle_mod):
+    g = si.edgeless(1)
+    theta = si.thetas(64, 2)
+    for T in (1, 2):
+        dev = gu.Device(g, 64, T)
+        out = dev.forward(theta, np.ones((1, 1), np.float32))
+        mu, gsum, q = gu.oracle_forward(oracle_mod, g, theta, np.ones(1), T)
+        assert gu.rel_err(out["mu"][:, 0, :], mu) <= 1e-5 and gu.rel_err(out["q"][0], q) <= 1e-5
+
+
+def test_results_are_deterministic():
+    # fixed reduction trees and no float atomics: two runs give the same bits
+    w = si.config(3, 0.02)
+    g = w.graph
+    S = 16
+    x = si.node_flags(g.n, 0.05, 3, n_states=S)
+    action, target = si.training_batch(x, 4)
+    outs = []
+    for _ in range(2):
+        dev = gu.Device(g, w.p, w.T, S=S, k_max=50, training=True)
+        loss, qp, grads = dev.train_iter(dev.params(w.theta), x, action, target)
+        dev1 = gu.Device(g, w.p, w.T, k_max=50)
+        f = dev1.forward(w.theta, w.x)
+        sel = dev1.select(f["q"][0], w.x[0], None, 50)
+        outs.append((loss, qp, grads, f, sel))
+    a, b = outs
+    assert a[0] == b[0] and np.array_equal(a[1], b[1])
+    for k in si.THETA_NAMES:
+        assert np.array_equal(a[2][k], b[2][k]), k
+    assert np.array_equal(a[3]["mu"], b[3]["mu"]) and np.array_equal(a[3]["q"], b[3]["q"])
+    assert all(np.array_equal(u, v) for u, v in zip(a[4], b[4]))
+
+
+def test_hub_rows_of_every_kind(oracle_mod):
+    # a star of 3000 leaves plus a clique: rows of 3000 and of 299 entries cross the 256-entry hub
+    # threshold in row mode (S = 3) and in node mode (S = 16), forward and backward
+    star = si.star_graph(3000)
+    clique = si.complete_graph(300)
+    g = si.block_diagonal([star, clique])
+    g.w = si.symmetric_edge_weights(g, 3, 0.5, 1.5)
+    for S, p in ((3, 64), (16, 32)):
+        theta = si.thetas(p, 5, 0.01)
+        x = si.node_flags(g.n, 0.3, 7, n_states=S)
+        action, target = si.training_batch(x, 8)
+        action[0] = 0                      # the hub itself is an action node
+        action[1] = g.graph_off[1] + 5     # and a clique node
+        x[0, 0] = 0
+        dev = gu.Device(g, p, 3, S=S, training=True)
+        loss, qp, grads = dev.train_iter(dev.params(theta), x, action, target)
+        oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, g.graph_off, theta, x, 3, action, target)
+        assert gu.rel_err(qp, oqp) <= 1e-4 and abs(loss - oloss) <= 1e-4 * abs(oloss)
+        for name in si.THETA_NAMES:
+            assert gu.rel_err(grads[name], ograds[name], whole=True) <= 1e-4, (S, name)
