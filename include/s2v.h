@@ -101,11 +101,14 @@ int32_t s2v_destroy(s2v_ctx *ctx);
 int32_t s2v_last_hip_error(const s2v_ctx *ctx);
 
 /*
- * Bytes of workspace that every call below needs for this graph shape (only n_nodes,
- * nnz and n_graphs of `g` are read) with embedding size p, T rounds, S states and at
- * most k_max selected nodes per call.  `training` non-zero includes the scratch of
- * s2v_embed_bwd (two [N][S][p] buffers and the partial-gradient tables); leave it zero
- * for inference.  `out` is a host pointer.
+ * Bytes of workspace that every call below needs for this graph with embedding size p, T
+ * rounds, S states and at most k_max selected nodes per call.  `training` non-zero includes
+ * the scratch of s2v_embed_bwd (up to two [N][S][p] buffers, the relu-mask words and the
+ * partial-gradient tables); leave it zero for inference.  `out` is a host pointer.
+ * If ctx and g->rowptr are non-NULL the row lengths are read back from the device (the call
+ * waits for the stream) and the buffers for long rows are sized exactly; with ctx == NULL or
+ * rowptr == NULL only n_nodes, nnz and n_graphs are used and a safe upper bound is returned
+ * (larger by up to nnz * S * p / 16 bytes).
  */
 int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t T, int32_t S,
                             int32_t k_max, int32_t training, size_t *out);
@@ -143,6 +146,7 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
  * selection, not here):
  *   Q_v = theta5[0:p] . relu(theta6 g_b) + theta5[p:2p] . relu(theta7 mu_v),  b = graph of v.
  *   mu [N][S][p], gsum [S][G][p] (from s2v_embed_fwd), q [S][N] (output).
+ * Errors: INVALID_ARG, UNSUPPORTED, NOT_PREPARED, WORKSPACE_TOO_SMALL, HIP.
  */
 int32_t s2v_q_score(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *mu,
                     const float *gsum, int32_t S, float *q, void *ws, size_t ws_bytes);

@@ -39,13 +39,34 @@ struct HeadLayout {
     int max_chunks, max_hubs, max_segs;
 };
 
-// Upper bounds from the shape alone: a hub has more than kHubDegree entries, and a hub of d
-// entries has ceil(d / kHubDegree) <= d / kHubDegree + 1 segments.
-HeadLayout head_layout(int64_t N, int64_t G, int64_t nnz) {
+// Bounds on hub rows and segments from the shape alone: a hub has more than kHubDegree entries,
+// and a hub of d entries has ceil(d / kHubSegment) <= d / kHubSegment + 1 segments.
+void hub_bounds(int64_t nnz, int *hubs, int *segs) {
+    *hubs = (int)(nnz / (kHubDegree + 1));
+    *segs = (int)(nnz / kHubSegment) + *hubs;
+}
+
+// Exact counts from the row pointers (host copy).
+void hub_counts(const std::vector<int32_t> &rp, int *hubs, int *segs) {
+    int h = 0, sg = 0;
+    for (size_t v = 0; v + 1 < rp.size(); ++v) {
+        const int d = rp[v + 1] - rp[v];
+        if (d > kHubDegree) {
+            ++h;
+            sg += (d + kHubSegment - 1) / kHubSegment;
+        }
+    }
+    *hubs = h;
+    *segs = sg;
+}
+
+// The head holds room for `hubs` hub rows and `segs` segments: the exact counts once the graph is
+// prepared, an upper bound when only its shape is known.
+HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     HeadLayout h;
     h.max_chunks = (int)((N + kChunkNodes - 1) / kChunkNodes + G);
-    h.max_hubs = (int)(nnz / (kHubDegree + 1));
-    h.max_segs = (int)(nnz / kHubDegree) + h.max_hubs;
+    h.max_hubs = hubs;
+    h.max_segs = segs;
     Carver c(0);
     h.s_pos = c.take(sizeof(float) * N);
     h.s_neg = c.take(sizeof(float) * N);
@@ -332,11 +353,20 @@ int32_t s2v_last_hip_error(const s2v_ctx *ctx) { return ctx ? ctx->last_hip : 0;
 
 int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t T, int32_t S, int32_t k_max,
                             int32_t training, size_t *out) {
-    (void)ctx;
     if (!g || !out || g->n_nodes < 0 || g->n_graphs < 1 || T < 1 || S < 1 || k_max < 0) return S2V_ERR_INVALID_ARG;
     if (!p_supported(p)) return S2V_ERR_UNSUPPORTED;
     if ((int64_t)g->n_nodes * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
-    const HeadLayout h = head_layout(g->n_nodes, g->n_graphs, g->nnz);
+    int hubs = 0, segs = 0;
+    if (ctx && g->rowptr && g->n_nodes > 0) {
+        // exact hub counts from the graph itself (reads rowptr back: waits for the stream)
+        std::vector<int32_t> rp((size_t)g->n_nodes + 1);
+        S2V_TRY(hipMemcpyAsync(rp.data(), g->rowptr, sizeof(int32_t) * rp.size(), hipMemcpyDeviceToHost, ctx->stream));
+        S2V_TRY(hipStreamSynchronize(ctx->stream));
+        hub_counts(rp, &hubs, &segs);
+    } else {
+        hub_bounds(g->nnz, &hubs, &segs);
+    }
+    const HeadLayout h = head_layout(g->n_nodes, g->n_graphs, hubs, segs);
     size_t need = fwd_layout(h, g->n_nodes, p, S, true).end;
     const size_t q_end = q_layout(h, S, g->n_graphs).end;
     const size_t s_end = sel_layout(h, g->n_nodes, k_max > 0 ? k_max : 1).end;
@@ -357,7 +387,16 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     rc = check_ws(ws);
     if (rc != S2V_OK) return rc;
     const int32_t N = g->n_nodes, G = g->n_graphs;
-    const HeadLayout h = head_layout(N, G, g->nnz);
+    // hub rows and their segments, from a host copy of rowptr
+    std::vector<int32_t> rp((size_t)N + 1);
+    S2V_TRY(hipMemcpyAsync(rp.data(), g->rowptr, sizeof(int32_t) * ((size_t)N + 1), hipMemcpyDeviceToHost, ctx->stream));
+    S2V_TRY(hipStreamSynchronize(ctx->stream));
+    if (rp[0] != 0 || (int64_t)rp[N] != g->nnz) return S2V_ERR_INVALID_ARG;
+    for (int32_t v = 0; v < N; ++v)
+        if (rp[v + 1] < rp[v]) return S2V_ERR_INVALID_ARG;
+    int n_hubs = 0, n_segs = 0;
+    hub_counts(rp, &n_hubs, &n_segs);
+    const HeadLayout h = head_layout(N, G, n_hubs, n_segs);
     if (ws_bytes < h.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
 
     // graph offsets to the host: the chunk table is built here, once per graph
@@ -390,26 +429,19 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_graph), cg.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
     }
     S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.graph_chunk_off), gco.data(), sizeof(int32_t) * (G + 1), hipMemcpyHostToDevice, ctx->stream));
-    // hub rows and their segments, from a host copy of rowptr
-    std::vector<int32_t> rp((size_t)N + 1);
-    S2V_TRY(hipMemcpyAsync(rp.data(), g->rowptr, sizeof(int32_t) * ((size_t)N + 1), hipMemcpyDeviceToHost, ctx->stream));
-    S2V_TRY(hipStreamSynchronize(ctx->stream));
-    if (rp[0] != 0 || (int64_t)rp[N] != g->nnz) return S2V_ERR_INVALID_ARG;
     std::vector<int32_t> hub_rows, hub_seg_off, seg_begin, seg_end;
     for (int32_t v = 0; v < N; ++v) {
-        if (rp[v + 1] < rp[v]) return S2V_ERR_INVALID_ARG;
         if (rp[v + 1] - rp[v] > kHubDegree) {
             hub_rows.push_back(v);
             hub_seg_off.push_back((int32_t)seg_begin.size());
-            for (int32_t b = rp[v]; b < rp[v + 1]; b += kHubDegree) {
+            for (int32_t b = rp[v]; b < rp[v + 1]; b += kHubSegment) {
                 seg_begin.push_back(b);
-                seg_end.push_back(b + kHubDegree < rp[v + 1] ? b + kHubDegree : rp[v + 1]);
+                seg_end.push_back(b + kHubSegment < rp[v + 1] ? b + kHubSegment : rp[v + 1]);
             }
         }
     }
     hub_seg_off.push_back((int32_t)seg_begin.size());
-    const int n_hubs = (int)hub_rows.size(), n_segs = (int)seg_begin.size();
-    if (n_hubs > h.max_hubs || n_segs > h.max_segs) return S2V_ERR_INVALID_ARG;
+    if ((int)hub_rows.size() != n_hubs || (int)seg_begin.size() != n_segs) return S2V_ERR_INVALID_ARG;
     if (n_hubs > 0) {
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.hub_rows), hub_rows.data(), sizeof(int32_t) * n_hubs, hipMemcpyHostToDevice, ctx->stream));
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.hub_seg_off), hub_seg_off.data(), sizeof(int32_t) * (n_hubs + 1), hipMemcpyHostToDevice, ctx->stream));
@@ -442,7 +474,7 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
-    const HeadLayout h = head_layout(N, G, g->nnz);
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
     const bool need_tmp = !mu_saved && T >= 3;  // round 2 reads no embedding from memory
     const FwdLayout f = fwd_layout(h, N, p, S, need_tmp);
     if (ws_bytes < f.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
@@ -502,7 +534,9 @@ int32_t s2v_q_score(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, 
     const int32_t N = g->n_nodes, G = g->n_graphs, p = params->p;
     if (N > 0 && (!mu || !q)) return S2V_ERR_INVALID_ARG;
     if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
-    const HeadLayout h = head_layout(N, G, g->nnz);
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
     const QLayout ql = q_layout(h, S, G);
     if (ws_bytes < ql.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = ctx->stream;
@@ -525,7 +559,7 @@ int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const 
     if (G > 1 && k > 1) return S2V_ERR_UNSUPPORTED;
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
-    const HeadLayout h = head_layout(N, G, g->nnz);
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
     const SelLayout sl = sel_layout(h, N, k);
     if (ws_bytes < sl.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
     SelectScratch sc;
@@ -568,7 +602,7 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     if ((int64_t)N * S >= ((int64_t)1 << 31)) return S2V_ERR_UNSUPPORTED;
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
-    const HeadLayout h = head_layout(N, G, g->nnz);
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
     const BwdLayout bl = bwd_layout(h, N, p, T, S);
     if (ws_bytes < bl.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
 

@@ -21,10 +21,11 @@ constexpr int kSortTile = 1024;
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
-// Rows with more stored entries than this are "hubs": their neighbour sums are formed ahead of
-// the round kernel by many waves, each summing one segment of at most kHubDegree entries, so
+// Rows with more stored entries than kHubDegree are "hubs": their neighbour sums are formed ahead
+// of the round kernel by many waves, each summing one segment of at most kHubSegment entries, so
 // that no single wave ever walks a long row.
 constexpr int kHubDegree = 256;
+constexpr int kHubSegment = 64;
 
 struct HubTable {              // device pointers into the prepared head of the workspace
     int n_hubs, n_segs;
