@@ -556,11 +556,35 @@ __global__ __launch_bounds__(kThreads) void k_qnode(int n_vrows, int N, int S, i
         bfrag[cb] = load_b_frag_rows<P>(theta7, cb, lane);
         t5[cb] = theta5[P + 16 * cb + jl];
     }
+    // The wave's 16 x P tile is 16 contiguous rows: fetch it with fully coalesced float4 loads (one
+    // tile ahead of the arithmetic) and turn it into matrix-core fragments through LDS.
+    __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * Ge::STRIDE];
+    float *tile = lds[wave];
+    constexpr int MV = (kTileRows * Ge::LPR) / 64;
     const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    float4 nxt[MV];
+    auto fetch = [&](int t) {
+        const int r0 = t * kWgRows + wave * kTileRows;
+#pragma unroll
+        for (int c = 0; c < MV; ++c) {
+            const int f = c * 64 + lane, row = f / Ge::LPR, col4 = f % Ge::LPR;
+            nxt[c] = (t < n_tiles && r0 + row < n_vrows) ? ld4(mu + (size_t)(r0 + row) * P + 4 * col4)
+                                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    fetch(blockIdx.x);
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const int r0 = t * kWgRows + wave * kTileRows;
+#pragma unroll
+        for (int c = 0; c < MV; ++c) {
+            const int f = c * 64 + lane;
+            st4(tile + (f / Ge::LPR) * Ge::STRIDE + 4 * (f % Ge::LPR), nxt[c]);
+        }
+        fetch(t + gridDim.x);
+        __builtin_amdgcn_wave_barrier();
+        const Frag<P> afrag = load_a_frag_lds<P>(tile, lane);
+        __builtin_amdgcn_wave_barrier();
         if (r0 >= n_vrows) continue;
-        const Frag<P> afrag = load_a_frag_global<P>(mu, r0, n_vrows, lane);
         float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int cb = 0; cb < Ge::CB; ++cb) {
