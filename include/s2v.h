@@ -73,6 +73,9 @@ typedef struct {
     const float *w;           /* device [nnz] edge weights W(v,u) of Eq. 1, or NULL = all 1.0 */
     int32_t n_graphs;         /* G >= 1 */
     const int32_t *graph_off; /* device [G+1] ascending node offsets (0 .. N), or NULL when G == 1 */
+    const int32_t *row_end;   /* device [N]: one past the last LIVE entry of each row, rowptr[v] <= row_end[v]
+                                 <= rowptr[v+1], or NULL = every stored entry is live.  Used by the inference
+                                 loop, whose rows shrink as nodes join the solution (s2v_residual_update). */
 } s2v_graph;
 
 /* The seven parameter tensors (device pointers), also used for their gradients. */
@@ -185,6 +188,44 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
 /* Plain gradient descent on all seven tensors: theta <- theta - lr * grad (Sec. 4.5.2 repeats
  * forward, backward and this update several times on one minibatch). */
 int32_t s2v_sgd_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, float lr);
+
+/*
+ * State update of the inference loop, Alg. 3 lines 8-10, for a graph whose arrays the caller
+ * owns as a MUTABLE copy (colidx, w and row_end are written through the const pointers of `g`;
+ * g->row_end must be non-NULL, initially a copy of rowptr[1..N]):
+ *   - the selected nodes sel_idx[G][k] (first sel_count[g] of each row; sel_idx may be NULL for
+ *     "nothing selected") join the partial solution: x[v] = 1;
+ *   - every edge with an endpoint in the solution (x != 0) is removed: rows shrink in place,
+ *     keeping the order of the surviving entries; rows of solution nodes become empty;
+ *   - s+ / s- in the workspace head are recomputed over the surviving entries, so the graph stays
+ *     prepared for s2v_embed_fwd;
+ *   - cand[v] = 1 for nodes outside the solution that still have an edge, else 0 (the set C);
+ *   - stats[g] = {number of candidates, number of live stored entries} of graph g (device [G][2]).
+ * The solution is a vertex cover of graph g exactly when stats[g][1] == 0.
+ * Errors: INVALID_ARG, NOT_PREPARED, WORKSPACE_TOO_SMALL, HIP.
+ */
+int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const int32_t *sel_idx,
+                            const int32_t *sel_count, int32_t k, uint8_t *cand, int32_t *stats, void *ws,
+                            size_t ws_bytes);
+
+/*
+ * The whole inference loop of Alg. 3 with the multiple-node selection of Sec. 4.5.1, for the
+ * minimum-vertex-cover setting of the paper: repeat { embed (Eq. 1), score (Eq. 2), take the d best
+ * candidates, update the state } until no edge is left or max_steps policy evaluations were made.
+ * d = 1 when adaptive == 0; otherwise the 8/4/2/1 rule of s2v_adaptive_d on |C| and N (one graph
+ * only; a batch with G > 1 always uses d = 1, each graph taking its own argmax per step).
+ *   g        mutable graph copy as for s2v_residual_update, prepared with `ws`
+ *   x        [N] in/out: the partial solution (0/1); on return a vertex cover unless max_steps hit
+ *   buffers  mu [N][p], gsum [G][p], q [N], cand [N] bytes, sel_idx [G][8], sel_val [G][8],
+ *            sel_count [G], stats [G][2]: device scratch owned by the caller
+ *   steps_out, picked_out, live_out: host pointers; policy evaluations made, nodes added, live
+ *            stored entries left (0 = complete cover)
+ * Reads two small counters back per step, so the call waits for the stream.
+ */
+int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, float *x, int32_t T,
+                          int32_t adaptive, int32_t max_steps, float *mu, float *gsum, float *q, uint8_t *cand,
+                          int32_t *sel_idx, float *sel_val, int32_t *sel_count, int32_t *stats,
+                          int32_t *steps_out, int64_t *picked_out, int64_t *live_out, void *ws, size_t ws_bytes);
 
 /*
  * Optional live timing of the gather kernels (for benchmarks; not part of the method).

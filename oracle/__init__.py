@@ -151,3 +151,58 @@ def sgd(theta: dict, grads: dict, lr: float) -> dict:
         lib.oracle_sgd(ctypes.c_int64(t.size), _ptr(t), _ptr(g), ctypes.c_double(lr))
         out[k] = t
     return out
+
+
+# ---- the inference loop of Alg. 3 with the multiple-node selection of Sec. 4.5.1 ---------------
+
+def residual_graph(rowptr, colidx, w, x):
+    """The adjacency structure after Alg. 3's update: every edge with an endpoint in the partial
+    solution (x != 0) removed.  Same node set; returns (rowptr, colidx, w) of the remaining edges."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    n = rowptr.shape[0] - 1
+    x = _f64(x).reshape(-1)
+    rows = np.repeat(np.arange(n), np.diff(rowptr))
+    keep = (x[rows] == 0) & (x[colidx] == 0)
+    counts = np.bincount(rows[keep], minlength=n)
+    rp = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(counts, out=rp[1:])
+    return rp.astype(np.int32), colidx[keep], (None if w is None else np.asarray(w)[keep])
+
+
+def adaptive_d(n_candidates: int, n_nodes: int) -> int:
+    """Sec. 4.5.1: 8 nodes per evaluation while |C| > N/2, 4 for (N/4, N/2], 2 for (N/8, N/4], else 1."""
+    if n_candidates > n_nodes / 2:
+        return 8
+    if n_candidates > n_nodes / 4:
+        return 4
+    if n_candidates > n_nodes / 8:
+        return 2
+    return 1
+
+
+def mvc_inference(rowptr, colidx, w, graph_off, theta: dict, x, T: int, adaptive: bool, max_steps: int):
+    """Alg. 3 for minimum vertex cover, one state: repeat {embed on the remaining graph, score,
+    add the d best candidates to the solution} until no edge remains.  Candidates are the nodes
+    outside the solution that still have an edge.  Returns (x, steps, trace) with trace a list of
+    (d, selected ids, candidates before the step, stored entries left before the step)."""
+    x = _f64(x).reshape(-1).copy()
+    n = x.shape[0]
+    go = None if graph_off is None else _i32(graph_off)
+    G = 1 if go is None else go.shape[0] - 1
+    trace = []
+    steps = 0
+    while steps < max_steps:
+        rp, ci, ww = residual_graph(rowptr, colidx, w, x)
+        live = int(ci.shape[0])
+        if live == 0:
+            break
+        cand = ((x == 0) & (np.diff(rp) > 0)).astype(np.uint8)
+        d = adaptive_d(int(cand.sum()), n) if (adaptive and G == 1) else 1
+        mu = embed(rp, ci, ww, theta, x, T)
+        _, q = q_scores(go, theta, mu)
+        idx, _, cnt = select(go, q, x, cand, d)
+        chosen = np.concatenate([idx[b, : cnt[b]] for b in range(G)])
+        trace.append((d, chosen.copy(), int(cand.sum()), live))
+        x[chosen] = 1.0
+        steps += 1
+    return x, steps, trace

@@ -27,7 +27,8 @@ THETA_NAMES = ("theta1", "theta2", "theta3", "theta4", "theta5", "theta6", "thet
 EXPORTS = (
     "s2v_status_str", "s2v_create", "s2v_destroy", "s2v_last_hip_error", "s2v_workspace_bytes",
     "s2v_graph_prepare", "s2v_embed_fwd", "s2v_q_score", "s2v_select_topk", "s2v_embed_bwd",
-    "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end",
+    "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end", "s2v_residual_update",
+    "s2v_mvc_inference",
 )
 
 
@@ -46,6 +47,7 @@ class CGraph(ctypes.Structure):
         ("w", ctypes.c_void_p),
         ("n_graphs", ctypes.c_int32),
         ("graph_off", ctypes.c_void_p),
+        ("row_end", ctypes.c_void_p),
     ]
 
 
@@ -109,17 +111,23 @@ def _want(t, dtype, what):
 class Graph:
     """Device-side CSR graph (or block-diagonal batch); keeps the tensors alive."""
 
-    def __init__(self, rowptr, colidx, w=None, graph_off=None):
+    def __init__(self, rowptr, colidx, w=None, graph_off=None, row_end=None):
+        _want(row_end, "int32", "row_end")
         _want(rowptr, "int32", "rowptr")
         _want(colidx, "int32", "colidx")
         _want(w, "float32", "w")
         _want(graph_off, "int32", "graph_off")
-        self.rowptr, self.colidx, self.w, self.graph_off = rowptr, colidx, w, graph_off
+        self.rowptr, self.colidx, self.w, self.graph_off, self.row_end = rowptr, colidx, w, graph_off, row_end
         self.n_nodes = int(rowptr.numel() - 1)
         self.nnz = int(colidx.numel())
         self.n_graphs = 1 if graph_off is None else int(graph_off.numel() - 1)
         self.c = CGraph(self.n_nodes, self.nnz, _dp(rowptr), _dp(colidx) if self.nnz else None, _dp(w),
-                        self.n_graphs, _dp(graph_off))
+                        self.n_graphs, _dp(graph_off), _dp(row_end))
+
+    def mutable_copy(self):
+        """A copy whose colidx / w / row_end the inference loop may edit in place."""
+        return Graph(self.rowptr, self.colidx.clone(), None if self.w is None else self.w.clone(), self.graph_off,
+                     self.rowptr[1:].clone())
 
 
 class Params:
@@ -218,6 +226,32 @@ class Context:
                                       ctypes.c_void_p(_dp(target)), ctypes.c_void_p(_dp(loss)),
                                       ctypes.c_void_p(_dp(q_pred)), ctypes.byref(grads.c), ctypes.c_void_p(_dp(ws)),
                                       ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_embed_bwd")
+
+    def s2v_residual_update(self, g: Graph, x, sel_idx, sel_count, k: int, cand, stats, ws) -> None:
+        _want(cand, "uint8", "cand")
+        _want(stats, "int32", "stats")
+        _check(self.lib.s2v_residual_update(self.handle, ctypes.byref(g.c), ctypes.c_void_p(_dp(x)),
+                                            ctypes.c_void_p(_dp(sel_idx)), ctypes.c_void_p(_dp(sel_count)),
+                                            ctypes.c_int32(k), ctypes.c_void_p(_dp(cand)), ctypes.c_void_p(_dp(stats)),
+                                            ctypes.c_void_p(_dp(ws)), ctypes.c_size_t(ws.numel() * ws.element_size())),
+               "s2v_residual_update")
+
+    def s2v_mvc_inference(self, g: Graph, params: Params, x, T: int, adaptive: bool, max_steps: int, mu, gsum, q, cand,
+                          sel_idx, sel_val, sel_count, stats, ws):
+        """Returns (policy evaluations, nodes added, live stored entries left)."""
+        steps = ctypes.c_int32(0)
+        picked = ctypes.c_int64(0)
+        live = ctypes.c_int64(0)
+        _check(self.lib.s2v_mvc_inference(self.handle, ctypes.byref(g.c), ctypes.byref(params.c),
+                                          ctypes.c_void_p(_dp(x)), ctypes.c_int32(T), ctypes.c_int32(int(adaptive)),
+                                          ctypes.c_int32(max_steps), ctypes.c_void_p(_dp(mu)),
+                                          ctypes.c_void_p(_dp(gsum)), ctypes.c_void_p(_dp(q)),
+                                          ctypes.c_void_p(_dp(cand)), ctypes.c_void_p(_dp(sel_idx)),
+                                          ctypes.c_void_p(_dp(sel_val)), ctypes.c_void_p(_dp(sel_count)),
+                                          ctypes.c_void_p(_dp(stats)), ctypes.byref(steps), ctypes.byref(picked),
+                                          ctypes.byref(live), ctypes.c_void_p(_dp(ws)),
+                                          ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_mvc_inference")
+        return int(steps.value), int(picked.value), int(live.value)
 
     def s2v_profile_begin(self, max_launches: int) -> None:
         _check(self.lib.s2v_profile_begin(self.handle, ctypes.c_int32(max_launches)), "s2v_profile_begin")

@@ -35,7 +35,7 @@ struct Carver {
 
 struct HeadLayout {
     size_t s_pos, s_neg, chunk_begin, chunk_end, chunk_graph, graph_chunk_off;
-    size_t hub_rows, hub_seg_off, seg_begin, seg_end, end;
+    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, end;
     int max_chunks, max_hubs, max_segs;
 };
 
@@ -76,6 +76,7 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     h.graph_chunk_off = c.take(sizeof(int32_t) * (G + 1));
     h.hub_rows = c.take(sizeof(int32_t) * h.max_hubs);
     h.hub_seg_off = c.take(sizeof(int32_t) * (h.max_hubs + 1));
+    h.seg_row = c.take(sizeof(int32_t) * h.max_segs);
     h.seg_begin = c.take(sizeof(int32_t) * h.max_segs);
     h.seg_end = c.take(sizeof(int32_t) * h.max_segs);
     h.end = c.off;
@@ -233,6 +234,9 @@ int32_t check_ws(const void *ws) {
     return S2V_OK;
 }
 
+// One past the last live entry of every row: the caller's row_end, or rowptr shifted by one.
+const int32_t *row_end_of(const s2v_graph *g) { return g->row_end ? g->row_end : g->rowptr + 1; }
+
 const Prepared *find_prepared(const s2v_ctx *ctx, const s2v_graph *g, const void *ws) {
     for (const Prepared &pr : ctx->prepared)
         if (pr.ws == ws && pr.rowptr == g->rowptr && pr.colidx == g->colidx && pr.N == g->n_nodes &&
@@ -247,6 +251,7 @@ HubTable hub_table(void *ws, const HeadLayout &h, const Prepared &pr) {
     ht.n_segs = pr.n_segs;
     ht.hub_rows = at<int32_t>(ws, h.hub_rows);
     ht.hub_seg_off = at<int32_t>(ws, h.hub_seg_off);
+    ht.seg_row = at<int32_t>(ws, h.seg_row);
     ht.seg_begin = at<int32_t>(ws, h.seg_begin);
     ht.seg_end = at<int32_t>(ws, h.seg_end);
     return ht;
@@ -394,6 +399,8 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     if (rp[0] != 0 || (int64_t)rp[N] != g->nnz) return S2V_ERR_INVALID_ARG;
     for (int32_t v = 0; v < N; ++v)
         if (rp[v + 1] < rp[v]) return S2V_ERR_INVALID_ARG;
+    // Hub rows are those that are long in STORAGE: rows only shrink afterwards, and the kernels test
+    // the live length, so a stored-long row that became short is simply handled as an ordinary row.
     int n_hubs = 0, n_segs = 0;
     hub_counts(rp, &n_hubs, &n_segs);
     const HeadLayout h = head_layout(N, G, n_hubs, n_segs);
@@ -429,12 +436,13 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_graph), cg.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
     }
     S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.graph_chunk_off), gco.data(), sizeof(int32_t) * (G + 1), hipMemcpyHostToDevice, ctx->stream));
-    std::vector<int32_t> hub_rows, hub_seg_off, seg_begin, seg_end;
+    std::vector<int32_t> hub_rows, hub_seg_off, seg_row, seg_begin, seg_end;
     for (int32_t v = 0; v < N; ++v) {
         if (rp[v + 1] - rp[v] > kHubDegree) {
             hub_rows.push_back(v);
             hub_seg_off.push_back((int32_t)seg_begin.size());
             for (int32_t b = rp[v]; b < rp[v + 1]; b += kHubSegment) {
+                seg_row.push_back(v);
                 seg_begin.push_back(b);
                 seg_end.push_back(b + kHubSegment < rp[v + 1] ? b + kHubSegment : rp[v + 1]);
             }
@@ -445,10 +453,11 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     if (n_hubs > 0) {
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.hub_rows), hub_rows.data(), sizeof(int32_t) * n_hubs, hipMemcpyHostToDevice, ctx->stream));
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.hub_seg_off), hub_seg_off.data(), sizeof(int32_t) * (n_hubs + 1), hipMemcpyHostToDevice, ctx->stream));
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_row), seg_row.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_begin), seg_begin.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_end), seg_end.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
     }
-    S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg)));
+    S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, row_end_of(g), g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg)));
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
 
     Prepared pr{ws, g->rowptr, g->colidx, N, g->nnz, G, n_chunks, n_hubs, n_segs};
@@ -502,9 +511,9 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     for (int t = 2; t <= T; ++t) {
         const float *src = t == 2 ? nullptr : dest(t - 1);
-        S2V_TRY(launch_hub_sums(st, p, S, ht, g->colidx, src, info, params->theta1, qvec, nullptr, hub_part, hub_sum));
+        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, src, info, params->theta1, qvec, nullptr, hub_part, hub_sum));
         SpanGuard span(ctx, t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND);
-        S2V_TRY(launch_round(st, p, N, S, g->rowptr, g->colidx, src, dest(t), info, params->theta1, params->theta2,
+        S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, src, dest(t), info, params->theta1, params->theta2,
                              qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum));
     }
     float *muT = dest(T);
@@ -640,23 +649,94 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         const bool first = t == T;
         const float *dz_in = first ? nullptr : sc.dz[cur];
         float *dz_out = t == 2 ? nullptr : sc.dz[cur ^ 1];  // dz^1 only feeds the sums
-        S2V_TRY(launch_hub_sums(st, p, S, ht, g->colidx, dz_in, nullptr, nullptr, nullptr, first ? sc.maskT : nullptr,
+        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, dz_in, nullptr, nullptr, nullptr, first ? sc.maskT : nullptr,
                                 hub_part, hub_sum));
         {
             SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
-            S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, g->colidx, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
+            S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
                                      dz_out, x, s_pos, s_neg, params->theta2, dc_part, d2_part, ht, hub_sum));
         }
         if (first) {
             float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;
             float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdGrid * p * p;
-            S2V_TRY(launch_bwd_action_fix(st, p, N, S, g->rowptr, g->colidx, action, sc.maskT, sc, params->theta2,
+            S2V_TRY(launch_bwd_action_fix(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, action, sc.maskT, sc, params->theta2,
                                           mu_prev, dz_out, x, s_pos, s_neg, dc_fix, d2_fix));
         }
         cur ^= 1;
     }
     S2V_TRY(launch_bwd_finish(st, p, bl.dc_rows, bl.d2_rows, sc, params->theta3, params->theta4, grads->theta1,
                               grads->theta2, grads->theta3, grads->theta4));
+    return S2V_OK;
+}
+
+int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const int32_t *sel_idx,
+                            const int32_t *sel_count, int32_t k, uint8_t *cand, int32_t *stats, void *ws,
+                            size_t ws_bytes) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    int32_t rc = check_graph(g);
+    if (rc != S2V_OK) return rc;
+    rc = check_ws(ws);
+    if (rc != S2V_OK) return rc;
+    const int32_t N = g->n_nodes, G = g->n_graphs;
+    if (!g->row_end || !cand || !stats || k < 0) return S2V_ERR_INVALID_ARG;
+    if (N > 0 && !x) return S2V_ERR_INVALID_ARG;
+    if (sel_idx && (!sel_count || k < 1)) return S2V_ERR_INVALID_ARG;
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
+    if (ws_bytes < h.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
+    S2V_TRY(launch_residual_update(ctx->stream, N, G, g->graph_off, g->rowptr, const_cast<int32_t *>(g->row_end),
+                                   const_cast<int32_t *>(g->colidx), const_cast<float *>(g->w), x, sel_idx, sel_count,
+                                   sel_idx ? k : 0, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg), cand, stats));
+    return S2V_OK;
+}
+
+int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, float *x, int32_t T,
+                          int32_t adaptive, int32_t max_steps, float *mu, float *gsum, float *q, uint8_t *cand,
+                          int32_t *sel_idx, float *sel_val, int32_t *sel_count, int32_t *stats,
+                          int32_t *steps_out, int64_t *picked_out, int64_t *live_out, void *ws, size_t ws_bytes) {
+    if (!ctx || !g || !steps_out || !picked_out || !live_out || max_steps < 0) return S2V_ERR_INVALID_ARG;
+    if (!mu || !gsum || !q || !cand || !sel_idx || !sel_val || !sel_count || !stats) return S2V_ERR_INVALID_ARG;
+    const int32_t N = g->n_nodes, G = g->n_graphs;
+    *steps_out = 0;
+    *picked_out = 0;
+    *live_out = 0;
+    // state from the incoming x: drops the edges already covered, fills cand and stats
+    int32_t rc = s2v_residual_update(ctx, g, x, nullptr, nullptr, 0, cand, stats, ws, ws_bytes);
+    if (rc != S2V_OK) return rc;
+    std::vector<int32_t> hstats(2 * (size_t)G), hcount(G);
+    auto read_stats = [&](int64_t *n_cand, int64_t *n_live) -> int32_t {
+        S2V_TRY(hipMemcpyAsync(hstats.data(), stats, sizeof(int32_t) * 2 * G, hipMemcpyDeviceToHost, ctx->stream));
+        S2V_TRY(hipStreamSynchronize(ctx->stream));
+        *n_cand = 0;
+        *n_live = 0;
+        for (int b = 0; b < G; ++b) { *n_cand += hstats[2 * b]; *n_live += hstats[2 * b + 1]; }
+        return S2V_OK;
+    };
+    int64_t n_cand = 0, n_live = 0;
+    rc = read_stats(&n_cand, &n_live);
+    if (rc != S2V_OK) return rc;
+    int32_t steps = 0;
+    int64_t picked = 0;
+    while (n_live > 0 && steps < max_steps) {
+        const int32_t d = (adaptive && G == 1) ? s2v_adaptive_d(n_cand, N) : 1;
+        rc = s2v_embed_fwd(ctx, g, params, x, T, 1, mu, nullptr, gsum, ws, ws_bytes);
+        if (rc != S2V_OK) return rc;
+        rc = s2v_q_score(ctx, g, params, mu, gsum, 1, q, ws, ws_bytes);
+        if (rc != S2V_OK) return rc;
+        rc = s2v_select_topk(ctx, g, q, x, cand, d, sel_idx, sel_val, sel_count, ws, ws_bytes);
+        if (rc != S2V_OK) return rc;
+        S2V_TRY(hipMemcpyAsync(hcount.data(), sel_count, sizeof(int32_t) * G, hipMemcpyDeviceToHost, ctx->stream));
+        rc = s2v_residual_update(ctx, g, x, sel_idx, sel_count, d, cand, stats, ws, ws_bytes);
+        if (rc != S2V_OK) return rc;
+        rc = read_stats(&n_cand, &n_live);   // also completes the copy of the counts
+        if (rc != S2V_OK) return rc;
+        for (int b = 0; b < G; ++b) picked += hcount[b];
+        ++steps;
+    }
+    *steps_out = steps;
+    *picked_out = picked;
+    *live_out = n_live;
     return S2V_OK;
 }
 

@@ -228,8 +228,8 @@ hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *mu
 // ------------------------------------------------------------------------------------------
 template <int P, bool NODE, bool MASK>
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
-    int n_vrows, int N, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
+    int n_vrows, int N, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
+    const int32_t *__restrict__ colidx, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
     const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
     float *__restrict__ dz_out, const float *__restrict__ x, const float *__restrict__ s_pos,
     const float *__restrict__ s_neg, const float *__restrict__ theta2, float *__restrict__ dc_part,
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
         const int v = valid ? r / S : 0;
         const int s = valid ? r - v * S : 0;
         const int rb = valid ? rowptr[v] : 0;
-        const int re = valid ? rowptr[v + 1] : 0;
+        const int re = valid ? rowend[v] : 0;
         const float xs = valid ? x[(size_t)s * N + v] : 0.f;
         const float sp = valid ? s_pos[v] : 0.f;
         const float sn = valid ? s_neg[v] : 0.f;
@@ -427,15 +427,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     }
 }
 
-hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
-                            const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
+hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                            const int32_t *colidx, const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
                             const float *s_neg, const float *theta2, float *dc_part, float *d2_part,
                             const HubTable &ht, const float *hub_sum) {
     const long n_vrows = (long)N * S;
     const bool node = (S % 16) == 0, mask = maskT != nullptr;
 #define S2V_LAUNCH_BWD(PP, NODE, MASK)                                                                              \
-    k_bwd_round<PP, NODE, MASK><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, colidx, dz_in, maskT, sc.dg, \
+    k_bwd_round<PP, NODE, MASK><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, rowend, colidx, dz_in, maskT, \
+                                                               sc.dg, \
                                                                sc.glo, sc.ghi, mu_prev, dz_out, x, s_pos, s_neg, theta2, \
                                                                dc_part, d2_part, ht, hub_sum)
 #define S2V_LAUNCH_BWD_P(PP)                                                                          \
@@ -459,6 +460,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 // ------------------------------------------------------------------------------------------
 template <int P>
 __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int32_t *__restrict__ rowptr,
+                                                        const int32_t *__restrict__ rowend,
                                                         const int32_t *__restrict__ colidx,
                                                         const int32_t *__restrict__ action,
                                                         const unsigned long long *__restrict__ maskT,
@@ -486,7 +488,7 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
     }
     __syncthreads();
     float cx = 0.f, cp = 0.f, cn = 0.f, msum = 0.f;
-    const int b = rowptr[a], e = rowptr[a + 1];
+    const int b = rowptr[a], e = rowend[a];
     for (int idx = b + split + slot * kFixSplit; idx < e; idx += SLOTS * kFixSplit) {
         const int u = colidx[idx];
         const size_t off = ((size_t)u * S + s) * P + j;
@@ -520,16 +522,19 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
     }
 }
 
-hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                                 const int32_t *colidx,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
                                  const float *theta2, const float *mu_prev, float *dz_out, const float *x,
                                  const float *s_pos, const float *s_neg, float *dc_part, float *d2_part) {
     const dim3 grid(kFixSplit, S);
     if (p == 32)
-        k_bwd_action_fix<32><<<grid, 256, 0, st>>>(N, S, rowptr, colidx, action, maskT, sc.da, theta2, mu_prev, dz_out, x,
+        k_bwd_action_fix<32><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, action, maskT, sc.da, theta2, mu_prev,
+                                                   dz_out, x,
                                                    s_pos, s_neg, dc_part, d2_part);
     else
-        k_bwd_action_fix<64><<<grid, 256, 0, st>>>(N, S, rowptr, colidx, action, maskT, sc.da, theta2, mu_prev, dz_out, x,
+        k_bwd_action_fix<64><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, action, maskT, sc.da, theta2, mu_prev,
+                                                   dz_out, x,
                                                    s_pos, s_neg, dc_part, d2_part);
     return hipGetLastError();
 }

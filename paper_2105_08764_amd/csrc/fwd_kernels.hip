@@ -11,10 +11,11 @@ namespace s2v {
 // the same for every round (Alg. 1 computes it before the layer loop).
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_prepare_s(int N, const int32_t *__restrict__ rowptr,
+                                                   const int32_t *__restrict__ rowend,
                                                    const float *__restrict__ w, float *__restrict__ s_pos,
                                                    float *__restrict__ s_neg) {
     for (int v = blockIdx.x * blockDim.x + threadIdx.x; v < N; v += gridDim.x * blockDim.x) {
-        const int b = rowptr[v], e = rowptr[v + 1];
+        const int b = rowptr[v], e = rowend[v];
         double sp = 0.0, sn = 0.0;
         if (w) {
             for (int j = b; j < e; ++j) {
@@ -30,10 +31,11 @@ __global__ __launch_bounds__(256) void k_prepare_s(int N, const int32_t *__restr
     }
 }
 
-hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const float *w, float *s_pos, float *s_neg) {
+hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const float *w,
+                            float *s_pos, float *s_neg) {
     if (N == 0) return hipSuccess;
     const int grid = min((N + 255) / 256, 65536);
-    k_prepare_s<<<grid, 256, 0, st>>>(N, rowptr, w, s_pos, s_neg);
+    k_prepare_s<<<grid, 256, 0, st>>>(N, rowptr, rowend, w, s_pos, s_neg);
     return hipGetLastError();
 }
 
@@ -135,6 +137,7 @@ hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const f
 // ------------------------------------------------------------------------------------------
 template <int P, bool NODE, bool MU1, bool GSUM>
 __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int ni, const int32_t *__restrict__ rowptr,
+                                                    const int32_t *__restrict__ rowend,
                                                     const int32_t *__restrict__ colidx,
                                                     const float *__restrict__ mu_in, float *__restrict__ mu_out,
                                                     const float *__restrict__ info,
@@ -180,7 +183,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
         const int v = valid ? r / S : 0;
         const int s = valid ? r - v * S : 0;
         const int rb = valid ? rowptr[v] : 0;
-        const int re = valid ? rowptr[v + 1] : 0;
+        const int re = valid ? rowend[v] : 0;
         const float *myinfo = info + (size_t)v * ni;
         const float sp = valid ? myinfo[0] : 0.f;
         const float sn = valid ? myinfo[1] : 0.f;
@@ -275,7 +278,8 @@ int round_grid(long n_vrows) {
 }
 
 template <int P>
-static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                                 const int32_t *colidx,
                                  const float *mu_in, float *mu_out, const float *info, const float *theta1,
                                  const float *theta2, const float *qvec, bool from_scalars, float *gpart,
                                  const HubTable &ht, const float *hub_sum) {
@@ -284,7 +288,8 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
     const int ni = nodeinfo_stride(S);
     const bool node = (S % 16) == 0;
 #define S2V_LAUNCH_ROUND(NODE, MU1, GSUM)                                                                         \
-    k_round<P, NODE, MU1, GSUM><<<grid, kThreads, 0, st>>>((int)n_vrows, S, ni, rowptr, colidx, mu_in, mu_out, info, \
+    k_round<P, NODE, MU1, GSUM><<<grid, kThreads, 0, st>>>((int)n_vrows, S, ni, rowptr, rowend, colidx, mu_in, mu_out, \
+                                                           info, \
                                                            theta1, theta2, qvec, gpart, ht, hub_sum)
     if (node) {
         if (from_scalars) S2V_LAUNCH_ROUND(true, true, false);
@@ -301,15 +306,15 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
 }
 
 // gpart != NULL asks for the fused column sums (only legal for S == 1 and a single graph).
-hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
-                        const float *mu_in, float *mu_out, const float *info, const float *theta1,
+hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                        const int32_t *colidx, const float *mu_in, float *mu_out, const float *info, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
                         const float *hub_sum) {
     if ((long)N * S == 0) return hipSuccess;
     if (p == 32)
-        return launch_round_p<32>(st, N, S, rowptr, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
+        return launch_round_p<32>(st, N, S, rowptr, rowend, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
                                   gpart, ht, hub_sum);
-    return launch_round_p<64>(st, N, S, rowptr, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
+    return launch_round_p<64>(st, N, S, rowptr, rowend, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
                               ht, hub_sum);
 }
 
@@ -320,6 +325,7 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
 // ------------------------------------------------------------------------------------------
 template <int P, bool NODE, int SRC>   // SRC: 0 rows in memory, 1 round-1 rows from scalars, 2 relu-mask bits
 __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTable ht,
+                                                          const int32_t *__restrict__ rowend,
                                                           const int32_t *__restrict__ colidx,
                                                           const float *__restrict__ src,
                                                           const float *__restrict__ info,
@@ -334,7 +340,8 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTabl
     const long items = (long)ht.n_segs * bpn;
     for (long item = (long)blockIdx.x * kWaves + wave; item < items; item += (long)gridDim.x * kWaves) {
         const int seg = (int)(item / bpn), blk = (int)(item - (long)seg * bpn);
-        const int b = ht.seg_begin[seg], e = ht.seg_end[seg];
+        // a segment covers stored entries of one row; entries past the row's live end do not count
+        const int b = ht.seg_begin[seg], e = min(ht.seg_end[seg], rowend[ht.seg_row[seg]]);
         if (NODE) {
             const int s0 = blk * 16;
             NodeAcc<P> acc;
@@ -374,7 +381,8 @@ __global__ __launch_bounds__(256) void k_hub_combine(int L, HubTable ht, const f
     }
 }
 
-hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *colidx, const float *src,
+hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
+                           const int32_t *colidx, const float *src,
                            const float *info, const float *theta1, const float *qvec,
                            const unsigned long long *mask, float *partial, float *hub_sum) {
     if (ht.n_hubs == 0) return hipSuccess;
@@ -384,7 +392,8 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
     const long items = (long)ht.n_segs * (node ? S / 16 : S);
     const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
 #define S2V_LAUNCH_HUB(PP, NODE, SRC) \
-    k_hub_partial<PP, NODE, SRC><<<grid, kThreads, 0, st>>>(S, ni, ht, colidx, src, info, theta1, qvec, mask, partial)
+    k_hub_partial<PP, NODE, SRC><<<grid, kThreads, 0, st>>>(S, ni, ht, rowend, colidx, src, info, theta1, qvec, mask, \
+                                                            partial)
 #define S2V_LAUNCH_HUB_P(PP)                                                                           \
     do {                                                                                               \
         if (node) {                                                                                    \

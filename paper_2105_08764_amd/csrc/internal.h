@@ -31,6 +31,7 @@ struct HubTable {              // device pointers into the prepared head of the 
     int n_hubs, n_segs;
     const int32_t *hub_rows;     // [n_hubs] node ids, ascending
     const int32_t *hub_seg_off;  // [n_hubs+1] segments of hub h are [off[h], off[h+1])
+    const int32_t *seg_row;      // [n_segs] node id of the segment's row
     const int32_t *seg_begin;    // [n_segs] first CSR entry of the segment
     const int32_t *seg_end;      // [n_segs] one past its last entry
 };
@@ -44,7 +45,8 @@ struct ChunkTable {            // device pointers into the prepared head of the 
 };
 
 // ---- forward (fwd_kernels.hip) ----
-hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const float *w, float *s_pos, float *s_neg);
+hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const float *w,
+                            float *s_pos, float *s_neg);
 hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec);
 hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *x, const float *s_pos, const float *s_neg,
                          const float *theta1, const float *qvec, float *mu_out);
@@ -58,11 +60,12 @@ hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const f
 // Neighbour sums of the hub rows: hub_sum[h][S][p] = sum over the row of hub h of src[u][s][:]
 // (mask != NULL: counts of set relu-mask bits instead; else src == NULL: the round-1 rows
 // recomputed from info).  partial is [n_segs][S][p] scratch.
-hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *colidx, const float *src,
+hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
+                           const int32_t *colidx, const float *src,
                            const float *info, const float *theta1, const float *qvec,
                            const unsigned long long *mask, float *partial, float *hub_sum);
-hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
-                        const float *mu_in, float *mu_out, const float *info, const float *theta1,
+hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                        const int32_t *colidx, const float *mu_in, float *mu_out, const float *info, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
                         const float *hub_sum);
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum);
@@ -72,6 +75,12 @@ hipError_t launch_qa(hipStream_t st, int p, int S, int G, const float *theta5, c
                      float *qa /*[S][G]*/);
 hipError_t launch_qnode(hipStream_t st, int p, int N, int S, int G, const int32_t *graph_off, const float *theta5,
                         const float *theta7, const float *mu, const float *qa, float *q /*[S][N]*/);
+
+// ---- state update of the inference loop (residual_kernels.hip) ----
+hipError_t launch_residual_update(hipStream_t st, int N, int G, const int32_t *graph_off, const int32_t *rowptr,
+                                  int32_t *rowend, int32_t *colidx, float *w, float *x, const int32_t *sel_idx,
+                                  const int32_t *sel_count, int k, float *s_pos, float *s_neg, uint8_t *cand,
+                                  int32_t *stats /*[G][2]*/);
 
 // ---- selection (select_kernels.hip) ----
 struct SelectScratch {
@@ -112,12 +121,13 @@ hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *mu
                             const float *s_neg, const int32_t *action, const BwdScratch &sc,
                             unsigned long long *mask /*[N][S] or NULL*/, float *dc_part /*[kBwdHeadGrid][3][p]*/);
 // maskT != NULL selects the first reversed round (t = T), which reads relu-mask words instead of dz_in.
-hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
-                            const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
+hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                            const int32_t *colidx, const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out /*may be NULL*/, const float *x, const float *s_pos,
                             const float *s_neg, const float *theta2, float *dc_part /*[kBwdGrid][3][p]*/,
                             float *d2_part /*[kBwdGrid][p][p]*/, const HubTable &ht, const float *hub_sum);
-hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *colidx,
+hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                                 const int32_t *colidx,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
                                  const float *theta2, const float *mu_prev, float *dz_out /*may be NULL*/,
                                  const float *x, const float *s_pos, const float *s_neg,
