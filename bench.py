@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the structure2vec / deep-Q hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-train] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-train] [--no-loop] [--no-cpu-baseline]
 
 A "step" is one RL inference step on the 30M-edge workload (benchmark configuration 4:
 Erdos-Renyi n = 2e6, average degree 30, p = 64, T = 4): embedding (s2v_embed_fwd), scores
@@ -165,6 +165,92 @@ def bench_training(args, s2v, torch):
     return out
 
 
+def bench_loop(args, s2v, torch, w4):
+    """The rest of the paper's inference step and the whole loop (Alg. 3, Sec. 4.5.1):
+    (a) the in-place state update at configuration 4, timed on its own;
+    (b) a whole minimum-vertex-cover solve on the paper's largest test-graph shape of Sec. 6.3
+        (Erdos-Renyi, 3000 nodes, edge probability 0.15, K = 32, L = 2), one node per evaluation
+        versus the adaptive 8/4/2/1 rule.  Random-init parameters: the solution quality means nothing,
+        the timing and the evaluation counts do."""
+    out = {}
+    g = w4.graph
+    ctx = s2v.Context()
+    graph = upload(s2v, torch, g).mutable_copy()
+    N = g.n
+    ws = torch.empty(ctx.s2v_workspace_bytes(graph, w4.p, w4.T, 1, 8), dtype=torch.uint8, device="cuda")
+    ctx.s2v_graph_prepare(graph, ws)
+    x = torch.from_numpy(w4.x[0].copy()).cuda()
+    cand = torch.empty(N, dtype=torch.uint8, device="cuda")
+    stats = torch.zeros((1, 2), dtype=torch.int32, device="cuda")
+    ctx.s2v_residual_update(graph, x, None, None, 0, cand, stats, ws)   # first call removes the covered edges
+    torch.cuda.synchronize()
+    reps = 10
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        ctx.s2v_residual_update(graph, x, None, None, 0, cand, stats, ws)
+    torch.cuda.synchronize()
+    out["state_update_full_ms_cfg4"] = (time.perf_counter() - t0) * 1e3 / reps
+    st = stats.cpu().numpy()
+    out["cfg4_candidates"], out["cfg4_live_entries"] = int(st[0, 0]), int(st[0, 1])
+    # incremental updates: ten real steps (embed, score, top-8, update); only the updates are timed
+    prm = s2v.Params.from_numpy(w4.theta)
+    mu = torch.empty((N, 1, w4.p), device="cuda")
+    gsum = torch.empty((1, 1, w4.p), device="cuda")
+    q = torch.empty((1, N), device="cuda")
+    idx = torch.empty((1, 8), dtype=torch.int32, device="cuda")
+    val = torch.empty((1, 8), device="cuda")
+    cnt = torch.empty((1,), dtype=torch.int32, device="cuda")
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        ctx.s2v_embed_fwd(graph, prm, x.view(1, -1), w4.T, 1, mu, None, gsum, ws)
+        ctx.s2v_q_score(graph, prm, mu, gsum, 1, q, ws)
+        ctx.s2v_select_topk(graph, q[0], x, cand, 8, idx, val, cnt, ws)
+        a.record()
+        ctx.s2v_residual_update(graph, x, idx, cnt, 8, cand, stats, ws)
+        b.record()
+    torch.cuda.synchronize()
+    out["full_step_with_update_ms_cfg4"] = (time.perf_counter() - t0) * 1e3 / reps
+    out["state_update_incremental_ms_cfg4"] = sum(a.elapsed_time(b) for a, b in ev) / reps
+    del graph, ws, x, cand, mu, q
+    torch.cuda.empty_cache()
+
+    n, prob, p, T = 3000, 0.15, 32, 2
+    gs = si.erdos_renyi_gnp(n, prob, 777)
+    theta = si.thetas(p, 778)
+    prm = s2v.Params.from_numpy(theta)
+    res = {}
+    for adaptive in (False, True):
+        graph = upload(s2v, torch, gs).mutable_copy()
+        ws = torch.empty(ctx.s2v_workspace_bytes(graph, p, T, 1, 8), dtype=torch.uint8, device="cuda")
+        ctx.s2v_graph_prepare(graph, ws)
+        x = torch.zeros(n, device="cuda")
+        bufs = dict(mu=torch.empty((n, 1, p), device="cuda"), gsum=torch.empty((1, 1, p), device="cuda"),
+                    q=torch.empty((1, n), device="cuda"), cand=torch.empty(n, dtype=torch.uint8, device="cuda"),
+                    sel_idx=torch.empty((1, 8), dtype=torch.int32, device="cuda"),
+                    sel_val=torch.empty((1, 8), device="cuda"), sel_count=torch.empty(1, dtype=torch.int32, device="cuda"),
+                    stats=torch.empty((1, 2), dtype=torch.int32, device="cuda"))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        steps, picked, live = ctx.s2v_mvc_inference(graph, prm, x, T, adaptive, 10 * n, bufs["mu"], bufs["gsum"],
+                                                    bufs["q"], bufs["cand"], bufs["sel_idx"], bufs["sel_val"],
+                                                    bufs["sel_count"], bufs["stats"], ws)
+        torch.cuda.synchronize()
+        sec = time.perf_counter() - t0
+        assert live == 0
+        res[adaptive] = dict(seconds=sec, evaluations=steps, cover_size=picked, ms_per_evaluation=sec * 1e3 / steps)
+    out["whole_solve_er3000"] = {"graph": f"ER n={n} p={prob} ({gs.nnz // 2} edges), K={p}, L={T}",
+                                 "d1": res[False], "adaptive_d": res[True],
+                                 "cover_size_ratio": res[True]["cover_size"] / res[False]["cover_size"],
+                                 "paper_context_1xV100_s": {"d1": 407.5, "adaptive_d": 109.9, "size_ratio": 1.004}}
+    log(f"[bench] state update at cfg 4: full {out['state_update_full_ms_cfg4']:.3f} ms, incremental "
+        f"{out['state_update_incremental_ms_cfg4']:.3f} ms, whole step {out['full_step_with_update_ms_cfg4']:.3f} ms; "
+        f"whole solve ER(3000,0.15): "
+        f"d=1 {res[False]['seconds']:.3f} s / {res[False]['evaluations']} evaluations, "
+        f"adaptive {res[True]['seconds']:.3f} s / {res[True]['evaluations']} evaluations")
+    return out
+
+
 def cpu_baseline(w):
     """The float64 oracle, as it stands, on the same inference step (embed + scores + top-k)."""
     import oracle
@@ -193,6 +279,7 @@ def main():
     ap.add_argument("--counters", action="store_true",
                     help="short run for rocprofv3 --pmc: a 1 GiB device copy (calibration) and 3 inference steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-loop", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -220,6 +307,10 @@ def main():
     if not args.no_train:
         torch.cuda.empty_cache()
         train = bench_training(args, s2v, torch)
+    loop = None
+    if not args.no_loop and not args.counters:
+        torch.cuda.empty_cache()
+        loop = bench_loop(args, s2v, torch, w4)
     cpu = None if args.no_cpu_baseline else cpu_baseline(w4)
 
     traffic = read_traffic(os.path.join(ROOT, "profiles", "k_round_cfg4_pmc.txt"))
@@ -259,6 +350,7 @@ def main():
         "prepare_ms": round(inf["prepare_ms"], 2),
         "peak_device_mib": round(inf["peak_device_mib"], 1),
         "training": train,
+        "inference_loop": loop,
         "paper_context": {"inference_step_s_1xV100": 23.8, "training_step_s_1xV100": 316.4,
                           "note": "Summit, ER N=21000 (~33M edges), K=32, L=2; another machine and graph shape"},
     }

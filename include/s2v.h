@@ -193,8 +193,11 @@ int32_t s2v_sgd_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, 
  * State update of the inference loop, Alg. 3 lines 8-10, for a graph whose arrays the caller
  * owns as a MUTABLE copy (colidx, w and row_end are written through the const pointers of `g`;
  * g->row_end must be non-NULL, initially a copy of rowptr[1..N]):
- *   - the selected nodes sel_idx[G][k] (first sel_count[g] of each row; sel_idx may be NULL for
- *     "nothing selected") join the partial solution: x[v] = 1;
+ *   - the selected nodes sel_idx[G][k] (first sel_count[g] of each row) join the partial
+ *     solution: x[v] = 1.  With sel_idx == NULL the whole state is rebuilt from x alone (a pass over
+ *     every row); with a selection the update is incremental (only the rows next to the selected
+ *     nodes are touched), so cand, stats, row_end and the arrays of `g` must then be the outcome of
+ *     the previous call on this graph, the first of which was a full rebuild;
  *   - every edge with an endpoint in the solution (x != 0) is removed: rows shrink in place,
  *     keeping the order of the surviving entries; rows of solution nodes become empty;
  *   - s+ / s- in the workspace head are recomputed over the surviving entries, so the graph stays

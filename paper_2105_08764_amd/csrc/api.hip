@@ -35,7 +35,7 @@ struct Carver {
 
 struct HeadLayout {
     size_t s_pos, s_neg, chunk_begin, chunk_end, chunk_graph, graph_chunk_off;
-    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, end;
+    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, list, end;
     int max_chunks, max_hubs, max_segs;
 };
 
@@ -79,6 +79,8 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     h.seg_row = c.take(sizeof(int32_t) * h.max_segs);
     h.seg_begin = c.take(sizeof(int32_t) * h.max_segs);
     h.seg_end = c.take(sizeof(int32_t) * h.max_segs);
+    h.touched = c.take(sizeof(int32_t) * N);        // per-node flags of the incremental state update
+    h.list = c.take(sizeof(int32_t) * (N + 1));     // its work list
     h.end = c.off;
     return h;
 }
@@ -457,6 +459,7 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_begin), seg_begin.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_end), seg_end.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
     }
+    S2V_TRY(launch_zero_i32(ctx->stream, N, at<int32_t>(ws, h.touched)));
     S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, row_end_of(g), g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg)));
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
 
@@ -687,7 +690,8 @@ int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const in
     if (ws_bytes < h.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
     S2V_TRY(launch_residual_update(ctx->stream, N, G, g->graph_off, g->rowptr, const_cast<int32_t *>(g->row_end),
                                    const_cast<int32_t *>(g->colidx), const_cast<float *>(g->w), x, sel_idx, sel_count,
-                                   sel_idx ? k : 0, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg), cand, stats));
+                                   sel_idx ? k : 0, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg), cand, stats,
+                                   at<int32_t>(ws, h.touched), at<int32_t>(ws, h.list)));
     return S2V_OK;
 }
 

@@ -80,7 +80,9 @@ hipError_t launch_qnode(hipStream_t st, int p, int N, int S, int G, const int32_
 hipError_t launch_residual_update(hipStream_t st, int N, int G, const int32_t *graph_off, const int32_t *rowptr,
                                   int32_t *rowend, int32_t *colidx, float *w, float *x, const int32_t *sel_idx,
                                   const int32_t *sel_count, int k, float *s_pos, float *s_neg, uint8_t *cand,
-                                  int32_t *stats /*[G][2]*/);
+                                  int32_t *stats /*[G][2]*/, int32_t *touched /*[N], all zero between calls*/,
+                                  int32_t *list /*[N+1]*/);
+hipError_t launch_zero_i32(hipStream_t st, long n, int32_t *p);
 
 // ---- selection (select_kernels.hip) ----
 struct SelectScratch {

@@ -83,7 +83,8 @@ def test_state_update_matches_oracle_residual_graph(oracle_mod, kind):
     dev = LoopDevice(g, 32, 3)
     rng = np.random.default_rng(7)
     x = np.zeros(g.n, np.float32)
-    for rnd in range(4):
+    dev.update()                                                                    # full rebuild first
+    for rnd in range(5):
         # a few nodes enter the solution through the selection arrays, a few directly through x
         pick = rng.choice(np.flatnonzero(x == 0), size=min(8, int((x == 0).sum())), replace=False).astype(np.int32)
         if kind == "hub" and rnd == 1:
@@ -98,7 +99,12 @@ def test_state_update_matches_oracle_residual_graph(oracle_mod, kind):
             cnt[b] += 1
         dev.sel_idx.copy_(torch.from_numpy(sel))
         dev.sel_cnt.copy_(torch.from_numpy(cnt))
-        stats = dev.update(k=8)
+        if rnd == 3:
+            # nodes that entered the solution behind the library's back: only a full rebuild sees them
+            dev.x[torch.from_numpy(pick.astype(np.int64)).cuda()] = 1.0
+            stats = dev.update()
+        else:
+            stats = dev.update(k=8)                                                 # incremental
         x[pick] = 1.0
         assert np.array_equal(dev.x.cpu().numpy(), x)
         rp, ci, ww = oracle_mod.residual_graph(g.rowptr, g.colidx, g.w, x)
