@@ -251,6 +251,81 @@ def bench_loop(args, s2v, torch, w4):
     return out
 
 
+def bench_paper_shape(args, s2v, torch):
+    """Context line on the paper's own large graph shape (Sec. 6.4: ER, 21 000 nodes, p = 0.15, about
+    33 M edges, K = 32, L = 2): one inference step as the paper counts it (embed, score, argmax, state
+    update) and one training iteration (forward, loss, backward, SGD) on a 16-state minibatch (the
+    paper does not state its batch size).  Next to the paper's 23.8 s / 316.4 s on one V100."""
+    t0 = time.time()
+    w = si.config(6, args.scale)
+    g = w.graph
+    N, p, T = g.n, w.p, w.T
+    log(f"[bench] paper shape generated: n={N} nnz={g.nnz} ({time.time() - t0:.1f}s)")
+    ctx = s2v.Context()
+    graph = upload(s2v, torch, g).mutable_copy()
+    prm = s2v.Params.from_numpy(w.theta)
+    S = 16
+    ws = torch.empty(ctx.s2v_workspace_bytes(graph, p, T, S, 8, True), dtype=torch.uint8, device="cuda")
+    ctx.s2v_graph_prepare(graph, ws)
+    x = torch.zeros(N, device="cuda")
+    mu = torch.empty((N, 1, p), device="cuda")
+    gsum = torch.empty((1, 1, p), device="cuda")
+    q = torch.empty((1, N), device="cuda")
+    cand = torch.empty(N, dtype=torch.uint8, device="cuda")
+    idx = torch.empty((1, 1), dtype=torch.int32, device="cuda")
+    val = torch.empty((1, 1), device="cuda")
+    cnt = torch.empty((1,), dtype=torch.int32, device="cuda")
+    stats = torch.empty((1, 2), dtype=torch.int32, device="cuda")
+    ctx.s2v_residual_update(graph, x, None, None, 0, cand, stats, ws)
+
+    def inf_step():
+        ctx.s2v_embed_fwd(graph, prm, x.view(1, -1), T, 1, mu, None, gsum, ws)
+        ctx.s2v_q_score(graph, prm, mu, gsum, 1, q, ws)
+        ctx.s2v_select_topk(graph, q[0], x, cand, 1, idx, val, cnt, ws)
+        ctx.s2v_residual_update(graph, x, idx, cnt, 1, cand, stats, ws)
+
+    for _ in range(3):
+        inf_step()
+    torch.cuda.synchronize()
+    reps = 20
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        inf_step()
+    torch.cuda.synchronize()
+    inf_ms = (time.perf_counter() - t0) * 1e3 / reps
+
+    # training iteration on the (slightly reduced) graph left by those steps
+    xs = torch.from_numpy(si.node_flags(N, 0.05, 99, n_states=S)).cuda()
+    xs[:, (x != 0)] = 1.0
+    action_np, target_np = si.training_batch(xs.cpu().numpy(), 98)
+    action, target = torch.from_numpy(action_np).cuda(), torch.from_numpy(target_np).cuda()
+    saved = torch.empty((T, N, S, p), device="cuda")
+    gs16 = torch.empty((S, 1, p), device="cuda")
+    loss = torch.empty((1,), device="cuda")
+    qp = torch.empty((S,), device="cuda")
+    grads = s2v.Params.zeros_like(prm)
+    theta0 = {k: v.clone() for k, v in prm.t.items()}
+
+    def train_iter():
+        ctx.s2v_embed_fwd(graph, prm, xs, T, S, None, saved, gs16, ws)
+        ctx.s2v_embed_bwd(graph, prm, xs, T, S, saved, gs16, action, target, loss, qp, grads, ws)
+        ctx.s2v_sgd_step(prm, grads, 1e-5)
+
+    train_iter()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        train_iter()
+    torch.cuda.synchronize()
+    train_ms = (time.perf_counter() - t0) * 1e3 / 5
+    for k_, v in theta0.items():
+        prm.t[k_].copy_(v)
+    log(f"[bench] paper shape ER({N}, 0.15): inference step {inf_ms:.3f} ms, training iteration (S={S}) {train_ms:.3f} ms")
+    return {"graph": f"ER n={N}, p=0.15 ({g.nnz // 2} edges), K={p}, L={T}",
+            "inference_step_ms": inf_ms, "training_iteration_ms_S16": train_ms,
+            "paper_1xV100": {"inference_step_s": 23.8, "training_step_s": 316.4}}
+
+
 def cpu_baseline(w):
     """The float64 oracle, as it stands, on the same inference step (embed + scores + top-k)."""
     import oracle
@@ -311,6 +386,10 @@ def main():
     if not args.no_loop and not args.counters:
         torch.cuda.empty_cache()
         loop = bench_loop(args, s2v, torch, w4)
+    paper = None
+    if not args.no_loop and not args.counters:
+        torch.cuda.empty_cache()
+        paper = bench_paper_shape(args, s2v, torch)
     cpu = None if args.no_cpu_baseline else cpu_baseline(w4)
 
     traffic = read_traffic(os.path.join(ROOT, "profiles", "k_round_cfg4_pmc.txt"))
@@ -351,6 +430,7 @@ def main():
         "peak_device_mib": round(inf["peak_device_mib"], 1),
         "training": train,
         "inference_loop": loop,
+        "paper_shape": paper,
         "paper_context": {"inference_step_s_1xV100": 23.8, "training_step_s_1xV100": 316.4,
                           "note": "Summit, ER N=21000 (~33M edges), K=32, L=2; another machine and graph shape"},
     }

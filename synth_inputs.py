@@ -325,8 +325,9 @@ def _one_percent_k(x_row: np.ndarray) -> int:
 
 
 def config(c: int, scale: float = 1.0) -> Workload:
-    """Benchmark configuration c in 1..5.  scale < 1 shrinks the node count of the
-    large configurations (3, 4, 5) for quick parity runs; the structure is unchanged."""
+    """Benchmark configuration c in 1..5 (6 = the paper's own ER(21000, 0.15) shape).  scale < 1
+    shrinks the node count of the large configurations for quick parity runs; the structure is
+    unchanged."""
     gs, xs, ts, ws, trs = 1000 + c, 2000 + c, 3000 + c, 4000 + c, 5000 + c
     if c == 1:
         g = erdos_renyi_gnp(1000, 0.01, gs)
@@ -354,4 +355,12 @@ def config(c: int, scale: float = 1.0) -> Workload:
         g.w = symmetric_edge_weights(g, ws, 0.5, 1.5)
         x = node_flags(g.n, 0.05, xs)
         return Workload("cfg4_er2m", g, 64, 4, thetas(64, ts), x, _one_percent_k(x[0]))
+    if c == 6:
+        # The paper's own large test shape (Sec. 6.4): Erdos-Renyi, 21 000 nodes, edge probability
+        # 0.15 (about 33 million edges, average degree 3 150), K = 32, L = 2.  G(n, M) stands in for
+        # G(n, p); M = -ln(1 - p) * C(n, 2) random pairs leave p * C(n, 2) distinct ones on average.
+        n = max(64, int(round(21_000 * scale)))
+        g = erdos_renyi_gnm(n, int(-np.log(1.0 - 0.15) * n * (n - 1) / 2), gs)
+        x = node_flags(g.n, 0.05, xs)
+        return Workload("cfg6_paper_er21k", g, 32, 2, thetas(32, ts), x, 1)
     raise ValueError(f"no such configuration: {c}")

@@ -31,6 +31,13 @@ def test_config4_full(oracle_mod):
     _run_config(oracle_mod, 4, 1.0)
 
 
+@pytest.mark.timeout(900)
+def test_paper_shape_er21000(oracle_mod):
+    # the paper's own large graph (Sec. 6.4): every row has about 3 150 entries, so the whole
+    # neighbour sum goes through the long-row (segmented) path; K = 32, L = 2
+    _run_config(oracle_mod, 6, 1.0)
+
+
 @pytest.mark.timeout(1200)
 def test_config5_full_training(oracle_mod):
     import torch
