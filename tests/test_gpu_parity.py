@@ -118,7 +118,7 @@ def _select_cases():
     return n, {"ties": q_ties, "cont": q_cont, "zeros": q_neg0, "const": np.full(n, 2.5, np.float32)}, x
 
 
-@pytest.mark.parametrize("k", [1, 2, 8, 100, 1024, 1025, 6999, 20000])
+@pytest.mark.parametrize("k", [1, 2, 8, 100, 1024, 1025, 6999, 20000])   # 20000 > candidates: everything is taken
 @pytest.mark.parametrize("name", ["ties", "cont", "zeros", "const"])
 def test_topk_bit_exact_on_same_scores(oracle_mod, name, k):
     print(f"case topk {name} k={k}", flush=True)
@@ -133,6 +133,22 @@ def test_topk_bit_exact_on_same_scores(oracle_mod, name, k):
     take = oc[0]
     assert np.array_equal(val[0, :take].astype(np.float64), ov[0, :take])
     assert np.isneginf(val[0, take:]).all()
+
+
+@pytest.mark.parametrize("name", ["ties", "cont"])
+def test_topk_above_the_single_workgroup_sort_limit(oracle_mod, name):
+    # a selection much larger than the benchmark configurations use
+    rng = np.random.default_rng(11)
+    n, k = 300_000, 70_000
+    q = rng.normal(size=n).astype(np.float32)
+    if name == "ties":
+        q = np.round(q, 2)
+    x = (rng.random(n) < 0.2).astype(np.float32)
+    dev = gu.Device(si.edgeless(n), 32, 1, k_max=k)
+    idx, val, cnt = dev.select(q, x, None, k)
+    oi, ov, oc = oracle_mod.select(None, q, x, None, k)
+    assert cnt[0] == oc[0] == k and np.array_equal(idx, oi)
+    assert np.array_equal(val[0].astype(np.float64), ov[0])
 
 
 def test_topk_candidate_mask_and_empty(oracle_mod):
