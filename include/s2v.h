@@ -190,6 +190,28 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
 int32_t s2v_sgd_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, float lr);
 
 /*
+ * Adam step on all seven tensors (the paper trains with Adam, Sec. 4.4; learning rate 1e-5 in
+ * Sec. 6.1), with the usual bias correction: m, v are the first and second moment tensors
+ * (device, updated in place, zero before the first step), step >= 1 is the step number.
+ *   theta <- theta - lr / (1 - beta1^step) * m / (sqrt(v) / sqrt(1 - beta2^step) + eps)
+ */
+int32_t s2v_adam_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, s2v_params *m, s2v_params *v,
+                      int32_t step, float lr, float beta1, float beta2, float eps);
+
+/*
+ * Deep-Q target values of a minibatch (Alg. 4: "compute a target value using the reward";
+ * discount gamma = 0.9 in Sec. 6.1).  The paper does not define its reward, so it is an input:
+ *   target[b] = reward[b] + gamma * max_{v in C'_b} q_next[b][v],   or reward[b] if C'_b is empty,
+ * where q_next [S][N] are the scores of the NEXT states (s2v_embed_fwd + s2v_q_score on x_next) and
+ * C'_b are the next state's candidates (cand_next [S][N] bytes, or NULL = nodes with x_next == 0)
+ * inside the graph that holds action[b] (action [S]; may be NULL for a single graph).
+ *   reward [S], target [S] (output).  Errors: INVALID_ARG, NOT_PREPARED, WORKSPACE_TOO_SMALL, HIP.
+ */
+int32_t s2v_q_target(s2v_ctx *ctx, const s2v_graph *g, const float *q_next, const float *x_next,
+                     const uint8_t *cand_next, const int32_t *action, const float *reward, float gamma, int32_t S,
+                     float *target, void *ws, size_t ws_bytes);
+
+/*
  * State update of the inference loop, Alg. 3 lines 8-10, for a graph whose arrays the caller
  * owns as a MUTABLE copy (colidx, w and row_end are written through the const pointers of `g`;
  * g->row_end must be non-NULL, initially a copy of rowptr[1..N]):

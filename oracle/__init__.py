@@ -206,3 +206,39 @@ def mvc_inference(rowptr, colidx, w, graph_off, theta: dict, x, T: int, adaptive
         x[chosen] = 1.0
         steps += 1
     return x, steps, trace
+
+
+# ---- the rest of the paper's Train step: Adam and the deep-Q target ----------------------------
+
+def adam(theta: dict, grads: dict, m: dict, v: dict, step: int, lr: float, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam step in float64 (the optimiser of Sec. 4.4): returns new (theta, m, v) dicts."""
+    out_t, out_m, out_v = {}, {}, {}
+    for k in THETA_NAMES:
+        g = _f64(grads[k])
+        mk = beta1 * _f64(m[k]) + (1.0 - beta1) * g
+        vk = beta2 * _f64(v[k]) + (1.0 - beta2) * g * g
+        m_hat = mk / (1.0 - beta1 ** step)
+        v_hat = vk / (1.0 - beta2 ** step)
+        out_t[k] = _f64(theta[k]) - lr * m_hat / (np.sqrt(v_hat) + eps)
+        out_m[k], out_v[k] = mk, vk
+    return out_t, out_m, out_v
+
+
+def q_target(graph_off, q_next, x_next, cand_next, action, reward, gamma: float):
+    """target[b] = reward[b] + gamma * (largest next-state score among the candidates of the graph
+    that holds action[b]); reward[b] alone when no candidate is left (Alg. 4's target value)."""
+    q_next = _f64(q_next)
+    S, n = q_next.shape
+    x_next = _f64(x_next).reshape(S, n)
+    go = np.array([0, n], dtype=np.int32) if graph_off is None else _i32(graph_off)
+    out = np.zeros(S, dtype=np.float64)
+    for b in range(S):
+        gidx = int(np.searchsorted(go, int(action[b]) if action is not None else 0, side="right") - 1)
+        lo, hi = int(go[gidx]), int(go[gidx + 1])
+        best = None
+        for v in range(lo, hi):
+            is_c = (cand_next[b][v] != 0) if cand_next is not None else (x_next[b][v] == 0)
+            if is_c and (best is None or q_next[b][v] > best):
+                best = q_next[b][v]
+        out[b] = reward[b] + (gamma * best if best is not None else 0.0)
+    return out

@@ -28,7 +28,7 @@ EXPORTS = (
     "s2v_status_str", "s2v_create", "s2v_destroy", "s2v_last_hip_error", "s2v_workspace_bytes",
     "s2v_graph_prepare", "s2v_embed_fwd", "s2v_q_score", "s2v_select_topk", "s2v_embed_bwd",
     "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end", "s2v_residual_update",
-    "s2v_mvc_inference",
+    "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target",
 )
 
 
@@ -226,6 +226,21 @@ class Context:
                                       ctypes.c_void_p(_dp(target)), ctypes.c_void_p(_dp(loss)),
                                       ctypes.c_void_p(_dp(q_pred)), ctypes.byref(grads.c), ctypes.c_void_p(_dp(ws)),
                                       ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_embed_bwd")
+
+    def s2v_adam_step(self, params: Params, grads: Params, m: Params, v: Params, step: int, lr: float,
+                      beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+        _check(self.lib.s2v_adam_step(self.handle, ctypes.byref(params.c), ctypes.byref(grads.c), ctypes.byref(m.c),
+                                      ctypes.byref(v.c), ctypes.c_int32(step), ctypes.c_float(lr),
+                                      ctypes.c_float(beta1), ctypes.c_float(beta2), ctypes.c_float(eps)),
+               "s2v_adam_step")
+
+    def s2v_q_target(self, g: Graph, q_next, x_next, cand_next, action, reward, gamma: float, S: int, target, ws) -> None:
+        _check(self.lib.s2v_q_target(self.handle, ctypes.byref(g.c), ctypes.c_void_p(_dp(q_next)),
+                                     ctypes.c_void_p(_dp(x_next)), ctypes.c_void_p(_dp(cand_next)),
+                                     ctypes.c_void_p(_dp(action)), ctypes.c_void_p(_dp(reward)),
+                                     ctypes.c_float(gamma), ctypes.c_int32(S), ctypes.c_void_p(_dp(target)),
+                                     ctypes.c_void_p(_dp(ws)), ctypes.c_size_t(ws.numel() * ws.element_size())),
+               "s2v_q_target")
 
     def s2v_residual_update(self, g: Graph, x, sel_idx, sel_count, k: int, cand, stats, ws) -> None:
         _want(cand, "uint8", "cand")

@@ -1,5 +1,6 @@
 // C interface of libs2v.so: argument checks, workspace layout and the order of kernel launches.
 // See include/s2v.h for the contract of every entry point.
+#include <cmath>
 #include <new>
 #include <vector>
 
@@ -379,6 +380,9 @@ int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t
     const size_t s_end = sel_layout(h, g->n_nodes, k_max > 0 ? k_max : 1).end;
     if (q_end > need) need = q_end;
     if (s_end > need) need = s_end;
+    const size_t t_end = align_up(align_up(h.end) + align_up(sizeof(float) * (size_t)S * h.max_chunks) +
+                                  sizeof(int32_t) * (size_t)S * h.max_chunks);
+    if (t_end > need) need = t_end;
     if (training) {
         const size_t b_end = bwd_layout(h, g->n_nodes, p, T, S).end;
         if (b_end > need) need = b_end;
@@ -756,6 +760,52 @@ int32_t s2v_sgd_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, 
     const float *const gr[7] = {grads->theta1, grads->theta2, grads->theta3, grads->theta4,
                                 grads->theta5, grads->theta6, grads->theta7};
     S2V_TRY(launch_sgd(ctx->stream, params->p, th, gr, lr));
+    return S2V_OK;
+}
+
+int32_t s2v_adam_step(s2v_ctx *ctx, s2v_params *params, const s2v_params *grads, s2v_params *m, s2v_params *v,
+                      int32_t step, float lr, float beta1, float beta2, float eps) {
+    if (!ctx || step < 1) return S2V_ERR_INVALID_ARG;
+    const s2v_params *all[4] = {params, grads, m, v};
+    for (const s2v_params *t : all) {
+        int32_t rc = check_params(t);
+        if (rc != S2V_OK) return rc;
+        if (t->p != params->p) return S2V_ERR_INVALID_ARG;
+    }
+    float *const th[7] = {params->theta1, params->theta2, params->theta3, params->theta4,
+                          params->theta5, params->theta6, params->theta7};
+    const float *const gr[7] = {grads->theta1, grads->theta2, grads->theta3, grads->theta4,
+                                grads->theta5, grads->theta6, grads->theta7};
+    float *const mm[7] = {m->theta1, m->theta2, m->theta3, m->theta4, m->theta5, m->theta6, m->theta7};
+    float *const vv[7] = {v->theta1, v->theta2, v->theta3, v->theta4, v->theta5, v->theta6, v->theta7};
+    const float bias1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    const float bias2_sqrt = (float)std::sqrt(1.0 - std::pow((double)beta2, (double)step));
+    S2V_TRY(launch_adam(ctx->stream, params->p, th, gr, mm, vv, lr, beta1, beta2, eps, bias1, bias2_sqrt));
+    return S2V_OK;
+}
+
+int32_t s2v_q_target(s2v_ctx *ctx, const s2v_graph *g, const float *q_next, const float *x_next,
+                     const uint8_t *cand_next, const int32_t *action, const float *reward, float gamma, int32_t S,
+                     float *target, void *ws, size_t ws_bytes) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    int32_t rc = check_graph(g);
+    if (rc != S2V_OK) return rc;
+    rc = check_ws(ws);
+    if (rc != S2V_OK) return rc;
+    if (S < 1 || !reward || !target) return S2V_ERR_INVALID_ARG;
+    const int32_t N = g->n_nodes, G = g->n_graphs;
+    if (N > 0 && (!q_next || (!x_next && !cand_next))) return S2V_ERR_INVALID_ARG;
+    if (G > 1 && !action) return S2V_ERR_INVALID_ARG;
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
+    Carver c(h.end);
+    const size_t pv = c.take(sizeof(float) * (size_t)S * h.max_chunks);
+    const size_t pi = c.take(sizeof(int32_t) * (size_t)S * h.max_chunks);
+    if (ws_bytes < c.off) return S2V_ERR_WORKSPACE_TOO_SMALL;
+    const ChunkTable ct = chunk_table(ws, h, *pr);
+    S2V_TRY(launch_q_target(ctx->stream, N, S, G, g->graph_off, ct, q_next, x_next, cand_next, action, reward, gamma,
+                            at<float>(ws, pv), at<int32_t>(ws, pi), target));
     return S2V_OK;
 }
 

@@ -630,4 +630,39 @@ hipError_t launch_sgd(hipStream_t st, int p, float *const theta[7], const float 
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Adam (the optimiser the paper trains with, Sec. 4.4), one step over the seven tensors:
+//   m <- b1 m + (1-b1) g,  v <- b2 v + (1-b2) g^2,
+//   theta <- theta - lr / (1 - b1^t) * m / (sqrt(v) / sqrt(1 - b2^t) + eps).
+// ------------------------------------------------------------------------------------------
+struct AdamArgs {
+    float *theta[7];
+    const float *grad[7];
+    float *m[7];
+    float *v[7];
+    int len[7];
+};
+
+__global__ __launch_bounds__(256) void k_adam(AdamArgs a, float lr, float b1, float b2, float eps, float bias1,
+                                              float bias2_sqrt) {
+    const int t = blockIdx.y;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < a.len[t]; i += gridDim.x * 256) {
+        const float g = a.grad[t][i];
+        const float m = b1 * a.m[t][i] + (1.f - b1) * g;
+        const float v = b2 * a.v[t][i] + (1.f - b2) * g * g;
+        a.m[t][i] = m;
+        a.v[t][i] = v;
+        a.theta[t][i] = a.theta[t][i] - (lr / bias1) * (m / (sqrtf(v) / bias2_sqrt + eps));
+    }
+}
+
+hipError_t launch_adam(hipStream_t st, int p, float *const theta[7], const float *const grad[7], float *const m[7],
+                       float *const v[7], float lr, float b1, float b2, float eps, float bias1, float bias2_sqrt) {
+    AdamArgs a;
+    const int len[7] = {p, p * p, p * p, p, 2 * p, p * p, p * p};
+    for (int i = 0; i < 7; ++i) { a.theta[i] = theta[i]; a.grad[i] = grad[i]; a.m[i] = m[i]; a.v[i] = v[i]; a.len[i] = len[i]; }
+    k_adam<<<dim3((p * p + 255) / 256, 7), 256, 0, st>>>(a, lr, b1, b2, eps, bias1, bias2_sqrt);
+    return hipGetLastError();
+}
+
 }  // namespace s2v

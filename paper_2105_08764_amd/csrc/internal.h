@@ -97,6 +97,10 @@ struct SelectScratch {
 };
 hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, const float *q, const float *x,
                          const uint8_t *cand, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
+hipError_t launch_q_target(hipStream_t st, int N, int S, int G, const int32_t *graph_off, const ChunkTable &ct,
+                           const float *q_next, const float *x_next, const uint8_t *cand_next, const int32_t *action,
+                           const float *reward, float gamma, float *part_val /*[S][n_chunks]*/,
+                           int32_t *part_idx /*[S][n_chunks]*/, float *target);
 hipError_t launch_topk(hipStream_t st, int N, const float *q, const float *x, const uint8_t *cand, int k,
                        const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
 
@@ -137,5 +141,7 @@ hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int3
 hipError_t launch_bwd_finish(hipStream_t st, int p, int dc_rows, int d2_rows, const BwdScratch &sc, const float *theta3,
                              const float *theta4, float *d1, float *d2, float *d3, float *d4);
 hipError_t launch_sgd(hipStream_t st, int p, float *const theta[7], const float *const grad[7], float lr);
+hipError_t launch_adam(hipStream_t st, int p, float *const theta[7], const float *const grad[7], float *const m[7],
+                       float *const v[7], float lr, float b1, float b2, float eps, float bias1, float bias2_sqrt);
 
 }  // namespace s2v

@@ -92,6 +92,72 @@ hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, con
 }
 
 // ------------------------------------------------------------------------------------------
+// Deep-Q target of the training step (Alg. 4, "compute a target value using the reward"):
+//   target[b] = reward[b] + gamma * max over the candidates v of the next state b, inside the graph
+//   of action[b], of q_next[b][v];   target[b] = reward[b] when that state has no candidate left.
+// Same two-stage (chunk, graph) maximum as the argmax, once per state.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_target_stage1(int N, int n_chunks, const int32_t *__restrict__ chunk_begin,
+                                                       const int32_t *__restrict__ chunk_end,
+                                                       const float *__restrict__ q, const float *__restrict__ x,
+                                                       const uint8_t *__restrict__ cand,
+                                                       float *__restrict__ part_val, int32_t *__restrict__ part_idx) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    const int c = blockIdx.x, s = blockIdx.y;
+    const size_t off = (size_t)s * N;
+    const int vb = chunk_begin[c], ve = chunk_end[c];
+    float val = -INFINITY;
+    int idx = INT_MAX;
+    for (int v = vb + threadIdx.x; v < ve; v += 256)
+        if (is_candidate(x + off, cand ? cand + off : nullptr, v)) take_better(val, idx, q[off + v], v);
+    block_best(val, idx, sval, sidx);
+    if (threadIdx.x == 0) { part_val[(size_t)s * n_chunks + c] = val; part_idx[(size_t)s * n_chunks + c] = idx; }
+}
+
+__global__ __launch_bounds__(256) void k_target_stage2(int G, int n_chunks, const int32_t *__restrict__ graph_off,
+                                                       const int32_t *__restrict__ graph_chunk_off,
+                                                       const int32_t *__restrict__ action,
+                                                       const float *__restrict__ reward, float gamma,
+                                                       const float *__restrict__ part_val,
+                                                       const int32_t *__restrict__ part_idx,
+                                                       float *__restrict__ target) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    const int s = blockIdx.x;
+    int g = 0;
+    if (G > 1) {   // last graph whose offset is <= the action node
+        const int a = action[s];
+        int lo = 0, hi = G;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (graph_off[mid] <= a) lo = mid; else hi = mid;
+        }
+        g = lo;
+    }
+    float val = -INFINITY;
+    int idx = INT_MAX;
+    for (int c = graph_chunk_off[g] + threadIdx.x; c < graph_chunk_off[g + 1]; c += 256)
+        take_better(val, idx, part_val[(size_t)s * n_chunks + c], part_idx[(size_t)s * n_chunks + c]);
+    block_best(val, idx, sval, sidx);
+    if (threadIdx.x == 0) target[s] = idx != INT_MAX ? reward[s] + gamma * val : reward[s];
+}
+
+hipError_t launch_q_target(hipStream_t st, int N, int S, int G, const int32_t *graph_off, const ChunkTable &ct,
+                           const float *q_next, const float *x_next, const uint8_t *cand_next, const int32_t *action,
+                           const float *reward, float gamma, float *part_val, int32_t *part_idx, float *target) {
+    if (ct.n_chunks > 0) {
+        k_target_stage1<<<dim3(ct.n_chunks, S), 256, 0, st>>>(N, ct.n_chunks, ct.chunk_begin, ct.chunk_end, q_next, x_next,
+                                                            cand_next, part_val, part_idx);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    k_target_stage2<<<S, 256, 0, st>>>(G, ct.n_chunks, graph_off, ct.graph_chunk_off, action, reward, gamma, part_val,
+                                       part_idx, target);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // Top-k of one graph.
 //  1. radix select: four 8-bit histogram passes from the top byte find the k-th largest key tau
 //     and how many keys equal to tau are still needed (`need`);

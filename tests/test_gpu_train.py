@@ -124,3 +124,56 @@ def test_training_config5_scaled(oracle_mod):
             assert gu.rel_err(got[name], want[name], whole=True) <= TOL, name
         compared += 1
     assert compared >= 1
+
+
+def test_adam_steps_match_oracle(oracle_mod):
+    import torch
+
+    import paper_2105_08764_amd as s2v
+
+    p = 64
+    theta = si.thetas(p, 1)
+    ctx = s2v.Context()
+    prm = s2v.Params.from_numpy(theta)
+    m, v = s2v.Params.zeros_like(prm), s2v.Params.zeros_like(prm)
+    th = {k: a.astype(np.float64) for k, a in theta.items()}
+    om = {k: np.zeros_like(a) for k, a in th.items()}
+    ov = {k: np.zeros_like(a) for k, a in th.items()}
+    for step in (1, 2, 3, 4):
+        grad = si.thetas(p, 10 + step, 0.5)
+        ctx.s2v_adam_step(prm, s2v.Params.from_numpy(grad), m, v, step, 1e-3)
+        # the oracle takes the hyper-parameters as the float32 values the library receives
+        th, om, ov = oracle_mod.adam(th, grad, om, ov, step, float(np.float32(1e-3)), float(np.float32(0.9)),
+                                     float(np.float32(0.999)), float(np.float32(1e-8)))
+    torch.cuda.synchronize()
+    got, gm, gv = prm.to_numpy(), m.to_numpy(), v.to_numpy()
+    for name in si.THETA_NAMES:
+        assert gu.rel_err(got[name], th[name], whole=True) <= 1e-5, name
+        assert gu.rel_err(gm[name], om[name], whole=True) <= 1e-5 and gu.rel_err(gv[name], ov[name], whole=True) <= 1e-5
+
+
+def test_q_target_matches_oracle(oracle_mod):
+    import torch
+
+    parts = [si.barabasi_albert(n, 2, 3 + i) if n > 2 else si.edgeless(n) for i, n in enumerate((700, 1, 1500, 40))]
+    g = si.block_diagonal(parts)
+    S, p, T = 5, 32, 3
+    theta = si.thetas(p, 2)
+    x_next = si.node_flags(g.n, 0.3, 9, n_states=S)
+    x_next[3, g.graph_off[3]:g.graph_off[4]] = 1.0            # one state whose graph has no candidate left
+    action = np.array([5, 700, 900, g.graph_off[3] + 2, 100], dtype=np.int32)
+    reward = np.random.default_rng(0).normal(size=S).astype(np.float32)
+    dev = gu.Device(g, p, T, S=S)
+    out = dev.forward(theta, x_next)
+    tgt = torch.full((S,), float("nan"), device="cuda")
+    dev.ctx.s2v_q_target(dev.graph, dev.last["q"], dev.last["x"], None, torch.from_numpy(action).cuda(),
+                         torch.from_numpy(reward).cuda(), 0.9, S, tgt, dev.ws)
+    torch.cuda.synchronize()
+    # given the GPU's own float32 scores the maximum is exact; the sum is one float32 rounding away
+    want = oracle_mod.q_target(g.graph_off, out["q"], x_next, None, action, reward, np.float32(0.9))
+    np.testing.assert_allclose(tgt.cpu().numpy(), want, rtol=3e-7, atol=1e-30)
+    assert tgt.cpu().numpy()[3] == reward[3]
+    # and against the oracle's own float64 scores
+    q64 = np.stack([gu.oracle_forward(oracle_mod, g, theta, x_next[s], T)[2] for s in range(S)])
+    want64 = oracle_mod.q_target(g.graph_off, q64, x_next, None, action, reward, 0.9)
+    assert gu.rel_err(tgt.cpu().numpy(), want64) <= 1e-4

@@ -410,3 +410,52 @@ def test_barabasi_albert_is_heavy_tailed():
     g = si.barabasi_albert(20000, 8, 5)
     d = g.degrees()
     assert 15.5 < d.mean() < 16.0 and d.max() > 20 * d.mean() and np.median(d) < d.mean()
+
+
+# ---- Adam and the deep-Q target ------------------------------------------------------------------
+
+def test_adam_matches_torch_optim(oracle_mod):
+    # the optimiser of Sec. 4.4, against the library implementation (float64, three steps)
+    torch = pytest.importorskip("torch")
+    p = 4
+    theta = {k: v.astype(np.float64) for k, v in rand_theta(p, 90).items()}
+    params = {k: torch.tensor(v.copy(), dtype=torch.float64, requires_grad=True) for k, v in theta.items()}
+    opt = torch.optim.Adam(list(params.values()), lr=1e-2, betas=(0.9, 0.999), eps=1e-8)
+    m = {k: np.zeros_like(v) for k, v in theta.items()}
+    v2 = {k: np.zeros_like(v) for k, v in theta.items()}
+    for step in (1, 2, 3):
+        grads = {k: g.astype(np.float64) for k, g in rand_theta(p, 91 + step, std=1.0).items()}
+        for k in params:
+            params[k].grad = torch.tensor(grads[k])
+        opt.step()
+        theta, m, v2 = oracle_mod.adam(theta, grads, m, v2, step, 1e-2)
+        for k in params:
+            np.testing.assert_allclose(theta[k], params[k].detach().numpy(), rtol=1e-12, atol=1e-15, err_msg=k)
+
+
+def test_q_target_special_cases(oracle_mod):
+    rng = np.random.default_rng(12)
+    parts = [si.edgeless(n) for n in (6, 9, 4)]
+    g = si.block_diagonal(parts)
+    S = 5
+    q = rng.normal(size=(S, g.n))
+    x = (rng.random((S, g.n)) < 0.4).astype(np.float64)
+    action = np.array([0, 7, 16, 3, 10], dtype=np.int32)
+    reward = rng.normal(size=S)
+    # gamma = 0: the target is the reward
+    np.testing.assert_array_equal(oracle_mod.q_target(g.graph_off, q, x, None, action, reward, 0.0), reward)
+    # it agrees with the selection routine's best candidate of the action's graph (k = 1)
+    t = oracle_mod.q_target(g.graph_off, q, x, None, action, reward, 0.9)
+    for b in range(S):
+        idx, val, cnt = oracle_mod.select(g.graph_off, q[b], x[b], None, 1)
+        gi = int(np.searchsorted(g.graph_off, action[b], side="right") - 1)
+        want = reward[b] + (0.9 * val[gi, 0] if cnt[gi] else 0.0)
+        assert t[b] == want
+    # a state with no candidate in its graph keeps the bare reward
+    x[2, g.graph_off[2]:g.graph_off[3]] = 1.0
+    assert oracle_mod.q_target(g.graph_off, q, x, None, action, reward, 0.9)[2] == reward[2]
+    # an explicit candidate mask overrides x
+    cand = np.zeros((S, g.n), np.uint8)
+    cand[:, 1] = 1
+    t = oracle_mod.q_target(g.graph_off, q, x, cand, np.zeros(S, np.int32), reward, 0.5)
+    np.testing.assert_allclose(t, reward + 0.5 * q[:, 1], rtol=0, atol=0)
