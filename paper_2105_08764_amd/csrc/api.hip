@@ -35,7 +35,7 @@ struct Carver {
 };
 
 struct HeadLayout {
-    size_t s_pos, s_neg, chunk_begin, chunk_end, chunk_graph, graph_chunk_off;
+    size_t s_pos, s_neg, chunk_begin, chunk_end, graph_chunk_off;
     size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, list, end;
     int max_chunks, max_hubs, max_segs;
 };
@@ -73,7 +73,6 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     h.s_neg = c.take(sizeof(float) * N);
     h.chunk_begin = c.take(sizeof(int32_t) * h.max_chunks);
     h.chunk_end = c.take(sizeof(int32_t) * h.max_chunks);
-    h.chunk_graph = c.take(sizeof(int32_t) * h.max_chunks);
     h.graph_chunk_off = c.take(sizeof(int32_t) * (G + 1));
     h.hub_rows = c.take(sizeof(int32_t) * h.max_hubs);
     h.hub_seg_off = c.take(sizeof(int32_t) * (h.max_hubs + 1));
@@ -265,7 +264,6 @@ ChunkTable chunk_table(void *ws, const HeadLayout &h, const Prepared &pr) {
     ct.n_chunks = pr.n_chunks;
     ct.chunk_begin = at<int32_t>(ws, h.chunk_begin);
     ct.chunk_end = at<int32_t>(ws, h.chunk_end);
-    ct.chunk_graph = at<int32_t>(ws, h.chunk_graph);
     ct.graph_chunk_off = at<int32_t>(ws, h.graph_chunk_off);
     return ct;
 }
@@ -424,13 +422,12 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
         off[0] = 0;
         off[1] = N;
     }
-    std::vector<int32_t> cb, ce, cg, gco(G + 1);
+    std::vector<int32_t> cb, ce, gco(G + 1);
     for (int b = 0; b < G; ++b) {
         gco[b] = (int32_t)cb.size();
         for (int32_t v = off[b]; v < off[b + 1]; v += kChunkNodes) {
             cb.push_back(v);
             ce.push_back(v + kChunkNodes < off[b + 1] ? v + kChunkNodes : off[b + 1]);
-            cg.push_back(b);
         }
     }
     gco[G] = (int32_t)cb.size();
@@ -439,7 +436,6 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     if (n_chunks > 0) {
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_begin), cb.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_end), ce.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
-        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.chunk_graph), cg.data(), sizeof(int32_t) * n_chunks, hipMemcpyHostToDevice, ctx->stream));
     }
     S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.graph_chunk_off), gco.data(), sizeof(int32_t) * (G + 1), hipMemcpyHostToDevice, ctx->stream));
     std::vector<int32_t> hub_rows, hub_seg_off, seg_row, seg_begin, seg_end;

@@ -351,26 +351,6 @@ __device__ __forceinline__ Frag<P> load_a_frag_lds(const float *tile, int lane) 
     return f;
 }
 
-// A-fragment straight from a row-major [rows][P] matrix in global memory; rows past n_rows read as zero.
-template <int P>
-__device__ __forceinline__ Frag<P> load_a_frag_global(const float *__restrict__ m, long row0, long n_rows, int lane) {
-    constexpr int KS = Geo<P>::KS;
-    Frag<P> f;
-    const long r = row0 + (lane & 15);
-    if (r < n_rows) {
-        const float *row = m + (size_t)r * P + (lane >> 4) * KS;
-#pragma unroll
-        for (int c = 0; c < KS / 4; ++c) {
-            const float4 t = ld4(row + 4 * c);
-            f.v[4 * c] = t.x; f.v[4 * c + 1] = t.y; f.v[4 * c + 2] = t.z; f.v[4 * c + 3] = t.w;
-        }
-    } else {
-#pragma unroll
-        for (int c = 0; c < KS; ++c) f.v[c] = 0.f;
-    }
-    return f;
-}
-
 // B-fragments for column block cb of D = A * M^T, M row-major [P][P] (B[j][k] = M[j][k]).
 template <int P>
 __device__ __forceinline__ Frag<P> load_b_frag_rows(const float *__restrict__ m, int cb, int lane) {
@@ -382,17 +362,6 @@ __device__ __forceinline__ Frag<P> load_b_frag_rows(const float *__restrict__ m,
         const float4 t = ld4(row + 4 * c);
         f.v[4 * c] = t.x; f.v[4 * c + 1] = t.y; f.v[4 * c + 2] = t.z; f.v[4 * c + 3] = t.w;
     }
-    return f;
-}
-
-// B-fragments for column block cb of D = A * M, M row-major [P][P] (B[j][k] = M[k][j]).
-template <int P>
-__device__ __forceinline__ Frag<P> load_b_frag_cols(const float *__restrict__ m, int cb, int lane) {
-    constexpr int KS = Geo<P>::KS;
-    Frag<P> f;
-    const float *col = m + (size_t)((lane >> 4) * KS) * P + 16 * cb + (lane & 15);
-#pragma unroll
-    for (int c = 0; c < KS; ++c) f.v[c] = col[(size_t)c * P];
     return f;
 }
 

@@ -40,7 +40,6 @@ struct ChunkTable {            // device pointers into the prepared head of the 
     int n_chunks;
     const int32_t *chunk_begin;      // [n_chunks] first node
     const int32_t *chunk_end;        // [n_chunks] one past the last node
-    const int32_t *chunk_graph;      // [n_chunks] graph of the chunk
     const int32_t *graph_chunk_off;  // [G+1] chunks of graph g are [off[g], off[g+1])
 };
 
