@@ -76,6 +76,11 @@ typedef struct {
     const int32_t *row_end;   /* device [N]: one past the last LIVE entry of each row, rowptr[v] <= row_end[v]
                                  <= rowptr[v+1], or NULL = every stored entry is live.  Used by the inference
                                  loop, whose rows shrink as nodes join the solution (s2v_residual_update). */
+    int32_t state_residual;   /* non-zero: in s2v_embed_fwd / s2v_embed_bwd every state b lives on its OWN residual
+                                 graph: the edges with an endpoint v that has x[b][v] != 0 are absent for that state
+                                 (the sub-graphs the paper's Tuples2Graphs rebuilds for a training minibatch, Alg. 4);
+                                 such nodes stay as isolated nodes.  Nothing is copied or edited: the states share
+                                 this CSR.  Zero: all states use the stored graph as it is. */
 } s2v_graph;
 
 /* The seven parameter tensors (device pointers), also used for their gradients. */

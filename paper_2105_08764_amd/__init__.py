@@ -48,6 +48,7 @@ class CGraph(ctypes.Structure):
         ("n_graphs", ctypes.c_int32),
         ("graph_off", ctypes.c_void_p),
         ("row_end", ctypes.c_void_p),
+        ("state_residual", ctypes.c_int32),
     ]
 
 
@@ -111,7 +112,7 @@ def _want(t, dtype, what):
 class Graph:
     """Device-side CSR graph (or block-diagonal batch); keeps the tensors alive."""
 
-    def __init__(self, rowptr, colidx, w=None, graph_off=None, row_end=None):
+    def __init__(self, rowptr, colidx, w=None, graph_off=None, row_end=None, state_residual=False):
         _want(row_end, "int32", "row_end")
         _want(rowptr, "int32", "rowptr")
         _want(colidx, "int32", "colidx")
@@ -122,7 +123,8 @@ class Graph:
         self.nnz = int(colidx.numel())
         self.n_graphs = 1 if graph_off is None else int(graph_off.numel() - 1)
         self.c = CGraph(self.n_nodes, self.nnz, _dp(rowptr), _dp(colidx) if self.nnz else None, _dp(w),
-                        self.n_graphs, _dp(graph_off), _dp(row_end))
+                        self.n_graphs, _dp(graph_off), _dp(row_end), int(bool(state_residual)))
+        self.state_residual = bool(state_residual)
 
     def mutable_copy(self):
         """A copy whose colidx / w / row_end the inference loop may edit in place."""

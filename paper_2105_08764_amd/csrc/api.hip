@@ -131,7 +131,7 @@ SelLayout sel_layout(const HeadLayout &h, int64_t N, int64_t k) {
 }
 
 struct BwdLayout {
-    size_t dg, da, glo, ghi, head_part, dz0, dz1, maskT, dc_part, d2_part, dvec, red_tmp, hub_part, hub_sum, end;
+    size_t dg, da, glo, ghi, head_part, dz0, dz1, maskT, rec, dc_part, d2_part, dvec, red_tmp, hub_part, hub_sum, end;
     int dc_rows, d2_rows;
 };
 BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
@@ -150,6 +150,7 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.dz0 = c.take(T >= 3 ? sizeof(float) * (size_t)N * S * p : 0);
     b.dz1 = c.take(T >= 4 ? sizeof(float) * (size_t)N * S * p : 0);
     b.maskT = c.take(T >= 2 ? sizeof(unsigned long long) * (size_t)N * S : 0);
+    b.rec = c.take(sizeof(float) * (size_t)N * S * 4);
     b.dc_part = c.take(sizeof(float) * (size_t)b.dc_rows * 3 * p);
     b.d2_part = c.take(sizeof(float) * (size_t)b.d2_rows * p * p);
     b.dvec = c.take(sizeof(float) * 3 * p);
@@ -507,17 +508,24 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     // the neighbours' round-1 rows from the per-node scalars instead of gathering them.
     float *info = at<float>(ws, f.info);
     float *gpart = at<float>(ws, f.gpart);
-    if (T >= 2) S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info));
-    if (mu_saved || T == 1) S2V_TRY(launch_round1(st, p, N, S, x, s_pos, s_neg, params->theta1, qvec, dest(1)));
-    const bool fuse_gsum = gsum && S == 1 && G == 1 && T >= 2 && N > 0;
     const HubTable ht = hub_table(ws, h, *pr);
+    // per-(node, state) scalar records; with per-state residual graphs they hold each state's own edge sums
+    const float *x_res = g->state_residual ? x : nullptr;
+    if (x_res)
+        S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info));
+    else
+        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info));
+    if (mu_saved || T == 1)
+        S2V_TRY(launch_round1(st, p, N, S, info, x_res, T == 1, params->theta1, qvec, dest(1)));
+    const bool fuse_gsum = gsum && S == 1 && G == 1 && T >= 2 && N > 0;
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     for (int t = 2; t <= T; ++t) {
         const float *src = t == 2 ? nullptr : dest(t - 1);
         S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, src, info, params->theta1, qvec, nullptr, hub_part, hub_sum));
         SpanGuard span(ctx, t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND);
-        S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, src, dest(t), info, params->theta1, params->theta2,
-                             qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum));
+        S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, src, dest(t), info, params->theta1,
+                             params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum, x_res,
+                             t == T));
     }
     float *muT = dest(T);
     if (mu_saved && mu_out && mu_out != muT && nsp > 0)
@@ -629,6 +637,7 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     sc.dz[0] = at<float>(ws, bl.dz0);
     sc.dz[1] = at<float>(ws, bl.dz1);
     sc.maskT = at<unsigned long long>(ws, bl.maskT);
+    sc.rec = at<float>(ws, bl.rec);
     sc.dc_part = at<float>(ws, bl.dc_part);
     sc.d2_part = at<float>(ws, bl.d2_part);
     sc.dvec = at<float>(ws, bl.dvec);
@@ -640,8 +649,13 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
                             action, target, sc, q_pred));
     S2V_TRY(launch_bwd_head_reduce(st, p, S, sc, loss, grads->theta5, grads->theta6, grads->theta7));
     // dz^T is never materialised: its relu mask and its share of the sums come from one pass over mu^T
-    S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, x, s_pos, s_neg, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part));
     const HubTable ht = hub_table(ws, h, *pr);
+    const float *x_res = g->state_residual ? x : nullptr;
+    if (x_res)
+        S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, sc.rec));
+    else
+        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec));
+    S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, sc.rec, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part));
     float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);
     int cur = 1;  // the round t = T writes dz[0]
     for (int t = T; t >= 2; --t) {
@@ -657,13 +671,13 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         {
             SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
             S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
-                                     dz_out, x, s_pos, s_neg, params->theta2, dc_part, d2_part, ht, hub_sum));
+                                     dz_out, sc.rec, params->theta2, dc_part, d2_part, ht, hub_sum));
         }
         if (first) {
             float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;
             float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdGrid * p * p;
             S2V_TRY(launch_bwd_action_fix(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, action, sc.maskT, sc, params->theta2,
-                                          mu_prev, dz_out, x, s_pos, s_neg, dc_fix, d2_fix));
+                                          mu_prev, dz_out, sc.rec, dc_fix, d2_fix));
         }
         cur ^= 1;
     }

@@ -137,8 +137,8 @@ hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch
 // ------------------------------------------------------------------------------------------
 template <int P>
 __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, const float *__restrict__ muT,
-                                                   const float *__restrict__ x, const float *__restrict__ s_pos,
-                                                   const float *__restrict__ s_neg, const int32_t *__restrict__ action,
+                                                   const float *__restrict__ rec, const float *__restrict__ x_res,
+                                                   const int32_t *__restrict__ action,
                                                    const float *__restrict__ dg, const float *__restrict__ da,
                                                    const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi,
                                                    unsigned long long *__restrict__ mask,
@@ -176,7 +176,15 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
                 const unsigned nib = (mu[k].x > 0.f ? 1u : 0u) | (mu[k].y > 0.f ? 2u : 0u) |
                                      (mu[k].z > 0.f ? 4u : 0u) | (mu[k].w > 0.f ? 8u : 0u);
                 word = (unsigned long long)nib << (4 * c4);
-                const float xs = x[(size_t)s * N + v], sp = s_pos[v], sn = s_neg[v];
+                const float4 q = ld4(rec + r * 4);
+                float xs = q.z;
+                const float sp = q.x, sn = q.y;
+                if (x_res) {
+                    // per-state residual graphs: a solution node is isolated; it still feeds dtheta1 through
+                    // the graph sum, but its mask word is zero so that no neighbour gathers from it
+                    const float xo = x_res[(size_t)s * N + v];
+                    if (xo != 0.f) { xs = xo; word = 0ull; }
+                }
                 ax.x += xs * d.x; ax.y += xs * d.y; ax.z += xs * d.z; ax.w += xs * d.w;
                 ap.x += sp * d.x; ap.y += sp * d.y; ap.z += sp * d.z; ap.w += sp * d.w;
                 an.x += sn * d.x; an.y += sn * d.y; an.z += sn * d.z; an.w += sn * d.w;
@@ -201,15 +209,14 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
     }
 }
 
-hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const float *x, const float *s_pos,
-                            const float *s_neg, const int32_t *action, const BwdScratch &sc,
-                            unsigned long long *mask, float *dc_part) {
+hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const float *rec, const float *x_res,
+                            const int32_t *action, const BwdScratch &sc, unsigned long long *mask, float *dc_part) {
     const long n_vrows = (long)N * S;
     if (p == 32)
-        k_bwd_maskT<32><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, x, s_pos, s_neg, action, sc.dg, sc.da, sc.glo,
+        k_bwd_maskT<32><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, rec, x_res, action, sc.dg, sc.da, sc.glo,
                                                       sc.ghi, mask, dc_part);
     else
-        k_bwd_maskT<64><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, x, s_pos, s_neg, action, sc.dg, sc.da, sc.glo,
+        k_bwd_maskT<64><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, rec, x_res, action, sc.dg, sc.da, sc.glo,
                                                       sc.ghi, mask, dc_part);
     return hipGetLastError();
 }
@@ -231,8 +238,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     int n_vrows, int N, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
     const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
-    float *__restrict__ dz_out, const float *__restrict__ x, const float *__restrict__ s_pos,
-    const float *__restrict__ s_neg, const float *__restrict__ theta2, float *__restrict__ dc_part,
+    float *__restrict__ dz_out, const float *__restrict__ rec, const float *__restrict__ theta2,
+    float *__restrict__ dc_part,
     float *__restrict__ d2_part, HubTable ht, const float *__restrict__ hub_sum) {
     using Ge = Geo<P>;
     constexpr int CB = Ge::CB, STRIDE = Ge::STRIDE;
@@ -267,9 +274,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
         const int s = valid ? r - v * S : 0;
         const int rb = valid ? rowptr[v] : 0;
         const int re = valid ? rowend[v] : 0;
-        const float xs = valid ? x[(size_t)s * N + v] : 0.f;
-        const float sp = valid ? s_pos[v] : 0.f;
-        const float sn = valid ? s_neg[v] : 0.f;
+        const float4 mine = valid ? ld4(rec + (size_t)r * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float sp = mine.x, sn = mine.y, xs = mine.z;
         // MASK: rows outside the action's graph receive nothing from the broadcast part of dz^T
         const bool in_graph = MASK ? (valid && v >= glo[s] && v < ghi[s]) : true;
 
@@ -429,15 +435,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
 
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                             const int32_t *colidx, const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
-                            const float *mu_prev, float *dz_out, const float *x, const float *s_pos,
-                            const float *s_neg, const float *theta2, float *dc_part, float *d2_part,
-                            const HubTable &ht, const float *hub_sum) {
+                            const float *mu_prev, float *dz_out, const float *rec, const float *theta2,
+                            float *dc_part, float *d2_part, const HubTable &ht, const float *hub_sum) {
     const long n_vrows = (long)N * S;
     const bool node = (S % 16) == 0, mask = maskT != nullptr;
 #define S2V_LAUNCH_BWD(PP, NODE, MASK)                                                                              \
     k_bwd_round<PP, NODE, MASK><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, rowend, colidx, dz_in, maskT, \
                                                                sc.dg, \
-                                                               sc.glo, sc.ghi, mu_prev, dz_out, x, s_pos, s_neg, theta2, \
+                                                               sc.glo, sc.ghi, mu_prev, dz_out, rec, theta2, \
                                                                dc_part, d2_part, ht, hub_sum)
 #define S2V_LAUNCH_BWD_P(PP)                                                                          \
     do {                                                                                              \
@@ -467,8 +472,7 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
                                                         const float *__restrict__ da,
                                                         const float *__restrict__ theta2,
                                                         const float *__restrict__ mu_prev, float *__restrict__ dz_out,
-                                                        const float *__restrict__ x, const float *__restrict__ s_pos,
-                                                        const float *__restrict__ s_neg, float *__restrict__ dc_part,
+                                                        const float *__restrict__ rec, float *__restrict__ dc_part,
                                                         float *__restrict__ d2_part) {
     constexpr int SLOTS = 256 / P;
     __shared__ float g[P], w[P];
@@ -495,9 +499,10 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
         const float mprev = mu_prev[off];
         const float d = mprev > 0.f ? w[j] : 0.f;
         if (dz_out) dz_out[off] += d;
-        cx += x[(size_t)s * N + u] * d;
-        cp += s_pos[u] * d;
-        cn += s_neg[u] * d;
+        const float4 q = ld4(rec + ((size_t)u * S + s) * 4);
+        cx += q.z * d;
+        cp += q.x * d;
+        cn += q.y * d;
         msum += mprev;
     }
     red[0][slot][j] = cx; red[1][slot][j] = cp; red[2][slot][j] = cn; red[3][slot][j] = msum;
@@ -525,17 +530,15 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
 hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                                  const int32_t *colidx,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
-                                 const float *theta2, const float *mu_prev, float *dz_out, const float *x,
-                                 const float *s_pos, const float *s_neg, float *dc_part, float *d2_part) {
+                                 const float *theta2, const float *mu_prev, float *dz_out, const float *rec,
+                                 float *dc_part, float *d2_part) {
     const dim3 grid(kFixSplit, S);
     if (p == 32)
         k_bwd_action_fix<32><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, action, maskT, sc.da, theta2, mu_prev,
-                                                   dz_out, x,
-                                                   s_pos, s_neg, dc_part, d2_part);
+                                                   dz_out, rec, dc_part, d2_part);
     else
         k_bwd_action_fix<64><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, action, maskT, sc.da, theta2, mu_prev,
-                                                   dz_out, x,
-                                                   s_pos, s_neg, dc_part, d2_part);
+                                                   dz_out, rec, dc_part, d2_part);
     return hipGetLastError();
 }
 

@@ -40,21 +40,19 @@ struct MemRow {
 
 // Row (u, s) of the round-1 embedding, recomputed instead of read: mu^0 = 0 makes
 // mu^1_u = relu(theta1 x_u + s+_u q+ + s-_u q-) a function of three scalars per (node, state),
-// kept as info[u] = {s+, s-, x_0 .. x_{S-1}} (row length ni floats).
+// kept as one 16-byte record rec[u][s] = {s+, s-, x, 0}.  An all-zero record gives a zero row.
 struct Mu1Row {
-    const float *__restrict__ info;
-    int ni;
+    const float *__restrict__ rec;
+    int S;
     int s;
     float4 t1, qp, qn;  // theta1, q+, q- at this lane's four columns
     __device__ __forceinline__ float4 operator()(int u) const {
-        const float *r = info + (size_t)u * ni;
-        const float2 spn = *reinterpret_cast<const float2 *>(r);
-        const float xs = r[2 + s];
+        const float4 r = ld4(rec + ((size_t)u * S + s) * 4);
         float4 o;
-        o.x = fmaxf(xs * t1.x + spn.x * qp.x + spn.y * qn.x, 0.f);
-        o.y = fmaxf(xs * t1.y + spn.x * qp.y + spn.y * qn.y, 0.f);
-        o.z = fmaxf(xs * t1.z + spn.x * qp.z + spn.y * qn.z, 0.f);
-        o.w = fmaxf(xs * t1.w + spn.x * qp.w + spn.y * qn.w, 0.f);
+        o.x = fmaxf(r.z * t1.x + r.x * qp.x + r.y * qn.x, 0.f);
+        o.y = fmaxf(r.z * t1.y + r.x * qp.y + r.y * qn.y, 0.f);
+        o.z = fmaxf(r.z * t1.z + r.x * qp.z + r.y * qn.z, 0.f);
+        o.w = fmaxf(r.z * t1.w + r.x * qp.w + r.y * qn.w, 0.f);
         return o;
     }
 };
@@ -202,9 +200,9 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict_
     return total;
 }
 
-// Node mode with the round-1 rows recomputed from info[u] = {s+, s-, x_0 ..} (see Mu1Row).
+// Node mode with the round-1 rows recomputed from the records rec[u][s0 .. s0+15] (see Mu1Row).
 template <int P>
-__device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restrict__ info, int ni, int s0,
+__device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restrict__ rec, int S, int s0,
                                                             const float *__restrict__ theta1,
                                                             const float *__restrict__ qvec,
                                                             const int *__restrict__ colidx, int b, int e, int lane) {
@@ -214,35 +212,32 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
     for (int c = 0; c < NC; ++c) total.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int col = 4 * (lane % LPR);
     const float4 t1 = ld4(theta1 + col), qp = ld4(qvec + col), qn = ld4(qvec + P + col);
-    const int srow = 2 + s0 + lane / LPR;
+    const int srow = s0 + lane / LPR;
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         const int cols = (lane < cnt) ? colidx[base + lane] : 0;
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-        // four neighbours per step: their scalar loads are issued together
+        // four neighbours per step: their records are fetched together
         for (int j = 0; j < cnt; j += 4) {
-            float sp[4], sn[4], xs[4][NC];
+            float4 r[4][NC];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int jj = min(j + k, cnt - 1);   // past the end: re-read the last record, dropped below
-                const float *r = info + (size_t)__builtin_amdgcn_readlane(cols, jj) * ni;
-                sp[k] = r[0];
-                sn[k] = r[1];
+                const int jj = min(j + k, cnt - 1);   // past the end: re-read the last records, dropped below
+                const float *ru = rec + ((size_t)__builtin_amdgcn_readlane(cols, jj) * S + srow) * 4;
 #pragma unroll
-                for (int c = 0; c < NC; ++c) xs[k][c] = r[srow + c * RPI];
+                for (int c = 0; c < NC; ++c) r[k][c] = ld4(ru + (size_t)c * RPI * 4);
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if (j + k < cnt) {
-                    const float bx = sp[k] * qp.x + sn[k] * qn.x, by = sp[k] * qp.y + sn[k] * qn.y;
-                    const float bz = sp[k] * qp.z + sn[k] * qn.z, bw = sp[k] * qp.w + sn[k] * qn.w;
 #pragma unroll
                     for (int c = 0; c < NC; ++c) {
-                        acc.a[c].x += fmaxf(xs[k][c] * t1.x + bx, 0.f);
-                        acc.a[c].y += fmaxf(xs[k][c] * t1.y + by, 0.f);
-                        acc.a[c].z += fmaxf(xs[k][c] * t1.z + bz, 0.f);
-                        acc.a[c].w += fmaxf(xs[k][c] * t1.w + bw, 0.f);
+                        const float4 q = r[k][c];
+                        acc.a[c].x += fmaxf(q.z * t1.x + q.x * qp.x + q.y * qn.x, 0.f);
+                        acc.a[c].y += fmaxf(q.z * t1.y + q.x * qp.y + q.y * qn.y, 0.f);
+                        acc.a[c].z += fmaxf(q.z * t1.z + q.x * qp.z + q.y * qn.z, 0.f);
+                        acc.a[c].w += fmaxf(q.z * t1.w + q.x * qp.w + q.y * qn.w, 0.f);
                     }
                 }
             }

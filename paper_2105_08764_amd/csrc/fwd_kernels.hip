@@ -61,11 +61,14 @@ hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *
 
 // ------------------------------------------------------------------------------------------
 // Round 1: mu^0 = 0 (Alg. 1), so mu^1_v = relu(theta1 x_v + s+_v q+ + s-_v q-): no neighbour sum.
-// One thread per float4 of the [N][S][p] output.
+// One thread per float4 of the [N][S][p] output; the scalars come from the records rec[v][s].
+// x_res != NULL (per-state residual graphs): a row whose node is in that state's solution is an
+// isolated node; its embedding is relu(theta1 x) in the final round and is stored as zero in
+// every earlier round, so that nobody's neighbour sum sees it.
 // ------------------------------------------------------------------------------------------
 template <int P>
-__global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, const float *__restrict__ x,
-                                                const float *__restrict__ s_pos, const float *__restrict__ s_neg,
+__global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, const float *__restrict__ rec,
+                                                const float *__restrict__ x_res, int last,
                                                 const float *__restrict__ theta1, const float *__restrict__ qvec,
                                                 float *__restrict__ mu_out) {
     constexpr int LPR = P / 4;
@@ -73,55 +76,146 @@ __global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, cons
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
         const long r = i / LPR;
         const int c = (int)(i - r * LPR) * 4;
-        const int v = (int)(r / S), s = (int)(r - (long)v * S);
-        const float xs = x[(size_t)s * N + v], sp = s_pos[v], sn = s_neg[v];
+        const float4 q = ld4(rec + r * 4);
+        float xs = q.z;
+        const float sp = q.x, sn = q.y;
+        float keep = 1.f;
+        if (x_res) {
+            const int v = (int)(r / S), s = (int)(r - (long)v * S);
+            const float xo = x_res[(size_t)s * N + v];
+            if (xo != 0.f) { xs = xo; keep = last ? 1.f : 0.f; }
+        }
         const float4 t1 = ld4(theta1 + c), qp = ld4(qvec + c), qn = ld4(qvec + P + c);
         float4 o;
-        o.x = fmaxf(xs * t1.x + sp * qp.x + sn * qn.x, 0.f);
-        o.y = fmaxf(xs * t1.y + sp * qp.y + sn * qn.y, 0.f);
-        o.z = fmaxf(xs * t1.z + sp * qp.z + sn * qn.z, 0.f);
-        o.w = fmaxf(xs * t1.w + sp * qp.w + sn * qn.w, 0.f);
+        o.x = keep * fmaxf(xs * t1.x + sp * qp.x + sn * qn.x, 0.f);
+        o.y = keep * fmaxf(xs * t1.y + sp * qp.y + sn * qn.y, 0.f);
+        o.z = keep * fmaxf(xs * t1.z + sp * qp.z + sn * qn.z, 0.f);
+        o.w = keep * fmaxf(xs * t1.w + sp * qp.w + sn * qn.w, 0.f);
         st4(mu_out + (size_t)r * P + c, o);
     }
 }
 
-hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *x, const float *s_pos, const float *s_neg,
+hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *rec, const float *x_res, bool last,
                          const float *theta1, const float *qvec, float *mu_out) {
     const long n_vrows = (long)N * S;
     if (n_vrows == 0) return hipSuccess;
     const long total = n_vrows * (p / 4);
     const int grid = (int)min((total + 255) / 256, (long)(256 * 32));
-    if (p == 32) k_round1<32><<<grid, 256, 0, st>>>(n_vrows, N, S, x, s_pos, s_neg, theta1, qvec, mu_out);
-    else k_round1<64><<<grid, 256, 0, st>>>(n_vrows, N, S, x, s_pos, s_neg, theta1, qvec, mu_out);
+    if (p == 32) k_round1<32><<<grid, 256, 0, st>>>(n_vrows, N, S, rec, x_res, last ? 1 : 0, theta1, qvec, mu_out);
+    else k_round1<64><<<grid, 256, 0, st>>>(n_vrows, N, S, rec, x_res, last ? 1 : 0, theta1, qvec, mu_out);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
-// Per-node scalars gathered in one place: info[v] = {s+_v, s-_v, x_0[v], .., x_{S-1}[v], pad}
-// (ni floats per node, ni a multiple of 4).  One 16-byte line per neighbour is all the second
-// round needs (see Mu1Row), and the epilogue of every round reads its own row's scalars here.
+// Per-(node, state) scalars gathered in one place: rec[v][s] = {s+_v, s-_v, x_s[v], 0}, 16 bytes.
+// One such record per neighbour is all the second round needs (see Mu1Row), and every kernel
+// reads its own row's scalars here.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const float *__restrict__ x,
+__global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, const float *__restrict__ x,
                                                   const float *__restrict__ s_pos, const float *__restrict__ s_neg,
-                                                  float *__restrict__ info) {
-    const long total = (long)N * ni;
+                                                  float *__restrict__ rec) {
+    const long total = (long)N * S;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
-        const int v = (int)(i / ni), c = (int)(i - (long)v * ni);
-        float o = 0.f;
-        if (c == 0) o = s_pos[v];
-        else if (c == 1) o = s_neg[v];
-        else if (c - 2 < S) o = x[(size_t)(c - 2) * N + v];
-        info[i] = o;
+        const int v = (int)(i / S), s = (int)(i - (long)v * S);
+        st4(rec + i * 4, make_float4(s_pos[v], s_neg[v], x[(size_t)s * N + v], 0.f));
     }
 }
 
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
-                           float *info) {
+                           float *rec) {
     if (N == 0) return hipSuccess;
-    const int ni = nodeinfo_stride(S);
-    const long total = (long)N * ni;
-    k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info);
+    const long total = (long)N * S;
+    k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, x, s_pos, s_neg, rec);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Records for per-state residual graphs (what the paper's Tuples2Graphs builds explicitly, Alg. 4):
+// in state s every edge with an endpoint in that state's solution (x_s != 0) is absent.  So
+//   rec[v][s] = {0, 0, 0, 1}                                   if x_s[v] != 0 (isolated, contributes nothing)
+//   rec[v][s] = {sum max(w,0), sum max(-w,0), x_s[v], 0}        over the neighbours u with x_s[u] == 0, else.
+// Pass 1 writes x and the flag, pass 2 the edge sums of ordinary rows (one thread per (v, s)),
+// pass 3 those of the long rows (one wave per (long row, s)).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_stateinfo_flags(int N, int S, const float *__restrict__ x,
+                                                         float *__restrict__ rec) {
+    const long total = (long)N * S;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int v = (int)(i / S), s = (int)(i - (long)v * S);
+        const float xs = x[(size_t)s * N + v];
+        st4(rec + i * 4, xs != 0.f ? make_float4(0.f, 0.f, 0.f, 1.f) : make_float4(0.f, 0.f, xs, 0.f));
+    }
+}
+
+__global__ __launch_bounds__(256) void k_stateinfo_sums(int N, int S, const int32_t *__restrict__ rowptr,
+                                                        const int32_t *__restrict__ rowend,
+                                                        const int32_t *__restrict__ colidx, const float *__restrict__ w,
+                                                        float *__restrict__ rec) {
+    const long total = (long)N * S;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int v = (int)(i / S), s = (int)(i - (long)v * S);
+        const int b = rowptr[v], e = rowend[v];
+        if (e - b > kHubDegree || rec[i * 4 + 3] != 0.f) continue;   // long rows: pass 3; solution nodes: done
+        double sp = 0.0, sn = 0.0;
+        for (int j = b; j < e; ++j) {
+            if (rec[((size_t)colidx[j] * S + s) * 4 + 3] != 0.f) continue;   // neighbour in the solution
+            const float wj = w ? w[j] : 1.f;
+            sp += (double)fmaxf(wj, 0.f);
+            sn += (double)fmaxf(-wj, 0.f);
+        }
+        rec[i * 4] = (float)sp;
+        rec[i * 4 + 1] = (float)sn;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_stateinfo_hubs(int S, HubTable ht, const int32_t *__restrict__ rowptr,
+                                                        const int32_t *__restrict__ rowend,
+                                                        const int32_t *__restrict__ colidx, const float *__restrict__ w,
+                                                        float *__restrict__ rec) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long items = (long)ht.n_hubs * S;
+    for (long it = (long)blockIdx.x * 4 + wave; it < items; it += (long)gridDim.x * 4) {
+        const int h = (int)(it / S), s = (int)(it - (long)h * S);
+        const int v = ht.hub_rows[h];
+        const int b = rowptr[v], e = rowend[v];
+        const size_t mine = ((size_t)v * S + s) * 4;
+        if (e - b <= kHubDegree || rec[mine + 3] != 0.f) continue;   // wave-uniform
+        double sp = 0.0, sn = 0.0;
+        for (int j = b + lane; j < e; j += 64) {
+            if (rec[((size_t)colidx[j] * S + s) * 4 + 3] != 0.f) continue;
+            const float wj = w ? w[j] : 1.f;
+            sp += (double)fmaxf(wj, 0.f);
+            sn += (double)fmaxf(-wj, 0.f);
+        }
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            sp += __shfl_xor(sp, m);
+            sn += __shfl_xor(sn, m);
+        }
+        if (lane == 0) {
+            rec[mine] = (float)sp;
+            rec[mine + 1] = (float)sn;
+        }
+    }
+}
+
+hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTable &ht, const int32_t *rowptr,
+                                     const int32_t *rowend, const int32_t *colidx, const float *w, const float *x,
+                                     float *rec) {
+    if (N == 0) return hipSuccess;
+    const long total = (long)N * S;
+    const int grid = (int)min((total + 255) / 256, (long)65536);
+    k_stateinfo_flags<<<grid, 256, 0, st>>>(N, S, x, rec);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_stateinfo_sums<<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, w, rec);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ht.n_hubs > 0) {
+        const long items = (long)ht.n_hubs * S;
+        k_stateinfo_hubs<<<(int)min((items + 3) / 4, (long)65536), 256, 0, st>>>(S, ht, rowptr, rowend, colidx, w, rec);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -136,7 +230,7 @@ hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const f
 //         gpart[blockIdx.x][P]: the first stage of the graph sum of Alg. 2 line 4.
 // ------------------------------------------------------------------------------------------
 template <int P, bool NODE, bool MU1, bool GSUM>
-__global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int ni, const int32_t *__restrict__ rowptr,
+__global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const int32_t *__restrict__ rowptr,
                                                     const int32_t *__restrict__ rowend,
                                                     const int32_t *__restrict__ colidx,
                                                     const float *__restrict__ mu_in, float *__restrict__ mu_out,
@@ -144,7 +238,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
                                                     const float *__restrict__ theta1,
                                                     const float *__restrict__ theta2,
                                                     const float *__restrict__ qvec, float *__restrict__ gpart,
-                                                    HubTable ht, const float *__restrict__ hub_sum) {
+                                                    HubTable ht, const float *__restrict__ hub_sum,
+                                                    const float *__restrict__ x_res, int N, int last) {
     using G = Geo<P>;
     __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
     __shared__ __attribute__((aligned(16))) float lds_b[P * G::STRIDE];   // theta2, the B operand
@@ -165,8 +260,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
     }
     Mu1Row mu1;
     if (MU1) {
-        mu1.info = info;
-        mu1.ni = ni;
+        mu1.rec = info;
+        mu1.S = S;
         mu1.s = 0;
         mu1.t1 = ld4(theta1 + 4 * li);
         mu1.qp = ld4(qvec + 4 * li);
@@ -184,10 +279,17 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
         const int s = valid ? r - v * S : 0;
         const int rb = valid ? rowptr[v] : 0;
         const int re = valid ? rowend[v] : 0;
-        const float *myinfo = info + (size_t)v * ni;
-        const float sp = valid ? myinfo[0] : 0.f;
-        const float sn = valid ? myinfo[1] : 0.f;
-        const float xs = valid ? myinfo[2 + s] : 0.f;
+        const float4 mine = valid ? ld4(info + (size_t)r * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float sp = mine.x, sn = mine.y;
+        float xs = mine.z;
+        // Per-state residual graphs: a row whose node is in its state's solution is an isolated node.
+        // Its record is zero (so it adds nothing to its neighbours); here it gets relu(theta1 x) in the
+        // final round and zero before, whatever its (ignored) neighbour sum is.
+        float keep = 1.f, cut = 1.f;     // cut = 0 drops the neighbour term of such a row
+        if (x_res && valid) {
+            const float xo = x_res[(size_t)s * N + v];
+            if (xo != 0.f) { xs = xo; cut = 0.f; keep = last ? 1.f : 0.f; }
+        }
 
         if (NODE) {
             // one node, 16 states: s0 = state of tile row 0
@@ -198,7 +300,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
                 acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
             } else {
-                acc = MU1 ? gather_node_block_mu1<P>(info, ni, s0, theta1, qvec, colidx, b, e, lane)
+                acc = MU1 ? gather_node_block_mu1<P>(info, S, s0, theta1, qvec, colidx, b, e, lane)
                           : gather_node_block<P>(mu_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
             }
             store_node_block<P>(tile, acc, lane);
@@ -243,12 +345,13 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, int n
         for (int rr = 0; rr < 4; ++rr) {
             const int i = 4 * gl + rr;
             const float xi = __shfl(xs, i), spi = __shfl(sp, i), sni = __shfl(sn, i);
+            const float keepi = __shfl(keep, i), cuti = __shfl(cut, i);
             const int ro = r0 + i;
             if (ro < n_vrows) {
                 float *out = mu_out + (size_t)ro * P + jl;
 #pragma unroll
                 for (int cb = 0; cb < G::CB; ++cb) {
-                    const float o = fmaxf(acc[cb][rr] + xi * t1[cb] + spi * qp[cb] + sni * qn[cb], 0.f);
+                    const float o = keepi * fmaxf(cuti * acc[cb][rr] + xi * t1[cb] + spi * qp[cb] + sni * qn[cb], 0.f);
                     out[16 * cb] = o;
                     if (GSUM) csum[cb] += o;
                 }
@@ -282,15 +385,14 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
                                  const int32_t *colidx,
                                  const float *mu_in, float *mu_out, const float *info, const float *theta1,
                                  const float *theta2, const float *qvec, bool from_scalars, float *gpart,
-                                 const HubTable &ht, const float *hub_sum) {
+                                 const HubTable &ht, const float *hub_sum, const float *x_res, bool last) {
     const long n_vrows = (long)N * S;
     const int grid = round_grid(n_vrows);
-    const int ni = nodeinfo_stride(S);
     const bool node = (S % 16) == 0;
 #define S2V_LAUNCH_ROUND(NODE, MU1, GSUM)                                                                         \
-    k_round<P, NODE, MU1, GSUM><<<grid, kThreads, 0, st>>>((int)n_vrows, S, ni, rowptr, rowend, colidx, mu_in, mu_out, \
+    k_round<P, NODE, MU1, GSUM><<<grid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, mu_in, mu_out, \
                                                            info, \
-                                                           theta1, theta2, qvec, gpart, ht, hub_sum)
+                                                           theta1, theta2, qvec, gpart, ht, hub_sum, x_res, N, last ? 1 : 0)
     if (node) {
         if (from_scalars) S2V_LAUNCH_ROUND(true, true, false);
         else S2V_LAUNCH_ROUND(true, false, false);
@@ -309,13 +411,13 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                         const int32_t *colidx, const float *mu_in, float *mu_out, const float *info, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
-                        const float *hub_sum) {
+                        const float *hub_sum, const float *x_res, bool last) {
     if ((long)N * S == 0) return hipSuccess;
     if (p == 32)
         return launch_round_p<32>(st, N, S, rowptr, rowend, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
-                                  gpart, ht, hub_sum);
+                                  gpart, ht, hub_sum, x_res, last);
     return launch_round_p<64>(st, N, S, rowptr, rowend, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
-                              ht, hub_sum);
+                              ht, hub_sum, x_res, last);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -324,7 +426,7 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
 // segment partials of each hub in segment order.
 // ------------------------------------------------------------------------------------------
 template <int P, bool NODE, int SRC>   // SRC: 0 rows in memory, 1 round-1 rows from scalars, 2 relu-mask bits
-__global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTable ht,
+__global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
                                                           const int32_t *__restrict__ rowend,
                                                           const int32_t *__restrict__ colidx,
                                                           const float *__restrict__ src,
@@ -345,7 +447,7 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTabl
         if (NODE) {
             const int s0 = blk * 16;
             NodeAcc<P> acc;
-            if (SRC == 1) acc = gather_node_block_mu1<P>(info, ni, s0, theta1, qvec, colidx, b, e, lane);
+            if (SRC == 1) acc = gather_node_block_mu1<P>(info, S, s0, theta1, qvec, colidx, b, e, lane);
             else if (SRC == 2) acc = gather_node_block_bits<P>(mask, S, s0, colidx, b, e, lane);
             else acc = gather_node_block<P>(src, (size_t)S * P, (size_t)s0 * P, colidx, b, e, lane);
             float *out = partial + ((size_t)seg * S + s0) * P;
@@ -356,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, int ni, HubTabl
             const int cols = (lane < min(64, e - b)) ? colidx[b + lane] : 0;
             float4 a;
             if (SRC == 1) {
-                Mu1Row mu1{info, ni, s, ld4(theta1 + 4 * li), ld4(qvec + 4 * li), ld4(qvec + P + 4 * li)};
+                Mu1Row mu1{info, S, s, ld4(theta1 + 4 * li), ld4(qvec + 4 * li), ld4(qvec + P + 4 * li)};
                 a = gather_row_sum<P>(mu1, colidx, b, e, cols, lane);
             } else if (SRC == 2) {
                 const BitsRow bits{mask, S, s, 4 * li};
@@ -388,11 +490,10 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
     if (ht.n_hubs == 0) return hipSuccess;
     const bool node = (S % 16) == 0;
     const int kind = mask ? 2 : (src ? 0 : 1);
-    const int ni = nodeinfo_stride(S);
     const long items = (long)ht.n_segs * (node ? S / 16 : S);
     const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
 #define S2V_LAUNCH_HUB(PP, NODE, SRC) \
-    k_hub_partial<PP, NODE, SRC><<<grid, kThreads, 0, st>>>(S, ni, ht, rowend, colidx, src, info, theta1, qvec, mask, \
+    k_hub_partial<PP, NODE, SRC><<<grid, kThreads, 0, st>>>(S, ht, rowend, colidx, src, info, theta1, qvec, mask, \
                                                             partial)
 #define S2V_LAUNCH_HUB_P(PP)                                                                           \
     do {                                                                                               \

@@ -47,10 +47,14 @@ struct ChunkTable {            // device pointers into the prepared head of the 
 hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const float *w,
                             float *s_pos, float *s_neg);
 hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec);
-hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *x, const float *s_pos, const float *s_neg,
+// x_res != NULL in the round launchers: per-state residual graphs (x_res is the caller's x [S][N]).
+hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *rec, const float *x_res, bool last,
                          const float *theta1, const float *qvec, float *mu_out);
-// floats per node of the scalar table {s+, s-, x_0 .. x_{S-1}}, padded to a multiple of 4
-inline int nodeinfo_stride(int S) { return (S + 2 + 3) / 4 * 4; }
+hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTable &ht, const int32_t *rowptr,
+                                     const int32_t *rowend, const int32_t *colidx, const float *w, const float *x,
+                                     float *rec);
+// floats per node of the scalar records rec[v][s] = {s+, s-, x_s, 0}
+inline int nodeinfo_stride(int S) { return 4 * S; }
 // upper bound of the embedding-round grid (also the number of partial rows of its fused graph sum)
 constexpr int kRoundGridMax = 256 * 16;
 int round_grid(long n_vrows);
@@ -66,7 +70,7 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                         const int32_t *colidx, const float *mu_in, float *mu_out, const float *info, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
-                        const float *hub_sum);
+                        const float *hub_sum, const float *x_res, bool last);
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum);
 hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu,
                        float *partial /*[n_chunks][S*p]*/, float *gsum /*[S][G][p]*/);
@@ -116,27 +120,28 @@ struct BwdScratch {
     float *d2_part;     // [d2_rows][p][p]   partial sums of G (x) mu
     float *dvec;        // [3][p] reduced dtheta1, dq+, dq-
     float *red_tmp;     // [ceil(max rows / 64)][max(3p, p*p)] second level of the final reductions
+    float *rec;         // [N][S][4] per-(node, state) scalar records {s+, s-, x, flag}
 };
 hipError_t launch_bwd_head(hipStream_t st, int p, int N, int S, int G, const int32_t *graph_off, const float *theta5,
                            const float *theta6, const float *theta7, const float *muT, const float *gsum,
                            const int32_t *action, const float *target, const BwdScratch &sc, float *q_pred);
 hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch &sc, float *loss, float *d5, float *d6,
                                   float *d7);
-hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const float *x, const float *s_pos,
-                            const float *s_neg, const int32_t *action, const BwdScratch &sc,
-                            unsigned long long *mask /*[N][S] or NULL*/, float *dc_part /*[kBwdHeadGrid][3][p]*/);
+hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const float *rec, const float *x_res,
+                            const int32_t *action, const BwdScratch &sc, unsigned long long *mask /*[N][S] or NULL*/,
+                            float *dc_part /*[kBwdHeadGrid][3][p]*/);
 // maskT != NULL selects the first reversed round (t = T), which reads relu-mask words instead of dz_in.
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                             const int32_t *colidx, const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
-                            const float *mu_prev, float *dz_out /*may be NULL*/, const float *x, const float *s_pos,
-                            const float *s_neg, const float *theta2, float *dc_part /*[kBwdGrid][3][p]*/,
-                            float *d2_part /*[kBwdGrid][p][p]*/, const HubTable &ht, const float *hub_sum);
+                            const float *mu_prev, float *dz_out /*may be NULL*/, const float *rec, const float *theta2,
+                            float *dc_part /*[kBwdGrid][3][p]*/, float *d2_part /*[kBwdGrid][p][p]*/,
+                            const HubTable &ht, const float *hub_sum);
 hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                                  const int32_t *colidx,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
                                  const float *theta2, const float *mu_prev, float *dz_out /*may be NULL*/,
-                                 const float *x, const float *s_pos, const float *s_neg,
-                                 float *dc_part /*[S*kFixSplit][3][p]*/, float *d2_part /*[S*kFixSplit][p][p]*/);
+                                 const float *rec, float *dc_part /*[S*kFixSplit][3][p]*/,
+                                 float *d2_part /*[S*kFixSplit][p][p]*/);
 hipError_t launch_bwd_finish(hipStream_t st, int p, int dc_rows, int d2_rows, const BwdScratch &sc, const float *theta3,
                              const float *theta4, float *d1, float *d2, float *d3, float *d4);
 hipError_t launch_sgd(hipStream_t st, int p, float *const theta[7], const float *const grad[7], float lr);

@@ -10,7 +10,8 @@ import synth_inputs as si
 class Device:
     """One context + uploaded graph + workspace, reused across calls of a test."""
 
-    def __init__(self, g: si.Graph, p: int, T: int, S: int = 1, k_max: int = 1, training: bool = False):
+    def __init__(self, g: si.Graph, p: int, T: int, S: int = 1, k_max: int = 1, training: bool = False,
+                 state_residual: bool = False):
         import torch
 
         import paper_2105_08764_amd as s2v
@@ -25,6 +26,7 @@ class Device:
             torch.from_numpy(g.colidx).to(dev),
             None if g.w is None else torch.from_numpy(g.w).to(dev),
             None if g.graph_off is None else torch.from_numpy(g.graph_off).to(dev),
+            state_residual=state_residual,
         )
         nbytes = self.ctx.s2v_workspace_bytes(self.graph, p, T, S, k_max, training)
         self.ws_bytes = nbytes
@@ -91,7 +93,20 @@ class Device:
 FLOOR_FRAC = 1e-2
 
 
-def rel_err(got: np.ndarray, ref: np.ndarray, floor_frac: float = FLOOR_FRAC, whole: bool = False) -> float:
+def q_term_scale(theta: dict, gsum: np.ndarray, mu: np.ndarray) -> float:
+    """Magnitude of the summed terms of Eq. 2 for one state of one graph: sum_i |theta5_i| * relu(.)_i,
+    the graph half plus the largest node half.  Q is a signed sum of 2p such terms and can be a
+    hundred times smaller than they are; its float32 rounding error follows the terms, so a parity
+    check of Q on inputs where that happens floors its denominator with this scale."""
+    th = {k: np.asarray(v, dtype=np.float64) for k, v in theta.items()}
+    p = th["theta1"].shape[0]
+    a = np.abs(th["theta5"][:p]) @ np.maximum(th["theta6"] @ gsum, 0.0)
+    b = np.maximum(mu @ th["theta7"].T, 0.0) @ np.abs(th["theta5"][p:])
+    return float(a + (b.max() if b.size else 0.0))
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray, floor_frac: float = FLOOR_FRAC, whole: bool = False,
+            scale: float = 0.0) -> float:
     """max_i |got_i - ref_i| / max(|ref_i|, floor_frac * max|ref| over the last axis).
     whole=True takes the maximum over the whole array instead (gradient tensors: every entry
     is a sum over the same nodes, states and rounds, so the scale is common to the tensor).
@@ -109,6 +124,7 @@ def rel_err(got: np.ndarray, ref: np.ndarray, floor_frac: float = FLOOR_FRAC, wh
         return 0.0
     assert np.isfinite(got).all(), "non-finite values in the GPU result"
     rowmax = np.abs(ref).max() if whole else np.abs(ref).max(axis=-1, keepdims=True)
+    rowmax = np.maximum(rowmax, scale)       # scale: magnitude of the terms the entries were summed from
     den = np.maximum(np.abs(ref), np.maximum(floor_frac * rowmax, 1e-30))
     return float(np.max(np.abs(got - ref) / den))
 
@@ -117,6 +133,31 @@ def oracle_forward(oracle, g: si.Graph, theta, x_row, T):
     mu = oracle.embed(g.rowptr, g.colidx, g.w, theta, x_row, T)
     gsum, q = oracle.q_scores(g.graph_off, theta, mu)
     return mu, gsum, q
+
+
+def oracle_per_state_residual(oracle, g: si.Graph, theta, x, T, action=None, target=None):
+    """Alg. 4's minibatch on per-state sub-graphs, composed from the oracle's own pieces: state b is
+    embedded and scored on residual_graph(x[b]) as a batch of one; with action/target the loss and the
+    gradients are the means over the states.  Returns dict(mu [N][S][p], gsum [S][G][p], q [S][N])
+    and, when training, (loss, q_pred [S], grads)."""
+    S = x.shape[0]
+    mus, gsums, qs, losses, qps, gsumd = [], [], [], [], [], None
+    for b in range(S):
+        rp, ci, w = oracle.residual_graph(g.rowptr, g.colidx, g.w, x[b])
+        mu = oracle.embed(rp, ci, w, theta, x[b], T)
+        gs, q = oracle.q_scores(g.graph_off, theta, mu)
+        mus.append(mu.reshape(g.n, -1))
+        gsums.append(gs.reshape(g.n_graphs, -1))
+        qs.append(q.reshape(-1))
+        if action is not None:
+            lb, qb, gb = oracle.loss_grad(rp, ci, w, g.graph_off, theta, x[b], T, action[b:b + 1], target[b:b + 1])
+            losses.append(lb)
+            qps.append(qb[0])
+            gsumd = gb if gsumd is None else {k: gsumd[k] + gb[k] for k in gb}
+    fwd = dict(mu=np.stack(mus, axis=1), gsum=np.stack(gsums, axis=0), q=np.stack(qs, axis=0))
+    if action is None:
+        return fwd
+    return fwd, (float(np.mean(losses)), np.array(qps), {k: v / S for k, v in gsumd.items()})
 
 
 def check_selection_with_margin(idx_gpu, cnt_gpu, q_oracle, cand_mask, k, band_rel=1e-4):
