@@ -60,8 +60,9 @@ def _th(theta: dict):
     return [_f64(theta[k]) for k in THETA_NAMES]
 
 
-def embed(rowptr, colidx, w, theta: dict, x, T: int, history: bool = False):
-    """mu^T as [n][p] float64 (and mu^1..mu^T as [T][n][p] when history is set)."""
+def embed(rowptr, colidx, w, theta: dict, x, T: int, history: bool = False, weighted: bool = False):
+    """mu^T as [n][p] float64 (and mu^1..mu^T as [T][n][p] when history is set).
+    weighted: the neighbour sum of Eq. 1 weights neighbour u of v by w(v, u)."""
     lib = _load()
     rowptr, colidx = _i32(rowptr), _i32(colidx)
     n = rowptr.shape[0] - 1
@@ -73,7 +74,8 @@ def embed(rowptr, colidx, w, theta: dict, x, T: int, history: bool = False):
     mu = np.zeros((n, p), dtype=np.float64)
     hist = np.zeros((T, n, p), dtype=np.float64) if history else None
     rc = lib.oracle_embed(
-        ctypes.c_int32(n), _ptr(rowptr), _ptr(colidx), _ptr(wd), ctypes.c_int32(p), ctypes.c_int32(T),
+        ctypes.c_int32(n), _ptr(rowptr), _ptr(colidx), _ptr(wd), ctypes.c_int32(int(bool(weighted))),
+        ctypes.c_int32(p), ctypes.c_int32(T),
         _ptr(th[0]), _ptr(th[1]), _ptr(th[2]), _ptr(th[3]), _ptr(xd), _ptr(mu), _ptr(hist),
     )
     assert rc == 0
@@ -114,7 +116,7 @@ def select(graph_off, q, x, cand, k: int):
     return idx, val, cnt
 
 
-def loss_grad(rowptr, colidx, w, graph_off, theta: dict, x, T: int, action, target):
+def loss_grad(rowptr, colidx, w, graph_off, theta: dict, x, T: int, action, target, weighted: bool = False):
     """(loss, q_pred [S], grads dict) for the squared loss averaged over the S states."""
     lib = _load()
     rowptr, colidx = _i32(rowptr), _i32(colidx)
@@ -133,7 +135,8 @@ def loss_grad(rowptr, colidx, w, graph_off, theta: dict, x, T: int, action, targ
     qp = np.zeros(S, dtype=np.float64)
     grads = [np.zeros_like(t) for t in th]
     rc = lib.oracle_loss_grad(
-        ctypes.c_int32(n), _ptr(rowptr), _ptr(colidx), _ptr(wd), ctypes.c_int32(G), _ptr(go),
+        ctypes.c_int32(n), _ptr(rowptr), _ptr(colidx), _ptr(wd), ctypes.c_int32(int(bool(weighted))),
+        ctypes.c_int32(G), _ptr(go),
         ctypes.c_int32(p), ctypes.c_int32(T), *[_ptr(t) for t in th], ctypes.c_int32(S), _ptr(xd),
         _ptr(act), _ptr(tgt), _ptr(loss), _ptr(qp), *[_ptr(g) for g in grads],
     )
@@ -180,7 +183,8 @@ def adaptive_d(n_candidates: int, n_nodes: int) -> int:
     return 1
 
 
-def mvc_inference(rowptr, colidx, w, graph_off, theta: dict, x, T: int, adaptive: bool, max_steps: int):
+def mvc_inference(rowptr, colidx, w, graph_off, theta: dict, x, T: int, adaptive: bool, max_steps: int,
+                  weighted: bool = False):
     """Alg. 3 for minimum vertex cover, one state: repeat {embed on the remaining graph, score,
     add the d best candidates to the solution} until no edge remains.  Candidates are the nodes
     outside the solution that still have an edge.  Returns (x, steps, trace) with trace a list of
@@ -198,7 +202,7 @@ def mvc_inference(rowptr, colidx, w, graph_off, theta: dict, x, T: int, adaptive
             break
         cand = ((x == 0) & (np.diff(rp) > 0)).astype(np.uint8)
         d = adaptive_d(int(cand.sum()), n) if (adaptive and G == 1) else 1
-        mu = embed(rp, ci, ww, theta, x, T)
+        mu = embed(rp, ci, ww, theta, x, T, weighted=weighted)
         _, q = q_scores(go, theta, mu)
         idx, _, cnt = select(go, q, x, cand, d)
         chosen = np.concatenate([idx[b, : cnt[b]] for b in range(G)])

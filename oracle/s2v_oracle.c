@@ -51,9 +51,12 @@ static void matvec_t(int p, const double *M, const double *v, double *y) {
  *   mu_next[v] = relu(theta1 * x_v + theta2 * sum_{u in N(v)} mu[u]
  *                     + theta3 * sum_{u in N(v)} relu(theta4 * w(v,u)))
  * N(v) is exactly the stored entries of CSR row v.  w == NULL means all weights 1.
+ * weighted != 0 takes the other reading of the aggregation step of Alg. 1 (a product with the
+ * adjacency matrix that holds the weights): the second term becomes
+ *   theta2 * sum_{u in N(v)} w(v,u) * mu[u].
  * If a_out / e_out are non-NULL the two neighbour sums are also stored ([n][p]).
  */
-static void embed_round(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int p,
+static void embed_round(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int weighted, int p,
                         const double *th1, const double *th2, const double *th3, const double *th4,
                         const double *x, const double *mu, double *mu_next, double *a_out, double *e_out) {
 #pragma omp parallel
@@ -66,8 +69,9 @@ static void embed_round(int32_t n, const int32_t *rowptr, const int32_t *colidx,
             for (int32_t j = rowptr[v]; j < rowptr[v + 1]; ++j) {
                 const double *mu_u = mu + (size_t)colidx[j] * p;
                 double wj = w ? w[j] : 1.0;
+                double cj = weighted ? wj : 1.0;
                 for (int i = 0; i < p; ++i) {
-                    a[i] += mu_u[i];
+                    a[i] += cj * mu_u[i];
                     e[i] += relu(th4[i] * wj);
                 }
             }
@@ -85,7 +89,8 @@ static void embed_round(int32_t n, const int32_t *rowptr, const int32_t *colidx,
  * Alg. 1 / Eq. (1): T rounds from mu^0 = 0.  mu_out is [n][p].  If mu_hist is
  * non-NULL it receives mu^1..mu^T as [T][n][p].
  */
-int oracle_embed(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int32_t p, int32_t T,
+int oracle_embed(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int32_t weighted,
+                 int32_t p, int32_t T,
                  const double *th1, const double *th2, const double *th3, const double *th4, const double *x,
                  double *mu_out, double *mu_hist) {
     size_t np_ = (size_t)n * p;
@@ -93,7 +98,7 @@ int oracle_embed(int32_t n, const int32_t *rowptr, const int32_t *colidx, const 
     double *nxt = (double *)calloc(np_ ? np_ : 1, sizeof(double));
     if (!cur || !nxt) { free(cur); free(nxt); return -1; }
     for (int t = 0; t < T; ++t) {
-        embed_round(n, rowptr, colidx, w, p, th1, th2, th3, th4, x, cur, nxt, NULL, NULL);
+        embed_round(n, rowptr, colidx, w, weighted, p, th1, th2, th3, th4, x, cur, nxt, NULL, NULL);
         if (mu_hist) memcpy(mu_hist + (size_t)t * np_, nxt, sizeof(double) * np_);
         double *tmp = cur; cur = nxt; nxt = tmp;
     }
@@ -171,10 +176,10 @@ int oracle_select(int32_t n, int32_t G, const int32_t *graph_off, const double *
     return 0;
 }
 
-/* Transpose of a CSR pattern by counting sort; pos_t[j'] is the entry of the original that
- * landed at j' (so per-entry data such as weights can follow).  No symmetry is assumed. */
-static void csr_transpose(int32_t n, const int32_t *rowptr, const int32_t *colidx, int32_t *rowptr_t,
-                          int32_t *colidx_t) {
+/* Transpose of a CSR matrix by counting sort; the values w (NULL: none) follow their entries into
+ * w_t.  No symmetry is assumed. */
+static void csr_transpose(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w,
+                          int32_t *rowptr_t, int32_t *colidx_t, double *w_t) {
     int32_t nnz = rowptr[n];
     for (int32_t v = 0; v <= n; ++v) rowptr_t[v] = 0;
     for (int32_t j = 0; j < nnz; ++j) rowptr_t[colidx[j] + 1]++;
@@ -182,7 +187,11 @@ static void csr_transpose(int32_t n, const int32_t *rowptr, const int32_t *colid
     int32_t *fill = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n + 1));
     memcpy(fill, rowptr_t, sizeof(int32_t) * (size_t)(n + 1));
     for (int32_t v = 0; v < n; ++v)
-        for (int32_t j = rowptr[v]; j < rowptr[v + 1]; ++j) colidx_t[fill[colidx[j]]++] = v;
+        for (int32_t j = rowptr[v]; j < rowptr[v + 1]; ++j) {
+            int32_t at = fill[colidx[j]]++;
+            colidx_t[at] = v;
+            if (w && w_t) w_t[at] = w[j];
+        }
     free(fill);
 }
 
@@ -193,11 +202,13 @@ static void csr_transpose(int32_t n, const int32_t *rowptr, const int32_t *colid
  * with Q^{(b)} computed from x[b][.] by T rounds of Eq. (1) and Eq. (2).
  * Gradients are taken by reverse-mode differentiation of exactly those formulas;
  * relu'(0) = 0.  The adjoint of the neighbour sum uses the explicit transpose of
- * the CSR pattern.  States are processed one at a time.
+ * the CSR matrix (with its weights when weighted != 0, see embed_round).  States are
+ * processed one at a time.
  * Outputs: loss_out[1], q_out[S] (the predicted Q of each action), and d1..d7 with
  * the shapes of theta1..theta7 (overwritten).
  */
-int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int32_t G,
+int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int32_t weighted,
+                     int32_t G,
                      const int32_t *graph_off, int32_t p, int32_t T, const double *th1, const double *th2,
                      const double *th3, const double *th4, const double *th5, const double *th6,
                      const double *th7, int32_t S, const double *x, const int32_t *action,
@@ -214,7 +225,9 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
 
     int32_t *rowptr_t = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n + 1));
     int32_t *colidx_t = (int32_t *)malloc(sizeof(int32_t) * (size_t)(nnz > 0 ? nnz : 1));
-    csr_transpose(n, rowptr, colidx, rowptr_t, colidx_t);
+    if (!w) weighted = 0; /* all weights 1: both readings coincide */
+    double *w_t = weighted ? (double *)malloc(sizeof(double) * (size_t)(nnz > 0 ? nnz : 1)) : NULL;
+    csr_transpose(n, rowptr, colidx, w, rowptr_t, colidx_t, w_t);
 
     /* mu[t] for t = 0..T, the two neighbour sums of the round that produced mu[t] */
     double *mu = (double *)calloc((size_t)(T + 1) * np_ + 1, sizeof(double));
@@ -231,7 +244,7 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
         const double *xb = x + (size_t)b * n;
         memset(mu, 0, sizeof(double) * np_);
         for (int t = 1; t <= T; ++t)
-            embed_round(n, rowptr, colidx, w, p, th1, th2, th3, th4, xb, mu + (size_t)(t - 1) * np_,
+            embed_round(n, rowptr, colidx, w, weighted, p, th1, th2, th3, th4, xb, mu + (size_t)(t - 1) * np_,
                         mu + (size_t)t * np_, asum + (size_t)t * np_, esum);
         const double *muT = mu + (size_t)T * np_;
         int32_t act = action[b];
@@ -318,20 +331,22 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
                 }
                 free(loc);
             }
-            /* adjoint of a_v = sum_{u in row v} mu[u]:  dmu_prev[u] = sum_{v : u in row v} da[v] */
+            /* adjoint of a_v = sum_{u in row v} c(v,u) mu[u], c = 1 or w:
+             * dmu_prev[u] = sum_{v : u in row v} c(v,u) da[v] */
 #pragma omp parallel for schedule(dynamic, 256)
             for (int32_t u = 0; u < n; ++u) {
                 double *out = dmu + (size_t)u * p;
                 for (int i = 0; i < p; ++i) out[i] = 0.0;
                 for (int32_t j = rowptr_t[u]; j < rowptr_t[u + 1]; ++j) {
                     const double *src = da + (size_t)colidx_t[j] * p;
-                    for (int i = 0; i < p; ++i) out[i] += src[i];
+                    double cj = weighted ? w_t[j] : 1.0;
+                    for (int i = 0; i < p; ++i) out[i] += cj * src[i];
                 }
             }
         }
     }
     *loss_out = loss;
-    free(mu); free(asum); free(esum); free(dmu); free(da); free(vec); free(rowptr_t); free(colidx_t);
+    free(mu); free(asum); free(esum); free(dmu); free(da); free(vec); free(rowptr_t); free(colidx_t); free(w_t);
     return 0;
 }
 

@@ -16,8 +16,10 @@ def edge_term(adj, wm, th4):
     return np.einsum("vu,vuk->vk", adj, relu(wm[:, :, None] * th4[None, None, :]))
 
 
-def embed_dense(adj, wm, th, x, T, history=False):
-    """T rounds of Eq. (1) from a zero embedding; rows of MU are nodes."""
+def embed_dense(adj, wm, th, x, T, history=False, agg=None):
+    """T rounds of Eq. (1) from a zero embedding; rows of MU are nodes.  agg is the matrix of the
+    neighbour sum: the 0/1 adjacency (default, Eq. 1 as printed) or the weighted adjacency."""
+    agg = adj if agg is None else agg
     th = {k: np.asarray(v, dtype=np.float64) for k, v in th.items()}
     n = adj.shape[0]
     p = th["theta1"].shape[0]
@@ -25,7 +27,7 @@ def embed_dense(adj, wm, th, x, T, history=False):
     const = np.outer(x, th["theta1"]) + edge_term(adj, wm, th["theta4"]) @ th["theta3"].T
     hist = []
     for _ in range(T):
-        mu = relu(const + (adj @ mu) @ th["theta2"].T)
+        mu = relu(const + (agg @ mu) @ th["theta2"].T)
         hist.append(mu)
     return (mu, hist) if history else mu
 
@@ -40,10 +42,11 @@ def q_dense(th, mu):
     return qa + qb
 
 
-def loss_torch(adj, wm, th_t, x_states, T, action, target):
+def loss_torch(adj, wm, th_t, x_states, T, action, target, agg=None):
     """Squared loss averaged over states, in torch float64 on dense matrices (for autograd)."""
     import torch
 
+    agg = adj if agg is None else agg
     p = th_t["theta1"].shape[0]
     total = 0.0
     S = x_states.shape[0]
@@ -52,7 +55,7 @@ def loss_torch(adj, wm, th_t, x_states, T, action, target):
         const = torch.outer(x_states[b], th_t["theta1"]) + e @ th_t["theta3"].T
         mu = torch.zeros(adj.shape[0], p, dtype=torch.float64)
         for _ in range(T):
-            mu = torch.relu(const + (adj @ mu) @ th_t["theta2"].T)
+            mu = torch.relu(const + (agg @ mu) @ th_t["theta2"].T)
         g = mu.sum(dim=0)
         q = th_t["theta5"][:p] @ torch.relu(th_t["theta6"] @ g) + th_t["theta5"][p:] @ torch.relu(
             th_t["theta7"] @ mu[action[b]]

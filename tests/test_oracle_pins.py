@@ -459,3 +459,61 @@ def test_q_target_special_cases(oracle_mod):
     cand[:, 1] = 1
     t = oracle_mod.q_target(g.graph_off, q, x, cand, np.zeros(S, np.int32), reward, 0.5)
     np.testing.assert_allclose(t, reward + 0.5 * q[:, 1], rtol=0, atol=0)
+
+
+# ---- weighted neighbour sum: the other reading of the aggregation step of Alg. 1 -----------------
+
+@pytest.mark.parametrize("n,prob,seed", [(8, 0.5, 1), (23, 0.3, 2), (64, 0.2, 3)])
+def test_weighted_sum_against_dense_weighted_adjacency(oracle_mod, n, prob, seed):
+    # Alg. 1 multiplies the embeddings by the adjacency matrix; with the weights stored in it the
+    # neighbour sum is W @ mu.  Dense brute force with that matrix, edge term unchanged.
+    p, T = 7, 4
+    th = rand_theta(p, 40 + seed)
+    g = si.erdos_renyi_gnp(n, prob, seed)
+    g.w = si.signed_edge_weights(g, seed, 1.5)
+    x = np.random.default_rng(seed).normal(size=n)
+    adj, wm = si.dense_adjacency(g), si.dense_weights(g)
+    mu, hist = oracle_mod.embed(g.rowptr, g.colidx, g.w, th, x, T, history=True, weighted=True)
+    want, want_hist = dr.embed_dense(adj, wm, th, x, T, history=True, agg=adj * wm)
+    for t in range(T):
+        np.testing.assert_allclose(hist[t], want_hist[t], rtol=1e-11, atol=1e-13)
+    plain = oracle_mod.embed(g.rowptr, g.colidx, g.w, th, x, T)
+    assert np.abs(mu - plain).max() > 1e-3          # the two readings really differ on these inputs
+
+
+def test_weighted_sum_special_weights(oracle_mod):
+    p, T = 5, 3
+    th = rand_theta(p, 61)
+    g = si.erdos_renyi_gnp(30, 0.2, 6)
+    x = np.random.default_rng(6).normal(size=g.n)
+    # all weights 1 (given or implied): both readings coincide exactly
+    ones = np.ones(g.colidx.shape[0])
+    a = oracle_mod.embed(g.rowptr, g.colidx, ones, th, x, T, weighted=True)
+    assert np.array_equal(a, oracle_mod.embed(g.rowptr, g.colidx, ones, th, x, T))
+    assert np.array_equal(a, oracle_mod.embed(g.rowptr, g.colidx, None, th, x, T, weighted=True))
+    # all weights c: the weighted sum is c times the plain one, i.e. the plain reading with c * theta2
+    c = 2.5
+    cw = np.full(g.colidx.shape[0], c)
+    th_c = dict(th)
+    th_c["theta2"] = th["theta2"].astype(np.float64) * c
+    np.testing.assert_allclose(oracle_mod.embed(g.rowptr, g.colidx, cw, th, x, T, weighted=True),
+                               oracle_mod.embed(g.rowptr, g.colidx, cw, th_c, x, T), rtol=1e-13, atol=1e-15)
+
+
+def test_weighted_sum_gradient_vs_torch_autograd_dense(oracle_mod):
+    torch = pytest.importorskip("torch")
+    p, T = 4, 4
+    g, x, action, target = _small_training_case(35)
+    th = {k: v.astype(np.float64) for k, v in rand_theta(p, 82, std=0.4).items()}
+    loss, _, grads = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, None, th, x, T, action, target, weighted=True)
+    th_t = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in th.items()}
+    adj = torch.tensor(si.dense_adjacency(g))
+    wm = torch.tensor(si.dense_weights(g))
+    lt = dr.loss_torch(adj, wm, th_t, torch.tensor(x), T, action, torch.tensor(target), agg=adj * wm)
+    lt.backward()
+    assert abs(float(lt) - loss) < 1e-12 * max(1.0, loss)
+    for name in si.THETA_NAMES:
+        assert np.abs(grads[name]).max() > 0, name
+        np.testing.assert_allclose(grads[name], th_t[name].grad.numpy(), rtol=1e-10, atol=1e-13, err_msg=name)
+    plain = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, None, th, x, T, action, target)[2]
+    assert np.abs(plain["theta2"] - grads["theta2"]).max() > 1e-6
