@@ -105,7 +105,32 @@ def bench_inference(args, s2v, torch):
     log(f"[bench] inference {ms:.3f} ms/step; round 2 (from scalars) {ms_r2 / max(n_r2, 1):.3f} ms; "
         f"gather round {round_ms:.3f} ms x {n_round}; "
         f"{achieved:.0f} GB/s algorithmic; prepare {prepare_ms:.1f} ms; peak {peak_mb:.0f} MiB")
+    # the same step with the weighted neighbour sum (the other reading of Alg. 1's aggregation):
+    # each round also reads the 4-byte weight of every stored entry
+    graph_w = s2v.Graph(graph.rowptr, graph.colidx, graph.w, graph.graph_off, weighted_sum=True)
+
+    def step_w():
+        ctx.s2v_embed_fwd(graph_w, prm, x, T, 1, mu, None, gsum, ws)
+        ctx.s2v_q_score(graph_w, prm, mu, gsum, 1, q, ws)
+        ctx.s2v_select_topk(graph_w, q[0], x[0], None, k, idx, val, cnt, ws)
+
+    step_w()
+    torch.cuda.synchronize()
+    ctx.s2v_profile_begin(3 * (T - 1) + 4)
+    t0 = time.perf_counter()
+    for _ in range(3):
+        step_w()
+    torch.cuda.synchronize()
+    ms_w = (time.perf_counter() - t0) * 1e3 / 3
+    (n_round_w, ms_round_w), _, _ = ctx.s2v_profile_end()
+    round_w_ms = ms_round_w / max(n_round_w, 1)
+    log(f"[bench] weighted neighbour sum: {ms_w:.3f} ms/step, gather round {round_w_ms:.3f} ms "
+        f"({(alg + 4 * g.nnz) / (round_w_ms * 1e-3) / 1e9:.0f} GB/s algorithmic)")
+    step()      # leave the buffers holding the plain reading's result
+    torch.cuda.synchronize()
     out = dict(
+        weighted_sum=dict(ms_per_step=ms_w, round_ms=round_w_ms,
+                          round_gbs=(alg + 4 * g.nnz) / (round_w_ms * 1e-3) / 1e9),
         ms=ms, prepare_ms=prepare_ms, peak_device_mib=peak_mb, n=N, nnz=g.nnz, k=k, p=p, T=T,
         round_ms=round_ms, round_launches=n_round, round2_ms=ms_r2 / max(n_r2, 1), alg_bytes=alg, achieved_gbs=achieved,
         selected_count=int(cnt.item()), first_selected=int(idx[0, 0].item()),
@@ -426,6 +451,7 @@ def main():
         },
         "cpu_baseline": cpu,
         "round2_from_scalars_ms": round(inf["round2_ms"], 4),
+        "weighted_sum_reading": inf["weighted_sum"],
         "prepare_ms": round(inf["prepare_ms"], 2),
         "peak_device_mib": round(inf["peak_device_mib"], 1),
         "training": train,

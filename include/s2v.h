@@ -81,6 +81,11 @@ typedef struct {
                                  (the sub-graphs the paper's Tuples2Graphs rebuilds for a training minibatch, Alg. 4);
                                  such nodes stay as isolated nodes.  Nothing is copied or edited: the states share
                                  this CSR.  Zero: all states use the stored graph as it is. */
+    int32_t weighted_sum;     /* non-zero: the neighbour sum of Eq. 1 (second term) weights neighbour u of v by w(u, v),
+                                 i.e. the aggregation step of Alg. 1 read as a product with the weighted adjacency
+                                 matrix.  Zero (the default reading, Eq. 1 as printed): plain sum over neighbours.
+                                 The edge term (third term of Eq. 1) uses w in both cases.  Applies to
+                                 s2v_embed_fwd, s2v_embed_bwd and s2v_mvc_inference.  Needs w(u, v) == w(v, u). */
 } s2v_graph;
 
 /* The seven parameter tensors (device pointers), also used for their gradients. */

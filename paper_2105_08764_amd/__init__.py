@@ -49,6 +49,7 @@ class CGraph(ctypes.Structure):
         ("graph_off", ctypes.c_void_p),
         ("row_end", ctypes.c_void_p),
         ("state_residual", ctypes.c_int32),
+        ("weighted_sum", ctypes.c_int32),
     ]
 
 
@@ -112,7 +113,7 @@ def _want(t, dtype, what):
 class Graph:
     """Device-side CSR graph (or block-diagonal batch); keeps the tensors alive."""
 
-    def __init__(self, rowptr, colidx, w=None, graph_off=None, row_end=None, state_residual=False):
+    def __init__(self, rowptr, colidx, w=None, graph_off=None, row_end=None, state_residual=False, weighted_sum=False):
         _want(row_end, "int32", "row_end")
         _want(rowptr, "int32", "rowptr")
         _want(colidx, "int32", "colidx")
@@ -123,13 +124,14 @@ class Graph:
         self.nnz = int(colidx.numel())
         self.n_graphs = 1 if graph_off is None else int(graph_off.numel() - 1)
         self.c = CGraph(self.n_nodes, self.nnz, _dp(rowptr), _dp(colidx) if self.nnz else None, _dp(w),
-                        self.n_graphs, _dp(graph_off), _dp(row_end), int(bool(state_residual)))
+                        self.n_graphs, _dp(graph_off), _dp(row_end), int(bool(state_residual)), int(bool(weighted_sum)))
         self.state_residual = bool(state_residual)
+        self.weighted_sum = bool(weighted_sum)
 
     def mutable_copy(self):
         """A copy whose colidx / w / row_end the inference loop may edit in place."""
         return Graph(self.rowptr, self.colidx.clone(), None if self.w is None else self.w.clone(), self.graph_off,
-                     self.rowptr[1:].clone())
+                     self.rowptr[1:].clone(), state_residual=self.state_residual, weighted_sum=self.weighted_sum)
 
 
 class Params:

@@ -511,6 +511,7 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     const HubTable ht = hub_table(ws, h, *pr);
     // per-(node, state) scalar records; with per-state residual graphs they hold each state's own edge sums
     const float *x_res = g->state_residual ? x : nullptr;
+    const float *wagg = g->weighted_sum ? g->w : nullptr;   // NULL weights mean w = 1: the plain sum
     if (x_res)
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info));
     else
@@ -521,9 +522,9 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     for (int t = 2; t <= T; ++t) {
         const float *src = t == 2 ? nullptr : dest(t - 1);
-        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, src, info, params->theta1, qvec, nullptr, hub_part, hub_sum));
+        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, src, info, params->theta1, qvec, nullptr, hub_part, hub_sum));
         SpanGuard span(ctx, t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND);
-        S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, src, dest(t), info, params->theta1,
+        S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, src, dest(t), info, params->theta1,
                              params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum, x_res,
                              t == T));
     }
@@ -651,6 +652,7 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     // dz^T is never materialised: its relu mask and its share of the sums come from one pass over mu^T
     const HubTable ht = hub_table(ws, h, *pr);
     const float *x_res = g->state_residual ? x : nullptr;
+    const float *wagg = g->weighted_sum ? g->w : nullptr;   // NULL weights mean w = 1: the plain sum
     if (x_res)
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, sc.rec));
     else
@@ -666,17 +668,17 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         const bool first = t == T;
         const float *dz_in = first ? nullptr : sc.dz[cur];
         float *dz_out = t == 2 ? nullptr : sc.dz[cur ^ 1];  // dz^1 only feeds the sums
-        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, dz_in, nullptr, nullptr, nullptr, first ? sc.maskT : nullptr,
+        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, dz_in, nullptr, nullptr, nullptr, first ? sc.maskT : nullptr,
                                 hub_part, hub_sum));
         {
             SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
-            S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
+            S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
                                      dz_out, sc.rec, params->theta2, dc_part, d2_part, ht, hub_sum));
         }
         if (first) {
             float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;
             float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdGrid * p * p;
-            S2V_TRY(launch_bwd_action_fix(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, action, sc.maskT, sc, params->theta2,
+            S2V_TRY(launch_bwd_action_fix(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, action, sc.maskT, sc, params->theta2,
                                           mu_prev, dz_out, sc.rec, dc_fix, d2_fix));
         }
         cur ^= 1;

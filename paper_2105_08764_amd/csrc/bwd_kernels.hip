@@ -233,10 +233,10 @@ hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *mu
 //         neighbours of u whose mask bit is set): the gather reads 8-byte mask words, not rows.
 //   dz_out may be NULL (t == 2: dz^1 is needed for the sums only).
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE, bool MASK>
+template <int P, bool NODE, bool MASK, bool W>   // W: weighted neighbour sum (weights wagg, symmetric like the pattern)
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     int n_vrows, int N, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
-    const int32_t *__restrict__ colidx, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
+    const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
     const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
     float *__restrict__ dz_out, const float *__restrict__ rec, const float *__restrict__ theta2,
     float *__restrict__ dc_part,
@@ -298,9 +298,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
                 ga = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
             } else if (MASK) {
-                ga = gather_node_block_bits<P>(maskT, S, s0, colidx, b, e, lane);
+                ga = W ? gather_node_block_bits_w<P>(maskT, S, s0, colidx, wagg, b, e, lane)
+                       : gather_node_block_bits<P>(maskT, S, s0, colidx, b, e, lane);
             } else {
-                ga = gather_node_block<P>(dz_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+                ga = gather_node_block<P, W>(dz_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
             }
             if (MASK) {
                 // counts -> G: times dg of this lane's state and columns (the node is wave-uniform)
@@ -337,10 +338,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                     a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
                 } else if (MASK) {
                     const BitsRow bits{maskT, S, si, 4 * li};
-                    a = gather_row_sum<P>(bits, colidx, b, e, cols, lane);
+                    a = gather_row_sum<P, W>(bits, colidx, wagg, b, e, cols, lane);
                 } else {
                     const MemRow mem{dz_in, row_stride, (size_t)si * P + 4 * li};
-                    a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
+                    a = gather_row_sum<P, W>(mem, colidx, wagg, b, e, cols, lane);
                 }
                 if (MASK) {
                     const bool ing = __shfl((int)in_graph, i) != 0;
@@ -434,16 +435,21 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
 }
 
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                            const int32_t *colidx, const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
+                            const int32_t *colidx, const float *wagg, const float *dz_in,
+                            const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out, const float *rec, const float *theta2,
                             float *dc_part, float *d2_part, const HubTable &ht, const float *hub_sum) {
     const long n_vrows = (long)N * S;
     const bool node = (S % 16) == 0, mask = maskT != nullptr;
-#define S2V_LAUNCH_BWD(PP, NODE, MASK)                                                                              \
-    k_bwd_round<PP, NODE, MASK><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, rowend, colidx, dz_in, maskT, \
-                                                               sc.dg, \
-                                                               sc.glo, sc.ghi, mu_prev, dz_out, rec, theta2, \
-                                                               dc_part, d2_part, ht, hub_sum)
+#define S2V_LAUNCH_BWD_W(PP, NODE, MASK, WW)                                                                        \
+    k_bwd_round<PP, NODE, MASK, WW><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, rowend, colidx, wagg,     \
+                                                                   dz_in, maskT, sc.dg, sc.glo, sc.ghi, mu_prev, dz_out, \
+                                                                   rec, theta2, dc_part, d2_part, ht, hub_sum)
+#define S2V_LAUNCH_BWD(PP, NODE, MASK)                    \
+    do {                                                  \
+        if (wagg) S2V_LAUNCH_BWD_W(PP, NODE, MASK, true);     \
+        else S2V_LAUNCH_BWD_W(PP, NODE, MASK, false);         \
+    } while (0)
 #define S2V_LAUNCH_BWD_P(PP)                                                                          \
     do {                                                                                              \
         if (node) { if (mask) S2V_LAUNCH_BWD(PP, true, true); else S2V_LAUNCH_BWD(PP, true, false); }  \
@@ -452,6 +458,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
     if (p == 32) S2V_LAUNCH_BWD_P(32); else S2V_LAUNCH_BWD_P(64);
 #undef S2V_LAUNCH_BWD_P
 #undef S2V_LAUNCH_BWD
+#undef S2V_LAUNCH_BWD_W
     return hipGetLastError();
 }
 
@@ -459,7 +466,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 // The action node's own term of dz^T, which the MASK round leaves out:
 //   dz^T[a_s][s] += da[s] (.) [mu^T[a_s][s] > 0] =: g_s.
 // The round is linear in dz^T, so its effect is added here.  Only the rows u in N(a_s) see it:
-//   G_u += g_s  =>  dz^{T-1}_u += (theta2^T g_s) (.) [mu^{T-1}_u > 0],  dtheta2 += g_s (sum_u mu^{T-1}_u)^T,
+//   G_u += g_s  (w_au g_s with a weighted sum)  =>  dz^{T-1}_u += (theta2^T g_s) (.) [mu^{T-1}_u > 0],  dtheta2 += g_s (sum_u mu^{T-1}_u)^T,
 // plus the matching share of the sum x dz, sum s+- dz partials.  Grid = (kFixSplit, S): block
 // (k, s) takes the entries of row a_s congruent to k modulo kFixSplit; thread = (slot, column).
 // ------------------------------------------------------------------------------------------
@@ -467,6 +474,7 @@ template <int P>
 __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int32_t *__restrict__ rowptr,
                                                         const int32_t *__restrict__ rowend,
                                                         const int32_t *__restrict__ colidx,
+                                                        const float *__restrict__ wagg /*NULL: unweighted sum*/,
                                                         const int32_t *__restrict__ action,
                                                         const unsigned long long *__restrict__ maskT,
                                                         const float *__restrict__ da,
@@ -497,13 +505,14 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
         const int u = colidx[idx];
         const size_t off = ((size_t)u * S + s) * P + j;
         const float mprev = mu_prev[off];
-        const float d = mprev > 0.f ? w[j] : 0.f;
+        const float wa = wagg ? wagg[idx] : 1.f;     // G_u += w_au g_s with a weighted sum
+        const float d = mprev > 0.f ? wa * w[j] : 0.f;
         if (dz_out) dz_out[off] += d;
         const float4 q = ld4(rec + ((size_t)u * S + s) * 4);
         cx += q.z * d;
         cp += q.x * d;
         cn += q.y * d;
-        msum += mprev;
+        msum += wa * mprev;
     }
     red[0][slot][j] = cx; red[1][slot][j] = cp; red[2][slot][j] = cn; red[3][slot][j] = msum;
     __syncthreads();
@@ -528,16 +537,16 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
 }
 
 hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                                 const int32_t *colidx,
+                                 const int32_t *colidx, const float *wagg,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
                                  const float *theta2, const float *mu_prev, float *dz_out, const float *rec,
                                  float *dc_part, float *d2_part) {
     const dim3 grid(kFixSplit, S);
     if (p == 32)
-        k_bwd_action_fix<32><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, action, maskT, sc.da, theta2, mu_prev,
+        k_bwd_action_fix<32><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, wagg, action, maskT, sc.da, theta2, mu_prev,
                                                    dz_out, rec, dc_part, d2_part);
     else
-        k_bwd_action_fix<64><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, action, maskT, sc.da, theta2, mu_prev,
+        k_bwd_action_fix<64><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, wagg, action, maskT, sc.da, theta2, mu_prev,
                                                    dz_out, rec, dc_part, d2_part);
     return hipGetLastError();
 }

@@ -28,6 +28,16 @@ __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast
 __device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
 __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
+// acc += v (W = false) or acc += w * v (W = true: the weighted neighbour sum)
+template <bool W>
+__device__ __forceinline__ float4 acc4(float4 a, float4 v, float w) {
+    if (W) return make_float4(fmaf(w, v.x, a.x), fmaf(w, v.y, a.y), fmaf(w, v.z, a.z), fmaf(w, v.w, a.w));
+    return add4(a, v);
+}
+__device__ __forceinline__ float readlane_f(float x, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+
 // ---- row loaders: the float4 (columns 4*li .. 4*li+3) of neighbour u's row -------------------
 
 // Row (u, s) of a [N][S][P] matrix in memory.
@@ -75,16 +85,19 @@ struct BitsRow {
 // Sum over the stored entries [b, e) of one CSR row of the neighbours' P-float rows (row mode:
 // any S).  All 64 lanes take part: lane = (group gq, lane-in-row li); one wave-wide load fetches
 // NPL neighbour rows.  `cols` holds colidx[b + lane] for the first (up to) 64 entries, loaded by
-// the caller ahead of time.  Returns the full row sum in every group.
-template <int P, class Loader>
-__device__ __forceinline__ float4 gather_row_sum(const Loader &row, const int *__restrict__ colidx, int b, int e,
-                                                 int cols, int lane) {
+// the caller ahead of time.  Returns the full row sum in every group.  W = true multiplies each
+// neighbour's row by the weight of its entry (wagg is indexed like colidx).
+template <int P, bool W = false, class Loader>
+__device__ __forceinline__ float4 gather_row_sum(const Loader &row, const int *__restrict__ colidx,
+                                                 const float *__restrict__ wagg, int b, int e, int cols, int lane) {
     constexpr int NPL = Geo<P>::NPL, LPR = Geo<P>::LPR;
     const int gq = lane / LPR;
     float4 total = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         if (base != b) cols = (lane < cnt) ? colidx[base + lane] : 0;
+        float wv = 0.f;
+        if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
         const int last = cnt - 1;
         // per-chunk accumulators folded into the running total: bounds the terms added into one float
         float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0, a2 = a0, a3 = a0;
@@ -95,32 +108,36 @@ __device__ __forceinline__ float4 gather_row_sum(const Loader &row, const int *_
         for (; cnt - s0 > 4 * NPL; s0 += 8 * NPL) {
             int sl[8];
             float4 v[8];
+            float wk[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 sl[k] = s0 + gq + k * NPL;
                 v[k] = row(__shfl(cols, min(sl[k], last)));
+                wk[k] = W ? __shfl(wv, min(sl[k], last)) : 1.f;
             }
-            if (sl[0] < cnt) a0 = add4(a0, v[0]);
-            if (sl[1] < cnt) a1 = add4(a1, v[1]);
-            if (sl[2] < cnt) a2 = add4(a2, v[2]);
-            if (sl[3] < cnt) a3 = add4(a3, v[3]);
-            if (sl[4] < cnt) a0 = add4(a0, v[4]);
-            if (sl[5] < cnt) a1 = add4(a1, v[5]);
-            if (sl[6] < cnt) a2 = add4(a2, v[6]);
-            if (sl[7] < cnt) a3 = add4(a3, v[7]);
+            if (sl[0] < cnt) a0 = acc4<W>(a0, v[0], wk[0]);
+            if (sl[1] < cnt) a1 = acc4<W>(a1, v[1], wk[1]);
+            if (sl[2] < cnt) a2 = acc4<W>(a2, v[2], wk[2]);
+            if (sl[3] < cnt) a3 = acc4<W>(a3, v[3], wk[3]);
+            if (sl[4] < cnt) a0 = acc4<W>(a0, v[4], wk[4]);
+            if (sl[5] < cnt) a1 = acc4<W>(a1, v[5], wk[5]);
+            if (sl[6] < cnt) a2 = acc4<W>(a2, v[6], wk[6]);
+            if (sl[7] < cnt) a3 = acc4<W>(a3, v[7], wk[7]);
         }
         if (s0 < cnt) {
             int sl[4];
             float4 v[4];
+            float wk[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 sl[k] = s0 + gq + k * NPL;
                 v[k] = row(__shfl(cols, min(sl[k], last)));
+                wk[k] = W ? __shfl(wv, min(sl[k], last)) : 1.f;
             }
-            if (sl[0] < cnt) a0 = add4(a0, v[0]);
-            if (sl[1] < cnt) a1 = add4(a1, v[1]);
-            if (sl[2] < cnt) a2 = add4(a2, v[2]);
-            if (sl[3] < cnt) a3 = add4(a3, v[3]);
+            if (sl[0] < cnt) a0 = acc4<W>(a0, v[0], wk[0]);
+            if (sl[1] < cnt) a1 = acc4<W>(a1, v[1], wk[1]);
+            if (sl[2] < cnt) a2 = acc4<W>(a2, v[2], wk[2]);
+            if (sl[3] < cnt) a3 = acc4<W>(a3, v[3], wk[3]);
         }
         total = add4(total, add4(add4(a0, a1), add4(a2, a3)));
     }
@@ -150,10 +167,10 @@ struct NodeAcc {
 #define S2V_NODE_UNROLL 2
 #endif
 
-template <int P>
+template <int P, bool W = false>
 __device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict__ src, size_t node_stride /*S*P*/,
-                                                        size_t blk_off /*s0*P*/, const int *__restrict__ colidx, int b,
-                                                        int e, int lane) {
+                                                        size_t blk_off /*s0*P*/, const int *__restrict__ colidx,
+                                                        const float *__restrict__ wagg, int b, int e, int lane) {
     constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, U = S2V_NODE_UNROLL;
     // U accumulators per 64-entry chunk, folded into the running total after each chunk, so a
     // row of d entries adds at most about 64 / U + d / 64 terms into any one float.
@@ -164,6 +181,8 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict_
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         const int cols = (lane < cnt) ? colidx[base + lane] : 0;
+        float wv = 0.f;
+        if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
 #pragma unroll
         for (int k = 0; k < U; ++k)
 #pragma unroll
@@ -171,24 +190,27 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict_
         int j = 0;
         for (; j + U <= cnt; j += U) {
             float4 v[U][NC];
+            float wk[U];
 #pragma unroll
             for (int k = 0; k < U; ++k) {
                 const float *pk = lane_src + (size_t)__builtin_amdgcn_readlane(cols, j + k) * node_stride;
+                wk[k] = W ? readlane_f(wv, j + k) : 1.f;
 #pragma unroll
                 for (int c = 0; c < NC; ++c) v[k][c] = ld4(pk + c * RPI * P);
             }
 #pragma unroll
             for (int k = 0; k < U; ++k)
 #pragma unroll
-                for (int c = 0; c < NC; ++c) acc[k].a[c] = add4(acc[k].a[c], v[k][c]);
+                for (int c = 0; c < NC; ++c) acc[k].a[c] = acc4<W>(acc[k].a[c], v[k][c], wk[k]);
         }
         for (; j < cnt; ++j) {
             const float *p0 = lane_src + (size_t)__builtin_amdgcn_readlane(cols, j) * node_stride;
+            const float w0 = W ? readlane_f(wv, j) : 1.f;
             float4 v0[NC];
 #pragma unroll
             for (int c = 0; c < NC; ++c) v0[c] = ld4(p0 + c * RPI * P);
 #pragma unroll
-            for (int c = 0; c < NC; ++c) acc[0].a[c] = add4(acc[0].a[c], v0[c]);
+            for (int c = 0; c < NC; ++c) acc[0].a[c] = acc4<W>(acc[0].a[c], v0[c], w0);
         }
 #pragma unroll
         for (int k = 1; k < U; ++k)
@@ -201,11 +223,12 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict_
 }
 
 // Node mode with the round-1 rows recomputed from the records rec[u][s0 .. s0+15] (see Mu1Row).
-template <int P>
+template <int P, bool W = false>
 __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restrict__ rec, int S, int s0,
                                                             const float *__restrict__ theta1,
                                                             const float *__restrict__ qvec,
-                                                            const int *__restrict__ colidx, int b, int e, int lane) {
+                                                            const int *__restrict__ colidx,
+                                                            const float *__restrict__ wagg, int b, int e, int lane) {
     constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
     NodeAcc<P> total, acc;
 #pragma unroll
@@ -216,15 +239,19 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         const int cols = (lane < cnt) ? colidx[base + lane] : 0;
+        float wv = 0.f;
+        if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
         // four neighbours per step: their records are fetched together
         for (int j = 0; j < cnt; j += 4) {
             float4 r[4][NC];
+            float wk[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int jj = min(j + k, cnt - 1);   // past the end: re-read the last records, dropped below
                 const float *ru = rec + ((size_t)__builtin_amdgcn_readlane(cols, jj) * S + srow) * 4;
+                wk[k] = W ? readlane_f(wv, jj) : 1.f;
 #pragma unroll
                 for (int c = 0; c < NC; ++c) r[k][c] = ld4(ru + (size_t)c * RPI * 4);
             }
@@ -234,10 +261,11 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
 #pragma unroll
                     for (int c = 0; c < NC; ++c) {
                         const float4 q = r[k][c];
-                        acc.a[c].x += fmaxf(q.z * t1.x + q.x * qp.x + q.y * qn.x, 0.f);
-                        acc.a[c].y += fmaxf(q.z * t1.y + q.x * qp.y + q.y * qn.y, 0.f);
-                        acc.a[c].z += fmaxf(q.z * t1.z + q.x * qp.z + q.y * qn.z, 0.f);
-                        acc.a[c].w += fmaxf(q.z * t1.w + q.x * qp.w + q.y * qn.w, 0.f);
+                        const float4 m = make_float4(fmaxf(q.z * t1.x + q.x * qp.x + q.y * qn.x, 0.f),
+                                                     fmaxf(q.z * t1.y + q.x * qp.y + q.y * qn.y, 0.f),
+                                                     fmaxf(q.z * t1.z + q.x * qp.z + q.y * qn.z, 0.f),
+                                                     fmaxf(q.z * t1.w + q.x * qp.w + q.y * qn.w, 0.f));
+                        acc.a[c] = acc4<W>(acc.a[c], m, wk[k]);
                     }
                 }
             }
@@ -250,6 +278,52 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
 
 // Node mode over relu-mask words (see BitsRow): per column, the number of neighbours of the node
 // whose entry is positive, for the 16 states s0 .. s0+15.
+// Weighted form of gather_node_block_bits: per column, the sum of the weights of the neighbours whose
+// entry is positive (per-chunk accumulators folded into a running total, as in the other gathers).
+template <int P>
+__device__ __forceinline__ NodeAcc<P> gather_node_block_bits_w(const unsigned long long *__restrict__ mask, int S,
+                                                               int s0, const int *__restrict__ colidx,
+                                                               const float *__restrict__ wagg, int b, int e, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+    NodeAcc<P> total, acc;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) total.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int shift = 4 * (lane % LPR);
+    const int srow = s0 + lane / LPR;
+    for (int base = b; base < e; base += 64) {
+        const int n = min(64, e - base);
+        const int cols = (lane < n) ? colidx[base + lane] : 0;
+        const float wv = (lane < n) ? wagg[base + lane] : 0.f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < n; j += 4) {
+            unsigned nib[4][NC];
+            float wk[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int jj = min(j + k, n - 1);   // past the end: re-read the last word, weight 0 below
+                const unsigned long long *w = mask + (size_t)__builtin_amdgcn_readlane(cols, jj) * S + srow;
+                wk[k] = (j + k < n) ? readlane_f(wv, jj) : 0.f;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) nib[k][c] = (unsigned)(w[c * RPI] >> shift);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const unsigned b4 = nib[k][c];
+                    acc.a[c].x += (b4 & 1u) ? wk[k] : 0.f;
+                    acc.a[c].y += (b4 & 2u) ? wk[k] : 0.f;
+                    acc.a[c].z += (b4 & 4u) ? wk[k] : 0.f;
+                    acc.a[c].w += (b4 & 8u) ? wk[k] : 0.f;
+                }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], acc.a[c]);
+    }
+    return total;
+}
+
 template <int P>
 __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long long *__restrict__ mask, int S, int s0,
                                                              const int *__restrict__ colidx, int b, int e, int lane) {

@@ -228,11 +228,14 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 //   MU1 : this is round 2; the neighbours' round-1 rows are recomputed from info[] instead of read.
 //   GSUM: also emit this workgroup's column sums of the output (S == 1, one graph) to
 //         gpart[blockIdx.x][P]: the first stage of the graph sum of Alg. 2 line 4.
+//   W   : the neighbour sum weights each neighbour by its entry of wagg (the reading of the
+//         aggregation step of Alg. 1 as a product with the weighted adjacency).
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE, bool MU1, bool GSUM>
+template <int P, bool NODE, bool MU1, bool GSUM, bool W>
 __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const int32_t *__restrict__ rowptr,
                                                     const int32_t *__restrict__ rowend,
                                                     const int32_t *__restrict__ colidx,
+                                                    const float *__restrict__ wagg,
                                                     const float *__restrict__ mu_in, float *__restrict__ mu_out,
                                                     const float *__restrict__ info,
                                                     const float *__restrict__ theta1,
@@ -300,8 +303,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
                 acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
             } else {
-                acc = MU1 ? gather_node_block_mu1<P>(info, S, s0, theta1, qvec, colidx, b, e, lane)
-                          : gather_node_block<P>(mu_in, row_stride, (size_t)s0 * P, colidx, b, e, lane);
+                acc = MU1 ? gather_node_block_mu1<P, W>(info, S, s0, theta1, qvec, colidx, wagg, b, e, lane)
+                          : gather_node_block<P, W>(mu_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
             }
             store_node_block<P>(tile, acc, lane);
         } else {
@@ -323,10 +326,10 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const
                     a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
                 } else if (MU1) {
                     mu1.s = si;
-                    a = gather_row_sum<P>(mu1, colidx, b, e, cols, lane);
+                    a = gather_row_sum<P, W>(mu1, colidx, wagg, b, e, cols, lane);
                 } else {
                     const MemRow mem{mu_in, row_stride, (size_t)si * P + 4 * li};
-                    a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
+                    a = gather_row_sum<P, W>(mem, colidx, wagg, b, e, cols, lane);
                 }
                 if (lane < G::LPR) st4(tile + i * G::STRIDE + 4 * lane, a);
             }
@@ -382,17 +385,22 @@ int round_grid(long n_vrows) {
 
 template <int P>
 static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                                 const int32_t *colidx,
+                                 const int32_t *colidx, const float *wagg,
                                  const float *mu_in, float *mu_out, const float *info, const float *theta1,
                                  const float *theta2, const float *qvec, bool from_scalars, float *gpart,
                                  const HubTable &ht, const float *hub_sum, const float *x_res, bool last) {
     const long n_vrows = (long)N * S;
     const int grid = round_grid(n_vrows);
     const bool node = (S % 16) == 0;
-#define S2V_LAUNCH_ROUND(NODE, MU1, GSUM)                                                                         \
-    k_round<P, NODE, MU1, GSUM><<<grid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, mu_in, mu_out, \
-                                                           info, \
-                                                           theta1, theta2, qvec, gpart, ht, hub_sum, x_res, N, last ? 1 : 0)
+#define S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, WW)                                                                  \
+    k_round<P, NODE, MU1, GSUM, WW><<<grid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in,  \
+                                                               mu_out, info, theta1, theta2, qvec, gpart, ht, hub_sum, \
+                                                               x_res, N, last ? 1 : 0)
+#define S2V_LAUNCH_ROUND(NODE, MU1, GSUM)                \
+    do {                                                 \
+        if (wagg) S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, true); \
+        else S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, false);     \
+    } while (0)
     if (node) {
         if (from_scalars) S2V_LAUNCH_ROUND(true, true, false);
         else S2V_LAUNCH_ROUND(true, false, false);
@@ -404,19 +412,20 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
         else S2V_LAUNCH_ROUND(false, false, false);
     }
 #undef S2V_LAUNCH_ROUND
+#undef S2V_LAUNCH_ROUND_W
     return hipGetLastError();
 }
 
 // gpart != NULL asks for the fused column sums (only legal for S == 1 and a single graph).
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                        const int32_t *colidx, const float *mu_in, float *mu_out, const float *info, const float *theta1,
+                        const int32_t *colidx, const float *wagg, const float *mu_in, float *mu_out, const float *info, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
                         const float *hub_sum, const float *x_res, bool last) {
     if ((long)N * S == 0) return hipSuccess;
     if (p == 32)
-        return launch_round_p<32>(st, N, S, rowptr, rowend, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
+        return launch_round_p<32>(st, N, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
                                   gpart, ht, hub_sum, x_res, last);
-    return launch_round_p<64>(st, N, S, rowptr, rowend, colidx, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
+    return launch_round_p<64>(st, N, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
                               ht, hub_sum, x_res, last);
 }
 
@@ -425,10 +434,11 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
 // kHubDegree neighbour rows with the same gather code as the round kernel.  Stage B adds the
 // segment partials of each hub in segment order.
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE, int SRC>   // SRC: 0 rows in memory, 1 round-1 rows from scalars, 2 relu-mask bits
+template <int P, bool NODE, int SRC, bool W>   // SRC: 0 rows in memory, 1 round-1 rows from scalars, 2 relu-mask bits
 __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
                                                           const int32_t *__restrict__ rowend,
                                                           const int32_t *__restrict__ colidx,
+                                                          const float *__restrict__ wagg,
                                                           const float *__restrict__ src,
                                                           const float *__restrict__ info,
                                                           const float *__restrict__ theta1,
@@ -447,9 +457,11 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
         if (NODE) {
             const int s0 = blk * 16;
             NodeAcc<P> acc;
-            if (SRC == 1) acc = gather_node_block_mu1<P>(info, S, s0, theta1, qvec, colidx, b, e, lane);
-            else if (SRC == 2) acc = gather_node_block_bits<P>(mask, S, s0, colidx, b, e, lane);
-            else acc = gather_node_block<P>(src, (size_t)S * P, (size_t)s0 * P, colidx, b, e, lane);
+            if (SRC == 1) acc = gather_node_block_mu1<P, W>(info, S, s0, theta1, qvec, colidx, wagg, b, e, lane);
+            else if (SRC == 2)
+                acc = W ? gather_node_block_bits_w<P>(mask, S, s0, colidx, wagg, b, e, lane)
+                        : gather_node_block_bits<P>(mask, S, s0, colidx, b, e, lane);
+            else acc = gather_node_block<P, W>(src, (size_t)S * P, (size_t)s0 * P, colidx, wagg, b, e, lane);
             float *out = partial + ((size_t)seg * S + s0) * P;
 #pragma unroll
             for (int c = 0; c < 16 / G::NPL; ++c) st4(out + c * G::NPL * P + 4 * lane, acc.a[c]);
@@ -459,13 +471,13 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
             float4 a;
             if (SRC == 1) {
                 Mu1Row mu1{info, S, s, ld4(theta1 + 4 * li), ld4(qvec + 4 * li), ld4(qvec + P + 4 * li)};
-                a = gather_row_sum<P>(mu1, colidx, b, e, cols, lane);
+                a = gather_row_sum<P, W>(mu1, colidx, wagg, b, e, cols, lane);
             } else if (SRC == 2) {
                 const BitsRow bits{mask, S, s, 4 * li};
-                a = gather_row_sum<P>(bits, colidx, b, e, cols, lane);
+                a = gather_row_sum<P, W>(bits, colidx, wagg, b, e, cols, lane);
             } else {
                 const MemRow mem{src, (size_t)S * P, (size_t)s * P + 4 * li};
-                a = gather_row_sum<P>(mem, colidx, b, e, cols, lane);
+                a = gather_row_sum<P, W>(mem, colidx, wagg, b, e, cols, lane);
             }
             if (lane < G::LPR) st4(partial + ((size_t)seg * S + s) * P + 4 * lane, a);
         }
@@ -484,7 +496,7 @@ __global__ __launch_bounds__(256) void k_hub_combine(int L, HubTable ht, const f
 }
 
 hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
-                           const int32_t *colidx, const float *src,
+                           const int32_t *colidx, const float *wagg, const float *src,
                            const float *info, const float *theta1, const float *qvec,
                            const unsigned long long *mask, float *partial, float *hub_sum) {
     if (ht.n_hubs == 0) return hipSuccess;
@@ -492,9 +504,14 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
     const int kind = mask ? 2 : (src ? 0 : 1);
     const long items = (long)ht.n_segs * (node ? S / 16 : S);
     const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
-#define S2V_LAUNCH_HUB(PP, NODE, SRC) \
-    k_hub_partial<PP, NODE, SRC><<<grid, kThreads, 0, st>>>(S, ht, rowend, colidx, src, info, theta1, qvec, mask, \
-                                                            partial)
+#define S2V_LAUNCH_HUB_W(PP, NODE, SRC, WW)                                                                       \
+    k_hub_partial<PP, NODE, SRC, WW><<<grid, kThreads, 0, st>>>(S, ht, rowend, colidx, wagg, src, info, theta1, qvec, \
+                                                                mask, partial)
+#define S2V_LAUNCH_HUB(PP, NODE, SRC)                   \
+    do {                                                \
+        if (wagg) S2V_LAUNCH_HUB_W(PP, NODE, SRC, true);    \
+        else S2V_LAUNCH_HUB_W(PP, NODE, SRC, false);        \
+    } while (0)
 #define S2V_LAUNCH_HUB_P(PP)                                                                           \
     do {                                                                                               \
         if (node) {                                                                                    \
@@ -508,6 +525,7 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
     if (p == 32) S2V_LAUNCH_HUB_P(32); else S2V_LAUNCH_HUB_P(64);
 #undef S2V_LAUNCH_HUB_P
 #undef S2V_LAUNCH_HUB
+#undef S2V_LAUNCH_HUB_W
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const int L = S * p;

@@ -64,11 +64,12 @@ hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const f
 // (mask != NULL: counts of set relu-mask bits instead; else src == NULL: the round-1 rows
 // recomputed from info).  partial is [n_segs][S][p] scratch.
 hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
-                           const int32_t *colidx, const float *src,
+                           const int32_t *colidx, const float *wagg, const float *src,
                            const float *info, const float *theta1, const float *qvec,
                            const unsigned long long *mask, float *partial, float *hub_sum);
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                        const int32_t *colidx, const float *mu_in, float *mu_out, const float *info, const float *theta1,
+                        const int32_t *colidx, const float *wagg /*NULL: unweighted neighbour sum*/, const float *mu_in,
+                        float *mu_out, const float *info, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
                         const float *hub_sum, const float *x_res, bool last);
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum);
@@ -132,12 +133,13 @@ hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *mu
                             float *dc_part /*[kBwdHeadGrid][3][p]*/);
 // maskT != NULL selects the first reversed round (t = T), which reads relu-mask words instead of dz_in.
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                            const int32_t *colidx, const float *dz_in, const unsigned long long *maskT, const BwdScratch &sc,
+                            const int32_t *colidx, const float *wagg, const float *dz_in,
+                            const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out /*may be NULL*/, const float *rec, const float *theta2,
                             float *dc_part /*[kBwdGrid][3][p]*/, float *d2_part /*[kBwdGrid][p][p]*/,
                             const HubTable &ht, const float *hub_sum);
 hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                                 const int32_t *colidx,
+                                 const int32_t *colidx, const float *wagg,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
                                  const float *theta2, const float *mu_prev, float *dz_out /*may be NULL*/,
                                  const float *rec, float *dc_part /*[S*kFixSplit][3][p]*/,

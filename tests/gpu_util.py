@@ -11,7 +11,7 @@ class Device:
     """One context + uploaded graph + workspace, reused across calls of a test."""
 
     def __init__(self, g: si.Graph, p: int, T: int, S: int = 1, k_max: int = 1, training: bool = False,
-                 state_residual: bool = False):
+                 state_residual: bool = False, weighted_sum: bool = False):
         import torch
 
         import paper_2105_08764_amd as s2v
@@ -26,7 +26,7 @@ class Device:
             torch.from_numpy(g.colidx).to(dev),
             None if g.w is None else torch.from_numpy(g.w).to(dev),
             None if g.graph_off is None else torch.from_numpy(g.graph_off).to(dev),
-            state_residual=state_residual,
+            state_residual=state_residual, weighted_sum=weighted_sum,
         )
         nbytes = self.ctx.s2v_workspace_bytes(self.graph, p, T, S, k_max, training)
         self.ws_bytes = nbytes
@@ -135,7 +135,7 @@ def oracle_forward(oracle, g: si.Graph, theta, x_row, T):
     return mu, gsum, q
 
 
-def oracle_per_state_residual(oracle, g: si.Graph, theta, x, T, action=None, target=None):
+def oracle_per_state_residual(oracle, g: si.Graph, theta, x, T, action=None, target=None, weighted=False):
     """Alg. 4's minibatch on per-state sub-graphs, composed from the oracle's own pieces: state b is
     embedded and scored on residual_graph(x[b]) as a batch of one; with action/target the loss and the
     gradients are the means over the states.  Returns dict(mu [N][S][p], gsum [S][G][p], q [S][N])
@@ -144,13 +144,14 @@ def oracle_per_state_residual(oracle, g: si.Graph, theta, x, T, action=None, tar
     mus, gsums, qs, losses, qps, gsumd = [], [], [], [], [], None
     for b in range(S):
         rp, ci, w = oracle.residual_graph(g.rowptr, g.colidx, g.w, x[b])
-        mu = oracle.embed(rp, ci, w, theta, x[b], T)
+        mu = oracle.embed(rp, ci, w, theta, x[b], T, weighted=weighted)
         gs, q = oracle.q_scores(g.graph_off, theta, mu)
         mus.append(mu.reshape(g.n, -1))
         gsums.append(gs.reshape(g.n_graphs, -1))
         qs.append(q.reshape(-1))
         if action is not None:
-            lb, qb, gb = oracle.loss_grad(rp, ci, w, g.graph_off, theta, x[b], T, action[b:b + 1], target[b:b + 1])
+            lb, qb, gb = oracle.loss_grad(rp, ci, w, g.graph_off, theta, x[b], T, action[b:b + 1], target[b:b + 1],
+                                         weighted=weighted)
             losses.append(lb)
             qps.append(qb[0])
             gsumd = gb if gsumd is None else {k: gsumd[k] + gb[k] for k in gb}
