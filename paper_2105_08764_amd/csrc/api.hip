@@ -150,7 +150,7 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.dz0 = c.take(T >= 3 ? sizeof(float) * (size_t)N * S * p : 0);
     b.dz1 = c.take(T >= 4 ? sizeof(float) * (size_t)N * S * p : 0);
     b.maskT = c.take(T >= 2 ? sizeof(unsigned long long) * (size_t)N * S : 0);
-    b.rec = c.take(sizeof(float) * (size_t)N * S * 4);
+    b.rec = c.take(sizeof(float) * (size_t)N * nodeinfo_stride(S));
     b.dc_part = c.take(sizeof(float) * (size_t)b.dc_rows * 3 * p);
     b.d2_part = c.take(sizeof(float) * (size_t)b.d2_rows * p * p);
     b.dvec = c.take(sizeof(float) * 3 * p);
@@ -516,15 +516,16 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info));
     else
         S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info));
+    const NodeInfo ninfo = make_nodeinfo(info, S, x_res != nullptr);
     if (mu_saved || T == 1)
-        S2V_TRY(launch_round1(st, p, N, S, info, x_res, T == 1, params->theta1, qvec, dest(1)));
+        S2V_TRY(launch_round1(st, p, N, S, ninfo, x_res, T == 1, params->theta1, qvec, dest(1)));
     const bool fuse_gsum = gsum && S == 1 && G == 1 && T >= 2 && N > 0;
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     for (int t = 2; t <= T; ++t) {
         const float *src = t == 2 ? nullptr : dest(t - 1);
-        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, src, info, params->theta1, qvec, nullptr, hub_part, hub_sum));
+        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, src, ninfo, params->theta1, qvec, nullptr, hub_part, hub_sum));
         SpanGuard span(ctx, t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND);
-        S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, src, dest(t), info, params->theta1,
+        S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, src, dest(t), ninfo, params->theta1,
                              params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum, x_res,
                              t == T));
     }
@@ -657,7 +658,8 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, sc.rec));
     else
         S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec));
-    S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, sc.rec, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part));
+    const NodeInfo ninfo = make_nodeinfo(sc.rec, S, x_res != nullptr);
+    S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part));
     float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);
     int cur = 1;  // the round t = T writes dz[0]
     for (int t = T; t >= 2; --t) {
@@ -668,18 +670,18 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         const bool first = t == T;
         const float *dz_in = first ? nullptr : sc.dz[cur];
         float *dz_out = t == 2 ? nullptr : sc.dz[cur ^ 1];  // dz^1 only feeds the sums
-        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, dz_in, nullptr, nullptr, nullptr, first ? sc.maskT : nullptr,
+        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, dz_in, ninfo, nullptr, nullptr, first ? sc.maskT : nullptr,
                                 hub_part, hub_sum));
         {
             SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
             S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
-                                     dz_out, sc.rec, params->theta2, dc_part, d2_part, ht, hub_sum));
+                                     dz_out, ninfo, params->theta2, dc_part, d2_part, ht, hub_sum));
         }
         if (first) {
             float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;
             float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdGrid * p * p;
             S2V_TRY(launch_bwd_action_fix(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, action, sc.maskT, sc, params->theta2,
-                                          mu_prev, dz_out, sc.rec, dc_fix, d2_fix));
+                                          mu_prev, dz_out, ninfo, dc_fix, d2_fix));
         }
         cur ^= 1;
     }

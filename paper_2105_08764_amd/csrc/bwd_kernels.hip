@@ -137,7 +137,7 @@ hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch
 // ------------------------------------------------------------------------------------------
 template <int P>
 __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, const float *__restrict__ muT,
-                                                   const float *__restrict__ rec, const float *__restrict__ x_res,
+                                                   NodeInfo ni, const float *__restrict__ x_res,
                                                    const int32_t *__restrict__ action,
                                                    const float *__restrict__ dg, const float *__restrict__ da,
                                                    const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi,
@@ -176,9 +176,9 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
                 const unsigned nib = (mu[k].x > 0.f ? 1u : 0u) | (mu[k].y > 0.f ? 2u : 0u) |
                                      (mu[k].z > 0.f ? 4u : 0u) | (mu[k].w > 0.f ? 8u : 0u);
                 word = (unsigned long long)nib << (4 * c4);
-                const float4 q = ld4(rec + r * 4);
-                float xs = q.z;
-                const float sp = q.x, sn = q.y;
+                const float3 q = ni.get(v, s);
+                float xs = q.x;
+                const float sp = q.y, sn = q.z;
                 if (x_res) {
                     // per-state residual graphs: a solution node is isolated; it still feeds dtheta1 through
                     // the graph sum, but its mask word is zero so that no neighbour gathers from it
@@ -209,14 +209,14 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
     }
 }
 
-hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const float *rec, const float *x_res,
+hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const NodeInfo &ni, const float *x_res,
                             const int32_t *action, const BwdScratch &sc, unsigned long long *mask, float *dc_part) {
     const long n_vrows = (long)N * S;
     if (p == 32)
-        k_bwd_maskT<32><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, rec, x_res, action, sc.dg, sc.da, sc.glo,
+        k_bwd_maskT<32><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, ni, x_res, action, sc.dg, sc.da, sc.glo,
                                                       sc.ghi, mask, dc_part);
     else
-        k_bwd_maskT<64><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, rec, x_res, action, sc.dg, sc.da, sc.glo,
+        k_bwd_maskT<64><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, ni, x_res, action, sc.dg, sc.da, sc.glo,
                                                       sc.ghi, mask, dc_part);
     return hipGetLastError();
 }
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     int n_vrows, int N, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
     const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
-    float *__restrict__ dz_out, const float *__restrict__ rec, const float *__restrict__ theta2,
+    float *__restrict__ dz_out, NodeInfo ni, const float *__restrict__ theta2,
     float *__restrict__ dc_part,
     float *__restrict__ d2_part, HubTable ht, const float *__restrict__ hub_sum) {
     using Ge = Geo<P>;
@@ -246,6 +246,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     constexpr int TILE_F = kTileRows * STRIDE;
     static_assert(kWaves * TILE_F >= kWaves * 16 * P, "tile area is reused for the final reductions");
     __shared__ __attribute__((aligned(16))) float lds[kWaves * TILE_F];
+    // staging area of the mask-word gather (node mode of the MASK round only)
+    __shared__ __attribute__((aligned(16))) unsigned bits_stage[(NODE && MASK) ? kWaves * kBitsStageBytes / 4 : 4];
     __shared__ __attribute__((aligned(16))) float lds_b[P * STRIDE];   // theta2^T: B operand of G theta2
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float *tile_g = lds + wave * TILE_F;
@@ -274,8 +276,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
         const int s = valid ? r - v * S : 0;
         const int rb = valid ? rowptr[v] : 0;
         const int re = valid ? rowend[v] : 0;
-        const float4 mine = valid ? ld4(rec + (size_t)r * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-        const float sp = mine.x, sn = mine.y, xs = mine.z;
+        const float3 mine = valid ? ni.get(v, s) : make_float3(0.f, 0.f, 0.f);
+        const float xs = mine.x, sp = mine.y, sn = mine.z;
         // MASK: rows outside the action's graph receive nothing from the broadcast part of dz^T
         const bool in_graph = MASK ? (valid && v >= glo[s] && v < ghi[s]) : true;
 
@@ -299,7 +301,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                 ga = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
             } else if (MASK) {
                 ga = W ? gather_node_block_bits_w<P>(maskT, S, s0, colidx, wagg, b, e, lane)
-                       : gather_node_block_bits<P>(maskT, S, s0, colidx, b, e, lane);
+                       : gather_node_block_bits<P>(maskT, S, s0, colidx, b, e, lane,
+                                                   bits_stage + (NODE && MASK ? wave * (kBitsStageBytes / 4) : 0));
             } else {
                 ga = gather_node_block<P, W>(dz_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
             }
@@ -437,14 +440,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                             const int32_t *colidx, const float *wagg, const float *dz_in,
                             const unsigned long long *maskT, const BwdScratch &sc,
-                            const float *mu_prev, float *dz_out, const float *rec, const float *theta2,
+                            const float *mu_prev, float *dz_out, const NodeInfo &ni, const float *theta2,
                             float *dc_part, float *d2_part, const HubTable &ht, const float *hub_sum) {
     const long n_vrows = (long)N * S;
     const bool node = (S % 16) == 0, mask = maskT != nullptr;
 #define S2V_LAUNCH_BWD_W(PP, NODE, MASK, WW)                                                                        \
     k_bwd_round<PP, NODE, MASK, WW><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, rowend, colidx, wagg,     \
                                                                    dz_in, maskT, sc.dg, sc.glo, sc.ghi, mu_prev, dz_out, \
-                                                                   rec, theta2, dc_part, d2_part, ht, hub_sum)
+                                                                   ni, theta2, dc_part, d2_part, ht, hub_sum)
 #define S2V_LAUNCH_BWD(PP, NODE, MASK)                    \
     do {                                                  \
         if (wagg) S2V_LAUNCH_BWD_W(PP, NODE, MASK, true);     \
@@ -480,7 +483,7 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
                                                         const float *__restrict__ da,
                                                         const float *__restrict__ theta2,
                                                         const float *__restrict__ mu_prev, float *__restrict__ dz_out,
-                                                        const float *__restrict__ rec, float *__restrict__ dc_part,
+                                                        NodeInfo ni, float *__restrict__ dc_part,
                                                         float *__restrict__ d2_part) {
     constexpr int SLOTS = 256 / P;
     __shared__ float g[P], w[P];
@@ -508,10 +511,10 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
         const float wa = wagg ? wagg[idx] : 1.f;     // G_u += w_au g_s with a weighted sum
         const float d = mprev > 0.f ? wa * w[j] : 0.f;
         if (dz_out) dz_out[off] += d;
-        const float4 q = ld4(rec + ((size_t)u * S + s) * 4);
-        cx += q.z * d;
-        cp += q.x * d;
-        cn += q.y * d;
+        const float3 q = ni.get(u, s);
+        cx += q.x * d;
+        cp += q.y * d;
+        cn += q.z * d;
         msum += wa * mprev;
     }
     red[0][slot][j] = cx; red[1][slot][j] = cp; red[2][slot][j] = cn; red[3][slot][j] = msum;
@@ -539,15 +542,15 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
 hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                                  const int32_t *colidx, const float *wagg,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
-                                 const float *theta2, const float *mu_prev, float *dz_out, const float *rec,
+                                 const float *theta2, const float *mu_prev, float *dz_out, const NodeInfo &ni,
                                  float *dc_part, float *d2_part) {
     const dim3 grid(kFixSplit, S);
     if (p == 32)
         k_bwd_action_fix<32><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, wagg, action, maskT, sc.da, theta2, mu_prev,
-                                                   dz_out, rec, dc_part, d2_part);
+                                                   dz_out, ni, dc_part, d2_part);
     else
         k_bwd_action_fix<64><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, wagg, action, maskT, sc.da, theta2, mu_prev,
-                                                   dz_out, rec, dc_part, d2_part);
+                                                   dz_out, ni, dc_part, d2_part);
     return hipGetLastError();
 }
 

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "internal.h"
+
 namespace s2v {
 
 constexpr int kWaves = 4;         // waves per workgroup
@@ -50,19 +52,33 @@ struct MemRow {
 
 // Row (u, s) of the round-1 embedding, recomputed instead of read: mu^0 = 0 makes
 // mu^1_u = relu(theta1 x_u + s+_u q+ + s-_u q-) a function of three scalars per (node, state),
-// kept as one 16-byte record rec[u][s] = {s+, s-, x, 0}.  An all-zero record gives a zero row.
+// read from the node's record.  A record of zeros gives a zero row.
 struct Mu1Row {
-    const float *__restrict__ rec;
-    int S;
+    NodeInfo ni;
     int s;
     float4 t1, qp, qn;  // theta1, q+, q- at this lane's four columns
     __device__ __forceinline__ float4 operator()(int u) const {
-        const float4 r = ld4(rec + ((size_t)u * S + s) * 4);
+        const float3 r = ni.get(u, s);
         float4 o;
-        o.x = fmaxf(r.z * t1.x + r.x * qp.x + r.y * qn.x, 0.f);
-        o.y = fmaxf(r.z * t1.y + r.x * qp.y + r.y * qn.y, 0.f);
-        o.z = fmaxf(r.z * t1.z + r.x * qp.z + r.y * qn.z, 0.f);
-        o.w = fmaxf(r.z * t1.w + r.x * qp.w + r.y * qn.w, 0.f);
+        o.x = fmaxf(r.x * t1.x + r.y * qp.x + r.z * qn.x, 0.f);
+        o.y = fmaxf(r.x * t1.y + r.y * qp.y + r.z * qn.y, 0.f);
+        o.z = fmaxf(r.x * t1.z + r.y * qp.z + r.z * qn.z, 0.f);
+        o.w = fmaxf(r.x * t1.w + r.y * qp.w + r.z * qn.w, 0.f);
+        return o;
+    }
+};
+
+// The same for S = 1, where a node's record is the 16 bytes {x, s+, s-, pad}: one load.
+struct Mu1RowSingle {
+    const float *__restrict__ base;
+    float4 t1, qp, qn;
+    __device__ __forceinline__ float4 operator()(int u) const {
+        const float4 r = ld4(base + (size_t)u * 4);
+        float4 o;
+        o.x = fmaxf(r.x * t1.x + r.y * qp.x + r.z * qn.x, 0.f);
+        o.y = fmaxf(r.x * t1.y + r.y * qp.y + r.z * qn.y, 0.f);
+        o.z = fmaxf(r.x * t1.z + r.y * qp.z + r.z * qn.z, 0.f);
+        o.w = fmaxf(r.x * t1.w + r.y * qp.w + r.z * qn.w, 0.f);
         return o;
     }
 };
@@ -222,13 +238,15 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict_
     return total;
 }
 
-// Node mode with the round-1 rows recomputed from the records rec[u][s0 .. s0+15] (see Mu1Row).
-template <int P, bool W = false>
-__device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restrict__ rec, int S, int s0,
-                                                            const float *__restrict__ theta1,
-                                                            const float *__restrict__ qvec,
-                                                            const int *__restrict__ colidx,
-                                                            const float *__restrict__ wagg, int b, int e, int lane) {
+// Node mode with the round-1 rows recomputed from the neighbours' records (see Mu1Row): per
+// neighbour the x of the 16 states and its edge sums, one pair per node (SHARED) or per state.
+template <int P, bool W, bool SHARED>
+__device__ __forceinline__ NodeAcc<P> gather_node_block_mu1_impl(const NodeInfo &ni, int s0,
+                                                                 const float *__restrict__ theta1,
+                                                                 const float *__restrict__ qvec,
+                                                                 const int *__restrict__ colidx,
+                                                                 const float *__restrict__ wagg, int b, int e,
+                                                                 int lane) {
     constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
     NodeAcc<P> total, acc;
 #pragma unroll
@@ -243,28 +261,38 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
         if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-        // four neighbours per step: their records are fetched together
+        // four neighbours per step: their scalars are fetched together
         for (int j = 0; j < cnt; j += 4) {
-            float4 r[4][NC];
+            float xs[4][NC], sp[4][SHARED ? 1 : NC], sn[4][SHARED ? 1 : NC];
             float wk[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int jj = min(j + k, cnt - 1);   // past the end: re-read the last records, dropped below
-                const float *ru = rec + ((size_t)__builtin_amdgcn_readlane(cols, jj) * S + srow) * 4;
+                const int jj = min(j + k, cnt - 1);   // past the end: re-read the last record, dropped below
+                const float *r = ni.node(__builtin_amdgcn_readlane(cols, jj));
                 wk[k] = W ? readlane_f(wv, jj) : 1.f;
 #pragma unroll
-                for (int c = 0; c < NC; ++c) r[k][c] = ld4(ru + (size_t)c * RPI * 4);
+                for (int c = 0; c < NC; ++c) xs[k][c] = r[srow + c * RPI];
+                if (SHARED) {
+                    sp[k][0] = r[ni.sp_off];
+                    sn[k][0] = r[ni.sn_off];
+                } else {
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        sp[k][SHARED ? 0 : c] = r[ni.sp_off + srow + c * RPI];
+                        sn[k][SHARED ? 0 : c] = r[ni.sn_off + srow + c * RPI];
+                    }
+                }
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if (j + k < cnt) {
 #pragma unroll
                     for (int c = 0; c < NC; ++c) {
-                        const float4 q = r[k][c];
-                        const float4 m = make_float4(fmaxf(q.z * t1.x + q.x * qp.x + q.y * qn.x, 0.f),
-                                                     fmaxf(q.z * t1.y + q.x * qp.y + q.y * qn.y, 0.f),
-                                                     fmaxf(q.z * t1.z + q.x * qp.z + q.y * qn.z, 0.f),
-                                                     fmaxf(q.z * t1.w + q.x * qp.w + q.y * qn.w, 0.f));
+                        const float p_ = sp[k][SHARED ? 0 : c], n_ = sn[k][SHARED ? 0 : c], x_ = xs[k][c];
+                        const float4 m = make_float4(fmaxf(x_ * t1.x + p_ * qp.x + n_ * qn.x, 0.f),
+                                                     fmaxf(x_ * t1.y + p_ * qp.y + n_ * qn.y, 0.f),
+                                                     fmaxf(x_ * t1.z + p_ * qp.z + n_ * qn.z, 0.f),
+                                                     fmaxf(x_ * t1.w + p_ * qp.w + n_ * qn.w, 0.f));
                         acc.a[c] = acc4<W>(acc.a[c], m, wk[k]);
                     }
                 }
@@ -276,8 +304,16 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const float *__restr
     return total;
 }
 
-// Node mode over relu-mask words (see BitsRow): per column, the number of neighbours of the node
-// whose entry is positive, for the 16 states s0 .. s0+15.
+template <int P, bool W = false>
+__device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const NodeInfo &ni, int s0,
+                                                            const float *__restrict__ theta1,
+                                                            const float *__restrict__ qvec,
+                                                            const int *__restrict__ colidx,
+                                                            const float *__restrict__ wagg, int b, int e, int lane) {
+    if (ni.ss == 0) return gather_node_block_mu1_impl<P, W, true>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+    return gather_node_block_mu1_impl<P, W, false>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+}
+
 // Weighted form of gather_node_block_bits: per column, the sum of the weights of the neighbours whose
 // entry is positive (per-chunk accumulators folded into a running total, as in the other gathers).
 template <int P>
@@ -324,39 +360,61 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_bits_w(const unsigned lo
     return total;
 }
 
+// `stage` is wave-private LDS of at least kBitsStageBytes bytes.  The words of up to 32 neighbours
+// are fetched at once (one wave-wide load brings the 16 consecutive state words of 4 neighbours),
+// parked in `stage`, and each lane then counts its four columns for its NC states; counts are
+// integers, so the order of the neighbours does not matter.
+constexpr int kBitsStageBytes = 32 * 16 * 8;
+
 template <int P>
 __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long long *__restrict__ mask, int S, int s0,
-                                                             const int *__restrict__ colidx, int b, int e, int lane) {
+                                                             const int *__restrict__ colidx, int b, int e, int lane,
+                                                             unsigned *stage) {
     constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
     int4 cnt[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) cnt[c] = make_int4(0, 0, 0, 0);
     const int shift = 4 * (lane % LPR);
-    const int srow = s0 + lane / LPR;
+    const int srow = lane / LPR;                 // this lane's state within a block of RPI states
+    const int q = lane >> 4, st = lane & 15;     // load role: neighbour slot, state
+    const int half = shift >> 5, sh = shift & 31;
     for (int base = b; base < e; base += 64) {
         const int n = min(64, e - base);
         const int cols = (lane < n) ? colidx[base + lane] : 0;
-        // four neighbours per step keeps 4 * NC independent loads in flight
-        for (int j = 0; j < n; j += 4) {
-            unsigned nib[4][NC];
+        for (int j0 = 0; j0 < n; j0 += 32) {
+            const int m = min(32, n - j0);       // neighbours in this batch
+            unsigned long long wv[8];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int jj = min(j + k, n - 1);   // past the end: re-read the last word, masked below
-                const unsigned long long *w = mask + (size_t)__builtin_amdgcn_readlane(cols, jj) * S + srow;
-#pragma unroll
-                for (int c = 0; c < NC; ++c) nib[k][c] = (unsigned)(w[c * RPI] >> shift);
+            for (int k = 0; k < 8; ++k) {
+                const int jj = j0 + min(4 * k + q, m - 1);   // past the end: a valid word again, never counted
+                wv[k] = mask[(size_t)__shfl(cols, jj) * S + s0 + st];
             }
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const unsigned live = (j + k < n) ? 0xFu : 0u;
+            for (int k = 0; k < 8; ++k) {
+                stage[((4 * k + q) * 16 + st) * 2] = (unsigned)wv[k];
+                stage[((4 * k + q) * 16 + st) * 2 + 1] = (unsigned)(wv[k] >> 32);
+            }
+            __builtin_amdgcn_wave_barrier();
+            // four columns of one state packed as four byte counters (at most 32 per batch)
+            unsigned packed[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) packed[c] = 0u;
+            for (int i = 0; i < m; ++i) {
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
-                    const unsigned b4 = nib[k][c] & live;
-                    cnt[c].x += (int)(b4 & 1u);
-                    cnt[c].y += (int)((b4 >> 1) & 1u);
-                    cnt[c].z += (int)((b4 >> 2) & 1u);
-                    cnt[c].w += (int)((b4 >> 3) & 1u);
+                    const unsigned w32 = stage[((i * 16) + c * RPI + srow) * 2 + half];
+                    const unsigned nib = (w32 >> sh) & 0xFu;
+                    // bit t of the nibble -> bit 8 * t
+                    packed[c] += __umul24(nib, 0x00204081u) & 0x01010101u;
                 }
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                cnt[c].x += (int)(packed[c] & 0xFFu);
+                cnt[c].y += (int)((packed[c] >> 8) & 0xFFu);
+                cnt[c].z += (int)((packed[c] >> 16) & 0xFFu);
+                cnt[c].w += (int)(packed[c] >> 24);
             }
         }
     }

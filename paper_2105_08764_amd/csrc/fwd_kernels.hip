@@ -61,13 +61,13 @@ hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *
 
 // ------------------------------------------------------------------------------------------
 // Round 1: mu^0 = 0 (Alg. 1), so mu^1_v = relu(theta1 x_v + s+_v q+ + s-_v q-): no neighbour sum.
-// One thread per float4 of the [N][S][p] output; the scalars come from the records rec[v][s].
+// One thread per float4 of the [N][S][p] output; the scalars come from the node records.
 // x_res != NULL (per-state residual graphs): a row whose node is in that state's solution is an
 // isolated node; its embedding is relu(theta1 x) in the final round and is stored as zero in
 // every earlier round, so that nobody's neighbour sum sees it.
 // ------------------------------------------------------------------------------------------
 template <int P>
-__global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, const float *__restrict__ rec,
+__global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, NodeInfo ni,
                                                 const float *__restrict__ x_res, int last,
                                                 const float *__restrict__ theta1, const float *__restrict__ qvec,
                                                 float *__restrict__ mu_out) {
@@ -76,12 +76,12 @@ __global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, cons
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
         const long r = i / LPR;
         const int c = (int)(i - r * LPR) * 4;
-        const float4 q = ld4(rec + r * 4);
-        float xs = q.z;
-        const float sp = q.x, sn = q.y;
+        const int v = (int)(r / S), s = (int)(r - (long)v * S);
+        const float3 q = ni.get(v, s);
+        float xs = q.x;
+        const float sp = q.y, sn = q.z;
         float keep = 1.f;
         if (x_res) {
-            const int v = (int)(r / S), s = (int)(r - (long)v * S);
             const float xo = x_res[(size_t)s * N + v];
             if (xo != 0.f) { xs = xo; keep = last ? 1.f : 0.f; }
         }
@@ -95,94 +95,101 @@ __global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, cons
     }
 }
 
-hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *rec, const float *x_res, bool last,
+hipError_t launch_round1(hipStream_t st, int p, int N, int S, const NodeInfo &ni, const float *x_res, bool last,
                          const float *theta1, const float *qvec, float *mu_out) {
     const long n_vrows = (long)N * S;
     if (n_vrows == 0) return hipSuccess;
     const long total = n_vrows * (p / 4);
     const int grid = (int)min((total + 255) / 256, (long)(256 * 32));
-    if (p == 32) k_round1<32><<<grid, 256, 0, st>>>(n_vrows, N, S, rec, x_res, last ? 1 : 0, theta1, qvec, mu_out);
-    else k_round1<64><<<grid, 256, 0, st>>>(n_vrows, N, S, rec, x_res, last ? 1 : 0, theta1, qvec, mu_out);
+    if (p == 32) k_round1<32><<<grid, 256, 0, st>>>(n_vrows, N, S, ni, x_res, last ? 1 : 0, theta1, qvec, mu_out);
+    else k_round1<64><<<grid, 256, 0, st>>>(n_vrows, N, S, ni, x_res, last ? 1 : 0, theta1, qvec, mu_out);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
-// Per-(node, state) scalars gathered in one place: rec[v][s] = {s+_v, s-_v, x_s[v], 0}, 16 bytes.
-// One such record per neighbour is all the second round needs (see Mu1Row), and every kernel
-// reads its own row's scalars here.
+// The scalar records (see NodeInfo) when all states share the graph: per node the S values of x,
+// then s+ and s- once.  A neighbour's record is all the second round needs (see Mu1Row), and
+// every kernel reads its own rows' scalars here.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, const float *__restrict__ x,
+__global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const float *__restrict__ x,
                                                   const float *__restrict__ s_pos, const float *__restrict__ s_neg,
-                                                  float *__restrict__ rec) {
-    const long total = (long)N * S;
+                                                  float *__restrict__ info) {
+    const long total = (long)N * ni;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
-        const int v = (int)(i / S), s = (int)(i - (long)v * S);
-        st4(rec + i * 4, make_float4(s_pos[v], s_neg[v], x[(size_t)s * N + v], 0.f));
+        const int v = (int)(i / ni), c = (int)(i - (long)v * ni);
+        float o = 0.f;
+        if (c < S) o = x[(size_t)c * N + v];
+        else if (c == S) o = s_pos[v];
+        else if (c == S + 1) o = s_neg[v];
+        info[i] = o;
     }
 }
 
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
-                           float *rec) {
+                           float *info) {
     if (N == 0) return hipSuccess;
-    const long total = (long)N * S;
-    k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, x, s_pos, s_neg, rec);
+    const int ni = make_nodeinfo(info, S, false).ni;
+    const long total = (long)N * ni;
+    k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
 // Records for per-state residual graphs (what the paper's Tuples2Graphs builds explicitly, Alg. 4):
-// in state s every edge with an endpoint in that state's solution (x_s != 0) is absent.  So
-//   rec[v][s] = {0, 0, 0, 1}                                   if x_s[v] != 0 (isolated, contributes nothing)
-//   rec[v][s] = {sum max(w,0), sum max(-w,0), x_s[v], 0}        over the neighbours u with x_s[u] == 0, else.
-// Pass 1 writes x and the flag, pass 2 the edge sums of ordinary rows (one thread per (v, s)),
-// pass 3 those of the long rows (one wave per (long row, s)).
+// in state s every edge with an endpoint in that state's solution (x_s != 0) is absent.  So for a
+// solution node all three scalars of that state are zero (isolated, and its recomputed round-1 row
+// is zero for its neighbours); any other node keeps x (= 0) and gets
+//   s+ = sum max(w, 0),  s- = sum max(-w, 0)   over its neighbours u with x_s[u] == 0.
+// Pass 1 copies x into the records and clears the sums, pass 2 writes the sums of ordinary rows
+// (one thread per (v, s); a neighbour is in the solution when its x in the records is non-zero),
+// pass 3 those of the long rows (one wave per (long row, s)), pass 4 clears x of the solution nodes.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_stateinfo_flags(int N, int S, const float *__restrict__ x,
-                                                         float *__restrict__ rec) {
-    const long total = (long)N * S;
+__global__ __launch_bounds__(256) void k_stateinfo_x(int N, int S, int ni, const float *__restrict__ x,
+                                                     float *__restrict__ info) {
+    const long total = (long)N * ni;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
-        const int v = (int)(i / S), s = (int)(i - (long)v * S);
-        const float xs = x[(size_t)s * N + v];
-        st4(rec + i * 4, xs != 0.f ? make_float4(0.f, 0.f, 0.f, 1.f) : make_float4(0.f, 0.f, xs, 0.f));
+        const int v = (int)(i / ni), c = (int)(i - (long)v * ni);
+        info[i] = c < S ? x[(size_t)c * N + v] : 0.f;
     }
 }
 
-__global__ __launch_bounds__(256) void k_stateinfo_sums(int N, int S, const int32_t *__restrict__ rowptr,
+__global__ __launch_bounds__(256) void k_stateinfo_sums(int N, int S, int ni, const int32_t *__restrict__ rowptr,
                                                         const int32_t *__restrict__ rowend,
                                                         const int32_t *__restrict__ colidx, const float *__restrict__ w,
-                                                        float *__restrict__ rec) {
+                                                        float *__restrict__ info) {
     const long total = (long)N * S;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
         const int v = (int)(i / S), s = (int)(i - (long)v * S);
         const int b = rowptr[v], e = rowend[v];
-        if (e - b > kHubDegree || rec[i * 4 + 3] != 0.f) continue;   // long rows: pass 3; solution nodes: done
+        float *mine = info + (size_t)v * ni;
+        if (e - b > kHubDegree || mine[s] != 0.f) continue;   // long rows: pass 3; solution nodes keep zero sums
         double sp = 0.0, sn = 0.0;
         for (int j = b; j < e; ++j) {
-            if (rec[((size_t)colidx[j] * S + s) * 4 + 3] != 0.f) continue;   // neighbour in the solution
+            if (info[(size_t)colidx[j] * ni + s] != 0.f) continue;   // neighbour in the solution
             const float wj = w ? w[j] : 1.f;
             sp += (double)fmaxf(wj, 0.f);
             sn += (double)fmaxf(-wj, 0.f);
         }
-        rec[i * 4] = (float)sp;
-        rec[i * 4 + 1] = (float)sn;
+        mine[S + s] = (float)sp;
+        mine[2 * S + s] = (float)sn;
     }
 }
 
-__global__ __launch_bounds__(256) void k_stateinfo_hubs(int S, HubTable ht, const int32_t *__restrict__ rowptr,
+__global__ __launch_bounds__(256) void k_stateinfo_hubs(int S, int ni, HubTable ht, const int32_t *__restrict__ rowptr,
                                                         const int32_t *__restrict__ rowend,
                                                         const int32_t *__restrict__ colidx, const float *__restrict__ w,
-                                                        float *__restrict__ rec) {
+                                                        float *__restrict__ info) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long items = (long)ht.n_hubs * S;
     for (long it = (long)blockIdx.x * 4 + wave; it < items; it += (long)gridDim.x * 4) {
         const int h = (int)(it / S), s = (int)(it - (long)h * S);
         const int v = ht.hub_rows[h];
         const int b = rowptr[v], e = rowend[v];
-        const size_t mine = ((size_t)v * S + s) * 4;
-        if (e - b <= kHubDegree || rec[mine + 3] != 0.f) continue;   // wave-uniform
+        float *mine = info + (size_t)v * ni;
+        if (e - b <= kHubDegree || mine[s] != 0.f) continue;   // wave-uniform
         double sp = 0.0, sn = 0.0;
         for (int j = b + lane; j < e; j += 64) {
-            if (rec[((size_t)colidx[j] * S + s) * 4 + 3] != 0.f) continue;
+            if (info[(size_t)colidx[j] * ni + s] != 0.f) continue;
             const float wj = w ? w[j] : 1.f;
             sp += (double)fmaxf(wj, 0.f);
             sn += (double)fmaxf(-wj, 0.f);
@@ -193,29 +200,40 @@ __global__ __launch_bounds__(256) void k_stateinfo_hubs(int S, HubTable ht, cons
             sn += __shfl_xor(sn, m);
         }
         if (lane == 0) {
-            rec[mine] = (float)sp;
-            rec[mine + 1] = (float)sn;
+            mine[S + s] = (float)sp;
+            mine[2 * S + s] = (float)sn;
         }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_stateinfo_clear_x(int N, int S, int ni, float *__restrict__ info) {
+    const long total = (long)N * S;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int v = (int)(i / S), s = (int)(i - (long)v * S);
+        info[(size_t)v * ni + s] = 0.f;   // a live node has x = 0 already, a solution node gets it now
     }
 }
 
 hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTable &ht, const int32_t *rowptr,
                                      const int32_t *rowend, const int32_t *colidx, const float *w, const float *x,
-                                     float *rec) {
+                                     float *info) {
     if (N == 0) return hipSuccess;
+    const int ni = make_nodeinfo(info, S, true).ni;
     const long total = (long)N * S;
     const int grid = (int)min((total + 255) / 256, (long)65536);
-    k_stateinfo_flags<<<grid, 256, 0, st>>>(N, S, x, rec);
+    k_stateinfo_x<<<(int)min(((long)N * ni + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, info);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_stateinfo_sums<<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, w, rec);
+    k_stateinfo_sums<<<grid, 256, 0, st>>>(N, S, ni, rowptr, rowend, colidx, w, info);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (ht.n_hubs > 0) {
         const long items = (long)ht.n_hubs * S;
-        k_stateinfo_hubs<<<(int)min((items + 3) / 4, (long)65536), 256, 0, st>>>(S, ht, rowptr, rowend, colidx, w, rec);
-        e = hipGetLastError();
+        k_stateinfo_hubs<<<(int)min((items + 3) / 4, (long)65536), 256, 0, st>>>(S, ni, ht, rowptr, rowend, colidx, w,
+                                                                                 info);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    return e;
+    k_stateinfo_clear_x<<<grid, 256, 0, st>>>(N, S, ni, info);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
@@ -225,19 +243,25 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 // (u, s) for u in N(v).  A wave owns 16 consecutive rows at a time: it gathers their sums into
 // its own LDS tile, multiplies the tile by theta2 and writes the 16 output rows.
 //   NODE: S is a multiple of 16, so a tile is 16 states of one node (contiguous 1 KB loads).
-//   MU1 : this is round 2; the neighbours' round-1 rows are recomputed from info[] instead of read.
+//   MU1 : this is round 2; the neighbours' round-1 rows are recomputed from their records instead of read.
 //   GSUM: also emit this workgroup's column sums of the output (S == 1, one graph) to
 //         gpart[blockIdx.x][P]: the first stage of the graph sum of Alg. 2 line 4.
 //   W   : the neighbour sum weights each neighbour by its entry of wagg (the reading of the
 //         aggregation step of Alg. 1 as a product with the weighted adjacency).
 // ------------------------------------------------------------------------------------------
 template <int P, bool NODE, bool MU1, bool GSUM, bool W>
-__global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const int32_t *__restrict__ rowptr,
+#ifndef S2V_ROUND_OCC
+#define S2V_ROUND_OCC 4
+#endif
+#ifndef S2V_ROUND2_OCC
+#define S2V_ROUND2_OCC 4
+#endif
+__global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) void k_round(int n_vrows, int S, const int32_t *__restrict__ rowptr,
                                                     const int32_t *__restrict__ rowend,
                                                     const int32_t *__restrict__ colidx,
                                                     const float *__restrict__ wagg,
                                                     const float *__restrict__ mu_in, float *__restrict__ mu_out,
-                                                    const float *__restrict__ info,
+                                                    NodeInfo info,
                                                     const float *__restrict__ theta1,
                                                     const float *__restrict__ theta2,
                                                     const float *__restrict__ qvec, float *__restrict__ gpart,
@@ -263,8 +287,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const
     }
     Mu1Row mu1;
     if (MU1) {
-        mu1.rec = info;
-        mu1.S = S;
+        mu1.ni = info;
         mu1.s = 0;
         mu1.t1 = ld4(theta1 + 4 * li);
         mu1.qp = ld4(qvec + 4 * li);
@@ -282,9 +305,9 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const
         const int s = valid ? r - v * S : 0;
         const int rb = valid ? rowptr[v] : 0;
         const int re = valid ? rowend[v] : 0;
-        const float4 mine = valid ? ld4(info + (size_t)r * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-        const float sp = mine.x, sn = mine.y;
-        float xs = mine.z;
+        const float3 mine = valid ? info.get(v, s) : make_float3(0.f, 0.f, 0.f);
+        const float sp = mine.y, sn = mine.z;
+        float xs = mine.x;
         // Per-state residual graphs: a row whose node is in its state's solution is an isolated node.
         // Its record is zero (so it adds nothing to its neighbours); here it gets relu(theta1 x) in the
         // final round and zero before, whatever its (ignored) neighbour sum is.
@@ -303,7 +326,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
                 acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
             } else {
-                acc = MU1 ? gather_node_block_mu1<P, W>(info, S, s0, theta1, qvec, colidx, wagg, b, e, lane)
+                acc = MU1 ? gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane)
                           : gather_node_block<P, W>(mu_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
             }
             store_node_block<P>(tile, acc, lane);
@@ -325,8 +348,13 @@ __global__ __launch_bounds__(kThreads, 4) void k_round(int n_vrows, int S, const
                     const int h = hub_index(ht.hub_rows, ht.n_hubs, __shfl(v, i));
                     a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
                 } else if (MU1) {
-                    mu1.s = si;
-                    a = gather_row_sum<P, W>(mu1, colidx, wagg, b, e, cols, lane);
+                    if (S == 1) {
+                        const Mu1RowSingle one{info.base, mu1.t1, mu1.qp, mu1.qn};
+                        a = gather_row_sum<P, W>(one, colidx, wagg, b, e, cols, lane);
+                    } else {
+                        mu1.s = si;
+                        a = gather_row_sum<P, W>(mu1, colidx, wagg, b, e, cols, lane);
+                    }
                 } else {
                     const MemRow mem{mu_in, row_stride, (size_t)si * P + 4 * li};
                     a = gather_row_sum<P, W>(mem, colidx, wagg, b, e, cols, lane);
@@ -386,7 +414,7 @@ int round_grid(long n_vrows) {
 template <int P>
 static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                                  const int32_t *colidx, const float *wagg,
-                                 const float *mu_in, float *mu_out, const float *info, const float *theta1,
+                                 const float *mu_in, float *mu_out, const NodeInfo &info, const float *theta1,
                                  const float *theta2, const float *qvec, bool from_scalars, float *gpart,
                                  const HubTable &ht, const float *hub_sum, const float *x_res, bool last) {
     const long n_vrows = (long)N * S;
@@ -418,7 +446,8 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
 
 // gpart != NULL asks for the fused column sums (only legal for S == 1 and a single graph).
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                        const int32_t *colidx, const float *wagg, const float *mu_in, float *mu_out, const float *info, const float *theta1,
+                        const int32_t *colidx, const float *wagg, const float *mu_in, float *mu_out, const NodeInfo &info,
+                        const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
                         const float *hub_sum, const float *x_res, bool last) {
     if ((long)N * S == 0) return hipSuccess;
@@ -440,12 +469,13 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
                                                           const int32_t *__restrict__ colidx,
                                                           const float *__restrict__ wagg,
                                                           const float *__restrict__ src,
-                                                          const float *__restrict__ info,
+                                                          NodeInfo info,
                                                           const float *__restrict__ theta1,
                                                           const float *__restrict__ qvec,
                                                           const unsigned long long *__restrict__ mask,
                                                           float *__restrict__ partial) {
     using G = Geo<P>;
+    __shared__ __attribute__((aligned(16))) unsigned bits_stage[(NODE && SRC == 2) ? kWaves * kBitsStageBytes / 4 : 4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane % G::LPR;
     const int bpn = NODE ? S / 16 : S;  // blocks per node
@@ -457,10 +487,11 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
         if (NODE) {
             const int s0 = blk * 16;
             NodeAcc<P> acc;
-            if (SRC == 1) acc = gather_node_block_mu1<P, W>(info, S, s0, theta1, qvec, colidx, wagg, b, e, lane);
+            if (SRC == 1) acc = gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane);
             else if (SRC == 2)
                 acc = W ? gather_node_block_bits_w<P>(mask, S, s0, colidx, wagg, b, e, lane)
-                        : gather_node_block_bits<P>(mask, S, s0, colidx, b, e, lane);
+                        : gather_node_block_bits<P>(mask, S, s0, colidx, b, e, lane,
+                                                    bits_stage + (NODE && SRC == 2 ? wave * (kBitsStageBytes / 4) : 0));
             else acc = gather_node_block<P, W>(src, (size_t)S * P, (size_t)s0 * P, colidx, wagg, b, e, lane);
             float *out = partial + ((size_t)seg * S + s0) * P;
 #pragma unroll
@@ -470,7 +501,7 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
             const int cols = (lane < min(64, e - b)) ? colidx[b + lane] : 0;
             float4 a;
             if (SRC == 1) {
-                Mu1Row mu1{info, S, s, ld4(theta1 + 4 * li), ld4(qvec + 4 * li), ld4(qvec + P + 4 * li)};
+                Mu1Row mu1{info, s, ld4(theta1 + 4 * li), ld4(qvec + 4 * li), ld4(qvec + P + 4 * li)};
                 a = gather_row_sum<P, W>(mu1, colidx, wagg, b, e, cols, lane);
             } else if (SRC == 2) {
                 const BitsRow bits{mask, S, s, 4 * li};
@@ -497,7 +528,7 @@ __global__ __launch_bounds__(256) void k_hub_combine(int L, HubTable ht, const f
 
 hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
                            const int32_t *colidx, const float *wagg, const float *src,
-                           const float *info, const float *theta1, const float *qvec,
+                           const NodeInfo &info, const float *theta1, const float *qvec,
                            const unsigned long long *mask, float *partial, float *hub_sum) {
     if (ht.n_hubs == 0) return hipSuccess;
     const bool node = (S % 16) == 0;

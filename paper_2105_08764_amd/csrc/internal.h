@@ -43,33 +43,74 @@ struct ChunkTable {            // device pointers into the prepared head of the 
     const int32_t *graph_chunk_off;  // [G+1] chunks of graph g are [off[g], off[g+1])
 };
 
+// Per-node scalar records.  Node v owns `ni` consecutive floats:
+//   x_0[v] .. x_{S-1}[v],  then the edge sums s+ and s-,
+// the sums stored once per node (all states live on the same graph: ss = 0) or once per state
+// (per-state residual graphs: ss = 1).  ni is a multiple of 4; for S = 1 the record is the 16 bytes
+// {x, s+, s-, pad}.
+struct NodeInfo {
+    const float *__restrict__ base;
+    int ni;       // floats per node
+    int S;
+    int sp_off;   // offset of s+ (of state 0)
+    int sn_off;   // offset of s- (of state 0)
+    int ss;       // stride over states of s+ / s-: 0 or 1
+    __device__ __forceinline__ const float *node(int v) const { return base + (size_t)v * ni; }
+    __device__ __forceinline__ float x(int v, int s) const { return node(v)[s]; }
+    __device__ __forceinline__ float sp(int v, int s) const { return node(v)[sp_off + s * ss]; }
+    __device__ __forceinline__ float sn(int v, int s) const { return node(v)[sn_off + s * ss]; }
+    // {x, s+, s-} of (v, s)
+    __device__ __forceinline__ float3 get(int v, int s) const {
+        if (S == 1) {
+            const float4 r = *reinterpret_cast<const float4 *>(base + (size_t)v * 4);
+            return make_float3(r.x, r.y, r.z);
+        }
+        const float *r = node(v);
+        return make_float3(r[s], r[sp_off + s * ss], r[sn_off + s * ss]);
+    }
+};
+
+// Floats reserved per node for the records (an upper bound of both layouts).
+inline int nodeinfo_stride(int S) { return 4 * S; }
+inline NodeInfo make_nodeinfo(const float *base, int S, bool per_state) {
+    NodeInfo n;
+    n.base = base;
+    n.S = S;
+    n.sp_off = S;
+    n.sn_off = S + (per_state ? S : 1);
+    n.ss = per_state ? 1 : 0;
+    n.ni = (n.sn_off + (per_state ? S : 1) + 3) / 4 * 4;
+    return n;
+}
+
 // ---- forward (fwd_kernels.hip) ----
 hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const float *w,
                             float *s_pos, float *s_neg);
 hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec);
 // x_res != NULL in the round launchers: per-state residual graphs (x_res is the caller's x [S][N]).
-hipError_t launch_round1(hipStream_t st, int p, int N, int S, const float *rec, const float *x_res, bool last,
+hipError_t launch_round1(hipStream_t st, int p, int N, int S, const NodeInfo &ni, const float *x_res, bool last,
                          const float *theta1, const float *qvec, float *mu_out);
 hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTable &ht, const int32_t *rowptr,
                                      const int32_t *rowend, const int32_t *colidx, const float *w, const float *x,
-                                     float *rec);
-// floats per node of the scalar records rec[v][s] = {s+, s-, x_s, 0}
-inline int nodeinfo_stride(int S) { return 4 * S; }
+                                     float *info /*written in the per-state layout of make_nodeinfo*/);
 // upper bound of the embedding-round grid (also the number of partial rows of its fused graph sum)
-constexpr int kRoundGridMax = 256 * 16;
+#ifndef S2V_ROUND_GRID
+#define S2V_ROUND_GRID (256 * 16)
+#endif
+constexpr int kRoundGridMax = S2V_ROUND_GRID;
 int round_grid(long n_vrows);
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
-                           float *info);
+                           float *info /*written in the shared-sums layout of make_nodeinfo*/);
 // Neighbour sums of the hub rows: hub_sum[h][S][p] = sum over the row of hub h of src[u][s][:]
 // (mask != NULL: counts of set relu-mask bits instead; else src == NULL: the round-1 rows
 // recomputed from info).  partial is [n_segs][S][p] scratch.
 hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
                            const int32_t *colidx, const float *wagg, const float *src,
-                           const float *info, const float *theta1, const float *qvec,
+                           const NodeInfo &ni, const float *theta1, const float *qvec,
                            const unsigned long long *mask, float *partial, float *hub_sum);
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                         const int32_t *colidx, const float *wagg /*NULL: unweighted neighbour sum*/, const float *mu_in,
-                        float *mu_out, const float *info, const float *theta1,
+                        float *mu_out, const NodeInfo &ni, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
                         const float *hub_sum, const float *x_res, bool last);
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum);
@@ -121,28 +162,28 @@ struct BwdScratch {
     float *d2_part;     // [d2_rows][p][p]   partial sums of G (x) mu
     float *dvec;        // [3][p] reduced dtheta1, dq+, dq-
     float *red_tmp;     // [ceil(max rows / 64)][max(3p, p*p)] second level of the final reductions
-    float *rec;         // [N][S][4] per-(node, state) scalar records {s+, s-, x, flag}
+    float *rec;         // per-node scalar records (see NodeInfo), nodeinfo_stride(S) floats per node
 };
 hipError_t launch_bwd_head(hipStream_t st, int p, int N, int S, int G, const int32_t *graph_off, const float *theta5,
                            const float *theta6, const float *theta7, const float *muT, const float *gsum,
                            const int32_t *action, const float *target, const BwdScratch &sc, float *q_pred);
 hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch &sc, float *loss, float *d5, float *d6,
                                   float *d7);
-hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const float *rec, const float *x_res,
+hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const NodeInfo &ni, const float *x_res,
                             const int32_t *action, const BwdScratch &sc, unsigned long long *mask /*[N][S] or NULL*/,
                             float *dc_part /*[kBwdHeadGrid][3][p]*/);
 // maskT != NULL selects the first reversed round (t = T), which reads relu-mask words instead of dz_in.
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                             const int32_t *colidx, const float *wagg, const float *dz_in,
                             const unsigned long long *maskT, const BwdScratch &sc,
-                            const float *mu_prev, float *dz_out /*may be NULL*/, const float *rec, const float *theta2,
+                            const float *mu_prev, float *dz_out /*may be NULL*/, const NodeInfo &ni, const float *theta2,
                             float *dc_part /*[kBwdGrid][3][p]*/, float *d2_part /*[kBwdGrid][p][p]*/,
                             const HubTable &ht, const float *hub_sum);
 hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                                  const int32_t *colidx, const float *wagg,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
                                  const float *theta2, const float *mu_prev, float *dz_out /*may be NULL*/,
-                                 const float *rec, float *dc_part /*[S*kFixSplit][3][p]*/,
+                                 const NodeInfo &ni, float *dc_part /*[S*kFixSplit][3][p]*/,
                                  float *d2_part /*[S*kFixSplit][p][p]*/);
 hipError_t launch_bwd_finish(hipStream_t st, int p, int dc_rows, int d2_rows, const BwdScratch &sc, const float *theta3,
                              const float *theta4, float *d1, float *d2, float *d3, float *d4);
