@@ -275,16 +275,14 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
     const int li = lane % G::LPR;
     const int jl = lane & 15, gl = lane >> 4;
 
+    // theta1, q+, q- of the epilogue live in LDS, not in registers, while a tile is gathered
+    __shared__ float lds_c[3 * P];
     stage_matrix_lds<P>(lds_b, theta2, false);
+    for (int i = threadIdx.x; i < 3 * P; i += kThreads) lds_c[i] = i < P ? theta1[i] : qvec[i - P];
     __syncthreads();
-    float t1[G::CB], qp[G::CB], qn[G::CB], csum[G::CB];
+    float csum[G::CB];
 #pragma unroll
-    for (int cb = 0; cb < G::CB; ++cb) {
-        t1[cb] = theta1[16 * cb + jl];
-        qp[cb] = qvec[16 * cb + jl];
-        qn[cb] = qvec[P + 16 * cb + jl];
-        csum[cb] = 0.f;
-    }
+    for (int cb = 0; cb < G::CB; ++cb) csum[cb] = 0.f;
     Mu1Row mu1;
     if (MU1) {
         mu1.ni = info;
@@ -331,6 +329,19 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
             }
             store_node_block<P>(tile, acc, lane);
         } else {
+            // The long rows of the tile first: their sums are ready in hub_sum, and all lanes fetch
+            // them together (each lane looks up its own row, then RPI rows per wave-wide load).
+            const bool long_mine = re - rb > kHubDegree;
+            if (__builtin_amdgcn_ballot_w64(long_mine) != 0ull) {
+                const int h_mine = long_mine ? hub_index(ht.hub_rows, ht.n_hubs, v) : -1;
+                constexpr int RPI = G::NPL, NC = 16 / RPI;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const int i = c * RPI + lane / G::LPR;
+                    const int hi = __shfl(h_mine, i), si = __shfl(s, i);
+                    if (hi >= 0) st4(tile + i * G::STRIDE + 4 * li, ld4(hub_sum + ((size_t)hi * S + si) * P + 4 * li));
+                }
+            }
             int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
 #pragma unroll 1
@@ -341,13 +352,12 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
                 if (i + 1 < kTileRows) {
                     b_next = __shfl(rb, i + 1);
                     e_next = __shfl(re, i + 1);
-                    cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+                    // long rows need no indices here
+                    cols_next = (e_next - b_next <= kHubDegree && lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
                 }
+                if (e - b > kHubDegree) continue;   // stored by the pass above
                 float4 a;
-                if (e - b > kHubDegree) {
-                    const int h = hub_index(ht.hub_rows, ht.n_hubs, __shfl(v, i));
-                    a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
-                } else if (MU1) {
+                if (MU1) {
                     if (S == 1) {
                         const Mu1RowSingle one{info.base, mu1.t1, mu1.qp, mu1.qn};
                         a = gather_row_sum<P, W>(one, colidx, wagg, b, e, cols, lane);
@@ -372,6 +382,13 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
             acc[cb] = mfma_tile<P>(afrag, load_b_frag_lds<P>(lds_b, cb, lane), acc[cb]);
         }
         // lane (jl, gl) holds rows 4*gl + rr, columns 16*cb + jl
+        float t1[G::CB], qp[G::CB], qn[G::CB];
+#pragma unroll
+        for (int cb = 0; cb < G::CB; ++cb) {
+            t1[cb] = lds_c[16 * cb + jl];
+            qp[cb] = lds_c[P + 16 * cb + jl];
+            qn[cb] = lds_c[2 * P + 16 * cb + jl];
+        }
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
             const int i = 4 * gl + rr;
