@@ -18,6 +18,7 @@ constexpr int kFixSplit = 16;
 // Elements per block of the selection scan / sort passes.
 constexpr int kScanBlock = 2048;
 constexpr int kSortTile = 1024;
+constexpr int kSortFusedMaxBlocks = 512;   // above this the sort uses separate count / scan / scatter kernels
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
@@ -138,7 +139,7 @@ struct SelectScratch {
     uint32_t *blk;      // [2][n_scan_blocks][2]
     uint32_t *keys[2];  // [k] each
     int32_t *ids[2];    // [k] each
-    uint32_t *sort_cnt; // [256][n_sort_blocks]
+    uint32_t *sort_cnt; // [n_sort_blocks][256] ([256][n_sort_blocks] with more than kSortFusedMaxBlocks tiles)
 };
 hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, const float *q, const float *x,
                          const uint8_t *cand, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);

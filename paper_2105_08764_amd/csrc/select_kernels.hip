@@ -160,57 +160,117 @@ hipError_t launch_q_target(hipStream_t st, int N, int S, int G, const int32_t *g
 // ------------------------------------------------------------------------------------------
 // Top-k of one graph.
 //  1. radix select: four 8-bit histogram passes from the top byte find the k-th largest key tau
-//     and how many keys equal to tau are still needed (`need`);
+//     and how many keys equal to tau are still needed (`need`).  No kernel of its own picks the
+//     digit between two passes: every workgroup of the next kernel re-derives it from the finished
+//     histograms (topk_resolve, a 256-bin suffix scan by one wave);
 //  2. index-ordered compaction of {key > tau} and the first `need` nodes with key == tau;
 //  3. stable LSD radix sort of the selected (<= k) entries by key descending; stability keeps
 //     equal scores in ascending node index.
-// state: [0] prefix (tau after pass 3), [1] k still to find, [2] number of candidates,
-//        [3] 1 if candidates < k (take all), [4] count = min(k, candidates)
+// state (written by the scan kernel of step 2 for the kernels after it):
+//   [0] tau, [1] need, [2] number of candidates, [3] 1 if candidates < k (take all),
+//   [4] count = min(k, candidates)
 // ------------------------------------------------------------------------------------------
-__global__ void k_topk_init(uint32_t *__restrict__ hist, uint32_t *__restrict__ state, int k) {
+__global__ void k_topk_init(uint32_t *__restrict__ hist, uint32_t *__restrict__ state) {
     for (int i = threadIdx.x; i < 4 * 256; i += blockDim.x) hist[i] = 0;
-    if (threadIdx.x < 16) state[threadIdx.x] = (threadIdx.x == 1) ? (uint32_t)k : 0u;
+    if (threadIdx.x < 16) state[threadIdx.x] = 0u;
 }
 
-__global__ __launch_bounds__(256) void k_topk_hist(int N, int pass, const float *__restrict__ q,
-                                                   const float *__restrict__ x, const uint8_t *__restrict__ cand,
-                                                   uint32_t *__restrict__ hist, const uint32_t *__restrict__ state) {
-    __shared__ uint32_t h[256];
-    h[threadIdx.x] = 0;
-    __syncthreads();
-    if (state[3] == 0) {
-        const int shift = 24 - 8 * pass;
-        const uint32_t mask_hi = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-        const uint32_t prefix = state[0];
-        for (int v = blockIdx.x * 256 + threadIdx.x; v < N; v += gridDim.x * 256) {
-            if (!is_candidate(x, cand, v)) continue;
-            const uint32_t key = score_key(q[v]);
-            if ((key & mask_hi) == prefix) atomicAdd(&h[(key >> shift) & 255u], 1u);
+struct TopkSel {
+    uint32_t prefix;    // the digits fixed so far, in place
+    uint32_t k_rem;     // entries still to find among the keys that match the prefix
+    uint32_t total;     // number of candidates (known after pass 0)
+    uint32_t take_all;  // fewer candidates than k
+};
+
+// The selection state after `passes` finished histogram passes.  Called by all threads of a
+// workgroup (blockDim.x >= 64); wave 0 computes, `sh` is 4 words of shared memory.
+__device__ __forceinline__ TopkSel topk_resolve(const uint32_t *__restrict__ hist, uint32_t k, int passes,
+                                                uint32_t *sh) {
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        uint32_t prefix = 0, k_rem = k, total = 0, take_all = 0;
+        for (int p = 0; p < passes; ++p) {
+            const uint4 hv = *reinterpret_cast<const uint4 *>(hist + p * 256 + 4 * lane);   // bins 4l .. 4l+3
+            const uint32_t mine = hv.x + hv.y + hv.z + hv.w;
+            uint32_t suf = mine;                                 // sum over the bins of lanes >= l
+#pragma unroll
+            for (int m = 1; m < 64; m <<= 1) {
+                const uint32_t t = __shfl_down(suf, m);
+                if (lane + m < 64) suf += t;
+            }
+            if (p == 0) {
+                total = __shfl(suf, 0);
+                if (total < k_rem) { take_all = 1; break; }
+            }
+            // the digit is the largest d with (sum of bins >= d) >= k_rem; it lies in the highest lane
+            // whose suffix sum reaches k_rem
+            const unsigned long long reach = __ballot(suf >= k_rem) | 1ull;
+            const int ls = 63 - __clzll(reach);
+            uint32_t cum = suf - mine;                           // bins above this lane's four
+            int d = 0;
+            if (cum + hv.w >= k_rem) d = 3;
+            else if (cum + hv.w + hv.z >= k_rem) { d = 2; cum += hv.w; }
+            else if (cum + hv.w + hv.z + hv.y >= k_rem) { d = 1; cum += hv.w + hv.z; }
+            else cum += hv.w + hv.z + hv.y;
+            const uint32_t digit = (uint32_t)__shfl(4 * lane + d, ls);
+            const uint32_t above = __shfl(cum, ls);
+            prefix |= digit << (24 - 8 * p);
+            k_rem -= above;
         }
+        if (lane == 0) { sh[0] = prefix; sh[1] = k_rem; sh[2] = total; sh[3] = take_all; }
+    }
+    __syncthreads();
+    TopkSel r;
+    r.prefix = sh[0]; r.k_rem = sh[1]; r.total = sh[2]; r.take_all = sh[3];
+    return r;
+}
+
+// One count into a shared-memory histogram per active lane, with the lanes that share the digit
+// of the first active lane combined into a single add (twice): scores that agree in their leading
+// bytes would otherwise serialise on one bin.  Must be called by whole waves.
+__device__ __forceinline__ void hist_add(uint32_t *h, bool active, uint32_t digit) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const unsigned long long act = __ballot(active);
+        if (act == 0ull) return;
+        const int leader = __ffsll((long long)act) - 1;
+        const uint32_t d0 = (uint32_t)__shfl((int)digit, leader);
+        const bool same = active && digit == d0;
+        const unsigned long long grp = __ballot(same);
+        if (lane == leader) atomicAdd(&h[d0], (uint32_t)__popcll(grp));
+        if (same) active = false;
+    }
+    if (active) atomicAdd(&h[digit], 1u);
+}
+
+__global__ __launch_bounds__(256) void k_topk_hist(int N, int pass, uint32_t k, const float *__restrict__ q,
+                                                   const float *__restrict__ x, const uint8_t *__restrict__ cand,
+                                                   uint32_t *__restrict__ hist) {
+    __shared__ uint32_t h[256];
+    __shared__ uint32_t sel_sh[4];
+    h[threadIdx.x] = 0;
+    const TopkSel sel = topk_resolve(hist, k, pass, sel_sh);     // includes the barrier after h[] = 0
+    if (sel.take_all) return;
+    const int shift = 24 - 8 * pass;
+    const uint32_t mask_hi = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    // four independent elements per thread and step; few workgroups, because each ends with up to 256
+    // adds to the same global bins
+    for (int base = blockIdx.x * 1024; base < N; base += gridDim.x * 1024) {
+        bool active[4];
+        uint32_t key[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int v = base + j * 256 + threadIdx.x;
+            active[j] = v < N && is_candidate(x, cand, v);
+            key[j] = active[j] ? score_key(q[v]) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            hist_add(h, active[j] && (key[j] & mask_hi) == sel.prefix, (key[j] >> shift) & 255u);
     }
     __syncthreads();
     if (h[threadIdx.x]) atomicAdd(&hist[pass * 256 + threadIdx.x], h[threadIdx.x]);
-}
-
-__global__ void k_topk_pick(int pass, const uint32_t *__restrict__ hist, uint32_t *__restrict__ state) {
-    if (threadIdx.x != 0 || state[3] != 0) return;
-    const uint32_t *h = hist + pass * 256;
-    uint32_t k_rem = state[1];
-    if (pass == 0) {
-        uint32_t total = 0;
-        for (int d = 0; d < 256; ++d) total += h[d];
-        state[2] = total;
-        if (total < k_rem) { state[3] = 1; state[4] = total; return; }
-        state[4] = k_rem;
-    }
-    uint32_t cum = 0;
-    int d = 255;
-    for (; d > 0; --d) {
-        if (cum + h[d] >= k_rem) break;
-        cum += h[d];
-    }
-    state[0] |= (uint32_t)d << (24 - 8 * pass);
-    state[1] = k_rem - cum;
 }
 
 // flags of one node: bit 0 = key > tau (or any candidate when taking all), bit 1 = key == tau
@@ -223,12 +283,14 @@ __device__ __forceinline__ uint32_t sel_flags(const float *__restrict__ q, const
     return key == tau ? 2u : 0u;
 }
 
-__global__ __launch_bounds__(256) void k_topk_scan1(int N, const float *__restrict__ q, const float *__restrict__ x,
-                                                    const uint8_t *__restrict__ cand,
-                                                    const uint32_t *__restrict__ state, uint32_t *__restrict__ blk) {
+__global__ __launch_bounds__(256) void k_topk_scan1(int N, uint32_t k, const float *__restrict__ q,
+                                                    const float *__restrict__ x, const uint8_t *__restrict__ cand,
+                                                    const uint32_t *__restrict__ hist, uint32_t *__restrict__ blk) {
     __shared__ uint32_t sg[4], se[4];
-    const uint32_t tau = state[0];
-    const bool take_all = state[3] != 0;
+    __shared__ uint32_t sel_sh[4];
+    const TopkSel sel = topk_resolve(hist, k, 4, sel_sh);
+    const uint32_t tau = sel.prefix;
+    const bool take_all = sel.take_all != 0;
     const int base = blockIdx.x * kScanBlock + threadIdx.x * 8;
     uint32_t gt = 0, eq = 0, key;
     for (int i = 0; i < 8; ++i) {
@@ -248,12 +310,24 @@ __global__ __launch_bounds__(256) void k_topk_scan1(int N, const float *__restri
     }
 }
 
-// exclusive scan of the per-block (gt, eq) pairs, single workgroup
-__global__ __launch_bounds__(256) void k_topk_scan2(int n_blk, const uint32_t *__restrict__ blk,
-                                                    uint32_t *__restrict__ blk_scan,
-                                                    const uint32_t *__restrict__ state, int32_t *__restrict__ count) {
+// exclusive scan of the per-block (gt, eq) pairs, single workgroup; also publishes the selection
+// state for the kernels that follow
+__global__ __launch_bounds__(256) void k_topk_scan2(int n_blk, uint32_t k, const uint32_t *__restrict__ hist,
+                                                    const uint32_t *__restrict__ blk, uint32_t *__restrict__ blk_scan,
+                                                    uint32_t *__restrict__ state, int32_t *__restrict__ count) {
     __shared__ uint32_t sg[256], se[256];
+    __shared__ uint32_t sel_sh[4];
     const int tid = threadIdx.x;
+    const TopkSel sel = topk_resolve(hist, k, 4, sel_sh);
+    if (tid == 0) {
+        const uint32_t n_sel = sel.take_all ? sel.total : k;
+        state[0] = sel.prefix;
+        state[1] = sel.k_rem;
+        state[2] = sel.total;
+        state[3] = sel.take_all;
+        state[4] = n_sel;
+        count[0] = (int32_t)n_sel;
+    }
     const int per = (n_blk + 255) / 256;
     const int b0 = tid * per, b1 = min(n_blk, b0 + per);
     uint32_t gt = 0, eq = 0;
@@ -267,7 +341,6 @@ __global__ __launch_bounds__(256) void k_topk_scan2(int n_blk, const uint32_t *_
             sg[i] = cg; se[i] = ce;
             cg += tg; ce += te;
         }
-        count[0] = (int32_t)state[4];
     }
     __syncthreads();
     gt = sg[tid]; eq = se[tid];
@@ -392,6 +465,100 @@ __global__ __launch_bounds__(64) void k_sort_scatter(int pass, int n_blk, const 
     }
 }
 
+// ---- the same sort with fewer launches, for up to kSortFusedMaxBlocks tiles --------------------
+// The count table is [tile][256].  k_sort_count writes the plain counts of digit p per tile;
+// k_sort_pass derives its scatter offsets from them inside every workgroup (the per-digit totals
+// and the part of the tiles before its own: the scan kernel folded in).  The last pass writes the
+// result arrays directly.
+__global__ __launch_bounds__(64) void k_sort_count(int pass, const uint32_t *__restrict__ state,
+                                                   const uint32_t *__restrict__ keys, uint32_t *__restrict__ cnt) {
+    __shared__ uint32_t h[256];
+    const int n = (int)state[4];
+    for (int i = threadIdx.x; i < 256; i += 64) h[i] = 0;
+    __syncthreads();
+    const int b = blockIdx.x * kSortTile, e = min(n, b + kSortTile);
+    for (int i = b + threadIdx.x; i < e; i += 64) atomicAdd(&h[((~keys[i]) >> (8 * pass)) & 255u], 1u);
+    __syncthreads();
+    for (int d = threadIdx.x; d < 256; d += 64) cnt[(size_t)blockIdx.x * 256 + d] = h[d];
+}
+
+__global__ __launch_bounds__(64) void k_sort_pass(int pass, int n_blk, int k, const uint32_t *__restrict__ state,
+                                                  const uint32_t *__restrict__ keys_in,
+                                                  const int32_t *__restrict__ ids_in,
+                                                  const uint32_t *__restrict__ cnt_cur, uint32_t *__restrict__ keys_out,
+                                                  int32_t *__restrict__ ids_out, int32_t *__restrict__ idx /*last pass*/,
+                                                  float *__restrict__ val /*last pass*/) {
+    __shared__ uint32_t base[256];
+    const int n = (int)state[4];
+    const int lane = threadIdx.x;
+    // digits 4*lane .. 4*lane+3: totals over all tiles and over the tiles before this one
+    uint4 tot = make_uint4(0, 0, 0, 0), bef = make_uint4(0, 0, 0, 0);
+#pragma unroll 8
+    for (int t = 0; t < n_blk; ++t) {
+        const uint4 c = *reinterpret_cast<const uint4 *>(cnt_cur + (size_t)t * 256 + 4 * lane);
+        tot.x += c.x; tot.y += c.y; tot.z += c.z; tot.w += c.w;
+        if (t < (int)blockIdx.x) { bef.x += c.x; bef.y += c.y; bef.z += c.z; bef.w += c.w; }
+    }
+    const uint32_t mine = tot.x + tot.y + tot.z + tot.w;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        const uint32_t t = __shfl_up(incl, m);
+        if (lane >= m) incl += t;
+    }
+    const uint32_t excl = incl - mine;
+    base[4 * lane] = excl + bef.x;
+    base[4 * lane + 1] = excl + tot.x + bef.y;
+    base[4 * lane + 2] = excl + tot.x + tot.y + bef.z;
+    base[4 * lane + 3] = excl + tot.x + tot.y + tot.z + bef.w;
+    __syncthreads();
+    const int b = blockIdx.x * kSortTile, e = min(n, b + kSortTile);
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    // The workgroup is ONE wave: its LDS operations execute in program order for all lanes, so the
+    // running offsets in base[] need no workgroup barrier (which would also wait for every store of
+    // the step to land); the entries of the next step are fetched while this one is placed.
+    uint32_t key_next = (b + lane < e) ? keys_in[b + lane] : 0u;
+    int32_t id_next = (b + lane < e) ? ids_in[b + lane] : 0;
+    for (int i0 = b; i0 < e; i0 += 64) {
+        const bool valid = i0 + lane < e;
+        const uint32_t key = key_next;
+        const int32_t id = id_next;
+        if (i0 + 64 < e) {
+            const int i = i0 + 64 + lane;
+            key_next = i < e ? keys_in[i] : 0u;
+            id_next = i < e ? ids_in[i] : 0;
+        }
+        const uint32_t digit = ((~key) >> (8 * pass)) & 255u;
+        uint64_t m = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const bool on = (digit >> bit) & 1u;
+            const uint64_t bm = __ballot(on);
+            m &= on ? bm : ~bm;
+        }
+        uint32_t pos = 0;
+        if (valid) pos = base[digit] + (uint32_t)__popcll(m & lt_mask);
+        __builtin_amdgcn_wave_barrier();
+        if (valid) {
+            if (idx) {
+                idx[pos] = id;
+                val[pos] = key_score(key);
+            } else {
+                keys_out[pos] = key;
+                ids_out[pos] = id;
+            }
+            if ((m >> lane) == 1ull) base[digit] += (uint32_t)__popcll(m);  // highest lane of its digit group
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (idx) {   // result slots beyond the selected count
+        for (int i = max(b, n) + lane; i < min(k, b + kSortTile); i += 64) {
+            idx[i] = -1;
+            val[i] = -INFINITY;
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_topk_write(int k, const uint32_t *__restrict__ state,
                                                     const uint32_t *__restrict__ keys, const int32_t *__restrict__ ids,
                                                     int32_t *__restrict__ idx, float *__restrict__ val) {
@@ -410,37 +577,50 @@ __global__ __launch_bounds__(256) void k_topk_write(int k, const uint32_t *__res
 
 hipError_t launch_topk(hipStream_t st, int N, const float *q, const float *x, const uint8_t *cand, int k,
                        const SelectScratch &sc, int32_t *idx, float *val, int32_t *count) {
-    k_topk_init<<<1, 256, 0, st>>>(sc.hist, sc.state, k);
+    k_topk_init<<<1, 256, 0, st>>>(sc.hist, sc.state);
     S2V_CHECK_LAUNCH();
     const int n_scan_blk = (N + kScanBlock - 1) / kScanBlock;
     uint32_t *blk = sc.blk, *blk_scan = sc.blk + 2 * (size_t)n_scan_blk;
+    const uint32_t ku = (uint32_t)k;
     if (N > 0) {
-        const int hist_grid = min((N + 255) / 256, 256 * 8);
+        const int hist_grid = min((N + 1023) / 1024, 512);
         for (int pass = 0; pass < 4; ++pass) {
-            k_topk_hist<<<hist_grid, 256, 0, st>>>(N, pass, q, x, cand, sc.hist, sc.state);
-            S2V_CHECK_LAUNCH();
-            k_topk_pick<<<1, 64, 0, st>>>(pass, sc.hist, sc.state);
+            k_topk_hist<<<hist_grid, 256, 0, st>>>(N, pass, ku, q, x, cand, sc.hist);
             S2V_CHECK_LAUNCH();
         }
-        k_topk_scan1<<<n_scan_blk, 256, 0, st>>>(N, q, x, cand, sc.state, blk);
+        k_topk_scan1<<<n_scan_blk, 256, 0, st>>>(N, ku, q, x, cand, sc.hist, blk);
         S2V_CHECK_LAUNCH();
     }
-    k_topk_scan2<<<1, 256, 0, st>>>(n_scan_blk, blk, blk_scan, sc.state, count);
+    k_topk_scan2<<<1, 256, 0, st>>>(n_scan_blk, ku, sc.hist, blk, blk_scan, sc.state, count);
     S2V_CHECK_LAUNCH();
-    if (N > 0) {
-        k_topk_scan3<<<n_scan_blk, 256, 0, st>>>(N, q, x, cand, sc.state, blk_scan, sc.keys[0], sc.ids[0]);
-        S2V_CHECK_LAUNCH();
-        const int n_sort_blk = (k + kSortTile - 1) / kSortTile;
+    if (N == 0) {
+        k_topk_write<<<min((k + 255) / 256, 1024), 256, 0, st>>>(k, sc.state, sc.keys[0], sc.ids[0], idx, val);
+        return hipGetLastError();
+    }
+    k_topk_scan3<<<n_scan_blk, 256, 0, st>>>(N, q, x, cand, sc.state, blk_scan, sc.keys[0], sc.ids[0]);
+    S2V_CHECK_LAUNCH();
+    const int n_sort_blk = (k + kSortTile - 1) / kSortTile;
+    if (n_sort_blk <= kSortFusedMaxBlocks) {
         for (int pass = 0; pass < 4; ++pass) {
             const int a = pass & 1, b = a ^ 1;
-            k_sort_hist<<<n_sort_blk, 64, 0, st>>>(pass, n_sort_blk, sc.state, sc.keys[a], sc.sort_cnt);
+            const bool last = pass == 3;
+            k_sort_count<<<n_sort_blk, 64, 0, st>>>(pass, sc.state, sc.keys[a], sc.sort_cnt);
             S2V_CHECK_LAUNCH();
-            k_sort_scan<<<1, 256, 0, st>>>(n_sort_blk, sc.sort_cnt);
-            S2V_CHECK_LAUNCH();
-            k_sort_scatter<<<n_sort_blk, 64, 0, st>>>(pass, n_sort_blk, sc.state, sc.keys[a], sc.ids[a], sc.sort_cnt,
-                                                      sc.keys[b], sc.ids[b]);
+            k_sort_pass<<<n_sort_blk, 64, 0, st>>>(pass, n_sort_blk, k, sc.state, sc.keys[a], sc.ids[a], sc.sort_cnt,
+                                                   sc.keys[b], sc.ids[b], last ? idx : nullptr, last ? val : nullptr);
             S2V_CHECK_LAUNCH();
         }
+        return hipGetLastError();
+    }
+    for (int pass = 0; pass < 4; ++pass) {
+        const int a = pass & 1, b = a ^ 1;
+        k_sort_hist<<<n_sort_blk, 64, 0, st>>>(pass, n_sort_blk, sc.state, sc.keys[a], sc.sort_cnt);
+        S2V_CHECK_LAUNCH();
+        k_sort_scan<<<1, 256, 0, st>>>(n_sort_blk, sc.sort_cnt);
+        S2V_CHECK_LAUNCH();
+        k_sort_scatter<<<n_sort_blk, 64, 0, st>>>(pass, n_sort_blk, sc.state, sc.keys[a], sc.ids[a], sc.sort_cnt,
+                                                  sc.keys[b], sc.ids[b]);
+        S2V_CHECK_LAUNCH();
     }
     k_topk_write<<<min((k + 255) / 256, 1024), 256, 0, st>>>(k, sc.state, sc.keys[0], sc.ids[0], idx, val);
     return hipGetLastError();

@@ -151,6 +151,45 @@ def test_topk_above_the_single_workgroup_sort_limit(oracle_mod, name):
     assert np.array_equal(val[0].astype(np.float64), ov[0])
 
 
+@pytest.mark.parametrize("k", [600_000, 900_000])
+def test_topk_with_more_sort_tiles_than_the_fused_sort_takes(oracle_mod, k):
+    # k above 512 tiles of 1024 entries: the sort runs as separate count / scan / scatter kernels;
+    # the second k exceeds the number of candidates
+    rng = np.random.default_rng(12)
+    n = 1_000_000
+    q = np.round(rng.normal(size=n), 3).astype(np.float32)
+    x = (rng.random(n) < 0.2).astype(np.float32)
+    dev = gu.Device(si.edgeless(n), 32, 1, k_max=k)
+    idx, val, cnt = dev.select(q, x, None, k)
+    oi, ov, oc = oracle_mod.select(None, q, x, None, k)
+    assert cnt[0] == oc[0] and np.array_equal(idx, oi)
+    assert np.array_equal(val[0, :oc[0]].astype(np.float64), ov[0, :oc[0]])
+    assert (idx[0, oc[0]:] == -1).all() and np.isneginf(val[0, oc[0]:]).all()
+
+
+@pytest.mark.parametrize("kind", ["near_equal", "two_values", "offset_large", "all_negative"])
+def test_topk_on_skewed_score_distributions(oracle_mod, kind):
+    # Scores that agree in their leading bytes (the regime of large graphs, where the graph term of
+    # Eq. 2 dominates): almost every key falls into one histogram bin per pass.
+    rng = np.random.default_rng(13)
+    n = 200_000
+    if kind == "near_equal":
+        q = (1.0e6 + rng.normal(size=n)).astype(np.float32)
+    elif kind == "two_values":
+        q = np.where(rng.random(n) < 0.5, 3.0, -3.0).astype(np.float32)
+    elif kind == "offset_large":
+        q = (-7.3e8 + 64.0 * rng.integers(0, 50, size=n)).astype(np.float32)
+    else:
+        q = (-np.abs(rng.normal(size=n)) - 1.0).astype(np.float32)
+    x = (rng.random(n) < 0.1).astype(np.float32)
+    dev = gu.Device(si.edgeless(n), 32, 1, k_max=5000)
+    for k in (1, 37, 1900, 5000, 1900):          # the same workspace serves all calls
+        idx, val, cnt = dev.select(q, x, None, k)
+        oi, ov, oc = oracle_mod.select(None, q, x, None, k)
+        assert cnt[0] == oc[0] == k and np.array_equal(idx, oi), (kind, k)
+        assert np.array_equal(val[0].astype(np.float64), ov[0])
+
+
 def test_topk_candidate_mask_and_empty(oracle_mod):
     n, qs, x = _select_cases()
     q = qs["ties"]
