@@ -4,8 +4,8 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-train] [--no-loop] [--no-cpu-baseline]
 
 A "step" is one RL inference step on the 30M-edge workload (benchmark configuration 4:
-Erdos-Renyi n = 2e6, average degree 30, p = 64, T = 4): embedding (s2v_embed_fwd), scores
-(s2v_q_score) and top-k selection with k = 1 % of the candidates (s2v_select_topk), with all
+Erdos-Renyi n = 2e6, average degree 30, p = 64, T = 4): embedding and scores (s2v_policy_eval:
+the work of s2v_embed_fwd + s2v_q_score) and top-k selection with k = 1 % of the candidates (s2v_select_topk), with all
 inputs resident in HBM.  The one-time graph preparation is timed separately.  Also reported:
 the training step of configuration 5 (Barabasi-Albert n = 1e6, 16 states, 4 SGD iterations),
 the live HIP-event time of the fused embedding-round kernel against the HBM roofline, and the
@@ -84,8 +84,7 @@ def bench_inference(args, s2v, torch):
     prepare_ms = (time.perf_counter() - t0) * 1e3
 
     def step():
-        ctx.s2v_embed_fwd(graph, prm, x, T, 1, mu, None, gsum, ws)
-        ctx.s2v_q_score(graph, prm, mu, gsum, 1, q, ws)
+        ctx.s2v_policy_eval(graph, prm, x, T, 1, mu, gsum, q, ws)      # embedding (Alg. 1) + scores (Alg. 2)
         ctx.s2v_select_topk(graph, q[0], x[0], None, k, idx, val, cnt, ws)
 
     for _ in range(args.warmup):
@@ -97,21 +96,21 @@ def bench_inference(args, s2v, torch):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    (n_round, ms_round), _, (n_r2, ms_r2) = ctx.s2v_profile_end()
+    (n_round, ms_round), _, (n_r2, ms_r2), (n_rq, ms_rq) = ctx.s2v_profile_end()
     peak_mb = torch.cuda.max_memory_allocated() / 2**20
     round_ms = ms_round / max(n_round, 1)
     alg = round_algorithmic_bytes(N, g.nnz, p)
     achieved = alg / (round_ms * 1e-3) / 1e9
     log(f"[bench] inference {ms:.3f} ms/step; round 2 (from scalars) {ms_r2 / max(n_r2, 1):.3f} ms; "
-        f"gather round {round_ms:.3f} ms x {n_round}; "
+        f"gather round {round_ms:.3f} ms x {n_round}, last round with the node term of Q "
+        f"{ms_rq / max(n_rq, 1):.3f} ms x {n_rq}; "
         f"{achieved:.0f} GB/s algorithmic; prepare {prepare_ms:.1f} ms; peak {peak_mb:.0f} MiB")
     # the same step with the weighted neighbour sum (the other reading of Alg. 1's aggregation):
     # each round also reads the 4-byte weight of every stored entry
     graph_w = s2v.Graph(graph.rowptr, graph.colidx, graph.w, graph.graph_off, weighted_sum=True)
 
     def step_w():
-        ctx.s2v_embed_fwd(graph_w, prm, x, T, 1, mu, None, gsum, ws)
-        ctx.s2v_q_score(graph_w, prm, mu, gsum, 1, q, ws)
+        ctx.s2v_policy_eval(graph_w, prm, x, T, 1, mu, gsum, q, ws)
         ctx.s2v_select_topk(graph_w, q[0], x[0], None, k, idx, val, cnt, ws)
 
     step_w()
@@ -122,7 +121,7 @@ def bench_inference(args, s2v, torch):
         step_w()
     torch.cuda.synchronize()
     ms_w = (time.perf_counter() - t0) * 1e3 / 3
-    (n_round_w, ms_round_w), _, _ = ctx.s2v_profile_end()
+    (n_round_w, ms_round_w), _, _, _ = ctx.s2v_profile_end()
     round_w_ms = ms_round_w / max(n_round_w, 1)
     log(f"[bench] weighted neighbour sum: {ms_w:.3f} ms/step, gather round {round_w_ms:.3f} ms "
         f"({(alg + 4 * g.nnz) / (round_w_ms * 1e-3) / 1e9:.0f} GB/s algorithmic)")
@@ -132,7 +131,8 @@ def bench_inference(args, s2v, torch):
         weighted_sum=dict(ms_per_step=ms_w, round_ms=round_w_ms,
                           round_gbs=(alg + 4 * g.nnz) / (round_w_ms * 1e-3) / 1e9),
         ms=ms, prepare_ms=prepare_ms, peak_device_mib=peak_mb, n=N, nnz=g.nnz, k=k, p=p, T=T,
-        round_ms=round_ms, round_launches=n_round, round2_ms=ms_r2 / max(n_r2, 1), alg_bytes=alg, achieved_gbs=achieved,
+        round_ms=round_ms, round_launches=n_round, round2_ms=ms_r2 / max(n_r2, 1),
+        round_q_ms=ms_rq / max(n_rq, 1), alg_bytes=alg, achieved_gbs=achieved,
         selected_count=int(cnt.item()), first_selected=int(idx[0, 0].item()),
     )
     return out, w
@@ -179,7 +179,7 @@ def bench_training(args, s2v, torch):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    (n_f, ms_f), (n_b, ms_b), (n_f2, ms_f2) = ctx.s2v_profile_end()
+    (n_f, ms_f), (n_b, ms_b), (n_f2, ms_f2), _ = ctx.s2v_profile_end()
     alg = round_algorithmic_bytes(N, g.nnz, p, S)
     out = dict(ms_per_step=ms, ms_per_iteration=ms / w.iters, steps=steps, iterations=w.iters, S=S, n=N, nnz=g.nnz,
                fwd_round_ms=ms_f / max(n_f, 1), bwd_round_ms=ms_b / max(n_b, 1), fwd_round2_ms=ms_f2 / max(n_f2, 1),
@@ -228,8 +228,7 @@ def bench_loop(args, s2v, torch, w4):
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     t0 = time.perf_counter()
     for a, b in ev:
-        ctx.s2v_embed_fwd(graph, prm, x.view(1, -1), w4.T, 1, mu, None, gsum, ws)
-        ctx.s2v_q_score(graph, prm, mu, gsum, 1, q, ws)
+        ctx.s2v_policy_eval(graph, prm, x.view(1, -1), w4.T, 1, mu, gsum, q, ws)
         ctx.s2v_select_topk(graph, q[0], x, cand, 8, idx, val, cnt, ws)
         a.record()
         ctx.s2v_residual_update(graph, x, idx, cnt, 8, cand, stats, ws)
@@ -304,8 +303,7 @@ def bench_paper_shape(args, s2v, torch):
     ctx.s2v_residual_update(graph, x, None, None, 0, cand, stats, ws)
 
     def inf_step():
-        ctx.s2v_embed_fwd(graph, prm, x.view(1, -1), T, 1, mu, None, gsum, ws)
-        ctx.s2v_q_score(graph, prm, mu, gsum, 1, q, ws)
+        ctx.s2v_policy_eval(graph, prm, x.view(1, -1), T, 1, mu, gsum, q, ws)
         ctx.s2v_select_topk(graph, q[0], x, cand, 1, idx, val, cnt, ws)
         ctx.s2v_residual_update(graph, x, idx, cnt, 1, cand, stats, ws)
 
@@ -438,7 +436,7 @@ def main():
             "scale": args.scale,
         },
         "roofline": {
-            "kernel": "k_round<64,false,false,*> (fused CSR gather + theta2 product + relu, rounds 3..T)",
+            "kernel": "k_round<64,false,false,false,false,false> (fused CSR gather + theta2 product + relu, rounds 3..T-1; the last round also forms the node term of Eq. 2 and is timed separately)",
             "bound": "hbm",
             "achieved": round(inf["achieved_gbs"], 1),
             "peak": HBM_PEAK_GBS,
@@ -451,6 +449,7 @@ def main():
         },
         "cpu_baseline": cpu,
         "round2_from_scalars_ms": round(inf["round2_ms"], 4),
+        "last_round_with_q_node_term_ms": round(inf["round_q_ms"], 4),
         "weighted_sum_reading": inf["weighted_sum"],
         "prepare_ms": round(inf["prepare_ms"], 2),
         "peak_device_mib": round(inf["peak_device_mib"], 1),

@@ -165,6 +165,18 @@ int32_t s2v_q_score(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, 
                     const float *gsum, int32_t S, float *q, void *ws, size_t ws_bytes);
 
 /*
+ * One policy evaluation (Alg. 3 lines 5-6: the embedding of Alg. 1, then the scores of Alg. 2 /
+ * Eq. 2) in a single call: the same mu_out [N][S][p], gsum [S][G][p] and q [S][N] that
+ * s2v_embed_fwd (without saved rounds) followed by s2v_q_score produce, all three required.
+ * When the last embedding round runs row by row (S not a multiple of 16, T >= 2) the node term of
+ * Eq. 2 is computed inside that round while the finished rows are still on chip, so the embedding
+ * is not read a second time; otherwise the call is exactly the two calls in sequence.
+ * Errors: as s2v_embed_fwd and s2v_q_score.
+ */
+int32_t s2v_policy_eval(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                        int32_t S, float *mu_out, float *gsum, float *q, void *ws, size_t ws_bytes);
+
+/*
  * Node selection for one state: per graph, the k candidates with the highest scores,
  * ordered by score descending and node index ascending among equal scores (k == 1 is
  * the argmax of Alg. 3 line 7; k > 1 is the top-d selection of Sec. 4.5.1).
@@ -270,13 +282,16 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
  *   S2V_PROFILE_FWD_ROUND   rounds 3..T of Eq. 1 inside s2v_embed_fwd (neighbour rows read from memory)
  *   S2V_PROFILE_BWD_ROUND   the reversed rounds inside s2v_embed_bwd
  *   S2V_PROFILE_FWD_ROUND2  round 2 of Eq. 1 (neighbour rows recomputed from per-node scalars)
+ *   S2V_PROFILE_FWD_ROUND_Q a last round that also forms the node term of Eq. 2 (inside s2v_policy_eval);
+ *                           such a launch is not counted under S2V_PROFILE_FWD_ROUND
  * s2v_profile_end waits for the stream and returns, per kind, the number of bracketed launches
  * and the sum of their durations in milliseconds (host arrays of S2V_PROFILE_KINDS elements).
  */
 #define S2V_PROFILE_FWD_ROUND 0
 #define S2V_PROFILE_BWD_ROUND 1
 #define S2V_PROFILE_FWD_ROUND2 2
-#define S2V_PROFILE_KINDS 3
+#define S2V_PROFILE_FWD_ROUND_Q 3
+#define S2V_PROFILE_KINDS 4
 int32_t s2v_profile_begin(s2v_ctx *ctx, int32_t max_launches);
 int32_t s2v_profile_end(s2v_ctx *ctx, int32_t *n_launches, float *total_ms);
 

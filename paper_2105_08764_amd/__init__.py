@@ -28,7 +28,7 @@ EXPORTS = (
     "s2v_status_str", "s2v_create", "s2v_destroy", "s2v_last_hip_error", "s2v_workspace_bytes",
     "s2v_graph_prepare", "s2v_embed_fwd", "s2v_q_score", "s2v_select_topk", "s2v_embed_bwd",
     "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end", "s2v_residual_update",
-    "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target",
+    "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target", "s2v_policy_eval",
 )
 
 
@@ -205,6 +205,14 @@ class Context:
                                       ctypes.c_void_p(_dp(ws)), ctypes.c_size_t(ws.numel() * ws.element_size())),
                "s2v_embed_fwd")
 
+    def s2v_policy_eval(self, g: Graph, params: Params, x, T: int, S: int, mu_out, gsum, q, ws) -> None:
+        _want(x, "float32", "x")
+        _check(self.lib.s2v_policy_eval(self.handle, ctypes.byref(g.c), ctypes.byref(params.c),
+                                        ctypes.c_void_p(_dp(x)), ctypes.c_int32(T), ctypes.c_int32(S),
+                                        ctypes.c_void_p(_dp(mu_out)), ctypes.c_void_p(_dp(gsum)),
+                                        ctypes.c_void_p(_dp(q)), ctypes.c_void_p(_dp(ws)),
+                                        ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_policy_eval")
+
     def s2v_q_score(self, g: Graph, params: Params, mu, gsum, S: int, q, ws) -> None:
         _check(self.lib.s2v_q_score(self.handle, ctypes.byref(g.c), ctypes.byref(params.c), ctypes.c_void_p(_dp(mu)),
                                     ctypes.c_void_p(_dp(gsum)), ctypes.c_int32(S), ctypes.c_void_p(_dp(q)),
@@ -276,11 +284,12 @@ class Context:
         _check(self.lib.s2v_profile_begin(self.handle, ctypes.c_int32(max_launches)), "s2v_profile_begin")
 
     def s2v_profile_end(self):
-        """[(launches, total ms)] for the kinds fwd round (from memory), bwd round, fwd round 2."""
-        n = (ctypes.c_int32 * 3)()
-        ms = (ctypes.c_float * 3)()
+        """[(launches, total ms)] for the kinds fwd round (from memory), bwd round, fwd round 2, and
+        last fwd round with the node term of Eq. 2 fused in."""
+        n = (ctypes.c_int32 * 4)()
+        ms = (ctypes.c_float * 4)()
         _check(self.lib.s2v_profile_end(self.handle, n, ms), "s2v_profile_end")
-        return [(int(n[i]), float(ms[i])) for i in range(3)]
+        return [(int(n[i]), float(ms[i])) for i in range(4)]
 
     def s2v_sgd_step(self, params: Params, grads: Params, lr: float) -> None:
         _check(self.lib.s2v_sgd_step(self.handle, ctypes.byref(params.c), ctypes.byref(grads.c), ctypes.c_float(lr)),

@@ -471,8 +471,12 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     return S2V_OK;
 }
 
-int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
-                      int32_t S, float *mu_out, float *mu_saved, float *gsum, void *ws, size_t ws_bytes) {
+// Alg. 1 for all states.  q_node != NULL asks the last round to leave the node term of Eq. 2 in
+// q_node [S][N] as well; *q_node_done says whether it did (only the row-mode round kernel can).
+static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                              int32_t S, float *mu_out, float *mu_saved, float *gsum, void *ws, size_t ws_bytes,
+                              float *q_node, bool *q_node_done) {
+    if (q_node_done) *q_node_done = false;
     if (!ctx) return S2V_ERR_INVALID_ARG;
     int32_t rc = check_graph(g);
     if (rc != S2V_OK) return rc;
@@ -520,15 +524,18 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     if (mu_saved || T == 1)
         S2V_TRY(launch_round1(st, p, N, S, ninfo, x_res, T == 1, params->theta1, qvec, dest(1)));
     const bool fuse_gsum = gsum && S == 1 && G == 1 && T >= 2 && N > 0;
+    const bool fuse_q = q_node && T >= 2 && N > 0 && round_fuses_qnode(S);
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     for (int t = 2; t <= T; ++t) {
+        QHead qh{params->theta5, params->theta7, (fuse_q && t == T) ? q_node : nullptr};
         const float *src = t == 2 ? nullptr : dest(t - 1);
         S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, src, ninfo, params->theta1, qvec, nullptr, hub_part, hub_sum));
-        SpanGuard span(ctx, t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND);
+        SpanGuard span(ctx, qh.q ? S2V_PROFILE_FWD_ROUND_Q : (t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND));
         S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, src, dest(t), ninfo, params->theta1,
                              params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum, x_res,
-                             t == T));
+                             t == T, qh));
     }
+    if (q_node_done) *q_node_done = fuse_q;
     float *muT = dest(T);
     if (mu_saved && mu_out && mu_out != muT && nsp > 0)
         S2V_TRY(hipMemcpyAsync(mu_out, muT, sizeof(float) * nsp, hipMemcpyDeviceToDevice, st));
@@ -540,6 +547,30 @@ int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
             S2V_TRY(launch_gsum(st, p, N, S, G, ct, muT, gpart, gsum));
         }
     }
+    return S2V_OK;
+}
+
+int32_t s2v_embed_fwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                      int32_t S, float *mu_out, float *mu_saved, float *gsum, void *ws, size_t ws_bytes) {
+    return embed_fwd_impl(ctx, g, params, x, T, S, mu_out, mu_saved, gsum, ws, ws_bytes, nullptr, nullptr);
+}
+
+int32_t s2v_policy_eval(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                        int32_t S, float *mu_out, float *gsum, float *q, void *ws, size_t ws_bytes) {
+    if (!gsum || (g && g->n_nodes > 0 && (!mu_out || !q))) return S2V_ERR_INVALID_ARG;
+    bool q_node_done = false;
+    int32_t rc = embed_fwd_impl(ctx, g, params, x, T, S, mu_out, nullptr, gsum, ws, ws_bytes, q, &q_node_done);
+    if (rc != S2V_OK) return rc;
+    if (!q_node_done) return s2v_q_score(ctx, g, params, mu_out, gsum, S, q, ws, ws_bytes);
+    const int32_t N = g->n_nodes, G = g->n_graphs;
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
+    const QLayout ql = q_layout(h, S, G);
+    if (ws_bytes < ql.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
+    float *qa = at<float>(ws, ql.qa);
+    S2V_TRY(launch_qa(ctx->stream, params->p, S, G, params->theta5, params->theta6, gsum, qa));
+    S2V_TRY(launch_qfinish(ctx->stream, N, S, G, g->graph_off, qa, q));
     return S2V_OK;
 }
 
@@ -742,9 +773,7 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     int64_t picked = 0;
     while (n_live > 0 && steps < max_steps) {
         const int32_t d = (adaptive && G == 1) ? s2v_adaptive_d(n_cand, N) : 1;
-        rc = s2v_embed_fwd(ctx, g, params, x, T, 1, mu, nullptr, gsum, ws, ws_bytes);
-        if (rc != S2V_OK) return rc;
-        rc = s2v_q_score(ctx, g, params, mu, gsum, 1, q, ws, ws_bytes);
+        rc = s2v_policy_eval(ctx, g, params, x, T, 1, mu, gsum, q, ws, ws_bytes);
         if (rc != S2V_OK) return rc;
         rc = s2v_select_topk(ctx, g, q, x, cand, d, sel_idx, sel_val, sel_count, ws, ws_bytes);
         if (rc != S2V_OK) return rc;

@@ -248,8 +248,11 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 //         gpart[blockIdx.x][P]: the first stage of the graph sum of Alg. 2 line 4.
 //   W   : the neighbour sum weights each neighbour by its entry of wagg (the reading of the
 //         aggregation step of Alg. 1 as a product with the weighted adjacency).
+//   QN  : this is the last round and Eq. 2 follows: also emit the node term of Q,
+//         theta5[p:2p] . relu(theta7 mu_v), for every output row (row mode only).  The product with
+//         theta7 runs on the matrix cores while the wave's next gather is already the bottleneck.
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE, bool MU1, bool GSUM, bool W>
+template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN>
 #ifndef S2V_ROUND_OCC
 #define S2V_ROUND_OCC 4
 #endif
@@ -266,8 +269,9 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
                                                     const float *__restrict__ theta2,
                                                     const float *__restrict__ qvec, float *__restrict__ gpart,
                                                     HubTable ht, const float *__restrict__ hub_sum,
-                                                    const float *__restrict__ x_res, int N, int last) {
+                                                    const float *__restrict__ x_res, int N, int last, QHead qh) {
     using G = Geo<P>;
+    static_assert(!(QN && NODE), "the node term of Q is fused in row mode only");
     __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
     __shared__ __attribute__((aligned(16))) float lds_b[P * G::STRIDE];   // theta2, the B operand
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -402,6 +406,37 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
                     const float o = keepi * fmaxf(cuti * acc[cb][rr] + xi * t1[cb] + spi * qp[cb] + sni * qn[cb], 0.f);
                     out[16 * cb] = o;
                     if (GSUM) csum[cb] += o;
+                    if (QN) tile[i * G::STRIDE + 16 * cb + jl] = o;
+                }
+            }
+        }
+        if (QN) {
+            // the finished tile (rows past the end hold stale values, never written out) times theta7
+            __builtin_amdgcn_wave_barrier();
+            const Frag<P> ofrag = load_a_frag_lds<P>(tile, lane);
+            __builtin_amdgcn_wave_barrier();
+            float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int cb = 0; cb < G::CB; ++cb) {
+                f32x4 h = (f32x4){0.f, 0.f, 0.f, 0.f};
+                h = mfma_tile<P>(ofrag, load_b_frag_rows<P>(qh.theta7, cb, lane), h);
+                const float t5 = qh.theta5[P + 16 * cb + jl];
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) part[rr] += t5 * fmaxf(h[rr], 0.f);
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+#pragma unroll
+                for (int m = 1; m < 16; m <<= 1) part[rr] += __shfl_xor(part[rr], m);
+            }
+            if (jl == 0) {
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int ro = r0 + 4 * gl + rr;
+                    if (ro < n_vrows) {
+                        const int vo = ro / S, so = ro - vo * S;
+                        qh.q[(size_t)so * N + vo] = part[rr];
+                    }
                 }
             }
         }
@@ -433,14 +468,20 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
                                  const int32_t *colidx, const float *wagg,
                                  const float *mu_in, float *mu_out, const NodeInfo &info, const float *theta1,
                                  const float *theta2, const float *qvec, bool from_scalars, float *gpart,
-                                 const HubTable &ht, const float *hub_sum, const float *x_res, bool last) {
+                                 const HubTable &ht, const float *hub_sum, const float *x_res, bool last,
+                                 const QHead &qh) {
     const long n_vrows = (long)N * S;
     const int grid = round_grid(n_vrows);
     const bool node = (S % 16) == 0;
-#define S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, WW)                                                                  \
-    k_round<P, NODE, MU1, GSUM, WW><<<grid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in,  \
-                                                               mu_out, info, theta1, theta2, qvec, gpart, ht, hub_sum, \
-                                                               x_res, N, last ? 1 : 0)
+#define S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, QQ)                                                                   \
+    k_round<P, NODE, MU1, GSUM, WW, QQ><<<grid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in,  \
+                                                                   mu_out, info, theta1, theta2, qvec, gpart, ht,         \
+                                                                   hub_sum, x_res, N, last ? 1 : 0, qh)
+#define S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, WW)                            \
+    do {                                                                   \
+        if (!NODE && qh.q) S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, !NODE); \
+        else S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, false);               \
+    } while (0)
 #define S2V_LAUNCH_ROUND(NODE, MU1, GSUM)                \
     do {                                                 \
         if (wagg) S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, true); \
@@ -458,6 +499,7 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
     }
 #undef S2V_LAUNCH_ROUND
 #undef S2V_LAUNCH_ROUND_W
+#undef S2V_LAUNCH_ROUND_Q
     return hipGetLastError();
 }
 
@@ -466,13 +508,13 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
                         const int32_t *colidx, const float *wagg, const float *mu_in, float *mu_out, const NodeInfo &info,
                         const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
-                        const float *hub_sum, const float *x_res, bool last) {
+                        const float *hub_sum, const float *x_res, bool last, const QHead &qh) {
     if ((long)N * S == 0) return hipSuccess;
     if (p == 32)
         return launch_round_p<32>(st, N, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
-                                  gpart, ht, hub_sum, x_res, last);
+                                  gpart, ht, hub_sum, x_res, last, qh);
     return launch_round_p<64>(st, N, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
-                              ht, hub_sum, x_res, last);
+                              ht, hub_sum, x_res, last, qh);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -632,12 +674,12 @@ __global__ __launch_bounds__(256) void k_gsum_stage1(int L, const int32_t *__res
 }
 
 // Stage 2: per (graph, column) add the partial rows [row_begin, row_end) of that graph.  A block
-// owns 16 columns; its 16 row lanes take rows round-robin (double accumulators) and are combined
-// through LDS in lane order, so the result does not depend on timing.
-__global__ __launch_bounds__(256) void k_gsum_stage2(int p, int S, int G, const int32_t *__restrict__ graph_row_off,
+// owns 16 columns; its 64 row lanes take rows round-robin (double accumulators, four loads in
+// flight each) and are combined through LDS in lane order, so the result does not depend on timing.
+__global__ __launch_bounds__(1024) void k_gsum_stage2(int p, int S, int G, const int32_t *__restrict__ graph_row_off,
                                                      int rows_if_single, const float *__restrict__ partial,
                                                      float *__restrict__ gsum) {
-    __shared__ double red[16][17];
+    __shared__ double red[64][17];
     const int L = S * p;
     const int blocks_per_graph = L / 16;
     const int g = blockIdx.x / blocks_per_graph;
@@ -645,18 +687,19 @@ __global__ __launch_bounds__(256) void k_gsum_stage2(int p, int S, int G, const 
     const int rl = threadIdx.x >> 4;
     const int rb = graph_row_off ? graph_row_off[g] : 0;
     const int re = graph_row_off ? graph_row_off[g + 1] : rows_if_single;
-    double a0 = 0.0, a1 = 0.0;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     int c = rb + rl;
-    for (; c + 16 < re; c += 32) {
-        a0 += (double)partial[(size_t)c * L + col];
-        a1 += (double)partial[(size_t)(c + 16) * L + col];
+    for (; c + 192 < re; c += 256) {
+        const float v0 = partial[(size_t)c * L + col], v1 = partial[(size_t)(c + 64) * L + col];
+        const float v2 = partial[(size_t)(c + 128) * L + col], v3 = partial[(size_t)(c + 192) * L + col];
+        a0 += (double)v0; a1 += (double)v1; a2 += (double)v2; a3 += (double)v3;
     }
-    if (c < re) a0 += (double)partial[(size_t)c * L + col];
-    red[rl][threadIdx.x & 15] = a0 + a1;
+    for (; c < re; c += 64) a0 += (double)partial[(size_t)c * L + col];
+    red[rl][threadIdx.x & 15] = (a0 + a1) + (a2 + a3);
     __syncthreads();
     if (rl == 0) {
         double acc = 0.0;
-        for (int k = 0; k < 16; ++k) acc += red[k][threadIdx.x];
+        for (int k = 0; k < 64; ++k) acc += red[k][threadIdx.x];
         const int s = col / p, j = col - s * p;
         gsum[((size_t)s * G + g) * p + j] = (float)acc;
     }
@@ -671,13 +714,13 @@ hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTa
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    k_gsum_stage2<<<G * (L / 16), 256, 0, st>>>(p, S, G, ct.graph_chunk_off, 0, partial, gsum);
+    k_gsum_stage2<<<G * (L / 16), 1024, 0, st>>>(p, S, G, ct.graph_chunk_off, 0, partial, gsum);
     return hipGetLastError();
 }
 
 // Second stage alone, over `rows` partial rows written by the last embedding round (S == 1, G == 1).
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum) {
-    k_gsum_stage2<<<p / 16, 256, 0, st>>>(p, 1, 1, nullptr, rows, partial, gsum);
+    k_gsum_stage2<<<p / 16, 1024, 0, st>>>(p, 1, 1, nullptr, rows, partial, gsum);
     return hipGetLastError();
 }
 
@@ -714,10 +757,37 @@ hipError_t launch_qa(hipStream_t st, int p, int S, int G, const float *theta5, c
 
 // ------------------------------------------------------------------------------------------
 // Eq. 2, node term + sum: q[s][v] = qa[s][graph(v)] + theta5[p:2p] . relu(theta7 mu[v][s])
-// Same 16-row wave tiles as the embedding round; the A operand comes straight from mu.
+// Same 16-row wave tiles as the embedding round; the A operand comes straight from mu, theta7 is
+// staged in LDS.  Streaming and latency-bound: four workgroups per CU, each wave two tiles ahead.
 // ------------------------------------------------------------------------------------------
+// The node term is already in q (written by the last embedding round): add the graph term.
+__global__ __launch_bounds__(256) void k_qfinish(int N, int S, int G, const int32_t *__restrict__ graph_off,
+                                                 const float *__restrict__ qa, float *__restrict__ q) {
+    const long total = (long)N * S;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int s = (int)(i / N), v = (int)(i - (long)s * N);
+        int g = 0;
+        if (G > 1) {  // last graph whose offset is <= v
+            int lo = 0, hi = G;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (graph_off[mid] <= v) lo = mid; else hi = mid;
+            }
+            g = lo;
+        }
+        q[i] = qa[(size_t)s * G + g] + q[i];
+    }
+}
+
+hipError_t launch_qfinish(hipStream_t st, int N, int S, int G, const int32_t *graph_off, const float *qa, float *q) {
+    const long total = (long)N * S;
+    if (total == 0) return hipSuccess;
+    k_qfinish<<<(int)min((total + 255) / 256, (long)8192), 256, 0, st>>>(N, S, G, graph_off, qa, q);
+    return hipGetLastError();
+}
+
 template <int P>
-__global__ __launch_bounds__(kThreads) void k_qnode(int n_vrows, int N, int S, int G,
+__global__ __launch_bounds__(kThreads, 4) void k_qnode(int n_vrows, int N, int S, int G,
                                                     const int32_t *__restrict__ graph_off,
                                                     const float *__restrict__ theta5,
                                                     const float *__restrict__ theta7, const float *__restrict__ mu,
@@ -725,38 +795,39 @@ __global__ __launch_bounds__(kThreads) void k_qnode(int n_vrows, int N, int S, i
     using Ge = Geo<P>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int jl = lane & 15, gl = lane >> 4;
-    Frag<P> bfrag[Ge::CB];
+    __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * Ge::STRIDE];
+    __shared__ __attribute__((aligned(16))) float lds_b[P * Ge::STRIDE];   // theta7, the B operand
+    stage_matrix_lds<P>(lds_b, theta7, false);
+    __syncthreads();
     float t5[Ge::CB];
 #pragma unroll
-    for (int cb = 0; cb < Ge::CB; ++cb) {
-        bfrag[cb] = load_b_frag_rows<P>(theta7, cb, lane);
-        t5[cb] = theta5[P + 16 * cb + jl];
-    }
-    // The wave's 16 x P tile is 16 contiguous rows: fetch it with fully coalesced float4 loads (one
-    // tile ahead of the arithmetic) and turn it into matrix-core fragments through LDS.
-    __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * Ge::STRIDE];
+    for (int cb = 0; cb < Ge::CB; ++cb) t5[cb] = theta5[P + 16 * cb + jl];
+    // The wave's 16 x P tile is 16 contiguous rows: fetch it with fully coalesced float4 loads (two
+    // tiles ahead of the arithmetic) and turn it into matrix-core fragments through LDS.
     float *tile = lds[wave];
     constexpr int MV = (kTileRows * Ge::LPR) / 64;
     const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
-    float4 nxt[MV];
-    auto fetch = [&](int t) {
+    float4 cur[MV], nxt[MV];
+    auto fetch = [&](int t, float4 *dst) {
         const int r0 = t * kWgRows + wave * kTileRows;
 #pragma unroll
         for (int c = 0; c < MV; ++c) {
             const int f = c * 64 + lane, row = f / Ge::LPR, col4 = f % Ge::LPR;
-            nxt[c] = (t < n_tiles && r0 + row < n_vrows) ? ld4(mu + (size_t)(r0 + row) * P + 4 * col4)
+            dst[c] = (t < n_tiles && r0 + row < n_vrows) ? ld4(mu + (size_t)(r0 + row) * P + 4 * col4)
                                                          : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
-    fetch(blockIdx.x);
+    fetch(blockIdx.x, cur);
+    fetch(blockIdx.x + gridDim.x, nxt);
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const int r0 = t * kWgRows + wave * kTileRows;
 #pragma unroll
         for (int c = 0; c < MV; ++c) {
             const int f = c * 64 + lane;
-            st4(tile + (f / Ge::LPR) * Ge::STRIDE + 4 * (f % Ge::LPR), nxt[c]);
+            st4(tile + (f / Ge::LPR) * Ge::STRIDE + 4 * (f % Ge::LPR), cur[c]);
+            cur[c] = nxt[c];
         }
-        fetch(t + gridDim.x);
+        fetch(t + 2 * gridDim.x, nxt);
         __builtin_amdgcn_wave_barrier();
         const Frag<P> afrag = load_a_frag_lds<P>(tile, lane);
         __builtin_amdgcn_wave_barrier();
@@ -765,7 +836,7 @@ __global__ __launch_bounds__(kThreads) void k_qnode(int n_vrows, int N, int S, i
 #pragma unroll
         for (int cb = 0; cb < Ge::CB; ++cb) {
             f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-            acc = mfma_tile<P>(afrag, bfrag[cb], acc);
+            acc = mfma_tile<P>(afrag, load_b_frag_lds<P>(lds_b, cb, lane), acc);
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) part[rr] += t5[cb] * fmaxf(acc[rr], 0.f);
         }

@@ -109,11 +109,20 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
                            const int32_t *colidx, const float *wagg, const float *src,
                            const NodeInfo &ni, const float *theta1, const float *qvec,
                            const unsigned long long *mask, float *partial, float *hub_sum);
+// Eq. 2's node term fused into the last embedding round (row mode): q == NULL switches it off.
+struct QHead {
+    const float *theta5;
+    const float *theta7;
+    float *q;   // [S][N], receives theta5[p:2p] . relu(theta7 mu[v][s])
+};
+// whether launch_round honours a QHead for this S (else the caller runs the separate node-term kernel)
+inline bool round_fuses_qnode(int S) { return (S % 16) != 0; }
+hipError_t launch_qfinish(hipStream_t st, int N, int S, int G, const int32_t *graph_off, const float *qa, float *q);
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                         const int32_t *colidx, const float *wagg /*NULL: unweighted neighbour sum*/, const float *mu_in,
                         float *mu_out, const NodeInfo &ni, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
-                        const float *hub_sum, const float *x_res, bool last);
+                        const float *hub_sum, const float *x_res, bool last, const QHead &qh);
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum);
 hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu,
                        float *partial /*[n_chunks][S*p]*/, float *gsum /*[S][G][p]*/);

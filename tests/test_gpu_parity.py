@@ -104,6 +104,41 @@ def test_permutation_equivariance_on_gpu():
     assert gu.rel_err(b["q"][0, perm], a["q"][0]) <= 1e-5
 
 
+@pytest.mark.parametrize("flags", [{}, {"weighted_sum": True}, {"state_residual": True}])
+@pytest.mark.parametrize("kind,p,T,S", [("er_small", 64, 4, 1), ("ba", 32, 2, 1), ("batch", 64, 3, 3), ("ba", 64, 2, 5),
+                                        ("hub", 32, 3, 1), ("er_dense", 64, 1, 2), ("ba", 32, 3, 16)])
+def test_policy_eval_equals_embedding_then_scores(oracle_mod, kind, p, T, S, flags):
+    # One call for Alg. 3's "embed, then score": same three outputs as the two calls, bit for bit (the
+    # node term of Eq. 2 is formed by the same arithmetic inside the last round), and within the bar
+    # of the oracle.  T = 1 and S = 16 take the unfused route inside the call.
+    import torch
+
+    print(f"case policy_eval kind={kind} p={p} T={T} S={S} {flags}", flush=True)
+    if kind == "hub":
+        g = si.block_diagonal([si.star_graph(900), si.complete_graph(280)])
+        g.w = si.symmetric_edge_weights(g, 3, 0.5, 1.5)
+    else:
+        g = _graph(kind, 7)
+    theta = si.thetas(p, 41 + p + T, 0.02 if kind in ("hub", "er_dense") else 0.05)
+    x = si.node_flags(g.n, 0.2, 3, n_states=S)
+    dev = gu.Device(g, p, T, S=S, **flags)
+    two = dev.forward(theta, x)
+    prm = dev.params(theta)
+    xd = torch.from_numpy(x).cuda()
+    mu = torch.full((g.n, S, p), float("nan"), device="cuda")
+    gsum = torch.full((S, g.n_graphs, p), float("nan"), device="cuda")
+    q = torch.full((S, g.n), float("nan"), device="cuda")
+    dev.ctx.s2v_policy_eval(dev.graph, prm, xd, T, S, mu, gsum, q, dev.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(mu.cpu().numpy(), two["mu"])
+    assert np.array_equal(gsum.cpu().numpy(), two["gsum"])
+    assert np.array_equal(q.cpu().numpy(), two["q"])
+    if not flags:
+        for b in range(S):
+            omu, ogs, oq = gu.oracle_forward(oracle_mod, g, theta, x[b], T)
+            assert gu.rel_err(q.cpu().numpy()[b], oq) <= TOL
+
+
 # ---- selection ------------------------------------------------------------------------------
 
 def _select_cases():
