@@ -63,6 +63,17 @@ def test_error_codes():
     with pytest.raises(s2v.S2VError) as e:
         ctx.s2v_embed_fwd(graph, prm, x, 3, 1, mu, None, gsum, ws[8:])
     assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    # the one-call policy evaluation needs all three outputs and refuses what its two halves refuse
+    for args in ((None, gsum, q), (mu, None, q), (mu, gsum, None)):
+        with pytest.raises(s2v.S2VError) as e:
+            ctx.s2v_policy_eval(graph, prm, x, 3, 1, args[0], args[1], args[2], ws)
+        assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_policy_eval(graph, prm, x, 0, 1, mu, gsum, q, ws)
+    assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_policy_eval(graph, prm, x, 3, 1, mu, gsum, q, other)
+    assert _status(e) == s2v.S2V_ERR_NOT_PREPARED
     # selection: k < 1; batch with k > 1
     with pytest.raises(s2v.S2VError) as e:
         ctx.s2v_select_topk(graph, q[0], x[0], None, 0, idx, val, cnt, ws)
@@ -101,6 +112,11 @@ def test_empty_graph():
     for k in (1, 3):
         idx, val, cnt = dev.select(np.zeros(0, np.float32), np.zeros(0, np.float32), None, k)
         assert cnt[0] == 0 and (idx == -1).all() and np.isneginf(val).all()
+    gsum = torch.full((1, 1, 32), float("nan"), device="cuda")
+    dev.ctx.s2v_policy_eval(dev.graph, dev.params(si.thetas(32, 1)), torch.zeros((1, 0), device="cuda"), 3, 1,
+                            torch.zeros((0, 1, 32), device="cuda"), gsum, torch.zeros((1, 0), device="cuda"), dev.ws)
+    torch.cuda.synchronize()
+    assert (gsum == 0).all()
 
 
 def test_single_node_and_single_round(oracle_mod):
