@@ -165,7 +165,7 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
             const bool valid = r < r_end;
             unsigned long long word = 0ull;
             if (valid) {
-                const int v = (int)(r / S), s = (int)(r - (long)v * S);
+                const int v = (int)r / S, s = (int)r - v * S;   // n_vrows < 2^31: 32-bit division
                 float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * c4);
                 if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * c4));

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, Node
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
         const long r = i / LPR;
         const int c = (int)(i - r * LPR) * 4;
-        const int v = (int)(r / S), s = (int)(r - (long)v * S);
+        const int v = (int)r / S, s = (int)r - v * S;   // n_vrows < 2^31: 32-bit division
         const float3 q = ni.get(v, s);
         float xs = q.x;
         const float sp = q.y, sn = q.z;
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void k_stateinfo_sums(int N, int S, int ni, co
                                                         float *__restrict__ info) {
     const long total = (long)N * S;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
-        const int v = (int)(i / S), s = (int)(i - (long)v * S);
+        const int v = (int)i / S, s = (int)i - v * S;   // N * S < 2^31: 32-bit division
         const int b = rowptr[v], e = rowend[v];
         float *mine = info + (size_t)v * ni;
         if (e - b > kHubDegree || mine[s] != 0.f) continue;   // long rows: pass 3; solution nodes keep zero sums
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(256) void k_stateinfo_hubs(int S, int ni, HubTable 
 __global__ __launch_bounds__(256) void k_stateinfo_clear_x(int N, int S, int ni, float *__restrict__ info) {
     const long total = (long)N * S;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
-        const int v = (int)(i / S), s = (int)(i - (long)v * S);
+        const int v = (int)i / S, s = (int)i - v * S;   // N * S < 2^31: 32-bit division
         info[(size_t)v * ni + s] = 0.f;   // a live node has x = 0 already, a solution node gets it now
     }
 }
