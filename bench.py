@@ -39,6 +39,24 @@ def round_algorithmic_bytes(n, nnz, p, S=1):
     return 4 * (n + 1) + 4 * nnz + 4 * p * nnz * S + 12 * n * S + 4 * p * n * S
 
 
+def copy_ceiling_gbs(torch):
+    """Empirical streaming ceiling of this GPU: a plain 1 GiB device-to-device copy (1 GiB read +
+    1 GiB written), best of five, in GB/s of total traffic."""
+    src = torch.empty(1 << 28, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    best = float("inf")
+    for _ in range(6):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        dst.copy_(src)
+        b.record()
+        torch.cuda.synchronize()
+        best = min(best, a.elapsed_time(b))
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2 * (1 << 30) / (best * 1e-3) / 1e9
+
+
 def read_traffic(path):
     """HBM bytes per launch of the embedding-round kernel from a committed rocprofv3 counter
     summary (FETCH_SIZE + WRITE_SIZE, scaled); None if the summary is not there."""
@@ -400,6 +418,8 @@ def main():
         del src, dst
         args.steps, args.warmup, args.no_train, args.no_cpu_baseline = 3, 1, True, True
 
+    ceiling = copy_ceiling_gbs(torch)
+    log(f"[bench] streaming ceiling (1 GiB copy, read + write): {ceiling:.0f} GB/s")
     inf, w4 = bench_inference(args, s2v, torch)
     train = None
     if not args.no_train:
@@ -446,6 +466,12 @@ def main():
             "algorithmic_bytes_per_launch": inf["alg_bytes"],
             "avg_launch_ms": round(inf["round_ms"], 4),
             "launches_timed": inf["round_launches"],
+            # the same launch on the other byte models: counter-measured traffic, and the compulsory
+            # bytes if every embedding row were fetched once (perfect reuse)
+            "measured_traffic_gbs": None if traffic is None else round(traffic / (inf["round_ms"] * 1e-3) / 1e9, 1),
+            "compulsory_bytes_per_launch": inf["alg_bytes"] - 4 * inf["p"] * (inf["nnz"] - inf["n"]),
+            "copy_ceiling_gbs": round(ceiling, 1),
+            "frac_of_copy_ceiling": round(inf["achieved_gbs"] / ceiling, 4),
         },
         "cpu_baseline": cpu,
         "round2_from_scalars_ms": round(inf["round2_ms"], 4),

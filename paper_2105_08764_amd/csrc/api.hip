@@ -711,7 +711,7 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         if (first) {
             float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;
             float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdGrid * p * p;
-            S2V_TRY(launch_bwd_action_fix(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, action, sc.maskT, sc, params->theta2,
+            S2V_TRY(launch_bwd_action_fix(st, p, S, g->rowptr, row_end_of(g), g->colidx, wagg, action, sc.maskT, sc, params->theta2,
                                           mu_prev, dz_out, ninfo, dc_fix, d2_fix));
         }
         cur ^= 1;

@@ -235,7 +235,7 @@ hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *mu
 // ------------------------------------------------------------------------------------------
 template <int P, bool NODE, bool MASK, bool W>   // W: weighted neighbour sum (weights wagg, symmetric like the pattern)
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
-    int n_vrows, int N, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
+    int n_vrows, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
     const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
     float *__restrict__ dz_out, NodeInfo ni, const float *__restrict__ theta2,
@@ -445,7 +445,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
     const long n_vrows = (long)N * S;
     const bool node = (S % 16) == 0, mask = maskT != nullptr;
 #define S2V_LAUNCH_BWD_W(PP, NODE, MASK, WW)                                                                        \
-    k_bwd_round<PP, NODE, MASK, WW><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, N, S, rowptr, rowend, colidx, wagg,     \
+    k_bwd_round<PP, NODE, MASK, WW><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg,     \
                                                                    dz_in, maskT, sc.dg, sc.glo, sc.ghi, mu_prev, dz_out, \
                                                                    ni, theta2, dc_part, d2_part, ht, hub_sum)
 #define S2V_LAUNCH_BWD(PP, NODE, MASK)                    \
@@ -474,7 +474,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 // (k, s) takes the entries of row a_s congruent to k modulo kFixSplit; thread = (slot, column).
 // ------------------------------------------------------------------------------------------
 template <int P>
-__global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int32_t *__restrict__ rowptr,
+__global__ __launch_bounds__(256) void k_bwd_action_fix(int S, const int32_t *__restrict__ rowptr,
                                                         const int32_t *__restrict__ rowend,
                                                         const int32_t *__restrict__ colidx,
                                                         const float *__restrict__ wagg /*NULL: unweighted sum*/,
@@ -539,17 +539,17 @@ __global__ __launch_bounds__(256) void k_bwd_action_fix(int N, int S, const int3
     }
 }
 
-hipError_t launch_bwd_action_fix(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+hipError_t launch_bwd_action_fix(hipStream_t st, int p, int S, const int32_t *rowptr, const int32_t *rowend,
                                  const int32_t *colidx, const float *wagg,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
                                  const float *theta2, const float *mu_prev, float *dz_out, const NodeInfo &ni,
                                  float *dc_part, float *d2_part) {
     const dim3 grid(kFixSplit, S);
     if (p == 32)
-        k_bwd_action_fix<32><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, wagg, action, maskT, sc.da, theta2, mu_prev,
+        k_bwd_action_fix<32><<<grid, 256, 0, st>>>(S, rowptr, rowend, colidx, wagg, action, maskT, sc.da, theta2, mu_prev,
                                                    dz_out, ni, dc_part, d2_part);
     else
-        k_bwd_action_fix<64><<<grid, 256, 0, st>>>(N, S, rowptr, rowend, colidx, wagg, action, maskT, sc.da, theta2, mu_prev,
+        k_bwd_action_fix<64><<<grid, 256, 0, st>>>(S, rowptr, rowend, colidx, wagg, action, maskT, sc.da, theta2, mu_prev,
                                                    dz_out, ni, dc_part, d2_part);
     return hipGetLastError();
 }
