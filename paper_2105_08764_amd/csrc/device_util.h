@@ -168,6 +168,139 @@ __device__ __forceinline__ float4 gather_row_sum(const Loader &row, const int *_
     return a0;
 }
 
+// The round-2 neighbour sum for S = 1 (records {x, s+, s-, pad}, see Mu1RowSingle), with the cheap
+// case split off: for a neighbour with x = 0 and s- = 0 the recomputed row is
+// relu(s+ q+) = s+ relu(q+) (s+ >= 0), i.e. linear in one scalar, so such neighbours only add
+// s+ (times the edge weight when W) to a running scalar and the vector arithmetic runs for the
+// others alone (a wave-uniform branch per wave-wide load).  On a partial solution that marks few
+// nodes and with non-negative weights almost every neighbour is of the cheap kind.  Same
+// arguments and result as gather_row_sum; rp = relu(q+) at this lane's columns.
+template <int P, bool W>
+__device__ __forceinline__ float4 gather_row_sum_mu1_single(const float *__restrict__ rec, float4 t1, float4 qp,
+                                                            float4 qn, float4 rp, const int *__restrict__ colidx,
+                                                            const float *__restrict__ wagg, int b, int e, int cols,
+                                                            int lane) {
+    constexpr int NPL = Geo<P>::NPL, LPR = Geo<P>::LPR;
+    const int gq = lane / LPR;
+    float4 total = make_float4(0.f, 0.f, 0.f, 0.f);
+    float stotal = 0.f;
+    for (int base = b; base < e; base += 64) {
+        const int cnt = min(64, e - base);
+        if (base != b) cols = (lane < cnt) ? colidx[base + lane] : 0;
+        float wv = 0.f;
+        if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
+        const int last = cnt - 1;
+        float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0;
+        float s0acc = 0.f, s1acc = 0.f;
+        for (int s0 = 0; s0 < cnt; s0 += 8 * NPL) {
+            float4 r[8];
+            float wk[8];
+            int sl[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                sl[k] = s0 + gq + k * NPL;
+                const int at = min(sl[k], last);   // past the end: a live lane's record again, dropped below
+                r[k] = ld4(rec + (size_t)__shfl(cols, at) * 4);
+                wk[k] = W ? __shfl(wv, at) : 1.f;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool live = sl[k] < cnt;
+                const bool cheap = r[k].x == 0.f && r[k].z == 0.f;
+                const float sadd = (live && cheap) ? wk[k] * r[k].y : 0.f;
+                if (k & 1) s1acc += sadd; else s0acc += sadd;
+                const bool full = live && !cheap;
+                if (__ballot(full) != 0ull) {
+                    float4 m;
+                    m.x = fmaxf(r[k].x * t1.x + r[k].y * qp.x + r[k].z * qn.x, 0.f);
+                    m.y = fmaxf(r[k].x * t1.y + r[k].y * qp.y + r[k].z * qn.y, 0.f);
+                    m.z = fmaxf(r[k].x * t1.z + r[k].y * qp.z + r[k].z * qn.z, 0.f);
+                    m.w = fmaxf(r[k].x * t1.w + r[k].y * qp.w + r[k].z * qn.w, 0.f);
+                    const float wf = full ? wk[k] : 0.f;
+                    if (k & 1) a1 = make_float4(fmaf(wf, m.x, a1.x), fmaf(wf, m.y, a1.y), fmaf(wf, m.z, a1.z), fmaf(wf, m.w, a1.w));
+                    else a0 = make_float4(fmaf(wf, m.x, a0.x), fmaf(wf, m.y, a0.y), fmaf(wf, m.z, a0.z), fmaf(wf, m.w, a0.w));
+                }
+            }
+        }
+        total = add4(total, add4(a0, a1));
+        stotal += s0acc + s1acc;
+    }
+    float4 a0 = make_float4(fmaf(stotal, rp.x, total.x), fmaf(stotal, rp.y, total.y), fmaf(stotal, rp.z, total.z),
+                            fmaf(stotal, rp.w, total.w));
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) {
+        a0.x += __shfl_xor(a0.x, m);
+        a0.y += __shfl_xor(a0.y, m);
+        a0.z += __shfl_xor(a0.z, m);
+        a0.w += __shfl_xor(a0.w, m);
+    }
+    return a0;
+}
+
+// Round 2 for S = 1, a whole tile at once and one LANE per neighbour: the column indices of eight
+// rows are fetched together, then the 16-byte records of all their neighbours (up to 64 per row)
+// with one load per row, so a wave has hundreds of records in flight instead of 32.  Cheap
+// neighbours (see gather_row_sum_mu1_single) are summed by a wave reduction of one scalar; the few
+// others are visited one by one, lane j forming column j of relu(x theta1 + s+ q+ + s- q-).
+// Rows with more than 64 entries continue in 64-entry chunks; rows longer than max_len are skipped
+// (their sums are already in the tile).  rb / re: lane i (mod 16) holds begin / end of tile row i.
+// The result of row i goes to tile[i * STRIDE + column].  lc = {theta1, q+, q-} in LDS ([3][P]).
+template <int P>
+__device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float *__restrict__ rec, const float *lc,
+                                                       const int *__restrict__ colidx, int rb, int re, int max_len,
+                                                       int lane) {
+    constexpr int STRIDE = Geo<P>::STRIDE;
+    const int j = lane % P;
+    const float t1 = lc[j], qp = lc[P + j], qn = lc[2 * P + j];
+    const float rp = fmaxf(qp, 0.f);
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        int cols[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = 8 * half + k;
+            const int b = __shfl(rb, i), n = __shfl(re, i) - b;
+            cols[k] = (n <= max_len && lane < n) ? colidx[b + lane] : -1;   // lane < n <= 64 entries of the first chunk
+        }
+        float rx[8], rs[8], rn[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float4 r = make_float4(0.f, 0.f, 0.f, 0.f);       // no neighbour: adds nothing
+            if (cols[k] >= 0) r = ld4(rec + (size_t)cols[k] * 4);
+            rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = 8 * half + k;
+            const int b = __shfl(rb, i), e = __shfl(re, i);
+            if (e - b > max_len) continue;                     // wave-uniform
+            float ssum = 0.f, acc = 0.f;
+            float x = rx[k], sp = rs[k], sn = rn[k];
+            int base = b;
+            while (true) {
+                const bool cheap = x == 0.f && sn == 0.f;
+                ssum += cheap ? sp : 0.f;
+                unsigned long long todo = __ballot(!cheap);
+                while (todo != 0ull) {
+                    const int l = __ffsll((long long)todo) - 1;
+                    todo &= todo - 1ull;
+                    const float xl = readlane_f(x, l), pl = readlane_f(sp, l), nl = readlane_f(sn, l);
+                    acc += fmaxf(xl * t1 + pl * qp + nl * qn, 0.f);
+                }
+                base += 64;
+                if (base >= e) break;                          // wave-uniform
+                const int c = (base + lane < e) ? colidx[base + lane] : -1;
+                float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (c >= 0) r = ld4(rec + (size_t)c * 4);
+                x = r.x; sp = r.y; sn = r.z;
+            }
+#pragma unroll
+            for (int m = 1; m < 64; m <<= 1) ssum += __shfl_xor(ssum, m);
+            if (lane < P) tile[i * STRIDE + lane] = fmaf(ssum, rp, acc);
+        }
+    }
+}
+
 // Node mode (S a multiple of 16): the 16 rows of a wave tile are 16 consecutive states
 // s0 .. s0+15 of ONE node v, so every neighbour u contributes one contiguous block of 16 * P
 // floats, mu[u][s0 .. s0+15][:].  A wave-wide float4 load covers RPI = 64 / LPR of those rows

@@ -346,6 +346,10 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
                     if (hi >= 0) st4(tile + i * G::STRIDE + 4 * li, ld4(hub_sum + ((size_t)hi * S + si) * P + 4 * li));
                 }
             }
+            if (MU1 && !W && S == 1) {
+                // single state, round 2: one lane per neighbour, the whole tile's records in flight
+                gather_tile_mu1_single<P>(tile, info.base, lds_c, colidx, rb, re, kHubDegree, lane);
+            } else {
             int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
 #pragma unroll 1
@@ -363,8 +367,10 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
                 float4 a;
                 if (MU1) {
                     if (S == 1) {
-                        const Mu1RowSingle one{info.base, mu1.t1, mu1.qp, mu1.qn};
-                        a = gather_row_sum<P, W>(one, colidx, wagg, b, e, cols, lane);
+                        const float4 rp = make_float4(fmaxf(mu1.qp.x, 0.f), fmaxf(mu1.qp.y, 0.f), fmaxf(mu1.qp.z, 0.f),
+                                                      fmaxf(mu1.qp.w, 0.f));
+                        a = gather_row_sum_mu1_single<P, W>(info.base, mu1.t1, mu1.qp, mu1.qn, rp, colidx, wagg, b, e,
+                                                            cols, lane);
                     } else {
                         mu1.s = si;
                         a = gather_row_sum<P, W>(mu1, colidx, wagg, b, e, cols, lane);
@@ -374,6 +380,7 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
                     a = gather_row_sum<P, W>(mem, colidx, wagg, b, e, cols, lane);
                 }
                 if (lane < G::LPR) st4(tile + i * G::STRIDE + 4 * lane, a);
+            }
             }
         }
         __builtin_amdgcn_wave_barrier();
