@@ -21,6 +21,7 @@ struct Prepared {
     int32_t n_chunks;
     int32_t n_hubs;
     int32_t n_segs;
+    bool has_neg;   // some stored weight is negative
 };
 
 // Carves consecutive 256-byte aligned pieces out of a byte range.
@@ -461,10 +462,17 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_end), seg_end.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
     }
     S2V_TRY(launch_zero_i32(ctx->stream, N, at<int32_t>(ws, h.touched)));
-    S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, row_end_of(g), g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg)));
+    // whether any weight is negative: the first word of the (still unused) work list serves as the flag
+    int32_t *neg_flag = at<int32_t>(ws, h.list);
+    int32_t has_neg = 0;
+    S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
+    S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, row_end_of(g), g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg),
+                             neg_flag));
+    S2V_TRY(hipMemcpyAsync(&has_neg, neg_flag, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
+    S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
 
-    Prepared pr{ws, g->rowptr, g->colidx, N, g->nnz, G, n_chunks, n_hubs, n_segs};
+    Prepared pr{ws, g->rowptr, g->colidx, N, g->nnz, G, n_chunks, n_hubs, n_segs, has_neg != 0};
     for (Prepared &old : ctx->prepared)
         if (old.ws == ws) { old = pr; return S2V_OK; }
     ctx->prepared.push_back(pr);
@@ -516,11 +524,14 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     // per-(node, state) scalar records; with per-state residual graphs they hold each state's own edge sums
     const float *x_res = g->state_residual ? x : nullptr;
     const float *wagg = g->weighted_sum ? g->w : nullptr;   // NULL weights mean w = 1: the plain sum
+    // S = 1 without negative weights: round 2 reads a 4-byte table first (see gather_tile_mu1_single)
+    float *compact = (S == 1 && !pr->has_neg) ? info + (size_t)N * 4 : nullptr;
     if (x_res)
-        S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info));
+        S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info, compact));
     else
-        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info));
-    const NodeInfo ninfo = make_nodeinfo(info, S, x_res != nullptr);
+        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info, compact));
+    NodeInfo ninfo = make_nodeinfo(info, S, x_res != nullptr);
+    ninfo.compact = compact;
     if (mu_saved || T == 1)
         S2V_TRY(launch_round1(st, p, N, S, ninfo, x_res, T == 1, params->theta1, qvec, dest(1)));
     const bool fuse_gsum = gsum && S == 1 && G == 1 && T >= 2 && N > 0;
@@ -686,9 +697,9 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     const float *x_res = g->state_residual ? x : nullptr;
     const float *wagg = g->weighted_sum ? g->w : nullptr;   // NULL weights mean w = 1: the plain sum
     if (x_res)
-        S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, sc.rec));
+        S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, sc.rec, nullptr));
     else
-        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec));
+        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec, nullptr));
     const NodeInfo ninfo = make_nodeinfo(sc.rec, S, x_res != nullptr);
     S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part));
     float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);

@@ -238,21 +238,38 @@ __device__ __forceinline__ float4 gather_row_sum_mu1_single(const float *__restr
 }
 
 // Round 2 for S = 1, a whole tile at once and one LANE per neighbour: the column indices of eight
-// rows are fetched together, then the 16-byte records of all their neighbours (up to 64 per row)
-// with one load per row, so a wave has hundreds of records in flight instead of 32.  Cheap
-// neighbours (see gather_row_sum_mu1_single) are summed by a wave reduction of one scalar; the few
-// others are visited one by one, lane j forming column j of relu(x theta1 + s+ q+ + s- q-).
+// rows are fetched together, then the scalars of all their neighbours (up to 64 per row) with one
+// load per row, so a wave has hundreds of them in flight instead of 32.  Cheap neighbours (see
+// gather_row_sum_mu1_single) are summed by a wave reduction of one scalar; the few others are
+// visited one by one, lane j forming column j of relu(x theta1 + s+ q+ + s- q-).
+// COMPACT: the first load reads the 4-byte table compact[u] (s+ of a cheap neighbour, NaN for any
+// other) instead of the 16-byte record, and only the lanes that met a NaN fetch the record: the
+// table is a quarter of the records' size, so far more of it stays in the L2.
 // Rows with more than 64 entries continue in 64-entry chunks; rows longer than max_len are skipped
 // (their sums are already in the tile).  rb / re: lane i (mod 16) holds begin / end of tile row i.
 // The result of row i goes to tile[i * STRIDE + column].  lc = {theta1, q+, q-} in LDS ([3][P]).
-template <int P>
-__device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float *__restrict__ rec, const float *lc,
+template <int P, bool COMPACT>
+__device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float *__restrict__ rec,
+                                                       const float *__restrict__ compact, const float *lc,
                                                        const int *__restrict__ colidx, int rb, int re, int max_len,
                                                        int lane) {
     constexpr int STRIDE = Geo<P>::STRIDE;
     const int j = lane % P;
     const float t1 = lc[j], qp = lc[P + j], qn = lc[2 * P + j];
     const float rp = fmaxf(qp, 0.f);
+    // the scalars of neighbour u as {x, s+, s-}; a missing neighbour (u < 0) adds nothing
+    auto fetch = [&](int u, float &x, float &sp, float &sn) {
+        x = 0.f; sp = 0.f; sn = 0.f;
+        if (COMPACT) {
+            const float c = u >= 0 ? compact[u] : 0.f;
+            if (c == c) { sp = c; return; }
+            const float4 r = ld4(rec + (size_t)u * 4);
+            x = r.x; sp = r.y; sn = r.z;
+        } else if (u >= 0) {
+            const float4 r = ld4(rec + (size_t)u * 4);
+            x = r.x; sp = r.y; sn = r.z;
+        }
+    };
 #pragma unroll 1
     for (int half = 0; half < 2; ++half) {
         int cols[8];
@@ -263,11 +280,22 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
             cols[k] = (n <= max_len && lane < n) ? colidx[b + lane] : -1;   // lane < n <= 64 entries of the first chunk
         }
         float rx[8], rs[8], rn[8];
+        if (COMPACT) {
+            // all eight table loads first, then the record loads of the lanes that need one
+            float c[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            float4 r = make_float4(0.f, 0.f, 0.f, 0.f);       // no neighbour: adds nothing
-            if (cols[k] >= 0) r = ld4(rec + (size_t)cols[k] * 4);
-            rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
+            for (int k = 0; k < 8; ++k) c[k] = cols[k] >= 0 ? compact[cols[k]] : 0.f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                rx[k] = 0.f; rs[k] = c[k]; rn[k] = 0.f;
+                if (c[k] != c[k]) {
+                    const float4 r = ld4(rec + (size_t)cols[k] * 4);
+                    rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) fetch(cols[k], rx[k], rs[k], rn[k]);
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -289,10 +317,7 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
                 }
                 base += 64;
                 if (base >= e) break;                          // wave-uniform
-                const int c = (base + lane < e) ? colidx[base + lane] : -1;
-                float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (c >= 0) r = ld4(rec + (size_t)c * 4);
-                x = r.x; sp = r.y; sn = r.z;
+                fetch((base + lane < e) ? colidx[base + lane] : -1, x, sp, sn);
             }
 #pragma unroll
             for (int m = 1; m < 64; m <<= 1) ssum += __shfl_xor(ssum, m);

@@ -13,7 +13,7 @@ namespace s2v {
 __global__ __launch_bounds__(256) void k_prepare_s(int N, const int32_t *__restrict__ rowptr,
                                                    const int32_t *__restrict__ rowend,
                                                    const float *__restrict__ w, float *__restrict__ s_pos,
-                                                   float *__restrict__ s_neg) {
+                                                   float *__restrict__ s_neg, int32_t *__restrict__ neg_flag) {
     for (int v = blockIdx.x * blockDim.x + threadIdx.x; v < N; v += gridDim.x * blockDim.x) {
         const int b = rowptr[v], e = rowend[v];
         double sp = 0.0, sn = 0.0;
@@ -28,14 +28,15 @@ __global__ __launch_bounds__(256) void k_prepare_s(int N, const int32_t *__restr
         }
         s_pos[v] = (float)sp;
         s_neg[v] = (float)sn;
+        if (neg_flag && sn > 0.0) atomicOr(neg_flag, 1);   // the graph has a negative weight
     }
 }
 
 hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const float *w,
-                            float *s_pos, float *s_neg) {
+                            float *s_pos, float *s_neg, int32_t *neg_flag) {
     if (N == 0) return hipSuccess;
     const int grid = min((N + 255) / 256, 65536);
-    k_prepare_s<<<grid, 256, 0, st>>>(N, rowptr, rowend, w, s_pos, s_neg);
+    k_prepare_s<<<grid, 256, 0, st>>>(N, rowptr, rowend, w, s_pos, s_neg, neg_flag);
     return hipGetLastError();
 }
 
@@ -113,7 +114,7 @@ hipError_t launch_round1(hipStream_t st, int p, int N, int S, const NodeInfo &ni
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const float *__restrict__ x,
                                                   const float *__restrict__ s_pos, const float *__restrict__ s_neg,
-                                                  float *__restrict__ info) {
+                                                  float *__restrict__ info, float *__restrict__ compact) {
     const long total = (long)N * ni;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
         const int v = (int)(i / ni), c = (int)(i - (long)v * ni);
@@ -122,15 +123,18 @@ __global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const fl
         else if (c == S) o = s_pos[v];
         else if (c == S + 1) o = s_neg[v];
         info[i] = o;
+        // S = 1: s+ alone for a node whose round-1 row is s+ relu(q+), NaN for any other node
+        if (compact && c == 0) compact[v] = (o == 0.f && s_neg[v] == 0.f) ? s_pos[v] : __int_as_float(0x7fc00000);
     }
 }
 
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
-                           float *info) {
+                           float *info, float *compact) {
     if (N == 0) return hipSuccess;
     const int ni = make_nodeinfo(info, S, false).ni;
     const long total = (long)N * ni;
-    k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info);
+    k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info,
+                                                                           S == 1 ? compact : nullptr);
     return hipGetLastError();
 }
 
@@ -206,17 +210,21 @@ __global__ __launch_bounds__(256) void k_stateinfo_hubs(int S, int ni, HubTable 
     }
 }
 
-__global__ __launch_bounds__(256) void k_stateinfo_clear_x(int N, int S, int ni, float *__restrict__ info) {
+__global__ __launch_bounds__(256) void k_stateinfo_clear_x(int N, int S, int ni, float *__restrict__ info,
+                                                           float *__restrict__ compact) {
     const long total = (long)N * S;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
         const int v = (int)i / S, s = (int)i - v * S;   // N * S < 2^31: 32-bit division
-        info[(size_t)v * ni + s] = 0.f;   // a live node has x = 0 already, a solution node gets it now
+        float *mine = info + (size_t)v * ni;
+        mine[s] = 0.f;   // a live node has x = 0 already, a solution node gets it now
+        // S = 1 (see k_nodeinfo): x is 0 for every node here
+        if (compact) compact[v] = mine[2] == 0.f ? mine[1] : __int_as_float(0x7fc00000);
     }
 }
 
 hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTable &ht, const int32_t *rowptr,
                                      const int32_t *rowend, const int32_t *colidx, const float *w, const float *x,
-                                     float *info) {
+                                     float *info, float *compact) {
     if (N == 0) return hipSuccess;
     const int ni = make_nodeinfo(info, S, true).ni;
     const long total = (long)N * S;
@@ -232,7 +240,7 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
                                                                                  info);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    k_stateinfo_clear_x<<<grid, 256, 0, st>>>(N, S, ni, info);
+    k_stateinfo_clear_x<<<grid, 256, 0, st>>>(N, S, ni, info, S == 1 ? compact : nullptr);
     return hipGetLastError();
 }
 
@@ -348,7 +356,10 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
             }
             if (MU1 && !W && S == 1) {
                 // single state, round 2: one lane per neighbour, the whole tile's records in flight
-                gather_tile_mu1_single<P>(tile, info.base, lds_c, colidx, rb, re, kHubDegree, lane);
+                if (info.compact)
+                    gather_tile_mu1_single<P, true>(tile, info.base, info.compact, lds_c, colidx, rb, re, kHubDegree, lane);
+                else
+                    gather_tile_mu1_single<P, false>(tile, info.base, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
             } else {
             int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;

@@ -56,6 +56,8 @@ struct NodeInfo {
     int sp_off;   // offset of s+ (of state 0)
     int sn_off;   // offset of s- (of state 0)
     int ss;       // stride over states of s+ / s-: 0 or 1
+    // S = 1 only, optional: compact[v] = s+ of v if its round-1 row is s+ relu(q+) (x = 0 and s- = 0), else NaN
+    const float *__restrict__ compact;
     __device__ __forceinline__ const float *node(int v) const { return base + (size_t)v * ni; }
     __device__ __forceinline__ float x(int v, int s) const { return node(v)[s]; }
     __device__ __forceinline__ float sp(int v, int s) const { return node(v)[sp_off + s * ss]; }
@@ -71,8 +73,8 @@ struct NodeInfo {
     }
 };
 
-// Floats reserved per node for the records (an upper bound of both layouts).
-inline int nodeinfo_stride(int S) { return 4 * S; }
+// Floats reserved per node for the records (an upper bound of both layouts) and the compact table.
+inline int nodeinfo_stride(int S) { return 4 * S + 1; }
 inline NodeInfo make_nodeinfo(const float *base, int S, bool per_state) {
     NodeInfo n;
     n.base = base;
@@ -81,19 +83,21 @@ inline NodeInfo make_nodeinfo(const float *base, int S, bool per_state) {
     n.sn_off = S + (per_state ? S : 1);
     n.ss = per_state ? 1 : 0;
     n.ni = (n.sn_off + (per_state ? S : 1) + 3) / 4 * 4;
+    n.compact = nullptr;
     return n;
 }
 
 // ---- forward (fwd_kernels.hip) ----
 hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const float *w,
-                            float *s_pos, float *s_neg);
+                            float *s_pos, float *s_neg, int32_t *neg_flag /*set to 1 if a weight is negative; may be NULL*/);
 hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec);
 // x_res != NULL in the round launchers: per-state residual graphs (x_res is the caller's x [S][N]).
 hipError_t launch_round1(hipStream_t st, int p, int N, int S, const NodeInfo &ni, const float *x_res, bool last,
                          const float *theta1, const float *qvec, float *mu_out);
 hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTable &ht, const int32_t *rowptr,
                                      const int32_t *rowend, const int32_t *colidx, const float *w, const float *x,
-                                     float *info /*written in the per-state layout of make_nodeinfo*/);
+                                     float *info /*written in the per-state layout of make_nodeinfo*/,
+                                     float *compact /*[N], written when S == 1; may be NULL*/);
 // upper bound of the embedding-round grid (also the number of partial rows of its fused graph sum)
 #ifndef S2V_ROUND_GRID
 #define S2V_ROUND_GRID (256 * 16)
@@ -101,7 +105,8 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 constexpr int kRoundGridMax = S2V_ROUND_GRID;
 int round_grid(long n_vrows);
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
-                           float *info /*written in the shared-sums layout of make_nodeinfo*/);
+                           float *info /*written in the shared-sums layout of make_nodeinfo*/,
+                           float *compact /*[N], written when S == 1; may be NULL*/);
 // Neighbour sums of the hub rows: hub_sum[h][S][p] = sum over the row of hub h of src[u][s][:]
 // (mask != NULL: counts of set relu-mask bits instead; else src == NULL: the round-1 rows
 // recomputed from info).  partial is [n_segs][S][p] scratch.
