@@ -466,6 +466,249 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 }
 
 // ------------------------------------------------------------------------------------------
+// The last reversed round (t = 2) in node mode, taken from the scalars instead of gathering dz^2.
+// What the round must deliver is only sums over the nodes (dz^1 is never needed as a matrix):
+//   dtheta2[i][j] += sum_u G_u[i] mu^1_u[j],   sum_u x_u dz^1_u,  sum_u s+-_u dz^1_u,
+//   with G = A dz^2 and dz^1_u = (theta2^T G_u) (.) [mu^1_u > 0].
+// Moving the (symmetric) adjacency to the other factor,
+//   sum_u G_u[i] mu^1_u[j]      = sum_v dz^2_v[i] a_v[j],         a_v  = sum_{u in N(v)} mu^1_u,
+//   sum_u x_u dz^1_u[j]         = sum_v e_v[j] cx_v[j],           e_v  = theta2^T dz^2_v,
+//                                                                 cx_v = sum_{u in N(v)} x_u [mu^1_u > 0],
+// (likewise with s+ and s-), and mu^1_u is a function of the three scalars of u.  So the kernel
+// STREAMS dz^2 once and gathers the neighbours' scalars (80 bytes per neighbour at S = 16, see
+// gather_node_block_mu1_grad) where the generic round gathers 4 KB rows of dz^2 and reads mu^1.
+//   FROM_MASK: T == 2, so dz^2 = dz^T is not in memory: it is rebuilt per row from the relu-mask word,
+//              dg and, at the action node, da (no separate action pass is needed then).
+// A wave owns one node's 16-state block at a time; hub_sum4 holds the four sums of the long rows
+// as [hub][4][S][P].
+// ------------------------------------------------------------------------------------------
+template <int P, bool W, bool FROM_MASK, bool NEG>
+__global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
+    int n_vrows, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
+    const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in,
+    const unsigned long long *__restrict__ maskT, const float *__restrict__ dg, const float *__restrict__ da,
+    const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const int32_t *__restrict__ action,
+    NodeInfo ni, const float *__restrict__ theta1, const float *__restrict__ theta2,
+    const float *__restrict__ qvec, float *__restrict__ dc_part, float *__restrict__ d2_part, HubTable ht,
+    const float *__restrict__ hub_sum4) {
+    using Ge = Geo<P>;
+    constexpr int CB = Ge::CB, STRIDE = Ge::STRIDE, LPR = Ge::LPR, RPI = Ge::NPL, NC = 16 / RPI;
+    constexpr int TILE_F = kTileRows * STRIDE;
+    static_assert(2 * kWaves * TILE_F >= kWaves * 16 * P, "tile area is reused for the final reductions");
+    __shared__ __attribute__((aligned(16))) float lds[2 * kWaves * TILE_F];   // per wave: dz^2 tile, a tile
+    __shared__ __attribute__((aligned(16))) float lds_b[P * STRIDE];          // theta2^T: B operand of dz theta2
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float *tile_d = lds + wave * 2 * TILE_F, *tile_a = tile_d + TILE_F;
+    const int li = lane % LPR;
+    const int jl = lane & 15, gl = lane >> 4;
+
+    stage_matrix_lds<P>(lds_b, theta2, true);
+    __syncthreads();
+
+    f32x4 d2acc[CB][CB];
+#pragma unroll
+    for (int ib = 0; ib < CB; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < CB; ++jb) d2acc[ib][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float4 cx4 = make_float4(0.f, 0.f, 0.f, 0.f), cp4 = cx4, cn4 = cx4;
+
+    const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const int r0 = t * kWgRows + wave * kTileRows;
+        if (r0 >= n_vrows) continue;        // S is a multiple of 16: tiles are whole
+        const int v = r0 / S, s0 = r0 - v * S;
+        const int b = rowptr[v], e = rowend[v];
+
+        // this node's 16 rows of dz^2, lane (row c * RPI + lane / LPR, columns 4 * li ..)
+        NodeAcc<P> dz;
+        if (FROM_MASK) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const int s = s0 + c * RPI + lane / LPR;
+                const unsigned nib = (unsigned)(maskT[(size_t)v * S + s] >> (4 * li)) & 15u;
+                float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * li);
+                if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * li));
+                dz.a[c] = make_float4((nib & 1u) ? d.x : 0.f, (nib & 2u) ? d.y : 0.f, (nib & 4u) ? d.z : 0.f,
+                                      (nib & 8u) ? d.w : 0.f);
+            }
+        } else {
+            dz = load_node_block<P>(dz_in + (size_t)r0 * P, lane);
+        }
+        store_node_block<P>(tile_d, dz, lane);
+
+        NodeAcc4<P> g4;
+        if (e - b > kHubDegree) {
+            const int h = hub_index(ht.hub_rows, ht.n_hubs, v);
+            const float *hb = hub_sum4 + ((size_t)h * 4 * S + s0) * P;
+            g4.a = load_node_block<P>(hb, lane);
+            g4.cx = load_node_block<P>(hb + (size_t)S * P, lane);
+            g4.cp = load_node_block<P>(hb + 2 * (size_t)S * P, lane);
+            g4.cn = load_node_block<P>(hb + 3 * (size_t)S * P, lane);
+        } else {
+            g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+        }
+        store_node_block<P>(tile_a, g4.a, lane);
+        __builtin_amdgcn_wave_barrier();
+
+        // e = dz^2 theta2 (row r, column j: sum_k dz^2[r][k] theta2[k][j])
+        const Frag<P> afrag = load_a_frag_lds<P>(tile_d, lane);
+        f32x4 acc[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            acc[cb] = mfma_tile<P>(afrag, load_b_frag_lds<P>(lds_b, cb, lane), acc[cb]);
+        }
+        // dtheta2[i][j] += sum_r dz^2[r][i] a[r][j]: 16x16 blocks, k runs over the 16 tile rows
+        float ya[CB][4];
+#pragma unroll
+        for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) ya[jb][ks] = tile_a[(4 * gl + ks) * STRIDE + 16 * jb + jl];
+#pragma unroll
+        for (int ib = 0; ib < CB; ++ib) {
+            float a2[4];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) a2[ks] = tile_d[(4 * gl + ks) * STRIDE + 16 * ib + jl];
+#pragma unroll
+            for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    d2acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[ks], ya[jb][ks], d2acc[ib][jb], 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();
+        // e back into the layout of the gathered sums, through the dz tile
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) tile_d[(4 * gl + rr) * STRIDE + 16 * cb + jl] = acc[cb][rr];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const float4 e4 = ld4(tile_d + (c * RPI + lane / LPR) * STRIDE + 4 * li);
+            cx4.x = fmaf(e4.x, g4.cx.a[c].x, cx4.x); cx4.y = fmaf(e4.y, g4.cx.a[c].y, cx4.y);
+            cx4.z = fmaf(e4.z, g4.cx.a[c].z, cx4.z); cx4.w = fmaf(e4.w, g4.cx.a[c].w, cx4.w);
+            cp4.x = fmaf(e4.x, g4.cp.a[c].x, cp4.x); cp4.y = fmaf(e4.y, g4.cp.a[c].y, cp4.y);
+            cp4.z = fmaf(e4.z, g4.cp.a[c].z, cp4.z); cp4.w = fmaf(e4.w, g4.cp.a[c].w, cp4.w);
+            if (NEG) {
+                cn4.x = fmaf(e4.x, g4.cn.a[c].x, cn4.x); cn4.y = fmaf(e4.y, g4.cn.a[c].y, cn4.y);
+                cn4.z = fmaf(e4.z, g4.cn.a[c].z, cn4.z); cn4.w = fmaf(e4.w, g4.cn.a[c].w, cn4.w);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- workgroup reductions, fixed order over the four waves ----
+    __syncthreads();
+#pragma unroll
+    for (int ib = 0; ib < CB; ++ib) {
+        float *slab = lds + wave * (16 * P);
+#pragma unroll
+        for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) slab[(4 * gl + rr) * P + 16 * jb + jl] = d2acc[ib][jb][rr];
+        __syncthreads();
+        for (int el = threadIdx.x; el < 16 * P; el += kThreads) {
+            const float sum = (lds[el] + lds[16 * P + el]) + (lds[2 * 16 * P + el] + lds[3 * 16 * P + el]);
+            d2_part[(size_t)blockIdx.x * P * P + (size_t)ib * 16 * P + el] = sum;
+        }
+        __syncthreads();
+    }
+    // the three column sums: lanes with equal li first, then the waves
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) {
+        cx4.x += __shfl_xor(cx4.x, m); cx4.y += __shfl_xor(cx4.y, m); cx4.z += __shfl_xor(cx4.z, m); cx4.w += __shfl_xor(cx4.w, m);
+        cp4.x += __shfl_xor(cp4.x, m); cp4.y += __shfl_xor(cp4.y, m); cp4.z += __shfl_xor(cp4.z, m); cp4.w += __shfl_xor(cp4.w, m);
+        cn4.x += __shfl_xor(cn4.x, m); cn4.y += __shfl_xor(cn4.y, m); cn4.z += __shfl_xor(cn4.z, m); cn4.w += __shfl_xor(cn4.w, m);
+    }
+    if (lane < LPR) {
+        st4(lds + (wave * 3 + 0) * P + 4 * lane, cx4);
+        st4(lds + (wave * 3 + 1) * P + 4 * lane, cp4);
+        st4(lds + (wave * 3 + 2) * P + 4 * lane, cn4);
+    }
+    __syncthreads();
+    for (int el = threadIdx.x; el < 3 * P; el += kThreads) {
+        const float sum = (lds[el] + lds[3 * P + el]) + (lds[2 * 3 * P + el] + lds[3 * 3 * P + el]);
+        dc_part[(size_t)blockIdx.x * 3 * P + el] = sum;
+    }
+}
+
+hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                            const int32_t *colidx, const float *wagg, const float *dz_in,
+                            const unsigned long long *maskT, const int32_t *action, const BwdScratch &sc,
+                            const NodeInfo &ni, bool has_neg, const float *theta1, const float *theta2,
+                            const float *qvec, float *dc_part, float *d2_part, const HubTable &ht,
+                            const float *hub_sum4) {
+    const long n_vrows = (long)N * S;
+#define S2V_LAUNCH_FIRST(PP, WW, MM, NN)                                                                           \
+    k_bwd_first<PP, WW, MM, NN><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, dz_in,    \
+                                                               maskT, sc.dg, sc.da, sc.glo, sc.ghi, action, ni, theta1, \
+                                                               theta2, qvec, dc_part, d2_part, ht, hub_sum4)
+#define S2V_LAUNCH_FIRST_N(PP, WW, MM) \
+    do { if (has_neg) S2V_LAUNCH_FIRST(PP, WW, MM, true); else S2V_LAUNCH_FIRST(PP, WW, MM, false); } while (0)
+#define S2V_LAUNCH_FIRST_M(PP, WW) \
+    do { if (dz_in) S2V_LAUNCH_FIRST_N(PP, WW, false); else S2V_LAUNCH_FIRST_N(PP, WW, true); } while (0)
+#define S2V_LAUNCH_FIRST_W(PP) \
+    do { if (wagg) S2V_LAUNCH_FIRST_M(PP, true); else S2V_LAUNCH_FIRST_M(PP, false); } while (0)
+    if (p == 32) S2V_LAUNCH_FIRST_W(32); else S2V_LAUNCH_FIRST_W(64);
+#undef S2V_LAUNCH_FIRST_W
+#undef S2V_LAUNCH_FIRST_M
+#undef S2V_LAUNCH_FIRST_N
+#undef S2V_LAUNCH_FIRST
+    return hipGetLastError();
+}
+
+// The four sums of the long rows for k_bwd_first: one wave per (64-entry segment, 16-state block),
+// then the segments of a row added in order (k_hub_combine with rows of 4 * S * p floats).
+template <int P, bool W, bool NEG>
+__global__ __launch_bounds__(kThreads) void k_hub_partial_grad(int S, HubTable ht, const int32_t *__restrict__ rowend,
+                                                               const int32_t *__restrict__ colidx,
+                                                               const float *__restrict__ wagg, NodeInfo ni,
+                                                               const float *__restrict__ theta1,
+                                                               const float *__restrict__ qvec,
+                                                               float *__restrict__ partial) {
+    using Ge = Geo<P>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int bpn = S / 16;
+    const long items = (long)ht.n_segs * bpn;
+    for (long item = (long)blockIdx.x * kWaves + wave; item < items; item += (long)gridDim.x * kWaves) {
+        const int seg = (int)(item / bpn), s0 = (int)(item - (long)seg * bpn) * 16;
+        const int b = ht.seg_begin[seg], e = min(ht.seg_end[seg], rowend[ht.seg_row[seg]]);
+        const NodeAcc4<P> g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+        float *out = partial + ((size_t)seg * 4 * S + s0) * P;
+#pragma unroll
+        for (int c = 0; c < 16 / Ge::NPL; ++c) {
+            const size_t o = (size_t)c * Ge::NPL * P + 4 * lane;
+            st4(out + o, g4.a.a[c]);
+            st4(out + (size_t)S * P + o, g4.cx.a[c]);
+            st4(out + 2 * (size_t)S * P + o, g4.cp.a[c]);
+            st4(out + 3 * (size_t)S * P + o, NEG ? g4.cn.a[c] : make_float4(0.f, 0.f, 0.f, 0.f));
+        }
+    }
+}
+
+hipError_t launch_hub_sums_grad(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
+                                const int32_t *colidx, const float *wagg, const NodeInfo &ni, bool has_neg,
+                                const float *theta1, const float *qvec, float *partial4, float *hub_sum4) {
+    if (ht.n_hubs == 0) return hipSuccess;
+    const long items = (long)ht.n_segs * (S / 16);
+    const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
+#define S2V_LAUNCH_HG(PP, WW, NN) \
+    k_hub_partial_grad<PP, WW, NN><<<grid, kThreads, 0, st>>>(S, ht, rowend, colidx, wagg, ni, theta1, qvec, partial4)
+#define S2V_LAUNCH_HG_N(PP, WW) \
+    do { if (has_neg) S2V_LAUNCH_HG(PP, WW, true); else S2V_LAUNCH_HG(PP, WW, false); } while (0)
+#define S2V_LAUNCH_HG_W(PP) \
+    do { if (wagg) S2V_LAUNCH_HG_N(PP, true); else S2V_LAUNCH_HG_N(PP, false); } while (0)
+    if (p == 32) S2V_LAUNCH_HG_W(32); else S2V_LAUNCH_HG_W(64);
+#undef S2V_LAUNCH_HG_W
+#undef S2V_LAUNCH_HG_N
+#undef S2V_LAUNCH_HG
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    return launch_hub_combine(st, 4 * S * p, ht, partial4, hub_sum4);
+}
+
+// ------------------------------------------------------------------------------------------
 // The action node's own term of dz^T, which the MASK round leaves out:
 //   dz^T[a_s][s] += da[s] (.) [mu^T[a_s][s] > 0] =: g_s.
 // The round is linear in dz^T, so its effect is added here.  Only the rows u in N(a_s) see it:

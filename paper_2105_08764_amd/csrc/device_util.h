@@ -472,6 +472,102 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const NodeInfo &ni, 
     return gather_node_block_mu1_impl<P, W, false>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
 }
 
+// The neighbour sums that the LAST reversed round (t = 2) needs when it is taken from the scalars
+// instead of gathering dz^2 (node mode).  With z_u = x_u theta1 + s+_u q+ + s-_u q- (the round-1
+// pre-activation of neighbour u, recomputed as in gather_node_block_mu1) and m_u = [z_u > 0]:
+//   a  = sum_u relu(z_u)    (the round-2 neighbour sum of mu^1: the second factor of dtheta2)
+//   cx = sum_u x_u m_u,   cp = sum_u s+_u m_u,   cn = sum_u s-_u m_u
+// each weighted by the edge weight when W.  NEG = false: no weight of the graph is negative, so
+// s- = 0 everywhere and cn is not formed.  One running sum per quantity: callers pass at most
+// kHubDegree entries (longer rows go through 64-entry segments).
+template <int P>
+struct NodeAcc4 {
+    NodeAcc<P> a, cx, cp, cn;
+};
+
+template <int P, bool W, bool SHARED, bool NEG>
+__device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad_impl(const NodeInfo &ni, int s0,
+                                                                       const float *__restrict__ theta1,
+                                                                       const float *__restrict__ qvec,
+                                                                       const int *__restrict__ colidx,
+                                                                       const float *__restrict__ wagg, int b, int e,
+                                                                       int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+    NodeAcc4<P> r;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        r.a.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        r.cx.a[c] = r.a.a[c]; r.cp.a[c] = r.a.a[c]; r.cn.a[c] = r.a.a[c];
+    }
+    const int col = 4 * (lane % LPR);
+    const float4 t1 = ld4(theta1 + col), qp = ld4(qvec + col), qn = ld4(qvec + P + col);
+    const int srow = s0 + lane / LPR;
+    for (int base = b; base < e; base += 64) {
+        const int cnt = min(64, e - base);
+        const int cols = (lane < cnt) ? colidx[base + lane] : 0;
+        float wv = 0.f;
+        if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
+        for (int j = 0; j < cnt; j += 2) {
+            float xs[2][NC], sp[2][SHARED ? 1 : NC], sn[2][SHARED ? 1 : NC];
+            float wk[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int jj = min(j + k, cnt - 1);   // past the end: re-read the last record, weight 0 below
+                const float *rec = ni.node(__builtin_amdgcn_readlane(cols, jj));
+                wk[k] = (j + k < cnt) ? (W ? readlane_f(wv, jj) : 1.f) : 0.f;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) xs[k][c] = rec[srow + c * RPI];
+                if (SHARED) {
+                    sp[k][0] = rec[ni.sp_off];
+                    sn[k][0] = NEG ? rec[ni.sn_off] : 0.f;
+                } else {
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        sp[k][SHARED ? 0 : c] = rec[ni.sp_off + srow + c * RPI];
+                        sn[k][SHARED ? 0 : c] = NEG ? rec[ni.sn_off + srow + c * RPI] : 0.f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const float w = wk[k];
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const float p_ = sp[k][SHARED ? 0 : c], n_ = sn[k][SHARED ? 0 : c], x_ = xs[k][c];
+                    // the same expression as the forward pass, so that the masks agree
+                    const float zx = x_ * t1.x + p_ * qp.x + n_ * qn.x, zy = x_ * t1.y + p_ * qp.y + n_ * qn.y;
+                    const float zz = x_ * t1.z + p_ * qp.z + n_ * qn.z, zw = x_ * t1.w + p_ * qp.w + n_ * qn.w;
+                    r.a.a[c].x = fmaf(w, fmaxf(zx, 0.f), r.a.a[c].x);
+                    r.a.a[c].y = fmaf(w, fmaxf(zy, 0.f), r.a.a[c].y);
+                    r.a.a[c].z = fmaf(w, fmaxf(zz, 0.f), r.a.a[c].z);
+                    r.a.a[c].w = fmaf(w, fmaxf(zw, 0.f), r.a.a[c].w);
+                    const float fx = zx > 0.f ? w : 0.f, fy = zy > 0.f ? w : 0.f;
+                    const float fz = zz > 0.f ? w : 0.f, fw = zw > 0.f ? w : 0.f;
+                    r.cx.a[c].x = fmaf(fx, x_, r.cx.a[c].x); r.cx.a[c].y = fmaf(fy, x_, r.cx.a[c].y);
+                    r.cx.a[c].z = fmaf(fz, x_, r.cx.a[c].z); r.cx.a[c].w = fmaf(fw, x_, r.cx.a[c].w);
+                    r.cp.a[c].x = fmaf(fx, p_, r.cp.a[c].x); r.cp.a[c].y = fmaf(fy, p_, r.cp.a[c].y);
+                    r.cp.a[c].z = fmaf(fz, p_, r.cp.a[c].z); r.cp.a[c].w = fmaf(fw, p_, r.cp.a[c].w);
+                    if (NEG) {
+                        r.cn.a[c].x = fmaf(fx, n_, r.cn.a[c].x); r.cn.a[c].y = fmaf(fy, n_, r.cn.a[c].y);
+                        r.cn.a[c].z = fmaf(fz, n_, r.cn.a[c].z); r.cn.a[c].w = fmaf(fw, n_, r.cn.a[c].w);
+                    }
+                }
+            }
+        }
+    }
+    return r;
+}
+
+template <int P, bool W, bool NEG>
+__device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad(const NodeInfo &ni, int s0,
+                                                                  const float *__restrict__ theta1,
+                                                                  const float *__restrict__ qvec,
+                                                                  const int *__restrict__ colidx,
+                                                                  const float *__restrict__ wagg, int b, int e, int lane) {
+    if (ni.ss == 0) return gather_node_block_mu1_grad_impl<P, W, true, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+    return gather_node_block_mu1_grad_impl<P, W, false, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+}
+
 // Weighted form of gather_node_block_bits: per column, the sum of the weights of the neighbours whose
 // entry is positive (per-chunk accumulators folded into a running total, as in the other gathers).
 template <int P>

@@ -603,6 +603,14 @@ __global__ __launch_bounds__(256) void k_hub_combine(int L, HubTable ht, const f
     }
 }
 
+// hub_sum[h][c] = sum over the segments of hub h, in segment order, of partial[seg][c]  (c < L)
+hipError_t launch_hub_combine(hipStream_t st, int L, const HubTable &ht, const float *partial, float *hub_sum) {
+    const long total = (long)ht.n_hubs * L;
+    if (total == 0) return hipSuccess;
+    k_hub_combine<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(L, ht, partial, hub_sum);
+    return hipGetLastError();
+}
+
 hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
                            const int32_t *colidx, const float *wagg, const float *src,
                            const NodeInfo &info, const float *theta1, const float *qvec,
@@ -636,10 +644,7 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
 #undef S2V_LAUNCH_HUB_W
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    const int L = S * p;
-    const long total = (long)ht.n_hubs * L;
-    k_hub_combine<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(L, ht, partial, hub_sum);
-    return hipGetLastError();
+    return launch_hub_combine(st, S * p, ht, partial, hub_sum);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -123,6 +123,7 @@ struct QHead {
 // whether launch_round honours a QHead for this S (else the caller runs the separate node-term kernel)
 inline bool round_fuses_qnode(int S) { return (S % 16) != 0; }
 hipError_t launch_qfinish(hipStream_t st, int N, int S, int G, const int32_t *graph_off, const float *qa, float *q);
+hipError_t launch_hub_combine(hipStream_t st, int L, const HubTable &ht, const float *partial, float *hub_sum);
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                         const int32_t *colidx, const float *wagg /*NULL: unweighted neighbour sum*/, const float *mu_in,
                         float *mu_out, const NodeInfo &ni, const float *theta1,
@@ -194,6 +195,19 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
                             const float *mu_prev, float *dz_out /*may be NULL*/, const NodeInfo &ni, const float *theta2,
                             float *dc_part /*[kBwdGrid][3][p]*/, float *d2_part /*[kBwdGrid][p][p]*/,
                             const HubTable &ht, const float *hub_sum);
+// The last reversed round (t = 2) from the scalars, node mode only (S a multiple of 16).  dz_in == NULL:
+// T == 2, dz^2 is rebuilt from maskT / dg / da (the action node's term included).
+hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
+                            const int32_t *colidx, const float *wagg, const float *dz_in,
+                            const unsigned long long *maskT, const int32_t *action, const BwdScratch &sc,
+                            const NodeInfo &ni, bool has_neg, const float *theta1, const float *theta2,
+                            const float *qvec, float *dc_part /*[kBwdGrid][3][p]*/,
+                            float *d2_part /*[kBwdGrid][p][p]*/, const HubTable &ht,
+                            const float *hub_sum4 /*[n_hubs][4][S][p]*/);
+hipError_t launch_hub_sums_grad(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
+                                const int32_t *colidx, const float *wagg, const NodeInfo &ni, bool has_neg,
+                                const float *theta1, const float *qvec, float *partial4 /*[n_segs][4][S][p]*/,
+                                float *hub_sum4 /*[n_hubs][4][S][p]*/);
 hipError_t launch_bwd_action_fix(hipStream_t st, int p, int S, const int32_t *rowptr, const int32_t *rowend,
                                  const int32_t *colidx, const float *wagg,
                                  const int32_t *action, const unsigned long long *maskT, const BwdScratch &sc,
