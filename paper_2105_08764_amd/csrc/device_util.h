@@ -412,6 +412,7 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1_impl(const NodeInfo 
     const int col = 4 * (lane % LPR);
     const float4 t1 = ld4(theta1 + col), qp = ld4(qvec + col), qn = ld4(qvec + P + col);
     const int srow = s0 + lane / LPR;
+    float ssum = 0.f;   // sum of (weight times) s+ over the neighbours whose rows are s+ relu(q+)
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         const int cols = (lane < cnt) ? colidx[base + lane] : 0;
@@ -444,6 +445,16 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1_impl(const NodeInfo 
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if (j + k < cnt) {
+                    if (SHARED) {
+                        // x = 0 in all 16 states and s- = 0: the row is s+ relu(q+) in every state
+                        bool any = false;
+#pragma unroll
+                        for (int c = 0; c < NC; ++c) any = any || xs[k][c] != 0.f;
+                        if (sn[k][0] == 0.f && __ballot(any) == 0ull) {
+                            ssum += wk[k] * sp[k][0];
+                            continue;
+                        }
+                    }
 #pragma unroll
                     for (int c = 0; c < NC; ++c) {
                         const float p_ = sp[k][SHARED ? 0 : c], n_ = sn[k][SHARED ? 0 : c], x_ = xs[k][c];
@@ -458,6 +469,13 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1_impl(const NodeInfo 
         }
 #pragma unroll
         for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], acc.a[c]);
+    }
+    if (SHARED) {
+        const float4 rp = make_float4(fmaxf(qp.x, 0.f), fmaxf(qp.y, 0.f), fmaxf(qp.z, 0.f), fmaxf(qp.w, 0.f));
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            total.a[c] = make_float4(fmaf(ssum, rp.x, total.a[c].x), fmaf(ssum, rp.y, total.a[c].y),
+                                     fmaf(ssum, rp.z, total.a[c].z), fmaf(ssum, rp.w, total.a[c].w));
     }
     return total;
 }
@@ -502,6 +520,7 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad_impl(const Nod
     const int col = 4 * (lane % LPR);
     const float4 t1 = ld4(theta1 + col), qp = ld4(qvec + col), qn = ld4(qvec + P + col);
     const int srow = s0 + lane / LPR;
+    float ssum = 0.f;   // sum of (weight times) s+ over the neighbours with x = 0 in all states and s- = 0
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         const int cols = (lane < cnt) ? colidx[base + lane] : 0;
@@ -531,6 +550,17 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad_impl(const Nod
 #pragma unroll
             for (int k = 0; k < 2; ++k) {
                 const float w = wk[k];
+                if (SHARED) {
+                    // x = 0 in all 16 states and s- = 0: z = s+ q+ in every state, so the neighbour adds
+                    // s+ relu(q+) to a, s+ [q+ > 0] to cp and nothing to cx, cn
+                    bool any = false;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) any = any || xs[k][c] != 0.f;
+                    if (sn[k][0] == 0.f && __ballot(any) == 0ull) {
+                        ssum += w * sp[k][0];
+                        continue;
+                    }
+                }
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
                     const float p_ = sp[k][SHARED ? 0 : c], n_ = sn[k][SHARED ? 0 : c], x_ = xs[k][c];
@@ -553,6 +583,17 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad_impl(const Nod
                     }
                 }
             }
+        }
+    }
+    if (SHARED) {
+        const float4 ra = make_float4(ssum * fmaxf(qp.x, 0.f), ssum * fmaxf(qp.y, 0.f), ssum * fmaxf(qp.z, 0.f),
+                                      ssum * fmaxf(qp.w, 0.f));
+        const float4 rc = make_float4(qp.x > 0.f ? ssum : 0.f, qp.y > 0.f ? ssum : 0.f, qp.z > 0.f ? ssum : 0.f,
+                                      qp.w > 0.f ? ssum : 0.f);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            r.a.a[c] = add4(r.a.a[c], ra);
+            r.cp.a[c] = add4(r.cp.a[c], rc);
         }
     }
     return r;
