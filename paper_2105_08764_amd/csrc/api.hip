@@ -158,7 +158,7 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.dvec = c.take(sizeof(float) * 3 * p);
     b.red_tmp = c.take(sizeof(float) * segs * width);
     // the scalar form of the last reversed round keeps four sums per long row
-    const size_t hub_mult = (S % 16 == 0 && T >= 2) ? 4 : 1;
+    const size_t hub_mult = (S % 16 == 0 && T >= 3) ? 4 : 1;
     b.hub_part = c.take(sizeof(float) * (size_t)h.max_segs * S * p * hub_mult);
     b.hub_sum = c.take(sizeof(float) * (size_t)h.max_hubs * S * p * hub_mult);
     b.end = c.off;
@@ -715,23 +715,17 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         const bool first = t == T;
         const float *dz_in = first ? nullptr : sc.dz[cur];
         float *dz_out = t == 2 ? nullptr : sc.dz[cur ^ 1];  // dz^1 only feeds the sums
-        if (t == 2 && S % 16 == 0 && N > 0) {
-            // node mode: the last reversed round streams dz^2 and gathers scalars instead of rows
+        if (t == 2 && !first && S % 16 == 0 && N > 0) {
+            // node mode, T >= 3: the last reversed round streams dz^2 and gathers scalars instead of rows
+            // (for T == 2 the round reads mask words, which is cheaper still)
             float *qvec = at<float>(ws, bl.qvec);
             S2V_TRY(launch_qvec(st, p, params->theta3, params->theta4, qvec));
             S2V_TRY(launch_hub_sums_grad(st, p, S, ht, row_end_of(g), g->colidx, wagg, ninfo, pr->has_neg, params->theta1,
                                          qvec, hub_part, hub_sum));
             {
                 SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
-                S2V_TRY(launch_bwd_first(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, sc.maskT, action, sc,
-                                         ninfo, pr->has_neg, params->theta1, params->theta2, qvec, dc_part, d2_part, ht,
-                                         hub_sum));
-            }
-            if (first) {   // T == 2: the action node's term is part of the rebuilt dz^2; its partial rows stay empty
-                float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;
-                float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdGrid * p * p;
-                S2V_TRY(launch_zero_i32(st, (long)S * kFixSplit * 3 * p, reinterpret_cast<int32_t *>(dc_fix)));
-                S2V_TRY(launch_zero_i32(st, (long)S * kFixSplit * p * p, reinterpret_cast<int32_t *>(d2_fix)));
+                S2V_TRY(launch_bwd_first(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, ninfo, pr->has_neg,
+                                         params->theta1, params->theta2, qvec, dc_part, d2_part, ht, hub_sum));
             }
             cur ^= 1;
             continue;

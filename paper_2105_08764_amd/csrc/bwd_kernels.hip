@@ -477,17 +477,15 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 // (likewise with s+ and s-), and mu^1_u is a function of the three scalars of u.  So the kernel
 // STREAMS dz^2 once and gathers the neighbours' scalars (80 bytes per neighbour at S = 16, see
 // gather_node_block_mu1_grad) where the generic round gathers 4 KB rows of dz^2 and reads mu^1.
-//   FROM_MASK: T == 2, so dz^2 = dz^T is not in memory: it is rebuilt per row from the relu-mask word,
-//              dg and, at the action node, da (no separate action pass is needed then).
+// Used for T >= 3 only: when t = 2 is also the first reversed round (T = 2), dz^2 = dz^T is not in
+// memory and the mask-word round is cheaper than recomputing masks from the scalars.
 // A wave owns one node's 16-state block at a time; hub_sum4 holds the four sums of the long rows
 // as [hub][4][S][P].
 // ------------------------------------------------------------------------------------------
-template <int P, bool W, bool FROM_MASK, bool NEG>
+template <int P, bool W, bool NEG>
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
     int n_vrows, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in,
-    const unsigned long long *__restrict__ maskT, const float *__restrict__ dg, const float *__restrict__ da,
-    const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const int32_t *__restrict__ action,
     NodeInfo ni, const float *__restrict__ theta1, const float *__restrict__ theta2,
     const float *__restrict__ qvec, float *__restrict__ dc_part, float *__restrict__ d2_part, HubTable ht,
     const float *__restrict__ hub_sum4) {
@@ -520,21 +518,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
         const int b = rowptr[v], e = rowend[v];
 
         // this node's 16 rows of dz^2, lane (row c * RPI + lane / LPR, columns 4 * li ..)
-        NodeAcc<P> dz;
-        if (FROM_MASK) {
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const int s = s0 + c * RPI + lane / LPR;
-                const unsigned nib = (unsigned)(maskT[(size_t)v * S + s] >> (4 * li)) & 15u;
-                float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * li);
-                if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * li));
-                dz.a[c] = make_float4((nib & 1u) ? d.x : 0.f, (nib & 2u) ? d.y : 0.f, (nib & 4u) ? d.z : 0.f,
-                                      (nib & 8u) ? d.w : 0.f);
-            }
-        } else {
-            dz = load_node_block<P>(dz_in + (size_t)r0 * P, lane);
-        }
+        const NodeAcc<P> dz = load_node_block<P>(dz_in + (size_t)r0 * P, lane);
         store_node_block<P>(tile_d, dz, lane);
 
         NodeAcc4<P> g4;
@@ -634,25 +618,19 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
 }
 
 hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                            const int32_t *colidx, const float *wagg, const float *dz_in,
-                            const unsigned long long *maskT, const int32_t *action, const BwdScratch &sc,
-                            const NodeInfo &ni, bool has_neg, const float *theta1, const float *theta2,
-                            const float *qvec, float *dc_part, float *d2_part, const HubTable &ht,
-                            const float *hub_sum4) {
+                            const int32_t *colidx, const float *wagg, const float *dz_in, const NodeInfo &ni,
+                            bool has_neg, const float *theta1, const float *theta2, const float *qvec, float *dc_part,
+                            float *d2_part, const HubTable &ht, const float *hub_sum4) {
     const long n_vrows = (long)N * S;
-#define S2V_LAUNCH_FIRST(PP, WW, MM, NN)                                                                           \
-    k_bwd_first<PP, WW, MM, NN><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, dz_in,    \
-                                                               maskT, sc.dg, sc.da, sc.glo, sc.ghi, action, ni, theta1, \
-                                                               theta2, qvec, dc_part, d2_part, ht, hub_sum4)
-#define S2V_LAUNCH_FIRST_N(PP, WW, MM) \
-    do { if (has_neg) S2V_LAUNCH_FIRST(PP, WW, MM, true); else S2V_LAUNCH_FIRST(PP, WW, MM, false); } while (0)
-#define S2V_LAUNCH_FIRST_M(PP, WW) \
-    do { if (dz_in) S2V_LAUNCH_FIRST_N(PP, WW, false); else S2V_LAUNCH_FIRST_N(PP, WW, true); } while (0)
+#define S2V_LAUNCH_FIRST(PP, WW, NN)                                                                              \
+    k_bwd_first<PP, WW, NN><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, dz_in, ni,  \
+                                                           theta1, theta2, qvec, dc_part, d2_part, ht, hub_sum4)
+#define S2V_LAUNCH_FIRST_N(PP, WW) \
+    do { if (has_neg) S2V_LAUNCH_FIRST(PP, WW, true); else S2V_LAUNCH_FIRST(PP, WW, false); } while (0)
 #define S2V_LAUNCH_FIRST_W(PP) \
-    do { if (wagg) S2V_LAUNCH_FIRST_M(PP, true); else S2V_LAUNCH_FIRST_M(PP, false); } while (0)
+    do { if (wagg) S2V_LAUNCH_FIRST_N(PP, true); else S2V_LAUNCH_FIRST_N(PP, false); } while (0)
     if (p == 32) S2V_LAUNCH_FIRST_W(32); else S2V_LAUNCH_FIRST_W(64);
 #undef S2V_LAUNCH_FIRST_W
-#undef S2V_LAUNCH_FIRST_M
 #undef S2V_LAUNCH_FIRST_N
 #undef S2V_LAUNCH_FIRST
     return hipGetLastError();

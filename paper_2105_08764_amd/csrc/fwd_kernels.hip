@@ -578,8 +578,15 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
             const int cols = (lane < min(64, e - b)) ? colidx[b + lane] : 0;
             float4 a;
             if (SRC == 1) {
-                Mu1Row mu1{info, s, ld4(theta1 + 4 * li), ld4(qvec + 4 * li), ld4(qvec + P + 4 * li)};
-                a = gather_row_sum<P, W>(mu1, colidx, wagg, b, e, cols, lane);
+                const float4 t1 = ld4(theta1 + 4 * li), qp = ld4(qvec + 4 * li), qn = ld4(qvec + P + 4 * li);
+                if (S == 1) {
+                    // single state: neighbours with x = 0 and s- = 0 are summed as scalars
+                    const float4 rp = make_float4(fmaxf(qp.x, 0.f), fmaxf(qp.y, 0.f), fmaxf(qp.z, 0.f), fmaxf(qp.w, 0.f));
+                    a = gather_row_sum_mu1_single<P, W>(info.base, t1, qp, qn, rp, colidx, wagg, b, e, cols, lane);
+                } else {
+                    Mu1Row mu1{info, s, t1, qp, qn};
+                    a = gather_row_sum<P, W>(mu1, colidx, wagg, b, e, cols, lane);
+                }
             } else if (SRC == 2) {
                 const BitsRow bits{mask, S, s, 4 * li};
                 a = gather_row_sum<P, W>(bits, colidx, wagg, b, e, cols, lane);

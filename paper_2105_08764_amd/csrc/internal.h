@@ -195,11 +195,9 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
                             const float *mu_prev, float *dz_out /*may be NULL*/, const NodeInfo &ni, const float *theta2,
                             float *dc_part /*[kBwdGrid][3][p]*/, float *d2_part /*[kBwdGrid][p][p]*/,
                             const HubTable &ht, const float *hub_sum);
-// The last reversed round (t = 2) from the scalars, node mode only (S a multiple of 16).  dz_in == NULL:
-// T == 2, dz^2 is rebuilt from maskT / dg / da (the action node's term included).
+// The last reversed round (t = 2) from the scalars: node mode (S a multiple of 16) and T >= 3 only.
 hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
-                            const int32_t *colidx, const float *wagg, const float *dz_in,
-                            const unsigned long long *maskT, const int32_t *action, const BwdScratch &sc,
+                            const int32_t *colidx, const float *wagg, const float *dz_in /*dz^2 [N][S][p]*/,
                             const NodeInfo &ni, bool has_neg, const float *theta1, const float *theta2,
                             const float *qvec, float *dc_part /*[kBwdGrid][3][p]*/,
                             float *d2_part /*[kBwdGrid][p][p]*/, const HubTable &ht,
