@@ -202,7 +202,9 @@ def bench_training(args, s2v, torch):
     out = dict(ms_per_step=ms, ms_per_iteration=ms / w.iters, steps=steps, iterations=w.iters, S=S, n=N, nnz=g.nnz,
                fwd_round_ms=ms_f / max(n_f, 1), bwd_round_ms=ms_b / max(n_b, 1), fwd_round2_ms=ms_f2 / max(n_f2, 1),
                fwd_round_gbs=alg / (ms_f / max(n_f, 1) * 1e-3) / 1e9 if n_f else None,
-               bwd_round_gbs=(alg + 4 * p * N * S) / (ms_b / max(n_b, 1) * 1e-3) / 1e9 if n_b else None)
+               bwd_rounds="mean over the T-1 reversed rounds of an iteration, which differ in kind: the first "
+                          "gathers 8-byte mask words, the middle ones gather rows like the forward rounds, the "
+                          "last one (node mode) streams dz^2 and gathers the neighbours' scalars")
     log(f"[bench] training {ms:.1f} ms/step ({w.iters} iterations); fwd round {out['fwd_round_ms']:.2f} ms, "
         f"bwd round {out['bwd_round_ms']:.2f} ms")
     return out
