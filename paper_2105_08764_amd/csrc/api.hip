@@ -117,8 +117,8 @@ SelLayout sel_layout(const HeadLayout &h, int64_t N, int64_t k) {
     Carver c(h.end);
     const size_t n_scan_blk = (size_t)((N + kScanBlock - 1) / kScanBlock);
     const size_t n_sort_blk = (size_t)((k + kSortTile - 1) / kSortTile);
-    s.part_val = c.take(sizeof(float) * h.max_chunks);
-    s.part_idx = c.take(sizeof(int32_t) * h.max_chunks);
+    s.part_val = c.take(sizeof(float) * h.max_chunks * kSmallK);
+    s.part_idx = c.take(sizeof(int32_t) * h.max_chunks * kSmallK);
     s.hist = c.take(sizeof(uint32_t) * 4 * 256);
     s.state = c.take(sizeof(uint32_t) * 16);
     s.blk = c.take(sizeof(uint32_t) * 4 * n_scan_blk);
@@ -643,6 +643,9 @@ int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const 
     if (k == 1) {
         const ChunkTable ct = chunk_table(ws, h, *pr);
         S2V_TRY(launch_argmax(ctx->stream, N, G, ct, q, x, cand, sc, idx, val, count));
+    } else if (k <= kSmallK) {
+        const ChunkTable ct = chunk_table(ws, h, *pr);
+        S2V_TRY(launch_smallk(ctx->stream, ct, q, x, cand, k, sc, idx, val, count));
     } else {
         S2V_TRY(launch_topk(ctx->stream, N, q, x, cand, k, sc, idx, val, count));
     }

@@ -17,6 +17,7 @@ constexpr int kBwdHeadGrid = 1024;
 constexpr int kFixSplit = 16;
 // Elements per block of the selection scan / sort passes.
 constexpr int kScanBlock = 2048;
+constexpr int kSmallK = 8;         // top-k up to this k (the d of Sec. 4.5.1) takes the two-launch path
 constexpr int kSortTile = 1024;
 constexpr int kSortFusedMaxBlocks = 512;   // above this the sort uses separate count / scan / scatter kernels
 
@@ -147,8 +148,8 @@ hipError_t launch_zero_i32(hipStream_t st, long n, int32_t *p);
 
 // ---- selection (select_kernels.hip) ----
 struct SelectScratch {
-    float *part_val;    // [n_chunks]
-    int32_t *part_idx;  // [n_chunks]
+    float *part_val;    // [n_chunks][kSmallK]
+    int32_t *part_idx;  // [n_chunks][kSmallK]
     uint32_t *hist;     // [4][256]
     uint32_t *state;    // [16]
     uint32_t *blk;      // [2][n_scan_blocks][2]
@@ -162,6 +163,8 @@ hipError_t launch_q_target(hipStream_t st, int N, int S, int G, const int32_t *g
                            const float *q_next, const float *x_next, const uint8_t *cand_next, const int32_t *action,
                            const float *reward, float gamma, float *part_val /*[S][n_chunks]*/,
                            int32_t *part_idx /*[S][n_chunks]*/, float *target);
+hipError_t launch_smallk(hipStream_t st, const ChunkTable &ct, const float *q, const float *x, const uint8_t *cand,
+                         int k /*2..kSmallK, one graph*/, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
 hipError_t launch_topk(hipStream_t st, int N, const float *q, const float *x, const uint8_t *cand, int k,
                        const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
 

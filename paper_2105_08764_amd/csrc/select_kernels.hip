@@ -92,6 +92,112 @@ hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, con
 }
 
 // ------------------------------------------------------------------------------------------
+// Top-k for the small k of the adaptive rule of Sec. 4.5.1 (d = 2, 4, 8; here any 2 <= k <=
+// kSmallK): two launches instead of the radix chain.  The order (score descending, index
+// ascending) is total, so "the next best" is "the best entry that the last pick beats": stage 1
+// finds the k best candidates of every chunk that way, stage 2 the k best of those.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool beats(float va, int ia, float vb, int ib) {
+    return va > vb || (va == vb && ia < ib);
+}
+
+// Broadcasts thread 0's (val, idx) after block_best to the whole workgroup.
+__device__ __forceinline__ void share_best(float &val, int &idx, float *sval, int *sidx) {
+    __syncthreads();
+    if (threadIdx.x == 0) { sval[0] = val; sidx[0] = idx; }
+    __syncthreads();
+    val = sval[0];
+    idx = sidx[0];
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void k_smallk_stage1(int k, const int32_t *__restrict__ chunk_begin,
+                                                       const int32_t *__restrict__ chunk_end,
+                                                       const float *__restrict__ q, const float *__restrict__ x,
+                                                       const uint8_t *__restrict__ cand,
+                                                       float *__restrict__ part_val, int32_t *__restrict__ part_idx) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    const int c = blockIdx.x;
+    const int vb = chunk_begin[c], ve = chunk_end[c];
+    // this thread's (at most kChunkNodes / 256) candidates
+    float mv[kChunkNodes / 256];
+    int mi[kChunkNodes / 256];
+#pragma unroll
+    for (int i = 0; i < kChunkNodes / 256; ++i) {
+        const int v = vb + threadIdx.x + 256 * i;
+        const bool ok = v < ve && is_candidate(x, cand, v);
+        mv[i] = ok ? q[v] : -INFINITY;
+        mi[i] = ok ? v : INT_MAX;
+    }
+    float lv = INFINITY;
+    int lidx = -1;
+    for (int it = 0; it < k; ++it) {
+        float val = -INFINITY;
+        int idx = INT_MAX;
+#pragma unroll
+        for (int i = 0; i < kChunkNodes / 256; ++i)
+            if (mi[i] != INT_MAX && beats(lv, lidx, mv[i], mi[i])) take_better(val, idx, mv[i], mi[i]);
+        block_best(val, idx, sval, sidx);
+        share_best(val, idx, sval, sidx);
+        if (threadIdx.x == 0) { part_val[(size_t)c * kSmallK + it] = val; part_idx[(size_t)c * kSmallK + it] = idx; }
+        lv = val;
+        lidx = idx;
+        if (idx == INT_MAX) {   // the chunk has no further candidate (uniform: every thread holds the same pick)
+            for (int r = it + 1 + threadIdx.x; r < k; r += 256) {
+                part_val[(size_t)c * kSmallK + r] = -INFINITY;
+                part_idx[(size_t)c * kSmallK + r] = INT_MAX;
+            }
+            break;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_smallk_stage2(int k, int n_chunks, const float *__restrict__ part_val,
+                                                       const int32_t *__restrict__ part_idx,
+                                                       int32_t *__restrict__ idx_out, float *__restrict__ val_out,
+                                                       int32_t *__restrict__ count) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    float lv = INFINITY;
+    int lidx = -1;
+    int found = 0;
+    for (int it = 0; it < k; ++it) {
+        float val = -INFINITY;
+        int idx = INT_MAX;
+        for (int c = threadIdx.x; c < n_chunks; c += 256) {
+            // a chunk's picks are in order: the first one the last pick beats is its best remaining
+            for (int r = 0; r < k; ++r) {
+                const int pi = part_idx[(size_t)c * kSmallK + r];
+                if (pi == INT_MAX) break;
+                const float pv = part_val[(size_t)c * kSmallK + r];
+                if (beats(lv, lidx, pv, pi)) { take_better(val, idx, pv, pi); break; }
+            }
+        }
+        block_best(val, idx, sval, sidx);
+        share_best(val, idx, sval, sidx);
+        if (idx == INT_MAX) break;
+        if (threadIdx.x == 0) { idx_out[it] = idx; val_out[it] = val + 0.0f; }
+        lv = val;
+        lidx = idx;
+        ++found;
+    }
+    for (int r = found + threadIdx.x; r < k; r += 256) { idx_out[r] = -1; val_out[r] = -INFINITY; }
+    if (threadIdx.x == 0) count[0] = found;
+}
+
+hipError_t launch_smallk(hipStream_t st, const ChunkTable &ct, const float *q, const float *x, const uint8_t *cand,
+                         int k, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count) {
+    if (ct.n_chunks > 0) {
+        k_smallk_stage1<<<ct.n_chunks, 256, 0, st>>>(k, ct.chunk_begin, ct.chunk_end, q, x, cand, sc.part_val, sc.part_idx);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    k_smallk_stage2<<<1, 256, 0, st>>>(k, ct.n_chunks, sc.part_val, sc.part_idx, idx, val, count);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // Deep-Q target of the training step (Alg. 4, "compute a target value using the reward"):
 //   target[b] = reward[b] + gamma * max over the candidates v of the next state b, inside the graph
 //   of action[b], of q_next[b][v];   target[b] = reward[b] when that state has no candidate left.

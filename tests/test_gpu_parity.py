@@ -153,7 +153,7 @@ def _select_cases():
     return n, {"ties": q_ties, "cont": q_cont, "zeros": q_neg0, "const": np.full(n, 2.5, np.float32)}, x
 
 
-@pytest.mark.parametrize("k", [1, 2, 8, 100, 1024, 1025, 6999, 20000])   # 20000 > candidates: everything is taken
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 8, 9, 100, 1024, 1025, 6999, 20000])   # 20000 > candidates: everything is taken
 @pytest.mark.parametrize("name", ["ties", "cont", "zeros", "const"])
 def test_topk_bit_exact_on_same_scores(oracle_mod, name, k):
     print(f"case topk {name} k={k}", flush=True)
@@ -231,10 +231,16 @@ def test_topk_candidate_mask_and_empty(oracle_mod):
     g = si.edgeless(n)
     dev = gu.Device(g, 32, 1, k_max=64)
     cand = (np.random.default_rng(1).random(n) < 0.01).astype(np.uint8)
-    for k in (1, 64):
+    for k in (1, 4, 8, 64):
         idx, val, cnt = dev.select(q, x, cand, k)
         oi, ov, oc = oracle_mod.select(None, q, x, cand, k)
         assert np.array_equal(idx, oi) and cnt[0] == oc[0]
+    few = np.zeros(n, np.uint8)
+    few[[17, 4099, 9000]] = 1                      # fewer candidates than k, spread over several chunks
+    for k in (2, 8):
+        idx, val, cnt = dev.select(q, x, few, k)
+        oi, ov, oc = oracle_mod.select(None, q, x, few, k)
+        assert cnt[0] == oc[0] == min(k, 3) and np.array_equal(idx, oi) and np.isneginf(val[0, 3:]).all()
     for k in (1, 5):
         idx, val, cnt = dev.select(q, np.ones(n, np.float32), None, k)   # no candidates at all
         assert cnt[0] == 0 and (idx == -1).all() and np.isneginf(val).all()
