@@ -145,6 +145,16 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
                                                    float *__restrict__ dc_part) {
     constexpr int LPR = P / 4, SLOTS = 256 / LPR;
     __shared__ float red[3][SLOTS][P];
+    // per-state constants of up to kStatesInLds states, fetched once per workgroup
+    constexpr int kStatesInLds = 32;
+    __shared__ __attribute__((aligned(16))) float s_dg[kStatesInLds][P], s_da[kStatesInLds][P];
+    __shared__ int s_glo[kStatesInLds], s_ghi[kStatesInLds], s_act[kStatesInLds];
+    const bool cached = S <= kStatesInLds;
+    if (cached) {
+        for (int i = threadIdx.x; i < S * P; i += 256) { s_dg[i / P][i % P] = dg[i]; s_da[i / P][i % P] = da[i]; }
+        for (int i = threadIdx.x; i < S; i += 256) { s_glo[i] = glo[i]; s_ghi[i] = ghi[i]; s_act[i] = action[i]; }
+    }
+    __syncthreads();
     const int c4 = threadIdx.x % LPR, slot = threadIdx.x / LPR;
     const long per = (n_vrows + gridDim.x - 1) / gridDim.x;
     const long r_begin = (long)blockIdx.x * per, r_end = min(n_vrows, r_begin + per);
@@ -167,8 +177,13 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
             if (valid) {
                 const int v = (int)r / S, s = (int)r - v * S;   // n_vrows < 2^31: 32-bit division
                 float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * c4);
-                if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * c4));
+                if (cached) {
+                    if (v >= s_glo[s] && v < s_ghi[s]) d = ld4(&s_dg[s][4 * c4]);
+                    if (v == s_act[s]) d = add4(d, ld4(&s_da[s][4 * c4]));
+                } else {
+                    if (v >= glo[s] && v < ghi[s]) d = ld4(dg + (size_t)s * P + 4 * c4);
+                    if (v == action[s]) d = add4(d, ld4(da + (size_t)s * P + 4 * c4));
+                }
                 d.x = mu[k].x > 0.f ? d.x : 0.f;
                 d.y = mu[k].y > 0.f ? d.y : 0.f;
                 d.z = mu[k].z > 0.f ? d.z : 0.f;
