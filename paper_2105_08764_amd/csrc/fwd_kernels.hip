@@ -73,10 +73,11 @@ __global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, Node
                                                 const float *__restrict__ theta1, const float *__restrict__ qvec,
                                                 float *__restrict__ mu_out) {
     constexpr int LPR = P / 4;
-    const long total = n_vrows * LPR;
-    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
-        const long r = i / LPR;
-        const int c = (int)(i - r * LPR) * 4;
+    // the grid stride is a multiple of LPR, so a thread keeps its four columns: constants in registers
+    const int c = (int)(threadIdx.x % LPR) * 4;
+    const float4 t1 = ld4(theta1 + c), qp = ld4(qvec + c), qn = ld4(qvec + P + c);
+    const long rows_per_step = (long)gridDim.x * blockDim.x / LPR;
+    for (long r = ((long)blockIdx.x * blockDim.x + threadIdx.x) / LPR; r < n_vrows; r += rows_per_step) {
         const int v = (int)r / S, s = (int)r - v * S;   // n_vrows < 2^31: 32-bit division
         const float3 q = ni.get(v, s);
         float xs = q.x;
@@ -86,7 +87,6 @@ __global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, Node
             const float xo = x_res[(size_t)s * N + v];
             if (xo != 0.f) { xs = xo; keep = last ? 1.f : 0.f; }
         }
-        const float4 t1 = ld4(theta1 + c), qp = ld4(qvec + c), qn = ld4(qvec + P + c);
         float4 o;
         o.x = keep * fmaxf(xs * t1.x + sp * qp.x + sn * qn.x, 0.f);
         o.y = keep * fmaxf(xs * t1.y + sp * qp.y + sn * qn.y, 0.f);
