@@ -93,7 +93,8 @@ FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp
     f.qvec = c.take(sizeof(float) * 2 * p);
     f.info = c.take(sizeof(float) * (size_t)N * nodeinfo_stride(S));
     size_t part_rows = (size_t)h.max_chunks * S;
-    if (part_rows < (size_t)kRoundGridMax) part_rows = kRoundGridMax;
+    const size_t fused_rows = (size_t)kRoundGridMax * (S == 16 ? 16 : 1);   // partials of a fused graph sum
+    if (part_rows < fused_rows) part_rows = fused_rows;
     f.gpart = c.take(sizeof(float) * part_rows * p);
     f.tmp = c.take(need_tmp ? sizeof(float) * (size_t)N * S * p : 0);
     f.hub_part = c.take(sizeof(float) * (size_t)h.max_segs * S * p);
@@ -537,7 +538,7 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     ninfo.compact = compact;
     if (mu_saved || T == 1)
         S2V_TRY(launch_round1(st, p, N, S, ninfo, x_res, T == 1, params->theta1, qvec, dest(1)));
-    const bool fuse_gsum = gsum && S == 1 && G == 1 && T >= 2 && N > 0;
+    const bool fuse_gsum = gsum && (S == 1 || S == 16) && G == 1 && T >= 2 && N > 0;
     const bool fuse_q = q_node && T >= 2 && N > 0 && round_fuses_qnode(S);
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     for (int t = 2; t <= T; ++t) {
@@ -555,7 +556,7 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
         S2V_TRY(hipMemcpyAsync(mu_out, muT, sizeof(float) * nsp, hipMemcpyDeviceToDevice, st));
     if (gsum) {
         if (fuse_gsum) {
-            S2V_TRY(launch_gsum_from_round(st, p, round_grid((long)N * S), gpart, gsum));
+            S2V_TRY(launch_gsum_from_round(st, p, S, round_grid((long)N * S), gpart, gsum));
         } else {
             const ChunkTable ct = chunk_table(ws, h, *pr);
             S2V_TRY(launch_gsum(st, p, N, S, G, ct, muT, gpart, gsum));

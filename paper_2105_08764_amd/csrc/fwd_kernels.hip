@@ -252,8 +252,9 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 // its own LDS tile, multiplies the tile by theta2 and writes the 16 output rows.
 //   NODE: S is a multiple of 16, so a tile is 16 states of one node (contiguous 1 KB loads).
 //   MU1 : this is round 2; the neighbours' round-1 rows are recomputed from their records instead of read.
-//   GSUM: also emit this workgroup's column sums of the output (S == 1, one graph) to
-//         gpart[blockIdx.x][P]: the first stage of the graph sum of Alg. 2 line 4.
+//   GSUM: also emit this workgroup's column sums of the output, the first stage of the graph sum of
+//         Alg. 2 line 4 (one graph only): gpart[blockIdx.x][P] for S == 1; in node mode with S == 16
+//         every tile holds the same 16 states, so the sums are kept per state: gpart[blockIdx.x][16][P].
 //   W   : the neighbour sum weights each neighbour by its entry of wagg (the reading of the
 //         aggregation step of Alg. 1 as a product with the weighted adjacency).
 //   QN  : this is the last round and Eq. 2 follows: also emit the node term of Q,
@@ -292,9 +293,12 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
     stage_matrix_lds<P>(lds_b, theta2, false);
     for (int i = threadIdx.x; i < 3 * P; i += kThreads) lds_c[i] = i < P ? theta1[i] : qvec[i - P];
     __syncthreads();
-    float csum[G::CB];
+    constexpr int CS = NODE ? 4 : 1;   // node mode keeps the four tile rows of a lane apart (they are states)
+    float csum[G::CB][CS];
 #pragma unroll
-    for (int cb = 0; cb < G::CB; ++cb) csum[cb] = 0.f;
+    for (int cb = 0; cb < G::CB; ++cb)
+#pragma unroll
+        for (int k = 0; k < CS; ++k) csum[cb][k] = 0.f;
     Mu1Row mu1;
     if (MU1) {
         mu1.ni = info;
@@ -423,7 +427,7 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
                 for (int cb = 0; cb < G::CB; ++cb) {
                     const float o = keepi * fmaxf(cuti * acc[cb][rr] + xi * t1[cb] + spi * qp[cb] + sni * qn[cb], 0.f);
                     out[16 * cb] = o;
-                    if (GSUM) csum[cb] += o;
+                    if (GSUM) csum[cb][NODE ? rr : 0] += o;
                     if (QN) tile[i * G::STRIDE + 16 * cb + jl] = o;
                 }
             }
@@ -463,16 +467,29 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
         // column sums of everything this workgroup wrote: lanes with equal jl, then the four waves
         __syncthreads();
         float *red = &lds[0][0];
+        if (NODE) {
+            // lane (jl, gl) holds states 4*gl + k, columns 16*cb + jl: only the four waves are left to add
 #pragma unroll
-        for (int cb = 0; cb < G::CB; ++cb) {
-            csum[cb] += __shfl_xor(csum[cb], 16);
-            csum[cb] += __shfl_xor(csum[cb], 32);
-            if (gl == 0) red[wave * P + 16 * cb + jl] = csum[cb];
+            for (int cb = 0; cb < G::CB; ++cb)
+#pragma unroll
+                for (int k = 0; k < CS; ++k) red[(wave * 16 + 4 * gl + k) * P + 16 * cb + jl] = csum[cb][k];
+            __syncthreads();
+            for (int el = threadIdx.x; el < 16 * P; el += kThreads)
+                gpart[(size_t)blockIdx.x * 16 * P + el] =
+                    (red[el] + red[16 * P + el]) + (red[2 * 16 * P + el] + red[3 * 16 * P + el]);
+        } else {
+#pragma unroll
+            for (int cb = 0; cb < G::CB; ++cb) {
+                float c0 = csum[cb][0];
+                c0 += __shfl_xor(c0, 16);
+                c0 += __shfl_xor(c0, 32);
+                if (gl == 0) red[wave * P + 16 * cb + jl] = c0;
+            }
+            __syncthreads();
+            if (threadIdx.x < P)
+                gpart[(size_t)blockIdx.x * P + threadIdx.x] =
+                    (red[threadIdx.x] + red[P + threadIdx.x]) + (red[2 * P + threadIdx.x] + red[3 * P + threadIdx.x]);
         }
-        __syncthreads();
-        if (threadIdx.x < P)
-            gpart[(size_t)blockIdx.x * P + threadIdx.x] =
-                (red[threadIdx.x] + red[P + threadIdx.x]) + (red[2 * P + threadIdx.x] + red[3 * P + threadIdx.x]);
     }
 }
 
@@ -505,7 +522,10 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
         if (wagg) S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, true); \
         else S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, false);     \
     } while (0)
-    if (node) {
+    if (node && gpart) {
+        if (from_scalars) S2V_LAUNCH_ROUND(true, true, true);
+        else S2V_LAUNCH_ROUND(true, false, true);
+    } else if (node) {
         if (from_scalars) S2V_LAUNCH_ROUND(true, true, false);
         else S2V_LAUNCH_ROUND(true, false, false);
     } else if (gpart) {
@@ -521,7 +541,7 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
     return hipGetLastError();
 }
 
-// gpart != NULL asks for the fused column sums (only legal for S == 1 and a single graph).
+// gpart != NULL asks for the fused column sums (only legal for a single graph and S == 1 or S == 16).
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                         const int32_t *colidx, const float *wagg, const float *mu_in, float *mu_out, const NodeInfo &info,
                         const float *theta1,
@@ -748,9 +768,10 @@ hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTa
     return hipGetLastError();
 }
 
-// Second stage alone, over `rows` partial rows written by the last embedding round (S == 1, G == 1).
-hipError_t launch_gsum_from_round(hipStream_t st, int p, int rows, const float *partial, float *gsum) {
-    k_gsum_stage2<<<p / 16, 1024, 0, st>>>(p, 1, 1, nullptr, rows, partial, gsum);
+// Second stage alone, over `rows` partial rows of S * p floats written by the last embedding round
+// (one graph; S == 1 or S == 16).
+hipError_t launch_gsum_from_round(hipStream_t st, int p, int S, int rows, const float *partial, float *gsum) {
+    k_gsum_stage2<<<S * p / 16, 1024, 0, st>>>(p, S, 1, nullptr, rows, partial, gsum);
     return hipGetLastError();
 }
 
