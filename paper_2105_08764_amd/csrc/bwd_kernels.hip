@@ -510,6 +510,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
     static_assert(2 * kWaves * TILE_F >= kWaves * 16 * P, "tile area is reused for the final reductions");
     __shared__ __attribute__((aligned(16))) float lds[2 * kWaves * TILE_F];   // per wave: dz^2 tile, a tile
     __shared__ __attribute__((aligned(16))) float lds_b[P * STRIDE];          // theta2^T: B operand of dz theta2
+    __shared__ __attribute__((aligned(16))) float rec_stage[kWaves * kRecStageFloats];   // staging of the record gather
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float *tile_d = lds + wave * 2 * TILE_F, *tile_a = tile_d + TILE_F;
     const int li = lane % LPR;
@@ -540,14 +541,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
         if (e - b > kHubDegree) {
             const int h = hub_index(ht.hub_rows, ht.n_hubs, v);
             const float *hb = hub_sum4 + ((size_t)h * 4 * S + s0) * P;
-            g4.a = load_node_block<P>(hb, lane);
-            g4.cx = load_node_block<P>(hb + (size_t)S * P, lane);
-            g4.cp = load_node_block<P>(hb + 2 * (size_t)S * P, lane);
-            g4.cn = load_node_block<P>(hb + 3 * (size_t)S * P, lane);
+            g4.a = load_node_block_sm<P>(hb, lane);
+            g4.cx = load_node_block_sm<P>(hb + (size_t)S * P, lane);
+            g4.cp = load_node_block_sm<P>(hb + 2 * (size_t)S * P, lane);
+            g4.cn = load_node_block_sm<P>(hb + 3 * (size_t)S * P, lane);
         } else {
-            g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+            g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane,
+                                                       rec_stage + wave * kRecStageFloats);
         }
-        store_node_block<P>(tile_a, g4.a, lane);
+        store_node_block_sm<P>(tile_a, g4.a, lane);   // the four sums live in the state-major lane layout
         __builtin_amdgcn_wave_barrier();
 
         // e = dz^2 theta2 (row r, column j: sum_k dz^2[r][k] theta2[k][j])
@@ -584,7 +586,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            const float4 e4 = ld4(tile_d + (c * RPI + lane / LPR) * STRIDE + 4 * li);
+            const float4 e4 = ld4(tile_d + (NC * (lane / LPR) + c) * STRIDE + 4 * li);
             cx4.x = fmaf(e4.x, g4.cx.a[c].x, cx4.x); cx4.y = fmaf(e4.y, g4.cx.a[c].y, cx4.y);
             cx4.z = fmaf(e4.z, g4.cx.a[c].z, cx4.z); cx4.w = fmaf(e4.w, g4.cx.a[c].w, cx4.w);
             cp4.x = fmaf(e4.x, g4.cp.a[c].x, cp4.x); cp4.y = fmaf(e4.y, g4.cp.a[c].y, cp4.y);
@@ -660,23 +662,20 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial_grad(int S, HubTable h
                                                                const float *__restrict__ theta1,
                                                                const float *__restrict__ qvec,
                                                                float *__restrict__ partial) {
-    using Ge = Geo<P>;
+    __shared__ __attribute__((aligned(16))) float rec_stage[kWaves * kRecStageFloats];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int bpn = S / 16;
     const long items = (long)ht.n_segs * bpn;
     for (long item = (long)blockIdx.x * kWaves + wave; item < items; item += (long)gridDim.x * kWaves) {
         const int seg = (int)(item / bpn), s0 = (int)(item - (long)seg * bpn) * 16;
         const int b = ht.seg_begin[seg], e = min(ht.seg_end[seg], rowend[ht.seg_row[seg]]);
-        const NodeAcc4<P> g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+        const NodeAcc4<P> g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane,
+                                                                     rec_stage + wave * kRecStageFloats);
         float *out = partial + ((size_t)seg * 4 * S + s0) * P;
-#pragma unroll
-        for (int c = 0; c < 16 / Ge::NPL; ++c) {
-            const size_t o = (size_t)c * Ge::NPL * P + 4 * lane;
-            st4(out + o, g4.a.a[c]);
-            st4(out + (size_t)S * P + o, g4.cx.a[c]);
-            st4(out + 2 * (size_t)S * P + o, g4.cp.a[c]);
-            st4(out + 3 * (size_t)S * P + o, NEG ? g4.cn.a[c] : make_float4(0.f, 0.f, 0.f, 0.f));
-        }
+        write_node_block_sm<P>(out, g4.a, lane);
+        write_node_block_sm<P>(out + (size_t)S * P, g4.cx, lane);
+        write_node_block_sm<P>(out + 2 * (size_t)S * P, g4.cp, lane);
+        write_node_block_sm<P>(out + 3 * (size_t)S * P, g4.cn, lane);   // zeros when the graph has no negative weight
     }
 }
 

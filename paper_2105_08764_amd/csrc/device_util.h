@@ -396,22 +396,125 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block(const float *__restrict_
     return total;
 }
 
+// The gathers that recompute neighbour rows from the records use their own lane layout ("state-major"):
+// lane l, register c owns tile row NC * (l / LPR) + c, so that a lane's NC states are consecutive and
+// their x (or per-state s+-) come with ONE vector load per neighbour.
+template <int NC>
+__device__ __forceinline__ void ld_states(const float *p, float (&out)[NC]) {
+    static_assert(NC == 4 || NC == 2 || NC == 1, "");
+    if constexpr (NC == 4) {
+        const float4 t = ld4(p);
+        out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
+    } else if constexpr (NC == 2) {
+        const float2 t = *reinterpret_cast<const float2 *>(p);
+        out[0] = t.x; out[1] = t.y;
+    } else {
+        out[0] = p[0];
+    }
+}
+template <int P>
+__device__ __forceinline__ void store_node_block_sm(float *tile, const NodeAcc<P> &acc, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) st4(tile + (NC * (lane / LPR) + c) * Geo<P>::STRIDE + 4 * (lane % LPR), acc.a[c]);
+}
+// state-major block from / to a plain [16][P] block in memory
+template <int P>
+__device__ __forceinline__ NodeAcc<P> load_node_block_sm(const float *__restrict__ blk, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+    NodeAcc<P> acc;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc.a[c] = ld4(blk + (size_t)(NC * (lane / LPR) + c) * P + 4 * (lane % LPR));
+    return acc;
+}
+template <int P>
+__device__ __forceinline__ void write_node_block_sm(float *__restrict__ blk, const NodeAcc<P> &acc, int lane) {
+    constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) st4(blk + (size_t)(NC * (lane / LPR) + c) * P + 4 * (lane % LPR), acc.a[c]);
+}
+
+// A batch of neighbour records for one 16-state block goes through wave-private LDS: the wave
+// fetches the x of 16 neighbours with ONE float4 load (lane = (neighbour, group of four states)) and
+// the per-node sums with one lane per neighbour, so a whole batch costs a single trip to memory;
+// the lanes then read each neighbour's scalars back in their own (state-major) layout.
+// Staged neighbour: x[16], then {s+, s-} (SHARED) or s+[16], s-[16] (per state).
+template <bool SHARED>
+struct RecStage {
+    static constexpr int BATCH = SHARED ? 32 : 16;   // neighbours per batch
+    static constexpr int NF = SHARED ? 20 : 52;      // floats per staged neighbour (multiple of 4)
+};
+constexpr int kRecStageFloats = 16 * 52;             // >= BATCH * NF of both forms
+
+// cols: this lane's column index in the current 64-entry chunk; the batch is entries j0 .. j0 + m - 1.
+template <bool SHARED>
+__device__ __forceinline__ void stage_records(const NodeInfo &ni, int s0, int cols, int j0, int m, int lane,
+                                              float *stage) {
+    constexpr int BATCH = RecStage<SHARED>::BATCH, NF = RecStage<SHARED>::NF, NL = BATCH / 16;
+    const int part = lane & 3;
+    float4 x4[NL], p4[SHARED ? 1 : NL], n4[SHARED ? 1 : NL];
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+        const int n = 16 * k + (lane >> 2);
+        const float *r = ni.node(__shfl(cols, j0 + min(n, m - 1)));   // past the end: a valid record, never consumed
+        x4[k] = ld4(r + s0 + 4 * part);
+        if (!SHARED) {
+            p4[SHARED ? 0 : k] = ld4(r + ni.sp_off + s0 + 4 * part);
+            n4[SHARED ? 0 : k] = ld4(r + ni.sn_off + s0 + 4 * part);
+        }
+    }
+    float2 pn = make_float2(0.f, 0.f);
+    if (SHARED) {
+        const float *r = ni.node(__shfl(cols, j0 + min(lane & (BATCH - 1), m - 1)));
+        pn = *reinterpret_cast<const float2 *>(r + ni.sp_off);          // s+ and s- are adjacent
+    }
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+        float *dst = stage + (16 * k + (lane >> 2)) * NF + 4 * part;
+        st4(dst, x4[k]);
+        if (!SHARED) {
+            st4(dst + 16, p4[SHARED ? 0 : k]);
+            st4(dst + 32, n4[SHARED ? 0 : k]);
+        }
+    }
+    if (SHARED && lane < BATCH) *reinterpret_cast<float2 *>(stage + lane * NF + 16) = pn;
+}
+
+// Neighbour n of the staged batch in this lane's layout: x, s+, s- of its NC consecutive states
+// (s+ / s- in element 0 only when SHARED).
+template <int NC, bool SHARED>
+__device__ __forceinline__ void read_staged(const float *stage, int n, int q, float (&xs)[NC],
+                                            float (&sp)[SHARED ? 1 : NC], float (&sn)[SHARED ? 1 : NC]) {
+    const float *r = stage + n * RecStage<SHARED>::NF;
+    ld_states<NC>(r + NC * q, xs);
+    if constexpr (SHARED) {
+        const float2 pn = *reinterpret_cast<const float2 *>(r + 16);
+        sp[0] = pn.x;
+        sn[0] = pn.y;
+    } else {
+        ld_states<NC>(r + 16 + NC * q, sp);
+        ld_states<NC>(r + 32 + NC * q, sn);
+    }
+}
+
 // Node mode with the round-1 rows recomputed from the neighbours' records (see Mu1Row): per
 // neighbour the x of the 16 states and its edge sums, one pair per node (SHARED) or per state.
+// `stage`: kRecStageFloats floats of wave-private LDS.
 template <int P, bool W, bool SHARED>
 __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1_impl(const NodeInfo &ni, int s0,
                                                                  const float *__restrict__ theta1,
                                                                  const float *__restrict__ qvec,
                                                                  const int *__restrict__ colidx,
                                                                  const float *__restrict__ wagg, int b, int e,
-                                                                 int lane) {
+                                                                 int lane, float *stage) {
     constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+    constexpr int BATCH = RecStage<SHARED>::BATCH;
     NodeAcc<P> total, acc;
 #pragma unroll
     for (int c = 0; c < NC; ++c) total.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     const int col = 4 * (lane % LPR);
     const float4 t1 = ld4(theta1 + col), qp = ld4(qvec + col), qn = ld4(qvec + P + col);
-    const int srow = s0 + lane / LPR;
+    const int q = lane / LPR;   // this lane owns states NC * q .. of the block (state-major layout)
     float ssum = 0.f;   // sum of (weight times) s+ over the neighbours whose rows are s+ relu(q+)
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
@@ -420,52 +523,35 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1_impl(const NodeInfo 
         if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc.a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-        // four neighbours per step: their scalars are fetched together
-        for (int j = 0; j < cnt; j += 4) {
-            float xs[4][NC], sp[4][SHARED ? 1 : NC], sn[4][SHARED ? 1 : NC];
-            float wk[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int jj = min(j + k, cnt - 1);   // past the end: re-read the last record, dropped below
-                const float *r = ni.node(__builtin_amdgcn_readlane(cols, jj));
-                wk[k] = W ? readlane_f(wv, jj) : 1.f;
-#pragma unroll
-                for (int c = 0; c < NC; ++c) xs[k][c] = r[srow + c * RPI];
+        for (int j0 = 0; j0 < cnt; j0 += BATCH) {
+            const int m = min(BATCH, cnt - j0);
+            stage_records<SHARED>(ni, s0, cols, j0, m, lane, stage);
+            __builtin_amdgcn_wave_barrier();
+            for (int n = 0; n < m; ++n) {
+                float xs[NC], sp[SHARED ? 1 : NC], sn[SHARED ? 1 : NC];
+                read_staged<NC, SHARED>(stage, n, q, xs, sp, sn);
+                const float wk = W ? readlane_f(wv, j0 + n) : 1.f;
                 if (SHARED) {
-                    sp[k][0] = r[ni.sp_off];
-                    sn[k][0] = r[ni.sn_off];
-                } else {
+                    // x = 0 in all 16 states and s- = 0: the row is s+ relu(q+) in every state
+                    bool any = false;
 #pragma unroll
-                    for (int c = 0; c < NC; ++c) {
-                        sp[k][SHARED ? 0 : c] = r[ni.sp_off + srow + c * RPI];
-                        sn[k][SHARED ? 0 : c] = r[ni.sn_off + srow + c * RPI];
+                    for (int c = 0; c < NC; ++c) any = any || xs[c] != 0.f;
+                    if (sn[0] == 0.f && __ballot(any) == 0ull) {
+                        ssum += wk * sp[0];
+                        continue;
                     }
                 }
-            }
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (j + k < cnt) {
-                    if (SHARED) {
-                        // x = 0 in all 16 states and s- = 0: the row is s+ relu(q+) in every state
-                        bool any = false;
-#pragma unroll
-                        for (int c = 0; c < NC; ++c) any = any || xs[k][c] != 0.f;
-                        if (sn[k][0] == 0.f && __ballot(any) == 0ull) {
-                            ssum += wk[k] * sp[k][0];
-                            continue;
-                        }
-                    }
-#pragma unroll
-                    for (int c = 0; c < NC; ++c) {
-                        const float p_ = sp[k][SHARED ? 0 : c], n_ = sn[k][SHARED ? 0 : c], x_ = xs[k][c];
-                        const float4 m = make_float4(fmaxf(x_ * t1.x + p_ * qp.x + n_ * qn.x, 0.f),
-                                                     fmaxf(x_ * t1.y + p_ * qp.y + n_ * qn.y, 0.f),
-                                                     fmaxf(x_ * t1.z + p_ * qp.z + n_ * qn.z, 0.f),
-                                                     fmaxf(x_ * t1.w + p_ * qp.w + n_ * qn.w, 0.f));
-                        acc.a[c] = acc4<W>(acc.a[c], m, wk[k]);
-                    }
+                for (int c = 0; c < NC; ++c) {
+                    const float p_ = sp[SHARED ? 0 : c], n_ = sn[SHARED ? 0 : c], x_ = xs[c];
+                    const float4 mm = make_float4(fmaxf(x_ * t1.x + p_ * qp.x + n_ * qn.x, 0.f),
+                                                  fmaxf(x_ * t1.y + p_ * qp.y + n_ * qn.y, 0.f),
+                                                  fmaxf(x_ * t1.z + p_ * qp.z + n_ * qn.z, 0.f),
+                                                  fmaxf(x_ * t1.w + p_ * qp.w + n_ * qn.w, 0.f));
+                    acc.a[c] = acc4<W>(acc.a[c], mm, wk);
                 }
             }
+            __builtin_amdgcn_wave_barrier();
         }
 #pragma unroll
         for (int c = 0; c < NC; ++c) total.a[c] = add4(total.a[c], acc.a[c]);
@@ -485,9 +571,10 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const NodeInfo &ni, 
                                                             const float *__restrict__ theta1,
                                                             const float *__restrict__ qvec,
                                                             const int *__restrict__ colidx,
-                                                            const float *__restrict__ wagg, int b, int e, int lane) {
-    if (ni.ss == 0) return gather_node_block_mu1_impl<P, W, true>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
-    return gather_node_block_mu1_impl<P, W, false>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+                                                            const float *__restrict__ wagg, int b, int e, int lane,
+                                                            float *stage) {
+    if (ni.ss == 0) return gather_node_block_mu1_impl<P, W, true>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane, stage);
+    return gather_node_block_mu1_impl<P, W, false>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane, stage);
 }
 
 // The neighbour sums that the LAST reversed round (t = 2) needs when it is taken from the scalars
@@ -509,8 +596,9 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad_impl(const Nod
                                                                        const float *__restrict__ qvec,
                                                                        const int *__restrict__ colidx,
                                                                        const float *__restrict__ wagg, int b, int e,
-                                                                       int lane) {
+                                                                       int lane, float *stage) {
     constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
+    constexpr int BATCH = RecStage<SHARED>::BATCH;
     NodeAcc4<P> r;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -519,51 +607,35 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad_impl(const Nod
     }
     const int col = 4 * (lane % LPR);
     const float4 t1 = ld4(theta1 + col), qp = ld4(qvec + col), qn = ld4(qvec + P + col);
-    const int srow = s0 + lane / LPR;
+    const int q = lane / LPR;   // this lane owns states NC * q .. of the block (state-major layout)
     float ssum = 0.f;   // sum of (weight times) s+ over the neighbours with x = 0 in all states and s- = 0
     for (int base = b; base < e; base += 64) {
         const int cnt = min(64, e - base);
         const int cols = (lane < cnt) ? colidx[base + lane] : 0;
         float wv = 0.f;
         if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
-        for (int j = 0; j < cnt; j += 2) {
-            float xs[2][NC], sp[2][SHARED ? 1 : NC], sn[2][SHARED ? 1 : NC];
-            float wk[2];
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const int jj = min(j + k, cnt - 1);   // past the end: re-read the last record, weight 0 below
-                const float *rec = ni.node(__builtin_amdgcn_readlane(cols, jj));
-                wk[k] = (j + k < cnt) ? (W ? readlane_f(wv, jj) : 1.f) : 0.f;
-#pragma unroll
-                for (int c = 0; c < NC; ++c) xs[k][c] = rec[srow + c * RPI];
-                if (SHARED) {
-                    sp[k][0] = rec[ni.sp_off];
-                    sn[k][0] = NEG ? rec[ni.sn_off] : 0.f;
-                } else {
-#pragma unroll
-                    for (int c = 0; c < NC; ++c) {
-                        sp[k][SHARED ? 0 : c] = rec[ni.sp_off + srow + c * RPI];
-                        sn[k][SHARED ? 0 : c] = NEG ? rec[ni.sn_off + srow + c * RPI] : 0.f;
-                    }
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const float w = wk[k];
+        for (int j0 = 0; j0 < cnt; j0 += BATCH) {
+            const int m = min(BATCH, cnt - j0);
+            stage_records<SHARED>(ni, s0, cols, j0, m, lane, stage);
+            __builtin_amdgcn_wave_barrier();
+            for (int n = 0; n < m; ++n) {
+                float xs[NC], sp[SHARED ? 1 : NC], sn[SHARED ? 1 : NC];
+                read_staged<NC, SHARED>(stage, n, q, xs, sp, sn);
+                const float w = W ? readlane_f(wv, j0 + n) : 1.f;
                 if (SHARED) {
                     // x = 0 in all 16 states and s- = 0: z = s+ q+ in every state, so the neighbour adds
                     // s+ relu(q+) to a, s+ [q+ > 0] to cp and nothing to cx, cn
                     bool any = false;
 #pragma unroll
-                    for (int c = 0; c < NC; ++c) any = any || xs[k][c] != 0.f;
-                    if (sn[k][0] == 0.f && __ballot(any) == 0ull) {
-                        ssum += w * sp[k][0];
+                    for (int c = 0; c < NC; ++c) any = any || xs[c] != 0.f;
+                    if (sn[0] == 0.f && __ballot(any) == 0ull) {
+                        ssum += w * sp[0];
                         continue;
                     }
                 }
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
-                    const float p_ = sp[k][SHARED ? 0 : c], n_ = sn[k][SHARED ? 0 : c], x_ = xs[k][c];
+                    const float p_ = sp[SHARED ? 0 : c], n_ = NEG ? sn[SHARED ? 0 : c] : 0.f, x_ = xs[c];
                     // the same expression as the forward pass, so that the masks agree
                     const float zx = x_ * t1.x + p_ * qp.x + n_ * qn.x, zy = x_ * t1.y + p_ * qp.y + n_ * qn.y;
                     const float zz = x_ * t1.z + p_ * qp.z + n_ * qn.z, zw = x_ * t1.w + p_ * qp.w + n_ * qn.w;
@@ -583,6 +655,7 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad_impl(const Nod
                     }
                 }
             }
+            __builtin_amdgcn_wave_barrier();
         }
     }
     if (SHARED) {
@@ -604,9 +677,11 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad(const NodeInfo
                                                                   const float *__restrict__ theta1,
                                                                   const float *__restrict__ qvec,
                                                                   const int *__restrict__ colidx,
-                                                                  const float *__restrict__ wagg, int b, int e, int lane) {
-    if (ni.ss == 0) return gather_node_block_mu1_grad_impl<P, W, true, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
-    return gather_node_block_mu1_grad_impl<P, W, false, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane);
+                                                                  const float *__restrict__ wagg, int b, int e, int lane,
+                                                                  float *stage) {
+    if (ni.ss == 0)
+        return gather_node_block_mu1_grad_impl<P, W, true, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane, stage);
+    return gather_node_block_mu1_grad_impl<P, W, false, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane, stage);
 }
 
 // Weighted form of gather_node_block_bits: per column, the sum of the weights of the neighbours whose

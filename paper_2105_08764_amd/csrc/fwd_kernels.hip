@@ -268,7 +268,8 @@ template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN>
 #ifndef S2V_ROUND2_OCC
 #define S2V_ROUND2_OCC 4
 #endif
-__global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) void k_round(int n_vrows, int S, const int32_t *__restrict__ rowptr,
+// (node-mode round 2 also holds the record staging area in LDS: three workgroups per CU)
+__global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_ROUND_OCC) void k_round(int n_vrows, int S, const int32_t *__restrict__ rowptr,
                                                     const int32_t *__restrict__ rowend,
                                                     const int32_t *__restrict__ colidx,
                                                     const float *__restrict__ wagg,
@@ -290,6 +291,8 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
 
     // theta1, q+, q- of the epilogue live in LDS, not in registers, while a tile is gathered
     __shared__ float lds_c[3 * P];
+    // staging area of the record gather (node mode of round 2 only)
+    __shared__ __attribute__((aligned(16))) float rec_stage[(NODE && MU1) ? kWaves * kRecStageFloats : 4];
     stage_matrix_lds<P>(lds_b, theta2, false);
     for (int i = threadIdx.x; i < 3 * P; i += kThreads) lds_c[i] = i < P ? theta1[i] : qvec[i - P];
     __syncthreads();
@@ -339,11 +342,16 @@ __global__ __launch_bounds__(kThreads, MU1 ? S2V_ROUND2_OCC : S2V_ROUND_OCC) voi
             if (e - b > kHubDegree) {
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
                 acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
+                store_node_block<P>(tile, acc, lane);
+            } else if (MU1) {
+                // the gather from the records works in the state-major lane layout
+                acc = gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane,
+                                                  rec_stage + ((NODE && MU1) ? wave * kRecStageFloats : 0));
+                store_node_block_sm<P>(tile, acc, lane);
             } else {
-                acc = MU1 ? gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane)
-                          : gather_node_block<P, W>(mu_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
+                acc = gather_node_block<P, W>(mu_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
+                store_node_block<P>(tile, acc, lane);
             }
-            store_node_block<P>(tile, acc, lane);
         } else {
             // The long rows of the tile first: their sums are ready in hub_sum, and all lanes fetch
             // them together (each lane looks up its own row, then RPI rows per wave-wide load).
@@ -573,6 +581,7 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
                                                           float *__restrict__ partial) {
     using G = Geo<P>;
     __shared__ __attribute__((aligned(16))) unsigned bits_stage[(NODE && SRC == 2) ? kWaves * kBitsStageBytes / 4 : 4];
+    __shared__ __attribute__((aligned(16))) float rec_stage[(NODE && SRC == 1) ? kWaves * kRecStageFloats : 4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane % G::LPR;
     const int bpn = NODE ? S / 16 : S;  // blocks per node
@@ -584,15 +593,21 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
         if (NODE) {
             const int s0 = blk * 16;
             NodeAcc<P> acc;
-            if (SRC == 1) acc = gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane);
+            if (SRC == 1)
+                acc = gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane,
+                                                  rec_stage + ((NODE && SRC == 1) ? wave * kRecStageFloats : 0));
             else if (SRC == 2)
                 acc = W ? gather_node_block_bits_w<P>(mask, S, s0, colidx, wagg, b, e, lane)
                         : gather_node_block_bits<P>(mask, S, s0, colidx, b, e, lane,
                                                     bits_stage + (NODE && SRC == 2 ? wave * (kBitsStageBytes / 4) : 0));
             else acc = gather_node_block<P, W>(src, (size_t)S * P, (size_t)s0 * P, colidx, wagg, b, e, lane);
             float *out = partial + ((size_t)seg * S + s0) * P;
+            if (SRC == 1) {
+                write_node_block_sm<P>(out, acc, lane);   // gathered in the state-major lane layout
+            } else {
 #pragma unroll
-            for (int c = 0; c < 16 / G::NPL; ++c) st4(out + c * G::NPL * P + 4 * lane, acc.a[c]);
+                for (int c = 0; c < 16 / G::NPL; ++c) st4(out + c * G::NPL * P + 4 * lane, acc.a[c]);
+            }
         } else {
             const int s = blk;
             const int cols = (lane < min(64, e - b)) ? colidx[b + lane] : 0;
