@@ -283,14 +283,39 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
 
     const size_t row_stride = (size_t)S * P;
     const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    // Node mode: a tile is one node, and the row range and first column indices of the wave's NEXT tile
+    // are fetched while the current one is worked on (rowptr -> colidx -> data is a chain of three
+    // dependent trips to memory otherwise).
+    int pf_b = 0, pf_e = 0, pf_cols = 0;
+    if (NODE) {
+        const int r0 = blockIdx.x * kWgRows + wave * kTileRows;
+        if ((int)blockIdx.x < n_tiles && r0 < n_vrows) {
+            const int v0 = r0 / S;
+            pf_b = rowptr[v0];
+            pf_e = rowend[v0];
+            pf_cols = (lane < min(64, pf_e - pf_b)) ? colidx[pf_b + lane] : 0;
+        }
+    }
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const int r0 = t * kWgRows + wave * kTileRows;
         const int r = r0 + jl;
         const bool valid = r < n_vrows;
         const int v = valid ? r / S : 0;
         const int s = valid ? r - v * S : 0;
-        const int rb = valid ? rowptr[v] : 0;
-        const int re = valid ? rowend[v] : 0;
+        const int rb = NODE ? pf_b : (valid ? rowptr[v] : 0);
+        const int re = NODE ? pf_e : (valid ? rowend[v] : 0);
+        const int cols_first = pf_cols;
+        int nx_b = 0, nx_e = 0;
+        bool nx_ok = false;
+        if (NODE) {
+            const int tn = t + gridDim.x, r0n = tn * kWgRows + wave * kTileRows;
+            nx_ok = tn < n_tiles && r0n < n_vrows;
+            if (nx_ok) {
+                const int vn = r0n / S;
+                nx_b = rowptr[vn];
+                nx_e = rowend[vn];
+            }
+        }
         const float3 mine = valid ? ni.get(v, s) : make_float3(0.f, 0.f, 0.f);
         const float xs = mine.x, sp = mine.y, sn = mine.z;
         // MASK: rows outside the action's graph receive nothing from the broadcast part of dz^T
@@ -317,10 +342,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
             } else if (MASK) {
                 ga = W ? gather_node_block_bits_w<P>(maskT, S, s0, colidx, wagg, b, e, lane)
                        : gather_node_block_bits<P>(maskT, S, s0, colidx, b, e, lane,
-                                                   bits_stage + (NODE && MASK ? wave * (kBitsStageBytes / 4) : 0));
+                                                   bits_stage + (NODE && MASK ? wave * (kBitsStageBytes / 4) : 0),
+                                                   cols_first, true);
             } else {
                 ga = gather_node_block<P, W>(dz_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
             }
+            // the next tile's first column indices (its row range has arrived by now)
+            pf_cols = (nx_ok && lane < min(64, nx_e - nx_b)) ? colidx[nx_b + lane] : 0;
+            pf_b = nx_b;
+            pf_e = nx_e;
             if (MASK) {
                 // counts -> G: times dg of this lane's state and columns (the node is wave-uniform)
                 constexpr int RPI = Ge::NPL, NC = 16 / RPI;

@@ -739,7 +739,7 @@ constexpr int kBitsStageBytes = 32 * 16 * 8;
 template <int P>
 __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long long *__restrict__ mask, int S, int s0,
                                                              const int *__restrict__ colidx, int b, int e, int lane,
-                                                             unsigned *stage) {
+                                                             unsigned *stage, int cols0 = 0, bool have_cols0 = false) {
     constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
     int4 cnt[NC];
 #pragma unroll
@@ -750,7 +750,8 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long
     const int half = shift >> 5, sh = shift & 31;
     for (int base = b; base < e; base += 64) {
         const int n = min(64, e - base);
-        const int cols = (lane < n) ? colidx[base + lane] : 0;
+        // cols0: colidx[b + lane] of the first chunk, fetched by the caller ahead of time
+        const int cols = (have_cols0 && base == b) ? cols0 : ((lane < n) ? colidx[base + lane] : 0);
         for (int j0 = 0; j0 < n; j0 += 32) {
             const int m = min(32, n - j0);       // neighbours in this batch
             unsigned long long wv[8];
