@@ -133,7 +133,8 @@ SelLayout sel_layout(const HeadLayout &h, int64_t N, int64_t k) {
 }
 
 struct BwdLayout {
-    size_t dg, da, glo, ghi, head_part, dz0, dz1, maskT, rec, qvec, dc_part, d2_part, dvec, red_tmp, hub_part, hub_sum, end;
+    size_t dg, da, glo, ghi, head_part, dz0, dz1, maskT, rec, qvec, dc_part, d2_part, dvec, red_tmp, hub_part, hub_sum,
+        hub_part4, hub_sum4, end;
     int dc_rows, d2_rows;
 };
 BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
@@ -150,7 +151,8 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.ghi = c.take(sizeof(int32_t) * S);
     b.head_part = c.take(sizeof(float) * (size_t)S * (2 * p + 2 * p * p + 1));
     b.dz0 = c.take(T >= 3 ? sizeof(float) * (size_t)N * S * p : 0);
-    b.dz1 = c.take(T >= 4 ? sizeof(float) * (size_t)N * S * p : 0);
+    // (in node mode the last two reversed rounds run as one, so dz^2 is never stored)
+    b.dz1 = c.take((T >= 5 || (T == 4 && S % 16 != 0)) ? sizeof(float) * (size_t)N * S * p : 0);
     b.maskT = c.take(T >= 2 ? sizeof(unsigned long long) * (size_t)N * S : 0);
     b.rec = c.take(sizeof(float) * (size_t)N * nodeinfo_stride(S));
     b.qvec = c.take(sizeof(float) * 2 * p);
@@ -158,10 +160,12 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.d2_part = c.take(sizeof(float) * (size_t)b.d2_rows * p * p);
     b.dvec = c.take(sizeof(float) * 3 * p);
     b.red_tmp = c.take(sizeof(float) * segs * width);
+    b.hub_part = c.take(sizeof(float) * (size_t)h.max_segs * S * p);
+    b.hub_sum = c.take(sizeof(float) * (size_t)h.max_hubs * S * p);
     // the scalar form of the last reversed round keeps four sums per long row
-    const size_t hub_mult = (S % 16 == 0 && T >= 3) ? 4 : 1;
-    b.hub_part = c.take(sizeof(float) * (size_t)h.max_segs * S * p * hub_mult);
-    b.hub_sum = c.take(sizeof(float) * (size_t)h.max_hubs * S * p * hub_mult);
+    const size_t four = (S % 16 == 0 && T >= 3) ? 4 : 0;
+    b.hub_part4 = c.take(sizeof(float) * (size_t)h.max_segs * S * p * four);
+    b.hub_sum4 = c.take(sizeof(float) * (size_t)h.max_hubs * S * p * four);
     b.end = c.off;
     return b;
 }
@@ -710,6 +714,8 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     const NodeInfo ninfo = make_nodeinfo(sc.rec, S, x_res != nullptr);
     S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part));
     float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);
+    float *hub_part4 = at<float>(ws, bl.hub_part4), *hub_sum4 = at<float>(ws, bl.hub_sum4);
+    const bool node = S % 16 == 0 && N > 0;
     int cur = 1;  // the round t = T writes dz[0]
     for (int t = T; t >= 2; --t) {
         const int slot = T - t;  // 0 for the first reversed round
@@ -719,27 +725,43 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
         const bool first = t == T;
         const float *dz_in = first ? nullptr : sc.dz[cur];
         float *dz_out = t == 2 ? nullptr : sc.dz[cur ^ 1];  // dz^1 only feeds the sums
-        if (t == 2 && !first && S % 16 == 0 && N > 0) {
-            // node mode, T >= 3: the last reversed round streams dz^2 and gathers scalars instead of rows
+        float *qvec = at<float>(ws, bl.qvec);
+        if (t == 2 && !first && node && T >= 4) {
+            // done inside the round t = 3 (see below): this round's partial rows stay empty
+            S2V_TRY(launch_zero_i32(st, (long)kBwdGrid * 3 * p, reinterpret_cast<int32_t *>(dc_part)));
+            S2V_TRY(launch_zero_i32(st, (long)kBwdGrid * p * p, reinterpret_cast<int32_t *>(d2_part)));
+            continue;
+        }
+        if (t == 2 && !first && node) {
+            // node mode, T == 3: the last reversed round streams dz^2 and gathers scalars instead of rows
             // (for T == 2 the round reads mask words, which is cheaper still)
-            float *qvec = at<float>(ws, bl.qvec);
             S2V_TRY(launch_qvec(st, p, params->theta3, params->theta4, qvec));
             S2V_TRY(launch_hub_sums_grad(st, p, S, ht, row_end_of(g), g->colidx, wagg, ninfo, pr->has_neg, params->theta1,
-                                         qvec, hub_part, hub_sum));
+                                         qvec, hub_part4, hub_sum4));
             {
                 SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
                 S2V_TRY(launch_bwd_first(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, ninfo, pr->has_neg,
-                                         params->theta1, params->theta2, qvec, dc_part, d2_part, ht, hub_sum));
+                                         params->theta1, params->theta2, qvec, dc_part, d2_part, ht, hub_sum4));
             }
             cur ^= 1;
             continue;
+        }
+        // node mode, T >= 4: the round t = 3 (rows of dz^3 in memory) also does the round t = 2 for each
+        // of its tiles while the tile's dz^2 is on chip; dz^2 is neither written nor read
+        const bool fuse_last = t == 3 && !first && node;
+        BwdFuse bf{params->theta1, qvec, hub_sum4, pr->has_neg};
+        if (fuse_last) {
+            S2V_TRY(launch_qvec(st, p, params->theta3, params->theta4, qvec));
+            S2V_TRY(launch_hub_sums_grad(st, p, S, ht, row_end_of(g), g->colidx, wagg, ninfo, pr->has_neg, params->theta1,
+                                         qvec, hub_part4, hub_sum4));
+            dz_out = nullptr;
         }
         S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, dz_in, ninfo, nullptr, nullptr, first ? sc.maskT : nullptr,
                                 hub_part, hub_sum));
         {
             SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
             S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
-                                     dz_out, ninfo, params->theta2, dc_part, d2_part, ht, hub_sum));
+                                     dz_out, ninfo, params->theta2, dc_part, d2_part, ht, hub_sum, fuse_last ? &bf : nullptr));
         }
         if (first) {
             float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;

@@ -247,19 +247,33 @@ hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *mu
 //         dg[s] (.) [mu^T > 0] on the nodes of the action's graph, so G_u = dg[s] (.) (number of
 //         neighbours of u whose mask bit is set): the gather reads 8-byte mask words, not rows.
 //   dz_out may be NULL (t == 2: dz^1 is needed for the sums only).
+//   FUSE (node mode, not the mask round; used for t = 3): the round t = 2 that would follow is done here,
+//         tile by tile, in its scalar form (see k_bwd_first): the tile's dz^2 is still on chip, so it is
+//         neither written nor read back, and its contributions go into the SAME dtheta2 and column-sum
+//         accumulators (the parameter gradients are sums over the rounds anyway).  NEG as in k_bwd_first.
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE, bool MASK, bool W>   // W: weighted neighbour sum (weights wagg, symmetric like the pattern)
+struct FirstFuse {
+    const float *theta1;
+    const float *qvec;
+    const float *hub_sum4;   // [n_hubs][4][S][P]
+};
+
+template <int P, bool NODE, bool MASK, bool W, bool FUSE, bool NEG>   // W: weighted neighbour sum (symmetric weights wagg)
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     int n_vrows, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
     const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
     float *__restrict__ dz_out, NodeInfo ni, const float *__restrict__ theta2,
     float *__restrict__ dc_part,
-    float *__restrict__ d2_part, HubTable ht, const float *__restrict__ hub_sum) {
+    float *__restrict__ d2_part, HubTable ht, const float *__restrict__ hub_sum, FirstFuse ff) {
     using Ge = Geo<P>;
     constexpr int CB = Ge::CB, STRIDE = Ge::STRIDE;
     constexpr int TILE_F = kTileRows * STRIDE;
     static_assert(kWaves * TILE_F >= kWaves * 16 * P, "tile area is reused for the final reductions");
+    static_assert(!FUSE || (NODE && !MASK), "the fused last round needs node mode and dz in memory");
+    // second tile per wave and record staging of the fused last round
+    __shared__ __attribute__((aligned(16))) float lds_a[FUSE ? kWaves * TILE_F : 4];
+    __shared__ __attribute__((aligned(16))) float rec_stage[FUSE ? kWaves * kRecStageFloats : 4];
     __shared__ __attribute__((aligned(16))) float lds[kWaves * TILE_F];
     // staging area of the mask-word gather (node mode of the MASK round only)
     __shared__ __attribute__((aligned(16))) unsigned bits_stage[(NODE && MASK) ? kWaves * kBitsStageBytes / 4 : 4];
@@ -280,6 +294,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     float cx[CB], cp[CB], cn[CB];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) cx[cb] = cp[cb] = cn[cb] = 0.f;
+    // column sums of the fused last round (columns 4 * li .. of this lane)
+    float4 fx4 = make_float4(0.f, 0.f, 0.f, 0.f), fp4 = fx4, fn4 = fx4;
 
     const size_t row_stride = (size_t)S * P;
     const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
@@ -423,7 +439,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                     const float d = mp[cb][rr] > 0.f ? acc[cb][rr] : 0.f;
                     if (dz_out) dz_out[(size_t)ro * P + 16 * cb + jl] = d;
                     cx[cb] += xi * d; cp[cb] += spi * d; cn[cb] += sni * d;
+                    if (FUSE) acc[cb][rr] = d;
                 }
+            } else if (FUSE) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) acc[cb][rr] = 0.f;
             }
         }
 
@@ -441,6 +461,76 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                     d2acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[ks], mp[jb][ks], d2acc[ib][jb], 0, 0, 0);
         }
         __builtin_amdgcn_wave_barrier();
+
+        if (FUSE && r0 < n_vrows) {
+            // ---- the round after this one, for the same node (scalar form, see k_bwd_first) ----
+            constexpr int LPR = Ge::LPR, NC = 16 / Ge::NPL;
+            float *tile_a = lds_a + (FUSE ? wave * TILE_F : 0);
+            const int vf = r0 / S, s0f = r0 - vf * S;
+            const int bf = __builtin_amdgcn_readfirstlane(rb), ef = __builtin_amdgcn_readfirstlane(re);
+            // this tile's dz^{t-1} (masked, rows 4 * gl + rr, columns 16 * cb + jl) becomes the tile
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) tile_g[(4 * gl + rr) * STRIDE + 16 * cb + jl] = acc[cb][rr];
+            NodeAcc4<P> g4;
+            if (ef - bf > kHubDegree) {
+                const int h = hub_index(ht.hub_rows, ht.n_hubs, vf);
+                const float *hb = ff.hub_sum4 + ((size_t)h * 4 * S + s0f) * P;
+                g4.a = load_node_block_sm<P>(hb, lane);
+                g4.cx = load_node_block_sm<P>(hb + (size_t)S * P, lane);
+                g4.cp = load_node_block_sm<P>(hb + 2 * (size_t)S * P, lane);
+                g4.cn = load_node_block_sm<P>(hb + 3 * (size_t)S * P, lane);
+            } else {
+                g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0f, ff.theta1, ff.qvec, colidx, wagg, bf, ef, lane,
+                                                           rec_stage + (FUSE ? wave * kRecStageFloats : 0));
+            }
+            store_node_block_sm<P>(tile_a, g4.a, lane);
+            __builtin_amdgcn_wave_barrier();
+            // e = dz^{t-1} theta2 ; dtheta2 += dz^{t-1}^T a
+            const Frag<P> ffrag = load_a_frag_lds<P>(tile_g, lane);
+            f32x4 eacc[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                eacc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                eacc[cb] = mfma_tile<P>(ffrag, load_b_frag_lds<P>(lds_b, cb, lane), eacc[cb]);
+            }
+            float ya[CB][4];
+#pragma unroll
+            for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) ya[jb][ks] = tile_a[(4 * gl + ks) * STRIDE + 16 * jb + jl];
+#pragma unroll
+            for (int ib = 0; ib < CB; ++ib) {
+                float a2[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) a2[ks] = tile_g[(4 * gl + ks) * STRIDE + 16 * ib + jl];
+#pragma unroll
+                for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        d2acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[ks], ya[jb][ks], d2acc[ib][jb], 0, 0, 0);
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) tile_g[(4 * gl + rr) * STRIDE + 16 * cb + jl] = eacc[cb][rr];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const float4 e4 = ld4(tile_g + (NC * (lane / LPR) + c) * STRIDE + 4 * li);
+                fx4.x = fmaf(e4.x, g4.cx.a[c].x, fx4.x); fx4.y = fmaf(e4.y, g4.cx.a[c].y, fx4.y);
+                fx4.z = fmaf(e4.z, g4.cx.a[c].z, fx4.z); fx4.w = fmaf(e4.w, g4.cx.a[c].w, fx4.w);
+                fp4.x = fmaf(e4.x, g4.cp.a[c].x, fp4.x); fp4.y = fmaf(e4.y, g4.cp.a[c].y, fp4.y);
+                fp4.z = fmaf(e4.z, g4.cp.a[c].z, fp4.z); fp4.w = fmaf(e4.w, g4.cp.a[c].w, fp4.w);
+                if (NEG) {
+                    fn4.x = fmaf(e4.x, g4.cn.a[c].x, fn4.x); fn4.y = fmaf(e4.y, g4.cn.a[c].y, fn4.y);
+                    fn4.z = fmaf(e4.z, g4.cn.a[c].z, fn4.z); fn4.w = fmaf(e4.w, g4.cn.a[c].w, fn4.w);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
     }
 
     // ---- workgroup reductions, fixed order over the four waves ----
@@ -475,6 +565,24 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
             lds[(wave * 3 + 2) * P + 16 * cb + jl] = cn[cb];
         }
     }
+    if (FUSE) {
+        // the fused round's sums: lanes with equal li, then into the same slots of this wave
+        constexpr int LPR = Ge::LPR;
+#pragma unroll
+        for (int m = LPR; m < 64; m <<= 1) {
+            fx4.x += __shfl_xor(fx4.x, m); fx4.y += __shfl_xor(fx4.y, m); fx4.z += __shfl_xor(fx4.z, m); fx4.w += __shfl_xor(fx4.w, m);
+            fp4.x += __shfl_xor(fp4.x, m); fp4.y += __shfl_xor(fp4.y, m); fp4.z += __shfl_xor(fp4.z, m); fp4.w += __shfl_xor(fp4.w, m);
+            fn4.x += __shfl_xor(fn4.x, m); fn4.y += __shfl_xor(fn4.y, m); fn4.z += __shfl_xor(fn4.z, m); fn4.w += __shfl_xor(fn4.w, m);
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane < LPR) {
+            float *px = lds + (wave * 3 + 0) * P + 4 * lane, *pp = lds + (wave * 3 + 1) * P + 4 * lane;
+            float *pn = lds + (wave * 3 + 2) * P + 4 * lane;
+            st4(px, add4(ld4(px), fx4));
+            st4(pp, add4(ld4(pp), fp4));
+            st4(pn, add4(ld4(pn), fn4));
+        }
+    }
     __syncthreads();
     for (int e = threadIdx.x; e < 3 * P; e += kThreads) {
         const float sum = (lds[e] + lds[3 * P + e]) + (lds[2 * 3 * P + e] + lds[3 * 3 * P + e]);
@@ -486,13 +594,26 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
                             const int32_t *colidx, const float *wagg, const float *dz_in,
                             const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out, const NodeInfo &ni, const float *theta2,
-                            float *dc_part, float *d2_part, const HubTable &ht, const float *hub_sum) {
+                            float *dc_part, float *d2_part, const HubTable &ht, const float *hub_sum,
+                            const BwdFuse *fuse) {
     const long n_vrows = (long)N * S;
     const bool node = (S % 16) == 0, mask = maskT != nullptr;
-#define S2V_LAUNCH_BWD_W(PP, NODE, MASK, WW)                                                                        \
-    k_bwd_round<PP, NODE, MASK, WW><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg,     \
-                                                                   dz_in, maskT, sc.dg, sc.glo, sc.ghi, mu_prev, dz_out, \
-                                                                   ni, theta2, dc_part, d2_part, ht, hub_sum)
+    const bool do_fuse = fuse != nullptr && node && !mask;
+    const bool neg = do_fuse && fuse->has_neg;
+    FirstFuse ff{nullptr, nullptr, nullptr};
+    if (do_fuse) ff = FirstFuse{fuse->theta1, fuse->qvec, fuse->hub_sum4};
+#define S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, FF, NN)                                                                   \
+    k_bwd_round<PP, NODE, MASK, WW, FF, NN><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, \
+                                                                           dz_in, maskT, sc.dg, sc.glo, sc.ghi, mu_prev,  \
+                                                                           dz_out, ni, theta2, dc_part, d2_part, ht,       \
+                                                                           hub_sum, ff)
+#define S2V_LAUNCH_BWD_W(PP, NODE, MASK, WW)                                                   \
+    do {                                                                                       \
+        if (NODE && !MASK && do_fuse) {                                                        \
+            if (neg) S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, (NODE && !MASK), true);              \
+            else S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, (NODE && !MASK), false);                 \
+        } else S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, false, false);                             \
+    } while (0)
 #define S2V_LAUNCH_BWD(PP, NODE, MASK)                    \
     do {                                                  \
         if (wagg) S2V_LAUNCH_BWD_W(PP, NODE, MASK, true);     \
@@ -507,6 +628,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 #undef S2V_LAUNCH_BWD_P
 #undef S2V_LAUNCH_BWD
 #undef S2V_LAUNCH_BWD_W
+#undef S2V_LAUNCH_BWD_F
     return hipGetLastError();
 }
 

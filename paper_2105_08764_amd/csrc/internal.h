@@ -192,12 +192,19 @@ hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *mu
                             const int32_t *action, const BwdScratch &sc, unsigned long long *mask /*[N][S] or NULL*/,
                             float *dc_part /*[kBwdHeadGrid][3][p]*/);
 // maskT != NULL selects the first reversed round (t = T), which reads relu-mask words instead of dz_in.
+// Asks launch_bwd_round (node mode, rows in memory) to do the round after it as well, in its scalar form.
+struct BwdFuse {
+    const float *theta1;
+    const float *qvec;
+    const float *hub_sum4;   // [n_hubs][4][S][p], from launch_hub_sums_grad
+    bool has_neg;
+};
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                             const int32_t *colidx, const float *wagg, const float *dz_in,
                             const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out /*may be NULL*/, const NodeInfo &ni, const float *theta2,
                             float *dc_part /*[kBwdGrid][3][p]*/, float *d2_part /*[kBwdGrid][p][p]*/,
-                            const HubTable &ht, const float *hub_sum);
+                            const HubTable &ht, const float *hub_sum, const BwdFuse *fuse /*may be NULL*/);
 // The last reversed round (t = 2) from the scalars: node mode (S a multiple of 16) and T >= 3 only.
 hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                             const int32_t *colidx, const float *wagg, const float *dz_in /*dz^2 [N][S][p]*/,

@@ -159,16 +159,16 @@ def test_hub_rows_of_every_kind(oracle_mod):
     clique = si.complete_graph(300)
     g = si.block_diagonal([star, clique])
     g.w = si.symmetric_edge_weights(g, 3, 0.5, 1.5)
-    for S, p in ((3, 64), (16, 32)):
+    for S, p, T in ((3, 64, 3), (16, 32, 3), (16, 64, 4)):
         theta = si.thetas(p, 5, 0.01)
         x = si.node_flags(g.n, 0.3, 7, n_states=S)
         action, target = si.training_batch(x, 8)
         action[0] = 0                      # the hub itself is an action node
         action[1] = g.graph_off[1] + 5     # and a clique node
         x[0, 0] = 0
-        dev = gu.Device(g, p, 3, S=S, training=True)
+        dev = gu.Device(g, p, T, S=S, training=True)
         loss, qp, grads = dev.train_iter(dev.params(theta), x, action, target)
-        oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, g.graph_off, theta, x, 3, action, target)
+        oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, g.graph_off, theta, x, T, action, target)
         assert gu.rel_err(qp, oqp) <= 1e-4 and abs(loss - oloss) <= 1e-4 * abs(oloss)
         for name in si.THETA_NAMES:
             assert gu.rel_err(grads[name], ograds[name], whole=True) <= 1e-4, (S, name)

@@ -70,7 +70,7 @@ def test_forward_on_per_state_residual_graphs(oracle_mod, kind, p, T, S):
 
 
 @pytest.mark.parametrize("kind", ["er", "ba", "hub", "batch"])
-@pytest.mark.parametrize("p,T,S", [(32, 1, 3), (64, 2, 16), (32, 3, 5), (64, 4, 2)])
+@pytest.mark.parametrize("p,T,S", [(32, 1, 3), (64, 2, 16), (32, 3, 5), (64, 4, 2), (32, 4, 16), (64, 3, 16)])
 def test_gradients_on_per_state_residual_graphs(oracle_mod, kind, p, T, S):
     print(f"case state-residual train kind={kind} p={p} T={T} S={S}", flush=True)
     g = _graph(kind, 12)

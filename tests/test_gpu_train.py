@@ -6,6 +6,7 @@ import pytest
 
 import synth_inputs as si
 from tests import gpu_util as gu
+from tests import train_cases as tc
 
 pytestmark = pytest.mark.gpu
 
@@ -13,19 +14,7 @@ TOL = 1e-4
 
 
 def _case(kind, seed):
-    if kind == "er":
-        g = si.erdos_renyi_gnp(300, 0.05, seed)
-        g.w = si.signed_edge_weights(g, seed, 1.0)
-    elif kind == "ba":
-        g = si.barabasi_albert(1500, 4, seed)
-        g.w = si.symmetric_edge_weights(g, seed, 0.5, 1.5)
-    elif kind == "batch":
-        parts = [si.barabasi_albert(n, 2, seed + i) if n > 2 else si.edgeless(n)
-                 for i, n in enumerate((40, 1, 77, 1300, 64))]
-        g = si.block_diagonal(parts)
-    else:
-        raise ValueError(kind)
-    return g
+    return tc.graph(kind, seed)
 
 
 def _check_grads(got, want, tol=TOL):
@@ -37,14 +26,16 @@ def _check_grads(got, want, tol=TOL):
         assert e <= tol, name
 
 
-@pytest.mark.parametrize("kind", ["er", "ba", "batch"])
-@pytest.mark.parametrize("p,T,S", [(64, 4, 3), (32, 3, 1), (64, 1, 2), (32, 2, 16), (64, 2, 5)])
+@pytest.mark.parametrize("kind", tc.KINDS)
+@pytest.mark.parametrize("p,T,S", tc.SHAPES)
 def test_loss_and_gradients_match_oracle(oracle_mod, kind, p, T, S):
     print(f"case train kind={kind} p={p} T={T} S={S}", flush=True)
-    g = _case(kind, 3)
-    theta = si.thetas(p, 77 + p + T, 0.1 if kind != "ba" else 0.05)
-    x = si.node_flags(g.n, 0.15, 8, n_states=S)
-    action, target = si.training_batch(x, 21)
+    g, x, action, target = tc.inputs(kind, S)
+    # The parameter seed is the stored one: the first draw whose float64 gradient has no relu jump within
+    # float32 rounding of it (gu.thetas_clear_of_kinks; tests/test_train_seeds.py re-derives entries).
+    seed = tc.stored_seeds()[(kind, p, T, S)]
+    theta = si.thetas(p, seed, tc.theta_scale(kind))
+    print(f"theta seed {seed}", flush=True)
     dev = gu.Device(g, p, T, S=S, training=True)
     prm = dev.params(theta)
     loss, qp, grads = dev.train_iter(prm, x, action, target)

@@ -60,7 +60,7 @@ def test_weighted_forward(oracle_mod, kind, p, T, S):
 
 
 @pytest.mark.parametrize("kind", ["er", "ba", "hub"])
-@pytest.mark.parametrize("p,T,S", [(64, 4, 3), (32, 2, 16), (64, 3, 16), (32, 3, 1), (64, 1, 2)])
+@pytest.mark.parametrize("p,T,S", [(64, 4, 3), (32, 2, 16), (64, 3, 16), (32, 3, 1), (64, 1, 2), (32, 4, 16)])
 def test_weighted_gradients(oracle_mod, kind, p, T, S):
     print(f"case weighted train kind={kind} p={p} T={T} S={S}", flush=True)
     g = _graph(kind, 6)
