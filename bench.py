@@ -183,8 +183,8 @@ def bench_training(args, s2v, torch):
         for k_ in si.THETA_NAMES:
             prm.t[k_].copy_(theta0.t[k_])
         for _ in range(w.iters):
-            ctx.s2v_embed_fwd(graph, prm, x, T, S, None, saved, gsum, ws)
-            ctx.s2v_embed_bwd(graph, prm, x, T, S, saved, gsum, action, target, loss, qp, grads, ws)
+            # forward + backward in one call (bit for bit the results of s2v_embed_fwd then s2v_embed_bwd)
+            ctx.s2v_loss_grad(graph, prm, x, T, S, saved, gsum, action, target, loss, qp, grads, ws)
             ctx.s2v_sgd_step(prm, grads, w.lr)
 
     steps = max(1, min(args.steps, args.train_steps))
@@ -350,8 +350,7 @@ def bench_paper_shape(args, s2v, torch):
     theta0 = {k: v.clone() for k, v in prm.t.items()}
 
     def train_iter():
-        ctx.s2v_embed_fwd(graph, prm, xs, T, S, None, saved, gs16, ws)
-        ctx.s2v_embed_bwd(graph, prm, xs, T, S, saved, gs16, action, target, loss, qp, grads, ws)
+        ctx.s2v_loss_grad(graph, prm, xs, T, S, saved, gs16, action, target, loss, qp, grads, ws)
         ctx.s2v_sgd_step(prm, grads, 1e-5)
 
     train_iter()

@@ -116,7 +116,7 @@ int32_t s2v_last_hip_error(const s2v_ctx *ctx);
 /*
  * Bytes of workspace that every call below needs for this graph with embedding size p, T
  * rounds, S states and at most k_max selected nodes per call.  `training` non-zero includes
- * the scratch of s2v_embed_bwd (up to two [N][S][p] buffers, the relu-mask words and the
+ * the scratch of s2v_embed_bwd and s2v_loss_grad (up to two [N][S][p] buffers, the relu-mask words and the
  * partial-gradient tables); leave it zero for inference.  `out` is a host pointer.
  * If ctx and g->rowptr are non-NULL the row lengths are read back from the device (the call
  * waits for the stream) and the buffers for long rows are sized exactly; with ctx == NULL or
@@ -206,6 +206,24 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
                       int32_t S, const float *mu_saved, const float *gsum, const int32_t *action,
                       const float *target, float *loss, float *q_pred, s2v_params *grads, void *ws,
                       size_t ws_bytes);
+
+/*
+ * Forward and backward pass of one training iteration in a single call (Train of Alg. 4 up to, not
+ * including, the parameter update): the same loss, q_pred, grads and gsum, bit for bit, as
+ * s2v_embed_fwd (with mu_saved, without mu_out) followed by s2v_embed_bwd.
+ *   mu_saved [T][N][S][p] device scratch owned by the caller; its contents after the call are
+ *            unspecified.  Knowing that the backward pass follows, the forward pass leaves out what that
+ *            pass never reads when S == 16, G == 1, T >= 3 and state_residual == 0: the rows of round 1
+ *            (the last reversed round works from per-node scalars) and all of mu^T except its relu mask
+ *            (kept as one 64-bit word per (node, state) in the workspace), the action nodes' rows and the
+ *            graph sums.  For any other shape the call is exactly the two calls in sequence.
+ *   gsum     [S][G][p] output;  all other arguments as in s2v_embed_bwd.
+ * The workspace must have been sized with training != 0.
+ * Errors: as s2v_embed_fwd and s2v_embed_bwd.
+ */
+int32_t s2v_loss_grad(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                      int32_t S, float *mu_saved, float *gsum, const int32_t *action, const float *target,
+                      float *loss, float *q_pred, s2v_params *grads, void *ws, size_t ws_bytes);
 
 /* Plain gradient descent on all seven tensors: theta <- theta - lr * grad (Sec. 4.5.2 repeats
  * forward, backward and this update several times on one minibatch). */

@@ -28,7 +28,7 @@ EXPORTS = (
     "s2v_status_str", "s2v_create", "s2v_destroy", "s2v_last_hip_error", "s2v_workspace_bytes",
     "s2v_graph_prepare", "s2v_embed_fwd", "s2v_q_score", "s2v_select_topk", "s2v_embed_bwd",
     "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end", "s2v_residual_update",
-    "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target", "s2v_policy_eval",
+    "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target", "s2v_policy_eval", "s2v_loss_grad",
 )
 
 
@@ -238,6 +238,16 @@ class Context:
                                       ctypes.c_void_p(_dp(target)), ctypes.c_void_p(_dp(loss)),
                                       ctypes.c_void_p(_dp(q_pred)), ctypes.byref(grads.c), ctypes.c_void_p(_dp(ws)),
                                       ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_embed_bwd")
+
+    def s2v_loss_grad(self, g: Graph, params: Params, x, T: int, S: int, mu_saved, gsum, action, target, loss,
+                      q_pred, grads: Params, ws) -> None:
+        _want(action, "int32", "action")
+        _check(self.lib.s2v_loss_grad(self.handle, ctypes.byref(g.c), ctypes.byref(params.c), ctypes.c_void_p(_dp(x)),
+                                      ctypes.c_int32(T), ctypes.c_int32(S), ctypes.c_void_p(_dp(mu_saved)),
+                                      ctypes.c_void_p(_dp(gsum)), ctypes.c_void_p(_dp(action)),
+                                      ctypes.c_void_p(_dp(target)), ctypes.c_void_p(_dp(loss)),
+                                      ctypes.c_void_p(_dp(q_pred)), ctypes.byref(grads.c), ctypes.c_void_p(_dp(ws)),
+                                      ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_loss_grad")
 
     def s2v_adam_step(self, params: Params, grads: Params, m: Params, v: Params, step: int, lr: float,
                       beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:

@@ -87,9 +87,9 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
 }
 
 struct FwdLayout { size_t qvec, info, tmp, gpart, hub_part, hub_sum, end; };
-FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp) {
+FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp, size_t start = 0) {
     FwdLayout f;
-    Carver c(h.end);
+    Carver c(start ? start : h.end);   // (start: behind the backward pass's pieces when both run in one call)
     f.qvec = c.take(sizeof(float) * 2 * p);
     f.info = c.take(sizeof(float) * (size_t)N * nodeinfo_stride(S));
     size_t part_rows = (size_t)h.max_chunks * S;
@@ -394,6 +394,9 @@ int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t
     if (training) {
         const size_t b_end = bwd_layout(h, g->n_nodes, p, T, S).end;
         if (b_end > need) need = b_end;
+        // s2v_loss_grad keeps the forward pass's pieces behind the backward pass's
+        const size_t fb_end = fwd_layout(h, g->n_nodes, p, S, false, b_end).end;
+        if (fb_end > need) need = fb_end;
     }
     *out = need;
     return S2V_OK;
@@ -489,9 +492,18 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
 
 // Alg. 1 for all states.  q_node != NULL asks the last round to leave the node term of Eq. 2 in
 // q_node [S][N] as well; *q_node_done says whether it did (only the row-mode round kernel can).
+// fused != NULL: the backward pass follows in the same call (s2v_loss_grad, which has checked that the
+// shape allows it).  The workspace pieces then start at fused->layout_start, round 1 is not written (no
+// reversed round reads it) and the last round leaves relu-mask words, the action nodes' rows and the
+// graph sums instead of mu^T.
+struct FusedTrain {
+    size_t layout_start;
+    unsigned long long *mask_words;
+    const int32_t *action;
+};
 static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
                               int32_t S, float *mu_out, float *mu_saved, float *gsum, void *ws, size_t ws_bytes,
-                              float *q_node, bool *q_node_done) {
+                              float *q_node, bool *q_node_done, const FusedTrain *fused = nullptr) {
     if (q_node_done) *q_node_done = false;
     if (!ctx) return S2V_ERR_INVALID_ARG;
     int32_t rc = check_graph(g);
@@ -509,7 +521,7 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     if (!pr) return S2V_ERR_NOT_PREPARED;
     const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
     const bool need_tmp = !mu_saved && T >= 3;  // round 2 reads no embedding from memory
-    const FwdLayout f = fwd_layout(h, N, p, S, need_tmp);
+    const FwdLayout f = fwd_layout(h, N, p, S, need_tmp, fused ? fused->layout_start : 0);
     if (ws_bytes < f.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
 
     hipStream_t st = ctx->stream;
@@ -540,7 +552,7 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
         S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info, compact));
     NodeInfo ninfo = make_nodeinfo(info, S, x_res != nullptr);
     ninfo.compact = compact;
-    if (mu_saved || T == 1)
+    if ((mu_saved && !fused) || T == 1)
         S2V_TRY(launch_round1(st, p, N, S, ninfo, x_res, T == 1, params->theta1, qvec, dest(1)));
     const bool fuse_gsum = gsum && (S == 1 || S == 16) && G == 1 && T >= 2 && N > 0;
     const bool fuse_q = q_node && T >= 2 && N > 0 && round_fuses_qnode(S);
@@ -552,7 +564,8 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
         SpanGuard span(ctx, qh.q ? S2V_PROFILE_FWD_ROUND_Q : (t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND));
         S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, src, dest(t), ninfo, params->theta1,
                              params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum, x_res,
-                             t == T, qh));
+                             t == T, qh,
+                             (fused && t == T) ? MaskOut{fused->mask_words, fused->action} : MaskOut{nullptr, nullptr}));
     }
     if (q_node_done) *q_node_done = fuse_q;
     float *muT = dest(T);
@@ -657,10 +670,12 @@ int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const 
     return S2V_OK;
 }
 
-int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
-                      int32_t S, const float *mu_saved, const float *gsum, const int32_t *action,
-                      const float *target, float *loss, float *q_pred, s2v_params *grads, void *ws,
-                      size_t ws_bytes) {
+// words_ready: the forward pass of the same call has left the relu-mask words of mu^T in the workspace
+// (and of mu^T itself only the action nodes' rows), see FusedTrain.
+static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                              int32_t S, const float *mu_saved, const float *gsum, const int32_t *action,
+                              const float *target, float *loss, float *q_pred, s2v_params *grads, void *ws,
+                              size_t ws_bytes, bool words_ready) {
     if (!ctx) return S2V_ERR_INVALID_ARG;
     int32_t rc = check_graph(g);
     if (rc != S2V_OK) return rc;
@@ -712,7 +727,8 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     else
         S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec, nullptr));
     const NodeInfo ninfo = make_nodeinfo(sc.rec, S, x_res != nullptr);
-    S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part));
+    S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part,
+                             words_ready));
     float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);
     float *hub_part4 = at<float>(ws, bl.hub_part4), *hub_sum4 = at<float>(ws, bl.hub_sum4);
     const bool node = S % 16 == 0 && N > 0;
@@ -774,6 +790,43 @@ int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
     S2V_TRY(launch_bwd_finish(st, p, bl.dc_rows, bl.d2_rows, sc, params->theta3, params->theta4, grads->theta1,
                               grads->theta2, grads->theta3, grads->theta4));
     return S2V_OK;
+}
+
+int32_t s2v_embed_bwd(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                      int32_t S, const float *mu_saved, const float *gsum, const int32_t *action,
+                      const float *target, float *loss, float *q_pred, s2v_params *grads, void *ws,
+                      size_t ws_bytes) {
+    return embed_bwd_impl(ctx, g, params, x, T, S, mu_saved, gsum, action, target, loss, q_pred, grads, ws, ws_bytes,
+                          false);
+}
+
+int32_t s2v_loss_grad(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
+                      int32_t S, float *mu_saved, float *gsum, const int32_t *action, const float *target,
+                      float *loss, float *q_pred, s2v_params *grads, void *ws, size_t ws_bytes) {
+    if (!ctx || !g || !params || !mu_saved || !gsum || !action) return S2V_ERR_INVALID_ARG;
+    // The forward pass can leave out what the backward pass never reads (round 1's rows, and all of mu^T
+    // but its relu mask, the action nodes' rows and the graph sums) when the kernels that make do without
+    // them apply: 16 states sharing one graph, at least three rounds.  Otherwise the two passes run as
+    // they do when called one after the other.
+    const bool fuse = S == 16 && g->n_graphs == 1 && T >= 3 && !g->state_residual && g->n_nodes > 0 &&
+                      p_supported(params->p);
+    if (!fuse) {
+        const int32_t rc = embed_fwd_impl(ctx, g, params, x, T, S, nullptr, mu_saved, gsum, ws, ws_bytes, nullptr, nullptr);
+        if (rc != S2V_OK) return rc;
+        return embed_bwd_impl(ctx, g, params, x, T, S, mu_saved, gsum, action, target, loss, q_pred, grads, ws, ws_bytes,
+                              false);
+    }
+    int32_t rc = check_ws(ws);
+    if (rc != S2V_OK) return rc;
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(g->n_nodes, g->n_graphs, pr->n_hubs, pr->n_segs);
+    const BwdLayout bl = bwd_layout(h, g->n_nodes, params->p, T, S);
+    const FusedTrain ft{bl.end, at<unsigned long long>(ws, bl.maskT), action};
+    rc = embed_fwd_impl(ctx, g, params, x, T, S, nullptr, mu_saved, gsum, ws, ws_bytes, nullptr, nullptr, &ft);
+    if (rc != S2V_OK) return rc;
+    return embed_bwd_impl(ctx, g, params, x, T, S, mu_saved, gsum, action, target, loss, q_pred, grads, ws, ws_bytes,
+                          true);
 }
 
 int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const int32_t *sel_idx,

@@ -134,8 +134,11 @@ hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch
 // relu mask (one 64-bit word per (node, state), bit j = entry j positive; skipped when T == 1) and
 // adds dz^T's share of sum x dz, sum s+ dz, sum s- dz.  Fixed grid, each workgroup owns a
 // contiguous block of rows; thread = (row slot, float4 column).
+//   WORDS: the mask words are already there (the forward pass of the same call left them instead of
+//          mu^T): they are read in place of mu^T, by the same threads in the same order, so the sums
+//          come out bit for bit as from mu^T itself.
 // ------------------------------------------------------------------------------------------
-template <int P>
+template <int P, bool WORDS>
 __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, const float *__restrict__ muT,
                                                    NodeInfo ni, const float *__restrict__ x_res,
                                                    const int32_t *__restrict__ action,
@@ -167,7 +170,14 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
 #pragma unroll
         for (int k = 0; k < U; ++k) {
             const long r = rbase + k * SLOTS + slot;
-            mu[k] = r < r_end ? ld4(muT + (size_t)r * P + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (WORDS) {
+                // only the signs matter below: 1 where the bit is set
+                const unsigned nib = r < r_end ? (unsigned)(mask[r] >> (4 * c4)) & 15u : 0u;
+                mu[k] = make_float4((float)(nib & 1u), (float)((nib >> 1) & 1u), (float)((nib >> 2) & 1u),
+                                    (float)((nib >> 3) & 1u));
+            } else {
+                mu[k] = r < r_end ? ld4(muT + (size_t)r * P + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         }
 #pragma unroll
         for (int k = 0; k < U; ++k) {
@@ -204,7 +214,7 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
                 ap.x += sp * d.x; ap.y += sp * d.y; ap.z += sp * d.z; ap.w += sp * d.w;
                 an.x += sn * d.x; an.y += sn * d.y; an.z += sn * d.z; an.w += sn * d.w;
             }
-            if (mask) {
+            if (mask && !WORDS) {
                 // OR the nibbles of the LPR lanes that share a row
 #pragma unroll
                 for (int m = 1; m < LPR; m <<= 1) word |= __shfl_xor(word, m);
@@ -225,14 +235,21 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
 }
 
 hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const NodeInfo &ni, const float *x_res,
-                            const int32_t *action, const BwdScratch &sc, unsigned long long *mask, float *dc_part) {
+                            const int32_t *action, const BwdScratch &sc, unsigned long long *mask, float *dc_part,
+                            bool words_ready) {
     const long n_vrows = (long)N * S;
-    if (p == 32)
-        k_bwd_maskT<32><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, ni, x_res, action, sc.dg, sc.da, sc.glo,
-                                                      sc.ghi, mask, dc_part);
-    else
-        k_bwd_maskT<64><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, ni, x_res, action, sc.dg, sc.da, sc.glo,
-                                                      sc.ghi, mask, dc_part);
+    if (words_ready && (!mask || x_res)) return hipErrorInvalidValue;
+#define S2V_LAUNCH_MASKT(P, WORDS)                                                                                 \
+    k_bwd_maskT<P, WORDS><<<kBwdHeadGrid, 256, 0, st>>>(n_vrows, N, S, muT, ni, x_res, action, sc.dg, sc.da, sc.glo, \
+                                                        sc.ghi, mask, dc_part)
+    if (p == 32) {
+        if (words_ready) S2V_LAUNCH_MASKT(32, true);
+        else S2V_LAUNCH_MASKT(32, false);
+    } else {
+        if (words_ready) S2V_LAUNCH_MASKT(64, true);
+        else S2V_LAUNCH_MASKT(64, false);
+    }
+#undef S2V_LAUNCH_MASKT
     return hipGetLastError();
 }
 

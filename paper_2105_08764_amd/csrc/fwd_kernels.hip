@@ -260,8 +260,12 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 //   QN  : this is the last round and Eq. 2 follows: also emit the node term of Q,
 //         theta5[p:2p] . relu(theta7 mu_v), for every output row (row mode only).  The product with
 //         theta7 runs on the matrix cores while the wave's next gather is already the bottleneck.
+//   MO  : the last round of a training pass whose backward follows in the same call (node mode): of the
+//         output only the relu mask is kept, one 64-bit word per (node, state) with bit j = entry j
+//         positive, plus the rows of the action nodes (Eq. 2 is evaluated there) and whatever GSUM asks for.
+//         The backward pass needs nothing else of mu^T, so its N*S*p floats are neither written nor read.
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN>
+template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN, bool MO = false>
 #ifndef S2V_ROUND_OCC
 #define S2V_ROUND_OCC 4
 #endif
@@ -279,9 +283,11 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
                                                     const float *__restrict__ theta2,
                                                     const float *__restrict__ qvec, float *__restrict__ gpart,
                                                     HubTable ht, const float *__restrict__ hub_sum,
-                                                    const float *__restrict__ x_res, int N, int last, QHead qh) {
+                                                    const float *__restrict__ x_res, int N, int last, QHead qh,
+                                                    int sliced, MaskOut mo) {
     using G = Geo<P>;
     static_assert(!(QN && NODE), "the node term of Q is fused in row mode only");
+    static_assert(!MO || (NODE && !MU1 && !QN), "mask output is a node-mode variant of the rounds that read rows");
     __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
     __shared__ __attribute__((aligned(16))) float lds_b[P * G::STRIDE];   // theta2, the B operand
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -312,12 +318,27 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
     }
 
     const size_t row_stride = (size_t)S * P;
-    const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    // Row mode visits the rows either in memory order (16 consecutive rows per tile) or, sliced, state by
+    // state: tile row i is then (node v0 + i, state st), so that the launch works through one state's
+    // N rows of p floats at a time (a working set S times smaller than the whole matrix).
+    const int tps = (N + kWgRows - 1) / kWgRows;   // tiles per state when sliced
+    const int n_tiles = (!NODE && sliced) ? tps * S : (n_vrows + kWgRows - 1) / kWgRows;
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const int r0 = t * kWgRows + wave * kTileRows;
+        int r0, r_step, n_here;
+        if (!NODE && sliced) {
+            const int st = t / tps;
+            const int v0 = (t - st * tps) * kWgRows + wave * kTileRows;
+            r0 = v0 * S + st;
+            r_step = S;
+            n_here = N - v0;
+        } else {
+            r0 = t * kWgRows + wave * kTileRows;
+            r_step = 1;
+            n_here = n_vrows - r0;
+        }
         // lane i (mod 16) carries the metadata of tile row i
-        const int r = r0 + jl;
-        const bool valid = r < n_vrows;
+        const int r = r0 + jl * r_step;
+        const bool valid = jl < n_here;
         const int v = valid ? r / S : 0;
         const int s = valid ? r - v * S : 0;
         const int rb = valid ? rowptr[v] : 0;
@@ -423,22 +444,53 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
             qp[cb] = lds_c[P + 16 * cb + jl];
             qn[cb] = lds_c[2 * P + 16 * cb + jl];
         }
+        if constexpr (MO) {
+            // (node mode: the tile is one node's 16 states, all of them real rows, or lies past the end)
+            if (r0 < n_vrows) {
+                const int vt = __builtin_amdgcn_readfirstlane(v);
+                // is this node the action node of one of its 16 states?  Then its rows are written as usual.
+                const bool hit = mo.action[s] == vt;   // lane jl looks at state s0 + jl
+                const bool rows_out = __builtin_amdgcn_ballot_w64(hit) != 0ull;
+                unsigned long long word = 0ull;   // lane st < 16: the mask word of state s0 + st
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int i = 4 * gl + rr;
+                    const float xi = __shfl(xs, i), spi = __shfl(sp, i), sni = __shfl(sn, i);
+                    float *out = mu_out + (size_t)(r0 + i) * P + jl;
+#pragma unroll
+                    for (int cb = 0; cb < G::CB; ++cb) {
+                        const float o = fmaxf(__fmaf_rn(sni, qn[cb], __fmaf_rn(spi, qp[cb], __fmaf_rn(xi, t1[cb], acc[cb][rr]))), 0.f);
+                        if (rows_out) out[16 * cb] = o;
+                        if (GSUM) csum[cb][rr] += o;
+                        // lane (jl, gl) answered for state 4*gl + rr, column 16*cb + jl
+                        const unsigned long long bal = __builtin_amdgcn_ballot_w64(o > 0.f);
+                        if ((lane & 3) == rr)
+                            word |= ((bal >> (16 * ((lane >> 2) & 3))) & 0xFFFFull) << (16 * cb);
+                    }
+                }
+                if (lane < 16) mo.words[(size_t)r0 + lane] = word;
+            }
+        } else {
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
             const int i = 4 * gl + rr;
             const float xi = __shfl(xs, i), spi = __shfl(sp, i), sni = __shfl(sn, i);
             const float keepi = __shfl(keep, i), cuti = __shfl(cut, i);
-            const int ro = r0 + i;
-            if (ro < n_vrows) {
+            const int ro = r0 + i * r_step;
+            if (i < n_here) {
                 float *out = mu_out + (size_t)ro * P + jl;
 #pragma unroll
                 for (int cb = 0; cb < G::CB; ++cb) {
-                    const float o = keepi * fmaxf(cuti * acc[cb][rr] + xi * t1[cb] + spi * qp[cb] + sni * qn[cb], 0.f);
+                    // (the order of the fused multiply-adds is spelled out: the mask-output variant above must
+                    //  reproduce these values bit for bit)
+                    const float o = keepi * fmaxf(__fmaf_rn(sni, qn[cb], __fmaf_rn(spi, qp[cb],
+                                                  __fmaf_rn(xi, t1[cb], cuti * acc[cb][rr]))), 0.f);
                     out[16 * cb] = o;
                     if (GSUM) csum[cb][NODE ? rr : 0] += o;
                     if (QN) tile[i * G::STRIDE + 16 * cb + jl] = o;
                 }
             }
+        }
         }
         if (QN) {
             // the finished tile (rows past the end hold stale values, never written out) times theta7
@@ -462,8 +514,8 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
             if (jl == 0) {
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) {
-                    const int ro = r0 + 4 * gl + rr;
-                    if (ro < n_vrows) {
+                    const int ro = r0 + (4 * gl + rr) * r_step;
+                    if (4 * gl + rr < n_here) {
                         const int vo = ro / S, so = ro - vo * S;
                         qh.q[(size_t)so * N + vo] = part[rr];
                     }
@@ -512,14 +564,21 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
                                  const float *mu_in, float *mu_out, const NodeInfo &info, const float *theta1,
                                  const float *theta2, const float *qvec, bool from_scalars, float *gpart,
                                  const HubTable &ht, const float *hub_sum, const float *x_res, bool last,
-                                 const QHead &qh) {
+                                 const QHead &qh, const MaskOut &mo) {
     const long n_vrows = (long)N * S;
     const int grid = round_grid(n_vrows);
+#ifdef S2V_SLICED_PROBE
+    const bool sliced = (S % 16) == 0 && !from_scalars;
+    const bool node = (S % 16) == 0 && !sliced;
+    if (sliced) gpart = nullptr;
+#else
+    const bool sliced = false;
     const bool node = (S % 16) == 0;
+#endif
 #define S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, QQ)                                                                   \
     k_round<P, NODE, MU1, GSUM, WW, QQ><<<grid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in,  \
                                                                    mu_out, info, theta1, theta2, qvec, gpart, ht,         \
-                                                                   hub_sum, x_res, N, last ? 1 : 0, qh)
+                                                                   hub_sum, x_res, N, last ? 1 : 0, qh, sliced ? 1 : 0, mo)
 #define S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, WW)                            \
     do {                                                                   \
         if (!NODE && qh.q) S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, !NODE); \
@@ -530,6 +589,19 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
         if (wagg) S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, true); \
         else S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, false);     \
     } while (0)
+    if (mo.words) {
+        // checked by the caller: node mode, rows read from memory, fused graph sum, no per-state residuals
+        if (!node || from_scalars || !gpart || x_res) return hipErrorInvalidValue;
+        if (wagg)
+            k_round<P, true, false, true, true, false, true><<<grid, kThreads, 0, st>>>(
+                (int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, gpart, ht,
+                hub_sum, x_res, N, 1, qh, 0, mo);
+        else
+            k_round<P, true, false, true, false, false, true><<<grid, kThreads, 0, st>>>(
+                (int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, gpart, ht,
+                hub_sum, x_res, N, 1, qh, 0, mo);
+        return hipGetLastError();
+    }
     if (node && gpart) {
         if (from_scalars) S2V_LAUNCH_ROUND(true, true, true);
         else S2V_LAUNCH_ROUND(true, false, true);
@@ -554,13 +626,13 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
                         const int32_t *colidx, const float *wagg, const float *mu_in, float *mu_out, const NodeInfo &info,
                         const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
-                        const float *hub_sum, const float *x_res, bool last, const QHead &qh) {
+                        const float *hub_sum, const float *x_res, bool last, const QHead &qh, const MaskOut &mo) {
     if ((long)N * S == 0) return hipSuccess;
     if (p == 32)
         return launch_round_p<32>(st, N, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
-                                  gpart, ht, hub_sum, x_res, last, qh);
+                                  gpart, ht, hub_sum, x_res, last, qh, mo);
     return launch_round_p<64>(st, N, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
-                              ht, hub_sum, x_res, last, qh);
+                              ht, hub_sum, x_res, last, qh, mo);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -121,6 +121,12 @@ struct QHead {
     const float *theta7;
     float *q;   // [S][N], receives theta5[p:2p] . relu(theta7 mu[v][s])
 };
+// Mask output of the last embedding round of a fused training pass (node mode, S == 16, one graph):
+// words == NULL switches it off.
+struct MaskOut {
+    unsigned long long *words;   // [N*S]: bit j of word (v, s) = (mu^T[v][s][j] > 0)
+    const int32_t *action;       // [S]: the rows of these nodes are still written to mu_out
+};
 // whether launch_round honours a QHead for this S (else the caller runs the separate node-term kernel)
 inline bool round_fuses_qnode(int S) { return (S % 16) != 0; }
 hipError_t launch_qfinish(hipStream_t st, int N, int S, int G, const int32_t *graph_off, const float *qa, float *q);
@@ -129,7 +135,8 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
                         const int32_t *colidx, const float *wagg /*NULL: unweighted neighbour sum*/, const float *mu_in,
                         float *mu_out, const NodeInfo &ni, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
-                        const float *hub_sum, const float *x_res, bool last, const QHead &qh);
+                        const float *hub_sum, const float *x_res, bool last, const QHead &qh,
+                        const MaskOut &mo = MaskOut{nullptr, nullptr});
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int S, int rows, const float *partial, float *gsum);
 hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu,
                        float *partial /*[n_chunks][S*p]*/, float *gsum /*[S][G][p]*/);
@@ -190,7 +197,8 @@ hipError_t launch_bwd_head_reduce(hipStream_t st, int p, int S, const BwdScratch
                                   float *d7);
 hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *muT, const NodeInfo &ni, const float *x_res,
                             const int32_t *action, const BwdScratch &sc, unsigned long long *mask /*[N][S] or NULL*/,
-                            float *dc_part /*[kBwdHeadGrid][3][p]*/);
+                            float *dc_part /*[kBwdHeadGrid][3][p]*/,
+                            bool words_ready = false /*mask already holds the words: read them, not muT*/);
 // maskT != NULL selects the first reversed round (t = T), which reads relu-mask words instead of dz_in.
 // Asks launch_bwd_round (node mode, rows in memory) to do the round after it as well, in its scalar form.
 struct BwdFuse {

@@ -87,7 +87,26 @@ class Device:
         if lr is not None:
             self.ctx.s2v_sgd_step(prm, grads, lr)
         torch.cuda.synchronize()
+        self.last_gsum = gsum.cpu().numpy()
         return float(loss.item()), qp.cpu().numpy(), grads.to_numpy()
+
+
+    def loss_grad(self, prm, x, action, target):
+        """Forward + backward through the single-call entry point.  Returns (loss, q_pred, grads, gsum)."""
+        torch = self.torch
+        g = self.g_np
+        N, G, p, T, S = g.n, g.n_graphs, self.p, self.T, self.S
+        xd = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32).reshape(S, N)).cuda()
+        saved = torch.full((T, N, S, p), float("nan"), device="cuda")
+        gsum = torch.full((S, G, p), float("nan"), device="cuda")
+        ad = torch.from_numpy(np.ascontiguousarray(action, dtype=np.int32)).cuda()
+        td = torch.from_numpy(np.ascontiguousarray(target, dtype=np.float32)).cuda()
+        loss = torch.full((1,), float("nan"), device="cuda")
+        qp = torch.full((S,), float("nan"), device="cuda")
+        grads = self.s2v.Params(p, {k: torch.full_like(v, float("nan")) for k, v in prm.t.items()})
+        self.ctx.s2v_loss_grad(self.graph, prm, xd, T, S, saved, gsum, ad, td, loss, qp, grads, self.ws)
+        torch.cuda.synchronize()
+        return float(loss.item()), qp.cpu().numpy(), grads.to_numpy(), gsum.cpu().numpy()
 
 
 FLOOR_FRAC = 1e-2

@@ -45,6 +45,28 @@ def test_loss_and_gradients_match_oracle(oracle_mod, kind, p, T, S):
     _check_grads(grads, ograds)
 
 
+@pytest.mark.parametrize("kind", tc.KINDS)
+@pytest.mark.parametrize("p,T,S,weighted", [(64, 4, 16, False), (32, 3, 16, False), (32, 5, 16, True), (64, 3, 16, True),
+                                            (64, 4, 3, False), (32, 2, 16, False), (32, 3, 32, False)])
+def test_single_call_equals_forward_then_backward(kind, p, T, S, weighted):
+    # s2v_loss_grad promises the results of s2v_embed_fwd + s2v_embed_bwd bit for bit, whether it takes
+    # its short cut (16 states, one graph, T >= 3: no round-1 rows, mask words instead of mu^T) or not.
+    print(f"case single call kind={kind} p={p} T={T} S={S} weighted={weighted}", flush=True)
+    g, x, action, target = tc.inputs(kind, S)
+    if kind == "ba":
+        action = action.copy()
+        action[0] = int(np.argmax(np.diff(g.rowptr)))      # an action node with a long row
+    theta = si.thetas(p, 5 + p + T, tc.theta_scale(kind))
+    dev = gu.Device(g, p, T, S=S, training=True, weighted_sum=weighted)
+    prm = dev.params(theta)
+    loss2, qp2, grads2 = dev.train_iter(prm, x, action, target)
+    gsum2 = dev.last_gsum
+    loss1, qp1, grads1, gsum1 = dev.loss_grad(prm, x, action, target)
+    assert loss1 == loss2 and np.array_equal(qp1, qp2) and np.array_equal(gsum1, gsum2)
+    for name in si.THETA_NAMES:
+        assert np.array_equal(grads1[name], grads2[name]), name
+
+
 def test_sgd_iterations_follow_oracle(oracle_mod):
     # Sec. 4.5.2: several forward/backward/update iterations on the same minibatch.
     # Small parameters and the paper's learning rate (1e-5, Sec. 6.1) keep the four steps stable.
