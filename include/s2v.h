@@ -107,6 +107,11 @@ const char *s2v_status_str(int32_t status);
  * Create a context bound to a HIP stream (`hip_stream` is a hipStream_t passed as void*;
  * NULL is the default stream) on the current device.  Host memory only.
  * Errors: S2V_ERR_INVALID_ARG (out == NULL), S2V_ERR_NO_DEVICE.
+ * One tuning knob is read from the environment here: S2V_SLICED_MIN_BYTES (decimal bytes, default
+ * 1.5 GiB).  Embedding matrices [N][S][p] of at least that size with S a multiple of 16 are walked state
+ * by state instead of node by node in the rounds of Eq. 1 that read them, which keeps one state's rows
+ * in the last-level cache; the order of the float32 additions, and so the last bits of the results,
+ * depend on which walk is used.
  */
 int32_t s2v_create(void *hip_stream, s2v_ctx **out);
 int32_t s2v_destroy(s2v_ctx *ctx);

@@ -564,17 +564,13 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
                                  const float *mu_in, float *mu_out, const NodeInfo &info, const float *theta1,
                                  const float *theta2, const float *qvec, bool from_scalars, float *gpart,
                                  const HubTable &ht, const float *hub_sum, const float *x_res, bool last,
-                                 const QHead &qh, const MaskOut &mo) {
+                                 const QHead &qh, const MaskOut &mo, bool by_state) {
     const long n_vrows = (long)N * S;
     const int grid = round_grid(n_vrows);
-#ifdef S2V_SLICED_PROBE
-    const bool sliced = (S % 16) == 0 && !from_scalars;
+    // (sliced: the caller asks for the state-by-state row order; it applies to the rounds that read rows
+    //  and have no fused extras, and replaces node mode there)
+    const bool sliced = by_state && S > 1 && !from_scalars && !gpart && !mo.words && !qh.q;
     const bool node = (S % 16) == 0 && !sliced;
-    if (sliced) gpart = nullptr;
-#else
-    const bool sliced = false;
-    const bool node = (S % 16) == 0;
-#endif
 #define S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, QQ)                                                                   \
     k_round<P, NODE, MU1, GSUM, WW, QQ><<<grid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in,  \
                                                                    mu_out, info, theta1, theta2, qvec, gpart, ht,         \
@@ -626,13 +622,14 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
                         const int32_t *colidx, const float *wagg, const float *mu_in, float *mu_out, const NodeInfo &info,
                         const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
-                        const float *hub_sum, const float *x_res, bool last, const QHead &qh, const MaskOut &mo) {
+                        const float *hub_sum, const float *x_res, bool last, const QHead &qh, const MaskOut &mo,
+                        bool by_state) {
     if ((long)N * S == 0) return hipSuccess;
     if (p == 32)
         return launch_round_p<32>(st, N, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars,
-                                  gpart, ht, hub_sum, x_res, last, qh, mo);
+                                  gpart, ht, hub_sum, x_res, last, qh, mo, by_state);
     return launch_round_p<64>(st, N, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, from_scalars, gpart,
-                              ht, hub_sum, x_res, last, qh, mo);
+                              ht, hub_sum, x_res, last, qh, mo, by_state);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -136,7 +136,8 @@ hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowp
                         float *mu_out, const NodeInfo &ni, const float *theta1,
                         const float *theta2, const float *qvec, bool from_scalars, float *gpart, const HubTable &ht,
                         const float *hub_sum, const float *x_res, bool last, const QHead &qh,
-                        const MaskOut &mo = MaskOut{nullptr, nullptr});
+                        const MaskOut &mo = MaskOut{nullptr, nullptr},
+                        bool by_state = false /*visit the rows state by state (see k_round) where that applies*/);
 hipError_t launch_gsum_from_round(hipStream_t st, int p, int S, int rows, const float *partial, float *gsum);
 hipError_t launch_gsum(hipStream_t st, int p, int N, int S, int G, const ChunkTable &ct, const float *mu,
                        float *partial /*[n_chunks][S*p]*/, float *gsum /*[S][G][p]*/);
