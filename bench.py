@@ -457,7 +457,7 @@ def main():
             "scale": args.scale,
         },
         "roofline": {
-            "kernel": "k_round<64,false,false,false,false,false> (fused CSR gather + theta2 product + relu, rounds 3..T-1; the last round also forms the node term of Eq. 2 and is timed separately)",
+            "kernel": "k_round<64,false,false,false,false,false,0> (fused CSR gather + theta2 product + relu, rounds 3..T-1; the last round also forms the node term of Eq. 2 and is timed separately)",
             "bound": "hbm",
             "achieved": round(inf["achieved_gbs"], 1),
             "peak": HBM_PEAK_GBS,

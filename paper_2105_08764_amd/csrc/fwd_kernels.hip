@@ -260,12 +260,15 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 //   QN  : this is the last round and Eq. 2 follows: also emit the node term of Q,
 //         theta5[p:2p] . relu(theta7 mu_v), for every output row (row mode only).  The product with
 //         theta7 runs on the matrix cores while the wave's next gather is already the bottleneck.
-//   MO  : the last round of a training pass whose backward follows in the same call (node mode): of the
+//   VAR = kRoundMaskOut (MO below): the last round of a training pass whose backward follows in the same call (node mode): of the
 //         output only the relu mask is kept, one 64-bit word per (node, state) with bit j = entry j
 //         positive, plus the rows of the action nodes (Eq. 2 is evaluated there) and whatever GSUM asks for.
 //         The backward pass needs nothing else of mu^T, so its N*S*p floats are neither written nor read.
+//   VAR = kRoundByState: row mode with the rows visited state by state (see the tile loop); a variant of
+//         its own so that it shows under its own name in profiles.
 // ------------------------------------------------------------------------------------------
-template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN, bool MO = false>
+constexpr int kRoundPlain = 0, kRoundMaskOut = 1, kRoundByState = 2;
+template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN, int VAR = 0>
 #ifndef S2V_ROUND_OCC
 #define S2V_ROUND_OCC 4
 #endif
@@ -284,8 +287,10 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
                                                     const float *__restrict__ qvec, float *__restrict__ gpart,
                                                     HubTable ht, const float *__restrict__ hub_sum,
                                                     const float *__restrict__ x_res, int N, int last, QHead qh,
-                                                    int sliced, MaskOut mo) {
+                                                    MaskOut mo) {
     using G = Geo<P>;
+    constexpr bool MO = VAR == kRoundMaskOut, SLICED = VAR == kRoundByState;
+    static_assert(!SLICED || (!NODE && !MU1 && !GSUM && !QN), "the state-by-state order is a plain row-mode variant");
     static_assert(!(QN && NODE), "the node term of Q is fused in row mode only");
     static_assert(!MO || (NODE && !MU1 && !QN), "mask output is a node-mode variant of the rounds that read rows");
     __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
@@ -322,10 +327,10 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
     // state: tile row i is then (node v0 + i, state st), so that the launch works through one state's
     // N rows of p floats at a time (a working set S times smaller than the whole matrix).
     const int tps = (N + kWgRows - 1) / kWgRows;   // tiles per state when sliced
-    const int n_tiles = (!NODE && sliced) ? tps * S : (n_vrows + kWgRows - 1) / kWgRows;
+    const int n_tiles = SLICED ? tps * S : (n_vrows + kWgRows - 1) / kWgRows;
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         int r0, r_step, n_here;
-        if (!NODE && sliced) {
+        if (SLICED) {
             const int st = t / tps;
             const int v0 = (t - st * tps) * kWgRows + wave * kTileRows;
             r0 = v0 * S + st;
@@ -574,7 +579,7 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
 #define S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, QQ)                                                                   \
     k_round<P, NODE, MU1, GSUM, WW, QQ><<<grid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in,  \
                                                                    mu_out, info, theta1, theta2, qvec, gpart, ht,         \
-                                                                   hub_sum, x_res, N, last ? 1 : 0, qh, sliced ? 1 : 0, mo)
+                                                                   hub_sum, x_res, N, last ? 1 : 0, qh, mo)
 #define S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, WW)                            \
     do {                                                                   \
         if (!NODE && qh.q) S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, !NODE); \
@@ -589,13 +594,24 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
         // checked by the caller: node mode, rows read from memory, fused graph sum, no per-state residuals
         if (!node || from_scalars || !gpart || x_res) return hipErrorInvalidValue;
         if (wagg)
-            k_round<P, true, false, true, true, false, true><<<grid, kThreads, 0, st>>>(
+            k_round<P, true, false, true, true, false, kRoundMaskOut><<<grid, kThreads, 0, st>>>(
                 (int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, gpart, ht,
-                hub_sum, x_res, N, 1, qh, 0, mo);
+                hub_sum, x_res, N, 1, qh, mo);
         else
-            k_round<P, true, false, true, false, false, true><<<grid, kThreads, 0, st>>>(
+            k_round<P, true, false, true, false, false, kRoundMaskOut><<<grid, kThreads, 0, st>>>(
                 (int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, gpart, ht,
-                hub_sum, x_res, N, 1, qh, 0, mo);
+                hub_sum, x_res, N, 1, qh, mo);
+        return hipGetLastError();
+    }
+    if (sliced) {
+        if (wagg)
+            k_round<P, false, false, false, true, false, kRoundByState><<<grid, kThreads, 0, st>>>(
+                (int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, gpart, ht,
+                hub_sum, x_res, N, last ? 1 : 0, qh, mo);
+        else
+            k_round<P, false, false, false, false, false, kRoundByState><<<grid, kThreads, 0, st>>>(
+                (int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, gpart, ht,
+                hub_sum, x_res, N, last ? 1 : 0, qh, mo);
         return hipGetLastError();
     }
     if (node && gpart) {
