@@ -102,6 +102,55 @@ def test_error_codes():
     assert torch.isfinite(mu).all()
 
 
+def test_loss_grad_error_codes():
+    import torch
+
+    import paper_2105_08764_amd as s2v
+
+    g = si.erdos_renyi_gnp(200, 0.05, 1)
+    p, T, S = 32, 3, 16
+    dev = gu.Device(g, p, T, S=S, training=True)
+    ctx, graph, ws = dev.ctx, dev.graph, dev.ws
+    prm = dev.params(si.thetas(p, 1))
+    grads = s2v.Params.zeros_like(prm)
+    x = torch.zeros((S, g.n), device="cuda")
+    saved = torch.zeros((T, g.n, S, p), device="cuda")
+    gsum = torch.zeros((S, 1, p), device="cuda")
+    action = torch.zeros(S, dtype=torch.int32, device="cuda")
+    target = torch.zeros(S, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    qp = torch.zeros(S, device="cuda")
+    good = [saved, gsum, action, target, loss]
+    for hole in range(5):
+        a = list(good)
+        a[hole] = None
+        with pytest.raises(s2v.S2VError) as e:
+            ctx.s2v_loss_grad(graph, prm, x, T, S, a[0], a[1], a[2], a[3], a[4], qp, grads, ws)
+        assert _status(e) == s2v.S2V_ERR_INVALID_ARG, hole
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_loss_grad(graph, prm, x, 0, S, saved, gsum, action, target, loss, qp, grads, ws)
+    assert _status(e) == s2v.S2V_ERR_INVALID_ARG
+    # a workspace sized for inference only: refused before anything is launched, on the short-cut path
+    # (16 states, T >= 3) as on the plain one
+    small_bytes = ctx.s2v_workspace_bytes(graph, p, T, S, 1, False)
+    assert small_bytes < dev.ws_bytes
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_loss_grad(graph, prm, x, T, S, saved, gsum, action, target, loss, qp, grads, ws[:small_bytes])
+    assert _status(e) == s2v.S2V_ERR_WORKSPACE_TOO_SMALL
+    other = torch.empty(dev.ws_bytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_loss_grad(graph, prm, x, T, S, saved, gsum, action, target, loss, qp, grads, other)
+    assert _status(e) == s2v.S2V_ERR_NOT_PREPARED
+    bad = s2v.Params(48, {k: torch.zeros(1, device="cuda") for k in s2v.THETA_NAMES})
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_loss_grad(graph, bad, x, T, S, saved, gsum, action, target, loss, qp, grads, ws)
+    assert _status(e) == s2v.S2V_ERR_UNSUPPORTED
+    # q_pred is optional; and the context still works after the refusals
+    ctx.s2v_loss_grad(graph, prm, x, T, S, saved, gsum, action, target, loss, None, grads, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(loss).all()
+
+
 def test_empty_graph():
     import torch
 
