@@ -37,7 +37,7 @@ struct Carver {
 };
 
 struct HeadLayout {
-    size_t s_pos, s_neg, chunk_begin, chunk_end, graph_chunk_off;
+    size_t s_pos, s_neg, nbr_sp, chunk_begin, chunk_end, graph_chunk_off;
     size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, list, end;
     int max_chunks, max_hubs, max_segs;
 };
@@ -73,6 +73,7 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     Carver c(0);
     h.s_pos = c.take(sizeof(float) * N);
     h.s_neg = c.take(sizeof(float) * N);
+    h.nbr_sp = c.take(sizeof(float) * N);   // per row: s_pos summed over its neighbours (see NodeInfo::xbits)
     h.chunk_begin = c.take(sizeof(int32_t) * h.max_chunks);
     h.chunk_end = c.take(sizeof(int32_t) * h.max_chunks);
     h.graph_chunk_off = c.take(sizeof(int32_t) * (G + 1));
@@ -87,12 +88,13 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     return h;
 }
 
-struct FwdLayout { size_t qvec, info, tmp, gpart, hub_part, hub_sum, end; };
+struct FwdLayout { size_t qvec, info, xbits, tmp, gpart, hub_part, hub_sum, end; };
 FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp, size_t start = 0) {
     FwdLayout f;
     Carver c(start ? start : h.end);   // (start: behind the backward pass's pieces when both run in one call)
     f.qvec = c.take(sizeof(float) * 2 * p);
     f.info = c.take(sizeof(float) * (size_t)N * nodeinfo_stride(S));
+    f.xbits = c.take(S == 1 ? sizeof(unsigned long long) * (size_t)((N + 63) / 64) : 0);
     size_t part_rows = (size_t)h.max_chunks * S;
     const size_t fused_rows = (size_t)kRoundGridMax * (S == 16 ? 16 : 1);   // partials of a fused graph sum
     if (part_rows < fused_rows) part_rows = fused_rows;
@@ -493,6 +495,8 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
     S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, row_end_of(g), g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg),
                              neg_flag));
+    S2V_TRY(launch_prepare_nbr(ctx->stream, N, g->rowptr, row_end_of(g), g->colidx, at<float>(ws, h.s_pos),
+                               at<float>(ws, h.nbr_sp)));
     S2V_TRY(hipMemcpyAsync(&has_neg, neg_flag, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
     S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
@@ -560,12 +564,19 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     const float *wagg = g->weighted_sum ? g->w : nullptr;   // NULL weights mean w = 1: the plain sum
     // S = 1 without negative weights: round 2 reads a 4-byte table first (see gather_tile_mu1_single)
     float *compact = (S == 1 && !pr->has_neg) ? info + (size_t)N * 4 : nullptr;
+    // ... and on a graph whose rows do not shrink (the per-row totals of s_pos date from s2v_graph_prepare)
+    // flag bits come first and the table is not needed at all (see gather_tile_mu1_single, mode 2)
+    const bool by_bits = compact && !g->row_end && !x_res && !wagg && T >= 2;
+    unsigned long long *xbits = by_bits ? at<unsigned long long>(ws, f.xbits) : nullptr;
+    if (by_bits) compact = nullptr;
     if (x_res)
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info, compact));
     else
-        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info, compact));
+        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info, compact, by_bits ? at<float>(ws, h.nbr_sp) : nullptr,
+                                xbits));
     NodeInfo ninfo = make_nodeinfo(info, S, x_res != nullptr);
     ninfo.compact = compact;
+    ninfo.xbits = reinterpret_cast<const unsigned *>(xbits);
     if ((mu_saved && !fused) || T == 1)
         S2V_TRY(launch_round1(st, p, N, S, ninfo, x_res, T == 1, params->theta1, qvec, dest(1)));
     const bool fuse_gsum = gsum && (S == 1 || S == 16) && G == 1 && T >= 2 && N > 0;

@@ -242,29 +242,44 @@ __device__ __forceinline__ float4 gather_row_sum_mu1_single(const float *__restr
 // load per row, so a wave has hundreds of them in flight instead of 32.  Cheap neighbours (see
 // gather_row_sum_mu1_single) are summed by a wave reduction of one scalar; the few others are
 // visited one by one, lane j forming column j of relu(x theta1 + s+ q+ + s- q-).
-// COMPACT: the first load reads the 4-byte table compact[u] (s+ of a cheap neighbour, NaN for any
-// other) instead of the 16-byte record, and only the lanes that met a NaN fetch the record: the
-// table is a quarter of the records' size, so far more of it stays in the L2.
+// MODE 1 (compact table): the first load reads the 4-byte table compact[u] (s+ of a cheap neighbour,
+// NaN for any other) instead of the 16-byte record, and only the lanes that met a NaN fetch the record:
+// the table is a quarter of the records' size, so more of it stays in the L2.
+// MODE 2 (flag bits + per-row total; static graph without negative weights): even that table (4 N bytes)
+// exceeds an L2 at a few million nodes, and a miss moves a whole cache line for four useful bytes: at
+// 2 M nodes and 60 M entries the round fetched 5 GB that way.  Here the first load tests bit u of xbits
+// (N / 8 bytes: always in the L2), only flagged neighbours (x_u != 0) fetch their record, and the sum of
+// s+ over the unflagged ones is the row's precomputed total over all neighbours (fourth float of the
+// row's own record) minus the s+ of the flagged ones.
 // Rows with more than 64 entries continue in 64-entry chunks; rows longer than max_len are skipped
 // (their sums are already in the tile).  rb / re: lane i (mod 16) holds begin / end of tile row i.
 // The result of row i goes to tile[i * STRIDE + column].  lc = {theta1, q+, q-} in LDS ([3][P]).
-template <int P, bool COMPACT>
+template <int P, int MODE>
 __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float *__restrict__ rec,
-                                                       const float *__restrict__ compact, const float *lc,
+                                                       const float *__restrict__ compact,
+                                                       const unsigned *__restrict__ xbits, const float *lc,
                                                        const int *__restrict__ colidx, int rb, int re, int max_len,
-                                                       int lane) {
+                                                       int lane, float total_mine = 0.f) {
+    // total_mine (mode 2): lane i (mod 16) holds the total of s+ over all neighbours of tile row i
     constexpr int STRIDE = Geo<P>::STRIDE;
     const int j = lane % P;
     const float t1 = lc[j], qp = lc[P + j], qn = lc[2 * P + j];
     const float rp = fmaxf(qp, 0.f);
-    // the scalars of neighbour u as {x, s+, s-}; a missing neighbour (u < 0) adds nothing
+    // the scalars of neighbour u as {x, s+, s-}; a missing neighbour (u < 0) adds nothing.  In mode 2 an
+    // unflagged neighbour comes back as all zeros (it is accounted for by the row's total).
     auto fetch = [&](int u, float &x, float &sp, float &sn) {
         x = 0.f; sp = 0.f; sn = 0.f;
-        if (COMPACT) {
+        if (MODE == 1) {
             const float c = u >= 0 ? compact[u] : 0.f;
             if (c == c) { sp = c; return; }
             const float4 r = ld4(rec + (size_t)u * 4);
             x = r.x; sp = r.y; sn = r.z;
+        } else if (MODE == 2) {
+            const unsigned wd = u >= 0 ? xbits[u >> 5] : 0u;
+            if ((wd >> (u & 31)) & 1u) {
+                const float4 r = ld4(rec + (size_t)u * 4);
+                x = r.x; sp = r.y; sn = r.z;
+            }
         } else if (u >= 0) {
             const float4 r = ld4(rec + (size_t)u * 4);
             x = r.x; sp = r.y; sn = r.z;
@@ -280,7 +295,7 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
             cols[k] = (n <= max_len && lane < n) ? colidx[b + lane] : -1;   // lane < n <= 64 entries of the first chunk
         }
         float rx[8], rs[8], rn[8];
-        if (COMPACT) {
+        if (MODE == 1) {
             // all eight table loads first, then the record loads of the lanes that need one
             float c[8];
 #pragma unroll
@@ -289,6 +304,18 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
             for (int k = 0; k < 8; ++k) {
                 rx[k] = 0.f; rs[k] = c[k]; rn[k] = 0.f;
                 if (c[k] != c[k]) {
+                    const float4 r = ld4(rec + (size_t)cols[k] * 4);
+                    rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
+                }
+            }
+        } else if (MODE == 2) {
+            unsigned wd[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) wd[k] = cols[k] >= 0 ? xbits[cols[k] >> 5] : 0u;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                rx[k] = 0.f; rs[k] = 0.f; rn[k] = 0.f;
+                if ((wd[k] >> (cols[k] & 31)) & 1u) {
                     const float4 r = ld4(rec + (size_t)cols[k] * 4);
                     rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
                 }
@@ -303,24 +330,30 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
             const int b = __shfl(rb, i), e = __shfl(re, i);
             if (e - b > max_len) continue;                     // wave-uniform
             float ssum = 0.f, acc = 0.f;
+            float flagged_sp = 0.f;                            // mode 2: s+ of the flagged neighbours (wave-uniform)
             float x = rx[k], sp = rs[k], sn = rn[k];
             int base = b;
             while (true) {
                 const bool cheap = x == 0.f && sn == 0.f;
-                ssum += cheap ? sp : 0.f;
-                unsigned long long todo = __ballot(!cheap);
+                if (MODE != 2) ssum += cheap ? sp : 0.f;
+                unsigned long long todo = __ballot(MODE == 2 ? x != 0.f : !cheap);
                 while (todo != 0ull) {
                     const int l = __ffsll((long long)todo) - 1;
                     todo &= todo - 1ull;
                     const float xl = readlane_f(x, l), pl = readlane_f(sp, l), nl = readlane_f(sn, l);
                     acc += fmaxf(xl * t1 + pl * qp + nl * qn, 0.f);
+                    if (MODE == 2) flagged_sp += pl;
                 }
                 base += 64;
                 if (base >= e) break;                          // wave-uniform
                 fetch((base + lane < e) ? colidx[base + lane] : -1, x, sp, sn);
             }
+            if (MODE == 2) {
+                ssum = __shfl(total_mine, i) - flagged_sp;
+            } else {
 #pragma unroll
-            for (int m = 1; m < 64; m <<= 1) ssum += __shfl_xor(ssum, m);
+                for (int m = 1; m < 64; m <<= 1) ssum += __shfl_xor(ssum, m);
+            }
             if (lane < P) tile[i * STRIDE + lane] = fmaf(ssum, rp, acc);
         }
     }

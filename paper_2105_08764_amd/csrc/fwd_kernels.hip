@@ -40,6 +40,29 @@ hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const 
     return hipGetLastError();
 }
 
+// nbr_sp[v] = sum_{u in N(v)} s+_u: what the neighbour sum of round 2 comes to when no neighbour is in the
+// solution (then mu^1_u = s+_u relu(q+) for every u).  Rows beyond kHubDegree go through the long-row
+// pre-pass and never use it.
+__global__ __launch_bounds__(256) void k_prepare_nbr(int N, const int32_t *__restrict__ rowptr,
+                                                     const int32_t *__restrict__ rowend,
+                                                     const int32_t *__restrict__ colidx,
+                                                     const float *__restrict__ s_pos, float *__restrict__ nbr_sp) {
+    for (int v = blockIdx.x * blockDim.x + threadIdx.x; v < N; v += gridDim.x * blockDim.x) {
+        const int b = rowptr[v], e = rowend[v];
+        double a = 0.0;
+        if (e - b <= kHubDegree)
+            for (int j = b; j < e; ++j) a += (double)s_pos[colidx[j]];
+        nbr_sp[v] = (float)a;
+    }
+}
+
+hipError_t launch_prepare_nbr(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const int32_t *colidx,
+                              const float *s_pos, float *nbr_sp) {
+    if (N == 0) return hipSuccess;
+    k_prepare_nbr<<<min((N + 255) / 256, 65536), 256, 0, st>>>(N, rowptr, rowend, colidx, s_pos, nbr_sp);
+    return hipGetLastError();
+}
+
 // q+ = theta3 relu(theta4), q- = theta3 relu(-theta4)   (two p-vectors, qvec = [q+ ; q-])
 __global__ void k_qvec(int p, const float *__restrict__ theta3, const float *__restrict__ theta4,
                        float *__restrict__ qvec) {
@@ -114,7 +137,8 @@ hipError_t launch_round1(hipStream_t st, int p, int N, int S, const NodeInfo &ni
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const float *__restrict__ x,
                                                   const float *__restrict__ s_pos, const float *__restrict__ s_neg,
-                                                  float *__restrict__ info, float *__restrict__ compact) {
+                                                  float *__restrict__ info, float *__restrict__ compact,
+                                                  const float *__restrict__ nbr_sp) {
     const long total = (long)N * ni;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
         const int v = (int)(i / ni), c = (int)(i - (long)v * ni);
@@ -122,19 +146,36 @@ __global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const fl
         if (c < S) o = x[(size_t)c * N + v];
         else if (c == S) o = s_pos[v];
         else if (c == S + 1) o = s_neg[v];
+        else if (nbr_sp && c == 3) o = nbr_sp[v];   // (S == 1: the record's spare float)
         info[i] = o;
         // S = 1: s+ alone for a node whose round-1 row is s+ relu(q+), NaN for any other node
         if (compact && c == 0) compact[v] = (o == 0.f && s_neg[v] == 0.f) ? s_pos[v] : __int_as_float(0x7fc00000);
     }
 }
 
+// bit v of bits = (x[v] != 0); one 64-bit word per wave and step
+__global__ __launch_bounds__(256) void k_xbits(int N, const float *__restrict__ x, unsigned long long *__restrict__ bits) {
+    const int n_words = (N + 63) / 64;
+    const int lane = threadIdx.x & 63;
+    for (int wd = blockIdx.x * 4 + (threadIdx.x >> 6); wd < n_words; wd += gridDim.x * 4) {   // wave-uniform
+        const int v = wd * 64 + lane;
+        const unsigned long long b = __builtin_amdgcn_ballot_w64(v < N && x[v] != 0.f);
+        if (lane == 0) bits[wd] = b;
+    }
+}
+
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
-                           float *info, float *compact) {
+                           float *info, float *compact, const float *nbr_sp, unsigned long long *xbits) {
     if (N == 0) return hipSuccess;
     const int ni = make_nodeinfo(info, S, false).ni;
     const long total = (long)N * ni;
     k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info,
-                                                                           S == 1 ? compact : nullptr);
+                                                                           S == 1 ? compact : nullptr,
+                                                                           S == 1 ? nbr_sp : nullptr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || S != 1 || !xbits) return e;
+    const int n_words = (N + 63) / 64;
+    k_xbits<<<min((n_words + 3) / 4, 16384), 256, 0, st>>>(N, x, xbits);
     return hipGetLastError();
 }
 
@@ -268,7 +309,7 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 //         its own so that it shows under its own name in profiles.
 // ------------------------------------------------------------------------------------------
 constexpr int kRoundPlain = 0, kRoundMaskOut = 1, kRoundByState = 2;
-template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN, int VAR = 0>
+template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN, int VAR = kRoundPlain>
 #ifndef S2V_ROUND_OCC
 #define S2V_ROUND_OCC 4
 #endif
@@ -394,10 +435,13 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
             }
             if (MU1 && !W && S == 1) {
                 // single state, round 2: one lane per neighbour, the whole tile's records in flight
-                if (info.compact)
-                    gather_tile_mu1_single<P, true>(tile, info.base, info.compact, lds_c, colidx, rb, re, kHubDegree, lane);
+                if (info.xbits)
+                    gather_tile_mu1_single<P, 2>(tile, info.base, nullptr, info.xbits, lds_c, colidx, rb, re, kHubDegree, lane,
+                                                 valid ? info.base[(size_t)v * 4 + 3] : 0.f);
+                else if (info.compact)
+                    gather_tile_mu1_single<P, 1>(tile, info.base, info.compact, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
                 else
-                    gather_tile_mu1_single<P, false>(tile, info.base, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
+                    gather_tile_mu1_single<P, 0>(tile, info.base, nullptr, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
             } else {
             int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;

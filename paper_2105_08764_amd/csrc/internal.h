@@ -59,6 +59,11 @@ struct NodeInfo {
     int ss;       // stride over states of s+ / s-: 0 or 1
     // S = 1 only, optional: compact[v] = s+ of v if its round-1 row is s+ relu(q+) (x = 0 and s- = 0), else NaN
     const float *__restrict__ compact;
+    // S = 1 only, optional (static graph without negative weights): bit v of xbits = (x_v != 0), and the fourth
+    // float of node v's record holds nbr_sp[v] = the sum of s+ over ALL neighbours of v (computed once per
+    // graph).  The sum over the neighbours with x = 0 that round 2 needs is then nbr_sp[v] minus the s+ of
+    // the few flagged neighbours, and the round reads a 4-byte table entry only for those.
+    const unsigned *__restrict__ xbits;
     __device__ __forceinline__ const float *node(int v) const { return base + (size_t)v * ni; }
     __device__ __forceinline__ float x(int v, int s) const { return node(v)[s]; }
     __device__ __forceinline__ float sp(int v, int s) const { return node(v)[sp_off + s * ss]; }
@@ -85,6 +90,7 @@ inline NodeInfo make_nodeinfo(const float *base, int S, bool per_state) {
     n.ss = per_state ? 1 : 0;
     n.ni = (n.sn_off + (per_state ? S : 1) + 3) / 4 * 4;
     n.compact = nullptr;
+    n.xbits = nullptr;
     return n;
 }
 
@@ -107,7 +113,12 @@ constexpr int kRoundGridMax = S2V_ROUND_GRID;
 int round_grid(long n_vrows);
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
                            float *info /*written in the shared-sums layout of make_nodeinfo*/,
-                           float *compact /*[N], written when S == 1; may be NULL*/);
+                           float *compact /*[N], written when S == 1; may be NULL*/,
+                           const float *nbr_sp = nullptr /*[N]: S == 1, goes into the records' fourth float*/,
+                           unsigned long long *xbits = nullptr /*[ceil(N/64)]: S == 1, bit v = (x_v != 0)*/);
+// nbr_sp[v] = sum of s_pos over the live entries of row v (0 for rows longer than kHubDegree, which never use it)
+hipError_t launch_prepare_nbr(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const int32_t *colidx,
+                              const float *s_pos, float *nbr_sp);
 // Neighbour sums of the hub rows: hub_sum[h][S][p] = sum over the row of hub h of src[u][s][:]
 // (mask != NULL: counts of set relu-mask bits instead; else src == NULL: the round-1 rows
 // recomputed from info).  partial is [n_segs][S][p] scratch.
