@@ -57,6 +57,36 @@ def test_forward_and_scores_match_oracle(oracle_mod, kind, p, T):
     assert gu.rel_err(out["q"][0], q) <= TOL
 
 
+@pytest.mark.parametrize("weights", ["unit", "positive", "signed"])
+@pytest.mark.parametrize("n,prob,xprob", [(257, 0.4, 0.3), (700, 0.3, 0.02), (300, 0.05, 0.9)])
+def test_round2_single_state_every_neighbour_lookup(oracle_mod, weights, n, prob, xprob):
+    # Round 2 of a single state finds the neighbours outside the solution in one of three ways: flag bits
+    # plus the row's precomputed total (static graph, no negative weight), the 4-byte table (rows that can
+    # shrink) or the records (negative weights).  Rows of two to four 64-entry chunks, few and many flagged.
+    import torch
+
+    print(f"case round 2 lookups weights={weights} n={n} prob={prob} xprob={xprob}", flush=True)
+    p, T = 64, 2
+    g = si.erdos_renyi_gnp(n, prob, 21)
+    if weights == "positive":
+        g.w = si.symmetric_edge_weights(g, 3, 0.5, 1.5)
+    elif weights == "signed":
+        g.w = si.signed_edge_weights(g, 3, 1.0)
+    theta = si.thetas(p, 77, 0.02)
+    x = si.node_flags(g.n, xprob, 9)
+    mu = oracle_mod.embed(g.rowptr, g.colidx, g.w, theta, x[0], T)
+    dev = gu.Device(g, p, T)
+    out = dev.forward(theta, x)
+    assert gu.rel_err(out["mu"][:, 0, :], mu) <= TOL
+    # the same graph as a copy whose rows may shrink (none has yet)
+    mut = dev.graph.mutable_copy()
+    dev.ctx.s2v_graph_prepare(mut, dev.ws)
+    got = torch.full((g.n, 1, p), float("nan"), device="cuda")
+    dev.ctx.s2v_embed_fwd(mut, dev.params(theta), torch.from_numpy(x).cuda(), T, 1, got, None, None, dev.ws)
+    torch.cuda.synchronize()
+    assert gu.rel_err(got.cpu().numpy()[:, 0, :], mu) <= TOL
+
+
 @pytest.mark.parametrize("S", [2, 5, 16])
 def test_forward_many_states(oracle_mod, S):
     print(f"case states S={S}", flush=True)
