@@ -401,21 +401,21 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
             }
             store_node_block<P>(tile_g, ga, lane);
         } else {
-            int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
+            int b_next = __builtin_amdgcn_readlane(rb, 0), e_next = __builtin_amdgcn_readlane(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
 #pragma unroll 1
             for (int i = 0; i < kTileRows; ++i) {
                 const int b = b_next, e = e_next;
                 const int cols = cols_next;
-                const int si = __shfl(s, i);
+                const int si = __builtin_amdgcn_readlane(s, i);   // (i is wave-uniform)
                 if (i + 1 < kTileRows) {
-                    b_next = __shfl(rb, i + 1);
-                    e_next = __shfl(re, i + 1);
+                    b_next = __builtin_amdgcn_readlane(rb, i + 1);
+                    e_next = __builtin_amdgcn_readlane(re, i + 1);
                     cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
                 }
                 float4 a;
                 if (e - b > kHubDegree) {
-                    const int h = hub_index(ht.hub_rows, ht.n_hubs, __shfl(v, i));
+                    const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readlane(v, i));
                     a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
                 } else if (MASK) {
                     const BitsRow bits{maskT, S, si, 4 * li};
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                     a = gather_row_sum<P, W>(mem, colidx, wagg, b, e, cols, lane);
                 }
                 if (MASK) {
-                    const bool ing = __shfl((int)in_graph, i) != 0;
+                    const bool ing = __builtin_amdgcn_readlane((int)in_graph, i) != 0;
                     const float4 d = ld4(dg + (size_t)si * P + 4 * li);
                     a.x = ing ? a.x * d.x : 0.f;
                     a.y = ing ? a.y * d.y : 0.f;

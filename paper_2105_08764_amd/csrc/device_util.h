@@ -291,7 +291,8 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int i = 8 * half + k;
-            const int b = __shfl(rb, i), n = __shfl(re, i) - b;
+            // (i is wave-uniform: a lane read, not a shuffle through LDS)
+            const int b = __builtin_amdgcn_readlane(rb, i), n = __builtin_amdgcn_readlane(re, i) - b;
             cols[k] = (n <= max_len && lane < n) ? colidx[b + lane] : -1;   // lane < n <= 64 entries of the first chunk
         }
         float rx[8], rs[8], rn[8];
@@ -327,7 +328,7 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int i = 8 * half + k;
-            const int b = __shfl(rb, i), e = __shfl(re, i);
+            const int b = __builtin_amdgcn_readlane(rb, i), e = __builtin_amdgcn_readlane(re, i);
             if (e - b > max_len) continue;                     // wave-uniform
             float ssum = 0.f, acc = 0.f;
             float flagged_sp = 0.f;                            // mode 2: s+ of the flagged neighbours (wave-uniform)
@@ -349,7 +350,7 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
                 fetch((base + lane < e) ? colidx[base + lane] : -1, x, sp, sn);
             }
             if (MODE == 2) {
-                ssum = __shfl(total_mine, i) - flagged_sp;
+                ssum = readlane_f(total_mine, i) - flagged_sp;
             } else {
 #pragma unroll
                 for (int m = 1; m < 64; m <<= 1) ssum += __shfl_xor(ssum, m);

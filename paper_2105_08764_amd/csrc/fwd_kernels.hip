@@ -443,16 +443,16 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
                 else
                     gather_tile_mu1_single<P, 0>(tile, info.base, nullptr, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
             } else {
-            int b_next = __shfl(rb, 0), e_next = __shfl(re, 0);
+            int b_next = __builtin_amdgcn_readlane(rb, 0), e_next = __builtin_amdgcn_readlane(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
 #pragma unroll 1
             for (int i = 0; i < kTileRows; ++i) {
                 const int b = b_next, e = e_next;
                 const int cols = cols_next;
-                const int si = __shfl(s, i);
+                const int si = __builtin_amdgcn_readlane(s, i);   // (i is wave-uniform)
                 if (i + 1 < kTileRows) {
-                    b_next = __shfl(rb, i + 1);
-                    e_next = __shfl(re, i + 1);
+                    b_next = __builtin_amdgcn_readlane(rb, i + 1);
+                    e_next = __builtin_amdgcn_readlane(re, i + 1);
                     // long rows need no indices here
                     cols_next = (e_next - b_next <= kHubDegree && lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
                 }
