@@ -149,7 +149,7 @@ def rel_err(got: np.ndarray, ref: np.ndarray, floor_frac: float = FLOOR_FRAC, wh
 
 
 def thetas_clear_of_kinks(oracle, g: si.Graph, p: int, T: int, x, action, target, seed: int, scale: float,
-                          eps: float = 2.5e-7, limit: float = 2e-5, tries: int = 24):
+                          eps: float = 2.5e-7, limit: float = 2e-5, tries: int = 24, grad_fn=None):
     """Parameters for a gradient parity case, drawn so that the comparison with float64 is meaningful.
 
     The gradient of Eq. 1 jumps wherever a pre-activation crosses zero.  With some 10^6 pre-activations
@@ -161,10 +161,13 @@ def thetas_clear_of_kinks(oracle, g: si.Graph, p: int, T: int, x, action, target
     difference has the size of the jump.  The seeds seed, seed + 1000, ... are tried in order and the
     first is taken for which no second difference over k = -2..2 along three directions exceeds `limit`
     (measured like rel_err over the whole tensor); only the oracle is consulted.
+    grad_fn(theta) -> gradient dict replaces the plain oracle call (weighted sum, per-state residual graphs).
     Returns (theta, seed used)."""
     rng = np.random.default_rng(12345)
 
     def grad(th):
+        if grad_fn is not None:
+            return grad_fn(th)
         return oracle.loss_grad(g.rowptr, g.colidx, g.w, g.graph_off, th, x, T, action, target)[2]
 
     for k in range(tries):

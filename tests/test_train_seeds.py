@@ -24,3 +24,19 @@ def test_detector_flags_a_draw_next_to_a_jump(oracle_mod):
     g, x, action, target = tc.inputs(kind, S)
     _, seed = gu.thetas_clear_of_kinks(oracle_mod, g, p, T, x, action, target, tc.first_seed(p, T), tc.theta_scale(kind))
     assert seed == tc.stored_seeds()[(kind, p, T, S)] and seed != tc.first_seed(p, T)
+
+
+def test_every_sweep_case_has_a_seed():
+    from tests import sweep_cases as sc
+
+    assert set(sc.stored_seeds()) == set(range(sc.N_CASES))
+
+
+@pytest.mark.parametrize("case", [0, 7, 13, 21, 33])
+def test_stored_sweep_seed_is_the_first_clear_one(oracle_mod, case):
+    from tests import sweep_cases as sc
+
+    c = sc.draw(case)
+    x, action, target = sc.training_inputs(c)
+    _, seed = sc.screened_theta(oracle_mod, c, x, action, target)
+    assert seed == sc.stored_seeds()[case]
