@@ -202,9 +202,11 @@ def bench_training(args, s2v, torch):
     out = dict(ms_per_step=ms, ms_per_iteration=ms / w.iters, steps=steps, iterations=w.iters, S=S, n=N, nnz=g.nnz,
                fwd_round_ms=ms_f / max(n_f, 1), bwd_round_ms=ms_b / max(n_b, 1), fwd_round2_ms=ms_f2 / max(n_f2, 1),
                fwd_round_gbs=alg / (ms_f / max(n_f, 1) * 1e-3) / 1e9 if n_f else None,
-               bwd_rounds="mean over the T-1 reversed rounds of an iteration, which differ in kind: the first "
-                          "gathers 8-byte mask words, the middle ones gather rows like the forward rounds, the "
-                          "last one (node mode) streams dz^2 and gathers the neighbours' scalars")
+               fwd_rounds="mean over the rounds 3..T of an iteration: round 3 walks the rows state by state, the "
+                          "last round writes relu-mask words and the graph sums instead of its rows",
+               bwd_rounds="mean over the launched reversed rounds of an iteration, which differ in kind: the first "
+                          "gathers 8-byte mask words, the next gathers rows like the forward rounds and also does "
+                          "the last reversed round (from the neighbours' scalars) on each tile")
     log(f"[bench] training {ms:.1f} ms/step ({w.iters} iterations); fwd round {out['fwd_round_ms']:.2f} ms, "
         f"bwd round {out['bwd_round_ms']:.2f} ms")
     return out
