@@ -94,7 +94,8 @@ FwdLayout fwd_layout(const HeadLayout &h, int64_t N, int p, int S, bool need_tmp
     Carver c(start ? start : h.end);   // (start: behind the backward pass's pieces when both run in one call)
     f.qvec = c.take(sizeof(float) * 2 * p);
     f.info = c.take(sizeof(float) * (size_t)N * nodeinfo_stride(S));
-    f.xbits = c.take(S == 1 ? sizeof(unsigned long long) * (size_t)((N + 63) / 64) : 0);
+    f.xbits = c.take(S == 1 ? sizeof(unsigned long long) * (size_t)((N + 63) / 64)
+                            : (S % 16 == 0 ? sizeof(unsigned short) * (size_t)N * (S / 16) : 0));
     size_t part_rows = (size_t)h.max_chunks * S;
     const size_t fused_rows = (size_t)kRoundGridMax * (S == 16 ? 16 : 1);   // partials of a fused graph sum
     if (part_rows < fused_rows) part_rows = fused_rows;
@@ -566,7 +567,8 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     float *compact = (S == 1 && !pr->has_neg) ? info + (size_t)N * 4 : nullptr;
     // ... and on a graph whose rows do not shrink (the per-row totals of s_pos date from s2v_graph_prepare)
     // flag bits come first and the table is not needed at all (see gather_tile_mu1_single, mode 2)
-    const bool by_bits = compact && !g->row_end && !x_res && !wagg && T >= 2;
+    // (for S a multiple of 16 the same with one 16-bit flag word per node and block of 16 states)
+    const bool by_bits = (S == 1 || S % 16 == 0) && !pr->has_neg && !g->row_end && !x_res && !wagg && T >= 2;
     unsigned long long *xbits = by_bits ? at<unsigned long long>(ws, f.xbits) : nullptr;
     if (by_bits) compact = nullptr;
     if (x_res)
@@ -576,7 +578,8 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
                                 xbits));
     NodeInfo ninfo = make_nodeinfo(info, S, x_res != nullptr);
     ninfo.compact = compact;
-    ninfo.xbits = reinterpret_cast<const unsigned *>(xbits);
+    if (S == 1) ninfo.xbits = reinterpret_cast<const unsigned *>(xbits);
+    else ninfo.flags16 = reinterpret_cast<const unsigned short *>(xbits);
     if ((mu_saved && !fused) || T == 1)
         S2V_TRY(launch_round1(st, p, N, S, ninfo, x_res, T == 1, params->theta1, qvec, dest(1)));
     const bool fuse_gsum = gsum && (S == 1 || S == 16) && G == 1 && T >= 2 && N > 0;

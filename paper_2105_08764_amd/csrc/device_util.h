@@ -611,6 +611,53 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const NodeInfo &ni, 
     return gather_node_block_mu1_impl<P, W, false>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane, stage);
 }
 
+// Round 2 in node mode without reading the neighbours' records (static graph, no negative weight, plain
+// neighbour sum; see NodeInfo::flags16).  For the 16 states s0 .. s0+15 of node v, row s of the tile is
+//   sum_u mu^1_{u,s} = total_v relu(q+) + sum over the flagged (u, s) of [relu(x_{u,s} theta1 + s+_u q+) - s+_u relu(q+)],
+// total_v = sum of s+ over all neighbours (computed once per graph): a neighbour outside the solution of
+// state s has mu^1 = s+_u relu(q+).  One lane per neighbour fetches a 16-bit flag word; the records of the
+// flagged neighbours only are touched (their s+, and x in the flagged states), and each flagged pair costs
+// one p-wide vector operation (lane j = column j, one accumulator register per state).
+// b .. e: at most kHubDegree entries.  lc = {theta1, q+, q-} in LDS.  Writes tile[s * STRIDE + j].
+template <int P>
+__device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeInfo &ni, int s0, const float *lc,
+                                                       const int *__restrict__ colidx, int b, int e, int lane,
+                                                       float total) {
+    constexpr int STRIDE = Geo<P>::STRIDE;
+    const int j = lane % P;
+    const float t1 = lc[j], qp = lc[P + j];
+    const float rp = fmaxf(qp, 0.f);
+    const int nb = ni.S >> 4, blk = s0 >> 4;
+    float acc[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) acc[s] = 0.f;
+    for (int base = b; base < e; base += 64) {
+        const int u = (base + lane < e) ? colidx[base + lane] : -1;
+        const unsigned f = u >= 0 ? (unsigned)ni.flags16[(size_t)u * nb + blk] : 0u;
+        if (__ballot(f != 0u) == 0ull) continue;                     // wave-uniform
+        const float *r = ni.node(u >= 0 ? u : 0);
+        const float sp = f != 0u ? r[ni.sp_off] : 0.f;
+        float xs[16];
+#pragma unroll
+        for (int s = 0; s < 16; ++s) xs[s] = ((f >> s) & 1u) ? r[s0 + s] : 0.f;
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            unsigned long long todo = __ballot((f >> s) & 1u);
+            while (todo != 0ull) {
+                const int l = __ffsll((long long)todo) - 1;
+                todo &= todo - 1ull;
+                const float xl = readlane_f(xs[s], l), pl = readlane_f(sp, l);
+                acc[s] += fmaxf(fmaf(xl, t1, pl * qp), 0.f) - pl * rp;
+            }
+        }
+    }
+    const float base_row = total * rp;
+    if (lane < P) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s) tile[s * STRIDE + lane] = base_row + acc[s];
+    }
+}
+
 // The neighbour sums that the LAST reversed round (t = 2) needs when it is taken from the scalars
 // instead of gathering dz^2 (node mode).  With z_u = x_u theta1 + s+_u q+ + s-_u q- (the round-1
 // pre-activation of neighbour u, recomputed as in gather_node_block_mu1) and m_u = [z_u > 0]:

@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const fl
         if (c < S) o = x[(size_t)c * N + v];
         else if (c == S) o = s_pos[v];
         else if (c == S + 1) o = s_neg[v];
-        else if (nbr_sp && c == 3) o = nbr_sp[v];   // (S == 1: the record's spare float)
+        else if (nbr_sp && c == S + 2) o = nbr_sp[v];   // (the record's first spare float)
         info[i] = o;
         // S = 1: s+ alone for a node whose round-1 row is s+ relu(q+), NaN for any other node
         if (compact && c == 0) compact[v] = (o == 0.f && s_neg[v] == 0.f) ? s_pos[v] : __int_as_float(0x7fc00000);
@@ -164,6 +164,19 @@ __global__ __launch_bounds__(256) void k_xbits(int N, const float *__restrict__ 
     }
 }
 
+// flags[v * nb + k]: bit i = (x[16 k + i][v] != 0), nb = S / 16
+__global__ __launch_bounds__(256) void k_flags16(int N, int nb, const float *__restrict__ x,
+                                                 unsigned short *__restrict__ flags) {
+    const long total = (long)N * nb;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int k = (int)(i / N), v = (int)(i - (long)k * N);    // consecutive threads: consecutive nodes
+        unsigned f = 0u;
+#pragma unroll
+        for (int b = 0; b < 16; ++b) f |= (x[(size_t)(16 * k + b) * N + v] != 0.f ? 1u : 0u) << b;
+        flags[(size_t)v * nb + k] = (unsigned short)f;
+    }
+}
+
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
                            float *info, float *compact, const float *nbr_sp, unsigned long long *xbits) {
     if (N == 0) return hipSuccess;
@@ -171,9 +184,16 @@ hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const f
     const long total = (long)N * ni;
     k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info,
                                                                            S == 1 ? compact : nullptr,
-                                                                           S == 1 ? nbr_sp : nullptr);
+                                                                           (S == 1 || S % 16 == 0) ? nbr_sp : nullptr);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || S != 1 || !xbits) return e;
+    if (e != hipSuccess || !xbits) return e;
+    if (S % 16 == 0) {
+        const long total = (long)N * (S / 16);
+        k_flags16<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S / 16, x,
+                                                                             reinterpret_cast<unsigned short *>(xbits));
+        return hipGetLastError();
+    }
+    if (S != 1) return e;
     const int n_words = (N + 63) / 64;
     k_xbits<<<min((n_words + 3) / 4, 16384), 256, 0, st>>>(N, x, xbits);
     return hipGetLastError();
@@ -410,6 +430,10 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
                 acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
                 store_node_block<P>(tile, acc, lane);
+            } else if (MU1 && !W && info.flags16) {
+                // flag words and the row's total instead of the neighbours' records
+                gather_node_tile_flags<P>(tile, info, s0, lds_c, colidx, b, e, lane,
+                                          info.node(__builtin_amdgcn_readfirstlane(v))[info.sn_off + 1]);
             } else if (MU1) {
                 // the gather from the records works in the state-major lane layout
                 acc = gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane,

@@ -64,6 +64,10 @@ struct NodeInfo {
     // graph).  The sum over the neighbours with x = 0 that round 2 needs is then nbr_sp[v] minus the s+ of
     // the few flagged neighbours, and the round reads a 4-byte table entry only for those.
     const unsigned *__restrict__ xbits;
+    // The same idea for S a multiple of 16 (static graph, no negative weights, all states on the stored graph):
+    // flags16[v * (S / 16) + k] has bit i set when x of node v in state 16 k + i is non-zero, and the first
+    // spare float of node v's record (behind s-) holds nbr_sp[v].
+    const unsigned short *__restrict__ flags16;
     __device__ __forceinline__ const float *node(int v) const { return base + (size_t)v * ni; }
     __device__ __forceinline__ float x(int v, int s) const { return node(v)[s]; }
     __device__ __forceinline__ float sp(int v, int s) const { return node(v)[sp_off + s * ss]; }
@@ -91,6 +95,7 @@ inline NodeInfo make_nodeinfo(const float *base, int S, bool per_state) {
     n.ni = (n.sn_off + (per_state ? S : 1) + 3) / 4 * 4;
     n.compact = nullptr;
     n.xbits = nullptr;
+    n.flags16 = nullptr;
     return n;
 }
 
@@ -114,8 +119,9 @@ int round_grid(long n_vrows);
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
                            float *info /*written in the shared-sums layout of make_nodeinfo*/,
                            float *compact /*[N], written when S == 1; may be NULL*/,
-                           const float *nbr_sp = nullptr /*[N]: S == 1, goes into the records' fourth float*/,
-                           unsigned long long *xbits = nullptr /*[ceil(N/64)]: S == 1, bit v = (x_v != 0)*/);
+                           const float *nbr_sp = nullptr /*[N]: goes into the records' first spare float (S == 1 or S % 16 == 0)*/,
+                           unsigned long long *xbits = nullptr /*S == 1: [ceil(N/64)], bit v = (x_v != 0);
+                                                                 S % 16 == 0: [N][S/16] 16-bit words, see NodeInfo::flags16*/);
 // nbr_sp[v] = sum of s_pos over the live entries of row v (0 for rows longer than kHubDegree, which never use it)
 hipError_t launch_prepare_nbr(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const int32_t *colidx,
                               const float *s_pos, float *nbr_sp);
