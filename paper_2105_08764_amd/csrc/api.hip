@@ -137,8 +137,8 @@ SelLayout sel_layout(const HeadLayout &h, int64_t N, int64_t k) {
 }
 
 struct BwdLayout {
-    size_t dg, da, glo, ghi, head_part, dz0, dz1, maskT, rec, qvec, dc_part, d2_part, dvec, red_tmp, hub_part, hub_sum,
-        hub_part4, hub_sum4, end;
+    size_t dg, da, glo, ghi, head_part, dz0, dz1, maskT, rec, flags16, qvec, dc_part, d2_part, dvec, red_tmp, hub_part,
+        hub_sum, hub_part4, hub_sum4, end;
     int dc_rows, d2_rows;
 };
 BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
@@ -159,6 +159,7 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.dz1 = c.take((T >= 5 || (T == 4 && S % 16 != 0)) ? sizeof(float) * (size_t)N * S * p : 0);
     b.maskT = c.take(T >= 2 ? sizeof(unsigned long long) * (size_t)N * S : 0);
     b.rec = c.take(sizeof(float) * (size_t)N * nodeinfo_stride(S));
+    b.flags16 = c.take(S % 16 == 0 ? sizeof(unsigned short) * (size_t)N * (S / 16) : 0);
     b.qvec = c.take(sizeof(float) * 2 * p);
     b.dc_part = c.take(sizeof(float) * (size_t)b.dc_rows * 3 * p);
     b.d2_part = c.take(sizeof(float) * (size_t)b.d2_rows * p * p);
@@ -754,9 +755,15 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     const float *wagg = g->weighted_sum ? g->w : nullptr;   // NULL weights mean w = 1: the plain sum
     if (x_res)
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, sc.rec, nullptr));
-    else
-        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec, nullptr));
-    const NodeInfo ninfo = make_nodeinfo(sc.rec, S, x_res != nullptr);
+    // (node mode on a static graph without negative weights: the last reversed round, done inside the round
+    //  t = 3, works from flag words and the rows' totals of s+ like the forward's round 2)
+    const bool by_flags = S % 16 == 0 && T >= 4 && !pr->has_neg && !g->row_end && !x_res && !wagg;
+    unsigned long long *flags = by_flags ? at<unsigned long long>(ws, bl.flags16) : nullptr;
+    if (!x_res)
+        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec, nullptr, by_flags ? at<float>(ws, h.nbr_sp) : nullptr,
+                                flags));
+    NodeInfo ninfo = make_nodeinfo(sc.rec, S, x_res != nullptr);
+    ninfo.flags16 = reinterpret_cast<const unsigned short *>(flags);
     S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part,
                              words_ready));
     float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);

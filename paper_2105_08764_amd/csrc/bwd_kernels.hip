@@ -275,7 +275,7 @@ struct FirstFuse {
     const float *hub_sum4;   // [n_hubs][4][S][P]
 };
 
-template <int P, bool NODE, bool MASK, bool W, bool FUSE, bool NEG>   // W: weighted neighbour sum (symmetric weights wagg)
+template <int P, bool NODE, bool MASK, bool W, bool FUSE, bool NEG, bool FLAGS = false>   // W: weighted neighbour sum (symmetric weights wagg)
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     int n_vrows, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     static_assert(!FUSE || (NODE && !MASK), "the fused last round needs node mode and dz in memory");
     // second tile per wave and record staging of the fused last round
     __shared__ __attribute__((aligned(16))) float lds_a[FUSE ? kWaves * TILE_F : 4];
-    __shared__ __attribute__((aligned(16))) float rec_stage[FUSE ? kWaves * kRecStageFloats : 4];
+    __shared__ __attribute__((aligned(16))) float rec_stage[(FUSE && !FLAGS) ? kWaves * kRecStageFloats : 4];
     __shared__ __attribute__((aligned(16))) float lds[kWaves * TILE_F];
     // staging area of the mask-word gather (node mode of the MASK round only)
     __shared__ __attribute__((aligned(16))) unsigned bits_stage[(NODE && MASK) ? kWaves * kBitsStageBytes / 4 : 4];
@@ -313,6 +313,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     for (int cb = 0; cb < CB; ++cb) cx[cb] = cp[cb] = cn[cb] = 0.f;
     // column sums of the fused last round (columns 4 * li .. of this lane)
     float4 fx4 = make_float4(0.f, 0.f, 0.f, 0.f), fp4 = fx4, fn4 = fx4;
+    // FLAGS: that round works from flag words and the rows' totals (see gather_node_tile_flags_grad); its
+    // sums are kept per column lane % P
+    static_assert(!FLAGS || (FUSE && !W && !NEG), "flag words: plain neighbour sum, no negative weight");
+    float fxj = 0.f, fpj = 0.f, t1j = 0.f, qpj = 0.f;
+    if (FLAGS) {
+        t1j = ff.theta1[lane % P];
+        qpj = ff.qvec[lane % P];
+    }
 
     const size_t row_stride = (size_t)S * P;
     const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
@@ -491,7 +499,23 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) tile_g[(4 * gl + rr) * STRIDE + 16 * cb + jl] = acc[cb][rr];
             NodeAcc4<P> g4;
-            if (ef - bf > kHubDegree) {
+            float cx16[FLAGS ? 16 : 1], cp16[FLAGS ? 16 : 1];
+            if constexpr (FLAGS) {
+                if (ef - bf > kHubDegree) {
+                    // the long row's four sums, plain [4][S][P] blocks: a into the tile, cx and cp by column
+                    const int h = hub_index(ht.hub_rows, ht.n_hubs, vf);
+                    const float *hb = ff.hub_sum4 + ((size_t)h * 4 * S + s0f) * P + (lane % P);
+#pragma unroll
+                    for (int st = 0; st < 16; ++st) {
+                        if (lane < P) tile_a[st * STRIDE + lane] = hb[(size_t)st * P];
+                        cx16[st] = hb[((size_t)S + st) * P];
+                        cp16[st] = hb[(2 * (size_t)S + st) * P];
+                    }
+                } else {
+                    gather_node_tile_flags_grad<P>(tile_a, cx16, cp16, ni, s0f, t1j, qpj, colidx, bf, ef, lane,
+                                                   ni.node(vf)[ni.sn_off + 1]);
+                }
+            } else if (ef - bf > kHubDegree) {
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, vf);
                 const float *hb = ff.hub_sum4 + ((size_t)h * 4 * S + s0f) * P;
                 g4.a = load_node_block_sm<P>(hb, lane);
@@ -500,9 +524,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                 g4.cn = load_node_block_sm<P>(hb + 3 * (size_t)S * P, lane);
             } else {
                 g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0f, ff.theta1, ff.qvec, colidx, wagg, bf, ef, lane,
-                                                           rec_stage + (FUSE ? wave * kRecStageFloats : 0));
+                                                           rec_stage + ((FUSE && !FLAGS) ? wave * kRecStageFloats : 0));
             }
-            store_node_block_sm<P>(tile_a, g4.a, lane);
+            if constexpr (!FLAGS) store_node_block_sm<P>(tile_a, g4.a, lane);
             __builtin_amdgcn_wave_barrier();
             // e = dz^{t-1} theta2 ; dtheta2 += dz^{t-1}^T a
             const Frag<P> ffrag = load_a_frag_lds<P>(tile_g, lane);
@@ -534,6 +558,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) tile_g[(4 * gl + rr) * STRIDE + 16 * cb + jl] = eacc[cb][rr];
             __builtin_amdgcn_wave_barrier();
+            if constexpr (FLAGS) {
+                if (lane < P) {
+#pragma unroll
+                    for (int st = 0; st < 16; ++st) {
+                        const float ev = tile_g[st * STRIDE + lane];
+                        fxj = fmaf(ev, cx16[st], fxj);
+                        fpj = fmaf(ev, cp16[st], fpj);
+                    }
+                }
+            } else
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 const float4 e4 = ld4(tile_g + (NC * (lane / LPR) + c) * STRIDE + 4 * li);
@@ -599,6 +633,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
             st4(pp, add4(ld4(pp), fp4));
             st4(pn, add4(ld4(pn), fn4));
         }
+        if (FLAGS) {
+            __builtin_amdgcn_wave_barrier();
+            if (lane < P) {
+                lds[(wave * 3 + 0) * P + lane] += fxj;
+                lds[(wave * 3 + 1) * P + lane] += fpj;
+            }
+        }
     }
     __syncthreads();
     for (int e = threadIdx.x; e < 3 * P; e += kThreads) {
@@ -628,6 +669,11 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
     do {                                                                                       \
         if (NODE && !MASK && do_fuse) {                                                        \
             if (neg) S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, (NODE && !MASK), true);              \
+            else if (!WW && ni.flags16)                                                        \
+                k_bwd_round<PP, NODE, MASK, false, (NODE && !MASK), false, (NODE && !MASK && !WW)>  \
+                    <<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, dz_in, maskT, sc.dg,   \
+                                                    sc.glo, sc.ghi, mu_prev, dz_out, ni, theta2, dc_part, d2_part, ht,    \
+                                                    hub_sum, ff);                                                         \
             else S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, (NODE && !MASK), false);                 \
         } else S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, false, false);                             \
     } while (0)

@@ -658,6 +658,57 @@ __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeIn
     }
 }
 
+// The same for the sums of the last reversed round (see gather_node_block_mu1_grad for a, cx, cp; no
+// negative weight, so cn = 0): per state s of the block and column j = lane,
+//   a  = total relu(q+)   + sum over flagged (u, s) of [relu(z) - s+_u relu(q+)]
+//   cx =                    sum over flagged (u, s) of x_{u,s} [z > 0]
+//   cp = total [q+ > 0]   + sum over flagged (u, s) of s+_u ([z > 0] - [q+ > 0]),      z = x_{u,s} theta1 + s+_u q+
+// (z is formed exactly as in gather_node_tile_flags, so forward and backward agree on every relu).
+// a goes to tile_a[s * STRIDE + j]; cx and cp come back in registers (index = state).
+template <int P>
+__device__ __forceinline__ void gather_node_tile_flags_grad(float *tile_a, float (&cx)[16], float (&cp)[16],
+                                                            const NodeInfo &ni, int s0, float t1, float qp,
+                                                            const int *__restrict__ colidx, int b, int e, int lane,
+                                                            float total) {
+    constexpr int STRIDE = Geo<P>::STRIDE;
+    const float rp = fmaxf(qp, 0.f);
+    const float mq = qp > 0.f ? 1.f : 0.f;
+    const int nb = ni.S >> 4, blk = s0 >> 4;
+    float a[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) { a[s] = 0.f; cx[s] = 0.f; cp[s] = 0.f; }
+    for (int base = b; base < e; base += 64) {
+        const int u = (base + lane < e) ? colidx[base + lane] : -1;
+        const unsigned f = u >= 0 ? (unsigned)ni.flags16[(size_t)u * nb + blk] : 0u;
+        if (__ballot(f != 0u) == 0ull) continue;                     // wave-uniform
+        const float *r = ni.node(u >= 0 ? u : 0);
+        const float sp = f != 0u ? r[ni.sp_off] : 0.f;
+        float xs[16];
+#pragma unroll
+        for (int s = 0; s < 16; ++s) xs[s] = ((f >> s) & 1u) ? r[s0 + s] : 0.f;
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            unsigned long long todo = __ballot((f >> s) & 1u);
+            while (todo != 0ull) {
+                const int l = __ffsll((long long)todo) - 1;
+                todo &= todo - 1ull;
+                const float xl = readlane_f(xs[s], l), pl = readlane_f(sp, l);
+                const float z = fmaf(xl, t1, pl * qp);
+                const float m = z > 0.f ? 1.f : 0.f;
+                a[s] += fmaxf(z, 0.f) - pl * rp;
+                cx[s] = fmaf(xl, m, cx[s]);
+                cp[s] = fmaf(pl, m - mq, cp[s]);
+            }
+        }
+    }
+    const float a0 = total * rp, c0 = total * mq;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+        cp[s] += c0;
+        if (lane < P) tile_a[s * STRIDE + lane] = a0 + a[s];
+    }
+}
+
 // The neighbour sums that the LAST reversed round (t = 2) needs when it is taken from the scalars
 // instead of gathering dz^2 (node mode).  With z_u = x_u theta1 + s+_u q+ + s-_u q- (the round-1
 // pre-activation of neighbour u, recomputed as in gather_node_block_mu1) and m_u = [z_u > 0]:
