@@ -136,7 +136,10 @@ int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t
  * computes it once, before the layer loop).  Because relu(theta4_k * w) equals
  * relu(theta4_k) * max(w,0) + relu(-theta4_k) * max(-w,0), the sum over a row needs only
  * the two per-node scalars  s+_v = sum_u max(W(v,u),0)  and  s-_v = sum_u max(-W(v,u),0),
- * which are stored at the head of `ws` together with the reduction chunk table.  The head
+ * which are stored at the head of `ws` together with the reduction chunk table, the table of
+ * long rows and, per row, the sum of s+ over the row's neighbours (what the neighbour sum of
+ * round 2 comes to for a node none of whose neighbours is in the solution; used when the graph
+ * has no row_end and no negative weight).  The head
  * of `ws` must stay untouched for as long as the graph is used with that workspace; the
  * other calls use the rest as scratch.  Reads graph_off back to the host, so this call
  * waits for the stream.  Call again if the graph's arrays change.
