@@ -50,6 +50,14 @@ def test_config5_full_training(oracle_mod):
     # (1) the timed shape: 16 states, one iteration
     dev = gu.Device(g, w.p, w.T, S=S, training=True)
     loss16, qp16, grads16 = dev.train_iter(dev.params(w.theta), w.x, w.action, w.target)
+    gsum16 = dev.last_gsum
+    torch.cuda.empty_cache()
+    # ... and the call bench.py times: forward and backward in one (state-by-state round 3, mask words instead of
+    # mu^T, flag words in round 2 and in the last reversed round) must give the same bits
+    lossf, qpf, gradsf, gsumf = dev.loss_grad(dev.params(w.theta), w.x, w.action, w.target)
+    assert lossf == loss16 and np.array_equal(qpf, qp16) and np.array_equal(gsumf, gsum16)
+    for k in grads16:
+        assert np.array_equal(gradsf[k], grads16[k]), k
     del dev
     torch.cuda.empty_cache()
     print(f"S=16 loss {loss16:.6g}", flush=True)
