@@ -868,7 +868,7 @@ hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *
     return hipGetLastError();
 }
 
-// The four sums of the long rows for k_bwd_first: one wave per (64-entry segment, 16-state block),
+// The four sums of the long rows for k_bwd_first: one wave per (segment, 16-state block),
 // then the segments of a row added in order (k_hub_combine with rows of 4 * S * p floats).
 template <int P, bool W, bool NEG>
 __global__ __launch_bounds__(kThreads) void k_hub_partial_grad(int S, HubTable ht, const int32_t *__restrict__ rowend,

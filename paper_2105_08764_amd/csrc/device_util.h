@@ -618,7 +618,7 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const NodeInfo &ni, 
 // state s has mu^1 = s+_u relu(q+).  One lane per neighbour fetches a 16-bit flag word; the records of the
 // flagged neighbours only are touched (their s+, and x in the flagged states), and each flagged pair costs
 // one p-wide vector operation (lane j = column j, one accumulator register per state).
-// b .. e: at most kHubDegree entries.  lc = {theta1, q+, q-} in LDS.  Writes tile[s * STRIDE + j].
+// b .. e: a row of at most kHubDegree entries.  lc = {theta1, q+, q-} in LDS.  Writes tile[s * STRIDE + j].
 template <int P>
 __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeInfo &ni, int s0, const float *lc,
                                                        const int *__restrict__ colidx, int b, int e, int lane,
@@ -716,7 +716,7 @@ __device__ __forceinline__ void gather_node_tile_flags_grad(float *tile_a, float
 //   cx = sum_u x_u m_u,   cp = sum_u s+_u m_u,   cn = sum_u s-_u m_u
 // each weighted by the edge weight when W.  NEG = false: no weight of the graph is negative, so
 // s- = 0 everywhere and cn is not formed.  One running sum per quantity: callers pass at most
-// kHubDegree entries (longer rows go through 64-entry segments).
+// kHubSegment entries (longer rows go through segments).
 template <int P>
 struct NodeAcc4 {
     NodeAcc<P> a, cx, cp, cn;

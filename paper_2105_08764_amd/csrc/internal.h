@@ -27,7 +27,9 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 // of the round kernel by many waves, each summing one segment of at most kHubSegment entries, so
 // that no single wave ever walks a long row.
 constexpr int kHubDegree = 256;
-constexpr int kHubSegment = 64;
+// (512: with 64-entry segments the partial sums of a graph whose rows are ALL long, the paper's ER(21 000, 0.15),
+//  cost more to write and re-read than the gathers themselves: 0.79 ms per inference step against 0.54 ms)
+constexpr int kHubSegment = 512;
 
 struct HubTable {              // device pointers into the prepared head of the workspace
     int n_hubs, n_segs;
