@@ -197,17 +197,22 @@ def bench_training(args, s2v, torch):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    (n_f, ms_f), (n_b, ms_b), (n_f2, ms_f2), _ = ctx.s2v_profile_end()
+    (n_f, ms_f), (n_b, ms_b), (n_f2, ms_f2), (n_fl, ms_fl) = ctx.s2v_profile_end()
     alg = round_algorithmic_bytes(N, g.nnz, p, S)
+    alg_last = alg - 4 * p * N * S + 8 * N * S      # the last round writes 8-byte mask words, not its rows
     out = dict(ms_per_step=ms, ms_per_iteration=ms / w.iters, steps=steps, iterations=w.iters, S=S, n=N, nnz=g.nnz,
-               fwd_round_ms=ms_f / max(n_f, 1), bwd_round_ms=ms_b / max(n_b, 1), fwd_round2_ms=ms_f2 / max(n_f2, 1),
+               fwd_round_ms=ms_f / max(n_f, 1), fwd_last_round_ms=ms_fl / max(n_fl, 1),
+               bwd_round_ms=ms_b / max(n_b, 1), fwd_round2_ms=ms_f2 / max(n_f2, 1),
                fwd_round_gbs=alg / (ms_f / max(n_f, 1) * 1e-3) / 1e9 if n_f else None,
-               fwd_rounds="mean over the rounds 3..T of an iteration: round 3 walks the rows state by state, the "
-                          "last round writes relu-mask words and the graph sums instead of its rows",
+               fwd_last_round_gbs=alg_last / (ms_fl / max(n_fl, 1) * 1e-3) / 1e9 if n_fl else None,
+               fwd_rounds="fwd_round: rounds 3..T-1 (rows walked state by state at this size); fwd_last_round: "
+                          "round T, which writes relu-mask words and the graph sums instead of its rows; GB/s = "
+                          "algorithmic bytes of the round over its mean duration",
                bwd_rounds="mean over the launched reversed rounds of an iteration, which differ in kind: the first "
                           "gathers 8-byte mask words, the next gathers rows like the forward rounds and also does "
                           "the last reversed round (from the neighbours' scalars) on each tile")
     log(f"[bench] training {ms:.1f} ms/step ({w.iters} iterations); fwd round {out['fwd_round_ms']:.2f} ms, "
+        f"last fwd round {out['fwd_last_round_ms']:.2f} ms, "
         f"bwd round {out['bwd_round_ms']:.2f} ms")
     return out
 

@@ -308,7 +308,8 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
  *   S2V_PROFILE_FWD_ROUND   rounds 3..T of Eq. 1 inside s2v_embed_fwd (neighbour rows read from memory)
  *   S2V_PROFILE_BWD_ROUND   the reversed rounds inside s2v_embed_bwd
  *   S2V_PROFILE_FWD_ROUND2  round 2 of Eq. 1 (neighbour rows recomputed from per-node scalars)
- *   S2V_PROFILE_FWD_ROUND_Q a last round that also forms the node term of Eq. 2 (inside s2v_policy_eval);
+ *   S2V_PROFILE_FWD_ROUND_Q a last round with more fused into it: the node term of Eq. 2 (inside
+ *                           s2v_policy_eval) or relu-mask words instead of its rows (inside s2v_loss_grad);
  *                           such a launch is not counted under S2V_PROFILE_FWD_ROUND
  * s2v_profile_end waits for the stream and returns, per kind, the number of bracketed launches
  * and the sum of their durations in milliseconds (host arrays of S2V_PROFILE_KINDS elements).

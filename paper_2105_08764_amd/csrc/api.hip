@@ -591,7 +591,8 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
         QHead qh{params->theta5, params->theta7, (fuse_q && t == T) ? q_node : nullptr};
         const float *src = t == 2 ? nullptr : dest(t - 1);
         S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, src, ninfo, params->theta1, qvec, nullptr, hub_part, hub_sum));
-        SpanGuard span(ctx, qh.q ? S2V_PROFILE_FWD_ROUND_Q : (t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND));
+        SpanGuard span(ctx, (qh.q || (fused && t == T)) ? S2V_PROFILE_FWD_ROUND_Q
+                                                            : (t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND));
         S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, src, dest(t), ninfo, params->theta1,
                              params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum, x_res,
                              t == T, qh,
