@@ -189,6 +189,9 @@ def test_results_are_deterministic():
     for _ in range(2):
         dev = gu.Device(g, w.p, w.T, S=S, k_max=50, training=True)
         loss, qp, grads = dev.train_iter(dev.params(w.theta), x, action, target)
+        one = dev.loss_grad(dev.params(w.theta), x, action, target)      # the single call: the same bits again
+        assert one[0] == loss and np.array_equal(one[1], qp)
+        assert all(np.array_equal(one[2][k], grads[k]) for k in si.THETA_NAMES)
         dev1 = gu.Device(g, w.p, w.T, k_max=50)
         f = dev1.forward(w.theta, w.x)
         sel = dev1.select(f["q"][0], w.x[0], None, 50)
