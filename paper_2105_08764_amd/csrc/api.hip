@@ -37,7 +37,7 @@ struct Carver {
 };
 
 struct HeadLayout {
-    size_t s_pos, s_neg, nbr_sp, chunk_begin, chunk_end, graph_chunk_off;
+    size_t s_pos, s_neg, nbr_sp, nbr_spw, chunk_begin, chunk_end, graph_chunk_off;
     size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, list, end;
     int max_chunks, max_hubs, max_segs;
 };
@@ -74,6 +74,7 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     h.s_pos = c.take(sizeof(float) * N);
     h.s_neg = c.take(sizeof(float) * N);
     h.nbr_sp = c.take(sizeof(float) * N);   // per row: s_pos summed over its neighbours (see NodeInfo::xbits)
+    h.nbr_spw = c.take(sizeof(float) * N);  // the same, each neighbour weighted by its edge weight
     h.chunk_begin = c.take(sizeof(int32_t) * h.max_chunks);
     h.chunk_end = c.take(sizeof(int32_t) * h.max_chunks);
     h.graph_chunk_off = c.take(sizeof(int32_t) * (G + 1));
@@ -497,8 +498,8 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
     S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, row_end_of(g), g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg),
                              neg_flag));
-    S2V_TRY(launch_prepare_nbr(ctx->stream, N, g->rowptr, row_end_of(g), g->colidx, at<float>(ws, h.s_pos),
-                               at<float>(ws, h.nbr_sp)));
+    S2V_TRY(launch_prepare_nbr(ctx->stream, N, g->rowptr, row_end_of(g), g->colidx, g->w, at<float>(ws, h.s_pos),
+                               at<float>(ws, h.nbr_sp), at<float>(ws, h.nbr_spw)));
     S2V_TRY(hipMemcpyAsync(&has_neg, neg_flag, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
     S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
@@ -569,14 +570,14 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     // ... and on a graph whose rows do not shrink (the per-row totals of s_pos date from s2v_graph_prepare)
     // flag bits come first and the table is not needed at all (see gather_tile_mu1_single, mode 2)
     // (for S a multiple of 16 the same with one 16-bit flag word per node and block of 16 states)
-    const bool by_bits = (S == 1 || S % 16 == 0) && !pr->has_neg && !g->row_end && !x_res && !wagg && T >= 2;
+    const bool by_bits = (S == 1 || S % 16 == 0) && !pr->has_neg && !g->row_end && !x_res && T >= 2;
     unsigned long long *xbits = by_bits ? at<unsigned long long>(ws, f.xbits) : nullptr;
     if (by_bits) compact = nullptr;
     if (x_res)
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info, compact));
     else
-        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info, compact, by_bits ? at<float>(ws, h.nbr_sp) : nullptr,
-                                xbits));
+        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info, compact,
+                                by_bits ? at<float>(ws, wagg ? h.nbr_spw : h.nbr_sp) : nullptr, xbits));
     NodeInfo ninfo = make_nodeinfo(info, S, x_res != nullptr);
     ninfo.compact = compact;
     if (S == 1) ninfo.xbits = reinterpret_cast<const unsigned *>(xbits);
@@ -758,11 +759,11 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, sc.rec, nullptr));
     // (node mode on a static graph without negative weights: the last reversed round, done inside the round
     //  t = 3, works from flag words and the rows' totals of s+ like the forward's round 2)
-    const bool by_flags = S % 16 == 0 && T >= 4 && !pr->has_neg && !g->row_end && !x_res && !wagg;
+    const bool by_flags = S % 16 == 0 && T >= 4 && !pr->has_neg && !g->row_end && !x_res;
     unsigned long long *flags = by_flags ? at<unsigned long long>(ws, bl.flags16) : nullptr;
     if (!x_res)
-        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec, nullptr, by_flags ? at<float>(ws, h.nbr_sp) : nullptr,
-                                flags));
+        S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec, nullptr,
+                                by_flags ? at<float>(ws, wagg ? h.nbr_spw : h.nbr_sp) : nullptr, flags));
     NodeInfo ninfo = make_nodeinfo(sc.rec, S, x_res != nullptr);
     ninfo.flags16 = reinterpret_cast<const unsigned short *>(flags);
     S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part,

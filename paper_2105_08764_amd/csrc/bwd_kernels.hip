@@ -315,7 +315,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
     float4 fx4 = make_float4(0.f, 0.f, 0.f, 0.f), fp4 = fx4, fn4 = fx4;
     // FLAGS: that round works from flag words and the rows' totals (see gather_node_tile_flags_grad); its
     // sums are kept per column lane % P
-    static_assert(!FLAGS || (FUSE && !W && !NEG), "flag words: plain neighbour sum, no negative weight");
+    static_assert(!FLAGS || (FUSE && !NEG), "flag words: no negative weight");
     float fxj = 0.f, fpj = 0.f, t1j = 0.f, qpj = 0.f;
     if (FLAGS) {
         t1j = ff.theta1[lane % P];
@@ -512,8 +512,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                         cp16[st] = hb[(2 * (size_t)S + st) * P];
                     }
                 } else {
-                    gather_node_tile_flags_grad<P>(tile_a, cx16, cp16, ni, s0f, t1j, qpj, colidx, bf, ef, lane,
-                                                   ni.node(vf)[ni.sn_off + 1]);
+                    gather_node_tile_flags_grad<P, W>(tile_a, cx16, cp16, ni, s0f, t1j, qpj, colidx, bf, ef, lane,
+                                                      ni.node(vf)[ni.sn_off + 1], wagg);
                 }
             } else if (ef - bf > kHubDegree) {
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, vf);
@@ -669,8 +669,8 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
     do {                                                                                       \
         if (NODE && !MASK && do_fuse) {                                                        \
             if (neg) S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, (NODE && !MASK), true);              \
-            else if (!WW && ni.flags16)                                                        \
-                k_bwd_round<PP, NODE, MASK, false, (NODE && !MASK), false, (NODE && !MASK && !WW)>  \
+            else if (ni.flags16)                                                               \
+                k_bwd_round<PP, NODE, MASK, WW, (NODE && !MASK), false, (NODE && !MASK)>           \
                     <<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, dz_in, maskT, sc.dg,   \
                                                     sc.glo, sc.ghi, mu_prev, dz_out, ni, theta2, dc_part, d2_part, ht,    \
                                                     hub_sum, ff);                                                         \

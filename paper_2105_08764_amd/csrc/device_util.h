@@ -254,12 +254,16 @@ __device__ __forceinline__ float4 gather_row_sum_mu1_single(const float *__restr
 // Rows with more than 64 entries continue in 64-entry chunks; rows longer than max_len are skipped
 // (their sums are already in the tile).  rb / re: lane i (mod 16) holds begin / end of tile row i.
 // The result of row i goes to tile[i * STRIDE + column].  lc = {theta1, q+, q-} in LDS ([3][P]).
-template <int P, int MODE>
+// W (mode 2 only): the weighted neighbour sum; the row's total is then the weighted one, and a flagged
+// neighbour's edge weight is read next to its column index.
+template <int P, int MODE, bool W = false>
 __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float *__restrict__ rec,
                                                        const float *__restrict__ compact,
                                                        const unsigned *__restrict__ xbits, const float *lc,
                                                        const int *__restrict__ colidx, int rb, int re, int max_len,
-                                                       int lane, float total_mine = 0.f) {
+                                                       int lane, float total_mine = 0.f,
+                                                       const float *__restrict__ wagg = nullptr) {
+    static_assert(!W || MODE == 2, "only the flag-bit form has a weighted variant here");
     // total_mine (mode 2): lane i (mod 16) holds the total of s+ over all neighbours of tile row i
     constexpr int STRIDE = Geo<P>::STRIDE;
     const int j = lane % P;
@@ -296,6 +300,7 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
             cols[k] = (n <= max_len && lane < n) ? colidx[b + lane] : -1;   // lane < n <= 64 entries of the first chunk
         }
         float rx[8], rs[8], rn[8];
+        float rw[W ? 8 : 1];   // edge weights of the flagged neighbours
         if (MODE == 1) {
             // all eight table loads first, then the record loads of the lanes that need one
             float c[8];
@@ -316,9 +321,11 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 rx[k] = 0.f; rs[k] = 0.f; rn[k] = 0.f;
+                if (W) rw[W ? k : 0] = 0.f;
                 if ((wd[k] >> (cols[k] & 31)) & 1u) {
                     const float4 r = ld4(rec + (size_t)cols[k] * 4);
                     rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
+                    if (W) rw[W ? k : 0] = wagg[__builtin_amdgcn_readlane(rb, 8 * half + k) + lane];
                 }
             }
         } else {
@@ -333,6 +340,7 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
             float ssum = 0.f, acc = 0.f;
             float flagged_sp = 0.f;                            // mode 2: s+ of the flagged neighbours (wave-uniform)
             float x = rx[k], sp = rs[k], sn = rn[k];
+            float wl = W ? rw[W ? k : 0] : 1.f;
             int base = b;
             while (true) {
                 const bool cheap = x == 0.f && sn == 0.f;
@@ -342,12 +350,20 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
                     const int l = __ffsll((long long)todo) - 1;
                     todo &= todo - 1ull;
                     const float xl = readlane_f(x, l), pl = readlane_f(sp, l), nl = readlane_f(sn, l);
-                    acc += fmaxf(xl * t1 + pl * qp + nl * qn, 0.f);
-                    if (MODE == 2) flagged_sp += pl;
+                    const float m1 = fmaxf(xl * t1 + pl * qp + nl * qn, 0.f);
+                    if (W) {
+                        const float wk = readlane_f(wl, l);
+                        acc = fmaf(wk, m1, acc);
+                        flagged_sp = fmaf(wk, pl, flagged_sp);
+                    } else {
+                        acc += m1;
+                        if (MODE == 2) flagged_sp += pl;
+                    }
                 }
                 base += 64;
                 if (base >= e) break;                          // wave-uniform
                 fetch((base + lane < e) ? colidx[base + lane] : -1, x, sp, sn);
+                if (W) wl = (x != 0.f) ? wagg[base + lane] : 0.f;
             }
             if (MODE == 2) {
                 ssum = readlane_f(total_mine, i) - flagged_sp;
@@ -619,10 +635,10 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const NodeInfo &ni, 
 // flagged neighbours only are touched (their s+, and x in the flagged states), and each flagged pair costs
 // one p-wide vector operation (lane j = column j, one accumulator register per state).
 // b .. e: a row of at most kHubDegree entries.  lc = {theta1, q+, q-} in LDS.  Writes tile[s * STRIDE + j].
-template <int P>
+template <int P, bool W = false>
 __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeInfo &ni, int s0, const float *lc,
                                                        const int *__restrict__ colidx, int b, int e, int lane,
-                                                       float total) {
+                                                       float total, const float *__restrict__ wagg = nullptr) {
     constexpr int STRIDE = Geo<P>::STRIDE;
     const int j = lane % P;
     const float t1 = lc[j], qp = lc[P + j];
@@ -637,6 +653,8 @@ __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeIn
         if (__ballot(f != 0u) == 0ull) continue;                     // wave-uniform
         const float *r = ni.node(u >= 0 ? u : 0);
         const float sp = f != 0u ? r[ni.sp_off] : 0.f;
+        float wl = 1.f;
+        if (W) wl = f != 0u ? wagg[base + lane] : 0.f;
         float xs[16];
 #pragma unroll
         for (int s = 0; s < 16; ++s) xs[s] = ((f >> s) & 1u) ? r[s0 + s] : 0.f;
@@ -647,7 +665,9 @@ __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeIn
                 const int l = __ffsll((long long)todo) - 1;
                 todo &= todo - 1ull;
                 const float xl = readlane_f(xs[s], l), pl = readlane_f(sp, l);
-                acc[s] += fmaxf(fmaf(xl, t1, pl * qp), 0.f) - pl * rp;
+                const float d = fmaxf(fmaf(xl, t1, pl * qp), 0.f) - pl * rp;
+                if (W) acc[s] = fmaf(readlane_f(wl, l), d, acc[s]);
+                else acc[s] += d;
             }
         }
     }
@@ -665,11 +685,11 @@ __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeIn
 //   cp = total [q+ > 0]   + sum over flagged (u, s) of s+_u ([z > 0] - [q+ > 0]),      z = x_{u,s} theta1 + s+_u q+
 // (z is formed exactly as in gather_node_tile_flags, so forward and backward agree on every relu).
 // a goes to tile_a[s * STRIDE + j]; cx and cp come back in registers (index = state).
-template <int P>
+template <int P, bool W = false>
 __device__ __forceinline__ void gather_node_tile_flags_grad(float *tile_a, float (&cx)[16], float (&cp)[16],
                                                             const NodeInfo &ni, int s0, float t1, float qp,
                                                             const int *__restrict__ colidx, int b, int e, int lane,
-                                                            float total) {
+                                                            float total, const float *__restrict__ wagg = nullptr) {
     constexpr int STRIDE = Geo<P>::STRIDE;
     const float rp = fmaxf(qp, 0.f);
     const float mq = qp > 0.f ? 1.f : 0.f;
@@ -683,6 +703,8 @@ __device__ __forceinline__ void gather_node_tile_flags_grad(float *tile_a, float
         if (__ballot(f != 0u) == 0ull) continue;                     // wave-uniform
         const float *r = ni.node(u >= 0 ? u : 0);
         const float sp = f != 0u ? r[ni.sp_off] : 0.f;
+        float wl = 1.f;
+        if (W) wl = f != 0u ? wagg[base + lane] : 0.f;
         float xs[16];
 #pragma unroll
         for (int s = 0; s < 16; ++s) xs[s] = ((f >> s) & 1u) ? r[s0 + s] : 0.f;
@@ -695,9 +717,10 @@ __device__ __forceinline__ void gather_node_tile_flags_grad(float *tile_a, float
                 const float xl = readlane_f(xs[s], l), pl = readlane_f(sp, l);
                 const float z = fmaf(xl, t1, pl * qp);
                 const float m = z > 0.f ? 1.f : 0.f;
-                a[s] += fmaxf(z, 0.f) - pl * rp;
-                cx[s] = fmaf(xl, m, cx[s]);
-                cp[s] = fmaf(pl, m - mq, cp[s]);
+                const float wk = W ? readlane_f(wl, l) : 1.f;
+                a[s] = fmaf(wk, fmaxf(z, 0.f) - pl * rp, a[s]);
+                cx[s] = fmaf(wk * xl, m, cx[s]);
+                cp[s] = fmaf(wk * pl, m - mq, cp[s]);
             }
         }
     }

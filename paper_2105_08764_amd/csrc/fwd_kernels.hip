@@ -46,20 +46,27 @@ hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const 
 __global__ __launch_bounds__(256) void k_prepare_nbr(int N, const int32_t *__restrict__ rowptr,
                                                      const int32_t *__restrict__ rowend,
                                                      const int32_t *__restrict__ colidx,
-                                                     const float *__restrict__ s_pos, float *__restrict__ nbr_sp) {
+                                                     const float *__restrict__ w,
+                                                     const float *__restrict__ s_pos, float *__restrict__ nbr_sp,
+                                                     float *__restrict__ nbr_spw) {
     for (int v = blockIdx.x * blockDim.x + threadIdx.x; v < N; v += gridDim.x * blockDim.x) {
         const int b = rowptr[v], e = rowend[v];
-        double a = 0.0;
+        double a = 0.0, aw = 0.0;   // aw: each neighbour weighted by its edge (the weighted neighbour sum)
         if (e - b <= kHubDegree)
-            for (int j = b; j < e; ++j) a += (double)s_pos[colidx[j]];
+            for (int j = b; j < e; ++j) {
+                const double sp = (double)s_pos[colidx[j]];
+                a += sp;
+                if (w) aw += (double)w[j] * sp;
+            }
         nbr_sp[v] = (float)a;
+        nbr_spw[v] = w ? (float)aw : (float)a;
     }
 }
 
 hipError_t launch_prepare_nbr(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const int32_t *colidx,
-                              const float *s_pos, float *nbr_sp) {
+                              const float *w, const float *s_pos, float *nbr_sp, float *nbr_spw) {
     if (N == 0) return hipSuccess;
-    k_prepare_nbr<<<min((N + 255) / 256, 65536), 256, 0, st>>>(N, rowptr, rowend, colidx, s_pos, nbr_sp);
+    k_prepare_nbr<<<min((N + 255) / 256, 65536), 256, 0, st>>>(N, rowptr, rowend, colidx, w, s_pos, nbr_sp, nbr_spw);
     return hipGetLastError();
 }
 
@@ -430,10 +437,10 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
                 const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
                 acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
                 store_node_block<P>(tile, acc, lane);
-            } else if (MU1 && !W && info.flags16) {
+            } else if (MU1 && info.flags16) {
                 // flag words and the row's total instead of the neighbours' records
-                gather_node_tile_flags<P>(tile, info, s0, lds_c, colidx, b, e, lane,
-                                          info.node(__builtin_amdgcn_readfirstlane(v))[info.sn_off + 1]);
+                gather_node_tile_flags<P, W>(tile, info, s0, lds_c, colidx, b, e, lane,
+                                             info.node(__builtin_amdgcn_readfirstlane(v))[info.sn_off + 1], wagg);
             } else if (MU1) {
                 // the gather from the records works in the state-major lane layout
                 acc = gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane,
@@ -457,11 +464,12 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
                     if (hi >= 0) st4(tile + i * G::STRIDE + 4 * li, ld4(hub_sum + ((size_t)hi * S + si) * P + 4 * li));
                 }
             }
-            if (MU1 && !W && S == 1) {
+            if (MU1 && S == 1 && (!W || info.xbits)) {
                 // single state, round 2: one lane per neighbour, the whole tile's records in flight
                 if (info.xbits)
-                    gather_tile_mu1_single<P, 2>(tile, info.base, nullptr, info.xbits, lds_c, colidx, rb, re, kHubDegree, lane,
-                                                 valid ? info.base[(size_t)v * 4 + 3] : 0.f);
+                    gather_tile_mu1_single<P, 2, W>(tile, info.base, nullptr, info.xbits, lds_c, colidx, rb, re, kHubDegree,
+                                                    lane, valid ? info.base[(size_t)v * 4 + 3] : 0.f, wagg);
+                else if (W) {}
                 else if (info.compact)
                     gather_tile_mu1_single<P, 1>(tile, info.base, info.compact, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
                 else

@@ -125,8 +125,9 @@ hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const f
                            unsigned long long *xbits = nullptr /*S == 1: [ceil(N/64)], bit v = (x_v != 0);
                                                                  S % 16 == 0: [N][S/16] 16-bit words, see NodeInfo::flags16*/);
 // nbr_sp[v] = sum of s_pos over the live entries of row v (0 for rows longer than kHubDegree, which never use it)
+// nbr_spw: the same with each neighbour weighted by its edge weight (w == NULL: equal to nbr_sp)
 hipError_t launch_prepare_nbr(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const int32_t *colidx,
-                              const float *s_pos, float *nbr_sp);
+                              const float *w, const float *s_pos, float *nbr_sp, float *nbr_spw);
 // Neighbour sums of the hub rows: hub_sum[h][S][p] = sum over the row of hub h of src[u][s][:]
 // (mask != NULL: counts of set relu-mask bits instead; else src == NULL: the round-1 rows
 // recomputed from info).  partial is [n_segs][S][p] scratch.
