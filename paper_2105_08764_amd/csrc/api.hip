@@ -757,9 +757,10 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     const float *wagg = g->weighted_sum ? g->w : nullptr;   // NULL weights mean w = 1: the plain sum
     if (x_res)
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, sc.rec, nullptr));
-    // (node mode on a static graph without negative weights: the last reversed round, done inside the round
-    //  t = 3, works from flag words and the rows' totals of s+ like the forward's round 2)
-    const bool by_flags = S % 16 == 0 && T >= 4 && !pr->has_neg && !g->row_end && !x_res;
+    // (node mode on a static graph without negative weights: the last reversed round -- done inside the round
+    //  t = 3, or by k_bwd_first when T = 3 -- works from flag words and the rows' totals of s+ like the
+    //  forward's round 2)
+    const bool by_flags = S % 16 == 0 && T >= 3 && !pr->has_neg && !g->row_end && !x_res;
     unsigned long long *flags = by_flags ? at<unsigned long long>(ws, bl.flags16) : nullptr;
     if (!x_res)
         S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, sc.rec, nullptr,

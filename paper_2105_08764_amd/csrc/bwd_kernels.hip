@@ -712,7 +712,9 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 // A wave owns one node's 16-state block at a time; hub_sum4 holds the four sums of the long rows
 // as [hub][4][S][P].
 // ------------------------------------------------------------------------------------------
-template <int P, bool W, bool NEG>
+// FLAGS: the four sums come from flag words and the rows' totals (gather_node_tile_flags_grad) instead of the
+// neighbours' records; they are then held per column (lane % P), not in the state-major layout.
+template <int P, bool W, bool NEG, bool FLAGS = false>
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
     int n_vrows, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in,
@@ -723,9 +725,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
     constexpr int CB = Ge::CB, STRIDE = Ge::STRIDE, LPR = Ge::LPR, RPI = Ge::NPL, NC = 16 / RPI;
     constexpr int TILE_F = kTileRows * STRIDE;
     static_assert(2 * kWaves * TILE_F >= kWaves * 16 * P, "tile area is reused for the final reductions");
+    static_assert(!FLAGS || !NEG, "flag words: no negative weight");
     __shared__ __attribute__((aligned(16))) float lds[2 * kWaves * TILE_F];   // per wave: dz^2 tile, a tile
     __shared__ __attribute__((aligned(16))) float lds_b[P * STRIDE];          // theta2^T: B operand of dz theta2
-    __shared__ __attribute__((aligned(16))) float rec_stage[kWaves * kRecStageFloats];   // staging of the record gather
+    __shared__ __attribute__((aligned(16))) float rec_stage[FLAGS ? 4 : kWaves * kRecStageFloats];   // staging of the record gather
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float *tile_d = lds + wave * 2 * TILE_F, *tile_a = tile_d + TILE_F;
     const int li = lane % LPR;
@@ -740,6 +743,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
 #pragma unroll
         for (int jb = 0; jb < CB; ++jb) d2acc[ib][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float4 cx4 = make_float4(0.f, 0.f, 0.f, 0.f), cp4 = cx4, cn4 = cx4;
+    float fxj = 0.f, fpj = 0.f, t1j = 0.f, qpj = 0.f;   // FLAGS: sums and constants of column lane % P
+    if (FLAGS) {
+        t1j = theta1[lane % P];
+        qpj = qvec[lane % P];
+    }
 
     const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
@@ -753,7 +761,22 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
         store_node_block<P>(tile_d, dz, lane);
 
         NodeAcc4<P> g4;
-        if (e - b > kHubDegree) {
+        float cx16[FLAGS ? 16 : 1], cp16[FLAGS ? 16 : 1];
+        if constexpr (FLAGS) {
+            if (e - b > kHubDegree) {
+                const int h = hub_index(ht.hub_rows, ht.n_hubs, v);
+                const float *hb = hub_sum4 + ((size_t)h * 4 * S + s0) * P + (lane % P);
+#pragma unroll
+                for (int st = 0; st < 16; ++st) {
+                    if (lane < P) tile_a[st * STRIDE + lane] = hb[(size_t)st * P];
+                    cx16[st] = hb[((size_t)S + st) * P];
+                    cp16[st] = hb[(2 * (size_t)S + st) * P];
+                }
+            } else {
+                gather_node_tile_flags_grad<P, W>(tile_a, cx16, cp16, ni, s0, t1j, qpj, colidx, b, e, lane,
+                                                  ni.node(v)[ni.sn_off + 1], wagg);
+            }
+        } else if (e - b > kHubDegree) {
             const int h = hub_index(ht.hub_rows, ht.n_hubs, v);
             const float *hb = hub_sum4 + ((size_t)h * 4 * S + s0) * P;
             g4.a = load_node_block_sm<P>(hb, lane);
@@ -762,9 +785,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
             g4.cn = load_node_block_sm<P>(hb + 3 * (size_t)S * P, lane);
         } else {
             g4 = gather_node_block_mu1_grad<P, W, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane,
-                                                       rec_stage + wave * kRecStageFloats);
+                                                       rec_stage + (FLAGS ? 0 : wave * kRecStageFloats));
         }
-        store_node_block_sm<P>(tile_a, g4.a, lane);   // the four sums live in the state-major lane layout
+        if constexpr (!FLAGS) store_node_block_sm<P>(tile_a, g4.a, lane);   // the four sums live in the state-major lane layout
         __builtin_amdgcn_wave_barrier();
 
         // e = dz^2 theta2 (row r, column j: sum_k dz^2[r][k] theta2[k][j])
@@ -799,6 +822,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) tile_d[(4 * gl + rr) * STRIDE + 16 * cb + jl] = acc[cb][rr];
         __builtin_amdgcn_wave_barrier();
+        if constexpr (FLAGS) {
+            if (lane < P) {
+#pragma unroll
+                for (int st = 0; st < 16; ++st) {
+                    const float ev = tile_d[st * STRIDE + lane];
+                    fxj = fmaf(ev, cx16[st], fxj);
+                    fpj = fmaf(ev, cp16[st], fpj);
+                }
+            }
+        } else
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const float4 e4 = ld4(tile_d + (NC * (lane / LPR) + c) * STRIDE + 4 * li);
@@ -837,7 +870,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
         cp4.x += __shfl_xor(cp4.x, m); cp4.y += __shfl_xor(cp4.y, m); cp4.z += __shfl_xor(cp4.z, m); cp4.w += __shfl_xor(cp4.w, m);
         cn4.x += __shfl_xor(cn4.x, m); cn4.y += __shfl_xor(cn4.y, m); cn4.z += __shfl_xor(cn4.z, m); cn4.w += __shfl_xor(cn4.w, m);
     }
-    if (lane < LPR) {
+    if (FLAGS) {
+        if (lane < P) {
+            lds[(wave * 3 + 0) * P + lane] = fxj;
+            lds[(wave * 3 + 1) * P + lane] = fpj;
+            lds[(wave * 3 + 2) * P + lane] = 0.f;
+        }
+    } else if (lane < LPR) {
         st4(lds + (wave * 3 + 0) * P + 4 * lane, cx4);
         st4(lds + (wave * 3 + 1) * P + 4 * lane, cp4);
         st4(lds + (wave * 3 + 2) * P + 4 * lane, cn4);
@@ -857,8 +896,15 @@ hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *
 #define S2V_LAUNCH_FIRST(PP, WW, NN)                                                                              \
     k_bwd_first<PP, WW, NN><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, dz_in, ni,  \
                                                            theta1, theta2, qvec, dc_part, d2_part, ht, hub_sum4)
-#define S2V_LAUNCH_FIRST_N(PP, WW) \
-    do { if (has_neg) S2V_LAUNCH_FIRST(PP, WW, true); else S2V_LAUNCH_FIRST(PP, WW, false); } while (0)
+#define S2V_LAUNCH_FIRST_N(PP, WW)                                                                                   \
+    do {                                                                                                             \
+        if (has_neg) S2V_LAUNCH_FIRST(PP, WW, true);                                                                 \
+        else if (ni.flags16)                                                                                         \
+            k_bwd_first<PP, WW, false, true><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, \
+                                                                            dz_in, ni, theta1, theta2, qvec, dc_part, \
+                                                                            d2_part, ht, hub_sum4);                   \
+        else S2V_LAUNCH_FIRST(PP, WW, false);                                                                        \
+    } while (0)
 #define S2V_LAUNCH_FIRST_W(PP) \
     do { if (wagg) S2V_LAUNCH_FIRST_N(PP, true); else S2V_LAUNCH_FIRST_N(PP, false); } while (0)
     if (p == 32) S2V_LAUNCH_FIRST_W(32); else S2V_LAUNCH_FIRST_W(64);
