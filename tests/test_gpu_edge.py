@@ -224,3 +224,45 @@ def test_hub_rows_of_every_kind(oracle_mod):
         assert gu.rel_err(qp, oqp) <= 1e-4 and abs(loss - oloss) <= 1e-4 * abs(oloss)
         for name in si.THETA_NAMES:
             assert gu.rel_err(grads[name], ograds[name], whole=True) <= 1e-4, (S, name)
+
+
+@pytest.mark.parametrize("S,p,T", [(1, 64, 3), (1, 32, 2), (16, 64, 4), (16, 32, 3), (5, 32, 3)])
+def test_row_lengths_around_the_long_row_and_segment_limits(oracle_mod, S, p, T):
+    # One graph made of stars whose centres have 255, 256, 257 entries (the long-row threshold is 256),
+    # 511, 512, 513 (one segment holds 512) and 1025 (three segments), plus a sparse part: forward through
+    # the single-call policy evaluation and one training iteration, unit weights (flag-bit forms) and
+    # signed weights (record forms).
+    import torch
+
+    print(f"case row lengths S={S} p={p} T={T}", flush=True)
+    parts = [si.star_graph(n) for n in (255, 256, 257, 511, 512, 513, 1025)] + [si.erdos_renyi_gnp(90, 0.1, 4)]
+    b = si.block_diagonal(parts)
+    centres = b.graph_off[:-2]
+    for signed in (False, True):
+        g = si.Graph(b.n, b.rowptr, b.colidx, None, None)
+        if signed:
+            g.w = si.signed_edge_weights(g, 6, 1.0)
+        assert sorted(np.diff(g.rowptr)[centres].tolist()) == [255, 256, 257, 511, 512, 513, 1025]
+        theta = si.thetas(p, 31 + p + T, 0.01)
+        x = si.node_flags(g.n, 0.2, 3, n_states=S)
+        x[:, centres[2]] = 0
+        action, target = si.training_batch(x, 9)
+        action[0] = centres[2]                      # the 257-entry row is an action node
+        dev = gu.Device(g, p, T, S=S, training=True)
+        xd = torch.from_numpy(x).cuda()
+        mu = torch.full((g.n, S, p), float("nan"), device="cuda")
+        gsum = torch.full((S, 1, p), float("nan"), device="cuda")
+        q = torch.full((S, g.n), float("nan"), device="cuda")
+        dev.ctx.s2v_policy_eval(dev.graph, dev.params(theta), xd, T, S, mu, gsum, q, dev.ws)
+        torch.cuda.synchronize()
+        mu, gsum, q = mu.cpu().numpy(), gsum.cpu().numpy(), q.cpu().numpy()
+        for s_ in range(S):
+            omu, ogs, oq = gu.oracle_forward(oracle_mod, g, theta, x[s_], T)
+            assert gu.rel_err(mu[:, s_, :], omu) <= 1e-4
+            assert gu.rel_err(gsum[s_], ogs) <= 1e-4
+            assert gu.rel_err(q[s_], oq, scale=gu.q_term_scale(theta, ogs[0], omu)) <= 1e-4
+        loss, qp, grads, _ = dev.loss_grad(dev.params(theta), x, action, target)
+        oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, None, theta, x, T, action, target)
+        assert abs(loss - oloss) <= 1e-4 * abs(oloss)
+        for name in si.THETA_NAMES:
+            assert gu.rel_err(grads[name], ograds[name], whole=True) <= 1e-4, (signed, name)
