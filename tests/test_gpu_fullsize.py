@@ -97,3 +97,32 @@ def test_config5_full_training(oracle_mod):
     errs = {k: gu.rel_err(g1[k], ograds[k], whole=True) for k in g1}
     print("S=1 gradient vs oracle:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     assert max(errs.values()) <= TOL
+
+
+@pytest.mark.timeout(900)
+def test_matrices_beyond_2_31_elements(oracle_mod):
+    # 4 M nodes x 16 states x 64 columns = 4.3e9 floats (16 GB) per embedding matrix: element offsets no
+    # longer fit 32 bits, and the matrix is large enough for the state-by-state row order.  Two of the 16
+    # states are checked in full against the oracle.
+    import torch
+
+    n, p, T, S = 4_000_000, 64, 3, 16
+    g = si.erdos_renyi_gnm(n, 15 * n, 77)
+    g.w = si.symmetric_edge_weights(g, 5, 0.5, 1.5)
+    print(f"big: n={g.n} nnz={g.nnz} S={S}", flush=True)
+    theta = si.thetas(p, 3, 0.05)
+    x = si.node_flags(g.n, 0.05, 7, n_states=S)
+    dev = gu.Device(g, p, T, S=S)
+    xd = torch.from_numpy(x).cuda()
+    mu = torch.empty((g.n, S, p), device="cuda")
+    gsum = torch.empty((S, 1, p), device="cuda")
+    q = torch.empty((S, g.n), device="cuda")
+    dev.ctx.s2v_policy_eval(dev.graph, dev.params(theta), xd, T, S, mu, gsum, q, dev.ws)
+    torch.cuda.synchronize()
+    for b in (0, 15):
+        omu = oracle_mod.embed(g.rowptr, g.colidx, g.w, theta, x[b], T)
+        ogs, oq = oracle_mod.q_scores(None, theta, omu)
+        errs = (gu.rel_err(mu[:, b, :].cpu().numpy(), omu), gu.rel_err(gsum[b].cpu().numpy(), ogs),
+                gu.rel_err(q[b].cpu().numpy(), oq, scale=gu.q_term_scale(theta, ogs[0], omu)))
+        print(f"state {b}: errors {errs}", flush=True)
+        assert max(errs) <= TOL
