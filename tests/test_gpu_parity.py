@@ -303,6 +303,17 @@ def _run_config(oracle_mod, c, scale):
     errs = (gu.rel_err(out["mu"][:, 0, :], mu), gu.rel_err(out["gsum"][0], gsum), gu.rel_err(out["q"][0], q))
     print("rel errors mu/gsum/q:", errs, flush=True)
     assert max(errs) <= TOL
+    # the call that bench.py times (embedding and scores in one) must give the same bits at this size too
+    import torch
+
+    mu1 = torch.full((g.n, 1, w.p), float("nan"), device="cuda")
+    gs1 = torch.full((1, g.n_graphs, w.p), float("nan"), device="cuda")
+    q1 = torch.full((1, g.n), float("nan"), device="cuda")
+    dev.ctx.s2v_policy_eval(dev.graph, dev.last["prm"], dev.last["x"], w.T, 1, mu1, gs1, q1, dev.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(mu1.cpu().numpy(), out["mu"]) and np.array_equal(gs1.cpu().numpy(), out["gsum"])
+    assert np.array_equal(q1.cpu().numpy(), out["q"])
+    del mu1, gs1, q1
     # selection on the GPU's own float32 scores: bit-exact against the oracle's rule
     idx, val, cnt = dev.select(out["q"][0], w.x[0], None, w.k)
     oi, ov, oc = oracle_mod.select(g.graph_off, out["q"][0], w.x[0], None, w.k)
