@@ -289,19 +289,26 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
             x = r.x; sp = r.y; sn = r.z;
         }
     };
+    // Rows per pass: the loads of a pass (indices, then table entries, then the records that are needed) are
+    // issued together, so a pass costs three trips to memory whatever its size.  The flag-bit form keeps two
+    // registers less per row and takes the whole tile in one pass.
+#ifndef S2V_R2_ROWS
+#define S2V_R2_ROWS 16
+#endif
+    constexpr int RB = MODE == 2 ? S2V_R2_ROWS : 8;
 #pragma unroll 1
-    for (int half = 0; half < 2; ++half) {
-        int cols[8];
+    for (int half = 0; half < 16 / RB; ++half) {
+        int cols[RB];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int i = 8 * half + k;
+        for (int k = 0; k < RB; ++k) {
+            const int i = RB * half + k;
             // (i is wave-uniform: a lane read, not a shuffle through LDS)
             const int b = __builtin_amdgcn_readlane(rb, i), n = __builtin_amdgcn_readlane(re, i) - b;
             cols[k] = (n <= max_len && lane < n) ? colidx[b + lane] : -1;   // lane < n <= 64 entries of the first chunk
         }
-        float rx[8], rs[8], rn[8];
-        float rw[W ? 8 : 1];   // edge weights of the flagged neighbours
-        if (MODE == 1) {
+        float rx[RB], rs[RB], rn[MODE == 2 ? 1 : RB];
+        float rw[W ? RB : 1];   // edge weights of the flagged neighbours
+        if constexpr (MODE == 1) {
             // all eight table loads first, then the record loads of the lanes that need one
             float c[8];
 #pragma unroll
@@ -314,18 +321,18 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
                     rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
                 }
             }
-        } else if (MODE == 2) {
-            unsigned wd[8];
+        } else if constexpr (MODE == 2) {
+            unsigned wd[RB];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) wd[k] = cols[k] >= 0 ? xbits[cols[k] >> 5] : 0u;
+            for (int k = 0; k < RB; ++k) wd[k] = cols[k] >= 0 ? xbits[cols[k] >> 5] : 0u;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                rx[k] = 0.f; rs[k] = 0.f; rn[k] = 0.f;
+            for (int k = 0; k < RB; ++k) {
+                rx[k] = 0.f; rs[k] = 0.f;   // (no negative weights here: s- is zero and not kept)
                 if (W) rw[W ? k : 0] = 0.f;
                 if ((wd[k] >> (cols[k] & 31)) & 1u) {
-                    const float4 r = ld4(rec + (size_t)cols[k] * 4);
-                    rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
-                    if (W) rw[W ? k : 0] = wagg[__builtin_amdgcn_readlane(rb, 8 * half + k) + lane];
+                    const float2 r = *reinterpret_cast<const float2 *>(rec + (size_t)cols[k] * 4);
+                    rx[k] = r.x; rs[k] = r.y;
+                    if (W) rw[W ? k : 0] = wagg[__builtin_amdgcn_readlane(rb, RB * half + k) + lane];
                 }
             }
         } else {
@@ -333,13 +340,13 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
             for (int k = 0; k < 8; ++k) fetch(cols[k], rx[k], rs[k], rn[k]);
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int i = 8 * half + k;
+        for (int k = 0; k < RB; ++k) {
+            const int i = RB * half + k;
             const int b = __builtin_amdgcn_readlane(rb, i), e = __builtin_amdgcn_readlane(re, i);
             if (e - b > max_len) continue;                     // wave-uniform
             float ssum = 0.f, acc = 0.f;
             float flagged_sp = 0.f;                            // mode 2: s+ of the flagged neighbours (wave-uniform)
-            float x = rx[k], sp = rs[k], sn = rn[k];
+            float x = rx[k], sp = rs[k], sn = MODE == 2 ? 0.f : rn[MODE == 2 ? 0 : k];
             float wl = W ? rw[W ? k : 0] : 1.f;
             int base = b;
             while (true) {
