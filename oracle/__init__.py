@@ -7,7 +7,7 @@ float64 before the C code sees them.
 
 Functions mirror the C entry points: embed (Eq. 1 / Alg. 1), q_scores (Eq. 2 / Alg. 2),
 select (Alg. 3's argmax and the top-d selection of Sec. 4.5.1), loss_grad (the Train
-step of Alg. 4) and sgd (plain gradient descent, repeated as in Sec. 4.5.2).
+step of Alg. 4; loss_grad_decided: the same with relu decisions given by the caller) and sgd (plain gradient descent, repeated as in Sec. 4.5.2).
 """
 from __future__ import annotations
 
@@ -142,6 +142,50 @@ def loss_grad(rowptr, colidx, w, graph_off, theta: dict, x, T: int, action, targ
     )
     assert rc == 0, rc
     return float(loss[0]), qp, dict(zip(THETA_NAMES, grads))
+
+
+def loss_grad_decided(rowptr, colidx, w, graph_off, theta: dict, x, T: int, action, target, weighted: bool = False,
+                      force=None, force_head=None):
+    """loss_grad with some relu decisions taken by the caller, plus every pre-activation.
+
+    force: int8 [S][T][n][p] or None, force_head: int8 [S][2][p] or None; -1 = follow the sign of the
+    pre-activation, 0 / 1 = unit off / on (Eq. 1 units; Eq. 2 units: row 0 theta6 g, row 1 theta7 mu_action).
+    Returns (loss, q_pred, grads, info) with info = dict(z, zs [S][T][n][p], h, hs [S][2][p]): the
+    pre-activations and the summed magnitudes of their terms.  With no forced decision the first three
+    equal loss_grad's bit for bit."""
+    lib = _load()
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    n = rowptr.shape[0] - 1
+    th = _th(theta)
+    p = th[0].shape[0]
+    wd = None if w is None else _f64(w)
+    xd = _f64(x).reshape(-1, n)
+    S = xd.shape[0]
+    go = None if graph_off is None else _i32(graph_off)
+    G = 1 if go is None else go.shape[0] - 1
+    act = _i32(action)
+    tgt = _f64(target)
+    assert act.shape[0] == S and tgt.shape[0] == S
+    fo = None if force is None else np.ascontiguousarray(force, dtype=np.int8)
+    fh = None if force_head is None else np.ascontiguousarray(force_head, dtype=np.int8)
+    assert fo is None or fo.shape == (S, T, n, p)
+    assert fh is None or fh.shape == (S, 2, p)
+    loss = np.zeros(1, dtype=np.float64)
+    qp = np.zeros(S, dtype=np.float64)
+    grads = [np.zeros_like(t) for t in th]
+    z = np.zeros((S, T, n, p), dtype=np.float64)
+    zs = np.zeros((S, T, n, p), dtype=np.float64)
+    h = np.zeros((S, 2, p), dtype=np.float64)
+    hs = np.zeros((S, 2, p), dtype=np.float64)
+    rc = lib.oracle_loss_grad_decided(
+        ctypes.c_int32(n), _ptr(rowptr), _ptr(colidx), _ptr(wd), ctypes.c_int32(int(bool(weighted))),
+        ctypes.c_int32(G), _ptr(go),
+        ctypes.c_int32(p), ctypes.c_int32(T), *[_ptr(t) for t in th], ctypes.c_int32(S), _ptr(xd),
+        _ptr(act), _ptr(tgt), _ptr(loss), _ptr(qp), *[_ptr(g) for g in grads],
+        _ptr(fo), _ptr(fh), _ptr(z), _ptr(zs), _ptr(h), _ptr(hs),
+    )
+    assert rc == 0, rc
+    return float(loss[0]), qp, dict(zip(THETA_NAMES, grads)), dict(z=z, zs=zs, h=h, hs=hs)
 
 
 def sgd(theta: dict, grads: dict, lr: float) -> dict:

@@ -30,6 +30,12 @@
 
 static inline double relu(double v) { return v > 0.0 ? v : 0.0; }
 
+/* Whether a relu unit with pre-activation z passes its input.  d < 0: the definition (z > 0).
+ * d = 0 / 1: the caller decides (oracle_loss_grad_decided: a float32 evaluation cannot tell the sign of
+ * a pre-activation that lies within its own rounding of zero; a test may then ask for the gradient of
+ * the branch that evaluation took). */
+static inline int decided(double z, int d) { return d < 0 ? (z > 0.0) : (d != 0); }
+
 /* y[p] = M[p][p] * v[p] */
 static void matvec(int p, const double *M, const double *v, double *y) {
     for (int i = 0; i < p; ++i) {
@@ -55,10 +61,13 @@ static void matvec_t(int p, const double *M, const double *v, double *y) {
  * adjacency matrix that holds the weights): the second term becomes
  *   theta2 * sum_{u in N(v)} w(v,u) * mu[u].
  * If a_out / e_out are non-NULL the two neighbour sums are also stored ([n][p]).
+ * force (NULL: none) holds one decision per unit, see decided(); on_out receives the decisions taken,
+ * z_out the pre-activations and zs_out the summed magnitudes of their terms (each [n][p], optional).
  */
 static void embed_round(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int weighted, int p,
                         const double *th1, const double *th2, const double *th3, const double *th4,
-                        const double *x, const double *mu, double *mu_next, double *a_out, double *e_out) {
+                        const double *x, const double *mu, double *mu_next, double *a_out, double *e_out,
+                        const int8_t *force, uint8_t *on_out, double *z_out, double *zs_out) {
 #pragma omp parallel
     {
         double *a = (double *)malloc(sizeof(double) * 4 * (size_t)p);
@@ -77,7 +86,19 @@ static void embed_round(int32_t n, const int32_t *rowptr, const int32_t *colidx,
             }
             matvec(p, th2, a, t2);
             matvec(p, th3, e, t3);
-            for (int i = 0; i < p; ++i) mu_next[(size_t)v * p + i] = relu(th1[i] * x[v] + t2[i] + t3[i]);
+            for (int i = 0; i < p; ++i) {
+                const double z = th1[i] * x[v] + t2[i] + t3[i];
+                const int on = decided(z, force ? force[(size_t)v * p + i] : -1);
+                mu_next[(size_t)v * p + i] = on ? z : 0.0;
+                if (on_out) on_out[(size_t)v * p + i] = (uint8_t)on;
+                if (z_out) z_out[(size_t)v * p + i] = z;
+                if (zs_out) {
+                    /* magnitude of what was summed into z: |theta1 x| + sum_j |theta2_ij a_j| + sum_j |theta3_ij e_j| */
+                    double s = fabs(th1[i] * x[v]);
+                    for (int j = 0; j < p; ++j) s += fabs(th2[(size_t)i * p + j] * a[j]) + fabs(th3[(size_t)i * p + j] * e[j]);
+                    zs_out[(size_t)v * p + i] = s;
+                }
+            }
             if (a_out) memcpy(a_out + (size_t)v * p, a, sizeof(double) * p);
             if (e_out) memcpy(e_out + (size_t)v * p, e, sizeof(double) * p);
         }
@@ -98,7 +119,8 @@ int oracle_embed(int32_t n, const int32_t *rowptr, const int32_t *colidx, const 
     double *nxt = (double *)calloc(np_ ? np_ : 1, sizeof(double));
     if (!cur || !nxt) { free(cur); free(nxt); return -1; }
     for (int t = 0; t < T; ++t) {
-        embed_round(n, rowptr, colidx, w, weighted, p, th1, th2, th3, th4, x, cur, nxt, NULL, NULL);
+        embed_round(n, rowptr, colidx, w, weighted, p, th1, th2, th3, th4, x, cur, nxt, NULL, NULL, NULL, NULL, NULL,
+                    NULL);
         if (mu_hist) memcpy(mu_hist + (size_t)t * np_, nxt, sizeof(double) * np_);
         double *tmp = cur; cur = nxt; nxt = tmp;
     }
@@ -207,13 +229,16 @@ static void csr_transpose(int32_t n, const int32_t *rowptr, const int32_t *colid
  * Outputs: loss_out[1], q_out[S] (the predicted Q of each action), and d1..d7 with
  * the shapes of theta1..theta7 (overwritten).
  */
-int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int32_t weighted,
-                     int32_t G,
-                     const int32_t *graph_off, int32_t p, int32_t T, const double *th1, const double *th2,
-                     const double *th3, const double *th4, const double *th5, const double *th6,
-                     const double *th7, int32_t S, const double *x, const int32_t *action,
-                     const double *target, double *loss_out, double *q_out, double *d1, double *d2,
-                     double *d3, double *d4, double *d5, double *d6, double *d7) {
+static int loss_grad_impl(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int32_t weighted,
+                          int32_t G,
+                          const int32_t *graph_off, int32_t p, int32_t T, const double *th1, const double *th2,
+                          const double *th3, const double *th4, const double *th5, const double *th6,
+                          const double *th7, int32_t S, const double *x, const int32_t *action,
+                          const double *target, double *loss_out, double *q_out, double *d1, double *d2,
+                          double *d3, double *d4, double *d5, double *d6, double *d7,
+                          const int8_t *force /*[S][T][n][p]*/, const int8_t *force_head /*[S][2][p]*/,
+                          double *z_out /*[S][T][n][p]*/, double *zs_out /*[S][T][n][p]*/,
+                          double *h_out /*[S][2][p]*/, double *hs_out /*[S][2][p]*/) {
     int32_t one[2] = {0, n};
     if (!graph_off) { graph_off = one; G = 1; }
     size_t np_ = (size_t)n * p, pp = (size_t)p * p;
@@ -235,17 +260,22 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
     double *esum = (double *)malloc(sizeof(double) * (np_ + 1));
     double *dmu = (double *)malloc(sizeof(double) * (np_ + 1));
     double *da = (double *)malloc(sizeof(double) * (np_ + 1));
+    /* the decision of every relu unit of rounds 1..T (index t * n * p as for mu) */
+    uint8_t *on = (uint8_t *)malloc((size_t)(T + 1) * np_ + 1);
     double *vec = (double *)malloc(sizeof(double) * 8 * (size_t)p);
     double *g = vec, *h1 = g + p, *h2 = h1 + p, *dh1 = h2 + p, *dh2 = dh1 + p, *dg = dh2 + p, *tmp = dg + p;
-    if (!mu || !asum || !esum || !dmu || !da || !vec || !rowptr_t || !colidx_t) return -1;
+    if (!mu || !asum || !esum || !dmu || !da || !vec || !on || !rowptr_t || !colidx_t) return -1;
 
     double loss = 0.0;
     for (int32_t b = 0; b < S; ++b) {
         const double *xb = x + (size_t)b * n;
         memset(mu, 0, sizeof(double) * np_);
-        for (int t = 1; t <= T; ++t)
+        for (int t = 1; t <= T; ++t) {
+            const size_t at = ((size_t)b * T + (size_t)(t - 1)) * np_;   /* this (state, round) in the optional arrays */
             embed_round(n, rowptr, colidx, w, weighted, p, th1, th2, th3, th4, xb, mu + (size_t)(t - 1) * np_,
-                        mu + (size_t)t * np_, asum + (size_t)t * np_, esum);
+                        mu + (size_t)t * np_, asum + (size_t)t * np_, esum, force ? force + at : NULL,
+                        on + (size_t)t * np_, z_out ? z_out + at : NULL, zs_out ? zs_out + at : NULL);
+        }
         const double *muT = mu + (size_t)T * np_;
         int32_t act = action[b];
         int32_t gb = 0;
@@ -259,8 +289,23 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
             for (int i = 0; i < p; ++i) g[i] += muT[(size_t)v * p + i];
         matvec(p, th6, g, h1);
         matvec(p, th7, muT + (size_t)act * p, h2);
+        /* decisions of the 2p relu units of Eq. (2) (p <= 128, checked by the entry points) */
+        int on1[128], on2[128];
+        for (int i = 0; i < p; ++i) {
+            on1[i] = decided(h1[i], force_head ? force_head[((size_t)b * 2) * p + i] : -1);
+            on2[i] = decided(h2[i], force_head ? force_head[((size_t)b * 2 + 1) * p + i] : -1);
+            if (h_out) { h_out[((size_t)b * 2) * p + i] = h1[i]; h_out[((size_t)b * 2 + 1) * p + i] = h2[i]; }
+            if (hs_out) {
+                double s1 = 0.0, s2 = 0.0;
+                for (int j = 0; j < p; ++j) {
+                    s1 += fabs(th6[(size_t)i * p + j] * g[j]);
+                    s2 += fabs(th7[(size_t)i * p + j] * muT[(size_t)act * p + j]);
+                }
+                hs_out[((size_t)b * 2) * p + i] = s1; hs_out[((size_t)b * 2 + 1) * p + i] = s2;
+            }
+        }
         double q = 0.0;
-        for (int i = 0; i < p; ++i) q += th5[i] * relu(h1[i]) + th5[p + i] * relu(h2[i]);
+        for (int i = 0; i < p; ++i) q += th5[i] * (on1[i] ? h1[i] : 0.0) + th5[p + i] * (on2[i] ? h2[i] : 0.0);
         q_out[b] = q;
         double diff = q - target[b];
         loss += diff * diff / S;
@@ -268,10 +313,10 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
 
         /* Q-head backward */
         for (int i = 0; i < p; ++i) {
-            d5[i] += dq * relu(h1[i]);
-            d5[p + i] += dq * relu(h2[i]);
-            dh1[i] = h1[i] > 0.0 ? dq * th5[i] : 0.0;
-            dh2[i] = h2[i] > 0.0 ? dq * th5[p + i] : 0.0;
+            d5[i] += dq * (on1[i] ? h1[i] : 0.0);
+            d5[p + i] += dq * (on2[i] ? h2[i] : 0.0);
+            dh1[i] = on1[i] ? dq * th5[i] : 0.0;
+            dh2[i] = on2[i] ? dq * th5[p + i] : 0.0;
         }
         for (int i = 0; i < p; ++i)
             for (int j = 0; j < p; ++j) {
@@ -287,7 +332,7 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
 
         /* rounds T..1 of Eq. (1), reversed */
         for (int t = T; t >= 1; --t) {
-            const double *mut = mu + (size_t)t * np_;
+            const uint8_t *ont = on + (size_t)t * np_;
             const double *at = asum + (size_t)t * np_;
 #pragma omp parallel
             {
@@ -299,7 +344,7 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
                     double *dz = dmu + (size_t)v * p; /* becomes d(pre-activation) in place */
                     int any = 0;
                     for (int i = 0; i < p; ++i) {
-                        if (!(mut[(size_t)v * p + i] > 0.0)) dz[i] = 0.0;
+                        if (!ont[(size_t)v * p + i]) dz[i] = 0.0;
                         any |= dz[i] != 0.0;
                     }
                     double *dav = da + (size_t)v * p;
@@ -346,8 +391,48 @@ int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, co
         }
     }
     *loss_out = loss;
-    free(mu); free(asum); free(esum); free(dmu); free(da); free(vec); free(rowptr_t); free(colidx_t); free(w_t);
+    free(mu); free(asum); free(esum); free(dmu); free(da); free(vec); free(on); free(rowptr_t); free(colidx_t); free(w_t);
     return 0;
+}
+
+int oracle_loss_grad(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w, int32_t weighted,
+                     int32_t G,
+                     const int32_t *graph_off, int32_t p, int32_t T, const double *th1, const double *th2,
+                     const double *th3, const double *th4, const double *th5, const double *th6,
+                     const double *th7, int32_t S, const double *x, const int32_t *action,
+                     const double *target, double *loss_out, double *q_out, double *d1, double *d2,
+                     double *d3, double *d4, double *d5, double *d6, double *d7) {
+    if (p > 128) return -3;
+    return loss_grad_impl(n, rowptr, colidx, w, weighted, G, graph_off, p, T, th1, th2, th3, th4, th5, th6, th7, S, x,
+                          action, target, loss_out, q_out, d1, d2, d3, d4, d5, d6, d7, NULL, NULL, NULL, NULL, NULL,
+                          NULL);
+}
+
+/*
+ * The same loss and gradient with some relu decisions taken by the caller, and a report of every
+ * pre-activation.  The gradient of Eq. (1) / Eq. (2) jumps where a pre-activation crosses zero; a float32
+ * evaluation cannot resolve the sign of one that lies within float32 rounding of zero, and its gradient
+ * is then that of the other branch.  A parity test reads the float32 path's decisions off its
+ * activations, checks with z / zs from here that they differ from the definition's only where
+ * |z| is within rounding of zero relative to zs, and asks for the gradient of that branch.
+ *   force      [S][T][n][p] (NULL: none): -1 follow the sign of z, 0 / 1 unit off / on, for every unit of Eq. (1)
+ *   force_head [S][2][p]    (NULL: none): the same for the units of Eq. (2): row 0 theta6 g, row 1 theta7 mu_a
+ *   z_out, zs_out [S][T][n][p], h_out, hs_out [S][2][p] (each optional): the pre-activations and the
+ *   summed magnitudes of their terms.
+ * With force == NULL and force_head == NULL the results equal oracle_loss_grad's bit for bit.
+ */
+int oracle_loss_grad_decided(int32_t n, const int32_t *rowptr, const int32_t *colidx, const double *w,
+                             int32_t weighted, int32_t G, const int32_t *graph_off, int32_t p, int32_t T,
+                             const double *th1, const double *th2, const double *th3, const double *th4,
+                             const double *th5, const double *th6, const double *th7, int32_t S, const double *x,
+                             const int32_t *action, const double *target, double *loss_out, double *q_out,
+                             double *d1, double *d2, double *d3, double *d4, double *d5, double *d6, double *d7,
+                             const int8_t *force, const int8_t *force_head, double *z_out, double *zs_out,
+                             double *h_out, double *hs_out) {
+    if (p > 128) return -3;
+    return loss_grad_impl(n, rowptr, colidx, w, weighted, G, graph_off, p, T, th1, th2, th3, th4, th5, th6, th7, S, x,
+                          action, target, loss_out, q_out, d1, d2, d3, d4, d5, d6, d7, force, force_head, z_out,
+                          zs_out, h_out, hs_out);
 }
 
 /* Plain gradient descent: theta <- theta - lr * grad (the optimiser of the benchmark's

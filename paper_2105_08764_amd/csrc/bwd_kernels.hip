@@ -50,10 +50,15 @@ __global__ __launch_bounds__(128) void k_bwd_head(int p, int N, int S, int G, co
     __syncthreads();
     float h1 = 0.f, h2 = 0.f, r1 = 0.f, r2 = 0.f, term = 0.f;
     if (i < p) {
+        // the 2p pre-activations of Eq. 2 in double, rounded once: each of these relu units carries a large
+        // share of the state's gradient, and the work is 2 p^2 operations per state
+        double a1 = 0.0, a2 = 0.0;
         for (int j = 0; j < p; ++j) {
-            h1 += theta6[i * p + j] * g[j];
-            h2 += theta7[i * p + j] * m[j];
+            a1 += (double)theta6[i * p + j] * (double)g[j];
+            a2 += (double)theta7[i * p + j] * (double)m[j];
         }
+        h1 = (float)a1;
+        h2 = (float)a2;
         r1 = fmaxf(h1, 0.f);
         r2 = fmaxf(h2, 0.f);
         term = theta5[i] * r1 + theta5[p + i] * r2;

@@ -40,6 +40,23 @@ __device__ __forceinline__ float readlane_f(float x, int l) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
 }
 
+// The round-1 pre-activation of one (node, state, column) from the node's three scalars (mu^0 = 0 in
+// Alg. 1, so z^1 = theta1 x + s+ q+ + s- q-).  Round 1 is recomputed wherever it is needed, forward (the
+// neighbour rows of round 2, the stored round-1 rows) and backward (the relu decisions of the last reversed
+// round): every such place calls this one function, whose order of operations is spelled out, so that all
+// of them take the same decision on every relu and produce the same value bit for bit.
+__device__ __forceinline__ float mu1_z(float x, float sp, float sn, float t1, float qp, float qn) {
+    return __fmaf_rn(sn, qn, __fmaf_rn(sp, qp, __fmul_rn(x, t1)));
+}
+// The same when s- = 0 (graphs without a negative weight): mu1_z(x, sp, 0, t1, qp, qn) adds an exact zero.
+__device__ __forceinline__ float mu1_z(float x, float sp, float t1, float qp) {
+    return __fmaf_rn(sp, qp, __fmul_rn(x, t1));
+}
+__device__ __forceinline__ float4 mu1_row(float x, float sp, float sn, float4 t1, float4 qp, float4 qn) {
+    return make_float4(fmaxf(mu1_z(x, sp, sn, t1.x, qp.x, qn.x), 0.f), fmaxf(mu1_z(x, sp, sn, t1.y, qp.y, qn.y), 0.f),
+                       fmaxf(mu1_z(x, sp, sn, t1.z, qp.z, qn.z), 0.f), fmaxf(mu1_z(x, sp, sn, t1.w, qp.w, qn.w), 0.f));
+}
+
 // ---- row loaders: the float4 (columns 4*li .. 4*li+3) of neighbour u's row -------------------
 
 // Row (u, s) of a [N][S][P] matrix in memory.
@@ -59,12 +76,7 @@ struct Mu1Row {
     float4 t1, qp, qn;  // theta1, q+, q- at this lane's four columns
     __device__ __forceinline__ float4 operator()(int u) const {
         const float3 r = ni.get(u, s);
-        float4 o;
-        o.x = fmaxf(r.x * t1.x + r.y * qp.x + r.z * qn.x, 0.f);
-        o.y = fmaxf(r.x * t1.y + r.y * qp.y + r.z * qn.y, 0.f);
-        o.z = fmaxf(r.x * t1.z + r.y * qp.z + r.z * qn.z, 0.f);
-        o.w = fmaxf(r.x * t1.w + r.y * qp.w + r.z * qn.w, 0.f);
-        return o;
+        return mu1_row(r.x, r.y, r.z, t1, qp, qn);
     }
 };
 
@@ -74,12 +86,7 @@ struct Mu1RowSingle {
     float4 t1, qp, qn;
     __device__ __forceinline__ float4 operator()(int u) const {
         const float4 r = ld4(base + (size_t)u * 4);
-        float4 o;
-        o.x = fmaxf(r.x * t1.x + r.y * qp.x + r.z * qn.x, 0.f);
-        o.y = fmaxf(r.x * t1.y + r.y * qp.y + r.z * qn.y, 0.f);
-        o.z = fmaxf(r.x * t1.z + r.y * qp.z + r.z * qn.z, 0.f);
-        o.w = fmaxf(r.x * t1.w + r.y * qp.w + r.z * qn.w, 0.f);
-        return o;
+        return mu1_row(r.x, r.y, r.z, t1, qp, qn);
     }
 };
 
@@ -211,11 +218,7 @@ __device__ __forceinline__ float4 gather_row_sum_mu1_single(const float *__restr
                 if (k & 1) s1acc += sadd; else s0acc += sadd;
                 const bool full = live && !cheap;
                 if (__ballot(full) != 0ull) {
-                    float4 m;
-                    m.x = fmaxf(r[k].x * t1.x + r[k].y * qp.x + r[k].z * qn.x, 0.f);
-                    m.y = fmaxf(r[k].x * t1.y + r[k].y * qp.y + r[k].z * qn.y, 0.f);
-                    m.z = fmaxf(r[k].x * t1.z + r[k].y * qp.z + r[k].z * qn.z, 0.f);
-                    m.w = fmaxf(r[k].x * t1.w + r[k].y * qp.w + r[k].z * qn.w, 0.f);
+                    const float4 m = mu1_row(r[k].x, r[k].y, r[k].z, t1, qp, qn);
                     const float wf = full ? wk[k] : 0.f;
                     if (k & 1) a1 = make_float4(fmaf(wf, m.x, a1.x), fmaf(wf, m.y, a1.y), fmaf(wf, m.z, a1.z), fmaf(wf, m.w, a1.w));
                     else a0 = make_float4(fmaf(wf, m.x, a0.x), fmaf(wf, m.y, a0.y), fmaf(wf, m.z, a0.z), fmaf(wf, m.w, a0.w));
@@ -357,7 +360,7 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
                     const int l = __ffsll((long long)todo) - 1;
                     todo &= todo - 1ull;
                     const float xl = readlane_f(x, l), pl = readlane_f(sp, l), nl = readlane_f(sn, l);
-                    const float m1 = fmaxf(xl * t1 + pl * qp + nl * qn, 0.f);
+                    const float m1 = fmaxf(mu1_z(xl, pl, nl, t1, qp, qn), 0.f);
                     if (W) {
                         const float wk = readlane_f(wl, l);
                         acc = fmaf(wk, m1, acc);
@@ -601,10 +604,7 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1_impl(const NodeInfo 
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
                     const float p_ = sp[SHARED ? 0 : c], n_ = sn[SHARED ? 0 : c], x_ = xs[c];
-                    const float4 mm = make_float4(fmaxf(x_ * t1.x + p_ * qp.x + n_ * qn.x, 0.f),
-                                                  fmaxf(x_ * t1.y + p_ * qp.y + n_ * qn.y, 0.f),
-                                                  fmaxf(x_ * t1.z + p_ * qp.z + n_ * qn.z, 0.f),
-                                                  fmaxf(x_ * t1.w + p_ * qp.w + n_ * qn.w, 0.f));
+                    const float4 mm = mu1_row(x_, p_, n_, t1, qp, qn);
                     acc.a[c] = acc4<W>(acc.a[c], mm, wk);
                 }
             }
@@ -672,7 +672,7 @@ __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeIn
                 const int l = __ffsll((long long)todo) - 1;
                 todo &= todo - 1ull;
                 const float xl = readlane_f(xs[s], l), pl = readlane_f(sp, l);
-                const float d = fmaxf(fmaf(xl, t1, pl * qp), 0.f) - pl * rp;
+                const float d = fmaxf(mu1_z(xl, pl, t1, qp), 0.f) - pl * rp;
                 if (W) acc[s] = fmaf(readlane_f(wl, l), d, acc[s]);
                 else acc[s] += d;
             }
@@ -690,7 +690,7 @@ __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeIn
 //   a  = total relu(q+)   + sum over flagged (u, s) of [relu(z) - s+_u relu(q+)]
 //   cx =                    sum over flagged (u, s) of x_{u,s} [z > 0]
 //   cp = total [q+ > 0]   + sum over flagged (u, s) of s+_u ([z > 0] - [q+ > 0]),      z = x_{u,s} theta1 + s+_u q+
-// (z is formed exactly as in gather_node_tile_flags, so forward and backward agree on every relu).
+// (z comes from mu1_z as in gather_node_tile_flags, so forward and backward agree on every relu).
 // a goes to tile_a[s * STRIDE + j]; cx and cp come back in registers (index = state).
 template <int P, bool W = false>
 __device__ __forceinline__ void gather_node_tile_flags_grad(float *tile_a, float (&cx)[16], float (&cp)[16],
@@ -722,7 +722,7 @@ __device__ __forceinline__ void gather_node_tile_flags_grad(float *tile_a, float
                 const int l = __ffsll((long long)todo) - 1;
                 todo &= todo - 1ull;
                 const float xl = readlane_f(xs[s], l), pl = readlane_f(sp, l);
-                const float z = fmaf(xl, t1, pl * qp);
+                const float z = mu1_z(xl, pl, t1, qp);
                 const float m = z > 0.f ? 1.f : 0.f;
                 const float wk = W ? readlane_f(wl, l) : 1.f;
                 a[s] = fmaf(wk, fmaxf(z, 0.f) - pl * rp, a[s]);
@@ -798,9 +798,9 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad_impl(const Nod
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
                     const float p_ = sp[SHARED ? 0 : c], n_ = NEG ? sn[SHARED ? 0 : c] : 0.f, x_ = xs[c];
-                    // the same expression as the forward pass, so that the masks agree
-                    const float zx = x_ * t1.x + p_ * qp.x + n_ * qn.x, zy = x_ * t1.y + p_ * qp.y + n_ * qn.y;
-                    const float zz = x_ * t1.z + p_ * qp.z + n_ * qn.z, zw = x_ * t1.w + p_ * qp.w + n_ * qn.w;
+                    // the forward pass's own function, so that the relu decisions agree
+                    const float zx = mu1_z(x_, p_, n_, t1.x, qp.x, qn.x), zy = mu1_z(x_, p_, n_, t1.y, qp.y, qn.y);
+                    const float zz = mu1_z(x_, p_, n_, t1.z, qp.z, qn.z), zw = mu1_z(x_, p_, n_, t1.w, qp.w, qn.w);
                     r.a.a[c].x = fmaf(w, fmaxf(zx, 0.f), r.a.a[c].x);
                     r.a.a[c].y = fmaf(w, fmaxf(zy, 0.f), r.a.a[c].y);
                     r.a.a[c].z = fmaf(w, fmaxf(zz, 0.f), r.a.a[c].z);

@@ -75,14 +75,16 @@ __global__ void k_qvec(int p, const float *__restrict__ theta3, const float *__r
                        float *__restrict__ qvec) {
     const int i = threadIdx.x;
     if (i >= p) return;
-    float qp = 0.f, qn = 0.f;
+    // double accumulation, one rounding: q+- multiply every node's edge sums, so an error here moves every
+    // pre-activation of the graph the same way
+    double qp = 0.0, qn = 0.0;
     for (int j = 0; j < p; ++j) {
         const float t4 = theta4[j], t3 = theta3[i * p + j];
-        qp += t3 * fmaxf(t4, 0.f);
-        qn += t3 * fmaxf(-t4, 0.f);
+        qp += (double)t3 * (double)fmaxf(t4, 0.f);
+        qn += (double)t3 * (double)fmaxf(-t4, 0.f);
     }
-    qvec[i] = qp;
-    qvec[p + i] = qn;
+    qvec[i] = (float)qp;
+    qvec[p + i] = (float)qn;
 }
 
 hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec) {
@@ -117,11 +119,8 @@ __global__ __launch_bounds__(256) void k_round1(long n_vrows, int N, int S, Node
             const float xo = x_res[(size_t)s * N + v];
             if (xo != 0.f) { xs = xo; keep = last ? 1.f : 0.f; }
         }
-        float4 o;
-        o.x = keep * fmaxf(xs * t1.x + sp * qp.x + sn * qn.x, 0.f);
-        o.y = keep * fmaxf(xs * t1.y + sp * qp.y + sn * qn.y, 0.f);
-        o.z = keep * fmaxf(xs * t1.z + sp * qp.z + sn * qn.z, 0.f);
-        o.w = keep * fmaxf(xs * t1.w + sp * qp.w + sn * qn.w, 0.f);
+        float4 o = mu1_row(xs, sp, sn, t1, qp, qn);
+        o.x *= keep; o.y *= keep; o.z *= keep; o.w *= keep;
         st4(mu_out + (size_t)r * P + c, o);
     }
 }
@@ -963,9 +962,11 @@ __global__ void k_qa(int p, const float *__restrict__ theta5, const float *__res
     __syncthreads();
     float term = 0.f;
     if (i < p) {
-        float h = 0.f;
-        for (int j = 0; j < p; ++j) h += theta6[i * p + j] * gs[j];
-        term = theta5[i] * fmaxf(h, 0.f);
+        // (double accumulation: p^2 operations per graph, and each of these p relu units carries 1/p of a
+        //  state's whole gradient in training)
+        double h = 0.0;
+        for (int j = 0; j < p; ++j) h += (double)theta6[i * p + j] * (double)gs[j];
+        term = theta5[i] * fmaxf((float)h, 0.f);
     }
     red[i] = term;
     __syncthreads();

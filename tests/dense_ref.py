@@ -62,3 +62,31 @@ def loss_torch(adj, wm, th_t, x_states, T, action, target, agg=None):
         )
         total = total + (q - target[b]) ** 2 / S
     return total
+
+
+def loss_torch_decided(adj, wm, th_t, x_states, T, action, target, force, force_head):
+    """loss_torch with relu decisions given from outside: force [S][T][n][p] and force_head [S][2][p] hold
+    -1 (the unit follows the sign of its pre-activation), 0 (off) or 1 (on: it passes its pre-activation
+    whatever its sign).  Pins oracle.loss_grad_decided."""
+    import torch
+
+    p = th_t["theta1"].shape[0]
+    total = 0.0
+    S = x_states.shape[0]
+
+    def act(z, f):
+        f = torch.as_tensor(np.asarray(f))
+        on = torch.where(f < 0, z.detach() > 0, f > 0)
+        return z * on.to(z.dtype)
+
+    for b in range(S):
+        e = (adj[:, :, None] * torch.relu(wm[:, :, None] * th_t["theta4"][None, None, :])).sum(dim=1)
+        const = torch.outer(x_states[b], th_t["theta1"]) + e @ th_t["theta3"].T
+        mu = torch.zeros(adj.shape[0], p, dtype=adj.dtype)
+        for t in range(T):
+            mu = act(const + (adj @ mu) @ th_t["theta2"].T, force[b][t])
+        g = mu.sum(dim=0)
+        q = th_t["theta5"][:p] @ act(th_t["theta6"] @ g, force_head[b][0]) + th_t["theta5"][p:] @ act(
+            th_t["theta7"] @ mu[action[b]], force_head[b][1])
+        total = total + (q - target[b]) ** 2 / S
+    return total

@@ -88,7 +88,12 @@ class Device:
             self.ctx.s2v_sgd_step(prm, grads, lr)
         torch.cuda.synchronize()
         self.last_gsum = gsum.cpu().numpy()
+        self.last_saved = saved      # [T][N][S][p] on the device: the activations the backward pass read
         return float(loss.item()), qp.cpu().numpy(), grads.to_numpy()
+
+    def last_decisions(self):
+        """The relu decisions of the last train_iter as [S][T][N][p] booleans (activation > 0)."""
+        return (self.last_saved > 0).permute(2, 0, 1, 3).contiguous().cpu().numpy()
 
 
     def loss_grad(self, prm, x, action, target):
