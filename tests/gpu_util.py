@@ -153,6 +153,19 @@ def rel_err(got: np.ndarray, ref: np.ndarray, floor_frac: float = FLOOR_FRAC, wh
     return float(np.max(np.abs(got - ref) / den))
 
 
+def rel_err_rms_floor(got: np.ndarray, ref: np.ndarray, floor_frac: float = 1e-3) -> float:
+    """max_i |got_i - ref_i| / max(|ref_i|, floor_frac * rms(ref)): the stricter reading of "max relative error"
+    near cancelled entries (floor at a thousandth of the tensor's root mean square instead of a hundredth of
+    the row's maximum).  Reported beside rel_err by the full-size tests; not a bar of its own."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    den = np.maximum(np.abs(ref), max(floor_frac * rms, 1e-30))
+    return float(np.max(np.abs(got - ref) / den))
+
+
 def thetas_clear_of_kinks(oracle, g: si.Graph, p: int, T: int, x, action, target, seed: int, scale: float,
                           eps: float = 2.5e-7, limit: float = 2e-5, tries: int = 24, grad_fn=None):
     """Parameters for a gradient parity case, drawn so that the comparison with float64 is meaningful.

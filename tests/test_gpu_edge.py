@@ -266,3 +266,57 @@ def test_row_lengths_around_the_long_row_and_segment_limits(oracle_mod, S, p, T)
         assert abs(loss - oloss) <= 1e-4 * abs(oloss)
         for name in si.THETA_NAMES:
             assert gu.rel_err(grads[name], ograds[name], whole=True) <= 1e-4, (signed, name)
+
+
+@pytest.mark.parametrize("batched", [False, True])
+def test_star_with_100000_leaves(oracle_mod, batched):
+    # One row of 10^5 entries (196 segments of the long-row pre-pass) next to 10^5 rows of one entry, alone and
+    # as one block of a block-diagonal batch: single-state policy evaluation and a 16-state training iteration
+    # (node-mode rounds, mask-word and fused reversed rounds, the hub as one of the action nodes).
+    import torch
+
+    print(f"case star 1e5 batched={batched}", flush=True)
+    star = si.star_graph(100_000)
+    if batched:
+        g = si.block_diagonal([si.barabasi_albert(300, 3, 5), star, si.edgeless(1), si.erdos_renyi_gnp(200, 0.05, 6)])
+        hub = int(g.graph_off[1])
+    else:
+        g, hub = star, 0
+    assert int(np.diff(g.rowptr).max()) == 100_000 and int(np.diff(g.rowptr)[hub]) == 100_000
+    g.w = si.symmetric_edge_weights(g, 3, 0.5, 1.5)
+    p, T = 64, 3
+    theta = si.thetas(p, 17, 0.01)
+    # one state: embedding, graph sums, scores of every node
+    x = si.node_flags(g.n, 0.1, 4)
+    x[0, hub] = 0
+    dev = gu.Device(g, p, T)
+    out = dev.forward(theta, x)
+    omu, ogs, oq = gu.oracle_forward(oracle_mod, g, theta, x[0], T)
+    errs = (gu.rel_err(out["mu"][:, 0, :], omu), gu.rel_err(out["gsum"][0], ogs), gu.rel_err(out["q"][0], oq))
+    print("  single state, rel errors mu/gsum/q:", errs, flush=True)
+    assert max(errs) <= 1e-4
+    idx, val, cnt = dev.select(out["q"][0], x[0], None, 1)
+    oi, ov, oc = oracle_mod.select(g.graph_off, out["q"][0], x[0], None, 1)
+    assert np.array_equal(idx, oi) and np.array_equal(cnt, oc)
+    del dev
+    torch.cuda.empty_cache()
+    # sixteen states: one training iteration, both entry points
+    S = 16
+    x = si.node_flags(g.n, 0.1, 8, n_states=S)
+    x[:, hub] = 0
+    action, target = si.training_batch(x, 9)
+    action[0] = hub
+    if batched:
+        action[1] = 5                                # a state whose action lies in another graph of the batch
+    dev = gu.Device(g, p, T, S=S, training=True)
+    prm = dev.params(theta)
+    loss, qp, grads = dev.train_iter(prm, x, action, target)
+    loss1, qp1, grads1, _ = dev.loss_grad(prm, x, action, target)
+    assert loss1 == loss and np.array_equal(qp1, qp)
+    oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, g.graph_off, theta, x, T, action, target)
+    errs = {k: gu.rel_err(grads[k], ograds[k], whole=True) for k in si.THETA_NAMES}
+    print("  16 states, gradient rel errors:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert gu.rel_err(qp, oqp) <= 1e-4 and abs(loss - oloss) <= 1e-4 * abs(oloss)
+    for k in si.THETA_NAMES:
+        assert np.array_equal(grads1[k], grads[k]), k
+        assert errs[k] <= 1e-4, k

@@ -3,11 +3,10 @@
 Configurations 3 and 4 (inference): the whole float64 oracle is run on the host (tens of seconds)
 and every embedding entry, graph sum and score is compared; selection is checked bit-exactly on
 the GPU's scores and, against the oracle's scores, outside the 1e-4 band.
-Configuration 5 (training, 16 states): predicted Q and loss against the oracle's forward pass of
-every state would take minutes, so two sampled states are checked against the oracle, the
-two-state minibatch gradient is checked against the oracle at full graph size, and the 16-state
-gradient (the timed launch shape) is checked through the identity grad(mean of losses) = mean of
-the single-state gradients, each of which takes the separately verified one-state path.
+Configuration 5 (training, 16 states, the timed launch shape): loss, the predicted Q of all sixteen
+states and every gradient tensor against the oracle's 16-state evaluation on the full graph (a few
+minutes of host time), with the configuration's own parameters; beside it the identity
+grad(mean of losses) = mean of the single-state gradients through the one-state path.
 """
 import numpy as np
 import pytest
@@ -62,16 +61,24 @@ def test_config5_full_training(oracle_mod):
     torch.cuda.empty_cache()
     print(f"S=16 loss {loss16:.6g}", flush=True)
 
-    # (2) predicted Q of two sampled states against the oracle's forward pass
-    for b in (3, 12):
-        mu = oracle_mod.embed(g.rowptr, g.colidx, g.w, w.theta, w.x[b], w.T)
-        _, q = oracle_mod.q_scores(None, w.theta, mu)
-        rel = abs(qp16[b] - q[w.action[b]]) / abs(q[w.action[b]])
-        print(f"state {b}: Q gpu {qp16[b]:.8g} oracle {q[w.action[b]]:.8g} rel {rel:.2e}", flush=True)
-        assert rel <= TOL
-    del mu, q
+    # (2) the 16-state minibatch against the oracle directly, with the configuration's own parameters: loss,
+    # the predicted Q of all sixteen states and every gradient tensor (the oracle walks the states one at a
+    # time: about ten seconds per state on the host)
+    import time
+    t0 = time.time()
+    oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, None, w.theta, w.x, w.T, w.action, w.target)
+    print(f"oracle, 16 states at full size: {time.time() - t0:.0f} s", flush=True)
+    qerr = float(np.max(np.abs(qp16 - oqp) / np.abs(oqp)))
+    print(f"S=16 loss gpu {loss16:.8g} oracle {oloss:.8g}; predicted Q, worst of 16 states: {qerr:.2e}", flush=True)
+    assert abs(loss16 - oloss) <= TOL * abs(oloss) and qerr <= TOL
+    errs = {k: gu.rel_err(grads16[k], ograds[k], whole=True) for k in grads16}
+    strict = {k: gu.rel_err_rms_floor(grads16[k], ograds[k]) for k in grads16}
+    print("S=16 gradient vs oracle:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    print("  (denominator floored at 1e-3 x rms instead:", {k: f"{v:.2e}" for k, v in strict.items()}, ")", flush=True)
+    assert max(errs.values()) <= TOL
 
-    # (3) gradient of the mean = mean of single-state gradients (one-state path, row-mode gathers)
+    # (3) gradient of the mean = mean of single-state gradients (one-state path, row-mode gathers), and the
+    # first single-state gradient against the oracle as well
     dev1 = gu.Device(g, w.p, w.T, S=1, training=True)
     acc = {k: np.zeros_like(v, dtype=np.float64) for k, v in grads16.items()}
     loss_sum = 0.0
@@ -82,14 +89,12 @@ def test_config5_full_training(oracle_mod):
         loss_sum += l1 / S
         for k in acc:
             acc[k] += g1[k].astype(np.float64) / S
-        if b in (0, 1):
+        if b == 0:
             singles[b] = (l1, q1, g1)
     assert abs(loss_sum - loss16) <= 1e-5 * abs(loss16)
     errs = {k: gu.rel_err(grads16[k], acc[k], whole=True) for k in acc}
     print("S=16 vs mean of S=1 gradients:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     assert max(errs.values()) <= TOL
-
-    # (4) the one-state gradient itself against the oracle at full graph size
     oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, None, w.theta, w.x[0:1], w.T,
                                               w.action[0:1], w.target[0:1])
     l1, q1, g1 = singles[0]

@@ -302,6 +302,10 @@ def _run_config(oracle_mod, c, scale):
     mu, gsum, q = gu.oracle_forward(oracle_mod, g, w.theta, w.x[0], w.T)
     errs = (gu.rel_err(out["mu"][:, 0, :], mu), gu.rel_err(out["gsum"][0], gsum), gu.rel_err(out["q"][0], q))
     print("rel errors mu/gsum/q:", errs, flush=True)
+    # the same differences with the denominator floored at 1e-3 x rms of the tensor (reported, not a bar)
+    print("  with the 1e-3 x rms floor:", (gu.rel_err_rms_floor(out["mu"][:, 0, :], mu),
+                                           gu.rel_err_rms_floor(out["gsum"][0], gsum),
+                                           gu.rel_err_rms_floor(out["q"][0], q)), flush=True)
     assert max(errs) <= TOL
     # the call that bench.py times (embedding and scores in one) must give the same bits at this size too
     import torch
