@@ -54,6 +54,7 @@ extern "C" {
 #define S2V_ERR_HIP (-4)                 /* a HIP call failed; see s2v_last_hip_error */
 #define S2V_ERR_NO_DEVICE (-5)           /* no usable GPU in this process */
 #define S2V_ERR_NOT_PREPARED (-6)        /* s2v_graph_prepare has not run for this graph + workspace */
+#define S2V_ERR_TOO_LARGE (-7)           /* s2v_select_topk_noalloc: n_nodes or k beyond its fixed maximum */
 
 typedef struct s2v_ctx s2v_ctx;
 
@@ -198,6 +199,25 @@ int32_t s2v_policy_eval(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *para
  */
 int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const float *x, const uint8_t *cand,
                         int32_t k, int32_t *idx, float *val, int32_t *count, void *ws, size_t ws_bytes);
+
+/*
+ * s2v_select_topk for callers that cannot allocate device memory or size a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same selection rule and outputs as
+ * s2v_select_topk for ONE graph (G == 1): idx [k], val [k], count [1]; q, x [n_nodes], cand [n_nodes] bytes or NULL.
+ * No graph struct, no workspace and no s2v_graph_prepare: the scratch of the selection kernels (chunk table,
+ * per-chunk partial results, radix histograms, scan and sort buffers) lives in a fixed array of 5 MiB of
+ * device memory inside the library, which every GPU this process creates a context on holds until the
+ * process ends.  The call allocates and frees nothing, on the host or on the device.
+ * Limits: n_nodes <= S2V_NOALLOC_MAX_NODES and k <= S2V_NOALLOC_MAX_K, else S2V_ERR_TOO_LARGE (nothing is
+ * enqueued).  All contexts of one GPU share that GPU's array: two calls of this entry point that overlap in
+ * time on the same GPU (different streams or contexts) race; calls on one stream are safe.  The context
+ * must have been created with the GPU of its stream current.
+ * Errors: INVALID_ARG, TOO_LARGE, HIP (also when the array's address could not be obtained in s2v_create).
+ */
+#define S2V_NOALLOC_MAX_NODES (1 << 22) /* 4 194 304 */
+#define S2V_NOALLOC_MAX_K (1 << 18)     /* 262 144 */
+int32_t s2v_select_topk_noalloc(s2v_ctx *ctx, int32_t n_nodes, const float *q, const float *x, const uint8_t *cand,
+                                int32_t k, int32_t *idx, float *val, int32_t *count);
 
 /*
  * Backward pass of the training step (Train of Alg. 4: forward = Alg. 1 then Alg. 2, then

@@ -22,6 +22,9 @@ S2V_ERR_WORKSPACE_TOO_SMALL = -3
 S2V_ERR_HIP = -4
 S2V_ERR_NO_DEVICE = -5
 S2V_ERR_NOT_PREPARED = -6
+S2V_ERR_TOO_LARGE = -7
+S2V_NOALLOC_MAX_NODES = 1 << 22
+S2V_NOALLOC_MAX_K = 1 << 18
 
 THETA_NAMES = ("theta1", "theta2", "theta3", "theta4", "theta5", "theta6", "theta7")
 EXPORTS = (
@@ -29,6 +32,7 @@ EXPORTS = (
     "s2v_graph_prepare", "s2v_embed_fwd", "s2v_q_score", "s2v_select_topk", "s2v_embed_bwd",
     "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end", "s2v_residual_update",
     "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target", "s2v_policy_eval", "s2v_loss_grad",
+    "s2v_select_topk_noalloc",
 )
 
 
@@ -228,6 +232,15 @@ class Context:
                                         ctypes.c_void_p(_dp(idx)), ctypes.c_void_p(_dp(val)),
                                         ctypes.c_void_p(_dp(count)), ctypes.c_void_p(_dp(ws)),
                                         ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_select_topk")
+
+    def s2v_select_topk_noalloc(self, n_nodes: int, q, x, cand, k: int, idx, val, count) -> None:
+        _want(idx, "int32", "idx")
+        _want(count, "int32", "count")
+        _want(cand, "uint8", "cand")
+        _check(self.lib.s2v_select_topk_noalloc(self.handle, ctypes.c_int32(n_nodes), ctypes.c_void_p(_dp(q)),
+                                                ctypes.c_void_p(_dp(x)), ctypes.c_void_p(_dp(cand)), ctypes.c_int32(k),
+                                                ctypes.c_void_p(_dp(idx)), ctypes.c_void_p(_dp(val)),
+                                                ctypes.c_void_p(_dp(count))), "s2v_select_topk_noalloc")
 
     def s2v_embed_bwd(self, g: Graph, params: Params, x, T: int, S: int, mu_saved, gsum, action, target, loss,
                       q_pred, grads: Params, ws) -> None:

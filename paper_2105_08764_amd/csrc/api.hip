@@ -1,6 +1,7 @@
 // C interface of libs2v.so: argument checks, workspace layout and the order of kernel launches.
 // See include/s2v.h for the contract of every entry point.
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <cstdlib>
 #include <vector>
@@ -185,6 +186,49 @@ bool p_supported(int p) { return p == 32 || p == 64; }
 
 }  // namespace
 
+// ---- scratch of s2v_select_topk_noalloc: device memory the library owns, so that the call allocates nothing ----
+// Layout for the largest supported call (N = S2V_NOALLOC_MAX_NODES, k = S2V_NOALLOC_MAX_K); a smaller call uses
+// the front part of every piece.
+namespace {
+struct NoallocLayout {
+    size_t chunk_begin, chunk_end, graph_chunk_off, part_val, part_idx, hist, state, blk, keys0, keys1, ids0, ids1,
+        sort_cnt, end;
+};
+constexpr NoallocLayout noalloc_layout() {
+    constexpr size_t n = S2V_NOALLOC_MAX_NODES, k = S2V_NOALLOC_MAX_K;
+    constexpr size_t chunks = (n + kChunkNodes - 1) / kChunkNodes;
+    NoallocLayout l{};
+    size_t off = 0;
+    auto take = [&off](size_t bytes) { const size_t at = off; off = align_up(off + bytes); return at; };
+    l.chunk_begin = take(sizeof(int32_t) * chunks);
+    l.chunk_end = take(sizeof(int32_t) * chunks);
+    l.graph_chunk_off = take(sizeof(int32_t) * 2);
+    l.part_val = take(sizeof(float) * chunks * kSmallK);
+    l.part_idx = take(sizeof(int32_t) * chunks * kSmallK);
+    l.hist = take(sizeof(uint32_t) * 4 * 256);
+    l.state = take(sizeof(uint32_t) * 16);
+    l.blk = take(sizeof(uint32_t) * 4 * ((n + kScanBlock - 1) / kScanBlock));
+    l.keys0 = take(sizeof(uint32_t) * k);
+    l.keys1 = take(sizeof(uint32_t) * k);
+    l.ids0 = take(sizeof(int32_t) * k);
+    l.ids1 = take(sizeof(int32_t) * k);
+    l.sort_cnt = take(sizeof(uint32_t) * 256 * ((k + kSortTile - 1) / kSortTile));
+    l.end = off;
+    return l;
+}
+constexpr size_t kNoallocScratchBytes = (size_t)5 << 20;   // 5 MiB per GPU, held until the process ends
+static_assert(noalloc_layout().end <= kNoallocScratchBytes, "scratch array too small for the largest call");
+}  // namespace
+
+// In host code this name is only a handle for hipGetSymbolAddress; kernels and copies get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU this process has used
+}  // namespace
+
 struct ProfSpan {
     hipEvent_t start, stop;
     int kind;
@@ -193,6 +237,8 @@ struct ProfSpan {
 struct s2v_ctx {
     hipStream_t stream;
     int32_t last_hip;
+    int device = -1;               // the device that was current in s2v_create
+    void *noalloc_scratch = nullptr;   // that device's copy of the library-owned scratch array
     std::vector<Prepared> prepared;
     // Embedding matrices of at least this many bytes ([N][S][p] floats, S a multiple of 16) have the rounds
     // that read them visit their rows state by state instead of node by node: one state's rows then fit the
@@ -305,6 +351,7 @@ const char *s2v_status_str(int32_t status) {
         case S2V_ERR_HIP: return "HIP runtime error";
         case S2V_ERR_NO_DEVICE: return "no usable GPU";
         case S2V_ERR_NOT_PREPARED: return "graph not prepared with this workspace";
+        case S2V_ERR_TOO_LARGE: return "size beyond the fixed maximum of an entry point that allocates nothing";
         default: return "unknown status";
     }
 }
@@ -321,6 +368,21 @@ int32_t s2v_create(void *hip_stream, s2v_ctx **out) {
     if (!ctx) return S2V_ERR_INVALID_ARG;
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     ctx->last_hip = 0;
+    // this device's copy of the scratch array of s2v_select_topk_noalloc, looked up once per device
+    // (the symbol is named here, in a function with external linkage: the device-side compilation keeps a
+    //  file-scope device variable visible to the runtime only when such a function refers to it)
+    if (hipGetDevice(&ctx->device) == hipSuccess && ctx->device >= 0 && ctx->device < kMaxDevices) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[ctx->device]) {
+            void *ptr = nullptr;
+            const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e == hipSuccess) g_scratch_ptr[ctx->device] = ptr;
+            else ctx->last_hip = (int32_t)e;   // only s2v_select_topk_noalloc is affected
+        }
+        ctx->noalloc_scratch = g_scratch_ptr[ctx->device];
+    } else {
+        (void)hipGetLastError();
+    }
     if (const char *e = std::getenv("S2V_SLICED_MIN_BYTES")) {
         char *end = nullptr;
         const unsigned long long v = std::strtoull(e, &end, 10);
@@ -699,6 +761,45 @@ int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const 
         S2V_TRY(launch_smallk(ctx->stream, ct, q, x, cand, k, sc, idx, val, count));
     } else {
         S2V_TRY(launch_topk(ctx->stream, N, q, x, cand, k, sc, idx, val, count));
+    }
+    return S2V_OK;
+}
+
+int32_t s2v_select_topk_noalloc(s2v_ctx *ctx, int32_t n_nodes, const float *q, const float *x, const uint8_t *cand,
+                                int32_t k, int32_t *idx, float *val, int32_t *count) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    if (n_nodes < 0 || k < 1 || !idx || !val || !count) return S2V_ERR_INVALID_ARG;
+    if (n_nodes > 0 && (!q || (!x && !cand))) return S2V_ERR_INVALID_ARG;
+    if (n_nodes > S2V_NOALLOC_MAX_NODES || k > S2V_NOALLOC_MAX_K) return S2V_ERR_TOO_LARGE;
+    if (!ctx->noalloc_scratch) return S2V_ERR_HIP;   // the lookup in s2v_create failed (see s2v_last_hip_error)
+    constexpr NoallocLayout l = noalloc_layout();
+    void *base = ctx->noalloc_scratch;   // the device address, never the array's name
+    ChunkTable ct;
+    ct.n_chunks = (n_nodes + kChunkNodes - 1) / kChunkNodes;
+    ct.chunk_begin = at<int32_t>(base, l.chunk_begin);
+    ct.chunk_end = at<int32_t>(base, l.chunk_end);
+    ct.graph_chunk_off = at<int32_t>(base, l.graph_chunk_off);
+    SelectScratch sc;
+    sc.part_val = at<float>(base, l.part_val);
+    sc.part_idx = at<int32_t>(base, l.part_idx);
+    sc.hist = at<uint32_t>(base, l.hist);
+    sc.state = at<uint32_t>(base, l.state);
+    sc.blk = at<uint32_t>(base, l.blk);
+    sc.keys[0] = at<uint32_t>(base, l.keys0);
+    sc.keys[1] = at<uint32_t>(base, l.keys1);
+    sc.ids[0] = at<int32_t>(base, l.ids0);
+    sc.ids[1] = at<int32_t>(base, l.ids1);
+    sc.sort_cnt = at<uint32_t>(base, l.sort_cnt);
+    // Everything the kernels read from the scratch is written earlier in the same call (the chunk table here,
+    // the histograms and the selection state by the chain's first kernel), so the previous call's contents
+    // do not matter.
+    if (k <= kSmallK) {
+        S2V_TRY(launch_chunk_table_single(ctx->stream, n_nodes, ct.n_chunks, at<int32_t>(base, l.chunk_begin),
+                                          at<int32_t>(base, l.chunk_end), at<int32_t>(base, l.graph_chunk_off)));
+        if (k == 1) S2V_TRY(launch_argmax(ctx->stream, n_nodes, 1, ct, q, x, cand, sc, idx, val, count));
+        else S2V_TRY(launch_smallk(ctx->stream, ct, q, x, cand, k, sc, idx, val, count));
+    } else {
+        S2V_TRY(launch_topk(ctx->stream, n_nodes, q, x, cand, k, sc, idx, val, count));
     }
     return S2V_OK;
 }

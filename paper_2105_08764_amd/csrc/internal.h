@@ -21,7 +21,7 @@ constexpr int kSmallK = 8;         // top-k up to this k (the d of Sec. 4.5.1) t
 constexpr int kSortTile = 1024;
 constexpr int kSortFusedMaxBlocks = 512;   // above this the sort uses separate count / scan / scatter kernels
 
-inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+constexpr size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // Rows with more stored entries than kHubDegree are "hubs": their neighbour sums are formed ahead
 // of the round kernel by many waves, each summing one segment of at most kHubSegment entries, so
@@ -185,6 +185,8 @@ struct SelectScratch {
     int32_t *ids[2];    // [k] each
     uint32_t *sort_cnt; // [n_sort_blocks][256] ([256][n_sort_blocks] with more than kSortFusedMaxBlocks tiles)
 };
+hipError_t launch_chunk_table_single(hipStream_t st, int N, int n_chunks, int32_t *chunk_begin, int32_t *chunk_end,
+                                     int32_t *graph_chunk_off /*[2]*/);
 hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, const float *q, const float *x,
                          const uint8_t *cand, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
 hipError_t launch_q_target(hipStream_t st, int N, int S, int G, const int32_t *graph_off, const ChunkTable &ct,

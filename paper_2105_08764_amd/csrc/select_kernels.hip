@@ -675,6 +675,28 @@ __global__ __launch_bounds__(256) void k_topk_write(int k, const uint32_t *__res
     }
 }
 
+// The reduction chunk table of ONE graph of N nodes (what s2v_graph_prepare builds on the host for a
+// prepared graph), written on the device: chunk c covers nodes [c * kChunkNodes, min(N, (c + 1) * kChunkNodes)).
+__global__ __launch_bounds__(256) void k_chunk_table_single(int N, int n_chunks, int32_t *__restrict__ chunk_begin,
+                                                            int32_t *__restrict__ chunk_end,
+                                                            int32_t *__restrict__ graph_chunk_off) {
+    for (int c = blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += gridDim.x * 256) {
+        chunk_begin[c] = c * kChunkNodes;
+        chunk_end[c] = min(N, (c + 1) * kChunkNodes);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        graph_chunk_off[0] = 0;
+        graph_chunk_off[1] = n_chunks;
+    }
+}
+
+hipError_t launch_chunk_table_single(hipStream_t st, int N, int n_chunks, int32_t *chunk_begin, int32_t *chunk_end,
+                                     int32_t *graph_chunk_off) {
+    k_chunk_table_single<<<max(1, min((n_chunks + 255) / 256, 64)), 256, 0, st>>>(N, n_chunks, chunk_begin, chunk_end,
+                                                                                  graph_chunk_off);
+    return hipGetLastError();
+}
+
 #define S2V_CHECK_LAUNCH()                         \
     do {                                           \
         hipError_t e_ = hipGetLastError();         \
