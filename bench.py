@@ -2,14 +2,16 @@
 """Benchmark of the structure2vec / deep-Q hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-train] [--no-loop] [--no-cpu-baseline]
+                    [--no-sweep] [--no-small]
 
 A "step" is one RL inference step on the 30M-edge workload (benchmark configuration 4:
 Erdos-Renyi n = 2e6, average degree 30, p = 64, T = 4): embedding and scores (s2v_policy_eval:
 the work of s2v_embed_fwd + s2v_q_score) and top-k selection with k = 1 % of the candidates (s2v_select_topk), with all
 inputs resident in HBM.  The one-time graph preparation is timed separately.  Also reported:
 the training step of configuration 5 (Barabasi-Albert n = 1e6, 16 states, 4 SGD iterations),
-the live HIP-event time of the fused embedding-round kernel against the HBM roofline, and the
-float64 CPU oracle timed on the host cores as a baseline.  Prints ONE JSON line.
+the live HIP-event time of the fused embedding-round kernel against the HBM roofline (with a sweep of
+the embedding's footprint from cache-resident to DRAM-resident), the other benchmark configurations,
+and the float64 CPU oracle timed on the host cores as a baseline.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -40,7 +42,7 @@ def round_algorithmic_bytes(n, nnz, p, S=1):
 
 
 def copy_ceiling_gbs(torch):
-    """Empirical streaming ceiling of this GPU: a plain 1 GiB device-to-device copy (1 GiB read +
+    """Empirical streaming ceiling of this GPU, read + write: a plain 1 GiB device-to-device copy (1 GiB read +
     1 GiB written), best of five, in GB/s of total traffic."""
     src = torch.empty(1 << 28, device="cuda").normal_()
     dst = torch.empty_like(src)
@@ -57,16 +59,75 @@ def copy_ceiling_gbs(torch):
     return 2 * (1 << 30) / (best * 1e-3) / 1e9
 
 
-def read_traffic(path):
-    """HBM bytes per launch of the embedding-round kernel from a committed rocprofv3 counter
-    summary (FETCH_SIZE + WRITE_SIZE, scaled); None if the summary is not there."""
+def read_ceiling_gbs(torch, s2v):
+    """Empirical streaming ceiling for memory that is only READ (the gather rounds are 97 % reads): the
+    library's read-only probe over a 2 GiB buffer (eight times the 256 MB memory-side cache), best of five."""
+    ctx = s2v.Context()
+    src = torch.empty(1 << 29, device="cuda").normal_()
+    out = torch.empty(4096, device="cuda")
+    best = float("inf")
+    for _ in range(6):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        ctx.s2v_stream_read(src, out)
+        b.record()
+        torch.cuda.synchronize()
+        best = min(best, a.elapsed_time(b))
+    del src, out
+    torch.cuda.empty_cache()
+    return (1 << 31) / (best * 1e-3) / 1e9
+
+
+def read_profile_summary(path):
+    """Numbers from a committed rocprofv3 counter summary under profiles/: KEY=value lines, and per-kernel
+    table rows (kernel name -> list of floats).  Empty when the file is not there."""
+    keys, rows = {}, {}
     try:
         for line in open(path):
-            if line.startswith("HBM_BYTES_PER_LAUNCH="):
-                return float(line.split("=", 1)[1])
+            line = line.rstrip("\n")
+            if line.startswith("#") or not line.strip():
+                continue
+            if "=" in line and not line.startswith("void") and " " not in line.split("=", 1)[0]:
+                k, v = line.split("=", 1)
+                keys[k] = v
+                continue
+            parts = line.split()
+            nums = []
+            while parts:
+                try:
+                    nums.insert(0, float(parts[-1]))
+                    parts.pop()
+                except ValueError:
+                    break
+            if nums and parts:
+                rows[" ".join(parts)] = nums
     except OSError:
         pass
-    return None
+    return keys, rows
+
+
+def er_gnm_device(torch, n, m, seed):
+    """G(n, M) on the device for the footprint sweep (timing only): M seeded random pairs, self-pairs and
+    repeats dropped, as a symmetric int32 CSR with sorted rows -- the recipe of synth_inputs.erdos_renyi_gnm
+    with torch's generator, fast enough to build a 240 M-entry graph inside the benchmark."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    u = torch.randint(0, n, (m,), generator=gen, device="cuda", dtype=torch.int64)
+    v = torch.randint(0, n, (m,), generator=gen, device="cuda", dtype=torch.int64)
+    keep = u != v
+    key = torch.unique(torch.minimum(u, v)[keep] * n + torch.maximum(u, v)[keep])
+    del u, v, keep
+    a, b = key // n, key % n
+    del key
+    both = torch.sort(torch.cat([a * n + b, b * n + a])).values
+    del a, b
+    rows, cols = both // n, (both % n).to(torch.int32)
+    del both
+    rowptr = torch.zeros(n + 1, dtype=torch.int64, device="cuda")
+    rowptr[1:] = torch.cumsum(torch.bincount(rows, minlength=n), 0)
+    del rows
+    torch.cuda.empty_cache()
+    return rowptr.to(torch.int32), cols
 
 
 def upload(s2v, torch, g):
@@ -108,13 +169,15 @@ def bench_inference(args, s2v, torch):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.s2v_profile_begin(args.steps * (T - 1) + 4)
+    ctx.s2v_profile_begin(args.steps * T + 4)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    (n_round, ms_round), _, (n_r2, ms_r2), (n_rq, ms_rq) = ctx.s2v_profile_end()
+    prof = ctx.s2v_profile_end()
+    (n_round, ms_round), (n_r2, ms_r2), (n_rq, ms_rq) = prof["fwd_round"], prof["fwd_round2"], prof["fwd_round_q"]
+    n_sel, ms_sel = prof["select"]
     peak_mb = torch.cuda.max_memory_allocated() / 2**20
     round_ms = ms_round / max(n_round, 1)
     alg = round_algorithmic_bytes(N, g.nnz, p)
@@ -133,13 +196,13 @@ def bench_inference(args, s2v, torch):
 
     step_w()
     torch.cuda.synchronize()
-    ctx.s2v_profile_begin(3 * (T - 1) + 4)
+    ctx.s2v_profile_begin(3 * T + 4)
     t0 = time.perf_counter()
     for _ in range(3):
         step_w()
     torch.cuda.synchronize()
     ms_w = (time.perf_counter() - t0) * 1e3 / 3
-    (n_round_w, ms_round_w), _, _, _ = ctx.s2v_profile_end()
+    n_round_w, ms_round_w = ctx.s2v_profile_end()["fwd_round"]
     round_w_ms = ms_round_w / max(n_round_w, 1)
     log(f"[bench] weighted neighbour sum: {ms_w:.3f} ms/step, gather round {round_w_ms:.3f} ms "
         f"({(alg + 4 * g.nnz) / (round_w_ms * 1e-3) / 1e9:.0f} GB/s algorithmic)")
@@ -150,10 +213,86 @@ def bench_inference(args, s2v, torch):
                           round_gbs=(alg + 4 * g.nnz) / (round_w_ms * 1e-3) / 1e9),
         ms=ms, prepare_ms=prepare_ms, peak_device_mib=peak_mb, n=N, nnz=g.nnz, k=k, p=p, T=T,
         round_ms=round_ms, round_launches=n_round, round2_ms=ms_r2 / max(n_r2, 1),
-        round_q_ms=ms_rq / max(n_rq, 1), alg_bytes=alg, achieved_gbs=achieved,
+        round_q_ms=ms_rq / max(n_rq, 1), select_ms=ms_sel / max(n_sel, 1), alg_bytes=alg, achieved_gbs=achieved,
         selected_count=int(cnt.item()), first_selected=int(idx[0, 0].item()),
     )
     return out, w
+
+
+def time_policy_steps(ctx, s2v, torch, graph, prm, x, N, p, T, k, G, steps, warmup):
+    """ms per inference step (policy evaluation + selection) and the profile of the timed steps."""
+    ws = torch.empty(max(ctx.s2v_workspace_bytes(graph, p, T, 1, k), 256), dtype=torch.uint8, device="cuda")
+    ctx.s2v_graph_prepare(graph, ws)
+    mu = torch.empty((N, 1, p), device="cuda")
+    gsum = torch.empty((1, G, p), device="cuda")
+    q = torch.empty((1, N), device="cuda")
+    idx = torch.empty((G, k), dtype=torch.int32, device="cuda")
+    val = torch.empty((G, k), device="cuda")
+    cnt = torch.empty((G,), dtype=torch.int32, device="cuda")
+
+    def step():
+        ctx.s2v_policy_eval(graph, prm, x, T, 1, mu, gsum, q, ws)
+        ctx.s2v_select_topk(graph, q[0], x[0], None, k, idx, val, cnt, ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.s2v_profile_begin(steps * (T + 1) + 4)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    return ms, ctx.s2v_profile_end()
+
+
+def bench_footprint_sweep(args, s2v, torch, w4):
+    """The plain gather round (the roofline kernel) on Erdos-Renyi graphs of the benchmark's density (average
+    degree 30, p = 64, T = 4) whose embedding matrix grows from half of the 256 MB memory-side cache to eight
+    times its size: the rate at the large end is what DRAM itself sustains for this access pattern."""
+    out = []
+    ctx = s2v.Context()
+    prm = s2v.Params.from_numpy(w4.theta)
+    for n in (500_000, 1_000_000, 4_000_000, 8_000_000):
+        n = max(64, int(round(n * args.scale)))
+        t0 = time.time()
+        rowptr, colidx = er_gnm_device(torch, n, 15 * n, 4242 + n)
+        graph = s2v.Graph(rowptr, colidx)
+        x = torch.from_numpy(si.node_flags(n, 0.05, 7)).cuda()
+        nnz = int(colidx.numel())
+        ms, prof = time_policy_steps(ctx, s2v, torch, graph, prm, x, n, w4.p, w4.T, 8, 1, 4, 1)
+        n_r, ms_r = prof["fwd_round"]
+        round_ms = ms_r / max(n_r, 1)
+        alg = round_algorithmic_bytes(n, nnz, w4.p)
+        gbs = alg / (round_ms * 1e-3) / 1e9
+        out.append(dict(n=n, nnz=nnz, embedding_mib=round(n * w4.p * 4 / 2**20, 1), step_ms=round(ms, 4),
+                        round_ms=round(round_ms, 4), algorithmic_gbs=round(gbs, 1), frac_of_peak=round(gbs / HBM_PEAK_GBS, 4)))
+        log(f"[bench] footprint n={n}: embedding {out[-1]['embedding_mib']:.0f} MiB, gather round {round_ms:.3f} ms, "
+            f"{gbs:.0f} GB/s algorithmic ({gbs / HBM_PEAK_GBS:.3f} of peak) ({time.time() - t0:.1f}s)")
+        del graph, rowptr, colidx, x
+        torch.cuda.empty_cache()
+    return out
+
+
+def bench_small_configs(args, s2v, torch):
+    """ms per inference step of benchmark configurations 1 (latency: ER n = 1000, p = 32, T = 3, argmax),
+    2 (128 x BA(500, 4) block-diagonal, per-graph argmax) and 3 (BA n = 1e6, top-k with k = 1 % of candidates)."""
+    out = {}
+    ctx = s2v.Context()
+    for c, steps, warm in ((1, 200, 20), (2, 100, 10), (3, max(5, args.steps), 3)):
+        w = si.config(c, args.scale if c == 3 else 1.0)
+        g = w.graph
+        graph = upload(s2v, torch, g)
+        prm = s2v.Params.from_numpy(w.theta)
+        x = torch.from_numpy(w.x).cuda()
+        ms, prof = time_policy_steps(ctx, s2v, torch, graph, prm, x, g.n, w.p, w.T, w.k, g.n_graphs, steps, warm)
+        n_sel, ms_sel = prof["select"]
+        out[f"cfg{c}"] = dict(workload=w.name, n=g.n, nnz=g.nnz, graphs=g.n_graphs, p=w.p, T=w.T, k=w.k,
+                              ms_per_step=round(ms, 5), steps=steps, select_ms=round(ms_sel / max(n_sel, 1), 5))
+        log(f"[bench] config {c} ({w.name}): {ms * 1e3:.1f} us per inference step over {steps} steps")
+        del graph, x
+        torch.cuda.empty_cache()
+    return out
 
 
 def bench_training(args, s2v, torch):
@@ -165,55 +304,102 @@ def bench_training(args, s2v, torch):
     ctx = s2v.Context()
     graph = upload(s2v, torch, g)
     N, p, T = g.n, w.p, w.T
-    ws = torch.empty(ctx.s2v_workspace_bytes(graph, p, T, S, 1, True), dtype=torch.uint8, device="cuda")
-    ctx.s2v_graph_prepare(graph, ws)
-    x = torch.from_numpy(w.x).cuda()
-    saved = torch.empty((T, N, S, p), device="cuda")
-    gsum = torch.empty((S, 1, p), device="cuda")
-    action = torch.from_numpy(w.action).cuda()
-    target = torch.from_numpy(w.target).cuda()
-    loss = torch.empty((1,), device="cuda")
-    qp = torch.empty((S,), device="cuda")
     theta0 = s2v.Params.from_numpy(w.theta)
     prm = s2v.Params.from_numpy(w.theta)
     grads = s2v.Params.zeros_like(prm)
 
-    def step():
-        # every step starts from the same parameters, then takes w.iters SGD iterations (Sec. 4.5.2)
-        for k_ in si.THETA_NAMES:
-            prm.t[k_].copy_(theta0.t[k_])
-        for _ in range(w.iters):
-            # forward + backward in one call (bit for bit the results of s2v_embed_fwd then s2v_embed_bwd)
-            ctx.s2v_loss_grad(graph, prm, x, T, S, saved, gsum, action, target, loss, qp, grads, ws)
-            ctx.s2v_sgd_step(prm, grads, w.lr)
+    def run(S_, x_np, action_np, target_np, steps):
+        """ms per training step (w.iters iterations of forward, loss, backward, SGD) with S_ states, and the profile."""
+        ws = torch.empty(ctx.s2v_workspace_bytes(graph, p, T, S_, 1, True), dtype=torch.uint8, device="cuda")
+        ctx.s2v_graph_prepare(graph, ws)
+        x = torch.from_numpy(x_np).cuda()
+        saved = torch.empty((T, N, S_, p), device="cuda")
+        gsum = torch.empty((S_, 1, p), device="cuda")
+        action = torch.from_numpy(action_np).cuda()
+        target = torch.from_numpy(target_np).cuda()
+        loss = torch.empty((1,), device="cuda")
+        qp = torch.empty((S_,), device="cuda")
+
+        def step():
+            # every step starts from the same parameters, then takes w.iters SGD iterations (Sec. 4.5.2)
+            for k_ in si.THETA_NAMES:
+                prm.t[k_].copy_(theta0.t[k_])
+            for _ in range(w.iters):
+                # forward + backward in one call (bit for bit the results of s2v_embed_fwd then s2v_embed_bwd)
+                ctx.s2v_loss_grad(graph, prm, x, T, S_, saved, gsum, action, target, loss, qp, grads, ws)
+                ctx.s2v_sgd_step(prm, grads, w.lr)
+
+        step()
+        torch.cuda.synchronize()
+        ctx.s2v_profile_begin(steps * w.iters * (2 * T + 2) + 4)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        prof = ctx.s2v_profile_end()
+        del ws, x, saved
+        torch.cuda.empty_cache()
+        return ms, prof
 
     steps = max(1, min(args.steps, args.train_steps))
-    for _ in range(1):
-        step()
-    torch.cuda.synchronize()
-    ctx.s2v_profile_begin(steps * w.iters * 2 * (T - 1) + 4)
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
-    (n_f, ms_f), (n_b, ms_b), (n_f2, ms_f2), (n_fl, ms_fl) = ctx.s2v_profile_end()
-    alg = round_algorithmic_bytes(N, g.nnz, p, S)
-    alg_last = alg - 4 * p * N * S + 8 * N * S      # the last round writes 8-byte mask words, not its rows
-    out = dict(ms_per_step=ms, ms_per_iteration=ms / w.iters, steps=steps, iterations=w.iters, S=S, n=N, nnz=g.nnz,
-               fwd_round_ms=ms_f / max(n_f, 1), fwd_last_round_ms=ms_fl / max(n_fl, 1),
-               bwd_round_ms=ms_b / max(n_b, 1), fwd_round2_ms=ms_f2 / max(n_f2, 1),
-               fwd_round_gbs=alg / (ms_f / max(n_f, 1) * 1e-3) / 1e9 if n_f else None,
-               fwd_last_round_gbs=alg_last / (ms_fl / max(n_fl, 1) * 1e-3) / 1e9 if n_fl else None,
-               fwd_rounds="fwd_round: rounds 3..T-1 (rows walked state by state at this size); fwd_last_round: "
-                          "round T, which writes relu-mask words and the graph sums instead of its rows; GB/s = "
-                          "algorithmic bytes of the round over its mean duration",
-               bwd_rounds="mean over the launched reversed rounds of an iteration, which differ in kind: the first "
-                          "gathers 8-byte mask words, the next gathers rows like the forward rounds and also does "
-                          "the last reversed round (from the neighbours' scalars) on each tile")
-    log(f"[bench] training {ms:.1f} ms/step ({w.iters} iterations); fwd round {out['fwd_round_ms']:.2f} ms, "
-        f"last fwd round {out['fwd_last_round_ms']:.2f} ms, "
-        f"bwd round {out['bwd_round_ms']:.2f} ms")
+    ms, prof = run(S, w.x, w.action, w.target, steps)
+
+    def avg(kind):
+        n_, ms_ = prof[kind]
+        return ms_ / n_ if n_ else None
+
+    nnz = g.nnz
+    mat = 4 * p * N * S                       # one [N][S][p] float matrix
+    gather = 4 * p * nnz * S                  # one p-float row per stored entry and state (no reuse)
+    idx_b = 4 * (N + 1) + 4 * nnz
+    # Algorithmic bytes per launch of the five large kernels of an iteration (what each must move when no gathered
+    # row is reused); the counter column is FETCH_SIZE + WRITE_SIZE from the committed rocprofv3 summary.
+    kernels = [
+        ("fwd_round2", "k_round<64, true, true, false, false, false, 0>",
+         "round 2 from flag words and the rows' totals: writes mu^2", idx_b + 2 * nnz * (S // 16) + 12 * N + mat),
+        ("fwd_round", "k_round<64, false, false, false, false, false, 2>",
+         "round 3, rows walked state by state: gathers mu^2, writes mu^3", S * idx_b + gather + 12 * N * S + mat),
+        ("fwd_round_q", "k_round<64, true, false, true, false, false, 1>",
+         "round 4: gathers mu^3, writes relu-mask words and the graph sums", idx_b + gather + 12 * N * S + 8 * N * S),
+        ("bwd_seed", "k_bwd_maskT<64, true>", "dz^4 seed from the mask words", 8 * N * S + 12 * N * S),
+        ("bwd_round_mask", "k_bwd_round<64, true, true, false, false, false, false>",
+         "reversed round 4: gathers mask words, reads mu^3, writes dz^3", idx_b + 8 * nnz * S + 2 * mat),
+        ("bwd_round", "k_bwd_round<64, true, false, false, true, false, true>",
+         "reversed rounds 3 and 2 in one launch: gathers dz^3, reads mu^2, scalar form of round 2 on chip",
+         idx_b + gather + mat + 2 * nnz * (S // 16)),
+    ]
+    keys, rows = read_profile_summary(os.path.join(ROOT, "profiles", "train_cfg5_pmc.txt"))
+    roof = []
+    for kind, name, what, alg in kernels:
+        a = avg(kind)
+        if a is None:
+            continue
+        cnt = rows.get("void s2v::" + name)
+        traffic = None if not cnt or len(cnt) < 3 else (cnt[-2] + cnt[-1]) * 1e9
+        roof.append(dict(kernel=name, what=what, launches=prof[kind][0], avg_ms=round(a, 4),
+                         algorithmic_bytes=alg, achieved_gbs=round(alg / (a * 1e-3) / 1e9, 1),
+                         frac=round(alg / (a * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), traffic=traffic,
+                         traffic_gbs=None if traffic is None else round(traffic / (a * 1e-3) / 1e9, 1),
+                         traffic_frac=None if traffic is None else round(traffic / (a * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)))
+    out = dict(ms_per_step=ms, ms_per_iteration=ms / w.iters, steps=steps, iterations=w.iters, S=S, n=N, nnz=nnz,
+               roofline=dict(bound="hbm", peak=HBM_PEAK_GBS, unit="GB/s", kernels=roof,
+                             traffic_from="profiles/train_cfg5_pmc.txt", traffic_commit=keys.get("COMMIT"),
+                             note="frac = algorithmic bytes (no-reuse model) / mean launch time / peak; traffic = "
+                                  "counter bytes per launch (fabric level: includes what the memory-side cache serves)"))
+    log(f"[bench] training {ms:.1f} ms/step ({w.iters} iterations): " +
+        ", ".join(f"{r['kernel'].split('<')[0]}[{r['what'].split(':')[0]}] {r['avg_ms']:.2f} ms" for r in roof))
+    # the same step with 8 and 24 states: S not a multiple of 16 leaves the 16-state (node-mode) kernels
+    other = {}
+    for S_ in (8, 24):
+        x_ = si.node_flags(N, 0.05, 2005, n_states=S_)
+        a_, t_ = si.training_batch(x_, 5005)
+        ms_, _ = run(S_, x_, a_, t_, 1)
+        other[f"S{S_}"] = dict(ms_per_iteration=round(ms_ / w.iters, 3), ms_per_iteration_per_state=round(ms_ / w.iters / S_, 4))
+        log(f"[bench] training with S={S_}: {ms_ / w.iters:.2f} ms per iteration ({ms_ / w.iters / S_:.3f} per state; "
+            f"S=16: {ms / w.iters / S:.3f})")
+    out["other_batch_sizes"] = other
+    out["_workload"] = w
     return out
 
 
@@ -375,11 +561,14 @@ def bench_paper_shape(args, s2v, torch):
             "paper_1xV100": {"inference_step_s": 23.8, "training_step_s": 316.4}}
 
 
-def cpu_baseline(w):
-    """The float64 oracle, as it stands, on the same inference step (embed + scores + top-k)."""
+def cpu_baseline(w, w5=None):
+    """The float64 oracle, as it stands, on the same inference step (embed + scores + top-k), on all host
+    threads; then one embedding round on ONE thread, and a sample of the training iteration."""
+    import ctypes
+
     import oracle
 
-    oracle.build()
+    lib = ctypes.CDLL(oracle.build())
     g = w.graph
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     # whole steps until about ten seconds of CPU work are in (at most four)
@@ -392,9 +581,34 @@ def cpu_baseline(w):
         times.append((time.perf_counter() - t0) * 1e3)
     ms = sum(times) / len(times)
     log(f"[bench] cpu oracle: {ms:.0f} ms per step on {threads} threads ({len(times)} repetitions)")
-    return dict(value=ms, unit="ms", cores=threads, kind="oracle",
-                sample=f"the whole configuration-4 inference step (n={g.n}, nnz={g.nnz}), mean of {len(times)} "
-                       f"repetitions ({sum(times) / 1e3:.1f} s of CPU work)")
+    out = dict(value=ms, unit="ms", cores=threads, kind="oracle",
+               sample=f"the whole configuration-4 inference step (n={g.n}, nnz={g.nnz}), mean of {len(times)} "
+                      f"repetitions ({sum(times) / 1e3:.1f} s of CPU work)")
+    # one thread: a single round of Eq. 1 over the whole graph (every round costs the oracle the same: it
+    # re-evaluates all three terms edge by edge), scaled to the T rounds of a step
+    try:
+        lib.omp_set_num_threads(1)
+        t0 = time.perf_counter()
+        oracle.embed(g.rowptr, g.colidx, g.w, w.theta, w.x[0], 1)
+        one = (time.perf_counter() - t0) * 1e3
+        out["one_thread"] = dict(value=one * w.T, unit="ms", cores=1,
+                                 sample=f"one of the {w.T} embedding rounds of the configuration-4 step timed on one "
+                                        f"thread ({one / 1e3:.1f} s) and multiplied by {w.T}; scores and selection left out")
+        log(f"[bench] cpu oracle on one thread: {one:.0f} ms per embedding round")
+    finally:
+        lib.omp_set_num_threads(threads)
+    if w5 is not None:
+        n_s = 2
+        g5 = w5.graph
+        t0 = time.perf_counter()
+        oracle.loss_grad(g5.rowptr, g5.colidx, g5.w, None, w5.theta, w5.x[:n_s], w5.T, w5.action[:n_s], w5.target[:n_s])
+        sec = time.perf_counter() - t0
+        S = w5.x.shape[0]
+        out["training"] = dict(value=sec * 1e3 * S / n_s * w5.iters, unit="ms per training step", cores=threads,
+                               sample=f"forward + backward of {n_s} of the {S} states of configuration 5 ({sec:.1f} s), "
+                                      f"scaled to {S} states and {w5.iters} iterations")
+        log(f"[bench] cpu oracle, training: {sec:.1f} s for {n_s} states of one iteration on {threads} threads")
+    return out
 
 
 def main():
@@ -409,6 +623,8 @@ def main():
                     help="short run for rocprofv3 --pmc: a 1 GiB device copy (calibration) and 3 inference steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loop", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the footprint sweep of the gather round")
+    ap.add_argument("--no-small", action="store_true", help="skip configurations 1, 2 and 3")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
@@ -430,14 +646,25 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         args.steps, args.warmup, args.no_train, args.no_cpu_baseline = 3, 1, True, True
+        args.no_sweep = args.no_small = True
 
     ceiling = copy_ceiling_gbs(torch)
-    log(f"[bench] streaming ceiling (1 GiB copy, read + write): {ceiling:.0f} GB/s")
+    read_ceiling = read_ceiling_gbs(torch, s2v)
+    log(f"[bench] streaming ceilings: 1 GiB copy (read + write) {ceiling:.0f} GB/s, 2 GiB read only {read_ceiling:.0f} GB/s")
     inf, w4 = bench_inference(args, s2v, torch)
-    train = None
+    sweep = None
+    if not args.no_sweep:
+        torch.cuda.empty_cache()
+        sweep = bench_footprint_sweep(args, s2v, torch, w4)
+    small = None
+    if not args.no_small:
+        torch.cuda.empty_cache()
+        small = bench_small_configs(args, s2v, torch)
+    train, w5 = None, None
     if not args.no_train:
         torch.cuda.empty_cache()
         train = bench_training(args, s2v, torch)
+        w5 = train.pop("_workload")
     loop = None
     if not args.no_loop and not args.counters:
         torch.cuda.empty_cache()
@@ -446,9 +673,15 @@ def main():
     if not args.no_loop and not args.counters:
         torch.cuda.empty_cache()
         paper = bench_paper_shape(args, s2v, torch)
-    cpu = None if args.no_cpu_baseline else cpu_baseline(w4)
+    cpu = None if args.no_cpu_baseline else cpu_baseline(w4, w5)
 
-    traffic = read_traffic(os.path.join(ROOT, "profiles", "k_round_cfg4_pmc.txt"))
+    keys, _ = read_profile_summary(os.path.join(ROOT, "profiles", "k_round_cfg4_pmc.txt"))
+    traffic = float(keys["HBM_BYTES_PER_LAUNCH"]) if "HBM_BYTES_PER_LAUNCH" in keys else None
+    dram = None
+    if sweep:
+        big = sweep[-1]
+        dram = dict(n=big["n"], embedding_mib=big["embedding_mib"], algorithmic_gbs=big["algorithmic_gbs"],
+                    frac_of_peak=big["frac_of_peak"])
     line = {
         "metric": "ms per RL inference step at 30M edges (embed + Q + top-k)",
         "value": round(inf["ms"], 4),
@@ -471,11 +704,19 @@ def main():
         "roofline": {
             "kernel": "k_round<64,false,false,false,false,false,0> (fused CSR gather + theta2 product + relu, rounds 3..T-1; the last round also forms the node term of Eq. 2 and is timed separately)",
             "bound": "hbm",
+            "bound_note": "bytes are counted where they leave the L2 for the fabric: at this configuration half of the "
+                          "512 MB embedding is served by the 256 MB memory-side Infinity Cache, so the rate is a "
+                          "fabric-level figure and exceeds what DRAM alone streams (the two ceilings below); no counter "
+                          "of this GPU separates cache hits from DRAM reads.  dram_bound holds the same kernel on a "
+                          "graph whose embedding is eight times the cache: the DRAM-level fraction",
+            "dram_bound": dram,
             "achieved": round(inf["achieved_gbs"], 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(inf["achieved_gbs"] / HBM_PEAK_GBS, 4),
             "traffic": traffic,
+            "traffic_from": "profiles/k_round_cfg4_pmc.txt",
+            "traffic_commit": keys.get("COMMIT"),
             "algorithmic_bytes_per_launch": inf["alg_bytes"],
             "avg_launch_ms": round(inf["round_ms"], 4),
             "launches_timed": inf["round_launches"],
@@ -485,10 +726,15 @@ def main():
             "compulsory_bytes_per_launch": inf["alg_bytes"] - 4 * inf["p"] * (inf["nnz"] - inf["n"]),
             "copy_ceiling_gbs": round(ceiling, 1),
             "frac_of_copy_ceiling": round(inf["achieved_gbs"] / ceiling, 4),
+            "read_ceiling_gbs": round(read_ceiling, 1),
+            "frac_of_read_ceiling": round(inf["achieved_gbs"] / read_ceiling, 4),
+            "footprint_sweep": sweep,
         },
         "cpu_baseline": cpu,
         "round2_from_scalars_ms": round(inf["round2_ms"], 4),
         "last_round_with_q_node_term_ms": round(inf["round_q_ms"], 4),
+        "select_topk_ms": round(inf["select_ms"], 4),
+        "other_configs": small,
         "weighted_sum_reading": inf["weighted_sum"],
         "prepare_ms": round(inf["prepare_ms"], 2),
         "peak_device_mib": round(inf["peak_device_mib"], 1),

@@ -108,16 +108,20 @@ const char *s2v_status_str(int32_t status);
  * Create a context bound to a HIP stream (`hip_stream` is a hipStream_t passed as void*;
  * NULL is the default stream) on the current device.  Host memory only.
  * Errors: S2V_ERR_INVALID_ARG (out == NULL), S2V_ERR_NO_DEVICE.
- * One tuning knob is read from the environment here: S2V_SLICED_MIN_BYTES (decimal bytes, default
- * 1.5 GiB).  Embedding matrices [N][S][p] of at least that size with S a multiple of 16 are walked state
- * by state instead of node by node in the rounds of Eq. 1 that read them, which keeps one state's rows
- * in the last-level cache; the order of the float32 additions, and so the last bits of the results,
- * depend on which walk is used.
  */
 int32_t s2v_create(void *hip_stream, s2v_ctx **out);
 int32_t s2v_destroy(s2v_ctx *ctx);
 /* hipError_t value of the last failed HIP call seen by this context (0 if none). */
 int32_t s2v_last_hip_error(const s2v_ctx *ctx);
+
+/*
+ * Tuning knob of a context (no passage of the paper stands behind it: it is a property of this GPU's cache
+ * hierarchy).  Embedding matrices [N][S][p] of at least `bytes` bytes (default 1.5 GiB) with S a multiple of
+ * 16 are walked state by state instead of node by node in the rounds of Eq. 1 that read them, which keeps
+ * one state's rows in the last-level cache.  The two walks add a row's neighbours in different orders, so
+ * the last bits of the results depend on which one is used; 0 forces the state-by-state walk.
+ */
+int32_t s2v_set_sliced_min_bytes(s2v_ctx *ctx, size_t bytes);
 
 /*
  * Bytes of workspace that every call below needs for this graph with embedding size p, T
@@ -143,7 +147,8 @@ int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t
  * has no row_end and no negative weight).  The head
  * of `ws` must stay untouched for as long as the graph is used with that workspace; the
  * other calls use the rest as scratch.  Reads graph_off back to the host, so this call
- * waits for the stream.  Call again if the graph's arrays change.
+ * waits for the stream.  Call again if the graph's arrays change; a graph struct whose rowptr, colidx or w
+ * pointer differs from the prepared one's is answered with S2V_ERR_NOT_PREPARED by the other calls.
  * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, HIP.
  */
 int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_bytes);
@@ -321,26 +326,42 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
                           int32_t *steps_out, int64_t *picked_out, int64_t *live_out, void *ws, size_t ws_bytes);
 
 /*
- * Optional live timing of the gather kernels (for benchmarks; not part of the method).
- * Between s2v_profile_begin and s2v_profile_end every launch of the fused embedding-round
- * kernel and of the fused backward-round kernel is bracketed by HIP events on the context's
- * stream, up to max_launches launches in total.  Kinds:
- *   S2V_PROFILE_FWD_ROUND   rounds 3..T of Eq. 1 inside s2v_embed_fwd (neighbour rows read from memory)
- *   S2V_PROFILE_BWD_ROUND   the reversed rounds inside s2v_embed_bwd
- *   S2V_PROFILE_FWD_ROUND2  round 2 of Eq. 1 (neighbour rows recomputed from per-node scalars)
- *   S2V_PROFILE_FWD_ROUND_Q a last round with more fused into it: the node term of Eq. 2 (inside
- *                           s2v_policy_eval) or relu-mask words instead of its rows (inside s2v_loss_grad);
- *                           such a launch is not counted under S2V_PROFILE_FWD_ROUND
- * s2v_profile_end waits for the stream and returns, per kind, the number of bracketed launches
- * and the sum of their durations in milliseconds (host arrays of S2V_PROFILE_KINDS elements).
+ * Optional live timing of the main kernels (for benchmarks; not part of the method).
+ * Between s2v_profile_begin and s2v_profile_end the launches listed below are bracketed by HIP events on
+ * the context's stream, up to max_launches spans in total.  Kinds:
+ *   S2V_PROFILE_FWD_ROUND      rounds 3..T of Eq. 1 inside s2v_embed_fwd (neighbour rows read from memory)
+ *   S2V_PROFILE_BWD_ROUND      a reversed round that gathers rows of dz (inside s2v_embed_bwd); for 16-state
+ *                              blocks and T >= 4 the launch of round t = 3 also does round t = 2 on each tile
+ *   S2V_PROFILE_FWD_ROUND2     round 2 of Eq. 1 (neighbour rows recomputed from per-node scalars)
+ *   S2V_PROFILE_FWD_ROUND_Q    a last round with more fused into it: the node term of Eq. 2 (inside
+ *                              s2v_policy_eval) or relu-mask words instead of its rows (inside s2v_loss_grad);
+ *                              such a launch is not counted under S2V_PROFILE_FWD_ROUND
+ *   S2V_PROFILE_BWD_ROUND_MASK the first reversed round (t = T), which gathers relu-mask words
+ *   S2V_PROFILE_BWD_FIRST      the stand-alone last reversed round from per-node scalars (16-state blocks, T = 3)
+ *   S2V_PROFILE_BWD_SEED       the kernel that forms dz^T's relu mask and its share of the parameter sums
+ *   S2V_PROFILE_SELECT         all kernels of one s2v_select_topk call, as one span
+ * s2v_profile_end waits for the stream and returns, per kind, the number of spans and the sum of their
+ * durations in milliseconds (host arrays of S2V_PROFILE_KINDS elements).
  */
 #define S2V_PROFILE_FWD_ROUND 0
 #define S2V_PROFILE_BWD_ROUND 1
 #define S2V_PROFILE_FWD_ROUND2 2
 #define S2V_PROFILE_FWD_ROUND_Q 3
-#define S2V_PROFILE_KINDS 4
+#define S2V_PROFILE_BWD_ROUND_MASK 4
+#define S2V_PROFILE_BWD_FIRST 5
+#define S2V_PROFILE_BWD_SEED 6
+#define S2V_PROFILE_SELECT 7
+#define S2V_PROFILE_KINDS 8
 int32_t s2v_profile_begin(s2v_ctx *ctx, int32_t max_launches);
 int32_t s2v_profile_end(s2v_ctx *ctx, int32_t *n_launches, float *total_ms);
+
+/*
+ * Read-only streaming probe (for benchmarks; not part of the method): loads every 16-byte word of the
+ * device range [src, src + bytes) once, fully coalesced, and writes 4096 partial float sums to `out`
+ * (device, 4096 floats).  Timed by the caller, it gives the rate at which this GPU streams memory that
+ * is only read -- the ceiling to hold the gather rounds against.  src 16-byte aligned, bytes a multiple of 16.
+ */
+int32_t s2v_stream_read(s2v_ctx *ctx, const void *src, size_t bytes, float *out);
 
 /*
  * Host helper: the adaptive number of nodes to select per policy evaluation (Sec. 4.5.1):

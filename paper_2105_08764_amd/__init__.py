@@ -26,13 +26,15 @@ S2V_ERR_TOO_LARGE = -7
 S2V_NOALLOC_MAX_NODES = 1 << 22
 S2V_NOALLOC_MAX_K = 1 << 18
 
+PROFILE_KINDS = ("fwd_round", "bwd_round", "fwd_round2", "fwd_round_q", "bwd_round_mask", "bwd_first", "bwd_seed",
+                 "select")
 THETA_NAMES = ("theta1", "theta2", "theta3", "theta4", "theta5", "theta6", "theta7")
 EXPORTS = (
     "s2v_status_str", "s2v_create", "s2v_destroy", "s2v_last_hip_error", "s2v_workspace_bytes",
     "s2v_graph_prepare", "s2v_embed_fwd", "s2v_q_score", "s2v_select_topk", "s2v_embed_bwd",
     "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end", "s2v_residual_update",
     "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target", "s2v_policy_eval", "s2v_loss_grad",
-    "s2v_select_topk_noalloc",
+    "s2v_select_topk_noalloc", "s2v_set_sliced_min_bytes", "s2v_stream_read",
 )
 
 
@@ -307,12 +309,19 @@ class Context:
         _check(self.lib.s2v_profile_begin(self.handle, ctypes.c_int32(max_launches)), "s2v_profile_begin")
 
     def s2v_profile_end(self):
-        """[(launches, total ms)] for the kinds fwd round (from memory), bwd round, fwd round 2, and
-        last fwd round with the node term of Eq. 2 fused in."""
-        n = (ctypes.c_int32 * 4)()
-        ms = (ctypes.c_float * 4)()
+        """{kind name: (spans, total ms)} for the kinds of include/s2v.h (S2V_PROFILE_*)."""
+        n = (ctypes.c_int32 * len(PROFILE_KINDS))()
+        ms = (ctypes.c_float * len(PROFILE_KINDS))()
         _check(self.lib.s2v_profile_end(self.handle, n, ms), "s2v_profile_end")
-        return [(int(n[i]), float(ms[i])) for i in range(4)]
+        return {name: (int(n[i]), float(ms[i])) for i, name in enumerate(PROFILE_KINDS)}
+
+    def s2v_set_sliced_min_bytes(self, nbytes: int) -> None:
+        _check(self.lib.s2v_set_sliced_min_bytes(self.handle, ctypes.c_size_t(nbytes)), "s2v_set_sliced_min_bytes")
+
+    def s2v_stream_read(self, src, out) -> None:
+        _check(self.lib.s2v_stream_read(self.handle, ctypes.c_void_p(_dp(src)),
+                                        ctypes.c_size_t(src.numel() * src.element_size()),
+                                        ctypes.c_void_p(_dp(out))), "s2v_stream_read")
 
     def s2v_sgd_step(self, params: Params, grads: Params, lr: float) -> None:
         _check(self.lib.s2v_sgd_step(self.handle, ctypes.byref(params.c), ctypes.byref(grads.c), ctypes.c_float(lr)),

@@ -17,6 +17,7 @@ struct Prepared {
     const void *ws;
     const int32_t *rowptr;
     const int32_t *colidx;
+    const float *w;      // the edge sums in the head of ws were formed from these weights
     int32_t N;
     int64_t nnz;
     int32_t G;
@@ -246,7 +247,7 @@ struct s2v_ctx {
     // with S = 16, p = 64: 2.39 against 2.63 ms per round for a 1 GB matrix (node by node is faster),
     // 5.62 against 5.16 ms at 2 GB, 12.3 against 11.2 ms at 4 GB.  The two orders add the neighbours in a
     // different sequence, so their results differ in the last float32 bits.
-    // Environment variable S2V_SLICED_MIN_BYTES, read by s2v_create, overrides the default.
+    // s2v_set_sliced_min_bytes overrides the default.
     size_t sliced_min_bytes = (size_t)3 << 29;
     // optional timing of the two gather kernels (s2v_profile_begin / s2v_profile_end)
     bool profiling = false;
@@ -311,7 +312,7 @@ const int32_t *row_end_of(const s2v_graph *g) { return g->row_end ? g->row_end :
 
 const Prepared *find_prepared(const s2v_ctx *ctx, const s2v_graph *g, const void *ws) {
     for (const Prepared &pr : ctx->prepared)
-        if (pr.ws == ws && pr.rowptr == g->rowptr && pr.colidx == g->colidx && pr.N == g->n_nodes &&
+        if (pr.ws == ws && pr.rowptr == g->rowptr && pr.colidx == g->colidx && pr.w == g->w && pr.N == g->n_nodes &&
             pr.nnz == g->nnz && pr.G == g->n_graphs)
             return &pr;
     return nullptr;
@@ -383,11 +384,6 @@ int32_t s2v_create(void *hip_stream, s2v_ctx **out) {
     } else {
         (void)hipGetLastError();
     }
-    if (const char *e = std::getenv("S2V_SLICED_MIN_BYTES")) {
-        char *end = nullptr;
-        const unsigned long long v = std::strtoull(e, &end, 10);
-        if (end && end != e && *end == '\0') ctx->sliced_min_bytes = (size_t)v;
-    }
     *out = ctx;
     return S2V_OK;
 }
@@ -447,6 +443,18 @@ int32_t s2v_profile_end(s2v_ctx *ctx, int32_t *n_launches, float *total_ms) {
 }
 
 int32_t s2v_last_hip_error(const s2v_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+int32_t s2v_set_sliced_min_bytes(s2v_ctx *ctx, size_t bytes) {
+    if (!ctx) return S2V_ERR_INVALID_ARG;
+    ctx->sliced_min_bytes = bytes;
+    return S2V_OK;
+}
+
+int32_t s2v_stream_read(s2v_ctx *ctx, const void *src, size_t bytes, float *out) {
+    if (!ctx || !src || !out || (bytes & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u)) return S2V_ERR_INVALID_ARG;
+    S2V_TRY(launch_stream_read(ctx->stream, src, bytes, out));
+    return S2V_OK;
+}
 
 int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t T, int32_t S, int32_t k_max,
                             int32_t training, size_t *out) {
@@ -566,7 +574,7 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
     S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
 
-    Prepared pr{ws, g->rowptr, g->colidx, N, g->nnz, G, n_chunks, n_hubs, n_segs, has_neg != 0};
+    Prepared pr{ws, g->rowptr, g->colidx, g->w, N, g->nnz, G, n_chunks, n_hubs, n_segs, has_neg != 0};
     for (Prepared &old : ctx->prepared)
         if (old.ws == ws) { old = pr; return S2V_OK; }
     ctx->prepared.push_back(pr);
@@ -753,6 +761,7 @@ int32_t s2v_select_topk(s2v_ctx *ctx, const s2v_graph *g, const float *q, const 
     sc.ids[0] = at<int32_t>(ws, sl.ids0);
     sc.ids[1] = at<int32_t>(ws, sl.ids1);
     sc.sort_cnt = at<uint32_t>(ws, sl.sort_cnt);
+    SpanGuard span(ctx, S2V_PROFILE_SELECT);   // the whole chain of selection kernels as one span
     if (k == 1) {
         const ChunkTable ct = chunk_table(ws, h, *pr);
         S2V_TRY(launch_argmax(ctx->stream, N, G, ct, q, x, cand, sc, idx, val, count));
@@ -868,8 +877,11 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
                                 by_flags ? at<float>(ws, wagg ? h.nbr_spw : h.nbr_sp) : nullptr, flags));
     NodeInfo ninfo = make_nodeinfo(sc.rec, S, x_res != nullptr);
     ninfo.flags16 = reinterpret_cast<const unsigned short *>(flags);
-    S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part,
-                             words_ready));
+    {
+        SpanGuard span(ctx, S2V_PROFILE_BWD_SEED);
+        S2V_TRY(launch_bwd_maskT(st, p, N, S, muT, ninfo, x_res, action, sc, T >= 2 ? sc.maskT : nullptr, sc.dc_part,
+                                 words_ready));
+    }
     float *hub_part = at<float>(ws, bl.hub_part), *hub_sum = at<float>(ws, bl.hub_sum);
     float *hub_part4 = at<float>(ws, bl.hub_part4), *hub_sum4 = at<float>(ws, bl.hub_sum4);
     const bool node = S % 16 == 0 && N > 0;
@@ -896,7 +908,7 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
             S2V_TRY(launch_hub_sums_grad(st, p, S, ht, row_end_of(g), g->colidx, wagg, ninfo, pr->has_neg, params->theta1,
                                          qvec, hub_part4, hub_sum4));
             {
-                SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
+                SpanGuard span(ctx, S2V_PROFILE_BWD_FIRST);
                 S2V_TRY(launch_bwd_first(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, ninfo, pr->has_neg,
                                          params->theta1, params->theta2, qvec, dc_part, d2_part, ht, hub_sum4));
             }
@@ -916,7 +928,7 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
         S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, dz_in, ninfo, nullptr, nullptr, first ? sc.maskT : nullptr,
                                 hub_part, hub_sum));
         {
-            SpanGuard span(ctx, S2V_PROFILE_BWD_ROUND);
+            SpanGuard span(ctx, first ? S2V_PROFILE_BWD_ROUND_MASK : S2V_PROFILE_BWD_ROUND);
             S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
                                      dz_out, ninfo, params->theta2, dc_part, d2_part, ht, hub_sum, fuse_last ? &bf : nullptr));
         }

@@ -1106,4 +1106,34 @@ hipError_t launch_qnode(hipStream_t st, int p, int N, int S, int G, const int32_
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Read-only streaming probe for benchmarks: every 16-byte word of [src, src + bytes) is loaded once,
+// fully coalesced, and folded into one float per workgroup (so the loads cannot be dropped).  Gives the
+// rate at which this GPU streams memory it only reads, the comparable ceiling for the gather rounds.
+// ------------------------------------------------------------------------------------------
+constexpr int kStreamReadGrid = 256 * 16;
+__global__ __launch_bounds__(256) void k_stream_read(const float4 *__restrict__ src, size_t n16, float *__restrict__ out) {
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a, c = a, d = a;
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const float4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+        a = add4(a, v0); b = add4(b, v1); c = add4(c, v2); d = add4(d, v3);
+    }
+    for (; i < n16; i += stride) a = add4(a, src[i]);
+    a = add4(add4(a, b), add4(c, d));
+    float s = (a.x + a.y) + (a.z + a.w);
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) s += __shfl_xor(s, m);
+    __shared__ float red[4];
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) out[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+hipError_t launch_stream_read(hipStream_t st, const void *src, size_t bytes, float *out /*[kStreamReadGrid]*/) {
+    k_stream_read<<<kStreamReadGrid, 256, 0, st>>>(static_cast<const float4 *>(src), bytes / 16, out);
+    return hipGetLastError();
+}
+
 }  // namespace s2v

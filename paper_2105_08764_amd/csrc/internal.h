@@ -166,6 +166,9 @@ hipError_t launch_qa(hipStream_t st, int p, int S, int G, const float *theta5, c
 hipError_t launch_qnode(hipStream_t st, int p, int N, int S, int G, const int32_t *graph_off, const float *theta5,
                         const float *theta7, const float *mu, const float *qa, float *q /*[S][N]*/);
 
+// read-only streaming probe (benchmarks): out receives 4096 floats
+hipError_t launch_stream_read(hipStream_t st, const void *src, size_t bytes, float *out);
+
 // ---- state update of the inference loop (residual_kernels.hip) ----
 hipError_t launch_residual_update(hipStream_t st, int N, int G, const int32_t *graph_off, const int32_t *rowptr,
                                   int32_t *rowend, int32_t *colidx, float *w, float *x, const int32_t *sel_idx,

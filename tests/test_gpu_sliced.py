@@ -1,7 +1,5 @@
-"""The state-by-state row order of the embedding rounds (chosen by size; forced here through the
-environment variable that s2v_create reads) against the oracle and against the node-by-node order."""
-import os
-
+"""The state-by-state row order of the embedding rounds (chosen by size; forced here through
+s2v_set_sliced_min_bytes) against the oracle and against the node-by-node order."""
 import numpy as np
 import pytest
 
@@ -14,19 +12,8 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-4
 
 
-@pytest.fixture
-def sliced_env():
-    old = os.environ.get("S2V_SLICED_MIN_BYTES")
-    os.environ["S2V_SLICED_MIN_BYTES"] = "0"
-    yield
-    if old is None:
-        del os.environ["S2V_SLICED_MIN_BYTES"]
-    else:
-        os.environ["S2V_SLICED_MIN_BYTES"] = old
-
-
 @pytest.mark.parametrize("kind,p,T,S", [("er", 64, 4, 16), ("ba", 32, 3, 32), ("batch", 64, 5, 16), ("hub", 64, 4, 16)])
-def test_sliced_forward_matches_oracle(oracle_mod, sliced_env, kind, p, T, S):
+def test_sliced_forward_matches_oracle(oracle_mod, kind, p, T, S):
     print(f"case sliced forward kind={kind} p={p} T={T} S={S}", flush=True)
     if kind == "hub":
         g = si.star_graph(700)             # one row far beyond the long-row threshold
@@ -36,6 +23,7 @@ def test_sliced_forward_matches_oracle(oracle_mod, sliced_env, kind, p, T, S):
     x = si.node_flags(g.n, 0.1, 4, n_states=S)
     theta = si.thetas(p, 11 + p + T, 0.05)
     dev = gu.Device(g, p, T, S=S)
+    dev.ctx.s2v_set_sliced_min_bytes(0)
     out = dev.forward(theta, x, save=True)
     for s in range(S):
         mu, gsum, q = gu.oracle_forward(oracle_mod, g, theta, x[s], T)
@@ -45,11 +33,12 @@ def test_sliced_forward_matches_oracle(oracle_mod, sliced_env, kind, p, T, S):
     assert np.array_equal(out["saved"][T - 1], out["mu"])
 
 
-def test_sliced_training_matches_oracle_and_single_call(oracle_mod, sliced_env):
+def test_sliced_training_matches_oracle_and_single_call(oracle_mod):
     kind, p, T, S = "ba", 64, 4, 16
     g, x, action, target = tc.inputs(kind, S)
     theta = si.thetas(p, tc.stored_seeds()[(kind, p, T, S)], tc.theta_scale(kind))
     dev = gu.Device(g, p, T, S=S, training=True)
+    dev.ctx.s2v_set_sliced_min_bytes(0)
     prm = dev.params(theta)
     loss2, qp2, grads2 = dev.train_iter(prm, x, action, target)
     loss1, qp1, grads1, _ = dev.loss_grad(prm, x, action, target)
