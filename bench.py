@@ -231,8 +231,9 @@ def time_policy_steps(ctx, s2v, torch, graph, prm, x, N, p, T, k, G, steps, warm
     cnt = torch.empty((G,), dtype=torch.int32, device="cuda")
 
     def step():
-        ctx.s2v_policy_eval(graph, prm, x, T, 1, mu, gsum, q, ws)
-        ctx.s2v_select_topk(graph, q[0], x[0], None, k, idx, val, cnt, ws)
+        # embed + score + select as one call: one kernel launch when every graph fits a compute unit's LDS
+        # (configurations 1 and 2), else s2v_policy_eval followed by s2v_select_topk
+        ctx.s2v_policy_select(graph, prm, x[0], None, T, k, mu, gsum, q, idx, val, cnt, ws)
 
     for _ in range(warmup):
         step()

@@ -191,6 +191,24 @@ int32_t s2v_policy_eval(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *para
                         int32_t S, float *mu_out, float *gsum, float *q, void *ws, size_t ws_bytes);
 
 /*
+ * One step of Alg. 3 up to the choice of nodes (lines 5-7: embed, score, select) for ONE state in a single
+ * call: s2v_policy_eval with S == 1 followed by s2v_select_topk on its scores, with the arguments of the
+ * two (x [N], cand [N] bytes or NULL; mu_out [N][p], gsum [G][p], q [N], idx [G][k], val [G][k], count [G]:
+ * all outputs required).  When every graph of the batch is small enough for its embedding to stay in the
+ * on-chip memory of one compute unit (n_nodes of the largest graph times p at most 32768: 1024 nodes at
+ * p = 32, 512 at p = 64), k <= 8 and the plain neighbour sum on the stored graph is asked for
+ * (weighted_sum == 0, state_residual == 0), the whole step is ONE kernel launch with one workgroup per
+ * graph: at those sizes the separate launches of the general path cost more than the arithmetic.  That
+ * kernel adds a row's neighbours in another order than the general round kernels, so mu_out, gsum and q
+ * then agree with s2v_policy_eval's up to float32 rounding (not bit for bit); given q, the selection is
+ * the same exact function of the scores.  For any other shape the call IS the two calls in sequence.
+ * Supported: (G >= 1, k == 1) and (G == 1, k >= 1).  Errors: as s2v_policy_eval and s2v_select_topk.
+ */
+int32_t s2v_policy_select(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x,
+                          const uint8_t *cand, int32_t T, int32_t k, float *mu_out, float *gsum, float *q, int32_t *idx,
+                          float *val, int32_t *count, void *ws, size_t ws_bytes);
+
+/*
  * Node selection for one state: per graph, the k candidates with the highest scores,
  * ordered by score descending and node index ascending among equal scores (k == 1 is
  * the argmax of Alg. 3 line 7; k > 1 is the top-d selection of Sec. 4.5.1).
@@ -339,7 +357,8 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
  *   S2V_PROFILE_BWD_ROUND_MASK the first reversed round (t = T), which gathers relu-mask words
  *   S2V_PROFILE_BWD_FIRST      the stand-alone last reversed round from per-node scalars (16-state blocks, T = 3)
  *   S2V_PROFILE_BWD_SEED       the kernel that forms dz^T's relu mask and its share of the parameter sums
- *   S2V_PROFILE_SELECT         all kernels of one s2v_select_topk call, as one span
+ *   S2V_PROFILE_SELECT         all kernels of one s2v_select_topk call, as one span (the single launch of
+ *                              s2v_policy_select on small graphs is counted here too)
  * s2v_profile_end waits for the stream and returns, per kind, the number of spans and the sum of their
  * durations in milliseconds (host arrays of S2V_PROFILE_KINDS elements).
  */

@@ -35,6 +35,7 @@ EXPORTS = (
     "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end", "s2v_residual_update",
     "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target", "s2v_policy_eval", "s2v_loss_grad",
     "s2v_select_topk_noalloc", "s2v_set_sliced_min_bytes", "s2v_stream_read",
+    "s2v_policy_select",
 )
 
 
@@ -234,6 +235,19 @@ class Context:
                                         ctypes.c_void_p(_dp(idx)), ctypes.c_void_p(_dp(val)),
                                         ctypes.c_void_p(_dp(count)), ctypes.c_void_p(_dp(ws)),
                                         ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_select_topk")
+
+    def s2v_policy_select(self, g: Graph, params: Params, x, cand, T: int, k: int, mu_out, gsum, q, idx, val, count,
+                          ws) -> None:
+        _want(x, "float32", "x")
+        _want(idx, "int32", "idx")
+        _want(count, "int32", "count")
+        _want(cand, "uint8", "cand")
+        _check(self.lib.s2v_policy_select(self.handle, ctypes.byref(g.c), ctypes.byref(params.c),
+                                          ctypes.c_void_p(_dp(x)), ctypes.c_void_p(_dp(cand)), ctypes.c_int32(T),
+                                          ctypes.c_int32(k), ctypes.c_void_p(_dp(mu_out)), ctypes.c_void_p(_dp(gsum)),
+                                          ctypes.c_void_p(_dp(q)), ctypes.c_void_p(_dp(idx)), ctypes.c_void_p(_dp(val)),
+                                          ctypes.c_void_p(_dp(count)), ctypes.c_void_p(_dp(ws)),
+                                          ctypes.c_size_t(ws.numel() * ws.element_size())), "s2v_policy_select")
 
     def s2v_select_topk_noalloc(self, n_nodes: int, q, x, cand, k: int, idx, val, count) -> None:
         _want(idx, "int32", "idx")

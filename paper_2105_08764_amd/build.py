@@ -13,7 +13,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs2v.so")
-SOURCES = ["api.hip", "fwd_kernels.hip", "select_kernels.hip", "bwd_kernels.hip", "residual_kernels.hip"]
+SOURCES = ["api.hip", "fwd_kernels.hip", "select_kernels.hip", "bwd_kernels.hip", "residual_kernels.hip",
+           "small_kernels.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950",

@@ -25,6 +25,7 @@ struct Prepared {
     int32_t n_hubs;
     int32_t n_segs;
     bool has_neg;   // some stored weight is negative
+    int32_t max_graph_nodes;   // nodes of the largest graph of the batch
 };
 
 // Carves consecutive 256-byte aligned pieces out of a byte range.
@@ -238,6 +239,7 @@ struct ProfSpan {
 struct s2v_ctx {
     hipStream_t stream;
     int32_t last_hip;
+    size_t max_lds_per_block = 0;  // of the device that was current in s2v_create
     int device = -1;               // the device that was current in s2v_create
     void *noalloc_scratch = nullptr;   // that device's copy of the library-owned scratch array
     std::vector<Prepared> prepared;
@@ -372,7 +374,14 @@ int32_t s2v_create(void *hip_stream, s2v_ctx **out) {
     // this device's copy of the scratch array of s2v_select_topk_noalloc, looked up once per device
     // (the symbol is named here, in a function with external linkage: the device-side compilation keeps a
     //  file-scope device variable visible to the runtime only when such a function refers to it)
-    if (hipGetDevice(&ctx->device) == hipSuccess && ctx->device >= 0 && ctx->device < kMaxDevices) {
+    if (hipGetDevice(&ctx->device) == hipSuccess) {
+        int lds = 0;
+        if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, ctx->device) == hipSuccess && lds > 0)
+            ctx->max_lds_per_block = (size_t)lds;
+        else
+            (void)hipGetLastError();
+    }
+    if (ctx->device >= 0 && ctx->device < kMaxDevices) {
         std::lock_guard<std::mutex> lock(g_scratch_mutex);
         if (!g_scratch_ptr[ctx->device]) {
             void *ptr = nullptr;
@@ -477,6 +486,8 @@ int32_t s2v_workspace_bytes(s2v_ctx *ctx, const s2v_graph *g, int32_t p, int32_t
     const size_t s_end = sel_layout(h, g->n_nodes, k_max > 0 ? k_max : 1).end;
     if (q_end > need) need = q_end;
     if (s_end > need) need = s_end;
+    const size_t sm_end = align_up(h.end) + align_up(sizeof(float) * (size_t)g->n_nodes * p);   // s2v_policy_select
+    if (sm_end > need) need = sm_end;
     const size_t t_end = align_up(align_up(h.end) + align_up(sizeof(float) * (size_t)S * h.max_chunks) +
                                   sizeof(int32_t) * (size_t)S * h.max_chunks);
     if (t_end > need) need = t_end;
@@ -574,7 +585,10 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
     S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
 
-    Prepared pr{ws, g->rowptr, g->colidx, g->w, N, g->nnz, G, n_chunks, n_hubs, n_segs, has_neg != 0};
+    int32_t max_graph_nodes = 0;
+    for (int b = 0; b < G; ++b)
+        if (off[b + 1] - off[b] > max_graph_nodes) max_graph_nodes = off[b + 1] - off[b];
+    Prepared pr{ws, g->rowptr, g->colidx, g->w, N, g->nnz, G, n_chunks, n_hubs, n_segs, has_neg != 0, max_graph_nodes};
     for (Prepared &old : ctx->prepared)
         if (old.ws == ws) { old = pr; return S2V_OK; }
     ctx->prepared.push_back(pr);
@@ -706,6 +720,44 @@ int32_t s2v_policy_eval(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *para
     float *qa = at<float>(ws, ql.qa);
     S2V_TRY(launch_qa(ctx->stream, params->p, S, G, params->theta5, params->theta6, gsum, qa));
     S2V_TRY(launch_qfinish(ctx->stream, N, S, G, g->graph_off, qa, q));
+    return S2V_OK;
+}
+
+int32_t s2v_policy_select(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x,
+                          const uint8_t *cand, int32_t T, int32_t k, float *mu_out, float *gsum, float *q, int32_t *idx,
+                          float *val, int32_t *count, void *ws, size_t ws_bytes) {
+    if (!ctx || !g || !params) return S2V_ERR_INVALID_ARG;
+    if (k < 1 || !idx || !val || !count || !gsum) return S2V_ERR_INVALID_ARG;
+    if (g->n_graphs > 1 && k > 1) return S2V_ERR_UNSUPPORTED;
+    const Prepared *pr = check_ws(ws) == S2V_OK ? find_prepared(ctx, g, ws) : nullptr;
+    // One launch for the whole step when every graph's embedding fits the LDS of a compute unit
+    // (see small_kernels.hip); plain neighbour sum on the stored graph only.
+    const bool small = pr && p_supported(params->p) && check_params(params) == S2V_OK && T >= 1 && g->n_nodes > 0 &&
+                       (int64_t)pr->max_graph_nodes * params->p <= kSmallLdsFloats && k <= kSmallK &&
+                       !g->weighted_sum && !g->state_residual && ctx->max_lds_per_block >= kSmallLdsBytes && x && mu_out &&
+                       q;
+    if (!small) {
+        int32_t rc = s2v_policy_eval(ctx, g, params, x, T, 1, mu_out, gsum, q, ws, ws_bytes);
+        if (rc != S2V_OK) return rc;
+        return s2v_select_topk(ctx, g, q, x, cand, k, idx, val, count, ws, ws_bytes);
+    }
+    const int32_t N = g->n_nodes, G = g->n_graphs, p = params->p;
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
+    const size_t agg_off = align_up(h.end);
+    if (ws_bytes < agg_off + sizeof(float) * (size_t)N * p) return S2V_ERR_WORKSPACE_TOO_SMALL;
+    SmallPolicyArgs a;
+    a.N = N; a.G = G; a.T = T; a.k = k;
+    a.graph_off = G > 1 ? g->graph_off : nullptr;
+    a.rowptr = g->rowptr; a.rowend = row_end_of(g); a.colidx = g->colidx;
+    a.x = x; a.s_pos = at<float>(ws, h.s_pos); a.s_neg = at<float>(ws, h.s_neg);
+    a.cand = cand;
+    a.theta1 = params->theta1; a.theta2 = params->theta2; a.theta3 = params->theta3; a.theta4 = params->theta4;
+    a.theta5 = params->theta5; a.theta6 = params->theta6; a.theta7 = params->theta7;
+    a.agg = at<float>(ws, agg_off);
+    a.mu_out = mu_out; a.gsum = gsum; a.q = q;
+    a.idx = idx; a.val = val; a.count = count;
+    SpanGuard span(ctx, S2V_PROFILE_SELECT);
+    S2V_TRY(launch_small_policy(ctx->stream, p, a));
     return S2V_OK;
 }
 
@@ -1034,9 +1086,7 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     int64_t picked = 0;
     while (n_live > 0 && steps < max_steps) {
         const int32_t d = (adaptive && G == 1) ? s2v_adaptive_d(n_cand, N) : 1;
-        rc = s2v_policy_eval(ctx, g, params, x, T, 1, mu, gsum, q, ws, ws_bytes);
-        if (rc != S2V_OK) return rc;
-        rc = s2v_select_topk(ctx, g, q, x, cand, d, sel_idx, sel_val, sel_count, ws, ws_bytes);
+        rc = s2v_policy_select(ctx, g, params, x, cand, T, d, mu, gsum, q, sel_idx, sel_val, sel_count, ws, ws_bytes);
         if (rc != S2V_OK) return rc;
         S2V_TRY(hipMemcpyAsync(hcount.data(), sel_count, sizeof(int32_t) * G, hipMemcpyDeviceToHost, ctx->stream));
         rc = s2v_residual_update(ctx, g, x, sel_idx, sel_count, d, cand, stats, ws, ws_bytes);

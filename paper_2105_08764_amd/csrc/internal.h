@@ -177,6 +177,26 @@ hipError_t launch_residual_update(hipStream_t st, int N, int G, const int32_t *g
                                   int32_t *list /*[N+1]*/);
 hipError_t launch_zero_i32(hipStream_t st, long n, int32_t *p);
 
+// ---- one launch per step of Alg. 3 on small graphs (small_kernels.hip) ----
+// floats of LDS that hold one graph's embedding: a graph qualifies when n_nodes * p does not exceed it
+constexpr int kSmallLdsFloats = 32768;
+// LDS bytes per workgroup the kernel needs (its static arrays, rounded up)
+constexpr size_t kSmallLdsBytes = 160 * 1024;
+struct SmallPolicyArgs {
+    int N, G, T, k;                       // k: nodes to select per graph (with idx != NULL)
+    const int32_t *graph_off;             // [G+1] or NULL (one graph)
+    const int32_t *rowptr, *rowend, *colidx;
+    const float *x, *s_pos, *s_neg;       // [N] each
+    const uint8_t *cand;                  // [N] or NULL (candidates: x == 0)
+    const float *theta1, *theta2, *theta3, *theta4, *theta5, *theta6, *theta7;
+    float *agg;                           // [N][p] scratch: the neighbour sums of the current round
+    float *mu_out, *gsum, *q;             // [N][p], [G][p], [N]
+    int32_t *idx;                         // [G][k] or NULL: no selection
+    float *val;                           // [G][k]
+    int32_t *count;                       // [G]
+};
+hipError_t launch_small_policy(hipStream_t st, int p, const SmallPolicyArgs &a);
+
 // ---- selection (select_kernels.hip) ----
 struct SelectScratch {
     float *part_val;    // [n_chunks][kSmallK]

@@ -5,26 +5,9 @@
 #include <limits.h>
 
 #include "internal.h"
+#include "select_util.h"
 
 namespace s2v {
-
-__device__ __forceinline__ bool is_candidate(const float *__restrict__ x, const uint8_t *__restrict__ cand, int v) {
-    return cand ? (cand[v] != 0) : (x[v] == 0.f);
-}
-
-// Order-preserving map float -> uint32 (larger score = larger key); -0.0 is folded onto +0.0.
-__device__ __forceinline__ uint32_t score_key(float q) {
-    const uint32_t b = __float_as_uint(q + 0.0f);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-__device__ __forceinline__ float key_score(uint32_t k) {
-    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
-}
-
-// (val, idx) beats (val2, idx2) if the score is higher, or equal with a lower node index.
-__device__ __forceinline__ void take_better(float &val, int &idx, float val2, int idx2) {
-    if (val2 > val || (val2 == val && idx2 < idx)) { val = val2; idx = idx2; }
-}
 
 __device__ __forceinline__ void block_best(float &val, int &idx, float *sval, int *sidx) {
 #pragma unroll
@@ -97,9 +80,6 @@ hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, con
 // ascending) is total, so "the next best" is "the best entry that the last pick beats": stage 1
 // finds the k best candidates of every chunk that way, stage 2 the k best of those.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ bool beats(float va, int ia, float vb, int ib) {
-    return va > vb || (va == vb && ia < ib);
-}
 
 // Broadcasts thread 0's (val, idx) after block_best to the whole workgroup.
 __device__ __forceinline__ void share_best(float &val, int &idx, float *sval, int *sidx) {

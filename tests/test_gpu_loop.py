@@ -146,11 +146,11 @@ def test_native_loop_matches_stepwise_run_and_covers(oracle_mod, kind, adaptive)
     steps = 0
     while stats[:, 1].sum() > 0:
         d = dev.s2v.s2v_adaptive_d(int(stats[0, 0]), g.n) if (adaptive and G == 1) else 1
-        dev.ctx.s2v_embed_fwd(dev.graph, prm, dev.x.view(1, -1), T, 1, dev.mu, None, dev.gsum, dev.ws)
-        dev.ctx.s2v_q_score(dev.graph, prm, dev.mu, dev.gsum, 1, dev.q, dev.ws)
         idx = torch.full((G, d), -1, dtype=torch.int32, device="cuda")
         val = torch.empty((G, d), device="cuda")
-        dev.ctx.s2v_select_topk(dev.graph, dev.q[0], dev.x, dev.cand, d, idx, val, dev.sel_cnt, dev.ws)
+        # (the call the native driver makes: embed, score and select as one step)
+        dev.ctx.s2v_policy_select(dev.graph, prm, dev.x, dev.cand, T, d, dev.mu, dev.gsum, dev.q, idx, val, dev.sel_cnt,
+                                  dev.ws)
         torch.cuda.synchronize()
         x_np = dev.x.cpu().numpy().astype(np.float64)
         rp, ci, ww = oracle_mod.residual_graph(g.rowptr, g.colidx, g.w, x_np)
