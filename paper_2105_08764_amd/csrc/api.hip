@@ -149,8 +149,9 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     BwdLayout b;
     Carver c(h.end);
     // partial rows: the mask/seed kernel, every reversed round, and the action-node fix-up
-    b.dc_rows = kBwdHeadGrid + (T - 1) * kBwdGrid + (T >= 2 ? S * kFixSplit : 0);
-    b.d2_rows = (T - 1) * kBwdGrid + (T >= 2 ? S * kFixSplit : 0);
+    // (a reversed round keeps a compensated pair of rows per workgroup: kBwdRoundRows = 2 * kBwdGrid)
+    b.dc_rows = kBwdHeadGrid + (T - 1) * kBwdRoundRows + (T >= 2 ? S * kFixSplit : 0);
+    b.d2_rows = (T - 1) * kBwdRoundRows + (T >= 2 ? S * kFixSplit : 0);
     const size_t width = (size_t)(3 * p > p * p ? 3 * p : p * p);
     const size_t segs = (size_t)(b.dc_rows + 63) / 64;
     b.dg = c.take(sizeof(float) * (size_t)S * p);
@@ -940,8 +941,8 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     int cur = 1;  // the round t = T writes dz[0]
     for (int t = T; t >= 2; --t) {
         const int slot = T - t;  // 0 for the first reversed round
-        float *dc_part = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)slot * kBwdGrid) * 3 * p;
-        float *d2_part = sc.d2_part + (size_t)slot * kBwdGrid * p * p;
+        float *dc_part = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)slot * kBwdRoundRows) * 3 * p;
+        float *d2_part = sc.d2_part + (size_t)slot * kBwdRoundRows * p * p;
         const float *mu_prev = mu_saved + (size_t)(t - 2) * nsp;
         const bool first = t == T;
         const float *dz_in = first ? nullptr : sc.dz[cur];
@@ -949,8 +950,8 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
         float *qvec = at<float>(ws, bl.qvec);
         if (t == 2 && !first && node && T >= 4) {
             // done inside the round t = 3 (see below): this round's partial rows stay empty
-            S2V_TRY(launch_zero_i32(st, (long)kBwdGrid * 3 * p, reinterpret_cast<int32_t *>(dc_part)));
-            S2V_TRY(launch_zero_i32(st, (long)kBwdGrid * p * p, reinterpret_cast<int32_t *>(d2_part)));
+            S2V_TRY(launch_zero_i32(st, (long)kBwdRoundRows * 3 * p, reinterpret_cast<int32_t *>(dc_part)));
+            S2V_TRY(launch_zero_i32(st, (long)kBwdRoundRows * p * p, reinterpret_cast<int32_t *>(d2_part)));
             continue;
         }
         if (t == 2 && !first && node) {
@@ -985,8 +986,8 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
                                      dz_out, ninfo, params->theta2, dc_part, d2_part, ht, hub_sum, fuse_last ? &bf : nullptr));
         }
         if (first) {
-            float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdGrid) * 3 * p;
-            float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdGrid * p * p;
+            float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdRoundRows) * 3 * p;
+            float *d2_fix = sc.d2_part + (size_t)(T - 1) * kBwdRoundRows * p * p;
             S2V_TRY(launch_bwd_action_fix(st, p, S, g->rowptr, row_end_of(g), g->colidx, wagg, action, sc.maskT, sc, params->theta2,
                                           mu_prev, dz_out, ninfo, dc_fix, d2_fix));
         }

@@ -258,6 +258,22 @@ hipError_t launch_bwd_maskT(hipStream_t st, int p, int N, int S, const float *mu
     return hipGetLastError();
 }
 
+// *hi + *lo += v without losing the rounding error of the addition (the exact remainder of h + v goes to lo).
+// first: the pair is uninitialised and becomes (v, 0).
+__device__ __forceinline__ void comp_add(float *hi, float *lo, float v, bool first) {
+    if (first) {
+        *hi = v;
+        *lo = 0.f;
+        return;
+    }
+    const float h = *hi;
+    const float s = h + v;
+    const float bb = s - h;
+    const float err = (h - (s - bb)) + (v - bb);
+    *hi = s;
+    *lo = *lo + err;
+}
+
 // ------------------------------------------------------------------------------------------
 // One reversed round t (T >= t >= 2), fused: G = A dz^t (same gathers as the forward round),
 // dtheta2 partial += G^T mu^{t-1}, dz^{t-1} = (G theta2) (.) [mu^{t-1} > 0], and this round's share
@@ -342,7 +358,88 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
             pf_cols = (lane < min(64, pf_e - pf_b)) ? colidx[pf_b + lane] : 0;
         }
     }
-    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    // ---- workgroup reductions, fixed order over the four waves: the accumulators go into this workgroup's
+    // partial rows (compensated pair: row blockIdx.x and row kBwdGrid + blockIdx.x) and start again at zero ----
+    int n_flushed = 0;
+    auto flush = [&](bool first) {
+        __syncthreads();
+        // dtheta2: in 16-row slabs of the p x p matrix (one ib at a time) to bound LDS use
+#pragma unroll
+        for (int ib = 0; ib < CB; ++ib) {
+            float *slab = lds + wave * (16 * P);
+#pragma unroll
+            for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    slab[(4 * gl + rr) * P + 16 * jb + jl] = d2acc[ib][jb][rr];
+                    d2acc[ib][jb][rr] = 0.f;
+                }
+            __syncthreads();
+            for (int e = threadIdx.x; e < 16 * P; e += kThreads) {
+                const float sum = (lds[e] + lds[16 * P + e]) + (lds[2 * 16 * P + e] + lds[3 * 16 * P + e]);
+                const size_t at = (size_t)blockIdx.x * P * P + (size_t)ib * 16 * P + e;
+                comp_add(d2_part + at, d2_part + (size_t)kBwdGrid * P * P + at, sum, first);
+            }
+            __syncthreads();
+        }
+        // sum x dz, sum s+ dz, sum s- dz: lanes with equal jl first, then waves
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            cx[cb] += __shfl_xor(cx[cb], 16); cx[cb] += __shfl_xor(cx[cb], 32);
+            cp[cb] += __shfl_xor(cp[cb], 16); cp[cb] += __shfl_xor(cp[cb], 32);
+            cn[cb] += __shfl_xor(cn[cb], 16); cn[cb] += __shfl_xor(cn[cb], 32);
+        }
+        if (gl == 0) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                lds[(wave * 3 + 0) * P + 16 * cb + jl] = cx[cb];
+                lds[(wave * 3 + 1) * P + 16 * cb + jl] = cp[cb];
+                lds[(wave * 3 + 2) * P + 16 * cb + jl] = cn[cb];
+            }
+        }
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) cx[cb] = cp[cb] = cn[cb] = 0.f;
+        if (FUSE) {
+            // the fused round's sums: lanes with equal li, then into the same slots of this wave
+            constexpr int LPR = Ge::LPR;
+#pragma unroll
+            for (int m = LPR; m < 64; m <<= 1) {
+                fx4.x += __shfl_xor(fx4.x, m); fx4.y += __shfl_xor(fx4.y, m); fx4.z += __shfl_xor(fx4.z, m); fx4.w += __shfl_xor(fx4.w, m);
+                fp4.x += __shfl_xor(fp4.x, m); fp4.y += __shfl_xor(fp4.y, m); fp4.z += __shfl_xor(fp4.z, m); fp4.w += __shfl_xor(fp4.w, m);
+                fn4.x += __shfl_xor(fn4.x, m); fn4.y += __shfl_xor(fn4.y, m); fn4.z += __shfl_xor(fn4.z, m); fn4.w += __shfl_xor(fn4.w, m);
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane < LPR) {
+                float *px = lds + (wave * 3 + 0) * P + 4 * lane, *pp = lds + (wave * 3 + 1) * P + 4 * lane;
+                float *pn = lds + (wave * 3 + 2) * P + 4 * lane;
+                st4(px, add4(ld4(px), fx4));
+                st4(pp, add4(ld4(pp), fp4));
+                st4(pn, add4(ld4(pn), fn4));
+            }
+            if (FLAGS) {
+                __builtin_amdgcn_wave_barrier();
+                if (lane < P) {
+                    lds[(wave * 3 + 0) * P + lane] += fxj;
+                    lds[(wave * 3 + 1) * P + lane] += fpj;
+                }
+            }
+            fx4 = fp4 = fn4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            fxj = fpj = 0.f;
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < 3 * P; e += kThreads) {
+            const float sum = (lds[e] + lds[3 * P + e]) + (lds[2 * 3 * P + e] + lds[3 * 3 * P + e]);
+            const size_t at = (size_t)blockIdx.x * 3 * P + e;
+            comp_add(dc_part + at, dc_part + (size_t)kBwdGrid * 3 * P + at, sum, first);
+        }
+        __syncthreads();   // the tile area is free again
+        ++n_flushed;
+    };
+
+    int it = 0;
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x, ++it) {
+        // (every wave of the workgroup makes the same number of iterations: the barriers inside are safe)
+        if (it > 0 && it % kBwdFlushTiles == 0) flush(n_flushed == 0);
         const int r0 = t * kWgRows + wave * kTileRows;
         const int r = r0 + jl;
         const bool valid = r < n_vrows;
@@ -589,68 +686,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
         }
     }
 
-    // ---- workgroup reductions, fixed order over the four waves ----
-    __syncthreads();
-    // dtheta2: in 16-row slabs of the p x p matrix (one ib at a time) to bound LDS use
-#pragma unroll
-    for (int ib = 0; ib < CB; ++ib) {
-        float *slab = lds + wave * (16 * P);
-#pragma unroll
-        for (int jb = 0; jb < CB; ++jb)
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) slab[(4 * gl + rr) * P + 16 * jb + jl] = d2acc[ib][jb][rr];
-        __syncthreads();
-        for (int e = threadIdx.x; e < 16 * P; e += kThreads) {
-            const float sum = (lds[e] + lds[16 * P + e]) + (lds[2 * 16 * P + e] + lds[3 * 16 * P + e]);
-            d2_part[(size_t)blockIdx.x * P * P + (size_t)ib * 16 * P + e] = sum;
-        }
-        __syncthreads();
-    }
-    // sum x dz, sum s+ dz, sum s- dz: lanes with equal jl first, then waves
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-        cx[cb] += __shfl_xor(cx[cb], 16); cx[cb] += __shfl_xor(cx[cb], 32);
-        cp[cb] += __shfl_xor(cp[cb], 16); cp[cb] += __shfl_xor(cp[cb], 32);
-        cn[cb] += __shfl_xor(cn[cb], 16); cn[cb] += __shfl_xor(cn[cb], 32);
-    }
-    if (gl == 0) {
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            lds[(wave * 3 + 0) * P + 16 * cb + jl] = cx[cb];
-            lds[(wave * 3 + 1) * P + 16 * cb + jl] = cp[cb];
-            lds[(wave * 3 + 2) * P + 16 * cb + jl] = cn[cb];
-        }
-    }
-    if (FUSE) {
-        // the fused round's sums: lanes with equal li, then into the same slots of this wave
-        constexpr int LPR = Ge::LPR;
-#pragma unroll
-        for (int m = LPR; m < 64; m <<= 1) {
-            fx4.x += __shfl_xor(fx4.x, m); fx4.y += __shfl_xor(fx4.y, m); fx4.z += __shfl_xor(fx4.z, m); fx4.w += __shfl_xor(fx4.w, m);
-            fp4.x += __shfl_xor(fp4.x, m); fp4.y += __shfl_xor(fp4.y, m); fp4.z += __shfl_xor(fp4.z, m); fp4.w += __shfl_xor(fp4.w, m);
-            fn4.x += __shfl_xor(fn4.x, m); fn4.y += __shfl_xor(fn4.y, m); fn4.z += __shfl_xor(fn4.z, m); fn4.w += __shfl_xor(fn4.w, m);
-        }
-        __builtin_amdgcn_wave_barrier();
-        if (lane < LPR) {
-            float *px = lds + (wave * 3 + 0) * P + 4 * lane, *pp = lds + (wave * 3 + 1) * P + 4 * lane;
-            float *pn = lds + (wave * 3 + 2) * P + 4 * lane;
-            st4(px, add4(ld4(px), fx4));
-            st4(pp, add4(ld4(pp), fp4));
-            st4(pn, add4(ld4(pn), fn4));
-        }
-        if (FLAGS) {
-            __builtin_amdgcn_wave_barrier();
-            if (lane < P) {
-                lds[(wave * 3 + 0) * P + lane] += fxj;
-                lds[(wave * 3 + 1) * P + lane] += fpj;
-            }
-        }
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < 3 * P; e += kThreads) {
-        const float sum = (lds[e] + lds[3 * P + e]) + (lds[2 * 3 * P + e] + lds[3 * 3 * P + e]);
-        dc_part[(size_t)blockIdx.x * 3 * P + e] = sum;
-    }
+    flush(n_flushed == 0);
 }
 
 hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
@@ -755,7 +791,63 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
     }
 
     const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
-    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    // ---- workgroup reductions, fixed order over the four waves, into this workgroup's compensated pair of
+    // partial rows (see k_bwd_round); the accumulators start again at zero ----
+    int n_flushed = 0;
+    auto flush = [&](bool first) {
+        __syncthreads();
+#pragma unroll
+        for (int ib = 0; ib < CB; ++ib) {
+            float *slab = lds + wave * (16 * P);
+#pragma unroll
+            for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    slab[(4 * gl + rr) * P + 16 * jb + jl] = d2acc[ib][jb][rr];
+                    d2acc[ib][jb][rr] = 0.f;
+                }
+            __syncthreads();
+            for (int el = threadIdx.x; el < 16 * P; el += kThreads) {
+                const float sum = (lds[el] + lds[16 * P + el]) + (lds[2 * 16 * P + el] + lds[3 * 16 * P + el]);
+                const size_t at = (size_t)blockIdx.x * P * P + (size_t)ib * 16 * P + el;
+                comp_add(d2_part + at, d2_part + (size_t)kBwdGrid * P * P + at, sum, first);
+            }
+            __syncthreads();
+        }
+        // the three column sums: lanes with equal li first, then the waves
+#pragma unroll
+        for (int m = LPR; m < 64; m <<= 1) {
+            cx4.x += __shfl_xor(cx4.x, m); cx4.y += __shfl_xor(cx4.y, m); cx4.z += __shfl_xor(cx4.z, m); cx4.w += __shfl_xor(cx4.w, m);
+            cp4.x += __shfl_xor(cp4.x, m); cp4.y += __shfl_xor(cp4.y, m); cp4.z += __shfl_xor(cp4.z, m); cp4.w += __shfl_xor(cp4.w, m);
+            cn4.x += __shfl_xor(cn4.x, m); cn4.y += __shfl_xor(cn4.y, m); cn4.z += __shfl_xor(cn4.z, m); cn4.w += __shfl_xor(cn4.w, m);
+        }
+        if (FLAGS) {
+            if (lane < P) {
+                lds[(wave * 3 + 0) * P + lane] = fxj;
+                lds[(wave * 3 + 1) * P + lane] = fpj;
+                lds[(wave * 3 + 2) * P + lane] = 0.f;
+            }
+        } else if (lane < LPR) {
+            st4(lds + (wave * 3 + 0) * P + 4 * lane, cx4);
+            st4(lds + (wave * 3 + 1) * P + 4 * lane, cp4);
+            st4(lds + (wave * 3 + 2) * P + 4 * lane, cn4);
+        }
+        cx4 = cp4 = cn4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        fxj = fpj = 0.f;
+        __syncthreads();
+        for (int el = threadIdx.x; el < 3 * P; el += kThreads) {
+            const float sum = (lds[el] + lds[3 * P + el]) + (lds[2 * 3 * P + el] + lds[3 * 3 * P + el]);
+            const size_t at = (size_t)blockIdx.x * 3 * P + el;
+            comp_add(dc_part + at, dc_part + (size_t)kBwdGrid * 3 * P + at, sum, first);
+        }
+        __syncthreads();   // the tile area is free again
+        ++n_flushed;
+    };
+
+    int it = 0;
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x, ++it) {
+        // (every wave of the workgroup makes the same number of iterations: the barriers inside are safe)
+        if (it > 0 && it % kBwdFlushTiles == 0) flush(n_flushed == 0);
         const int r0 = t * kWgRows + wave * kTileRows;
         if (r0 >= n_vrows) continue;        // S is a multiple of 16: tiles are whole
         const int v = r0 / S, s0 = r0 - v * S;
@@ -852,45 +944,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
         __builtin_amdgcn_wave_barrier();
     }
 
-    // ---- workgroup reductions, fixed order over the four waves ----
-    __syncthreads();
-#pragma unroll
-    for (int ib = 0; ib < CB; ++ib) {
-        float *slab = lds + wave * (16 * P);
-#pragma unroll
-        for (int jb = 0; jb < CB; ++jb)
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) slab[(4 * gl + rr) * P + 16 * jb + jl] = d2acc[ib][jb][rr];
-        __syncthreads();
-        for (int el = threadIdx.x; el < 16 * P; el += kThreads) {
-            const float sum = (lds[el] + lds[16 * P + el]) + (lds[2 * 16 * P + el] + lds[3 * 16 * P + el]);
-            d2_part[(size_t)blockIdx.x * P * P + (size_t)ib * 16 * P + el] = sum;
-        }
-        __syncthreads();
-    }
-    // the three column sums: lanes with equal li first, then the waves
-#pragma unroll
-    for (int m = LPR; m < 64; m <<= 1) {
-        cx4.x += __shfl_xor(cx4.x, m); cx4.y += __shfl_xor(cx4.y, m); cx4.z += __shfl_xor(cx4.z, m); cx4.w += __shfl_xor(cx4.w, m);
-        cp4.x += __shfl_xor(cp4.x, m); cp4.y += __shfl_xor(cp4.y, m); cp4.z += __shfl_xor(cp4.z, m); cp4.w += __shfl_xor(cp4.w, m);
-        cn4.x += __shfl_xor(cn4.x, m); cn4.y += __shfl_xor(cn4.y, m); cn4.z += __shfl_xor(cn4.z, m); cn4.w += __shfl_xor(cn4.w, m);
-    }
-    if (FLAGS) {
-        if (lane < P) {
-            lds[(wave * 3 + 0) * P + lane] = fxj;
-            lds[(wave * 3 + 1) * P + lane] = fpj;
-            lds[(wave * 3 + 2) * P + lane] = 0.f;
-        }
-    } else if (lane < LPR) {
-        st4(lds + (wave * 3 + 0) * P + 4 * lane, cx4);
-        st4(lds + (wave * 3 + 1) * P + 4 * lane, cp4);
-        st4(lds + (wave * 3 + 2) * P + 4 * lane, cn4);
-    }
-    __syncthreads();
-    for (int el = threadIdx.x; el < 3 * P; el += kThreads) {
-        const float sum = (lds[el] + lds[3 * P + el]) + (lds[2 * 3 * P + el] + lds[3 * 3 * P + el]);
-        dc_part[(size_t)blockIdx.x * 3 * P + el] = sum;
-    }
+    flush(n_flushed == 0);
 }
 
 hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,

@@ -13,6 +13,13 @@ constexpr int kChunkNodes = 1024;
 // per-workgroup partial gradients are summed does not depend on the device.
 constexpr int kBwdGrid = 1024;
 constexpr int kBwdHeadGrid = 1024;
+// A workgroup of the reversed rounds folds its float32 accumulators (the p x p sum for dtheta2 and the column
+// sums) into its partial rows every kBwdFlushTiles tiles, and the partial rows are kept as a compensated pair
+// (row b: running sum, row kBwdGrid + b: the rounding remainders), so that no float accumulator ever takes
+// more than kBwdFlushTiles * 16 terms however large the graph: with 10^6 nodes x 16 states a single running
+// float32 sum per wave (62 500 terms) left the gradients ten times less accurate than on one state.
+constexpr int kBwdFlushTiles = 32;
+constexpr int kBwdRoundRows = 2 * kBwdGrid;   // partial rows per reversed round
 // Blocks per state of the action-node fix-up of the backward pass (each adds one partial row).
 constexpr int kFixSplit = 16;
 // Elements per block of the selection scan / sort passes.
@@ -257,14 +264,14 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
                             const int32_t *colidx, const float *wagg, const float *dz_in,
                             const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out /*may be NULL*/, const NodeInfo &ni, const float *theta2,
-                            float *dc_part /*[kBwdGrid][3][p]*/, float *d2_part /*[kBwdGrid][p][p]*/,
+                            float *dc_part /*[kBwdRoundRows][3][p]*/, float *d2_part /*[kBwdRoundRows][p][p]*/,
                             const HubTable &ht, const float *hub_sum, const BwdFuse *fuse /*may be NULL*/);
 // The last reversed round (t = 2) from the scalars: node mode (S a multiple of 16) and T >= 3 only.
 hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                             const int32_t *colidx, const float *wagg, const float *dz_in /*dz^2 [N][S][p]*/,
                             const NodeInfo &ni, bool has_neg, const float *theta1, const float *theta2,
-                            const float *qvec, float *dc_part /*[kBwdGrid][3][p]*/,
-                            float *d2_part /*[kBwdGrid][p][p]*/, const HubTable &ht,
+                            const float *qvec, float *dc_part /*[kBwdRoundRows][3][p]*/,
+                            float *d2_part /*[kBwdRoundRows][p][p]*/, const HubTable &ht,
                             const float *hub_sum4 /*[n_hubs][4][S][p]*/);
 hipError_t launch_hub_sums_grad(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
                                 const int32_t *colidx, const float *wagg, const NodeInfo &ni, bool has_neg,
