@@ -336,7 +336,11 @@ int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const in
  *            sel_count [G], stats [G][2]: device scratch owned by the caller
  *   steps_out, picked_out, live_out: host pointers; policy evaluations made, nodes added, live
  *            stored entries left (0 = complete cover)
- * Reads two small counters back per step, so the call waits for the stream.
+ * Which d to use, whether an edge is left and the two counts are decided and kept on the device; the host
+ * reads the state back once per block of steps (1, 2, 4, 8, then 16 steps), so the call waits for the stream
+ * a few times per solve, and a block that outlasts the solve still makes its (then ineffective) evaluations.
+ * With the adaptive rule sel_idx / sel_val receive the eight best candidates of the last evaluation, of
+ * which the first sel_count joined the solution.
  */
 int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, float *x, int32_t T,
                           int32_t adaptive, int32_t max_steps, float *mu, float *gsum, float *q, uint8_t *cand,

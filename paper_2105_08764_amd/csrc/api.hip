@@ -41,7 +41,7 @@ struct Carver {
 
 struct HeadLayout {
     size_t s_pos, s_neg, nbr_sp, nbr_spw, chunk_begin, chunk_end, graph_chunk_off;
-    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, list, end;
+    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, list, loop_ctr, end;
     int max_chunks, max_hubs, max_segs;
 };
 
@@ -88,6 +88,7 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     h.seg_end = c.take(sizeof(int32_t) * h.max_segs);
     h.touched = c.take(sizeof(int32_t) * N);        // per-node flags of the incremental state update
     h.list = c.take(sizeof(int32_t) * (N + 1));     // its work list
+    h.loop_ctr = c.take(sizeof(unsigned long long) * 2);   // counters of s2v_mvc_inference
     h.end = c.off;
     return h;
 }
@@ -607,9 +608,16 @@ struct FusedTrain {
     unsigned long long *mask_words;
     const int32_t *action;
 };
+// defer != NULL (one state, one graph, T >= 2: the last round leaves per-workgroup partial rows of the graph sum):
+// the second stage of the graph sum is left to the caller, who gets the partial rows here.
+struct DeferredGsum {
+    const float *gpart;
+    int rows;
+};
 static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x, int32_t T,
                               int32_t S, float *mu_out, float *mu_saved, float *gsum, void *ws, size_t ws_bytes,
-                              float *q_node, bool *q_node_done, const FusedTrain *fused = nullptr) {
+                              float *q_node, bool *q_node_done, const FusedTrain *fused = nullptr,
+                              DeferredGsum *defer = nullptr) {
     if (q_node_done) *q_node_done = false;
     if (!ctx) return S2V_ERR_INVALID_ARG;
     int32_t rc = check_graph(g);
@@ -635,7 +643,6 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     float *qvec = at<float>(ws, f.qvec);
     float *tmp = at<float>(ws, f.tmp);
     const size_t nsp = (size_t)N * S * p;
-    S2V_TRY(launch_qvec(st, p, params->theta3, params->theta4, qvec));
     // destination of round t (1-based): the saved slot, or ping-pong so that round T lands in mu_out
     auto dest = [&](int t) -> float * {
         if (mu_saved) return mu_saved + (size_t)(t - 1) * nsp;
@@ -658,11 +665,15 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     const bool by_bits = (S == 1 || S % 16 == 0) && !pr->has_neg && !g->row_end && !x_res && T >= 2;
     unsigned long long *xbits = by_bits ? at<unsigned long long>(ws, f.xbits) : nullptr;
     if (by_bits) compact = nullptr;
-    if (x_res)
+    if (x_res) {
+        S2V_TRY(launch_qvec(st, p, params->theta3, params->theta4, qvec));
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info, compact));
-    else
+    } else {
+        // (q+- = theta3 relu(+-theta4) comes out of the same launch as the records)
         S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info, compact,
-                                by_bits ? at<float>(ws, wagg ? h.nbr_spw : h.nbr_sp) : nullptr, xbits));
+                                by_bits ? at<float>(ws, wagg ? h.nbr_spw : h.nbr_sp) : nullptr, xbits, p, params->theta3,
+                                params->theta4, qvec));
+    }
     NodeInfo ninfo = make_nodeinfo(info, S, x_res != nullptr);
     ninfo.compact = compact;
     if (S == 1) ninfo.xbits = reinterpret_cast<const unsigned *>(xbits);
@@ -690,7 +701,10 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     if (mu_saved && mu_out && mu_out != muT && nsp > 0)
         S2V_TRY(hipMemcpyAsync(mu_out, muT, sizeof(float) * nsp, hipMemcpyDeviceToDevice, st));
     if (gsum) {
-        if (fuse_gsum) {
+        if (fuse_gsum && defer) {
+            defer->gpart = gpart;
+            defer->rows = round_grid((long)N * S);
+        } else if (fuse_gsum) {
             S2V_TRY(launch_gsum_from_round(st, p, S, round_grid((long)N * S), gpart, gsum));
         } else {
             const ChunkTable ct = chunk_table(ws, h, *pr);
@@ -737,6 +751,41 @@ int32_t s2v_policy_select(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
                        (int64_t)pr->max_graph_nodes * params->p <= kSmallLdsFloats && k <= kSmallK &&
                        !g->weighted_sum && !g->state_residual && ctx->max_lds_per_block >= kSmallLdsBytes && x && mu_out &&
                        q;
+    // One state of one graph with few workgroups in the last round: the tail of the evaluation (graph sum,
+    // graph term of Eq. 2, q = graph term + node term) and the first stage of the selection share a launch.
+    // Same device functions as the separate kernels: the results are those of the two calls bit for bit.
+    const bool tail = !small && pr && g->n_graphs == 1 && T >= 2 && g->n_nodes > 0 && k <= kSmallK && x && mu_out && q &&
+                      round_grid((long)g->n_nodes) <= kTailMaxRows && check_params(params) == S2V_OK;
+    bool tail_fits = false;
+    if (tail) {
+        // the selection's partial results and the forward pass's partial rows both start behind the head of the
+        // workspace; the fused kernel reads the one while it writes the other, so they must not overlap
+        const HeadLayout h = head_layout(g->n_nodes, 1, pr->n_hubs, pr->n_segs);
+        const SelLayout sl = sel_layout(h, g->n_nodes, k);
+        const FwdLayout f = fwd_layout(h, g->n_nodes, params->p, 1, T >= 3);
+        tail_fits = sl.hist <= f.gpart;
+    }
+    if (tail && tail_fits) {
+        const int32_t N = g->n_nodes;
+        const HeadLayout h = head_layout(N, 1, pr->n_hubs, pr->n_segs);
+        const SelLayout sl = sel_layout(h, N, k);
+        if (ws_bytes < sl.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
+        DeferredGsum dg{nullptr, 0};
+        bool q_node_done = false;
+        int32_t rc = embed_fwd_impl(ctx, g, params, x, T, 1, mu_out, nullptr, gsum, ws, ws_bytes, q, &q_node_done, nullptr, &dg);
+        if (rc != S2V_OK) return rc;
+        if (!q_node_done || !dg.gpart) return S2V_ERR_INVALID_ARG;   // (cannot happen for this shape)
+        // (the partial rows live in the forward pass's part of the workspace, the selection's partial results
+        //  in its own: sel_layout's first two pieces lie below the forward pass's gpart)
+        SelectScratch sc{};
+        sc.part_val = at<float>(ws, sl.part_val);
+        sc.part_idx = at<int32_t>(ws, sl.part_idx);
+        const ChunkTable ct = chunk_table(ws, h, *pr);
+        SpanGuard span(ctx, S2V_PROFILE_SELECT);
+        S2V_TRY(launch_tail_select(ctx->stream, params->p, dg.rows, k, dg.gpart, params->theta5, params->theta6, gsum, q, x,
+                                   cand, ct, sc, idx, val, count));
+        return S2V_OK;
+    }
     if (!small) {
         int32_t rc = s2v_policy_eval(ctx, g, params, x, T, 1, mu_out, gsum, q, ws, ws_bytes);
         if (rc != S2V_OK) return rc;
@@ -1035,9 +1084,9 @@ int32_t s2v_loss_grad(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
                           true);
 }
 
-int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const int32_t *sel_idx,
-                            const int32_t *sel_count, int32_t k, uint8_t *cand, int32_t *stats, void *ws,
-                            size_t ws_bytes) {
+static int32_t residual_update_impl(s2v_ctx *ctx, const s2v_graph *g, float *x, const int32_t *sel_idx,
+                                    const int32_t *sel_count, int32_t k, uint8_t *cand, int32_t *stats, void *ws,
+                                    size_t ws_bytes, bool marked) {
     if (!ctx) return S2V_ERR_INVALID_ARG;
     int32_t rc = check_graph(g);
     if (rc != S2V_OK) return rc;
@@ -1054,8 +1103,14 @@ int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const in
     S2V_TRY(launch_residual_update(ctx->stream, N, G, g->graph_off, g->rowptr, const_cast<int32_t *>(g->row_end),
                                    const_cast<int32_t *>(g->colidx), const_cast<float *>(g->w), x, sel_idx, sel_count,
                                    sel_idx ? k : 0, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg), cand, stats,
-                                   at<int32_t>(ws, h.touched), at<int32_t>(ws, h.list)));
+                                   at<int32_t>(ws, h.touched), at<int32_t>(ws, h.list), marked));
     return S2V_OK;
+}
+
+int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const int32_t *sel_idx,
+                            const int32_t *sel_count, int32_t k, uint8_t *cand, int32_t *stats, void *ws,
+                            size_t ws_bytes) {
+    return residual_update_impl(ctx, g, x, sel_idx, sel_count, k, cand, stats, ws, ws_bytes, false);
 }
 
 int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, float *x, int32_t T,
@@ -1071,32 +1126,49 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     // state from the incoming x: drops the edges already covered, fills cand and stats
     int32_t rc = s2v_residual_update(ctx, g, x, nullptr, nullptr, 0, cand, stats, ws, ws_bytes);
     if (rc != S2V_OK) return rc;
-    std::vector<int32_t> hstats(2 * (size_t)G), hcount(G);
-    auto read_stats = [&](int64_t *n_cand, int64_t *n_live) -> int32_t {
+    // The loop runs in blocks of steps without reading anything back: which d to use, whether an edge is
+    // left, and the counts of evaluations and of added nodes are all decided and kept on the device
+    // (k_loop_control).  The host looks at the state once per block; a block that outlasts the solve costs the
+    // evaluations it still makes, which change nothing.  Blocks grow 1, 2, 4, ... up to kLoopBlock steps.
+    constexpr int kLoopBlock = 16;
+    const Prepared *pr = find_prepared(ctx, g, ws);
+    if (!pr) return S2V_ERR_NOT_PREPARED;
+    const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
+    unsigned long long *ctr = at<unsigned long long>(ws, h.loop_ctr);
+    S2V_TRY(launch_zero_i32(ctx->stream, 4, reinterpret_cast<int32_t *>(ctr)));
+    std::vector<int32_t> hstats(2 * (size_t)G);
+    unsigned long long hctr[2] = {0ull, 0ull};
+    auto read_state = [&](int64_t *n_live) -> int32_t {
         S2V_TRY(hipMemcpyAsync(hstats.data(), stats, sizeof(int32_t) * 2 * G, hipMemcpyDeviceToHost, ctx->stream));
+        S2V_TRY(hipMemcpyAsync(hctr, ctr, sizeof(hctr), hipMemcpyDeviceToHost, ctx->stream));
         S2V_TRY(hipStreamSynchronize(ctx->stream));
-        *n_cand = 0;
         *n_live = 0;
-        for (int b = 0; b < G; ++b) { *n_cand += hstats[2 * b]; *n_live += hstats[2 * b + 1]; }
+        for (int b = 0; b < G; ++b) *n_live += hstats[2 * b + 1];
         return S2V_OK;
     };
-    int64_t n_cand = 0, n_live = 0;
-    rc = read_stats(&n_cand, &n_live);
+    int64_t n_live = 0;
+    rc = read_state(&n_live);
     if (rc != S2V_OK) return rc;
-    int32_t steps = 0;
-    int64_t picked = 0;
-    while (n_live > 0 && steps < max_steps) {
-        const int32_t d = (adaptive && G == 1) ? s2v_adaptive_d(n_cand, N) : 1;
-        rc = s2v_policy_select(ctx, g, params, x, cand, T, d, mu, gsum, q, sel_idx, sel_val, sel_count, ws, ws_bytes);
+    const bool use_rule = adaptive && G == 1;
+    const int32_t k_sel = use_rule ? kSmallK : 1;   // the largest d of the rule; the device cuts the count to d
+    int32_t launched = 0, block = 1;
+    while (n_live > 0 && launched < max_steps) {
+        const int32_t todo = block < max_steps - launched ? block : max_steps - launched;
+        for (int32_t i = 0; i < todo; ++i) {
+            rc = s2v_policy_select(ctx, g, params, x, cand, T, k_sel, mu, gsum, q, sel_idx, sel_val, sel_count, ws, ws_bytes);
+            if (rc != S2V_OK) return rc;
+            S2V_TRY(launch_loop_control(ctx->stream, G, N, use_rule, stats, sel_count, ctr, k_sel, sel_idx, x,
+                                        at<int32_t>(ws, h.list)));
+            rc = residual_update_impl(ctx, g, x, sel_idx, sel_count, k_sel, cand, stats, ws, ws_bytes, true);
+            if (rc != S2V_OK) return rc;
+        }
+        launched += todo;
+        if (block < kLoopBlock) block *= 2;
+        rc = read_state(&n_live);
         if (rc != S2V_OK) return rc;
-        S2V_TRY(hipMemcpyAsync(hcount.data(), sel_count, sizeof(int32_t) * G, hipMemcpyDeviceToHost, ctx->stream));
-        rc = s2v_residual_update(ctx, g, x, sel_idx, sel_count, d, cand, stats, ws, ws_bytes);
-        if (rc != S2V_OK) return rc;
-        rc = read_stats(&n_cand, &n_live);   // also completes the copy of the counts
-        if (rc != S2V_OK) return rc;
-        for (int b = 0; b < G; ++b) picked += hcount[b];
-        ++steps;
     }
+    const int32_t steps = (int32_t)hctr[0];
+    const int64_t picked = (int64_t)hctr[1];
     *steps_out = steps;
     *picked_out = picked;
     *live_out = n_live;

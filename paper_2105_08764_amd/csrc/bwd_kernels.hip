@@ -1003,6 +1003,9 @@ hipError_t launch_hub_sums_grad(hipStream_t st, int p, int S, const HubTable &ht
                                 const int32_t *colidx, const float *wagg, const NodeInfo &ni, bool has_neg,
                                 const float *theta1, const float *qvec, float *partial4, float *hub_sum4) {
     if (ht.n_hubs == 0) return hipSuccess;
+    // (every long row a single segment: its sums are the row's sums, written in place; see launch_hub_sums)
+    const bool single = ht.n_segs == ht.n_hubs;
+    if (single) partial4 = hub_sum4;
     const long items = (long)ht.n_segs * (S / 16);
     const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
 #define S2V_LAUNCH_HG(PP, WW, NN) \
@@ -1016,7 +1019,7 @@ hipError_t launch_hub_sums_grad(hipStream_t st, int p, int S, const HubTable &ht
 #undef S2V_LAUNCH_HG_N
 #undef S2V_LAUNCH_HG
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
+    if (err != hipSuccess || single) return err;
     return launch_hub_combine(st, 4 * S * p, ht, partial4, hub_sum4);
 }
 

@@ -2,6 +2,7 @@
 // embedding sum (Alg. 2 lines 4-5) and the scores of Eq. 2 / Alg. 2.
 #include "device_util.h"
 #include "internal.h"
+#include "reduce_util.h"
 
 namespace s2v {
 
@@ -74,17 +75,16 @@ hipError_t launch_prepare_nbr(hipStream_t st, int N, const int32_t *rowptr, cons
 __global__ void k_qvec(int p, const float *__restrict__ theta3, const float *__restrict__ theta4,
                        float *__restrict__ qvec) {
     const int i = threadIdx.x;
-    if (i >= p) return;
-    // double accumulation, one rounding: q+- multiply every node's edge sums, so an error here moves every
-    // pre-activation of the graph the same way
-    double qp = 0.0, qn = 0.0;
+    if (i >= 2 * p) return;
+    // (the same double accumulation in the same order as the copy inside k_nodeinfo: identical bits)
+    const bool neg = i >= p;
+    const int r = neg ? i - p : i;
+    double acc = 0.0;
     for (int j = 0; j < p; ++j) {
-        const float t4 = theta4[j], t3 = theta3[i * p + j];
-        qp += (double)t3 * (double)fmaxf(t4, 0.f);
-        qn += (double)t3 * (double)fmaxf(-t4, 0.f);
+        const float t4 = theta4[j];
+        acc += (double)theta3[r * p + j] * (double)fmaxf(neg ? -t4 : t4, 0.f);
     }
-    qvec[i] = (float)qp;
-    qvec[p + i] = (float)qn;
+    qvec[i] = (float)acc;
 }
 
 hipError_t launch_qvec(hipStream_t st, int p, const float *theta3, const float *theta4, float *qvec) {
@@ -141,12 +141,34 @@ hipError_t launch_round1(hipStream_t st, int p, int N, int S, const NodeInfo &ni
 // then s+ and s- once.  A neighbour's record is all the second round needs (see Mu1Row), and
 // every kernel reads its own rows' scalars here.
 // ------------------------------------------------------------------------------------------
+// q+- of one output row i (i < p: q+, else q-), accumulated in double and rounded once: q+- multiply every
+// node's edge sums, so an error here moves every pre-activation of the graph the same way
+__device__ __forceinline__ float qvec_entry(int p, int i, const float *__restrict__ theta3,
+                                            const float *__restrict__ theta4) {
+    const bool neg = i >= p;
+    const int r = neg ? i - p : i;
+    double acc = 0.0;
+    for (int j = 0; j < p; ++j) {
+        const float t4 = theta4[j];
+        acc += (double)theta3[r * p + j] * (double)fmaxf(neg ? -t4 : t4, 0.f);
+    }
+    return (float)acc;
+}
+
+// (qvec != NULL: the last workgroup does not take part in the records; it forms q+- instead, which saves the
+//  launch of k_qvec where a round follows at once)
 __global__ __launch_bounds__(256) void k_nodeinfo(int N, int S, int ni, const float *__restrict__ x,
                                                   const float *__restrict__ s_pos, const float *__restrict__ s_neg,
                                                   float *__restrict__ info, float *__restrict__ compact,
-                                                  const float *__restrict__ nbr_sp) {
+                                                  const float *__restrict__ nbr_sp, int p,
+                                                  const float *__restrict__ theta3, const float *__restrict__ theta4,
+                                                  float *__restrict__ qvec, int work_blocks) {
+    if (qvec && (int)blockIdx.x == work_blocks) {
+        if ((int)threadIdx.x < 2 * p) qvec[threadIdx.x] = qvec_entry(p, threadIdx.x, theta3, theta4);
+        return;
+    }
     const long total = (long)N * ni;
-    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)work_blocks * 256) {
         const int v = (int)(i / ni), c = (int)(i - (long)v * ni);
         float o = 0.f;
         if (c < S) o = x[(size_t)c * N + v];
@@ -184,13 +206,15 @@ __global__ __launch_bounds__(256) void k_flags16(int N, int nb, const float *__r
 }
 
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
-                           float *info, float *compact, const float *nbr_sp, unsigned long long *xbits) {
-    if (N == 0) return hipSuccess;
+                           float *info, float *compact, const float *nbr_sp, unsigned long long *xbits, int p,
+                           const float *theta3, const float *theta4, float *qvec) {
+    if (N == 0) return qvec ? launch_qvec(st, p, theta3, theta4, qvec) : hipSuccess;
     const int ni = make_nodeinfo(info, S, false).ni;
     const long total = (long)N * ni;
-    k_nodeinfo<<<(int)min((total + 255) / 256, (long)65536), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info,
-                                                                           S == 1 ? compact : nullptr,
-                                                                           (S == 1 || S % 16 == 0) ? nbr_sp : nullptr);
+    const int work_blocks = (int)min((total + 255) / 256, (long)65535);
+    k_nodeinfo<<<work_blocks + (qvec ? 1 : 0), 256, 0, st>>>(N, S, ni, x, s_pos, s_neg, info, S == 1 ? compact : nullptr,
+                                                             (S == 1 || S % 16 == 0) ? nbr_sp : nullptr, p, theta3,
+                                                             theta4, qvec, work_blocks);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !xbits) return e;
     if (S % 16 == 0) {
@@ -820,6 +844,10 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
     if (ht.n_hubs == 0) return hipSuccess;
     const bool node = (S % 16) == 0;
     const int kind = mask ? 2 : (src ? 0 : 1);
+    // every long row a single segment: the segment sums ARE the row sums (segment h belongs to long row h),
+    // so they are written where the row sums go and the pass that adds a row's segments is not launched
+    const bool single = ht.n_segs == ht.n_hubs;
+    if (single) partial = hub_sum;
     const long items = (long)ht.n_segs * (node ? S / 16 : S);
     const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
 #define S2V_LAUNCH_HUB_W(PP, NODE, SRC, WW)                                                                       \
@@ -845,7 +873,7 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
 #undef S2V_LAUNCH_HUB
 #undef S2V_LAUNCH_HUB_W
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
+    if (err != hipSuccess || single) return err;
     return launch_hub_combine(st, S * p, ht, partial, hub_sum);
 }
 
@@ -909,22 +937,10 @@ __global__ __launch_bounds__(1024) void k_gsum_stage2(int p, int S, int G, const
     const int blocks_per_graph = L / 16;
     const int g = blockIdx.x / blocks_per_graph;
     const int col = (blockIdx.x - g * blocks_per_graph) * 16 + (threadIdx.x & 15);
-    const int rl = threadIdx.x >> 4;
     const int rb = graph_row_off ? graph_row_off[g] : 0;
     const int re = graph_row_off ? graph_row_off[g + 1] : rows_if_single;
-    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-    int c = rb + rl;
-    for (; c + 192 < re; c += 256) {
-        const float v0 = partial[(size_t)c * L + col], v1 = partial[(size_t)(c + 64) * L + col];
-        const float v2 = partial[(size_t)(c + 128) * L + col], v3 = partial[(size_t)(c + 192) * L + col];
-        a0 += (double)v0; a1 += (double)v1; a2 += (double)v2; a3 += (double)v3;
-    }
-    for (; c < re; c += 64) a0 += (double)partial[(size_t)c * L + col];
-    red[rl][threadIdx.x & 15] = (a0 + a1) + (a2 + a3);
-    __syncthreads();
-    if (rl == 0) {
-        double acc = 0.0;
-        for (int k = 0; k < 64; ++k) acc += red[k][threadIdx.x];
+    const double acc = gsum_stage2_cols(L, col, rb, re, partial, red);
+    if ((threadIdx.x >> 4) == 0) {
         const int s = col / p, j = col - s * p;
         gsum[((size_t)s * G + g) * p + j] = (float)acc;
     }
@@ -957,24 +973,9 @@ __global__ void k_qa(int p, const float *__restrict__ theta5, const float *__res
                      const float *__restrict__ gsum, float *__restrict__ qa) {
     __shared__ float gs[128];
     __shared__ float red[128];
-    const int b = blockIdx.x, i = threadIdx.x;
-    if (i < p) gs[i] = gsum[(size_t)b * p + i];
-    __syncthreads();
-    float term = 0.f;
-    if (i < p) {
-        // (double accumulation: p^2 operations per graph, and each of these p relu units carries 1/p of a
-        //  state's whole gradient in training)
-        double h = 0.0;
-        for (int j = 0; j < p; ++j) h += (double)theta6[i * p + j] * (double)gs[j];
-        term = theta5[i] * fmaxf((float)h, 0.f);
-    }
-    red[i] = term;
-    __syncthreads();
-    for (int w = 64; w >= 1; w >>= 1) {
-        if (i < w) red[i] += red[i + w];
-        __syncthreads();
-    }
-    if (i == 0) qa[b] = red[0];
+    const int b = blockIdx.x;
+    const float v = qa_value(p, theta5, theta6, gsum + (size_t)b * p, gs, red);
+    if (threadIdx.x == 0) qa[b] = v;
 }
 
 hipError_t launch_qa(hipStream_t st, int p, int S, int G, const float *theta5, const float *theta6, const float *gsum,

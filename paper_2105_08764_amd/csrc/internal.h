@@ -130,7 +130,9 @@ hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const f
                            float *compact /*[N], written when S == 1; may be NULL*/,
                            const float *nbr_sp = nullptr /*[N]: goes into the records' first spare float (S == 1 or S % 16 == 0)*/,
                            unsigned long long *xbits = nullptr /*S == 1: [ceil(N/64)], bit v = (x_v != 0);
-                                                                 S % 16 == 0: [N][S/16] 16-bit words, see NodeInfo::flags16*/);
+                                                                 S % 16 == 0: [N][S/16] 16-bit words, see NodeInfo::flags16*/,
+                           int p = 0, const float *theta3 = nullptr, const float *theta4 = nullptr,
+                           float *qvec = nullptr /*non-NULL: also q+- = theta3 relu(+-theta4), as launch_qvec writes it*/);
 // nbr_sp[v] = sum of s_pos over the live entries of row v (0 for rows longer than kHubDegree, which never use it)
 // nbr_spw: the same with each neighbour weighted by its edge weight (w == NULL: equal to nbr_sp)
 hipError_t launch_prepare_nbr(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const int32_t *colidx,
@@ -181,8 +183,11 @@ hipError_t launch_residual_update(hipStream_t st, int N, int G, const int32_t *g
                                   int32_t *rowend, int32_t *colidx, float *w, float *x, const int32_t *sel_idx,
                                   const int32_t *sel_count, int k, float *s_pos, float *s_neg, uint8_t *cand,
                                   int32_t *stats /*[G][2]*/, int32_t *touched /*[N], all zero between calls*/,
-                                  int32_t *list /*[N+1]*/);
+                                  int32_t *list /*[N+1]*/, bool marked = false);
 hipError_t launch_zero_i32(hipStream_t st, long n, int32_t *p);
+hipError_t launch_loop_control(hipStream_t st, int G, int N, bool adaptive, const int32_t *stats, int32_t *sel_count,
+                               unsigned long long *counters /*[2]: evaluations that mattered, nodes added*/, int k,
+                               const int32_t *sel_idx /*[G][k]*/, float *x, int32_t *list);
 
 // ---- one launch per step of Alg. 3 on small graphs (small_kernels.hip) ----
 // floats of LDS that hold one graph's embedding: a graph qualifies when n_nodes * p does not exceed it
@@ -225,6 +230,13 @@ hipError_t launch_q_target(hipStream_t st, int N, int S, int G, const int32_t *g
                            int32_t *part_idx /*[S][n_chunks]*/, float *target);
 hipError_t launch_smallk(hipStream_t st, const ChunkTable &ct, const float *q, const float *x, const uint8_t *cand,
                          int k /*2..kSmallK, one graph*/, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
+// gsum stage 2 + graph term of Eq. 2 + q = qa + node term + first selection stage in one launch, then the second
+// selection stage (one state, one graph, n_chunks >= 1, 1 <= k <= kSmallK, few partial rows)
+constexpr int kTailMaxRows = 256;
+hipError_t launch_tail_select(hipStream_t st, int p, int rows, int k, const float *gpart /*[rows][p]*/,
+                              const float *theta5, const float *theta6, float *gsum /*[p]*/,
+                              float *q /*[N]: in the node term, out Eq. 2*/, const float *x, const uint8_t *cand,
+                              const ChunkTable &ct, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
 hipError_t launch_topk(hipStream_t st, int N, const float *q, const float *x, const uint8_t *cand, int k,
                        const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
 

@@ -170,19 +170,77 @@ hipError_t launch_zero_i32(hipStream_t st, long n, int32_t *p) {
     return hipGetLastError();
 }
 
+// The decisions of one step of the loop of Alg. 3, taken on the device so that the host need not read anything
+// back between steps.  stats holds {candidates, live stored entries} per graph as the last state update left
+// them (the state this step's scores were computed on); sel_count holds how many nodes the selection found per
+// graph (it asked for the largest d of the rule).  For one graph and the adaptive rule of Sec. 4.5.1, d follows
+// from the candidate count and the count is cut to d (the selection is ordered, so its first d entries are the
+// top-d); when no edge is left anywhere the counts become zero and the state update that follows changes nothing.
+// counters[0] += 1 when an edge was left (a policy evaluation that mattered), counters[1] += nodes added.
+// The same launch also does the first two steps of the state update that follows: the selected nodes join the
+// solution (x = 1, as k_mark_selected) and the work list of the incremental update is emptied (as k_reset_list).
+__global__ __launch_bounds__(256) void k_loop_control(int G, int N, int adaptive, const int32_t *__restrict__ stats,
+                                                      int32_t *__restrict__ sel_count,
+                                                      unsigned long long *__restrict__ counters, int k,
+                                                      const int32_t *__restrict__ sel_idx, float *__restrict__ x,
+                                                      int32_t *__restrict__ list) {
+    __shared__ unsigned long long s_live, s_picked;
+    if (threadIdx.x == 0) { s_live = 0ull; s_picked = 0ull; }
+    __syncthreads();
+    unsigned long long live = 0ull;
+    for (int b = threadIdx.x; b < G; b += 256) live += (unsigned long long)stats[2 * b + 1];
+    if (live) atomicAdd(&s_live, live);
+    __syncthreads();
+    const bool going = s_live > 0ull;
+    int d = 1;
+    if (adaptive && G == 1) {
+        const long long c = stats[0];
+        d = 2 * c > N ? 8 : (4 * c > N ? 4 : (8 * c > N ? 2 : 1));
+    }
+    unsigned long long picked = 0ull;
+    for (int b = threadIdx.x; b < G; b += 256) {
+        const int c = going ? min(sel_count[b], d) : 0;
+        sel_count[b] = c;
+        picked += (unsigned long long)c;
+    }
+    if (picked) atomicAdd(&s_picked, picked);
+    __syncthreads();
+    if (threadIdx.x == 0 && going) {
+        counters[0] += 1ull;
+        counters[1] += s_picked;
+    }
+    if (threadIdx.x == 0) list[0] = 0;
+    // (this block wrote the counts: after the barrier above every thread sees them)
+    for (int i = threadIdx.x; i < G * k; i += 256) {
+        const int g = i / k, j = i - g * k;
+        if (j < sel_count[g]) {
+            const int v = sel_idx[i];
+            if (v >= 0) x[v] = 1.f;
+        }
+    }
+}
+
+hipError_t launch_loop_control(hipStream_t st, int G, int N, bool adaptive, const int32_t *stats, int32_t *sel_count,
+                               unsigned long long *counters, int k, const int32_t *sel_idx, float *x, int32_t *list) {
+    k_loop_control<<<1, 256, 0, st>>>(G, N, adaptive ? 1 : 0, stats, sel_count, counters, k, sel_idx, x, list);
+    return hipGetLastError();
+}
+
 // sel_idx == NULL: full pass over every row (state from x alone).  Otherwise incremental: cand, stats,
 // rowend and s+- must be the outcome of the previous call; only rows next to the selection change.
 hipError_t launch_residual_update(hipStream_t st, int N, int G, const int32_t *graph_off, const int32_t *rowptr,
                                   int32_t *rowend, int32_t *colidx, float *w, float *x, const int32_t *sel_idx,
                                   const int32_t *sel_count, int k, float *s_pos, float *s_neg, uint8_t *cand,
-                                  int32_t *stats, int32_t *touched, int32_t *list) {
+                                  int32_t *stats, int32_t *touched, int32_t *list, bool marked) {
     hipError_t e;
     if (sel_idx && k > 0) {
         const int total = G * k;
-        k_mark_selected<<<min((total + 255) / 256, 1024), 256, 0, st>>>(total, k, sel_idx, sel_count, x);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        k_reset_list<<<1, 64, 0, st>>>(list);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if (!marked) {   // (marked: launch_loop_control has set x and emptied the list already)
+            k_mark_selected<<<min((total + 255) / 256, 1024), 256, 0, st>>>(total, k, sel_idx, sel_count, x);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            k_reset_list<<<1, 64, 0, st>>>(list);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
         k_touch_rows<<<min((total + 3) / 4, 1024), 256, 0, st>>>(total, k, sel_idx, sel_count, rowptr, rowend, colidx,
                                                                 touched, list);
         if ((e = hipGetLastError()) != hipSuccess) return e;

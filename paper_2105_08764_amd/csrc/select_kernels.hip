@@ -5,6 +5,7 @@
 #include <limits.h>
 
 #include "internal.h"
+#include "reduce_util.h"
 #include "select_util.h"
 
 namespace s2v {
@@ -653,6 +654,93 @@ __global__ __launch_bounds__(256) void k_topk_write(int k, const uint32_t *__res
         idx[i] = i < n ? ids[i] : -1;
         val[i] = i < n ? key_score(keys[i]) : -INFINITY;
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// The tail of a policy evaluation and the first stage of the selection in one launch, for one state of one
+// small graph (few partial rows): what k_gsum_stage2, k_qa, k_qfinish and k_argmax_stage1 / k_smallk_stage1
+// do in four.  Every workgroup (one per chunk of kChunkNodes nodes, 1024 threads) adds the partial rows of
+// the graph sum and forms the graph term of Eq. 2 for itself -- the same device functions as the stand-alone
+// kernels, so the same bits --, completes the scores of its chunk (q = qa + node term) and finds the chunk's
+// k best candidates.  The second stage of the selection follows as usual.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_tail_select1(int p, int rows, int k, const float *__restrict__ gpart,
+                                                       const float *__restrict__ theta5,
+                                                       const float *__restrict__ theta6, float *__restrict__ gsum,
+                                                       float *__restrict__ q, const float *__restrict__ x,
+                                                       const uint8_t *__restrict__ cand,
+                                                       const int32_t *__restrict__ chunk_begin,
+                                                       const int32_t *__restrict__ chunk_end,
+                                                       float *__restrict__ part_val, int32_t *__restrict__ part_idx) {
+    __shared__ double red[64][17];
+    __shared__ float gsv[128], gs[128], redf[128];
+    __shared__ float sval[16];
+    __shared__ int sidx[16];
+    const int tid = threadIdx.x;
+    for (int cb = 0; cb < p / 16; ++cb) {
+        const int col = 16 * cb + (tid & 15);
+        const double acc = gsum_stage2_cols(p, col, 0, rows, gpart, red);
+        if ((tid >> 4) == 0) gsv[col] = (float)acc;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && tid < p) gsum[tid] = gsv[tid];
+    const float qa = qa_value(p, theta5, theta6, gsv, gs, redf);
+    const int c = blockIdx.x;
+    const int vb = chunk_begin[c], ve = chunk_end[c];
+    const int v = vb + tid;                                  // kChunkNodes == blockDim.x: one node per thread
+    float myv = -INFINITY;
+    int myi = INT_MAX;
+    if (v < ve) {
+        const float qv = qa + q[v];
+        q[v] = qv;
+        if (is_candidate(x, cand, v)) { myv = qv; myi = v; }
+    }
+    float lv = INFINITY;
+    int lidx = -1;
+    for (int it = 0; it < k; ++it) {
+        float val = -INFINITY;
+        int idx = INT_MAX;
+        if (myi != INT_MAX && beats(lv, lidx, myv, myi)) { val = myv; idx = myi; }
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            const float v2 = __shfl_xor(val, m);
+            const int i2 = __shfl_xor(idx, m);
+            take_better(val, idx, v2, i2);
+        }
+        __syncthreads();
+        if ((tid & 63) == 0) { sval[tid >> 6] = val; sidx[tid >> 6] = idx; }
+        __syncthreads();
+        val = sval[0];
+        idx = sidx[0];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) take_better(val, idx, sval[w], sidx[w]);
+        // same layout of the partial results as k_argmax_stage1 (k == 1) and k_smallk_stage1 (k > 1)
+        const size_t at = k == 1 ? (size_t)c : (size_t)c * kSmallK + it;
+        if (tid == 0) { part_val[at] = val; part_idx[at] = idx; }
+        lv = val;
+        lidx = idx;
+        if (idx == INT_MAX) {   // uniform: no further candidate in this chunk
+            if (k > 1)
+                for (int r = it + 1 + tid; r < k; r += 1024) {
+                    part_val[(size_t)c * kSmallK + r] = -INFINITY;
+                    part_idx[(size_t)c * kSmallK + r] = INT_MAX;
+                }
+            break;
+        }
+    }
+}
+
+hipError_t launch_tail_select(hipStream_t st, int p, int rows, int k, const float *gpart, const float *theta5,
+                              const float *theta6, float *gsum, float *q, const float *x, const uint8_t *cand,
+                              const ChunkTable &ct, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count) {
+    static_assert(kChunkNodes == 1024, "k_tail_select1 takes one node per thread");
+    k_tail_select1<<<ct.n_chunks, 1024, 0, st>>>(p, rows, k, gpart, theta5, theta6, gsum, q, x, cand, ct.chunk_begin,
+                                                 ct.chunk_end, sc.part_val, sc.part_idx);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (k == 1) k_argmax_stage2<<<1, 256, 0, st>>>(ct.graph_chunk_off, sc.part_val, sc.part_idx, idx, val, count);
+    else k_smallk_stage2<<<1, 256, 0, st>>>(k, ct.n_chunks, sc.part_val, sc.part_idx, idx, val, count);
+    return hipGetLastError();
 }
 
 // The reduction chunk table of ONE graph of N nodes (what s2v_graph_prepare builds on the host for a

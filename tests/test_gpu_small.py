@@ -120,12 +120,23 @@ def test_single_launch_on_a_shrinking_graph(oracle_mod):
     assert np.array_equal(idx.cpu().numpy(), oi) and np.array_equal(cnt.cpu().numpy(), oc)
 
 
-def test_larger_graphs_take_the_general_path_bit_for_bit():
-    # 1025 nodes at p = 32 no longer fit: the call is s2v_policy_eval + s2v_select_topk in sequence
-    g = si.erdos_renyi_gnp(1025, 0.01, 2)
-    theta = si.thetas(32, 3)
+@pytest.mark.parametrize("n,deg,p", [(1025, 10, 32), (3000, 450, 64), (16384, 6, 64), (16385, 6, 64)])
+@pytest.mark.parametrize("T", [2, 3])
+def test_larger_graphs_take_the_general_path_bit_for_bit(n, deg, p, T):
+    # 1025 nodes at p = 32 no longer fit a compute unit: the call is s2v_policy_eval followed by s2v_select_topk.
+    # Up to 16384 nodes the library runs the tail of the evaluation and the first stage of the selection as one
+    # launch (from 16385 on as separate ones); the caller must see the bits of the two calls either way.
+    print(f"case tail n={n} deg={deg} p={p} T={T}", flush=True)
+    g = si.erdos_renyi_gnp(n, deg / n, 2)
+    g.w = si.symmetric_edge_weights(g, 4, 0.5, 1.5)
+    theta = si.thetas(p, 3, 0.05 if deg > 100 else 0.1)
     x = si.node_flags(g.n, 0.2, 6)
-    dev = gu.Device(g, 32, 3, k_max=8)
-    out = _run(dev, theta, x, None, 8, 3)
-    for a, b in zip(out["small"], out["general"]):
-        assert np.array_equal(a, b)
+    dev = gu.Device(g, p, T, k_max=8)
+    rng = np.random.default_rng(8)
+    few = np.zeros(g.n, dtype=np.uint8)
+    few[[3, n - 1]] = 1                                                 # fewer candidates than k, none in most chunks
+    for k in (1, 2, 8):
+        for cand in (None, (rng.random(g.n) < 0.5).astype(np.uint8), few, np.zeros(g.n, dtype=np.uint8)):
+            out = _run(dev, theta, x, cand, k, T)
+            for a, b in zip(out["small"], out["general"]):
+                assert np.array_equal(a, b, equal_nan=True)
