@@ -8,6 +8,7 @@
 
 #include "../../include/s2v.h"
 #include "internal.h"
+#include "loop_util.h"
 
 using namespace s2v;
 
@@ -41,7 +42,7 @@ struct Carver {
 
 struct HeadLayout {
     size_t s_pos, s_neg, nbr_sp, nbr_spw, chunk_begin, chunk_end, graph_chunk_off;
-    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, list, loop_ctr, end;
+    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, hub_of, epoch, loop_ctr, end;
     int max_chunks, max_hubs, max_segs;
 };
 
@@ -86,8 +87,9 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     h.seg_row = c.take(sizeof(int32_t) * h.max_segs);
     h.seg_begin = c.take(sizeof(int32_t) * h.max_segs);
     h.seg_end = c.take(sizeof(int32_t) * h.max_segs);
-    h.touched = c.take(sizeof(int32_t) * N);        // per-node flags of the incremental state update
-    h.list = c.take(sizeof(int32_t) * (N + 1));     // its work list
+    h.touched = c.take(sizeof(int32_t) * N);        // per-node words of the incremental state update
+    h.hub_of = c.take(sizeof(int32_t) * (hubs > 0 ? N : 0));   // per node: its index among the long rows
+    h.epoch = c.take(sizeof(int32_t) * 2);          // number of incremental updates so far; a flag of the preparation
     h.loop_ctr = c.take(sizeof(unsigned long long) * 2);   // counters of s2v_mvc_inference
     h.end = c.off;
     return h;
@@ -327,6 +329,7 @@ HubTable hub_table(void *ws, const HeadLayout &h, const Prepared &pr) {
     ht.n_hubs = pr.n_hubs;
     ht.n_segs = pr.n_segs;
     ht.hub_rows = at<int32_t>(ws, h.hub_rows);
+    ht.hub_of = at<int32_t>(ws, h.hub_of);
     ht.hub_seg_off = at<int32_t>(ws, h.hub_seg_off);
     ht.seg_row = at<int32_t>(ws, h.seg_row);
     ht.seg_begin = at<int32_t>(ws, h.seg_begin);
@@ -574,18 +577,24 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_begin), seg_begin.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.seg_end), seg_end.data(), sizeof(int32_t) * n_segs, hipMemcpyHostToDevice, ctx->stream));
     }
+    // per node its index among the long rows (any value for other nodes): the round kernels look it up
+    std::vector<int32_t> hub_of;
+    if (n_hubs > 0) {
+        hub_of.assign((size_t)N, -1);
+        for (int i = 0; i < n_hubs; ++i) hub_of[hub_rows[i]] = i;
+        S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.hub_of), hub_of.data(), sizeof(int32_t) * (size_t)N, hipMemcpyHostToDevice, ctx->stream));
+    }
     S2V_TRY(launch_zero_i32(ctx->stream, N, at<int32_t>(ws, h.touched)));
-    // whether any weight is negative: the first word of the (still unused) work list serves as the flag
-    int32_t *neg_flag = at<int32_t>(ws, h.list);
+    // whether any weight is negative: a word beside the update counter serves as the flag
+    int32_t *neg_flag = at<int32_t>(ws, h.epoch) + 1;
     int32_t has_neg = 0;
-    S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
+    S2V_TRY(launch_zero_i32(ctx->stream, 2, at<int32_t>(ws, h.epoch)));
     S2V_TRY(launch_prepare_s(ctx->stream, N, g->rowptr, row_end_of(g), g->w, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg),
                              neg_flag));
     S2V_TRY(launch_prepare_nbr(ctx->stream, N, g->rowptr, row_end_of(g), g->colidx, g->w, at<float>(ws, h.s_pos),
                                at<float>(ws, h.nbr_sp), at<float>(ws, h.nbr_spw)));
     S2V_TRY(hipMemcpyAsync(&has_neg, neg_flag, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     S2V_TRY(hipStreamSynchronize(ctx->stream));  // the host vectors above must outlive the copies
-    S2V_TRY(launch_zero_i32(ctx->stream, 1, neg_flag));
 
     int32_t max_graph_nodes = 0;
     for (int b = 0; b < G; ++b)
@@ -738,9 +747,12 @@ int32_t s2v_policy_eval(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *para
     return S2V_OK;
 }
 
-int32_t s2v_policy_select(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x,
-                          const uint8_t *cand, int32_t T, int32_t k, float *mu_out, float *gsum, float *q, int32_t *idx,
-                          float *val, int32_t *count, void *ws, size_t ws_bytes) {
+// end != NULL (the inference loop): where the selection's last launch can also take the step's decisions and
+// begin the state update it does, and *ended says so; otherwise the caller launches them.
+static int32_t policy_select_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x,
+                                  const uint8_t *cand, int32_t T, int32_t k, float *mu_out, float *gsum, float *q,
+                                  int32_t *idx, float *val, int32_t *count, void *ws, size_t ws_bytes,
+                                  const StepEnd *end, bool *ended) {
     if (!ctx || !g || !params) return S2V_ERR_INVALID_ARG;
     if (k < 1 || !idx || !val || !count || !gsum) return S2V_ERR_INVALID_ARG;
     if (g->n_graphs > 1 && k > 1) return S2V_ERR_UNSUPPORTED;
@@ -783,7 +795,8 @@ int32_t s2v_policy_select(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
         const ChunkTable ct = chunk_table(ws, h, *pr);
         SpanGuard span(ctx, S2V_PROFILE_SELECT);
         S2V_TRY(launch_tail_select(ctx->stream, params->p, dg.rows, k, dg.gpart, params->theta5, params->theta6, gsum, q, x,
-                                   cand, ct, sc, idx, val, count));
+                                   cand, ct, sc, idx, val, count, end));
+        if (end) *ended = true;
         return S2V_OK;
     }
     if (!small) {
@@ -810,6 +823,14 @@ int32_t s2v_policy_select(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     S2V_TRY(launch_small_policy(ctx->stream, p, a));
     return S2V_OK;
 }
+
+int32_t s2v_policy_select(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *x,
+                          const uint8_t *cand, int32_t T, int32_t k, float *mu_out, float *gsum, float *q, int32_t *idx,
+                          float *val, int32_t *count, void *ws, size_t ws_bytes) {
+    return policy_select_impl(ctx, g, params, x, cand, T, k, mu_out, gsum, q, idx, val, count, ws, ws_bytes, nullptr,
+                              nullptr);
+}
+
 
 int32_t s2v_q_score(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params, const float *mu,
                     const float *gsum, int32_t S, float *q, void *ws, size_t ws_bytes) {
@@ -1084,9 +1105,28 @@ int32_t s2v_loss_grad(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
                           true);
 }
 
+static UpdateState update_state(const s2v_graph *g, const HeadLayout &h, void *ws, float *x, int32_t k, uint8_t *cand,
+                                int32_t *stats) {
+    UpdateState u{};
+    u.G = g->n_graphs;
+    u.k = k;
+    u.total = g->n_graphs * k;
+    u.graph_off = g->graph_off;
+    u.rowptr = g->rowptr;
+    u.rowend = const_cast<int32_t *>(g->row_end);
+    u.x = x;
+    u.s_pos = at<float>(ws, h.s_pos);
+    u.s_neg = at<float>(ws, h.s_neg);
+    u.cand = cand;
+    u.stats = stats;
+    u.touched = at<int32_t>(ws, h.touched);
+    u.epoch = at<int32_t>(ws, h.epoch);   // (the number of incremental updates since s2v_graph_prepare)
+    return u;
+}
+
 static int32_t residual_update_impl(s2v_ctx *ctx, const s2v_graph *g, float *x, const int32_t *sel_idx,
                                     const int32_t *sel_count, int32_t k, uint8_t *cand, int32_t *stats, void *ws,
-                                    size_t ws_bytes, bool marked) {
+                                    size_t ws_bytes, bool begun) {
     if (!ctx) return S2V_ERR_INVALID_ARG;
     int32_t rc = check_graph(g);
     if (rc != S2V_OK) return rc;
@@ -1096,14 +1136,14 @@ static int32_t residual_update_impl(s2v_ctx *ctx, const s2v_graph *g, float *x, 
     if (!g->row_end || !cand || !stats || k < 0) return S2V_ERR_INVALID_ARG;
     if (N > 0 && !x) return S2V_ERR_INVALID_ARG;
     if (sel_idx && (!sel_count || k < 1)) return S2V_ERR_INVALID_ARG;
+    if (sel_idx && (int64_t)G * k > INT32_MAX) return S2V_ERR_INVALID_ARG;
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
     const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
     if (ws_bytes < h.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
-    S2V_TRY(launch_residual_update(ctx->stream, N, G, g->graph_off, g->rowptr, const_cast<int32_t *>(g->row_end),
-                                   const_cast<int32_t *>(g->colidx), const_cast<float *>(g->w), x, sel_idx, sel_count,
-                                   sel_idx ? k : 0, at<float>(ws, h.s_pos), at<float>(ws, h.s_neg), cand, stats,
-                                   at<int32_t>(ws, h.touched), at<int32_t>(ws, h.list), marked));
+    const UpdateState u = update_state(g, h, ws, x, sel_idx ? k : 0, cand, stats);
+    S2V_TRY(launch_residual_update(ctx->stream, N, u, const_cast<int32_t *>(g->colidx), const_cast<float *>(g->w), sel_idx,
+                                   sel_count, begun));
     return S2V_OK;
 }
 
@@ -1151,14 +1191,18 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     if (rc != S2V_OK) return rc;
     const bool use_rule = adaptive && G == 1;
     const int32_t k_sel = use_rule ? kSmallK : 1;   // the largest d of the rule; the device cuts the count to d
+    if (!g->row_end) return S2V_ERR_INVALID_ARG;
+    const UpdateState upd = update_state(g, h, ws, x, k_sel, cand, stats);
+    const StepEnd end{N, use_rule, ctr, &upd};
     int32_t launched = 0, block = 1;
     while (n_live > 0 && launched < max_steps) {
         const int32_t todo = block < max_steps - launched ? block : max_steps - launched;
         for (int32_t i = 0; i < todo; ++i) {
-            rc = s2v_policy_select(ctx, g, params, x, cand, T, k_sel, mu, gsum, q, sel_idx, sel_val, sel_count, ws, ws_bytes);
+            bool ended = false;
+            rc = policy_select_impl(ctx, g, params, x, cand, T, k_sel, mu, gsum, q, sel_idx, sel_val, sel_count, ws, ws_bytes,
+                                    &end, &ended);
             if (rc != S2V_OK) return rc;
-            S2V_TRY(launch_loop_control(ctx->stream, G, N, use_rule, stats, sel_count, ctr, k_sel, sel_idx, x,
-                                        at<int32_t>(ws, h.list)));
+            if (!ended) S2V_TRY(launch_loop_control(ctx->stream, N, use_rule, sel_count, ctr, sel_idx, upd));
             rc = residual_update_impl(ctx, g, x, sel_idx, sel_count, k_sel, cand, stats, ws, ws_bytes, true);
             if (rc != S2V_OK) return rc;
         }

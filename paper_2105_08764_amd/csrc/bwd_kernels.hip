@@ -480,7 +480,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
             const int s0 = __builtin_amdgcn_readfirstlane(s);
             NodeAcc<P> ga;
             if (e - b > kHubDegree) {
-                const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
+                const int h = hub_index(ht, __builtin_amdgcn_readfirstlane(v));
                 ga = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
             } else if (MASK) {
                 ga = W ? gather_node_block_bits_w<P>(maskT, S, s0, colidx, wagg, b, e, lane)
@@ -525,7 +525,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                 }
                 float4 a;
                 if (e - b > kHubDegree) {
-                    const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readlane(v, i));
+                    const int h = hub_index(ht, __builtin_amdgcn_readlane(v, i));
                     a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
                 } else if (MASK) {
                     const BitsRow bits{maskT, S, si, 4 * li};
@@ -605,7 +605,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
             if constexpr (FLAGS) {
                 if (ef - bf > kHubDegree) {
                     // the long row's four sums, plain [4][S][P] blocks: a into the tile, cx and cp by column
-                    const int h = hub_index(ht.hub_rows, ht.n_hubs, vf);
+                    const int h = hub_index(ht, vf);
                     const float *hb = ff.hub_sum4 + ((size_t)h * 4 * S + s0f) * P + (lane % P);
 #pragma unroll
                     for (int st = 0; st < 16; ++st) {
@@ -618,7 +618,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
                                                       ni.node(vf)[ni.sn_off + 1], wagg);
                 }
             } else if (ef - bf > kHubDegree) {
-                const int h = hub_index(ht.hub_rows, ht.n_hubs, vf);
+                const int h = hub_index(ht, vf);
                 const float *hb = ff.hub_sum4 + ((size_t)h * 4 * S + s0f) * P;
                 g4.a = load_node_block_sm<P>(hb, lane);
                 g4.cx = load_node_block_sm<P>(hb + (size_t)S * P, lane);
@@ -861,7 +861,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
         float cx16[FLAGS ? 16 : 1], cp16[FLAGS ? 16 : 1];
         if constexpr (FLAGS) {
             if (e - b > kHubDegree) {
-                const int h = hub_index(ht.hub_rows, ht.n_hubs, v);
+                const int h = hub_index(ht, v);
                 const float *hb = hub_sum4 + ((size_t)h * 4 * S + s0) * P + (lane % P);
 #pragma unroll
                 for (int st = 0; st < 16; ++st) {
@@ -874,7 +874,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
                                                   ni.node(v)[ni.sn_off + 1], wagg);
             }
         } else if (e - b > kHubDegree) {
-            const int h = hub_index(ht.hub_rows, ht.n_hubs, v);
+            const int h = hub_index(ht, v);
             const float *hb = hub_sum4 + ((size_t)h * 4 * S + s0) * P;
             g4.a = load_node_block_sm<P>(hb, lane);
             g4.cx = load_node_block_sm<P>(hb + (size_t)S * P, lane);

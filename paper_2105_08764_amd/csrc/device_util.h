@@ -958,15 +958,8 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long
     return acc;
 }
 
-// Index of node v in the ascending list of hub rows (v is known to be a hub).
-__device__ __forceinline__ int hub_index(const int32_t *__restrict__ hub_rows, int n_hubs, int v) {
-    int lo = 0, hi = n_hubs - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (hub_rows[mid] < v) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
+// Index of node v among the long rows (v is known to be one): one load from the per-node table.
+__device__ __forceinline__ int hub_index(const HubTable &ht, int v) { return ht.hub_of[v]; }
 
 // A node-mode block read back from the hub sums instead of gathered.
 template <int P>

@@ -457,7 +457,7 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
             const int s0 = __builtin_amdgcn_readfirstlane(s);
             NodeAcc<P> acc;
             if (e - b > kHubDegree) {
-                const int h = hub_index(ht.hub_rows, ht.n_hubs, __builtin_amdgcn_readfirstlane(v));
+                const int h = hub_index(ht, __builtin_amdgcn_readfirstlane(v));
                 acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
                 store_node_block<P>(tile, acc, lane);
             } else if (MU1 && info.flags16) {
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
             // them together (each lane looks up its own row, then RPI rows per wave-wide load).
             const bool long_mine = re - rb > kHubDegree;
             if (__builtin_amdgcn_ballot_w64(long_mine) != 0ull) {
-                const int h_mine = long_mine ? hub_index(ht.hub_rows, ht.n_hubs, v) : -1;
+                const int h_mine = long_mine ? hub_index(ht, v) : -1;
                 constexpr int RPI = G::NPL, NC = 16 / RPI;
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {

@@ -41,6 +41,7 @@ constexpr int kHubSegment = 512;
 struct HubTable {              // device pointers into the prepared head of the workspace
     int n_hubs, n_segs;
     const int32_t *hub_rows;     // [n_hubs] node ids, ascending
+    const int32_t *hub_of;       // [N] (with n_hubs > 0) index of a long row's node in hub_rows
     const int32_t *hub_seg_off;  // [n_hubs+1] segments of hub h are [off[h], off[h+1])
     const int32_t *seg_row;      // [n_segs] node id of the segment's row
     const int32_t *seg_begin;    // [n_segs] first CSR entry of the segment
@@ -179,15 +180,21 @@ hipError_t launch_qnode(hipStream_t st, int p, int N, int S, int G, const int32_
 hipError_t launch_stream_read(hipStream_t st, const void *src, size_t bytes, float *out);
 
 // ---- state update of the inference loop (residual_kernels.hip) ----
-hipError_t launch_residual_update(hipStream_t st, int N, int G, const int32_t *graph_off, const int32_t *rowptr,
-                                  int32_t *rowend, int32_t *colidx, float *w, float *x, const int32_t *sel_idx,
-                                  const int32_t *sel_count, int k, float *s_pos, float *s_neg, uint8_t *cand,
-                                  int32_t *stats /*[G][2]*/, int32_t *touched /*[N], all zero between calls*/,
-                                  int32_t *list /*[N+1]*/, bool marked = false);
+struct UpdateState;   // (loop_util.h)
+// what the end of a step of the inference loop needs beyond the selection's outputs (see loop_control)
+struct StepEnd {
+    int N;
+    bool adaptive;
+    unsigned long long *counters;
+    const UpdateState *update;
+};
+hipError_t launch_residual_update(hipStream_t st, int N, const UpdateState &u, int32_t *colidx, float *w,
+                                  const int32_t *sel_idx /*[G][k] or NULL: full pass*/, const int32_t *sel_count,
+                                  bool begun = false);
 hipError_t launch_zero_i32(hipStream_t st, long n, int32_t *p);
-hipError_t launch_loop_control(hipStream_t st, int G, int N, bool adaptive, const int32_t *stats, int32_t *sel_count,
-                               unsigned long long *counters /*[2]: evaluations that mattered, nodes added*/, int k,
-                               const int32_t *sel_idx /*[G][k]*/, float *x, int32_t *list);
+hipError_t launch_loop_control(hipStream_t st, int N, bool adaptive, int32_t *sel_count,
+                               unsigned long long *counters /*[2]: evaluations that mattered, nodes added*/,
+                               const int32_t *sel_idx /*[G][k]*/, const UpdateState &u);
 
 // ---- one launch per step of Alg. 3 on small graphs (small_kernels.hip) ----
 // floats of LDS that hold one graph's embedding: a graph qualifies when n_nodes * p does not exceed it
@@ -236,7 +243,9 @@ constexpr int kTailMaxRows = 256;
 hipError_t launch_tail_select(hipStream_t st, int p, int rows, int k, const float *gpart /*[rows][p]*/,
                               const float *theta5, const float *theta6, float *gsum /*[p]*/,
                               float *q /*[N]: in the node term, out Eq. 2*/, const float *x, const uint8_t *cand,
-                              const ChunkTable &ct, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
+                              const ChunkTable &ct, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count,
+                              const StepEnd *end = nullptr /*non-NULL: the selection's last launch also takes the
+                                                             step's decisions and begins the state update*/);
 hipError_t launch_topk(hipStream_t st, int N, const float *q, const float *x, const uint8_t *cand, int k,
                        const SelectScratch &sc, int32_t *idx, float *val, int32_t *count);
 

@@ -1,0 +1,99 @@
+// The end of one step of the loop of Alg. 3 as device functions, so that the kernel that finishes the selection
+// can take the step's decisions and start the state update in the same launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace s2v {
+
+__device__ __forceinline__ int graph_of(int G, const int32_t *__restrict__ graph_off, int v) {
+    if (G == 1) return 0;
+    int lo = 0, hi = G;   // last graph whose offset is <= v
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (graph_off[mid] <= v) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// What the incremental state update needs to know and change (Alg. 3 lines 8-10 on the mutable CSR copy).
+struct UpdateState {
+    int G, total, k;                     // total = G * k entries of sel_idx
+    const int32_t *graph_off;
+    const int32_t *rowptr;
+    int32_t *rowend;
+    float *x, *s_pos, *s_neg;
+    uint8_t *cand;
+    int32_t *stats;                      // [G][2]: candidates, live stored entries
+    int32_t *touched;                    // [N]: > 0 the update that last filtered the row; < 0 see begin_update
+    int32_t *epoch;                      // [1]: number of updates so far
+};
+
+// First half of the incremental state update, by the threads [tid, tid + stride, ...) of one or more workgroups:
+// every selected node joins the solution (x = 1) and its row becomes empty.  The row's stored entries stay where
+// they are, and touched[v] = -(the length it had): the second half (k_refilter_neighbours) walks them to find
+// the rows that lose an entry.  A node listed twice is emptied once (the exchange on its row end decides).
+__device__ __forceinline__ void begin_update(const UpdateState &u, const int32_t *sel_idx, const int32_t *sel_count,
+                                             int tid, int stride) {
+    for (int i = tid; i < u.total; i += stride) {
+        const int g = i / u.k, j = i - g * u.k;
+        if (j >= sel_count[g]) continue;
+        const int v = sel_idx[i];
+        if (v < 0) continue;
+        u.x[v] = 1.f;
+        const int b = u.rowptr[v];
+        const int len = atomicExch(&u.rowend[v], b) - b;
+        if (len <= 0) continue;
+        u.touched[v] = -len;
+        u.s_pos[v] = 0.f;
+        u.s_neg[v] = 0.f;
+        const int gg = graph_of(u.G, u.graph_off, v);
+        if (u.cand[v]) atomicAdd(&u.stats[2 * gg], -1);
+        u.cand[v] = 0;
+        atomicAdd(&u.stats[2 * gg + 1], -len);
+    }
+}
+
+// The decisions of one step, taken on the device so that the host need not read anything back between steps; by
+// one workgroup of 256 threads.  stats holds {candidates, live stored entries} per graph as the last state update
+// left them (the state this step's scores were computed on); sel_count holds how many nodes the selection found
+// per graph (it asked for the largest d of the rule).  For one graph and the adaptive rule of Sec. 4.5.1, d
+// follows from the candidate count and the count is cut to d (the selection is ordered, so its first d entries
+// are the top-d); when no edge is left anywhere the counts become zero and the state update that follows changes
+// nothing.  counters[0] += 1 when an edge was left (a policy evaluation that mattered), counters[1] += nodes
+// added.  Then the first half of the state update (begin_update) and the update counter.
+// s_live, s_picked: LDS, one word each.  Starts with a barrier (the caller may just have written sel_count).
+// (no __restrict__ here: a caller may have written sel_idx and sel_count through pointers of its own)
+__device__ __forceinline__ void loop_control(int N, int adaptive, int32_t *sel_count, unsigned long long *counters,
+                                             const int32_t *sel_idx, const UpdateState &u,
+                                             unsigned long long *s_live, unsigned long long *s_picked) {
+    const int G = u.G;
+    if (threadIdx.x == 0) { *s_live = 0ull; *s_picked = 0ull; }
+    __syncthreads();
+    unsigned long long live = 0ull;
+    for (int b = threadIdx.x; b < G; b += 256) live += (unsigned long long)u.stats[2 * b + 1];
+    if (live) atomicAdd(s_live, live);
+    int d = 1;
+    if (adaptive && G == 1) {
+        const long long c = u.stats[0];
+        d = 2 * c > N ? 8 : (4 * c > N ? 4 : (8 * c > N ? 2 : 1));
+    }
+    __syncthreads();
+    const bool going = *s_live > 0ull;
+    unsigned long long picked = 0ull;
+    for (int b = threadIdx.x; b < G; b += 256) {
+        const int c = going ? min(sel_count[b], d) : 0;
+        sel_count[b] = c;
+        picked += (unsigned long long)c;
+    }
+    if (picked) atomicAdd(s_picked, picked);
+    __syncthreads();   // (this workgroup wrote the counts and read the statistics: both are settled from here on)
+    if (threadIdx.x == 0 && going) {
+        counters[0] += 1ull;
+        counters[1] += *s_picked;
+    }
+    begin_update(u, sel_idx, sel_count, threadIdx.x, 256);
+    if (threadIdx.x == 0) u.epoch[0] += 1;
+}
+
+}  // namespace s2v

@@ -5,19 +5,9 @@
 // the rows of solution nodes become empty.  The round-invariant edge sums s+ / s- are refreshed
 // in the same pass, so no new graph preparation is needed between steps.
 #include "internal.h"
+#include "loop_util.h"
 
 namespace s2v {
-
-__global__ __launch_bounds__(256) void k_mark_selected(int total, int k, const int32_t *__restrict__ idx,
-                                                       const int32_t *__restrict__ count, float *__restrict__ x) {
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
-        const int g = i / k, j = i - g * k;
-        if (j < count[g]) {
-            const int v = idx[i];
-            if (v >= 0) x[v] = 1.f;
-        }
-    }
-}
 
 __global__ void k_zero_stats(int n, int32_t *__restrict__ stats) {
     for (int i = threadIdx.x; i < n; i += blockDim.x) stats[i] = 0;
@@ -65,16 +55,6 @@ __device__ __forceinline__ int filter_row(int v, int lane, const int32_t *__rest
     return out;
 }
 
-__device__ __forceinline__ int graph_of(int G, const int32_t *__restrict__ graph_off, int v) {
-    if (G == 1) return 0;
-    int lo = 0, hi = G;   // last graph whose offset is <= v
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (graph_off[mid] <= v) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 // Full pass: one wave per row.  stats[g] = {candidates, live stored entries} of graph g (integer atomics).
 __global__ __launch_bounds__(256) void k_residual_rows(int N, const int32_t *__restrict__ rowptr,
                                                        int32_t *__restrict__ rowend, int32_t *__restrict__ colidx,
@@ -107,57 +87,56 @@ __global__ __launch_bounds__(256) void k_residual_rows(int N, const int32_t *__r
 }
 
 // ---- incremental update: only the rows next to the newly selected nodes change ------------------
-// Step 1 (one wave per selected node v): list v and every live neighbour of v, each row once
-// (`touched` is a per-node flag, test-and-set).  list[0] is the list length.
-__global__ __launch_bounds__(256) void k_touch_rows(int total, int k, const int32_t *__restrict__ idx,
-                                                    const int32_t *__restrict__ count,
-                                                    const int32_t *__restrict__ rowptr,
-                                                    const int32_t *__restrict__ rowend,
-                                                    const int32_t *__restrict__ colidx, int32_t *__restrict__ touched,
-                                                    int32_t *__restrict__ list) {
+// First half (begin_update): the selected nodes join the solution and their rows become empty; the stored entries
+// of such a row stay in place and touched[v] = -(its old length).
+__global__ __launch_bounds__(256) void k_begin_update(UpdateState u, const int32_t *__restrict__ sel_idx,
+                                                      const int32_t *__restrict__ sel_count) {
+    begin_update(u, sel_idx, sel_count, blockIdx.x * 256 + threadIdx.x, gridDim.x * 256);
+    if (blockIdx.x == 0 && threadIdx.x == 0) u.epoch[0] += 1;
+}
+
+// Second half: blockIdx.y walks the selected nodes, the waves of the blocks along x the entries their rows had.
+// Each neighbour u outside the solution is filtered once per update: the first wave to stamp touched[u] with the
+// update's number does it (a solution node's row is empty already, and its touched word holds a length).
+// The outcome of a row does not depend on the order in which rows are processed; the counters move by the change.
+__global__ __launch_bounds__(256) void k_refilter_neighbours(int total, int k, const int32_t *__restrict__ sel_idx,
+                                                             const int32_t *__restrict__ sel_count,
+                                                             const int32_t *__restrict__ rowptr,
+                                                             int32_t *__restrict__ rowend, int32_t *__restrict__ colidx,
+                                                             float *__restrict__ w, const float *__restrict__ x,
+                                                             float *__restrict__ s_pos, float *__restrict__ s_neg,
+                                                             uint8_t *__restrict__ cand, int G,
+                                                             const int32_t *__restrict__ graph_off,
+                                                             int32_t *__restrict__ stats, int32_t *__restrict__ touched,
+                                                             const int32_t *__restrict__ epoch) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int i = blockIdx.x * 4 + wave; i < total; i += gridDim.x * 4) {
+    const int ep = epoch[0];
+    for (int i = blockIdx.y; i < total; i += gridDim.y) {
         const int g = i / k, j = i - g * k;
-        if (j >= count[g]) continue;
-        const int v = idx[i];
+        if (j >= sel_count[g]) continue;
+        const int v = sel_idx[i];
         if (v < 0) continue;
-        if (lane == 0 && atomicExch(&touched[v], 1) == 0) list[1 + atomicAdd(&list[0], 1)] = v;
-        for (int e = rowptr[v] + lane; e < rowend[v]; e += 64) {
-            const int u = colidx[e];
-            if (atomicExch(&touched[u], 1) == 0) list[1 + atomicAdd(&list[0], 1)] = u;
+        const int len = -touched[v];
+        if (len <= 0) continue;   // (the node had no live entry when it joined)
+        const int b = rowptr[v];
+        for (int t = blockIdx.x * 4 + wave; t < len; t += gridDim.x * 4) {
+            const int u = colidx[b + t];
+            if (x[u] != 0.f) continue;
+            int first = 0;
+            if (lane == 0) first = atomicExch(&touched[u], ep) != ep ? 1 : 0;
+            if (!__shfl(first, 0)) continue;
+            const int old_len = rowend[u] - rowptr[u];
+            const int old_cand = cand[u];
+            const int out = filter_row(u, lane, rowptr, rowend, colidx, w, x, s_pos, s_neg);
+            if (lane == 0) {
+                const int new_cand = out > 0 ? 1 : 0;
+                cand[u] = (uint8_t)new_cand;
+                const int gg = graph_of(G, graph_off, u);
+                if (new_cand != old_cand) atomicAdd(&stats[2 * gg], new_cand - old_cand);
+                if (out != old_len) atomicAdd(&stats[2 * gg + 1], out - old_len);
+            }
         }
     }
-}
-
-// Step 2 (one wave per listed row): filter the row and move the counters by the change.  The
-// outcome of a row does not depend on the order in which rows are processed.
-__global__ __launch_bounds__(256) void k_refilter_rows(const int32_t *__restrict__ rowptr, int32_t *__restrict__ rowend,
-                                                       int32_t *__restrict__ colidx, float *__restrict__ w,
-                                                       const float *__restrict__ x, float *__restrict__ s_pos,
-                                                       float *__restrict__ s_neg, uint8_t *__restrict__ cand, int G,
-                                                       const int32_t *__restrict__ graph_off,
-                                                       int32_t *__restrict__ stats, int32_t *__restrict__ touched,
-                                                       const int32_t *__restrict__ list) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n = list[0];
-    for (int i = blockIdx.x * 4 + wave; i < n; i += gridDim.x * 4) {
-        const int v = list[1 + i];
-        const int old_len = rowend[v] - rowptr[v];
-        const int old_cand = cand[v];
-        const int out = filter_row(v, lane, rowptr, rowend, colidx, w, x, s_pos, s_neg);
-        if (lane == 0) {
-            const int new_cand = out > 0 ? 1 : 0;
-            cand[v] = (uint8_t)new_cand;
-            touched[v] = 0;
-            const int g = graph_of(G, graph_off, v);
-            if (new_cand != old_cand) atomicAdd(&stats[2 * g], new_cand - old_cand);
-            if (out != old_len) atomicAdd(&stats[2 * g + 1], out - old_len);
-        }
-    }
-}
-
-__global__ void k_reset_list(int32_t *__restrict__ list) {
-    if (threadIdx.x == 0) list[0] = 0;
 }
 
 __global__ __launch_bounds__(256) void k_zero_i32(long n, int32_t *__restrict__ p) {
@@ -170,89 +149,44 @@ hipError_t launch_zero_i32(hipStream_t st, long n, int32_t *p) {
     return hipGetLastError();
 }
 
-// The decisions of one step of the loop of Alg. 3, taken on the device so that the host need not read anything
-// back between steps.  stats holds {candidates, live stored entries} per graph as the last state update left
-// them (the state this step's scores were computed on); sel_count holds how many nodes the selection found per
-// graph (it asked for the largest d of the rule).  For one graph and the adaptive rule of Sec. 4.5.1, d follows
-// from the candidate count and the count is cut to d (the selection is ordered, so its first d entries are the
-// top-d); when no edge is left anywhere the counts become zero and the state update that follows changes nothing.
-// counters[0] += 1 when an edge was left (a policy evaluation that mattered), counters[1] += nodes added.
-// The same launch also does the first two steps of the state update that follows: the selected nodes join the
-// solution (x = 1, as k_mark_selected) and the work list of the incremental update is emptied (as k_reset_list).
-__global__ __launch_bounds__(256) void k_loop_control(int G, int N, int adaptive, const int32_t *__restrict__ stats,
-                                                      int32_t *__restrict__ sel_count,
-                                                      unsigned long long *__restrict__ counters, int k,
-                                                      const int32_t *__restrict__ sel_idx, float *__restrict__ x,
-                                                      int32_t *__restrict__ list) {
+// The decisions of one step of the loop and the first half of the state update that follows (see loop_util.h).
+__global__ __launch_bounds__(256) void k_loop_control(int N, int adaptive, int32_t *__restrict__ sel_count,
+                                                      unsigned long long *__restrict__ counters,
+                                                      const int32_t *__restrict__ sel_idx, UpdateState u) {
     __shared__ unsigned long long s_live, s_picked;
-    if (threadIdx.x == 0) { s_live = 0ull; s_picked = 0ull; }
-    __syncthreads();
-    unsigned long long live = 0ull;
-    for (int b = threadIdx.x; b < G; b += 256) live += (unsigned long long)stats[2 * b + 1];
-    if (live) atomicAdd(&s_live, live);
-    __syncthreads();
-    const bool going = s_live > 0ull;
-    int d = 1;
-    if (adaptive && G == 1) {
-        const long long c = stats[0];
-        d = 2 * c > N ? 8 : (4 * c > N ? 4 : (8 * c > N ? 2 : 1));
-    }
-    unsigned long long picked = 0ull;
-    for (int b = threadIdx.x; b < G; b += 256) {
-        const int c = going ? min(sel_count[b], d) : 0;
-        sel_count[b] = c;
-        picked += (unsigned long long)c;
-    }
-    if (picked) atomicAdd(&s_picked, picked);
-    __syncthreads();
-    if (threadIdx.x == 0 && going) {
-        counters[0] += 1ull;
-        counters[1] += s_picked;
-    }
-    if (threadIdx.x == 0) list[0] = 0;
-    // (this block wrote the counts: after the barrier above every thread sees them)
-    for (int i = threadIdx.x; i < G * k; i += 256) {
-        const int g = i / k, j = i - g * k;
-        if (j < sel_count[g]) {
-            const int v = sel_idx[i];
-            if (v >= 0) x[v] = 1.f;
-        }
-    }
+    loop_control(N, adaptive, sel_count, counters, sel_idx, u, &s_live, &s_picked);
 }
 
-hipError_t launch_loop_control(hipStream_t st, int G, int N, bool adaptive, const int32_t *stats, int32_t *sel_count,
-                               unsigned long long *counters, int k, const int32_t *sel_idx, float *x, int32_t *list) {
-    k_loop_control<<<1, 256, 0, st>>>(G, N, adaptive ? 1 : 0, stats, sel_count, counters, k, sel_idx, x, list);
+hipError_t launch_loop_control(hipStream_t st, int N, bool adaptive, int32_t *sel_count, unsigned long long *counters,
+                               const int32_t *sel_idx, const UpdateState &u) {
+    k_loop_control<<<1, 256, 0, st>>>(N, adaptive ? 1 : 0, sel_count, counters, sel_idx, u);
     return hipGetLastError();
 }
 
 // sel_idx == NULL: full pass over every row (state from x alone).  Otherwise incremental: cand, stats,
 // rowend and s+- must be the outcome of the previous call; only rows next to the selection change.
-hipError_t launch_residual_update(hipStream_t st, int N, int G, const int32_t *graph_off, const int32_t *rowptr,
-                                  int32_t *rowend, int32_t *colidx, float *w, float *x, const int32_t *sel_idx,
-                                  const int32_t *sel_count, int k, float *s_pos, float *s_neg, uint8_t *cand,
-                                  int32_t *stats, int32_t *touched, int32_t *list, bool marked) {
+// begun: launch_loop_control (or a kernel that runs loop_control) has done the first half already.
+hipError_t launch_residual_update(hipStream_t st, int N, const UpdateState &u, int32_t *colidx, float *w,
+                                  const int32_t *sel_idx, const int32_t *sel_count, bool begun) {
     hipError_t e;
-    if (sel_idx && k > 0) {
-        const int total = G * k;
-        if (!marked) {   // (marked: launch_loop_control has set x and emptied the list already)
-            k_mark_selected<<<min((total + 255) / 256, 1024), 256, 0, st>>>(total, k, sel_idx, sel_count, x);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-            k_reset_list<<<1, 64, 0, st>>>(list);
+    if (sel_idx && u.k > 0) {
+        if (!begun) {
+            k_begin_update<<<min((u.total + 255) / 256, 64), 256, 0, st>>>(u, sel_idx, sel_count);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
-        k_touch_rows<<<min((total + 3) / 4, 1024), 256, 0, st>>>(total, k, sel_idx, sel_count, rowptr, rowend, colidx,
-                                                                touched, list);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        k_refilter_rows<<<1024, 256, 0, st>>>(rowptr, rowend, colidx, w, x, s_pos, s_neg, cand, G, graph_off, stats,
-                                              touched, list);
+        const int gy = min(u.total, 1024);
+        const int gx = max(1, min(1024 / gy, (N + 3) / 4));
+        k_refilter_neighbours<<<dim3(gx, gy), 256, 0, st>>>(u.total, u.k, sel_idx, sel_count, u.rowptr, u.rowend, colidx, w,
+                                                           u.x, u.s_pos, u.s_neg, u.cand, u.G, u.graph_off, u.stats,
+                                                           u.touched, u.epoch);
         return hipGetLastError();
     }
-    k_zero_stats<<<1, 256, 0, st>>>(2 * G, stats);
+    k_zero_stats<<<1, 256, 0, st>>>(2 * u.G, u.stats);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (N > 0) {
         const int grid = min((N + 3) / 4, 256 * 32);
-        k_residual_rows<<<grid, 256, 0, st>>>(N, rowptr, rowend, colidx, w, x, s_pos, s_neg, cand, G, graph_off, stats);
+        k_residual_rows<<<grid, 256, 0, st>>>(N, u.rowptr, u.rowend, colidx, w, u.x, u.s_pos, u.s_neg, u.cand, u.G,
+                                              u.graph_off, u.stats);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;

@@ -5,6 +5,7 @@
 #include <limits.h>
 
 #include "internal.h"
+#include "loop_util.h"
 #include "reduce_util.h"
 #include "select_util.h"
 
@@ -42,14 +43,10 @@ __global__ __launch_bounds__(256) void k_argmax_stage1(const int32_t *__restrict
     if (threadIdx.x == 0) { part_val[c] = val; part_idx[c] = idx; }
 }
 
-__global__ __launch_bounds__(256) void k_argmax_stage2(const int32_t *__restrict__ graph_chunk_off,
-                                                       const float *__restrict__ part_val,
-                                                       const int32_t *__restrict__ part_idx,
-                                                       int32_t *__restrict__ idx_out, float *__restrict__ val_out,
-                                                       int32_t *__restrict__ count) {
-    __shared__ float sval[4];
-    __shared__ int sidx[4];
-    const int g = blockIdx.x;
+// Second stage of the argmax of graph g, by one workgroup of 256 threads.  sval, sidx: LDS, 4 entries each.
+__device__ __forceinline__ void argmax_stage2(int g, const int32_t *graph_chunk_off, const float *part_val,
+                                              const int32_t *part_idx, int32_t *idx_out, float *val_out, int32_t *count,
+                                              float *sval, int *sidx) {
     float val = -INFINITY;
     int idx = INT_MAX;
     for (int c = graph_chunk_off[g] + threadIdx.x; c < graph_chunk_off[g + 1]; c += 256)
@@ -61,6 +58,16 @@ __global__ __launch_bounds__(256) void k_argmax_stage2(const int32_t *__restrict
         val_out[g] = any ? val : -INFINITY;
         count[g] = any ? 1 : 0;
     }
+}
+
+__global__ __launch_bounds__(256) void k_argmax_stage2(const int32_t *__restrict__ graph_chunk_off,
+                                                       const float *__restrict__ part_val,
+                                                       const int32_t *__restrict__ part_idx,
+                                                       int32_t *__restrict__ idx_out, float *__restrict__ val_out,
+                                                       int32_t *__restrict__ count) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    argmax_stage2(blockIdx.x, graph_chunk_off, part_val, part_idx, idx_out, val_out, count, sval, sidx);
 }
 
 hipError_t launch_argmax(hipStream_t st, int N, int G, const ChunkTable &ct, const float *q, const float *x,
@@ -134,12 +141,9 @@ __global__ __launch_bounds__(256) void k_smallk_stage1(int k, const int32_t *__r
     }
 }
 
-__global__ __launch_bounds__(256) void k_smallk_stage2(int k, int n_chunks, const float *__restrict__ part_val,
-                                                       const int32_t *__restrict__ part_idx,
-                                                       int32_t *__restrict__ idx_out, float *__restrict__ val_out,
-                                                       int32_t *__restrict__ count) {
-    __shared__ float sval[4];
-    __shared__ int sidx[4];
+// Second stage of the top-k (k <= kSmallK) of one graph, by one workgroup of 256 threads.
+__device__ __forceinline__ void smallk_stage2(int k, int n_chunks, const float *part_val, const int32_t *part_idx,
+                                              int32_t *idx_out, float *val_out, int32_t *count, float *sval, int *sidx) {
     float lv = INFINITY;
     int lidx = -1;
     int found = 0;
@@ -165,6 +169,29 @@ __global__ __launch_bounds__(256) void k_smallk_stage2(int k, int n_chunks, cons
     }
     for (int r = found + threadIdx.x; r < k; r += 256) { idx_out[r] = -1; val_out[r] = -INFINITY; }
     if (threadIdx.x == 0) count[0] = found;
+}
+
+__global__ __launch_bounds__(256) void k_smallk_stage2(int k, int n_chunks, const float *__restrict__ part_val,
+                                                       const int32_t *__restrict__ part_idx,
+                                                       int32_t *__restrict__ idx_out, float *__restrict__ val_out,
+                                                       int32_t *__restrict__ count) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    smallk_stage2(k, n_chunks, part_val, part_idx, idx_out, val_out, count, sval, sidx);
+}
+
+// The last launch of a step of the loop on one graph: second stage of the selection, then the step's decisions
+// and the first half of the state update (loop_control).
+__global__ __launch_bounds__(256) void k_step_end(int k, int n_chunks, const int32_t *graph_chunk_off,
+                                                  const float *part_val, const int32_t *part_idx, int32_t *idx_out,
+                                                  float *val_out, int32_t *count, int N, int adaptive,
+                                                  unsigned long long *counters, UpdateState u) {
+    __shared__ float sval[4];
+    __shared__ int sidx[4];
+    __shared__ unsigned long long s_live, s_picked;
+    if (k == 1) argmax_stage2(0, graph_chunk_off, part_val, part_idx, idx_out, val_out, count, sval, sidx);
+    else smallk_stage2(k, n_chunks, part_val, part_idx, idx_out, val_out, count, sval, sidx);
+    loop_control(N, adaptive, count, counters, idx_out, u, &s_live, &s_picked);
 }
 
 hipError_t launch_smallk(hipStream_t st, const ChunkTable &ct, const float *q, const float *x, const uint8_t *cand,
@@ -732,13 +759,17 @@ __global__ __launch_bounds__(1024) void k_tail_select1(int p, int rows, int k, c
 
 hipError_t launch_tail_select(hipStream_t st, int p, int rows, int k, const float *gpart, const float *theta5,
                               const float *theta6, float *gsum, float *q, const float *x, const uint8_t *cand,
-                              const ChunkTable &ct, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count) {
+                              const ChunkTable &ct, const SelectScratch &sc, int32_t *idx, float *val, int32_t *count,
+                              const StepEnd *end) {
     static_assert(kChunkNodes == 1024, "k_tail_select1 takes one node per thread");
     k_tail_select1<<<ct.n_chunks, 1024, 0, st>>>(p, rows, k, gpart, theta5, theta6, gsum, q, x, cand, ct.chunk_begin,
                                                  ct.chunk_end, sc.part_val, sc.part_idx);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (k == 1) k_argmax_stage2<<<1, 256, 0, st>>>(ct.graph_chunk_off, sc.part_val, sc.part_idx, idx, val, count);
+    if (end)
+        k_step_end<<<1, 256, 0, st>>>(k, ct.n_chunks, ct.graph_chunk_off, sc.part_val, sc.part_idx, idx, val, count, end->N,
+                                      end->adaptive ? 1 : 0, end->counters, *end->update);
+    else if (k == 1) k_argmax_stage2<<<1, 256, 0, st>>>(ct.graph_chunk_off, sc.part_val, sc.part_idx, idx, val, count);
     else k_smallk_stage2<<<1, 256, 0, st>>>(k, ct.n_chunks, sc.part_val, sc.part_idx, idx, val, count);
     return hipGetLastError();
 }

@@ -86,7 +86,7 @@ def test_state_update_matches_oracle_residual_graph(oracle_mod, kind):
     dev.update()                                                                    # full rebuild first
     for rnd in range(5):
         # a few nodes enter the solution through the selection arrays, a few directly through x
-        pick = rng.choice(np.flatnonzero(x == 0), size=min(8, int((x == 0).sum())), replace=False).astype(np.int32)
+        pick = rng.choice(np.flatnonzero(x == 0), size=min(8 if rnd != 2 else 6, int((x == 0).sum())), replace=False).astype(np.int32)
         if kind == "hub" and rnd == 1:
             pick[0] = 0                                                             # the star's hub
         G = g.n_graphs
@@ -97,6 +97,15 @@ def test_state_update_matches_oracle_residual_graph(oracle_mod, kind):
             b = int(np.searchsorted(offs, v, side="right") - 1)
             sel[b, cnt[b]] = v
             cnt[b] += 1
+        if rnd == 2:
+            # a node listed twice, and one that joined the solution earlier: both must change nothing more
+            b = int(np.argmax(cnt))
+            old = np.flatnonzero(x != 0)
+            old = old[(old >= offs[b]) & (old < offs[b + 1])]
+            for extra in ([sel[b, 0]] + ([old[0]] if old.size else [])):
+                if cnt[b] < 8:
+                    sel[b, cnt[b]] = extra
+                    cnt[b] += 1
         dev.sel_idx.copy_(torch.from_numpy(sel))
         dev.sel_cnt.copy_(torch.from_numpy(cnt))
         if rnd == 3:
