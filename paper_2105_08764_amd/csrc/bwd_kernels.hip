@@ -296,8 +296,11 @@ struct FirstFuse {
     const float *hub_sum4;   // [n_hubs][4][S][P]
 };
 
+#ifndef S2V_BWD_MASK_OCC
+#define S2V_BWD_MASK_OCC 2
+#endif
 template <int P, bool NODE, bool MASK, bool W, bool FUSE, bool NEG, bool FLAGS = false>   // W: weighted neighbour sum (symmetric weights wagg)
-__global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
+__global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) void k_bwd_round(
     int n_vrows, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in, const unsigned long long *__restrict__ maskT, const float *__restrict__ dg,
     const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
@@ -356,6 +359,20 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
             pf_b = rowptr[v0];
             pf_e = rowend[v0];
             pf_cols = (lane < min(64, pf_e - pf_b)) ? colidx[pf_b + lane] : 0;
+        }
+    }
+    // The mask round does little per tile besides its two matrix products: there the next tile's mu^{t-1}
+    // (4 KB, needed first thing) is fetched a tile ahead as well.
+    constexpr bool PFM = NODE && MASK;
+    float mpn[PFM ? CB : 1][4];
+    if (PFM) {
+        const int r0 = blockIdx.x * kWgRows + wave * kTileRows;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int ro = r0 + 4 * gl + k;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+                mpn[PFM ? cb : 0][k] = ((int)blockIdx.x < n_tiles && ro < n_vrows) ? mu_prev[(size_t)ro * P + 16 * cb + jl] : 0.f;
         }
     }
     // ---- workgroup reductions, fixed order over the four waves: the accumulators go into this workgroup's
@@ -471,8 +488,20 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_round(
         for (int k = 0; k < 4; ++k) {
             const int ro = r0 + 4 * gl + k;
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-                mp[cb][k] = ro < n_vrows ? mu_prev[(size_t)ro * P + 16 * cb + jl] : 0.f;
+            for (int cb = 0; cb < CB; ++cb) {
+                if (PFM) mp[cb][k] = mpn[PFM ? cb : 0][k];
+                else mp[cb][k] = ro < n_vrows ? mu_prev[(size_t)ro * P + 16 * cb + jl] : 0.f;
+            }
+        }
+        if (PFM) {
+            const int r0n = (t + (int)gridDim.x) * kWgRows + wave * kTileRows;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int ro = r0n + 4 * gl + k;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    mpn[PFM ? cb : 0][k] = (nx_ok && ro < n_vrows) ? mu_prev[(size_t)ro * P + 16 * cb + jl] : 0.f;
+            }
         }
 
         if (NODE) {

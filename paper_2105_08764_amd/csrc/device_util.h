@@ -645,7 +645,8 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_mu1(const NodeInfo &ni, 
 template <int P, bool W = false>
 __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeInfo &ni, int s0, const float *lc,
                                                        const int *__restrict__ colidx, int b, int e, int lane,
-                                                       float total, const float *__restrict__ wagg = nullptr) {
+                                                       float total, const float *__restrict__ wagg = nullptr,
+                                                       int cols_first = 0, bool have_first = false) {
     constexpr int STRIDE = Geo<P>::STRIDE;
     const int j = lane % P;
     const float t1 = lc[j], qp = lc[P + j];
@@ -655,7 +656,8 @@ __device__ __forceinline__ void gather_node_tile_flags(float *tile, const NodeIn
 #pragma unroll
     for (int s = 0; s < 16; ++s) acc[s] = 0.f;
     for (int base = b; base < e; base += 64) {
-        const int u = (base + lane < e) ? colidx[base + lane] : -1;
+        // (have_first: the caller fetched colidx[b + lane] for the lanes below the row's length ahead of time)
+        const int u = (base + lane < e) ? ((have_first && base == b) ? cols_first : colidx[base + lane]) : -1;
         const unsigned f = u >= 0 ? (unsigned)ni.flags16[(size_t)u * nb + blk] : 0u;
         if (__ballot(f != 0u) == 0ull) continue;                     // wave-uniform
         const float *r = ni.node(u >= 0 ? u : 0);

@@ -419,6 +419,20 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
     // N rows of p floats at a time (a working set S times smaller than the whole matrix).
     const int tps = (N + kWgRows - 1) / kWgRows;   // tiles per state when sliced
     const int n_tiles = SLICED ? tps * S : (n_vrows + kWgRows - 1) / kWgRows;
+    // Node mode of round 2: a tile is one node with a handful of neighbours, and row range -> column indices ->
+    // flag words -> records is a chain of four dependent trips to memory.  The row range and the first column
+    // indices of the wave's NEXT tile are fetched while the current one is worked on.
+    constexpr bool PF = NODE && MU1;
+    int pf_b = 0, pf_e = 0, pf_cols = 0;
+    if (PF) {
+        const int r0 = blockIdx.x * kWgRows + wave * kTileRows;
+        if ((int)blockIdx.x < n_tiles && r0 < n_vrows) {
+            const int v0 = r0 / S;
+            pf_b = rowptr[v0];
+            pf_e = rowend[v0];
+            pf_cols = (lane < min(64, pf_e - pf_b)) ? colidx[pf_b + lane] : 0;
+        }
+    }
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         int r0, r_step, n_here;
         if (SLICED) {
@@ -437,8 +451,20 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
         const bool valid = jl < n_here;
         const int v = valid ? r / S : 0;
         const int s = valid ? r - v * S : 0;
-        const int rb = valid ? rowptr[v] : 0;
-        const int re = valid ? rowend[v] : 0;
+        const int rb = PF ? pf_b : (valid ? rowptr[v] : 0);
+        const int re = PF ? pf_e : (valid ? rowend[v] : 0);
+        const int cols_first = pf_cols;
+        int nx_b = 0, nx_e = 0;
+        bool nx_ok = false;
+        if (PF) {
+            const int tn = t + gridDim.x, r0n = tn * kWgRows + wave * kTileRows;
+            nx_ok = tn < n_tiles && r0n < n_vrows;
+            if (nx_ok) {
+                const int vn = r0n / S;
+                nx_b = rowptr[vn];
+                nx_e = rowend[vn];
+            }
+        }
         const float3 mine = valid ? info.get(v, s) : make_float3(0.f, 0.f, 0.f);
         const float sp = mine.y, sn = mine.z;
         float xs = mine.x;
@@ -463,7 +489,8 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
             } else if (MU1 && info.flags16) {
                 // flag words and the row's total instead of the neighbours' records
                 gather_node_tile_flags<P, W>(tile, info, s0, lds_c, colidx, b, e, lane,
-                                             info.node(__builtin_amdgcn_readfirstlane(v))[info.sn_off + 1], wagg);
+                                             info.node(__builtin_amdgcn_readfirstlane(v))[info.sn_off + 1], wagg,
+                                             cols_first, PF);
             } else if (MU1) {
                 // the gather from the records works in the state-major lane layout
                 acc = gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane,
@@ -472,6 +499,12 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
             } else {
                 acc = gather_node_block<P, W>(mu_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
                 store_node_block<P>(tile, acc, lane);
+            }
+            if (PF) {
+                // the next tile's first column indices (its row range has arrived by now)
+                pf_cols = (nx_ok && lane < min(64, nx_e - nx_b)) ? colidx[nx_b + lane] : 0;
+                pf_b = nx_b;
+                pf_e = nx_e;
             }
         } else {
             // The long rows of the tile first: their sums are ready in hub_sum, and all lanes fetch
