@@ -358,7 +358,9 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 //   VAR = kRoundByState: row mode with the rows visited state by state (see the tile loop); a variant of
 //         its own so that it shows under its own name in profiles.
 // ------------------------------------------------------------------------------------------
-constexpr int kRoundPlain = 0, kRoundMaskOut = 1, kRoundByState = 2;
+//   VAR = kRoundFlags: node mode of round 2 when the flag words are there (info.flags16): the gather from the
+//         records and its staging area in LDS are left out, which lets a fourth workgroup onto a compute unit.
+constexpr int kRoundPlain = 0, kRoundMaskOut = 1, kRoundByState = 2, kRoundFlags = 3;
 template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN, int VAR = kRoundPlain>
 #ifndef S2V_ROUND_OCC
 #define S2V_ROUND_OCC 4
@@ -367,7 +369,7 @@ template <int P, bool NODE, bool MU1, bool GSUM, bool W, bool QN, int VAR = kRou
 #define S2V_ROUND2_OCC 4
 #endif
 // (node-mode round 2 also holds the record staging area in LDS: three workgroups per CU)
-__global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_ROUND_OCC) void k_round(int n_vrows, int S, const int32_t *__restrict__ rowptr,
+__global__ __launch_bounds__(kThreads, MU1 ? ((NODE && VAR != kRoundFlags) ? 3 : S2V_ROUND2_OCC) : S2V_ROUND_OCC) void k_round(int n_vrows, int S, const int32_t *__restrict__ rowptr,
                                                     const int32_t *__restrict__ rowend,
                                                     const int32_t *__restrict__ colidx,
                                                     const float *__restrict__ wagg,
@@ -380,7 +382,8 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
                                                     const float *__restrict__ x_res, int N, int last, QHead qh,
                                                     MaskOut mo) {
     using G = Geo<P>;
-    constexpr bool MO = VAR == kRoundMaskOut, SLICED = VAR == kRoundByState;
+    constexpr bool MO = VAR == kRoundMaskOut, SLICED = VAR == kRoundByState, FL = VAR == kRoundFlags;
+    static_assert(!FL || (NODE && MU1), "the flag-word variant is node mode of round 2");
     static_assert(!SLICED || (!NODE && !MU1 && !GSUM && !QN), "the state-by-state order is a plain row-mode variant");
     static_assert(!(QN && NODE), "the node term of Q is fused in row mode only");
     static_assert(!MO || (NODE && !MU1 && !QN), "mask output is a node-mode variant of the rounds that read rows");
@@ -394,7 +397,7 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
     // theta1, q+, q- of the epilogue live in LDS, not in registers, while a tile is gathered
     __shared__ float lds_c[3 * P];
     // staging area of the record gather (node mode of round 2 only)
-    __shared__ __attribute__((aligned(16))) float rec_stage[(NODE && MU1) ? kWaves * kRecStageFloats : 4];
+    __shared__ __attribute__((aligned(16))) float rec_stage[(NODE && MU1 && !FL) ? kWaves * kRecStageFloats : 4];
     stage_matrix_lds<P>(lds_b, theta2, false);
     for (int i = threadIdx.x; i < 3 * P; i += kThreads) lds_c[i] = i < P ? theta1[i] : qvec[i - P];
     __syncthreads();
@@ -486,17 +489,17 @@ __global__ __launch_bounds__(kThreads, MU1 ? (NODE ? 3 : S2V_ROUND2_OCC) : S2V_R
                 const int h = hub_index(ht, __builtin_amdgcn_readfirstlane(v));
                 acc = load_node_block<P>(hub_sum + ((size_t)h * S + s0) * P, lane);
                 store_node_block<P>(tile, acc, lane);
-            } else if (MU1 && info.flags16) {
+            } else if (MU1 && (FL || info.flags16)) {
                 // flag words and the row's total instead of the neighbours' records
                 gather_node_tile_flags<P, W>(tile, info, s0, lds_c, colidx, b, e, lane,
                                              info.node(__builtin_amdgcn_readfirstlane(v))[info.sn_off + 1], wagg,
                                              cols_first, PF);
-            } else if (MU1) {
+            } else if (MU1 && !FL) {
                 // the gather from the records works in the state-major lane layout
                 acc = gather_node_block_mu1<P, W>(info, s0, theta1, qvec, colidx, wagg, b, e, lane,
-                                                  rec_stage + ((NODE && MU1) ? wave * kRecStageFloats : 0));
+                                                  rec_stage + ((NODE && MU1 && !FL) ? wave * kRecStageFloats : 0));
                 store_node_block_sm<P>(tile, acc, lane);
-            } else {
+            } else if (!MU1) {
                 acc = gather_node_block<P, W>(mu_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
                 store_node_block<P>(tile, acc, lane);
             }
@@ -746,7 +749,15 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
                 hub_sum, x_res, N, last ? 1 : 0, qh, mo);
         return hipGetLastError();
     }
-    if (node && gpart) {
+    if (node && from_scalars && info.flags16 && !qh.q) {
+#define S2V_LAUNCH_ROUND_FL(GSUM, WW)                                                                                  \
+    k_round<P, true, true, GSUM, WW, false, kRoundFlags><<<grid, kThreads, 0, st>>>(                                   \
+        (int)n_vrows, S, rowptr, rowend, colidx, wagg, mu_in, mu_out, info, theta1, theta2, qvec, gpart, ht, hub_sum, \
+        x_res, N, last ? 1 : 0, qh, mo)
+        if (gpart) { if (wagg) S2V_LAUNCH_ROUND_FL(true, true); else S2V_LAUNCH_ROUND_FL(true, false); }
+        else { if (wagg) S2V_LAUNCH_ROUND_FL(false, true); else S2V_LAUNCH_ROUND_FL(false, false); }
+#undef S2V_LAUNCH_ROUND_FL
+    } else if (node && gpart) {
         if (from_scalars) S2V_LAUNCH_ROUND(true, true, true);
         else S2V_LAUNCH_ROUND(true, false, true);
     } else if (node) {
