@@ -219,8 +219,9 @@ def bench_inference(args, s2v, torch):
     return out, w
 
 
-def time_policy_steps(ctx, s2v, torch, graph, prm, x, N, p, T, k, G, steps, warmup):
-    """ms per inference step (policy evaluation + selection) and the profile of the timed steps."""
+def time_policy_steps(ctx, s2v, torch, graph, prm, x, N, p, T, k, G, steps, warmup, profile=True):
+    """ms per inference step (policy evaluation + selection) and the profile of the timed steps (profile=False:
+    no per-launch HIP events, whose recording costs a few microseconds each: for steps of tens of microseconds)."""
     ws = torch.empty(max(ctx.s2v_workspace_bytes(graph, p, T, 1, k), 256), dtype=torch.uint8, device="cuda")
     ctx.s2v_graph_prepare(graph, ws)
     mu = torch.empty((N, 1, p), device="cuda")
@@ -238,13 +239,14 @@ def time_policy_steps(ctx, s2v, torch, graph, prm, x, N, p, T, k, G, steps, warm
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    ctx.s2v_profile_begin(steps * (T + 1) + 4)
+    if profile:
+        ctx.s2v_profile_begin(steps * (T + 1) + 4)
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    return ms, ctx.s2v_profile_end()
+    return ms, (ctx.s2v_profile_end() if profile else None)
 
 
 def bench_footprint_sweep(args, s2v, torch, w4):
@@ -286,10 +288,12 @@ def bench_small_configs(args, s2v, torch):
         graph = upload(s2v, torch, g)
         prm = s2v.Params.from_numpy(w.theta)
         x = torch.from_numpy(w.x).cuda()
-        ms, prof = time_policy_steps(ctx, s2v, torch, graph, prm, x, g.n, w.p, w.T, w.k, g.n_graphs, steps, warm)
-        n_sel, ms_sel = prof["select"]
+        ms, prof = time_policy_steps(ctx, s2v, torch, graph, prm, x, g.n, w.p, w.T, w.k, g.n_graphs, steps, warm,
+                                     profile=(c == 3))
+        n_sel, ms_sel = prof["select"] if prof else (0, 0.0)
         out[f"cfg{c}"] = dict(workload=w.name, n=g.n, nnz=g.nnz, graphs=g.n_graphs, p=w.p, T=w.T, k=w.k,
-                              ms_per_step=round(ms, 5), steps=steps, select_ms=round(ms_sel / max(n_sel, 1), 5))
+                              ms_per_step=round(ms, 5), steps=steps,
+                              select_ms=round(ms_sel / n_sel, 5) if n_sel else None)
         log(f"[bench] config {c} ({w.name}): {ms * 1e3:.1f} us per inference step over {steps} steps")
         del graph, x
         torch.cuda.empty_cache()

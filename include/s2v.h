@@ -124,6 +124,20 @@ int32_t s2v_last_hip_error(const s2v_ctx *ctx);
 int32_t s2v_set_sliced_min_bytes(s2v_ctx *ctx, size_t bytes);
 
 /*
+ * Second tuning knob of a context (again a property of this GPU, not of the paper): when s2v_policy_select
+ * runs the whole step as ONE kernel launch with one workgroup per graph.  That form needs every graph's
+ * embedding to fit a compute unit's LDS and uses one compute unit per graph, so by default
+ * (S2V_SINGLE_LAUNCH_AUTO) it is taken where it measured faster than the chain of launches: batches of at
+ * least 64 graphs, graphs of at most half the LDS capacity, or p <= 32 with at least 4 graphs.
+ * S2V_SINGLE_LAUNCH_ALWAYS takes it whenever the graphs fit, S2V_SINGLE_LAUNCH_NEVER never.
+ * Errors: INVALID_ARG (NULL context, unknown mode).
+ */
+#define S2V_SINGLE_LAUNCH_AUTO 0
+#define S2V_SINGLE_LAUNCH_ALWAYS 1
+#define S2V_SINGLE_LAUNCH_NEVER 2
+int32_t s2v_set_single_launch(s2v_ctx *ctx, int32_t mode);
+
+/*
  * Bytes of workspace that every call below needs for this graph with embedding size p, T
  * rounds, S states and at most k_max selected nodes per call.  `training` non-zero includes
  * the scratch of s2v_embed_bwd and s2v_loss_grad (up to two [N][S][p] buffers, the relu-mask words and the

@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libs2v.so")
 
 S2V_OK = 0
+SINGLE_LAUNCH_AUTO, SINGLE_LAUNCH_ALWAYS, SINGLE_LAUNCH_NEVER = 0, 1, 2   # modes of s2v_set_single_launch
 S2V_ERR_INVALID_ARG = -1
 S2V_ERR_UNSUPPORTED = -2
 S2V_ERR_WORKSPACE_TOO_SMALL = -3
@@ -34,7 +35,7 @@ EXPORTS = (
     "s2v_graph_prepare", "s2v_embed_fwd", "s2v_q_score", "s2v_select_topk", "s2v_embed_bwd",
     "s2v_sgd_step", "s2v_adaptive_d", "s2v_profile_begin", "s2v_profile_end", "s2v_residual_update",
     "s2v_mvc_inference", "s2v_adam_step", "s2v_q_target", "s2v_policy_eval", "s2v_loss_grad",
-    "s2v_select_topk_noalloc", "s2v_set_sliced_min_bytes", "s2v_stream_read",
+    "s2v_select_topk_noalloc", "s2v_set_sliced_min_bytes", "s2v_set_single_launch", "s2v_stream_read",
     "s2v_policy_select",
 )
 
@@ -331,6 +332,9 @@ class Context:
 
     def s2v_set_sliced_min_bytes(self, nbytes: int) -> None:
         _check(self.lib.s2v_set_sliced_min_bytes(self.handle, ctypes.c_size_t(nbytes)), "s2v_set_sliced_min_bytes")
+
+    def s2v_set_single_launch(self, mode: int) -> None:
+        _check(self.lib.s2v_set_single_launch(self.handle, ctypes.c_int32(mode)), "s2v_set_single_launch")
 
     def s2v_stream_read(self, src, out) -> None:
         _check(self.lib.s2v_stream_read(self.handle, ctypes.c_void_p(_dp(src)),

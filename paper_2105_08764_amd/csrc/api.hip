@@ -255,6 +255,7 @@ struct s2v_ctx {
     // different sequence, so their results differ in the last float32 bits.
     // s2v_set_sliced_min_bytes overrides the default.
     size_t sliced_min_bytes = (size_t)3 << 29;
+    int32_t single_launch = S2V_SINGLE_LAUNCH_AUTO;   // s2v_set_single_launch
     // optional timing of the two gather kernels (s2v_profile_begin / s2v_profile_end)
     bool profiling = false;
     std::vector<ProfSpan> spans;   // pre-created event pairs
@@ -461,6 +462,12 @@ int32_t s2v_last_hip_error(const s2v_ctx *ctx) { return ctx ? ctx->last_hip : 0;
 int32_t s2v_set_sliced_min_bytes(s2v_ctx *ctx, size_t bytes) {
     if (!ctx) return S2V_ERR_INVALID_ARG;
     ctx->sliced_min_bytes = bytes;
+    return S2V_OK;
+}
+
+int32_t s2v_set_single_launch(s2v_ctx *ctx, int32_t mode) {
+    if (!ctx || mode < S2V_SINGLE_LAUNCH_AUTO || mode > S2V_SINGLE_LAUNCH_NEVER) return S2V_ERR_INVALID_ARG;
+    ctx->single_launch = mode;
     return S2V_OK;
 }
 
@@ -759,7 +766,16 @@ static int32_t policy_select_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_pa
     const Prepared *pr = check_ws(ws) == S2V_OK ? find_prepared(ctx, g, ws) : nullptr;
     // One launch for the whole step when every graph's embedding fits the LDS of a compute unit
     // (see small_kernels.hip); plain neighbour sum on the stored graph only.
-    const bool small = pr && p_supported(params->p) && check_params(params) == S2V_OK && T >= 1 && g->n_nodes > 0 &&
+    // One workgroup per graph uses one compute unit per graph, so it pays for batches, or for graphs small enough
+    // that the launches of the general path cost more than the work (measured on scale-free graphs of 250-1000
+    // nodes, 1 to 512 per batch: at 64 graphs and more it wins or ties at every size that fits; one graph of
+    // 1000 nodes at p = 32 takes 78 us this way and 61 us as a chain of launches, one of 250 nodes at p = 64
+    // 66 against 81 us).
+    const bool small_pays = pr && ctx->single_launch != S2V_SINGLE_LAUNCH_NEVER &&
+                            (ctx->single_launch == S2V_SINGLE_LAUNCH_ALWAYS || g->n_graphs >= 64 ||
+                             (int64_t)pr->max_graph_nodes * params->p <= kSmallLdsFloats / 2 ||
+                             (params->p <= 32 && g->n_graphs >= 4));
+    const bool small = pr && small_pays && p_supported(params->p) && check_params(params) == S2V_OK && T >= 1 && g->n_nodes > 0 &&
                        (int64_t)pr->max_graph_nodes * params->p <= kSmallLdsFloats && k <= kSmallK &&
                        !g->weighted_sum && !g->state_residual && ctx->max_lds_per_block >= kSmallLdsBytes && x && mu_out &&
                        q;

@@ -70,6 +70,7 @@ def test_single_launch_step_matches_oracle(oracle_mod, kind, p, T):
     x = si.node_flags(g.n, 0.2, 6)
     ks = (1,) if g.n_graphs > 1 else (1, 3, 8)
     dev = gu.Device(g, p, T, k_max=8)
+    dev.ctx.s2v_set_single_launch(1)          # always: one graph of this size would take the chain of launches
     mu_o, gsum_o, q_o = gu.oracle_forward(oracle_mod, g, theta, x[0], T)
     rng = np.random.default_rng(3)
     for k in ks:
@@ -97,6 +98,7 @@ def test_single_launch_on_a_shrinking_graph(oracle_mod):
     p, T = 32, 3
     theta = si.thetas(p, 8, 0.05)
     dev = gu.Device(g, p, T, k_max=8)
+    dev.ctx.s2v_set_single_launch(1)
     mut = dev.graph.mutable_copy()
     dev.ctx.s2v_graph_prepare(mut, dev.ws)
     x = si.node_flags(g.n, 0.15, 4)[0]
@@ -140,3 +142,24 @@ def test_larger_graphs_take_the_general_path_bit_for_bit(n, deg, p, T):
             out = _run(dev, theta, x, cand, k, T)
             for a, b in zip(out["small"], out["general"]):
                 assert np.array_equal(a, b, equal_nan=True)
+
+
+def test_single_launch_is_chosen_where_it_pays():
+    # automatic choice: a batch of 64 graphs takes the single launch, one graph of 1000 nodes the chain of
+    # launches; "never" and "always" override.  The two forms differ in the last bits of mu, which tells them apart.
+    import torch
+
+    parts = [si.erdos_renyi_gnp(300, 0.03, 40 + i) for i in range(64)]
+    theta = si.thetas(32, 9)
+    for g, expect_single in ((si.block_diagonal(parts), True), (si.erdos_renyi_gnp(1000, 0.01, 3), False)):
+        x = si.node_flags(g.n, 0.2, 6)
+        dev = gu.Device(g, 32, 3, k_max=8)
+        got = {}
+        for mode in (2, 1, 0):                                           # never, always, automatic
+            dev.ctx.s2v_set_single_launch(mode)
+            got[mode] = _run(dev, theta, x, None, 1, 3)["small"]
+        same_as_single = all(np.array_equal(a, b) for a, b in zip(got[0], got[1]))
+        same_as_chain = all(np.array_equal(a, b) for a, b in zip(got[0], got[2]))
+        assert not np.array_equal(got[1][0], got[2][0])                  # the two forms round differently
+        assert same_as_single == expect_single and same_as_chain == (not expect_single)
+        assert np.array_equal(got[1][3], got[2][3])                      # and select the same nodes here
