@@ -320,3 +320,39 @@ def test_star_with_100000_leaves(oracle_mod, batched):
     for k in si.THETA_NAMES:
         assert np.array_equal(grads1[k], grads[k]), k
         assert errs[k] <= 1e-4, k
+
+
+@pytest.mark.parametrize("weighted", [False, True])
+def test_single_state_round2_over_solution_densities_and_without_symmetry(oracle_mod, weighted):
+    # One state, T >= 3, static graph without long rows or negative weights: round 2 works from flag bits and the
+    # rows' totals.  With a sparse, a dense and an empty partial solution, and on a pattern that is NOT symmetric
+    # (a promise of the interface that the forward pass does not need).
+    n, p, T = 5000, 64, 4
+    g = si.erdos_renyi_gnp(n, 30.0 / n, 17)
+    if weighted:
+        g.w = si.symmetric_edge_weights(g, 5, 0.5, 1.5)
+    theta = si.thetas(p, 31)
+    for frac in (0.05, 0.6, 0.0):
+        x = si.node_flags(n, frac, 8)
+        dev = gu.Device(g, p, T, weighted_sum=weighted)
+        out = dev.forward(theta, x)
+        mu = oracle_mod.embed(g.rowptr, g.colidx, g.w, theta, x[0], T, weighted=weighted)
+        gsum, q = oracle_mod.q_scores(g.graph_off, theta, mu)
+        errs = (gu.rel_err(out["mu"][:, 0, :], mu), gu.rel_err(out["q"][0], q))
+        print(f"  round 2 from flag bits, weighted={weighted}, x density {frac}: {errs}", flush=True)
+        assert max(errs) <= 1e-4, errs
+    if weighted:
+        return
+    # not symmetric: drop the entries (v, u) with v > u of every third row
+    keep = np.ones(g.nnz, dtype=bool)
+    rows = np.repeat(np.arange(n), np.diff(g.rowptr))
+    keep[(rows % 3 == 0) & (rows > g.colidx)] = False
+    rp = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum(np.bincount(rows[keep], minlength=n), out=rp[1:])
+    ga = si.Graph(n=n, rowptr=rp, colidx=g.colidx[keep].copy())
+    x = si.node_flags(n, 0.05, 8)
+    out = gu.Device(ga, p, T).forward(theta, x)
+    mu, gsum, q = gu.oracle_forward(oracle_mod, ga, theta, x[0], T)
+    errs = (gu.rel_err(out["mu"][:, 0, :], mu), gu.rel_err(out["q"][0], q))
+    print(f"  pattern without symmetry: {errs}", flush=True)
+    assert max(errs) <= 1e-4, errs
