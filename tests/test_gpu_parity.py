@@ -322,6 +322,29 @@ def _run_config(oracle_mod, c, scale):
     idx, val, cnt = dev.select(out["q"][0], w.x[0], None, w.k)
     oi, ov, oc = oracle_mod.select(g.graph_off, out["q"][0], w.x[0], None, w.k)
     assert np.array_equal(idx, oi) and np.array_equal(cnt, oc)
+    # the one-call step that bench.py times (embed, score, select): the same bits where it runs the general
+    # kernels; where it runs as one launch (a batch of small graphs) its own parity with the oracle
+    k = w.k
+    mu2 = torch.full((g.n, 1, w.p), float("nan"), device="cuda")
+    gs2 = torch.full((1, g.n_graphs, w.p), float("nan"), device="cuda")
+    q2 = torch.full((1, g.n), float("nan"), device="cuda")
+    idx2 = torch.full((g.n_graphs, k), -7, dtype=torch.int32, device="cuda")
+    val2 = torch.full((g.n_graphs, k), float("nan"), device="cuda")
+    cnt2 = torch.full((g.n_graphs,), -7, dtype=torch.int32, device="cuda")
+    dev.ctx.s2v_policy_select(dev.graph, dev.last["prm"], dev.last["x"][0], None, w.T, k, mu2, gs2, q2, idx2, val2, cnt2,
+                              dev.ws)
+    torch.cuda.synchronize()
+    mu2, gs2, q2, idx2, cnt2 = (t_.cpu().numpy() for t_ in (mu2, gs2, q2, idx2, cnt2))
+    if np.array_equal(mu2, out["mu"]):
+        assert np.array_equal(q2, out["q"]) and np.array_equal(gs2, out["gsum"])
+        assert np.array_equal(idx2, idx) and np.array_equal(cnt2, cnt)
+        print("one-call step: the bits of the separate calls", flush=True)
+    else:
+        errs2 = (gu.rel_err(mu2[:, 0, :], mu), gu.rel_err(gs2[0], gsum), gu.rel_err(q2[0], q))
+        print("one-call step (single launch) rel errors mu/gsum/q:", errs2, flush=True)
+        assert max(errs2) <= TOL
+        oi2, ov2, oc2 = oracle_mod.select(g.graph_off, q2[0], w.x[0], None, k)
+        assert np.array_equal(idx2, oi2) and np.array_equal(cnt2, oc2)
     # and end to end against the oracle's float64 scores, outside the 1e-4 band
     offs = g.offsets()
     exact = 0
