@@ -960,6 +960,51 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long
     return acc;
 }
 
+// A segment of a long row for ONE state, round 2 (neighbour rows recomputed from the records): one LANE per
+// neighbour, and the loads of the whole segment (at most 512 entries: eight per lane) issued together -- the column
+// indices, then the records -- so the segment costs two trips to memory instead of two per 64 entries.  Neighbours
+// with x = 0 and s- = 0 are summed as scalars (their row is s+ relu(q+)); the others are visited one at a time with
+// lane j forming column j.  Returns column lane % P of the segment's sum.
+template <int P, bool W>
+__device__ __forceinline__ float gather_segment_mu1_lanes(const float *__restrict__ rec, float t1j, float qpj, float qnj,
+                                                          const int *__restrict__ colidx, const float *__restrict__ wagg,
+                                                          int b, int e, int lane) {
+    constexpr int U = 8;
+    const float rpj = fmaxf(qpj, 0.f);
+    float ssum = 0.f, acc = 0.f;
+    for (int base = b; base < e; base += 64 * U) {
+        int c[U];
+        float wv[W ? U : 1];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = base + 64 * u + lane;
+            c[u] = i < e ? colidx[i] : -1;
+            if (W) wv[W ? u : 0] = i < e ? wagg[i] : 0.f;
+        }
+        float4 r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = c[u] >= 0 ? ld4(rec + (size_t)c[u] * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool cheap = r[u].x == 0.f && r[u].z == 0.f;   // (a missing neighbour: all zeros, adds nothing)
+            const float wl = W ? wv[W ? u : 0] : 1.f;
+            ssum += cheap ? wl * r[u].y : 0.f;
+            unsigned long long todo = __ballot(!cheap);
+            while (todo != 0ull) {
+                const int l = __ffsll((long long)todo) - 1;
+                todo &= todo - 1ull;
+                const float xl = readlane_f(r[u].x, l), pl = readlane_f(r[u].y, l), nl = readlane_f(r[u].z, l);
+                const float m1 = fmaxf(mu1_z(xl, pl, nl, t1j, qpj, qnj), 0.f);
+                if (W) acc = fmaf(readlane_f(wl, l), m1, acc);
+                else acc += m1;
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) ssum += __shfl_xor(ssum, m);
+    return fmaf(ssum, rpj, acc);
+}
+
 // Index of node v among the long rows (v is known to be one): one load from the per-node table.
 __device__ __forceinline__ int hub_index(const HubTable &ht, int v) { return ht.hub_of[v]; }
 

@@ -838,6 +838,14 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial(int S, HubTable ht,
             }
         } else {
             const int s = blk;
+            if (SRC == 1 && S == 1) {
+                // single state: one lane per neighbour, the whole segment's loads in flight at once
+                const int j = lane % P;
+                const float v1 = gather_segment_mu1_lanes<P, W>(info.base, theta1[j], qvec[j], qvec[P + j], colidx, wagg, b,
+                                                                e, lane);
+                if (lane < P) partial[(size_t)seg * P + lane] = v1;
+                continue;
+            }
             const int cols = (lane < min(64, e - b)) ? colidx[b + lane] : 0;
             float4 a;
             if (SRC == 1) {

@@ -16,30 +16,44 @@ __global__ void k_zero_stats(int n, int32_t *__restrict__ stats) {
 // Squeeze the entries of row v whose neighbour is in the solution out of the row (one wave; the
 // order of the survivors is kept), refresh s+ / s- over the survivors, and return the new length.
 // A row of a solution node becomes empty.  Every lane returns the same value.
+// The row is taken in batches of four 64-entry chunks whose loads (entries, then the neighbours' x) are issued
+// together: two trips to memory per 256 entries.  Survivors are written at or below the place they were read
+// from, and a batch is read completely before any of its survivors is written, so the squeeze works in place.
 __device__ __forceinline__ int filter_row(int v, int lane, const int32_t *__restrict__ rowptr,
                                           int32_t *__restrict__ rowend, int32_t *__restrict__ colidx,
                                           float *__restrict__ w, const float *__restrict__ x,
                                           float *__restrict__ s_pos, float *__restrict__ s_neg) {
+    constexpr int B = 4;
     const unsigned long long lt = (1ull << lane) - 1ull;
     const int b = rowptr[v], e = rowend[v];
     int out = 0;
     double sp = 0.0, sn = 0.0;
     if (x[v] == 0.f) {
-        for (int base = b; base < e; base += 64) {
-            const int i = base + lane;
-            const bool have = i < e;
-            const int c = have ? colidx[i] : 0;
-            const float ww = have ? (w ? w[i] : 1.f) : 0.f;
-            const bool keep = have && x[c] == 0.f;
-            const unsigned long long m = __ballot(keep);
-            if (keep) {
-                const int pos = b + out + __popcll(m & lt);   // never beyond the entry just read
-                colidx[pos] = c;
-                if (w) w[pos] = ww;
-                sp += (double)fmaxf(ww, 0.f);
-                sn += (double)fmaxf(-ww, 0.f);
+        for (int base = b; base < e; base += 64 * B) {
+            int c[B];
+            float ww[B], xc[B];
+#pragma unroll
+            for (int k = 0; k < B; ++k) {
+                const int i = base + 64 * k + lane;
+                const bool have = i < e;
+                c[k] = have ? colidx[i] : -1;
+                ww[k] = have ? (w ? w[i] : 1.f) : 0.f;
             }
-            out += __popcll(m);
+#pragma unroll
+            for (int k = 0; k < B; ++k) xc[k] = c[k] >= 0 ? x[c[k]] : 1.f;
+#pragma unroll
+            for (int k = 0; k < B; ++k) {
+                const bool keep = c[k] >= 0 && xc[k] == 0.f;
+                const unsigned long long m = __ballot(keep);
+                if (keep) {
+                    const int pos = b + out + __popcll(m & lt);   // never beyond the entry just read
+                    colidx[pos] = c[k];
+                    if (w) w[pos] = ww[k];
+                    sp += (double)fmaxf(ww[k], 0.f);
+                    sn += (double)fmaxf(-ww[k], 0.f);
+                }
+                out += __popcll(m);
+            }
         }
 #pragma unroll
         for (int mm = 1; mm < 64; mm <<= 1) {
