@@ -27,6 +27,10 @@ struct Prepared {
     int32_t n_segs;
     bool has_neg;   // some stored weight is negative
     int32_t max_graph_nodes;   // nodes of the largest graph of the batch
+    // s2v_mvc_inference keeps the single-state node records (and q+-) in the head of the workspace over its
+    // steps: the state update refreshes the records of the rows it changes, so they are not rebuilt per evaluation
+    mutable bool rec_keep = false;      // the loop is running on this workspace
+    mutable bool rec_current = false;   // ... and the records in the head match x, s+ and s-
 };
 
 // Carves consecutive 256-byte aligned pieces out of a byte range.
@@ -42,7 +46,7 @@ struct Carver {
 
 struct HeadLayout {
     size_t s_pos, s_neg, nbr_sp, nbr_spw, chunk_begin, chunk_end, graph_chunk_off;
-    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, hub_of, epoch, loop_ctr, end;
+    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, hub_of, epoch, loop_ctr, rec, qkeep, end;
     int max_chunks, max_hubs, max_segs;
 };
 
@@ -91,6 +95,8 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     h.hub_of = c.take(sizeof(int32_t) * (hubs > 0 ? N : 0));   // per node: its index among the long rows
     h.epoch = c.take(sizeof(int32_t) * 2);          // number of incremental updates so far; a flag of the preparation
     h.loop_ctr = c.take(sizeof(unsigned long long) * 2);   // counters of s2v_mvc_inference
+    h.rec = c.take(sizeof(float) * 5 * N);          // its node records {x, s+, s-, 0} and the 4-byte table behind them
+    h.qkeep = c.take(sizeof(float) * 2 * 128);      // its q+-
     h.end = c.off;
     return h;
 }
@@ -656,7 +662,9 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
 
     hipStream_t st = ctx->stream;
     const float *s_pos = at<float>(ws, h.s_pos), *s_neg = at<float>(ws, h.s_neg);
-    float *qvec = at<float>(ws, f.qvec);
+    // (inside s2v_mvc_inference: records and q+- live in the head and are kept current by the state update)
+    const bool keep = pr->rec_keep && S == 1 && !g->state_residual && !fused;
+    float *qvec = keep ? at<float>(ws, h.qkeep) : at<float>(ws, f.qvec);
     float *tmp = at<float>(ws, f.tmp);
     const size_t nsp = (size_t)N * S * p;
     // destination of round t (1-based): the saved slot, or ping-pong so that round T lands in mu_out
@@ -667,7 +675,7 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     // Round 1 has no neighbour term (mu^0 = 0).  Its result is written out only when somebody reads
     // it from memory: the caller (mu_saved) or, when T == 1, the output itself.  Round 2 recomputes
     // the neighbours' round-1 rows from the per-node scalars instead of gathering them.
-    float *info = at<float>(ws, f.info);
+    float *info = keep ? at<float>(ws, h.rec) : at<float>(ws, f.info);
     float *gpart = at<float>(ws, f.gpart);
     const HubTable ht = hub_table(ws, h, *pr);
     // per-(node, state) scalar records; with per-state residual graphs they hold each state's own edge sums
@@ -684,8 +692,9 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     if (x_res) {
         S2V_TRY(launch_qvec(st, p, params->theta3, params->theta4, qvec));
         S2V_TRY(launch_stateinfo_residual(st, N, S, ht, g->rowptr, row_end_of(g), g->colidx, g->w, x, info, compact));
-    } else {
+    } else if (!(keep && pr->rec_current)) {
         // (q+- = theta3 relu(+-theta4) comes out of the same launch as the records)
+        if (keep) pr->rec_current = true;
         S2V_TRY(launch_nodeinfo(st, N, S, x, s_pos, s_neg, info, compact,
                                 by_bits ? at<float>(ws, wagg ? h.nbr_spw : h.nbr_sp) : nullptr, xbits, p, params->theta3,
                                 params->theta4, qvec));
@@ -1121,8 +1130,8 @@ int32_t s2v_loss_grad(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *params
                           true);
 }
 
-static UpdateState update_state(const s2v_graph *g, const HeadLayout &h, void *ws, float *x, int32_t k, uint8_t *cand,
-                                int32_t *stats) {
+static UpdateState update_state(const s2v_graph *g, const Prepared &pr, const HeadLayout &h, void *ws, float *x, int32_t k,
+                                uint8_t *cand, int32_t *stats) {
     UpdateState u{};
     u.G = g->n_graphs;
     u.k = k;
@@ -1137,6 +1146,8 @@ static UpdateState update_state(const s2v_graph *g, const HeadLayout &h, void *w
     u.stats = stats;
     u.touched = at<int32_t>(ws, h.touched);
     u.epoch = at<int32_t>(ws, h.epoch);   // (the number of incremental updates since s2v_graph_prepare)
+    u.rec = pr.rec_keep ? at<float>(ws, h.rec) : nullptr;
+    u.compact = (pr.rec_keep && !pr.has_neg) ? at<float>(ws, h.rec) + (size_t)g->n_nodes * 4 : nullptr;
     return u;
 }
 
@@ -1157,7 +1168,8 @@ static int32_t residual_update_impl(s2v_ctx *ctx, const s2v_graph *g, float *x, 
     if (!pr) return S2V_ERR_NOT_PREPARED;
     const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
     if (ws_bytes < h.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
-    const UpdateState u = update_state(g, h, ws, x, sel_idx ? k : 0, cand, stats);
+    if (!sel_idx) pr->rec_current = false;   // a full rebuild does not touch the records
+    const UpdateState u = update_state(g, *pr, h, ws, x, sel_idx ? k : 0, cand, stats);
     S2V_TRY(launch_residual_update(ctx->stream, N, u, const_cast<int32_t *>(g->colidx), const_cast<float *>(g->w), sel_idx,
                                    sel_count, begun));
     return S2V_OK;
@@ -1208,7 +1220,13 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     const bool use_rule = adaptive && G == 1;
     const int32_t k_sel = use_rule ? kSmallK : 1;   // the largest d of the rule; the device cuts the count to d
     if (!g->row_end) return S2V_ERR_INVALID_ARG;
-    const UpdateState upd = update_state(g, h, ws, x, k_sel, cand, stats);
+    // from here to the return the node records stay in the head of the workspace (see Prepared::rec_keep)
+    struct KeepRecords {
+        const Prepared *pr;
+        explicit KeepRecords(const Prepared *p_) : pr(p_) { pr->rec_keep = true; pr->rec_current = false; }
+        ~KeepRecords() { pr->rec_keep = false; pr->rec_current = false; }
+    } keep_records(pr);
+    const UpdateState upd = update_state(g, *pr, h, ws, x, k_sel, cand, stats);
     const StepEnd end{N, use_rule, ctr, &upd};
     int32_t launched = 0, block = 1;
     while (n_live > 0 && launched < max_steps) {

@@ -27,7 +27,19 @@ struct UpdateState {
     int32_t *stats;                      // [G][2]: candidates, live stored entries
     int32_t *touched;                    // [N]: > 0 the update that last filtered the row; < 0 see begin_update
     int32_t *epoch;                      // [1]: number of updates so far
+    // optional (inside the inference loop): the single-state node records {x, s+, s-, 0} [N][4] and the table
+    // compact[v] = s+ of a node with x = 0 and s- = 0, NaN for any other, kept current for the rows that change
+    float *rec, *compact;
 };
+
+// The record of node v after its x, s+ or s- changed.
+__device__ __forceinline__ void refresh_record(float *rec, float *compact, int v, float xv, float sp, float sn) {
+    if (!rec) return;
+    rec[(size_t)v * 4 + 0] = xv;
+    rec[(size_t)v * 4 + 1] = sp;
+    rec[(size_t)v * 4 + 2] = sn;
+    if (compact) compact[v] = (xv == 0.f && sn == 0.f) ? sp : __int_as_float(0x7fc00000);
+}
 
 // First half of the incremental state update, by the threads [tid, tid + stride, ...) of one or more workgroups:
 // every selected node joins the solution (x = 1) and its row becomes empty.  The row's stored entries stay where
@@ -41,6 +53,7 @@ __device__ __forceinline__ void begin_update(const UpdateState &u, const int32_t
         const int v = sel_idx[i];
         if (v < 0) continue;
         u.x[v] = 1.f;
+        refresh_record(u.rec, u.compact, v, 1.f, 0.f, 0.f);   // (a solution node has no live entry: both sums are zero)
         const int b = u.rowptr[v];
         const int len = atomicExch(&u.rowend[v], b) - b;
         if (len <= 0) continue;

@@ -22,7 +22,8 @@ __global__ void k_zero_stats(int n, int32_t *__restrict__ stats) {
 __device__ __forceinline__ int filter_row(int v, int lane, const int32_t *__restrict__ rowptr,
                                           int32_t *__restrict__ rowend, int32_t *__restrict__ colidx,
                                           float *__restrict__ w, const float *__restrict__ x,
-                                          float *__restrict__ s_pos, float *__restrict__ s_neg) {
+                                          float *__restrict__ s_pos, float *__restrict__ s_neg,
+                                          float *rec = nullptr, float *compact = nullptr) {
     constexpr int B = 4;
     const unsigned long long lt = (1ull << lane) - 1ull;
     const int b = rowptr[v], e = rowend[v];
@@ -65,6 +66,7 @@ __device__ __forceinline__ int filter_row(int v, int lane, const int32_t *__rest
         rowend[v] = b + out;
         s_pos[v] = (float)sp;
         s_neg[v] = (float)sn;
+        refresh_record(rec, compact, v, x[v], (float)sp, (float)sn);
     }
     return out;
 }
@@ -122,7 +124,8 @@ __global__ __launch_bounds__(256) void k_refilter_neighbours(int total, int k, c
                                                              uint8_t *__restrict__ cand, int G,
                                                              const int32_t *__restrict__ graph_off,
                                                              int32_t *__restrict__ stats, int32_t *__restrict__ touched,
-                                                             const int32_t *__restrict__ epoch) {
+                                                             const int32_t *__restrict__ epoch, float *rec,
+                                                             float *compact) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ep = epoch[0];
     for (int i = blockIdx.y; i < total; i += gridDim.y) {
@@ -141,7 +144,7 @@ __global__ __launch_bounds__(256) void k_refilter_neighbours(int total, int k, c
             if (!__shfl(first, 0)) continue;
             const int old_len = rowend[u] - rowptr[u];
             const int old_cand = cand[u];
-            const int out = filter_row(u, lane, rowptr, rowend, colidx, w, x, s_pos, s_neg);
+            const int out = filter_row(u, lane, rowptr, rowend, colidx, w, x, s_pos, s_neg, rec, compact);
             if (lane == 0) {
                 const int new_cand = out > 0 ? 1 : 0;
                 cand[u] = (uint8_t)new_cand;
@@ -192,7 +195,7 @@ hipError_t launch_residual_update(hipStream_t st, int N, const UpdateState &u, i
         const int gx = max(1, min(1024 / gy, (N + 3) / 4));
         k_refilter_neighbours<<<dim3(gx, gy), 256, 0, st>>>(u.total, u.k, sel_idx, sel_count, u.rowptr, u.rowend, colidx, w,
                                                            u.x, u.s_pos, u.s_neg, u.cand, u.G, u.graph_off, u.stats,
-                                                           u.touched, u.epoch);
+                                                           u.touched, u.epoch, u.rec, u.compact);
         return hipGetLastError();
     }
     k_zero_stats<<<1, 256, 0, st>>>(2 * u.G, u.stats);
