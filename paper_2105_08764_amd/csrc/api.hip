@@ -27,6 +27,7 @@ struct Prepared {
     int32_t n_segs;
     bool has_neg;   // some stored weight is negative
     int32_t max_graph_nodes;   // nodes of the largest graph of the batch
+    int32_t max_hub_segs;      // segments of the longest row
     // s2v_mvc_inference keeps the single-state node records (and q+-) in the head of the workspace over its
     // steps: the state update refreshes the records of the rows it changes, so they are not rebuilt per evaluation
     mutable bool rec_keep = false;      // the loop is running on this workspace
@@ -337,6 +338,7 @@ HubTable hub_table(void *ws, const HeadLayout &h, const Prepared &pr) {
     ht.n_segs = pr.n_segs;
     ht.hub_rows = at<int32_t>(ws, h.hub_rows);
     ht.hub_of = at<int32_t>(ws, h.hub_of);
+    ht.fold = 0;
     ht.hub_seg_off = at<int32_t>(ws, h.hub_seg_off);
     ht.seg_row = at<int32_t>(ws, h.seg_row);
     ht.seg_begin = at<int32_t>(ws, h.seg_begin);
@@ -582,6 +584,9 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
         }
     }
     hub_seg_off.push_back((int32_t)seg_begin.size());
+    int32_t max_hub_segs = 0;
+    for (size_t i = 0; i + 1 < hub_seg_off.size(); ++i)
+        if (hub_seg_off[i + 1] - hub_seg_off[i] > max_hub_segs) max_hub_segs = hub_seg_off[i + 1] - hub_seg_off[i];
     if ((int)hub_rows.size() != n_hubs || (int)seg_begin.size() != n_segs) return S2V_ERR_INVALID_ARG;
     if (n_hubs > 0) {
         S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.hub_rows), hub_rows.data(), sizeof(int32_t) * n_hubs, hipMemcpyHostToDevice, ctx->stream));
@@ -612,7 +617,7 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     int32_t max_graph_nodes = 0;
     for (int b = 0; b < G; ++b)
         if (off[b + 1] - off[b] > max_graph_nodes) max_graph_nodes = off[b + 1] - off[b];
-    Prepared pr{ws, g->rowptr, g->colidx, g->w, N, g->nnz, G, n_chunks, n_hubs, n_segs, has_neg != 0, max_graph_nodes};
+    Prepared pr{ws, g->rowptr, g->colidx, g->w, N, g->nnz, G, n_chunks, n_hubs, n_segs, has_neg != 0, max_graph_nodes, max_hub_segs};
     for (Prepared &old : ctx->prepared)
         if (old.ws == ws) { old = pr; return S2V_OK; }
     ctx->prepared.push_back(pr);
@@ -709,15 +714,18 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     const bool fuse_q = q_node && T >= 2 && N > 0 && round_fuses_qnode(S);
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     const bool by_state = S % 16 == 0 && nsp * sizeof(float) >= ctx->sliced_min_bytes;
+    // one state and at most four segments per long row: no combine pass, the round kernel adds the segments
+    HubTable htf = ht;
+    htf.fold = (S == 1 && pr->n_segs != pr->n_hubs && pr->max_hub_segs <= 4) ? 1 : 0;
     for (int t = 2; t <= T; ++t) {
         QHead qh{params->theta5, params->theta7, (fuse_q && t == T) ? q_node : nullptr};
         const float *src = t == 2 ? nullptr : dest(t - 1);
-        S2V_TRY(launch_hub_sums(st, p, S, ht, row_end_of(g), g->colidx, wagg, src, ninfo, params->theta1, qvec, nullptr, hub_part, hub_sum));
+        S2V_TRY(launch_hub_sums(st, p, S, htf, row_end_of(g), g->colidx, wagg, src, ninfo, params->theta1, qvec, nullptr, hub_part, hub_sum));
         SpanGuard span(ctx, (qh.q || (fused && t == T)) ? S2V_PROFILE_FWD_ROUND_Q
                                                             : (t == 2 ? S2V_PROFILE_FWD_ROUND2 : S2V_PROFILE_FWD_ROUND));
         S2V_TRY(launch_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, src, dest(t), ninfo, params->theta1,
-                             params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, ht, hub_sum, x_res,
-                             t == T, qh,
+                             params->theta2, qvec, t == 2, (fuse_gsum && t == T) ? gpart : nullptr, htf,
+                             htf.fold ? hub_part : hub_sum, x_res, t == T, qh,
                              (fused && t == T) ? MaskOut{fused->mask_words, fused->action} : MaskOut{nullptr, nullptr},
                              by_state));
     }

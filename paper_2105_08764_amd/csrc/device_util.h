@@ -386,6 +386,88 @@ __device__ __forceinline__ void gather_tile_mu1_single(float *tile, const float 
     }
 }
 
+// Modes 0 and 1 of gather_tile_mu1_single for rows of several 64-entry chunks (the graphs of the inference loop,
+// whose rows shrink from hundreds of entries): eight rows at a time as before, but chunk LEVEL by chunk level --
+// the q-th chunks of all eight rows are fetched together (indices, then table entries, then the records that are
+// needed), so eight rows of 200 entries cost four rounds of dependent loads instead of eight times four.  Every
+// lane adds the same values in the same order as in gather_tile_mu1_single: the same bits.
+template <int P, int MODE>
+__device__ __forceinline__ void gather_tile_mu1_levels(float *tile, const float *__restrict__ rec,
+                                                       const float *__restrict__ compact, const float *lc,
+                                                       const int *__restrict__ colidx, int rb, int re, int max_len,
+                                                       int lane) {
+    static_assert(MODE == 0 || MODE == 1, "");
+    constexpr int STRIDE = Geo<P>::STRIDE;
+    const int j = lane % P;
+    const float t1 = lc[j], qp = lc[P + j], qn = lc[2 * P + j];
+    const float rp = fmaxf(qp, 0.f);
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        float ssum[8], acc[8];
+        int nlev = 0;   // chunk levels of the longest row of this half that is gathered here (wave-uniform)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            ssum[k] = 0.f; acc[k] = 0.f;
+            const int n = __builtin_amdgcn_readlane(re, 8 * half + k) - __builtin_amdgcn_readlane(rb, 8 * half + k);
+            if (n <= max_len) nlev = max(nlev, (n + 63) >> 6);
+        }
+#pragma unroll 1
+        for (int lev = 0; lev < nlev; ++lev) {
+            int cols[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int b = __builtin_amdgcn_readlane(rb, 8 * half + k), n = __builtin_amdgcn_readlane(re, 8 * half + k) - b;
+                const int i = 64 * lev + lane;
+                cols[k] = (n <= max_len && i < n) ? colidx[b + i] : -1;
+            }
+            float rx[8], rs[8], rn[8];
+            if constexpr (MODE == 1) {
+                float c[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) c[k] = cols[k] >= 0 ? compact[cols[k]] : 0.f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    rx[k] = 0.f; rs[k] = c[k]; rn[k] = 0.f;
+                    if (c[k] != c[k]) {
+                        const float4 r = ld4(rec + (size_t)cols[k] * 4);
+                        rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    rx[k] = 0.f; rs[k] = 0.f; rn[k] = 0.f;
+                    if (cols[k] >= 0) {
+                        const float4 r = ld4(rec + (size_t)cols[k] * 4);
+                        rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool cheap = rx[k] == 0.f && rn[k] == 0.f;
+                ssum[k] += cheap ? rs[k] : 0.f;
+                unsigned long long todo = __ballot(!cheap);
+                while (todo != 0ull) {
+                    const int l = __ffsll((long long)todo) - 1;
+                    todo &= todo - 1ull;
+                    const float xl = readlane_f(rx[k], l), pl = readlane_f(rs[k], l), nl = readlane_f(rn[k], l);
+                    acc[k] += fmaxf(mu1_z(xl, pl, nl, t1, qp, qn), 0.f);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = 8 * half + k;
+            if (__builtin_amdgcn_readlane(re, i) - __builtin_amdgcn_readlane(rb, i) > max_len) continue;   // wave-uniform
+            float sv = ssum[k];
+#pragma unroll
+            for (int m = 1; m < 64; m <<= 1) sv += __shfl_xor(sv, m);
+            if (lane < P) tile[i * STRIDE + lane] = fmaf(sv, rp, acc[k]);
+        }
+    }
+}
+
 // Node mode (S a multiple of 16): the 16 rows of a wave tile are 16 consecutive states
 // s0 .. s0+15 of ONE node v, so every neighbour u contributes one contiguous block of 16 * P
 // floats, mu[u][s0 .. s0+15][:].  A wave-wide float4 load covers RPI = 64 / LPR of those rows

@@ -520,7 +520,18 @@ __global__ __launch_bounds__(kThreads, MU1 ? ((NODE && VAR != kRoundFlags) ? 3 :
                 for (int c = 0; c < NC; ++c) {
                     const int i = c * RPI + lane / G::LPR;
                     const int hi = __shfl(h_mine, i), si = __shfl(s, i);
-                    if (hi >= 0) st4(tile + i * G::STRIDE + 4 * li, ld4(hub_sum + ((size_t)hi * S + si) * P + 4 * li));
+                    if (hi >= 0) {
+                        float4 a;
+                        if (ht.fold) {
+                            // (hub_sum holds the segment sums: added here in segment order, as k_hub_combine would)
+                            a = make_float4(0.f, 0.f, 0.f, 0.f);
+                            for (int seg = ht.hub_seg_off[hi]; seg < ht.hub_seg_off[hi + 1]; ++seg)
+                                a = add4(a, ld4(hub_sum + ((size_t)seg * S + si) * P + 4 * li));
+                        } else {
+                            a = ld4(hub_sum + ((size_t)hi * S + si) * P + 4 * li);
+                        }
+                        st4(tile + i * G::STRIDE + 4 * li, a);
+                    }
                 }
             }
             if (MU1 && S == 1 && (!W || info.xbits)) {
@@ -530,9 +541,9 @@ __global__ __launch_bounds__(kThreads, MU1 ? ((NODE && VAR != kRoundFlags) ? 3 :
                                                     lane, valid ? info.base[(size_t)v * 4 + 3] : 0.f, wagg);
                 else if (W) {}
                 else if (info.compact)
-                    gather_tile_mu1_single<P, 1>(tile, info.base, info.compact, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
+                    gather_tile_mu1_levels<P, 1>(tile, info.base, info.compact, lds_c, colidx, rb, re, kHubDegree, lane);
                 else
-                    gather_tile_mu1_single<P, 0>(tile, info.base, nullptr, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
+                    gather_tile_mu1_levels<P, 0>(tile, info.base, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
             } else {
             int b_next = __builtin_amdgcn_readlane(rb, 0), e_next = __builtin_amdgcn_readlane(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
@@ -900,6 +911,8 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
     // so they are written where the row sums go and the pass that adds a row's segments is not launched
     const bool single = ht.n_segs == ht.n_hubs;
     if (single) partial = hub_sum;
+    // (ht.fold: the caller's round kernel adds the segments; the caller passes the segment sums on as hub_sum)
+    const bool no_combine = single || ht.fold != 0;
     const long items = (long)ht.n_segs * (node ? S / 16 : S);
     const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
 #define S2V_LAUNCH_HUB_W(PP, NODE, SRC, WW)                                                                       \
@@ -925,7 +938,7 @@ hipError_t launch_hub_sums(hipStream_t st, int p, int S, const HubTable &ht, con
 #undef S2V_LAUNCH_HUB
 #undef S2V_LAUNCH_HUB_W
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess || single) return err;
+    if (err != hipSuccess || no_combine) return err;
     return launch_hub_combine(st, S * p, ht, partial, hub_sum);
 }
 

@@ -42,6 +42,7 @@ struct HubTable {              // device pointers into the prepared head of the 
     int n_hubs, n_segs;
     const int32_t *hub_rows;     // [n_hubs] node ids, ascending
     const int32_t *hub_of;       // [N] (with n_hubs > 0) index of a long row's node in hub_rows
+    int fold;                    // forward, one state: no combine pass; the round adds a long row's (few) segment sums itself
     const int32_t *hub_seg_off;  // [n_hubs+1] segments of hub h are [off[h], off[h+1])
     const int32_t *seg_row;      // [n_segs] node id of the segment's row
     const int32_t *seg_begin;    // [n_segs] first CSR entry of the segment
