@@ -351,8 +351,8 @@ int32_t s2v_residual_update(s2v_ctx *ctx, const s2v_graph *g, float *x, const in
  *   steps_out, picked_out, live_out: host pointers; policy evaluations made, nodes added, live
  *            stored entries left (0 = complete cover)
  * Which d to use, whether an edge is left and the two counts are decided and kept on the device; the host
- * reads the state back once per block of steps (1, 2, 4, 8, then 16 steps), so the call waits for the stream
- * a few times per solve, and a block that outlasts the solve still makes its (then ineffective) evaluations.
+ * reads the state back once per block of steps (1, 2, 4, ... up to 64 steps, and never more than a sixteenth of
+ * the candidates the largest graph has left), so the call waits for the stream a few times per solve, and a block that outlasts the solve still makes its (then ineffective) evaluations.
  * With the adaptive rule sel_idx / sel_val receive the eight best candidates of the last evaluation, of
  * which the first sel_count joined the solution.
  */

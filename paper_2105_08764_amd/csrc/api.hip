@@ -47,7 +47,7 @@ struct Carver {
 
 struct HeadLayout {
     size_t s_pos, s_neg, nbr_sp, nbr_spw, chunk_begin, chunk_end, graph_chunk_off;
-    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, hub_of, epoch, loop_ctr, rec, qkeep, end;
+    size_t hub_rows, hub_seg_off, seg_row, seg_begin, seg_end, touched, hub_of, epoch, loop_ctr, rec, qkeep, jobs, end;
     int max_chunks, max_hubs, max_segs;
 };
 
@@ -98,6 +98,7 @@ HeadLayout head_layout(int64_t N, int64_t G, int hubs, int segs) {
     h.loop_ctr = c.take(sizeof(unsigned long long) * 2);   // counters of s2v_mvc_inference
     h.rec = c.take(sizeof(float) * 5 * N);          // its node records {x, s+, s-, 0} and the 4-byte table behind them
     h.qkeep = c.take(sizeof(float) * 2 * 128);      // its q+-
+    h.jobs = c.take(sizeof(int32_t) * 2 * kUpdateJobs);   // row ranges handed from the first to the second half of an update
     h.end = c.off;
     return h;
 }
@@ -1154,6 +1155,7 @@ static UpdateState update_state(const s2v_graph *g, const Prepared &pr, const He
     u.stats = stats;
     u.touched = at<int32_t>(ws, h.touched);
     u.epoch = at<int32_t>(ws, h.epoch);   // (the number of incremental updates since s2v_graph_prepare)
+    u.jobs = at<int32_t>(ws, h.jobs);
     u.rec = pr.rec_keep ? at<float>(ws, h.rec) : nullptr;
     u.compact = (pr.rec_keep && !pr.has_neg) ? at<float>(ws, h.rec) + (size_t)g->n_nodes * 4 : nullptr;
     return u;
@@ -1205,8 +1207,9 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     // The loop runs in blocks of steps without reading anything back: which d to use, whether an edge is
     // left, and the counts of evaluations and of added nodes are all decided and kept on the device
     // (k_loop_control).  The host looks at the state once per block; a block that outlasts the solve costs the
-    // evaluations it still makes, which change nothing.  Blocks grow 1, 2, 4, ... up to kLoopBlock steps.
-    constexpr int kLoopBlock = 16;
+    // evaluations it still makes, which change nothing.  Blocks grow 1, 2, 4, ... up to kLoopBlock steps, and
+    // never beyond a sixteenth of the candidates the largest graph has left (every step removes at least one).
+    constexpr int kLoopBlock = 64;
     const Prepared *pr = find_prepared(ctx, g, ws);
     if (!pr) return S2V_ERR_NOT_PREPARED;
     const HeadLayout h = head_layout(N, G, pr->n_hubs, pr->n_segs);
@@ -1214,12 +1217,17 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     S2V_TRY(launch_zero_i32(ctx->stream, 4, reinterpret_cast<int32_t *>(ctr)));
     std::vector<int32_t> hstats(2 * (size_t)G);
     unsigned long long hctr[2] = {0ull, 0ull};
+    int32_t max_cand = 0;
     auto read_state = [&](int64_t *n_live) -> int32_t {
         S2V_TRY(hipMemcpyAsync(hstats.data(), stats, sizeof(int32_t) * 2 * G, hipMemcpyDeviceToHost, ctx->stream));
         S2V_TRY(hipMemcpyAsync(hctr, ctr, sizeof(hctr), hipMemcpyDeviceToHost, ctx->stream));
         S2V_TRY(hipStreamSynchronize(ctx->stream));
         *n_live = 0;
-        for (int b = 0; b < G; ++b) *n_live += hstats[2 * b + 1];
+        max_cand = 0;
+        for (int b = 0; b < G; ++b) {
+            *n_live += hstats[2 * b + 1];
+            if (hstats[2 * b] > max_cand) max_cand = hstats[2 * b];
+        }
         return S2V_OK;
     };
     int64_t n_live = 0;
@@ -1238,7 +1246,8 @@ int32_t s2v_mvc_inference(s2v_ctx *ctx, const s2v_graph *g, const s2v_params *pa
     const StepEnd end{N, use_rule, ctr, &upd};
     int32_t launched = 0, block = 1;
     while (n_live > 0 && launched < max_steps) {
-        const int32_t todo = block < max_steps - launched ? block : max_steps - launched;
+        int32_t todo = block < max_steps - launched ? block : max_steps - launched;
+        if (todo > max_cand / 16) todo = max_cand / 16 > 1 ? max_cand / 16 : 1;
         for (int32_t i = 0; i < todo; ++i) {
             bool ended = false;
             rc = policy_select_impl(ctx, g, params, x, cand, T, k_sel, mu, gsum, q, sel_idx, sel_val, sel_count, ws, ws_bytes,

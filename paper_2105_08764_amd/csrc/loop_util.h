@@ -30,7 +30,11 @@ struct UpdateState {
     // optional (inside the inference loop): the single-state node records {x, s+, s-, 0} [N][4] and the table
     // compact[v] = s+ of a node with x = 0 and s- = 0, NaN for any other, kept current for the rows that change
     float *rec, *compact;
+    // [kUpdateJobs][2]: first entry and old length of the row of selected entry i (written for every i when
+    // total <= kUpdateJobs), so that the second half finds a row's entries with one load
+    int32_t *jobs;
 };
+constexpr int kUpdateJobs = 64;
 
 // The record of node v after its x, s+ or s- changed.
 __device__ __forceinline__ void refresh_record(float *rec, float *compact, int v, float xv, float sp, float sn) {
@@ -47,23 +51,30 @@ __device__ __forceinline__ void refresh_record(float *rec, float *compact, int v
 // the rows that lose an entry.  A node listed twice is emptied once (the exchange on its row end decides).
 __device__ __forceinline__ void begin_update(const UpdateState &u, const int32_t *sel_idx, const int32_t *sel_count,
                                              int tid, int stride) {
+    const bool list_jobs = u.jobs && u.total <= kUpdateJobs;
     for (int i = tid; i < u.total; i += stride) {
         const int g = i / u.k, j = i - g * u.k;
-        if (j >= sel_count[g]) continue;
-        const int v = sel_idx[i];
-        if (v < 0) continue;
-        u.x[v] = 1.f;
-        refresh_record(u.rec, u.compact, v, 1.f, 0.f, 0.f);   // (a solution node has no live entry: both sums are zero)
-        const int b = u.rowptr[v];
-        const int len = atomicExch(&u.rowend[v], b) - b;
-        if (len <= 0) continue;
-        u.touched[v] = -len;
-        u.s_pos[v] = 0.f;
-        u.s_neg[v] = 0.f;
-        const int gg = graph_of(u.G, u.graph_off, v);
-        if (u.cand[v]) atomicAdd(&u.stats[2 * gg], -1);
-        u.cand[v] = 0;
-        atomicAdd(&u.stats[2 * gg + 1], -len);
+        int b = 0, len = 0;
+        const int v = j < sel_count[g] ? sel_idx[i] : -1;
+        if (v >= 0) {
+            u.x[v] = 1.f;
+            refresh_record(u.rec, u.compact, v, 1.f, 0.f, 0.f);   // (a solution node has no live entry: both sums are zero)
+            b = u.rowptr[v];
+            len = atomicExch(&u.rowend[v], b) - b;
+            if (len > 0) {
+                u.touched[v] = -len;
+                u.s_pos[v] = 0.f;
+                u.s_neg[v] = 0.f;
+                const int gg = graph_of(u.G, u.graph_off, v);
+                if (u.cand[v]) atomicAdd(&u.stats[2 * gg], -1);
+                u.cand[v] = 0;
+                atomicAdd(&u.stats[2 * gg + 1], -len);
+            }
+        }
+        if (list_jobs) {
+            u.jobs[2 * i] = b;
+            u.jobs[2 * i + 1] = len > 0 ? len : 0;
+        }
     }
 }
 

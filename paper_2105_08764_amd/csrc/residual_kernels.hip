@@ -125,17 +125,23 @@ __global__ __launch_bounds__(256) void k_refilter_neighbours(int total, int k, c
                                                              const int32_t *__restrict__ graph_off,
                                                              int32_t *__restrict__ stats, int32_t *__restrict__ touched,
                                                              const int32_t *__restrict__ epoch, float *rec,
-                                                             float *compact) {
+                                                             float *compact, const int32_t *__restrict__ jobs) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ep = epoch[0];
     for (int i = blockIdx.y; i < total; i += gridDim.y) {
-        const int g = i / k, j = i - g * k;
-        if (j >= sel_count[g]) continue;
-        const int v = sel_idx[i];
-        if (v < 0) continue;
-        const int len = -touched[v];
+        int b, len;
+        if (jobs) {   // (the first half listed first entry and old length of every selected entry's row)
+            b = jobs[2 * i];
+            len = jobs[2 * i + 1];
+        } else {
+            const int g = i / k, j = i - g * k;
+            if (j >= sel_count[g]) continue;
+            const int v = sel_idx[i];
+            if (v < 0) continue;
+            len = -touched[v];
+            b = rowptr[v];
+        }
         if (len <= 0) continue;   // (the node had no live entry when it joined)
-        const int b = rowptr[v];
         for (int t = blockIdx.x * 4 + wave; t < len; t += gridDim.x * 4) {
             const int u = colidx[b + t];
             if (x[u] != 0.f) continue;
@@ -195,7 +201,8 @@ hipError_t launch_residual_update(hipStream_t st, int N, const UpdateState &u, i
         const int gx = max(1, min(1024 / gy, (N + 3) / 4));
         k_refilter_neighbours<<<dim3(gx, gy), 256, 0, st>>>(u.total, u.k, sel_idx, sel_count, u.rowptr, u.rowend, colidx, w,
                                                            u.x, u.s_pos, u.s_neg, u.cand, u.G, u.graph_off, u.stats,
-                                                           u.touched, u.epoch, u.rec, u.compact);
+                                                           u.touched, u.epoch, u.rec, u.compact,
+                                                           (u.jobs && u.total <= kUpdateJobs) ? u.jobs : nullptr);
         return hipGetLastError();
     }
     k_zero_stats<<<1, 256, 0, st>>>(2 * u.G, u.stats);
