@@ -213,3 +213,45 @@ def test_adaptive_selection_needs_fewer_evaluations(oracle_mod):
         assert out[adaptive][2] == 0
     assert out[True][0] < out[False][0]
     print("evaluations d=1 / adaptive:", out[False][0], out[True][0], "cover sizes:", out[False][1], out[True][1])
+
+
+@pytest.mark.parametrize("adaptive", [False, True])
+def test_native_loop_beyond_the_fused_tail(adaptive):
+    # 20 000 nodes: past the size up to which the evaluation's tail and the selection share launches, so the loop
+    # runs s2v_policy_eval + s2v_select_topk and a separate decision kernel.  The first 200 steps must equal the
+    # step-by-step run bit for bit, and the full run must end with a vertex cover.
+    import torch
+
+    g = si.erdos_renyi_gnp(20000, 3.0 / 20000, 12)
+    p, T = 32, 3
+    theta = si.thetas(p, 6, 0.05)
+    dev = LoopDevice(g, p, T)
+    prm = dev.s2v.Params.from_numpy(theta)
+    stats = dev.update()
+    n_ref = 200
+    for _ in range(n_ref):
+        assert stats[:, 1].sum() > 0
+        d = dev.s2v.s2v_adaptive_d(int(stats[0, 0]), g.n) if adaptive else 1
+        idx = torch.full((1, d), -1, dtype=torch.int32, device="cuda")
+        val = torch.empty((1, d), device="cuda")
+        dev.ctx.s2v_policy_select(dev.graph, prm, dev.x, dev.cand, T, d, dev.mu, dev.gsum, dev.q, idx, val, dev.sel_cnt,
+                                  dev.ws)
+        dev.sel_idx.fill_(-1)
+        dev.sel_idx[:, :d] = idx
+        stats = dev.update(k=8)
+    dev2 = LoopDevice(g, p, T)
+    n2, picked2, live2 = dev2.ctx.s2v_mvc_inference(dev2.graph, prm, dev2.x, T, adaptive, n_ref, dev2.mu, dev2.gsum,
+                                                    dev2.q, dev2.cand, dev2.sel_idx, dev2.sel_val, dev2.sel_cnt,
+                                                    dev2.stats, dev2.ws)
+    assert n2 == n_ref and live2 == int(stats[:, 1].sum())
+    assert np.array_equal(dev2.x.cpu().numpy(), dev.x.cpu().numpy()) and picked2 == int(dev.x.sum().item())
+    assert np.array_equal(dev2.graph.row_end.cpu().numpy(), dev.graph.row_end.cpu().numpy())
+    # ... and on to the end
+    n3, picked3, live3 = dev2.ctx.s2v_mvc_inference(dev2.graph, prm, dev2.x, T, adaptive, 10 * g.n, dev2.mu, dev2.gsum,
+                                                    dev2.q, dev2.cand, dev2.sel_idx, dev2.sel_val, dev2.sel_cnt,
+                                                    dev2.stats, dev2.ws)
+    assert live3 == 0
+    xs = dev2.x.cpu().numpy()
+    rows = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    assert ((xs[rows] != 0) | (xs[g.colidx] != 0)).all() and int(xs.sum()) == picked2 + picked3
+    print(f"  20000 nodes, adaptive={adaptive}: {n2 + n3} evaluations, cover of {int(xs.sum())} nodes", flush=True)
