@@ -530,17 +530,29 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     rc = check_ws(ws);
     if (rc != S2V_OK) return rc;
     const int32_t N = g->n_nodes, G = g->n_graphs;
-    // hub rows and their segments, from a host copy of rowptr
-    std::vector<int32_t> rp((size_t)N + 1);
-    S2V_TRY(hipMemcpyAsync(rp.data(), g->rowptr, sizeof(int32_t) * ((size_t)N + 1), hipMemcpyDeviceToHost, ctx->stream));
-    S2V_TRY(hipStreamSynchronize(ctx->stream));
-    if (rp[0] != 0 || (int64_t)rp[N] != g->nnz) return S2V_ERR_INVALID_ARG;
-    for (int32_t v = 0; v < N; ++v)
-        if (rp[v + 1] < rp[v]) return S2V_ERR_INVALID_ARG;
+    // Long rows and their segments.  A kernel counts them and checks the row pointers; only a graph that has
+    // long rows gets its row pointers copied to the host, where the (ordered) tables are built.
+    // (the first words of the workspace serve as the kernel's output: the head is written after this)
+    if (ws_bytes < 256) return S2V_ERR_WORKSPACE_TOO_SMALL;
+    int32_t row_stats[3] = {0, 0, 0};
+    if (N > 0) {
+        S2V_TRY(launch_zero_i32(ctx->stream, 4, static_cast<int32_t *>(ws)));
+        S2V_TRY(launch_row_stats(ctx->stream, N, (long)g->nnz, g->rowptr, static_cast<int32_t *>(ws)));
+        S2V_TRY(hipMemcpyAsync(row_stats, ws, sizeof(row_stats), hipMemcpyDeviceToHost, ctx->stream));
+        S2V_TRY(hipStreamSynchronize(ctx->stream));
+        if (row_stats[2] != 0) return S2V_ERR_INVALID_ARG;
+    } else if (g->nnz != 0) {
+        return S2V_ERR_INVALID_ARG;
+    }
     // Hub rows are those that are long in STORAGE: rows only shrink afterwards, and the kernels test
     // the live length, so a stored-long row that became short is simply handled as an ordinary row.
-    int n_hubs = 0, n_segs = 0;
-    hub_counts(rp, &n_hubs, &n_segs);
+    const int n_hubs = row_stats[0], n_segs = row_stats[1];
+    std::vector<int32_t> rp;
+    if (n_hubs > 0) {
+        rp.resize((size_t)N + 1);
+        S2V_TRY(hipMemcpyAsync(rp.data(), g->rowptr, sizeof(int32_t) * ((size_t)N + 1), hipMemcpyDeviceToHost, ctx->stream));
+        S2V_TRY(hipStreamSynchronize(ctx->stream));
+    }
     const HeadLayout h = head_layout(N, G, n_hubs, n_segs);
     if (ws_bytes < h.end) return S2V_ERR_WORKSPACE_TOO_SMALL;
 
@@ -573,7 +585,7 @@ int32_t s2v_graph_prepare(s2v_ctx *ctx, const s2v_graph *g, void *ws, size_t ws_
     }
     S2V_TRY(hipMemcpyAsync(at<int32_t>(ws, h.graph_chunk_off), gco.data(), sizeof(int32_t) * (G + 1), hipMemcpyHostToDevice, ctx->stream));
     std::vector<int32_t> hub_rows, hub_seg_off, seg_row, seg_begin, seg_end;
-    for (int32_t v = 0; v < N; ++v) {
+    for (int32_t v = 0; n_hubs > 0 && v < N; ++v) {
         if (rp[v + 1] - rp[v] > kHubDegree) {
             hub_rows.push_back(v);
             hub_seg_off.push_back((int32_t)seg_begin.size());

@@ -44,30 +44,73 @@ hipError_t launch_prepare_s(hipStream_t st, int N, const int32_t *rowptr, const 
 // nbr_sp[v] = sum_{u in N(v)} s+_u: what the neighbour sum of round 2 comes to when no neighbour is in the
 // solution (then mu^1_u = s+_u relu(q+) for every u).  Rows beyond kHubDegree go through the long-row
 // pre-pass and never use it.
+// (sixteen lanes per row: the row's entries are read in coalesced pieces; double accumulators, added in a fixed
+//  order, so the rounded result does not depend on the launch)
 __global__ __launch_bounds__(256) void k_prepare_nbr(int N, const int32_t *__restrict__ rowptr,
                                                      const int32_t *__restrict__ rowend,
                                                      const int32_t *__restrict__ colidx,
                                                      const float *__restrict__ w,
                                                      const float *__restrict__ s_pos, float *__restrict__ nbr_sp,
                                                      float *__restrict__ nbr_spw) {
-    for (int v = blockIdx.x * blockDim.x + threadIdx.x; v < N; v += gridDim.x * blockDim.x) {
-        const int b = rowptr[v], e = rowend[v];
+    const int sub = threadIdx.x & 15;
+    const long groups = ((long)gridDim.x * blockDim.x) >> 4;
+    const long n_iter = (N + groups - 1) / groups;   // every lane makes the same number of steps (shuffles below)
+    for (long it = 0; it < n_iter; ++it) {
+        const long v = it * groups + (((long)blockIdx.x * blockDim.x + threadIdx.x) >> 4);
+        const bool in = v < N;
+        const int b = in ? rowptr[v] : 0, e = in ? rowend[v] : 0;
         double a = 0.0, aw = 0.0;   // aw: each neighbour weighted by its edge (the weighted neighbour sum)
         if (e - b <= kHubDegree)
-            for (int j = b; j < e; ++j) {
+            for (int j = b + sub; j < e; j += 16) {
                 const double sp = (double)s_pos[colidx[j]];
                 a += sp;
                 if (w) aw += (double)w[j] * sp;
             }
-        nbr_sp[v] = (float)a;
-        nbr_spw[v] = w ? (float)aw : (float)a;
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) {
+            a += __shfl_xor(a, m);
+            aw += __shfl_xor(aw, m);
+        }
+        if (in && sub == 0) {
+            nbr_sp[v] = (float)a;
+            nbr_spw[v] = w ? (float)aw : (float)a;
+        }
     }
 }
 
 hipError_t launch_prepare_nbr(hipStream_t st, int N, const int32_t *rowptr, const int32_t *rowend, const int32_t *colidx,
                               const float *w, const float *s_pos, float *nbr_sp, float *nbr_spw) {
     if (N == 0) return hipSuccess;
-    k_prepare_nbr<<<min((N + 255) / 256, 65536), 256, 0, st>>>(N, rowptr, rowend, colidx, w, s_pos, nbr_sp, nbr_spw);
+    k_prepare_nbr<<<(int)min(((long)N * 16 + 255) / 256, (long)65536), 256, 0, st>>>(N, rowptr, rowend, colidx, w, s_pos, nbr_sp,
+                                                                                  nbr_spw);
+    return hipGetLastError();
+}
+
+// Row statistics of a CSR graph, so that the host need not read the row pointers back for a graph without
+// long rows: out[0] = rows longer than kHubDegree, out[1] = their segments of kHubSegment entries,
+// out[2] = 1 when the row pointers are not a non-decreasing sequence from 0 to nnz.  out starts at zero.
+__global__ __launch_bounds__(256) void k_row_stats(int N, long nnz, const int32_t *__restrict__ rowptr,
+                                                   int32_t *__restrict__ out) {
+    int hubs = 0, segs = 0, bad = 0;
+    for (int v = blockIdx.x * 256 + threadIdx.x; v < N; v += gridDim.x * 256) {
+        const int a = rowptr[v], b = rowptr[v + 1];
+        if (b < a) bad = 1;
+        if (v == 0 && a != 0) bad = 1;
+        if (v == N - 1 && (long)b != nnz) bad = 1;
+        const int d = b - a;
+        if (d > kHubDegree) {
+            ++hubs;
+            segs += (d + kHubSegment - 1) / kHubSegment;
+        }
+    }
+    if (hubs) atomicAdd(&out[0], hubs);
+    if (segs) atomicAdd(&out[1], segs);
+    if (bad) atomicOr(&out[2], 1);
+}
+
+hipError_t launch_row_stats(hipStream_t st, int N, long nnz, const int32_t *rowptr, int32_t *out) {
+    if (N == 0) return hipSuccess;
+    k_row_stats<<<min((N + 255) / 256, 4096), 256, 0, st>>>(N, nnz, rowptr, out);
     return hipGetLastError();
 }
 

@@ -127,6 +127,8 @@ hipError_t launch_stateinfo_residual(hipStream_t st, int N, int S, const HubTabl
 #endif
 constexpr int kRoundGridMax = S2V_ROUND_GRID;
 int round_grid(long n_vrows);
+// out[0..2] (zeroed by the caller) += {long rows, their segments, 1 if the row pointers are malformed}
+hipError_t launch_row_stats(hipStream_t st, int N, long nnz, const int32_t *rowptr, int32_t *out);
 hipError_t launch_nodeinfo(hipStream_t st, int N, int S, const float *x, const float *s_pos, const float *s_neg,
                            float *info /*written in the shared-sums layout of make_nodeinfo*/,
                            float *compact /*[N], written when S == 1; may be NULL*/,
