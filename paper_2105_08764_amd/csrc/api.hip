@@ -724,7 +724,7 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     if ((mu_saved && !fused) || T == 1)
         S2V_TRY(launch_round1(st, p, N, S, ninfo, x_res, T == 1, params->theta1, qvec, dest(1)));
     const bool fuse_gsum = gsum && (S == 1 || S == 16) && G == 1 && T >= 2 && N > 0;
-    const bool fuse_q = q_node && T >= 2 && N > 0 && round_fuses_qnode(S);
+    const bool fuse_q = q_node && T >= 2 && N > 0 && round_fuses_qnode(S, T);
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
     const bool by_state = S % 16 == 0 && nsp * sizeof(float) >= ctx->sliced_min_bytes;
     // one state and at most four segments per long row: no combine pass, the round kernel adds the segments

@@ -428,7 +428,7 @@ __global__ __launch_bounds__(kThreads, MU1 ? ((NODE && VAR != kRoundFlags) ? 3 :
     constexpr bool MO = VAR == kRoundMaskOut, SLICED = VAR == kRoundByState, FL = VAR == kRoundFlags;
     static_assert(!FL || (NODE && MU1), "the flag-word variant is node mode of round 2");
     static_assert(!SLICED || (!NODE && !MU1 && !GSUM && !QN), "the state-by-state order is a plain row-mode variant");
-    static_assert(!(QN && NODE), "the node term of Q is fused in row mode only");
+    static_assert(!(QN && NODE && MU1), "in node mode the node term of Q is fused into rounds that read rows");
     static_assert(!MO || (NODE && !MU1 && !QN), "mask output is a node-mode variant of the rounds that read rows");
     __shared__ __attribute__((aligned(16))) float lds[kWaves][kTileRows * G::STRIDE];
     __shared__ __attribute__((aligned(16))) float lds_b[P * G::STRIDE];   // theta2, the B operand
@@ -771,7 +771,7 @@ static hipError_t launch_round_p(hipStream_t st, int N, int S, const int32_t *ro
                                                                    hub_sum, x_res, N, last ? 1 : 0, qh, mo)
 #define S2V_LAUNCH_ROUND_W(NODE, MU1, GSUM, WW)                            \
     do {                                                                   \
-        if (!NODE && qh.q) S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, !NODE); \
+        if (!(NODE && MU1) && qh.q) S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, !(NODE && MU1)); \
         else S2V_LAUNCH_ROUND_Q(NODE, MU1, GSUM, WW, false);               \
     } while (0)
 #define S2V_LAUNCH_ROUND(NODE, MU1, GSUM)                \

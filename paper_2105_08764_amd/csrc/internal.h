@@ -161,7 +161,7 @@ struct MaskOut {
     const int32_t *action;       // [S]: the rows of these nodes are still written to mu_out
 };
 // whether launch_round honours a QHead for this S (else the caller runs the separate node-term kernel)
-inline bool round_fuses_qnode(int S) { return (S % 16) != 0; }
+inline bool round_fuses_qnode(int S, int T) { return (S % 16) != 0 || T >= 3; }
 hipError_t launch_qfinish(hipStream_t st, int N, int S, int G, const int32_t *graph_off, const float *qa, float *q);
 hipError_t launch_hub_combine(hipStream_t st, int L, const HubTable &ht, const float *partial, float *hub_sum);
 hipError_t launch_round(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
