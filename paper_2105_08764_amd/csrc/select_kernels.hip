@@ -26,6 +26,40 @@ __device__ __forceinline__ void block_best(float &val, int &idx, float *sval, in
     }
 }
 
+// The best (val, idx) of a wave, returned to every lane.
+__device__ __forceinline__ void wave_best(float &val, int &idx) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        const float v2 = __shfl_xor(val, m);
+        const int i2 = __shfl_xor(idx, m);
+        take_better(val, idx, v2, i2);
+    }
+}
+
+// The k best of the (at most two) candidates every lane of ONE wave holds, in order, without a barrier: k times
+// the wave's best of what is left.  (v0, i0), (v1, i1): the lane's candidates, idx INT_MAX = none; node indices
+// are distinct, so the winner's owner knows itself by the index.  out(it, val, idx) is called by every lane with
+// the it-th pick (idx INT_MAX from the first pick that does not exist on; the loop stops there).
+// Returns the number of picks.
+template <class Out>
+__device__ __forceinline__ int wave_topk(float v0, int i0, float v1, int i1, int k, Out out) {
+    int found = 0;
+    for (int it = 0; it < k; ++it) {
+        float val = v0;
+        int idx = i0;
+        take_better(val, idx, v1, i1);
+        if (i0 == INT_MAX) { val = v1; idx = i1; }
+        if (idx == INT_MAX) val = -INFINITY;
+        wave_best(val, idx);
+        out(it, val, idx);
+        if (idx == INT_MAX) break;
+        if (i0 == idx) { i0 = INT_MAX; v0 = -INFINITY; }
+        if (i1 == idx) { i1 = INT_MAX; v1 = -INFINITY; }
+        ++found;
+    }
+    return found;
+}
+
 __global__ __launch_bounds__(256) void k_argmax_stage1(const int32_t *__restrict__ chunk_begin,
                                                        const int32_t *__restrict__ chunk_end,
                                                        const float *__restrict__ q, const float *__restrict__ x,
@@ -144,6 +178,28 @@ __global__ __launch_bounds__(256) void k_smallk_stage1(int k, const int32_t *__r
 // Second stage of the top-k (k <= kSmallK) of one graph, by one workgroup of 256 threads.
 __device__ __forceinline__ void smallk_stage2(int k, int n_chunks, const float *part_val, const int32_t *part_idx,
                                               int32_t *idx_out, float *val_out, int32_t *count, float *sval, int *sidx) {
+    if (n_chunks * kSmallK <= 128) {
+        // few chunks (a graph of up to 16 384 nodes): the first wave alone, two listed picks per lane, no barrier
+        if (threadIdx.x < 64) {
+            const int lane = threadIdx.x;
+            auto slot = [&](int sl, float &v, int &i) {
+                const int c = sl / kSmallK, r = sl - c * kSmallK;
+                const bool have = c < n_chunks && r < k;   // (a chunk's list is padded with INT_MAX behind its last pick)
+                i = have ? part_idx[(size_t)c * kSmallK + r] : INT_MAX;
+                v = (have && i != INT_MAX) ? part_val[(size_t)c * kSmallK + r] : -INFINITY;
+            };
+            float v0, v1;
+            int i0, i1;
+            slot(lane, v0, i0);
+            slot(lane + 64, v1, i1);
+            const int found = wave_topk(v0, i0, v1, i1, k, [&](int it, float val, int idx) {
+                if (lane == 0 && idx != INT_MAX) { idx_out[it] = idx; val_out[it] = val + 0.0f; }
+            });
+            for (int r = found + lane; r < k; r += 64) { idx_out[r] = -1; val_out[r] = -INFINITY; }
+            if (lane == 0) count[0] = found;
+        }
+        return;
+    }
     float lv = INFINITY;
     int lidx = -1;
     int found = 0;
@@ -701,8 +757,8 @@ __global__ __launch_bounds__(1024) void k_tail_select1(int p, int rows, int k, c
                                                        float *__restrict__ part_val, int32_t *__restrict__ part_idx) {
     __shared__ double red[64][17];
     __shared__ float gsv[128], gs[128], redf[128];
-    __shared__ float sval[16];
-    __shared__ int sidx[16];
+    __shared__ float wv[16][kSmallK];   // the waves' picks
+    __shared__ int wi[16][kSmallK];
     const int tid = threadIdx.x;
     for (int cb = 0; cb < p / 16; ++cb) {
         const int col = 16 * cb + (tid & 15);
@@ -722,38 +778,43 @@ __global__ __launch_bounds__(1024) void k_tail_select1(int p, int rows, int k, c
         q[v] = qv;
         if (is_candidate(x, cand, v)) { myv = qv; myi = v; }
     }
-    float lv = INFINITY;
-    int lidx = -1;
-    for (int it = 0; it < k; ++it) {
-        float val = -INFINITY;
-        int idx = INT_MAX;
-        if (myi != INT_MAX && beats(lv, lidx, myv, myi)) { val = myv; idx = myi; }
-#pragma unroll
-        for (int m = 1; m < 64; m <<= 1) {
-            const float v2 = __shfl_xor(val, m);
-            const int i2 = __shfl_xor(idx, m);
-            take_better(val, idx, v2, i2);
+    // the chunk's k best: every wave picks the k best of its 64 nodes (no barrier), then the first wave picks the
+    // k best of those 16 x k (two per lane); the order rule makes the outcome the same as any other way of picking
+    const int wave = tid >> 6, lane = tid & 63;
+    wave_topk(myv, myi, -INFINITY, INT_MAX, k, [&](int it, float val, int idx) {
+        if (lane == 0) { wv[wave][it] = val; wi[wave][it] = idx; }
+    });
+    __syncthreads();
+    if (wave == 0) {
+        // candidate slot s of the 16 x kSmallK table: wave s / kSmallK... laid out [wave][pick]; lane l takes slots l and l + 64
+        auto slot = [&](int sl, float &v, int &i) {
+            const int w = sl / kSmallK, r = sl - w * kSmallK;
+            const bool have = r < k;
+            // (a wave stops at its first missing pick: the slots behind it hold nothing valid)
+            i = have ? wi[w][r] : INT_MAX;
+            v = have ? wv[w][r] : -INFINITY;
+        };
+        float v0, v1;
+        int i0, i1;
+        slot(lane, v0, i0);
+        slot(lane + 64, v1, i1);
+        // a wave's list ends at its first INT_MAX: mask what lies behind it
+        {
+            const int w0 = lane / kSmallK, r0 = lane - w0 * kSmallK;
+            for (int r = 0; r < r0; ++r) if (r < k && wi[w0][r] == INT_MAX) { i0 = INT_MAX; v0 = -INFINITY; }
+            const int w1 = (lane + 64) / kSmallK, r1 = (lane + 64) - w1 * kSmallK;
+            for (int r = 0; r < r1; ++r) if (r < k && wi[w1][r] == INT_MAX) { i1 = INT_MAX; v1 = -INFINITY; }
         }
-        __syncthreads();
-        if ((tid & 63) == 0) { sval[tid >> 6] = val; sidx[tid >> 6] = idx; }
-        __syncthreads();
-        val = sval[0];
-        idx = sidx[0];
-#pragma unroll
-        for (int w = 1; w < 16; ++w) take_better(val, idx, sval[w], sidx[w]);
-        // same layout of the partial results as k_argmax_stage1 (k == 1) and k_smallk_stage1 (k > 1)
-        const size_t at = k == 1 ? (size_t)c : (size_t)c * kSmallK + it;
-        if (tid == 0) { part_val[at] = val; part_idx[at] = idx; }
-        lv = val;
-        lidx = idx;
-        if (idx == INT_MAX) {   // uniform: no further candidate in this chunk
-            if (k > 1)
-                for (int r = it + 1 + tid; r < k; r += 1024) {
-                    part_val[(size_t)c * kSmallK + r] = -INFINITY;
-                    part_idx[(size_t)c * kSmallK + r] = INT_MAX;
-                }
-            break;
-        }
+        const int found = wave_topk(v0, i0, v1, i1, k, [&](int it, float val, int idx) {
+            // same layout of the partial results as k_argmax_stage1 (k == 1) and k_smallk_stage1 (k > 1)
+            const size_t at = k == 1 ? (size_t)c : (size_t)c * kSmallK + it;
+            if (lane == 0) { part_val[at] = val; part_idx[at] = idx; }
+        });
+        if (k > 1)
+            for (int r = found + 1 + lane; r < k; r += 64) {   // (slot `found` holds the end mark already)
+                part_val[(size_t)c * kSmallK + r] = -INFINITY;
+                part_idx[(size_t)c * kSmallK + r] = INT_MAX;
+            }
     }
 }
 
