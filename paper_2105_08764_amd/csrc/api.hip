@@ -184,7 +184,7 @@ BwdLayout bwd_layout(const HeadLayout &h, int64_t N, int p, int T, int S) {
     b.hub_part = c.take(sizeof(float) * (size_t)h.max_segs * S * p);
     b.hub_sum = c.take(sizeof(float) * (size_t)h.max_hubs * S * p);
     // the scalar form of the last reversed round keeps four sums per long row
-    const size_t four = (S % 16 == 0 && T >= 3) ? 4 : 0;
+    const size_t four = T >= 3 ? 4 : 0;
     b.hub_part4 = c.take(sizeof(float) * (size_t)h.max_segs * S * p * four);
     b.hub_sum4 = c.take(sizeof(float) * (size_t)h.max_hubs * S * p * four);
     b.end = c.off;
@@ -1070,9 +1070,9 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
             S2V_TRY(launch_zero_i32(st, (long)kBwdRoundRows * p * p, reinterpret_cast<int32_t *>(d2_part)));
             continue;
         }
-        if (t == 2 && !first && node) {
-            // node mode, T == 3: the last reversed round streams dz^2 and gathers scalars instead of rows
-            // (for T == 2 the round reads mask words, which is cheaper still)
+        if (t == 2 && !first) {
+            // (node mode: T == 3; row mode: any T >= 3) the last reversed round streams dz^2 and gathers
+            // scalars instead of rows (for T == 2 the round reads mask words, which is cheaper still)
             S2V_TRY(launch_qvec(st, p, params->theta3, params->theta4, qvec));
             S2V_TRY(launch_hub_sums_grad(st, p, S, ht, row_end_of(g), g->colidx, wagg, ninfo, pr->has_neg, params->theta1,
                                          qvec, hub_part4, hub_sum4));

@@ -784,7 +784,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 // ------------------------------------------------------------------------------------------
 // FLAGS: the four sums come from flag words and the rows' totals (gather_node_tile_flags_grad) instead of the
 // neighbours' records; they are then held per column (lane % P), not in the state-major layout.
-template <int P, bool W, bool NEG, bool FLAGS = false>
+template <int P, bool W, bool NEG, bool FLAGS = false, bool NODE = true>
 __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
     int n_vrows, int S, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ rowend,
     const int32_t *__restrict__ colidx, const float *__restrict__ wagg, const float *__restrict__ dz_in,
@@ -796,11 +796,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
     constexpr int TILE_F = kTileRows * STRIDE;
     static_assert(2 * kWaves * TILE_F >= kWaves * 16 * P, "tile area is reused for the final reductions");
     static_assert(!FLAGS || !NEG, "flag words: no negative weight");
-    __shared__ __attribute__((aligned(16))) float lds[2 * kWaves * TILE_F];   // per wave: dz^2 tile, a tile
+    static_assert(!FLAGS || NODE, "flag words: node mode");
+    constexpr int NT = NODE ? 2 : 3;
+    __shared__ __attribute__((aligned(16))) float lds[NT * kWaves * TILE_F];   // per wave: dz^2 tile, a tile (row mode: and the e tile)
     __shared__ __attribute__((aligned(16))) float lds_b[P * STRIDE];          // theta2^T: B operand of dz theta2
-    __shared__ __attribute__((aligned(16))) float rec_stage[FLAGS ? 4 : kWaves * kRecStageFloats];   // staging of the record gather
+    __shared__ __attribute__((aligned(16))) float rec_stage[(FLAGS || !NODE) ? 4 : kWaves * kRecStageFloats];   // staging of the record gather
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float *tile_d = lds + wave * 2 * TILE_F, *tile_a = tile_d + TILE_F;
+    float *tile_d = lds + wave * NT * TILE_F, *tile_a = tile_d + TILE_F;
     const int li = lane % LPR;
     const int jl = lane & 15, gl = lane >> 4;
 
@@ -813,10 +815,12 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
 #pragma unroll
         for (int jb = 0; jb < CB; ++jb) d2acc[ib][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float4 cx4 = make_float4(0.f, 0.f, 0.f, 0.f), cp4 = cx4, cn4 = cx4;
-    float fxj = 0.f, fpj = 0.f, t1j = 0.f, qpj = 0.f;   // FLAGS: sums and constants of column lane % P
-    if (FLAGS) {
+    // FLAGS and row mode: sums and constants of column lane % P
+    float fxj = 0.f, fpj = 0.f, fnj = 0.f, t1j = 0.f, qpj = 0.f, qnj = 0.f;
+    if (FLAGS || !NODE) {
         t1j = theta1[lane % P];
         qpj = qvec[lane % P];
+        qnj = qvec[P + lane % P];
     }
 
     const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
@@ -850,11 +854,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
             cp4.x += __shfl_xor(cp4.x, m); cp4.y += __shfl_xor(cp4.y, m); cp4.z += __shfl_xor(cp4.z, m); cp4.w += __shfl_xor(cp4.w, m);
             cn4.x += __shfl_xor(cn4.x, m); cn4.y += __shfl_xor(cn4.y, m); cn4.z += __shfl_xor(cn4.z, m); cn4.w += __shfl_xor(cn4.w, m);
         }
-        if (FLAGS) {
+        if (FLAGS || !NODE) {
             if (lane < P) {
                 lds[(wave * 3 + 0) * P + lane] = fxj;
                 lds[(wave * 3 + 1) * P + lane] = fpj;
-                lds[(wave * 3 + 2) * P + lane] = 0.f;
+                lds[(wave * 3 + 2) * P + lane] = fnj;
             }
         } else if (lane < LPR) {
             st4(lds + (wave * 3 + 0) * P + 4 * lane, cx4);
@@ -862,7 +866,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
             st4(lds + (wave * 3 + 2) * P + 4 * lane, cn4);
         }
         cx4 = cp4 = cn4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        fxj = fpj = 0.f;
+        fxj = fpj = fnj = 0.f;
         __syncthreads();
         for (int el = threadIdx.x; el < 3 * P; el += kThreads) {
             const float sum = (lds[el] + lds[3 * P + el]) + (lds[2 * 3 * P + el] + lds[3 * 3 * P + el]);
@@ -878,7 +882,71 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
         // (every wave of the workgroup makes the same number of iterations: the barriers inside are safe)
         if (it > 0 && it % kBwdFlushTiles == 0) flush(n_flushed == 0);
         const int r0 = t * kWgRows + wave * kTileRows;
-        if (r0 >= n_vrows) continue;        // S is a multiple of 16: tiles are whole
+        if (r0 >= n_vrows) continue;        // (node mode: S is a multiple of 16, tiles are whole)
+        if constexpr (!NODE) {
+            // ---- row mode: 16 consecutive rows (v, s) of the [N * S][p] matrices, any S ----
+            float *tile_e = tile_a + TILE_F;
+            const int r = r0 + jl;
+            const bool valid = r < n_vrows;
+            const int v = valid ? r / S : 0;
+            const int s = valid ? r - v * S : 0;
+            const int rb = valid ? rowptr[v] : 0, re = valid ? rowend[v] : 0;
+            // the tile's rows of dz^2 (rows past the end are zero)
+            for (int f = lane; f < kTileRows * LPR; f += 64) {
+                const int row = f / LPR, c4 = f - row * LPR;
+                const float4 d = r0 + row < n_vrows ? ld4(dz_in + (size_t)(r0 + row) * P + 4 * c4)
+                                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+                st4(tile_d + row * STRIDE + 4 * c4, d);
+            }
+            __builtin_amdgcn_wave_barrier();
+            {
+                // e = dz^2 theta2, kept as a tile: each row meets its gathered sums below
+                const Frag<P> afrag = load_a_frag_lds<P>(tile_d, lane);
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    acc = mfma_tile<P>(afrag, load_b_frag_lds<P>(lds_b, cb, lane), acc);
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) tile_e[(4 * gl + rr) * STRIDE + 16 * cb + jl] = acc[rr];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            // the long rows of the tile: their four sums are ready, [hub][4][S][P]
+            if (__builtin_amdgcn_ballot_w64(re - rb > kHubDegree) != 0ull) {
+#pragma unroll 1
+                for (int i = 0; i < kTileRows; ++i) {
+                    if (__builtin_amdgcn_readlane(re, i) - __builtin_amdgcn_readlane(rb, i) <= kHubDegree) continue;
+                    const int si = __builtin_amdgcn_readlane(s, i), vi = __builtin_amdgcn_readlane(v, i);
+                    const float *hb = hub_sum4 + ((size_t)hub_index(ht, vi) * 4 * S + si) * P + (lane % P);
+                    const float ev = tile_e[i * STRIDE + lane % P];
+                    if (lane < P) tile_a[i * STRIDE + lane] = hb[0];
+                    fxj = fmaf(ev, hb[(size_t)S * P], fxj);
+                    fpj = fmaf(ev, hb[2 * (size_t)S * P], fpj);
+                    if (NEG) fnj = fmaf(ev, hb[3 * (size_t)S * P], fnj);
+                }
+            }
+            gather_tile_mu1_grad_rows<P, W, NEG>(tile_a, tile_e, ni, s, t1j, qpj, qnj, colidx, wagg, rb, re, kHubDegree,
+                                                 lane, fxj, fpj, fnj);
+            __builtin_amdgcn_wave_barrier();
+            // dtheta2[i][j] += sum_r dz^2[r][i] a[r][j], as in node mode
+            float ya[CB][4];
+#pragma unroll
+            for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) ya[jb][ks] = tile_a[(4 * gl + ks) * STRIDE + 16 * jb + jl];
+#pragma unroll
+            for (int ib = 0; ib < CB; ++ib) {
+                float a2[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) a2[ks] = tile_d[(4 * gl + ks) * STRIDE + 16 * ib + jl];
+#pragma unroll
+                for (int jb = 0; jb < CB; ++jb)
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        d2acc[ib][jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[ks], ya[jb][ks], d2acc[ib][jb], 0, 0, 0);
+            }
+            __builtin_amdgcn_wave_barrier();
+        } else {
         const int v = r0 / S, s0 = r0 - v * S;
         const int b = rowptr[v], e = rowend[v];
 
@@ -971,6 +1039,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_bwd_first(
             }
         }
         __builtin_amdgcn_wave_barrier();
+        }
     }
 
     flush(n_flushed == 0);
@@ -993,9 +1062,20 @@ hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *
                                                                             d2_part, ht, hub_sum4);                   \
         else S2V_LAUNCH_FIRST(PP, WW, false);                                                                        \
     } while (0)
-#define S2V_LAUNCH_FIRST_W(PP) \
-    do { if (wagg) S2V_LAUNCH_FIRST_N(PP, true); else S2V_LAUNCH_FIRST_N(PP, false); } while (0)
+#define S2V_LAUNCH_FIRST_ROWS(PP, WW, NN)                                                                            \
+    k_bwd_first<PP, WW, NN, false, false><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, \
+                                                                         dz_in, ni, theta1, theta2, qvec, dc_part,      \
+                                                                         d2_part, ht, hub_sum4)
+#define S2V_LAUNCH_FIRST_W(PP)                                                                   \
+    do {                                                                                         \
+        if (S % 16 != 0) {                                                                       \
+            if (wagg) { if (has_neg) S2V_LAUNCH_FIRST_ROWS(PP, true, true); else S2V_LAUNCH_FIRST_ROWS(PP, true, false); } \
+            else { if (has_neg) S2V_LAUNCH_FIRST_ROWS(PP, false, true); else S2V_LAUNCH_FIRST_ROWS(PP, false, false); }    \
+        } else if (wagg) S2V_LAUNCH_FIRST_N(PP, true);                                           \
+        else S2V_LAUNCH_FIRST_N(PP, false);                                                      \
+    } while (0)
     if (p == 32) S2V_LAUNCH_FIRST_W(32); else S2V_LAUNCH_FIRST_W(64);
+#undef S2V_LAUNCH_FIRST_ROWS
 #undef S2V_LAUNCH_FIRST_W
 #undef S2V_LAUNCH_FIRST_N
 #undef S2V_LAUNCH_FIRST
@@ -1028,6 +1108,34 @@ __global__ __launch_bounds__(kThreads) void k_hub_partial_grad(int S, HubTable h
     }
 }
 
+// Row mode (S not a multiple of 16): one wave per (segment, state).
+template <int P, bool W, bool NEG>
+__global__ __launch_bounds__(kThreads) void k_hub_partial_grad_rows(int S, HubTable ht,
+                                                                    const int32_t *__restrict__ rowend,
+                                                                    const int32_t *__restrict__ colidx,
+                                                                    const float *__restrict__ wagg, NodeInfo ni,
+                                                                    const float *__restrict__ theta1,
+                                                                    const float *__restrict__ qvec,
+                                                                    float *__restrict__ partial) {
+    constexpr int LPR = Geo<P>::LPR;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane % LPR;
+    const float4 t1 = ld4(theta1 + 4 * li), qp = ld4(qvec + 4 * li), qn = ld4(qvec + P + 4 * li);
+    const long items = (long)ht.n_segs * S;
+    for (long item = (long)blockIdx.x * kWaves + wave; item < items; item += (long)gridDim.x * kWaves) {
+        const int seg = (int)(item / S), s = (int)(item - (long)seg * S);
+        const int b = ht.seg_begin[seg], e = min(ht.seg_end[seg], rowend[ht.seg_row[seg]]);
+        const RowAcc4 g = gather_row_mu1_grad<P, W, NEG>(ni, s, t1, qp, qn, colidx, wagg, b, e, 0, false, lane);
+        if (lane < LPR) {
+            float *out = partial + ((size_t)seg * 4 * S + s) * P + 4 * lane;
+            st4(out, g.a);
+            st4(out + (size_t)S * P, g.cx);
+            st4(out + 2 * (size_t)S * P, g.cp);
+            st4(out + 3 * (size_t)S * P, g.cn);   // zeros when the graph has no negative weight
+        }
+    }
+}
+
 hipError_t launch_hub_sums_grad(hipStream_t st, int p, int S, const HubTable &ht, const int32_t *rowend,
                                 const int32_t *colidx, const float *wagg, const NodeInfo &ni, bool has_neg,
                                 const float *theta1, const float *qvec, float *partial4, float *hub_sum4) {
@@ -1035,10 +1143,18 @@ hipError_t launch_hub_sums_grad(hipStream_t st, int p, int S, const HubTable &ht
     // (every long row a single segment: its sums are the row's sums, written in place; see launch_hub_sums)
     const bool single = ht.n_segs == ht.n_hubs;
     if (single) partial4 = hub_sum4;
-    const long items = (long)ht.n_segs * (S / 16);
+    const bool rows = S % 16 != 0;
+    const long items = rows ? (long)ht.n_segs * S : (long)ht.n_segs * (S / 16);
     const int grid = (int)min((items + kWaves - 1) / kWaves, (long)65536);
-#define S2V_LAUNCH_HG(PP, WW, NN) \
-    k_hub_partial_grad<PP, WW, NN><<<grid, kThreads, 0, st>>>(S, ht, rowend, colidx, wagg, ni, theta1, qvec, partial4)
+#define S2V_LAUNCH_HG(PP, WW, NN)                                                                                          \
+    do {                                                                                                                   \
+        if (rows)                                                                                                          \
+            k_hub_partial_grad_rows<PP, WW, NN><<<grid, kThreads, 0, st>>>(S, ht, rowend, colidx, wagg, ni, theta1, qvec,  \
+                                                                          partial4);                                      \
+        else                                                                                                               \
+            k_hub_partial_grad<PP, WW, NN><<<grid, kThreads, 0, st>>>(S, ht, rowend, colidx, wagg, ni, theta1, qvec,       \
+                                                                     partial4);                                           \
+    } while (0)
 #define S2V_LAUNCH_HG_N(PP, WW) \
     do { if (has_neg) S2V_LAUNCH_HG(PP, WW, true); else S2V_LAUNCH_HG(PP, WW, false); } while (0)
 #define S2V_LAUNCH_HG_W(PP) \

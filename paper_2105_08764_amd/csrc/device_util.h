@@ -930,6 +930,189 @@ __device__ __forceinline__ NodeAcc4<P> gather_node_block_mu1_grad(const NodeInfo
     return gather_node_block_mu1_grad_impl<P, W, false, NEG>(ni, s0, theta1, qvec, colidx, wagg, b, e, lane, stage);
 }
 
+// Row mode of the same (any S): the four sums of ONE row (v, s) over its stored entries [b, e), at this
+// lane's four columns (4 * li ..).  A group of LPR lanes takes one neighbour at a time, four neighbours per
+// group in flight; a wave-wide step whose neighbours all have x = 0 and s- = 0 only adds their s+ to a
+// scalar (their row is s+ relu(q+), their mask [q+ > 0]).  The sums are returned complete in every group.
+// cols: colidx[b + lane] of the first 64 entries when have_cols.  At most kHubSegment entries (the segments
+// of the long rows are summed with this).
+struct RowAcc4 {
+    float4 a, cx, cp, cn;
+};
+
+template <int P, bool W, bool NEG>
+__device__ __forceinline__ RowAcc4 gather_row_mu1_grad(const NodeInfo &ni, int s, float4 t1, float4 qp, float4 qn,
+                                                       const int *__restrict__ colidx,
+                                                       const float *__restrict__ wagg, int b, int e, int cols,
+                                                       bool have_cols, int lane) {
+    constexpr int NPL = Geo<P>::NPL, LPR = Geo<P>::LPR;
+    const int gq = lane / LPR;
+    RowAcc4 r;
+    r.a = make_float4(0.f, 0.f, 0.f, 0.f);
+    r.cx = r.a; r.cp = r.a; r.cn = r.a;
+    float ssum = 0.f;
+    for (int base = b; base < e; base += 64) {
+        const int cnt = min(64, e - base);
+        if (!(have_cols && base == b)) cols = (lane < cnt) ? colidx[base + lane] : 0;
+        float wv = 0.f;
+        if (W) wv = (lane < cnt) ? wagg[base + lane] : 0.f;
+        const int last = cnt - 1;
+        for (int s0 = 0; s0 < cnt; s0 += 4 * NPL) {
+            float x_[4], p_[4], n_[4], wk[4];
+            bool any = false;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                // slots past the end re-read the last neighbour with weight zero
+                const int sl = s0 + gq + k * NPL;
+                const int u = __shfl(cols, min(sl, last));
+                if (ni.S == 1) {
+                    const float4 rec = ld4(ni.base + (size_t)u * 4);
+                    x_[k] = rec.x; p_[k] = rec.y; n_[k] = NEG ? rec.z : 0.f;
+                } else {
+                    x_[k] = ni.x(u, s); p_[k] = ni.sp(u, s); n_[k] = NEG ? ni.sn(u, s) : 0.f;
+                }
+                const float wl = W ? __shfl(wv, min(sl, last)) : 1.f;
+                wk[k] = sl < cnt ? wl : 0.f;
+                any = any || (sl < cnt && (x_[k] != 0.f || n_[k] != 0.f));
+            }
+            if (__ballot(any) == 0ull) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) ssum = fmaf(wk[k], p_[k], ssum);
+                continue;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float w = wk[k];
+                // the forward pass's own function, so that the relu decisions agree
+                const float zx = mu1_z(x_[k], p_[k], n_[k], t1.x, qp.x, qn.x), zy = mu1_z(x_[k], p_[k], n_[k], t1.y, qp.y, qn.y);
+                const float zz = mu1_z(x_[k], p_[k], n_[k], t1.z, qp.z, qn.z), zw = mu1_z(x_[k], p_[k], n_[k], t1.w, qp.w, qn.w);
+                r.a.x = fmaf(w, fmaxf(zx, 0.f), r.a.x); r.a.y = fmaf(w, fmaxf(zy, 0.f), r.a.y);
+                r.a.z = fmaf(w, fmaxf(zz, 0.f), r.a.z); r.a.w = fmaf(w, fmaxf(zw, 0.f), r.a.w);
+                const float fx = zx > 0.f ? w : 0.f, fy = zy > 0.f ? w : 0.f;
+                const float fz = zz > 0.f ? w : 0.f, fw = zw > 0.f ? w : 0.f;
+                r.cx.x = fmaf(fx, x_[k], r.cx.x); r.cx.y = fmaf(fy, x_[k], r.cx.y);
+                r.cx.z = fmaf(fz, x_[k], r.cx.z); r.cx.w = fmaf(fw, x_[k], r.cx.w);
+                r.cp.x = fmaf(fx, p_[k], r.cp.x); r.cp.y = fmaf(fy, p_[k], r.cp.y);
+                r.cp.z = fmaf(fz, p_[k], r.cp.z); r.cp.w = fmaf(fw, p_[k], r.cp.w);
+                if (NEG) {
+                    r.cn.x = fmaf(fx, n_[k], r.cn.x); r.cn.y = fmaf(fy, n_[k], r.cn.y);
+                    r.cn.z = fmaf(fz, n_[k], r.cn.z); r.cn.w = fmaf(fw, n_[k], r.cn.w);
+                }
+            }
+        }
+    }
+    // the neighbours that were summed as scalars: z = s+ q+ in every column
+    r.a.x = fmaf(ssum, fmaxf(qp.x, 0.f), r.a.x); r.a.y = fmaf(ssum, fmaxf(qp.y, 0.f), r.a.y);
+    r.a.z = fmaf(ssum, fmaxf(qp.z, 0.f), r.a.z); r.a.w = fmaf(ssum, fmaxf(qp.w, 0.f), r.a.w);
+    r.cp.x += qp.x > 0.f ? ssum : 0.f; r.cp.y += qp.y > 0.f ? ssum : 0.f;
+    r.cp.z += qp.z > 0.f ? ssum : 0.f; r.cp.w += qp.w > 0.f ? ssum : 0.f;
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) {
+        r.a.x += __shfl_xor(r.a.x, m); r.a.y += __shfl_xor(r.a.y, m);
+        r.a.z += __shfl_xor(r.a.z, m); r.a.w += __shfl_xor(r.a.w, m);
+        r.cx.x += __shfl_xor(r.cx.x, m); r.cx.y += __shfl_xor(r.cx.y, m);
+        r.cx.z += __shfl_xor(r.cx.z, m); r.cx.w += __shfl_xor(r.cx.w, m);
+        r.cp.x += __shfl_xor(r.cp.x, m); r.cp.y += __shfl_xor(r.cp.y, m);
+        r.cp.z += __shfl_xor(r.cp.z, m); r.cp.w += __shfl_xor(r.cp.w, m);
+        if (NEG) {
+            r.cn.x += __shfl_xor(r.cn.x, m); r.cn.y += __shfl_xor(r.cn.y, m);
+            r.cn.z += __shfl_xor(r.cn.z, m); r.cn.w += __shfl_xor(r.cn.w, m);
+        }
+    }
+    return r;
+}
+
+// The same sums for the 16 rows (v_i, s_i) of a row-mode tile at once, one LANE per stored entry: the column
+// indices of eight rows are requested together, then the records of all their neighbours, so a tile costs a
+// few trips to memory instead of two per row.  Neighbours with x = 0 and s- = 0 add their s+ to a scalar of
+// their row; the others are visited one at a time with lane j forming column j = lane % P.  Row i's sum `a`
+// goes to tile_a[i]; its cx, cp, cn meet row i of tile_e (e = dz^2 theta2) right away:
+//   fx += e[i][j] cx_i[j],  fp += e[i][j] cp_i[j],  fn += e[i][j] cn_i[j].
+// rb, re, s: lane i (mod 16) holds the range and the state of tile row i; rows longer than max_len are left
+// to the caller.  t1, qp, qn: theta1, q+, q- at column j.
+template <int P, bool W, bool NEG>
+__device__ __forceinline__ void gather_tile_mu1_grad_rows(float *tile_a, const float *tile_e, const NodeInfo &ni,
+                                                          int s, float t1, float qp, float qn,
+                                                          const int *__restrict__ colidx,
+                                                          const float *__restrict__ wagg, int rb, int re, int max_len,
+                                                          int lane, float &fx, float &fp, float &fn) {
+    constexpr int STRIDE = Geo<P>::STRIDE;
+    const int j = lane % P;
+    const float rp = fmaxf(qp, 0.f), mq = qp > 0.f ? 1.f : 0.f;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        float ssum[8], a[8], cx[8], cp[8], cn[NEG ? 8 : 1];
+        int nlev = 0;   // chunk levels of the longest row of this half that is gathered here (wave-uniform)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            ssum[k] = 0.f; a[k] = 0.f; cx[k] = 0.f; cp[k] = 0.f; cn[NEG ? k : 0] = 0.f;
+            const int n = __builtin_amdgcn_readlane(re, 8 * half + k) - __builtin_amdgcn_readlane(rb, 8 * half + k);
+            if (n <= max_len) nlev = max(nlev, (n + 63) >> 6);
+        }
+#pragma unroll 1
+        for (int lev = 0; lev < nlev; ++lev) {
+            int cols[8];
+            float wl[W ? 8 : 1];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int b = __builtin_amdgcn_readlane(rb, 8 * half + k), n = __builtin_amdgcn_readlane(re, 8 * half + k) - b;
+                const int i = 64 * lev + lane;
+                const bool ok = n <= max_len && i < n;
+                cols[k] = ok ? colidx[b + i] : -1;
+                if (W) wl[W ? k : 0] = ok ? wagg[b + i] : 0.f;
+            }
+            float rx[8], rs[8], rn[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int sk = __builtin_amdgcn_readlane(s, 8 * half + k);
+                rx[k] = 0.f; rs[k] = 0.f; rn[k] = 0.f;
+                if (cols[k] >= 0) {
+                    if (ni.S == 1) {
+                        const float4 r = ld4(ni.base + (size_t)cols[k] * 4);
+                        rx[k] = r.x; rs[k] = r.y; rn[k] = NEG ? r.z : 0.f;
+                    } else {
+                        rx[k] = ni.x(cols[k], sk); rs[k] = ni.sp(cols[k], sk);
+                        rn[k] = NEG ? ni.sn(cols[k], sk) : 0.f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool cheap = rx[k] == 0.f && rn[k] == 0.f;
+                ssum[k] += cheap ? (W ? wl[W ? k : 0] * rs[k] : rs[k]) : 0.f;
+                unsigned long long todo = __ballot(!cheap);
+                while (todo != 0ull) {
+                    const int l = __ffsll((long long)todo) - 1;
+                    todo &= todo - 1ull;
+                    const float xl = readlane_f(rx[k], l), pl = readlane_f(rs[k], l);
+                    const float nl = NEG ? readlane_f(rn[k], l) : 0.f;
+                    const float w = W ? readlane_f(wl[W ? k : 0], l) : 1.f;
+                    // the forward pass's own function, so that the relu decisions agree
+                    const float z = NEG ? mu1_z(xl, pl, nl, t1, qp, qn) : mu1_z(xl, pl, t1, qp);
+                    const float m = z > 0.f ? w : 0.f;
+                    a[k] = fmaf(w, fmaxf(z, 0.f), a[k]);
+                    cx[k] = fmaf(m, xl, cx[k]);
+                    cp[k] = fmaf(m, pl, cp[k]);
+                    if (NEG) cn[k] = fmaf(m, nl, cn[k]);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = 8 * half + k;
+            if (__builtin_amdgcn_readlane(re, i) - __builtin_amdgcn_readlane(rb, i) > max_len) continue;   // wave-uniform
+            float sv = ssum[k];
+#pragma unroll
+            for (int m = 1; m < 64; m <<= 1) sv += __shfl_xor(sv, m);
+            const float ev = tile_e[i * STRIDE + j];
+            if (lane < P) tile_a[i * STRIDE + lane] = fmaf(sv, rp, a[k]);
+            fx = fmaf(ev, cx[k], fx);
+            fp = fmaf(ev, fmaf(sv, mq, cp[k]), fp);
+            if (NEG) fn = fmaf(ev, cn[NEG ? k : 0], fn);
+        }
+    }
+}
+
 // Weighted form of gather_node_block_bits: per column, the sum of the weights of the neighbours whose
 // entry is positive (per-chunk accumulators folded into a running total, as in the other gathers).
 template <int P>
