@@ -468,6 +468,75 @@ __device__ __forceinline__ void gather_tile_mu1_levels(float *tile, const float 
     }
 }
 
+// The same for any S (row mode of round 2 with several states): tile row i is (node v_i, state s_i), and the
+// record of neighbour u for that row is {x_u[s_i], s+_u, s-_u} of the general layout.  rb, re, s: lane i
+// (mod 16) holds the range and the state of tile row i.  W: every neighbour's row times the weight of its entry.
+template <int P, bool W>
+__device__ __forceinline__ void gather_tile_mu1_rows(float *tile, const NodeInfo &ni, int s, const float *lc,
+                                                     const int *__restrict__ colidx, const float *__restrict__ wagg,
+                                                     int rb, int re, int max_len, int lane) {
+    constexpr int STRIDE = Geo<P>::STRIDE;
+    const int j = lane % P;
+    const float t1 = lc[j], qp = lc[P + j], qn = lc[2 * P + j];
+    const float rp = fmaxf(qp, 0.f);
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        float ssum[8], acc[8];
+        int nlev = 0;   // chunk levels of the longest row of this half that is gathered here (wave-uniform)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            ssum[k] = 0.f; acc[k] = 0.f;
+            const int n = __builtin_amdgcn_readlane(re, 8 * half + k) - __builtin_amdgcn_readlane(rb, 8 * half + k);
+            if (n <= max_len) nlev = max(nlev, (n + 63) >> 6);
+        }
+#pragma unroll 1
+        for (int lev = 0; lev < nlev; ++lev) {
+            int cols[8];
+            float wl[W ? 8 : 1];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int b = __builtin_amdgcn_readlane(rb, 8 * half + k), n = __builtin_amdgcn_readlane(re, 8 * half + k) - b;
+                const int i = 64 * lev + lane;
+                const bool ok = n <= max_len && i < n;
+                cols[k] = ok ? colidx[b + i] : -1;
+                if (W) wl[W ? k : 0] = ok ? wagg[b + i] : 0.f;
+            }
+            float rx[8], rs[8], rn[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int sk = __builtin_amdgcn_readlane(s, 8 * half + k);
+                rx[k] = 0.f; rs[k] = 0.f; rn[k] = 0.f;
+                if (cols[k] >= 0) {
+                    const float3 r = ni.get(cols[k], sk);
+                    rx[k] = r.x; rs[k] = r.y; rn[k] = r.z;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool cheap = rx[k] == 0.f && rn[k] == 0.f;
+                ssum[k] += cheap ? (W ? wl[W ? k : 0] * rs[k] : rs[k]) : 0.f;
+                unsigned long long todo = __ballot(!cheap);
+                while (todo != 0ull) {
+                    const int l = __ffsll((long long)todo) - 1;
+                    todo &= todo - 1ull;
+                    const float xl = readlane_f(rx[k], l), pl = readlane_f(rs[k], l), nl = readlane_f(rn[k], l);
+                    const float z = fmaxf(mu1_z(xl, pl, nl, t1, qp, qn), 0.f);
+                    acc[k] = W ? fmaf(readlane_f(wl[W ? k : 0], l), z, acc[k]) : acc[k] + z;
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = 8 * half + k;
+            if (__builtin_amdgcn_readlane(re, i) - __builtin_amdgcn_readlane(rb, i) > max_len) continue;   // wave-uniform
+            float sv = ssum[k];
+#pragma unroll
+            for (int m = 1; m < 64; m <<= 1) sv += __shfl_xor(sv, m);
+            if (lane < P) tile[i * STRIDE + lane] = fmaf(sv, rp, acc[k]);
+        }
+    }
+}
+
 // Node mode (S a multiple of 16): the 16 rows of a wave tile are 16 consecutive states
 // s0 .. s0+15 of ONE node v, so every neighbour u contributes one contiguous block of 16 * P
 // floats, mu[u][s0 .. s0+15][:].  A wave-wide float4 load covers RPI = 64 / LPR of those rows

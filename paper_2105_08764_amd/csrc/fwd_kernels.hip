@@ -587,6 +587,9 @@ __global__ __launch_bounds__(kThreads, MU1 ? ((NODE && VAR != kRoundFlags) ? 3 :
                     gather_tile_mu1_levels<P, 1>(tile, info.base, info.compact, lds_c, colidx, rb, re, kHubDegree, lane);
                 else
                     gather_tile_mu1_levels<P, 0>(tile, info.base, nullptr, lds_c, colidx, rb, re, kHubDegree, lane);
+            } else if (MU1 && S > 1) {
+                // several states, round 2: the same with the general records
+                gather_tile_mu1_rows<P, W>(tile, info, s, lds_c, colidx, wagg, rb, re, kHubDegree, lane);
             } else {
             int b_next = __builtin_amdgcn_readlane(rb, 0), e_next = __builtin_amdgcn_readlane(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
