@@ -139,6 +139,23 @@ def test_training_config5_scaled(oracle_mod):
     assert compared >= 1
 
 
+@pytest.mark.parametrize("S", [8, 24])
+def test_row_mode_minibatch_on_a_scale_free_graph(oracle_mod, S):
+    # Minibatch sizes that are not a multiple of 16 on configuration 5's kind of graph (long rows of several
+    # segments among them): every round in row mode, the last reversed round from the neighbours' scalars.
+    w = si.config(5, 0.03)
+    g = w.graph
+    x = si.node_flags(g.n, 0.05, 2005, n_states=S)
+    action, target = si.training_batch(x, 5005)
+    assert int(np.diff(g.rowptr).max()) > 1024
+    print(f"row-mode minibatch: n={g.n} nnz={g.nnz} S={S} longest row {int(np.diff(g.rowptr).max())}", flush=True)
+    dev = gu.Device(g, w.p, w.T, S=S, training=True)
+    loss, qp, grads = dev.train_iter(dev.params(w.theta), x, action, target)
+    oloss, oqp, ograds = oracle_mod.loss_grad(g.rowptr, g.colidx, g.w, None, w.theta, x, w.T, action, target)
+    assert gu.rel_err(qp, oqp) <= TOL and abs(loss - oloss) <= TOL * abs(oloss)
+    _check_grads(grads, ograds)
+
+
 def test_adam_steps_match_oracle(oracle_mod):
     import torch
 
