@@ -325,7 +325,23 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
     const int jl = lane & 15, gl = lane >> 4;
 
     stage_matrix_lds<P>(lds_b, theta2, true);
+    // MASK: the per-state constants (dg and the node range of the action's graph) of up to kMaskStatesLds states
+    // live in LDS: a load from memory inside the tile loop would have to wait for the prefetches issued before it
+    constexpr int kMaskStatesLds = 32;
+    __shared__ __attribute__((aligned(16))) float s_dg[MASK ? kMaskStatesLds * P : 4];
+    __shared__ int s_glo[MASK ? kMaskStatesLds : 1], s_ghi[MASK ? kMaskStatesLds : 1];
+    const bool dg_lds = MASK && S <= kMaskStatesLds;
+    if (dg_lds) {
+        for (int i = threadIdx.x; i < S * P; i += kThreads) s_dg[MASK ? i : 0] = dg[i];
+        for (int i = threadIdx.x; i < S; i += kThreads) { s_glo[MASK ? i : 0] = glo[i]; s_ghi[MASK ? i : 0] = ghi[i]; }
+    }
     __syncthreads();
+    auto in_range = [&](int node, int st) {
+        return dg_lds ? (node >= s_glo[MASK ? st : 0] && node < s_ghi[MASK ? st : 0]) : (node >= glo[st] && node < ghi[st]);
+    };
+    auto dg_at = [&](int st, int col) {
+        return dg_lds ? ld4(s_dg + (MASK ? st * P + col : 0)) : ld4(dg + (size_t)st * P + col);
+    };
 
     f32x4 d2acc[CB][CB];
 #pragma unroll
@@ -364,6 +380,40 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
     // The mask round does little per tile besides its two matrix products: there the next tile's mu^{t-1}
     // (4 KB, needed first thing) is fetched a tile ahead as well.
     constexpr bool PFM = NODE && MASK;
+    // ... and so are the mask words of the next tile's first 32 neighbours, which takes the row ranges three
+    // tiles and the column indices two tiles ahead: tile t (pf_*, pw), t + G (q1_*), t + 2G (q2_*).
+    constexpr bool PFW = PFM && !W;
+    int q1_b = 0, q1_e = 0, q1_cols = 0, q2_b = 0, q2_e = 0;
+    unsigned long long pw[PFW ? 8 : 1];
+    auto tile_range = [&](int tile, int &b, int &e) {
+        const int r0x = tile * kWgRows + wave * kTileRows;
+        b = 0;
+        e = 0;
+        if (tile < n_tiles && r0x < n_vrows) {
+            const int vx = r0x / S;
+            b = rowptr[vx];
+            e = rowend[vx];
+        }
+    };
+    auto tile_words = [&](int tile, int b, int e, int cols, unsigned long long *w) {
+        // in the load layout of gather_node_block_bits: lane = (neighbour slot lane / 16, state lane % 16)
+        const int r0x = tile * kWgRows + wave * kTileRows;
+        const bool ok = tile < n_tiles && r0x < n_vrows && e > b && e - b <= kHubDegree;   // wave-uniform
+        const int s0x = ok ? r0x - (r0x / S) * S : 0;
+        const int m = min(32, e - b);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int u = __shfl(cols, max(0, min(4 * k + (lane >> 4), m - 1)));
+            w[k] = ok ? maskT[(size_t)u * S + s0x + (lane & 15)] : 0ull;
+        }
+    };
+    if (PFW) {
+        const int G = (int)gridDim.x;
+        tile_range((int)blockIdx.x + G, q1_b, q1_e);
+        tile_range((int)blockIdx.x + 2 * G, q2_b, q2_e);
+        q1_cols = (lane < min(64, q1_e - q1_b)) ? colidx[q1_b + lane] : 0;
+        tile_words((int)blockIdx.x, pf_b, pf_e, pf_cols, pw);
+    }
     float mpn[PFM ? CB : 1][4];
     if (PFM) {
         const int r0 = blockIdx.x * kWgRows + wave * kTileRows;
@@ -467,7 +517,19 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
         const int cols_first = pf_cols;
         int nx_b = 0, nx_e = 0;
         bool nx_ok = false;
-        if (NODE) {
+        unsigned long long nw[PFW ? 8 : 1];
+        int q2_cols = 0, q3_b = 0, q3_e = 0;
+        if (PFW) {
+            // everything the tiles behind this one need next, issued before this tile's work
+            const int G = (int)gridDim.x;
+            const int r0n = (t + G) * kWgRows + wave * kTileRows;
+            nx_ok = t + G < n_tiles && r0n < n_vrows;
+            nx_b = q1_b;
+            nx_e = q1_e;
+            tile_words(t + G, q1_b, q1_e, q1_cols, nw);
+            q2_cols = (lane < min(64, q2_e - q2_b)) ? colidx[q2_b + lane] : 0;
+            tile_range(t + 3 * G, q3_b, q3_e);
+        } else if (NODE) {
             const int tn = t + gridDim.x, r0n = tn * kWgRows + wave * kTileRows;
             nx_ok = tn < n_tiles && r0n < n_vrows;
             if (nx_ok) {
@@ -479,7 +541,7 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
         const float3 mine = valid ? ni.get(v, s) : make_float3(0.f, 0.f, 0.f);
         const float xs = mine.x, sp = mine.y, sn = mine.z;
         // MASK: rows outside the action's graph receive nothing from the broadcast part of dz^T
-        const bool in_graph = MASK ? (valid && v >= glo[s] && v < ghi[s]) : true;
+        const bool in_graph = MASK ? (valid && in_range(v, s)) : true;
 
         // mu^{t-1} in the layout of the matrix-core result (row 4*gl + k, column 16*cb + jl): it is the
         // relu mask of this tile's output AND the B operand of the dtheta2 update.  Rows past the end: 0.
@@ -515,14 +577,22 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
                 ga = W ? gather_node_block_bits_w<P>(maskT, S, s0, colidx, wagg, b, e, lane)
                        : gather_node_block_bits<P>(maskT, S, s0, colidx, b, e, lane,
                                                    bits_stage + (NODE && MASK ? wave * (kBitsStageBytes / 4) : 0),
-                                                   cols_first, true);
+                                                   cols_first, true, PFW ? pw : nullptr);
             } else {
                 ga = gather_node_block<P, W>(dz_in, row_stride, (size_t)s0 * P, colidx, wagg, b, e, lane);
             }
-            // the next tile's first column indices (its row range has arrived by now)
-            pf_cols = (nx_ok && lane < min(64, nx_e - nx_b)) ? colidx[nx_b + lane] : 0;
-            pf_b = nx_b;
-            pf_e = nx_e;
+            if (PFW) {
+                pf_b = q1_b; pf_e = q1_e; pf_cols = q1_cols;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) pw[PFW ? k : 0] = nw[PFW ? k : 0];
+                q1_b = q2_b; q1_e = q2_e; q1_cols = q2_cols;
+                q2_b = q3_b; q2_e = q3_e;
+            } else {
+                // the next tile's first column indices (its row range has arrived by now)
+                pf_cols = (nx_ok && lane < min(64, nx_e - nx_b)) ? colidx[nx_b + lane] : 0;
+                pf_b = nx_b;
+                pf_e = nx_e;
+            }
             if (MASK) {
                 // counts -> G: times dg of this lane's state and columns (the node is wave-uniform)
                 constexpr int RPI = Ge::NPL, NC = 16 / RPI;
@@ -530,8 +600,8 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
                     const int sl = s0 + c * RPI + lane / Ge::LPR;      // this lane's state for block c
-                    const bool ing = vn >= glo[sl] && vn < ghi[sl];
-                    const float4 d = ld4(dg + (size_t)sl * P + 4 * li);
+                    const bool ing = in_range(vn, sl);
+                    const float4 d = dg_at(sl, 4 * li);
                     ga.a[c].x = ing ? ga.a[c].x * d.x : 0.f;
                     ga.a[c].y = ing ? ga.a[c].y * d.y : 0.f;
                     ga.a[c].z = ing ? ga.a[c].z * d.z : 0.f;
@@ -565,7 +635,7 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
                 }
                 if (MASK) {
                     const bool ing = __builtin_amdgcn_readlane((int)in_graph, i) != 0;
-                    const float4 d = ld4(dg + (size_t)si * P + 4 * li);
+                    const float4 d = dg_at(si, 4 * li);
                     a.x = ing ? a.x * d.x : 0.f;
                     a.y = ing ? a.y * d.y : 0.f;
                     a.z = ing ? a.z * d.z : 0.f;

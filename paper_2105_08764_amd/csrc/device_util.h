@@ -1237,7 +1237,8 @@ constexpr int kBitsStageBytes = 32 * 16 * 8;
 template <int P>
 __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long long *__restrict__ mask, int S, int s0,
                                                              const int *__restrict__ colidx, int b, int e, int lane,
-                                                             unsigned *stage, int cols0 = 0, bool have_cols0 = false) {
+                                                             unsigned *stage, int cols0 = 0, bool have_cols0 = false,
+                                                             const unsigned long long *words0 = nullptr) {
     constexpr int RPI = Geo<P>::NPL, NC = 16 / RPI, LPR = Geo<P>::LPR;
     int4 cnt[NC];
 #pragma unroll
@@ -1253,10 +1254,16 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long
         for (int j0 = 0; j0 < n; j0 += 32) {
             const int m = min(32, n - j0);       // neighbours in this batch
             unsigned long long wv[8];
+            if (words0 && base == b && j0 == 0) {
+                // words0: this first batch, fetched by the caller ahead of time in this very layout
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int jj = j0 + min(4 * k + q, m - 1);   // past the end: a valid word again, never counted
-                wv[k] = mask[(size_t)__shfl(cols, jj) * S + s0 + st];
+                for (int k = 0; k < 8; ++k) wv[k] = words0[k];
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int jj = j0 + min(4 * k + q, m - 1);   // past the end: a valid word again, never counted
+                    wv[k] = mask[(size_t)__shfl(cols, jj) * S + s0 + st];
+                }
             }
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
@@ -1268,13 +1275,23 @@ __device__ __forceinline__ NodeAcc<P> gather_node_block_bits(const unsigned long
             unsigned packed[NC];
 #pragma unroll
             for (int c = 0; c < NC; ++c) packed[c] = 0u;
-            for (int i = 0; i < m; ++i) {
+            // (four neighbours per step, their LDS reads in flight together; the staging area holds 32 slots,
+            //  and a slot past the last neighbour is read but not counted)
+            for (int i = 0; i < m; i += 4) {
+                unsigned w32[4][NC];
 #pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    const unsigned w32 = stage[((i * 16) + c * RPI + srow) * 2 + half];
-                    const unsigned nib = (w32 >> sh) & 0xFu;
-                    // bit t of the nibble -> bit 8 * t
-                    packed[c] += __umul24(nib, 0x00204081u) & 0x01010101u;
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) w32[k][c] = stage[(((i + k) * 16) + c * RPI + srow) * 2 + half];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const unsigned live = i + k < m ? 0xFu : 0u;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const unsigned nib = (w32[k][c] >> sh) & live;
+                        // bit t of the nibble -> bit 8 * t
+                        packed[c] += __umul24(nib, 0x00204081u) & 0x01010101u;
+                    }
                 }
             }
             __builtin_amdgcn_wave_barrier();
