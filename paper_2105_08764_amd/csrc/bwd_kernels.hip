@@ -170,11 +170,25 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
     // All lanes of a wave run the same number of iterations (the shuffles below need that); four
     // rows per thread and step keep four independent loads in flight.
     constexpr int U = 4;
+    // (node, state) of this thread's current row, advanced by SLOTS rows at a time without a division
+    const int step_v = SLOTS / S, step_s = SLOTS - step_v * S;
+    int v_cur = (int)((r_begin + slot) / S), s_cur = (int)((r_begin + slot) - (long)v_cur * S);
     for (long rbase = r_begin; rbase < r_end; rbase += U * SLOTS) {
         float4 mu[U];
+        int vk[U], sk[U];
+        float3 rec[U];
+        float xres[U];
 #pragma unroll
         for (int k = 0; k < U; ++k) {
             const long r = rbase + k * SLOTS + slot;
+            vk[k] = v_cur;
+            sk[k] = s_cur;
+            v_cur += step_v;
+            s_cur += step_s;
+            if (s_cur >= S) { s_cur -= S; ++v_cur; }
+            // the row's scalars are requested together with its data: one trip to memory per step
+            rec[k] = r < r_end ? ni.get(vk[k], sk[k]) : make_float3(0.f, 0.f, 0.f);
+            xres[k] = (x_res && r < r_end) ? x_res[(size_t)sk[k] * N + vk[k]] : 0.f;
             if (WORDS) {
                 // only the signs matter below: 1 where the bit is set
                 const unsigned nib = r < r_end ? (unsigned)(mask[r] >> (4 * c4)) & 15u : 0u;
@@ -189,8 +203,8 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
             const long r = rbase + k * SLOTS + slot;
             const bool valid = r < r_end;
             unsigned long long word = 0ull;
+            const int v = vk[k], s = sk[k];
             if (valid) {
-                const int v = (int)r / S, s = (int)r - v * S;   // n_vrows < 2^31: 32-bit division
                 float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (cached) {
                     if (v >= s_glo[s] && v < s_ghi[s]) d = ld4(&s_dg[s][4 * c4]);
@@ -206,13 +220,13 @@ __global__ __launch_bounds__(256) void k_bwd_maskT(long n_vrows, int N, int S, c
                 const unsigned nib = (mu[k].x > 0.f ? 1u : 0u) | (mu[k].y > 0.f ? 2u : 0u) |
                                      (mu[k].z > 0.f ? 4u : 0u) | (mu[k].w > 0.f ? 8u : 0u);
                 word = (unsigned long long)nib << (4 * c4);
-                const float3 q = ni.get(v, s);
+                const float3 q = rec[k];
                 float xs = q.x;
                 const float sp = q.y, sn = q.z;
                 if (x_res) {
                     // per-state residual graphs: a solution node is isolated; it still feeds dtheta1 through
                     // the graph sum, but its mask word is zero so that no neighbour gathers from it
-                    const float xo = x_res[(size_t)s * N + v];
+                    const float xo = xres[k];
                     if (xo != 0.f) { xs = xo; word = 0ull; }
                 }
                 ax.x += xs * d.x; ax.y += xs * d.y; ax.z += xs * d.z; ax.w += xs * d.w;
