@@ -361,7 +361,7 @@ def bench_training(args, s2v, torch):
     # Algorithmic bytes per launch of the five large kernels of an iteration (what each must move when no gathered
     # row is reused); the counter column is FETCH_SIZE + WRITE_SIZE from the committed rocprofv3 summary.
     kernels = [
-        ("fwd_round2", "k_round<64, true, true, false, false, false, 0>",
+        ("fwd_round2", "k_round<64, true, true, false, false, false, 3>",
          "round 2 from flag words and the rows' totals: writes mu^2", idx_b + 2 * nnz * (S // 16) + 12 * N + mat),
         ("fwd_round", "k_round<64, false, false, false, false, false, 2>",
          "round 3, rows walked state by state: gathers mu^2, writes mu^3", S * idx_b + gather + 12 * N * S + mat),
