@@ -850,7 +850,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 }
 
 // ------------------------------------------------------------------------------------------
-// The last reversed round (t = 2) in node mode, taken from the scalars instead of gathering dz^2.
+// The last reversed round (t = 2), taken from the scalars instead of gathering dz^2.
 // What the round must deliver is only sums over the nodes (dz^1 is never needed as a matrix):
 //   dtheta2[i][j] += sum_u G_u[i] mu^1_u[j],   sum_u x_u dz^1_u,  sum_u s+-_u dz^1_u,
 //   with G = A dz^2 and dz^1_u = (theta2^T G_u) (.) [mu^1_u > 0].
@@ -863,8 +863,11 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
 // gather_node_block_mu1_grad) where the generic round gathers 4 KB rows of dz^2 and reads mu^1.
 // Used for T >= 3 only: when t = 2 is also the first reversed round (T = 2), dz^2 = dz^T is not in
 // memory and the mask-word round is cheaper than recomputing masks from the scalars.
-// A wave owns one node's 16-state block at a time; hub_sum4 holds the four sums of the long rows
-// as [hub][4][S][P].
+// NODE (S a multiple of 16): a wave owns one node's 16-state block at a time.  Otherwise (row mode, any S) a
+// tile is 16 consecutive rows (node, state): e = dz^2 theta2 is formed first and kept as a tile, then
+// gather_tile_mu1_grad_rows walks the sixteen rows' entries (one lane per stored entry) and each row's cx, cp,
+// cn meet its row of e at once; the sums are held per column (lane % P).  hub_sum4 holds the four sums of
+// the long rows as [hub][4][S][P] in both modes.
 // ------------------------------------------------------------------------------------------
 // FLAGS: the four sums come from flag words and the rows' totals (gather_node_tile_flags_grad) instead of the
 // neighbours' records; they are then held per column (lane % P), not in the state-major layout.
