@@ -28,7 +28,7 @@
  *   - Work is enqueued on the HIP stream given to s2v_create and the call returns
  *     without waiting for it (s2v_graph_prepare is the exception: it waits).  Scalar
  *     results (loss, counts) are written to device memory.  Apart from s2v_graph_prepare,
- *     s2v_workspace_bytes and s2v_mvc_inference (which read device memory back) the calls
+ *     s2v_workspace_bytes, s2v_mvc_inference and s2v_profile_end (which wait for the stream) the calls
  *     only enqueue kernels and device-to-device copies, so they may be recorded under HIP
  *     stream capture and replayed.
  *   - Every call returns an int32 status: S2V_OK or a negative S2V_ERR_* code.  Nothing
