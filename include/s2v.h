@@ -26,11 +26,10 @@
  *     memory.  The library allocates no device memory: scratch space comes from the
  *     caller's workspace `ws`, sized by s2v_workspace_bytes.
  *   - Work is enqueued on the HIP stream given to s2v_create and the call returns
- *     without waiting for it (s2v_graph_prepare is the exception: it waits).  Scalar
- *     results (loss, counts) are written to device memory.  Apart from s2v_graph_prepare,
- *     s2v_workspace_bytes, s2v_mvc_inference and s2v_profile_end (which wait for the stream) the calls
- *     only enqueue kernels and device-to-device copies, so they may be recorded under HIP
- *     stream capture and replayed.
+ *     without waiting for it; scalar results (loss, counts) are written to device memory.
+ *     Four calls do wait for the stream: s2v_graph_prepare, s2v_workspace_bytes,
+ *     s2v_mvc_inference and s2v_profile_end.  All others only enqueue kernels and
+ *     device-to-device copies, so they may be recorded under HIP stream capture and replayed.
  *   - Every call returns an int32 status: S2V_OK or a negative S2V_ERR_* code.  Nothing
  *     throws, prints or exits.  A call that returns an error has enqueued nothing.
  *   - Layouts: x is [S][N]; embeddings are [N][S][p] (S states of one graph batch;
