@@ -118,10 +118,11 @@ int32_t s2v_last_hip_error(const s2v_ctx *ctx);
 
 /*
  * Tuning knob of a context (no passage of the paper stands behind it: it is a property of this GPU's cache
- * hierarchy).  Embedding matrices [N][S][p] of at least `bytes` bytes (default 1.5 GiB) with S a multiple of
- * 16 are walked state by state instead of node by node in the rounds of Eq. 1 that read them, which keeps
- * one state's rows in the last-level cache.  The two walks add a row's neighbours in different orders, so
- * the last bits of the results depend on which one is used; 0 forces the state-by-state walk.
+ * hierarchy).  Embedding matrices [N][S][p] of at least `bytes` bytes (default 1.5 GiB) with S > 1 are
+ * walked state by state instead of node by node (or row by row) in the rounds of Eq. 1 that read them, and
+ * for S not a multiple of 16 in the reversed rounds that read rows as well, which keeps one state's rows in
+ * the last-level cache.  The walks add their terms in different orders, so the last bits of the results
+ * depend on which one is used; 0 forces the state-by-state walk.
  */
 int32_t s2v_set_sliced_min_bytes(s2v_ctx *ctx, size_t bytes);
 

@@ -726,7 +726,7 @@ static int32_t embed_fwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
     const bool fuse_gsum = gsum && (S == 1 || S == 16) && G == 1 && T >= 2 && N > 0;
     const bool fuse_q = q_node && T >= 2 && N > 0 && round_fuses_qnode(S, T);
     float *hub_part = at<float>(ws, f.hub_part), *hub_sum = at<float>(ws, f.hub_sum);
-    const bool by_state = S % 16 == 0 && nsp * sizeof(float) >= ctx->sliced_min_bytes;
+    const bool by_state = S > 1 && nsp * sizeof(float) >= ctx->sliced_min_bytes;
     // one state and at most four segments per long row: no combine pass, the round kernel adds the segments
     HubTable htf = ht;
     htf.fold = (S == 1 && pr->n_segs != pr->n_hubs && pr->max_hub_segs <= 4) ? 1 : 0;
@@ -1099,7 +1099,8 @@ static int32_t embed_bwd_impl(s2v_ctx *ctx, const s2v_graph *g, const s2v_params
         {
             SpanGuard span(ctx, first ? S2V_PROFILE_BWD_ROUND_MASK : S2V_PROFILE_BWD_ROUND);
             S2V_TRY(launch_bwd_round(st, p, N, S, g->rowptr, row_end_of(g), g->colidx, wagg, dz_in, first ? sc.maskT : nullptr, sc, mu_prev,
-                                     dz_out, ninfo, params->theta2, dc_part, d2_part, ht, hub_sum, fuse_last ? &bf : nullptr));
+                                     dz_out, ninfo, params->theta2, dc_part, d2_part, ht, hub_sum, fuse_last ? &bf : nullptr,
+                                     nsp * sizeof(float) >= ctx->sliced_min_bytes));
         }
         if (first) {
             float *dc_fix = sc.dc_part + ((size_t)kBwdHeadGrid + (size_t)(T - 1) * kBwdRoundRows) * 3 * p;

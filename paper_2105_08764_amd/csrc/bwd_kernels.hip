@@ -320,7 +320,9 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
     const int32_t *__restrict__ glo, const int32_t *__restrict__ ghi, const float *__restrict__ mu_prev,
     float *__restrict__ dz_out, NodeInfo ni, const float *__restrict__ theta2,
     float *__restrict__ dc_part,
-    float *__restrict__ d2_part, HubTable ht, const float *__restrict__ hub_sum, FirstFuse ff) {
+    float *__restrict__ d2_part, HubTable ht, const float *__restrict__ hub_sum, FirstFuse ff, int by_state) {
+    // by_state (row mode only): tile row i is (node v0 + i, state st), the launch works through one state's rows
+    // at a time, as the forward rounds do for large matrices (the sums do not depend on the order of the tiles)
     using Ge = Geo<P>;
     constexpr int CB = Ge::CB, STRIDE = Ge::STRIDE;
     constexpr int TILE_F = kTileRows * STRIDE;
@@ -377,7 +379,10 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
     }
 
     const size_t row_stride = (size_t)S * P;
-    const int n_tiles = (n_vrows + kWgRows - 1) / kWgRows;
+    const bool sliced = !NODE && by_state != 0;
+    const int n_nodes = n_vrows / S;
+    const int tps = (n_nodes + kWgRows - 1) / kWgRows;   // tiles per state when sliced
+    const int n_tiles = sliced ? tps * S : (n_vrows + kWgRows - 1) / kWgRows;
     // Node mode: a tile is one node, and the row range and first column indices of the wave's NEXT tile
     // are fetched while the current one is worked on (rowptr -> colidx -> data is a chain of three
     // dependent trips to memory otherwise).
@@ -521,9 +526,16 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
     for (int t = blockIdx.x; t < n_tiles; t += gridDim.x, ++it) {
         // (every wave of the workgroup makes the same number of iterations: the barriers inside are safe)
         if (it > 0 && it % kBwdFlushTiles == 0) flush(n_flushed == 0);
-        const int r0 = t * kWgRows + wave * kTileRows;
-        const int r = r0 + jl;
-        const bool valid = r < n_vrows;
+        int r0 = t * kWgRows + wave * kTileRows, r_step = 1, n_here = n_vrows - r0;
+        if (sliced) {
+            const int st = t / tps;
+            const int v0 = (t - st * tps) * kWgRows + wave * kTileRows;
+            r0 = v0 * S + st;
+            r_step = S;
+            n_here = n_nodes - v0;
+        }
+        const int r = r0 + jl * r_step;
+        const bool valid = jl < n_here;
         const int v = valid ? r / S : 0;
         const int s = valid ? r - v * S : 0;
         const int rb = NODE ? pf_b : (valid ? rowptr[v] : 0);
@@ -562,11 +574,11 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
         float mp[CB][4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int ro = r0 + 4 * gl + k;
+            const int ro = r0 + (4 * gl + k) * r_step;
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
                 if (PFM) mp[cb][k] = mpn[PFM ? cb : 0][k];
-                else mp[cb][k] = ro < n_vrows ? mu_prev[(size_t)ro * P + 16 * cb + jl] : 0.f;
+                else mp[cb][k] = 4 * gl + k < n_here ? mu_prev[(size_t)ro * P + 16 * cb + jl] : 0.f;
             }
         }
         if (PFM) {
@@ -672,8 +684,8 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
         for (int rr = 0; rr < 4; ++rr) {
             const int i = 4 * gl + rr;
             const float xi = __shfl(xs, i), spi = __shfl(sp, i), sni = __shfl(sn, i);
-            const int ro = r0 + i;
-            if (ro < n_vrows) {
+            const int ro = r0 + i * r_step;
+            if (i < n_here) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
                     const float d = mp[cb][rr] > 0.f ? acc[cb][rr] : 0.f;
@@ -807,8 +819,9 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
                             const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out, const NodeInfo &ni, const float *theta2,
                             float *dc_part, float *d2_part, const HubTable &ht, const float *hub_sum,
-                            const BwdFuse *fuse) {
+                            const BwdFuse *fuse, bool by_state) {
     const long n_vrows = (long)N * S;
+    const int bs = (by_state && S % 16 != 0 && S > 1 && !maskT) ? 1 : 0;
     const bool node = (S % 16) == 0, mask = maskT != nullptr;
     const bool do_fuse = fuse != nullptr && node && !mask;
     const bool neg = do_fuse && fuse->has_neg;
@@ -818,7 +831,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
     k_bwd_round<PP, NODE, MASK, WW, FF, NN><<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, \
                                                                            dz_in, maskT, sc.dg, sc.glo, sc.ghi, mu_prev,  \
                                                                            dz_out, ni, theta2, dc_part, d2_part, ht,       \
-                                                                           hub_sum, ff)
+                                                                           hub_sum, ff, bs)
 #define S2V_LAUNCH_BWD_W(PP, NODE, MASK, WW)                                                   \
     do {                                                                                       \
         if (NODE && !MASK && do_fuse) {                                                        \
@@ -827,7 +840,7 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
                 k_bwd_round<PP, NODE, MASK, WW, (NODE && !MASK), false, (NODE && !MASK)>           \
                     <<<kBwdGrid, kThreads, 0, st>>>((int)n_vrows, S, rowptr, rowend, colidx, wagg, dz_in, maskT, sc.dg,   \
                                                     sc.glo, sc.ghi, mu_prev, dz_out, ni, theta2, dc_part, d2_part, ht,    \
-                                                    hub_sum, ff);                                                         \
+                                                    hub_sum, ff, bs);                                                     \
             else S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, (NODE && !MASK), false);                 \
         } else S2V_LAUNCH_BWD_F(PP, NODE, MASK, WW, false, false);                             \
     } while (0)

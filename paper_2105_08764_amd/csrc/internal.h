@@ -289,7 +289,8 @@ hipError_t launch_bwd_round(hipStream_t st, int p, int N, int S, const int32_t *
                             const unsigned long long *maskT, const BwdScratch &sc,
                             const float *mu_prev, float *dz_out /*may be NULL*/, const NodeInfo &ni, const float *theta2,
                             float *dc_part /*[kBwdRoundRows][3][p]*/, float *d2_part /*[kBwdRoundRows][p][p]*/,
-                            const HubTable &ht, const float *hub_sum, const BwdFuse *fuse /*may be NULL*/);
+                            const HubTable &ht, const float *hub_sum, const BwdFuse *fuse /*may be NULL*/,
+                            bool by_state = false /*row mode, rows in memory: walk the rows state by state*/);
 // The last reversed round (t = 2) from the scalars: node mode (S a multiple of 16) and T >= 3 only.
 hipError_t launch_bwd_first(hipStream_t st, int p, int N, int S, const int32_t *rowptr, const int32_t *rowend,
                             const int32_t *colidx, const float *wagg, const float *dz_in /*dz^2 [N][S][p]*/,

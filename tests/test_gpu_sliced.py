@@ -1,5 +1,6 @@
 """The state-by-state row order of the embedding rounds (chosen by size; forced here through
-s2v_set_sliced_min_bytes) against the oracle and against the node-by-node order."""
+s2v_set_sliced_min_bytes) against the oracle and against the node-by-node order, for minibatch sizes that are
+multiples of 16 (where it replaces the 16-state tiles) and for others (where it replaces the memory order)."""
 import numpy as np
 import pytest
 
@@ -12,7 +13,8 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-4
 
 
-@pytest.mark.parametrize("kind,p,T,S", [("er", 64, 4, 16), ("ba", 32, 3, 32), ("batch", 64, 5, 16), ("hub", 64, 4, 16)])
+@pytest.mark.parametrize("kind,p,T,S", [("er", 64, 4, 16), ("ba", 32, 3, 32), ("batch", 64, 5, 16), ("hub", 64, 4, 16),
+                                        ("er", 64, 4, 3), ("ba", 32, 4, 8), ("hub", 64, 3, 24), ("batch", 32, 4, 17)])
 def test_sliced_forward_matches_oracle(oracle_mod, kind, p, T, S):
     print(f"case sliced forward kind={kind} p={p} T={T} S={S}", flush=True)
     if kind == "hub":
@@ -33,8 +35,9 @@ def test_sliced_forward_matches_oracle(oracle_mod, kind, p, T, S):
     assert np.array_equal(out["saved"][T - 1], out["mu"])
 
 
-def test_sliced_training_matches_oracle_and_single_call(oracle_mod):
-    kind, p, T, S = "ba", 64, 4, 16
+@pytest.mark.parametrize("S", [16, 3])
+def test_sliced_training_matches_oracle_and_single_call(oracle_mod, S):
+    kind, p, T = "ba", 64, 4
     g, x, action, target = tc.inputs(kind, S)
     theta = si.thetas(p, tc.stored_seeds()[(kind, p, T, S)], tc.theta_scale(kind))
     dev = gu.Device(g, p, T, S=S, training=True)
