@@ -635,6 +635,26 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
                 }
             }
             store_node_block<P>(tile_g, ga, lane);
+        } else if constexpr (MASK) {
+            // row mode of the mask round: the long rows' sums are ready; the others by one lane per stored entry
+            if (__builtin_amdgcn_ballot_w64(re - rb > kHubDegree) != 0ull) {
+#pragma unroll 1
+                for (int i = 0; i < kTileRows; ++i) {
+                    if (__builtin_amdgcn_readlane(re, i) - __builtin_amdgcn_readlane(rb, i) <= kHubDegree) continue;
+                    const int si = __builtin_amdgcn_readlane(s, i);
+                    const int h = hub_index(ht, __builtin_amdgcn_readlane(v, i));
+                    const bool ing = __builtin_amdgcn_readlane((int)in_graph, i) != 0;
+                    float4 a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
+                    const float4 d = dg_at(si, 4 * li);
+                    a.x = ing ? a.x * d.x : 0.f;
+                    a.y = ing ? a.y * d.y : 0.f;
+                    a.z = ing ? a.z * d.z : 0.f;
+                    a.w = ing ? a.w * d.w : 0.f;
+                    if (lane < Ge::LPR) st4(tile_g + i * STRIDE + 4 * lane, a);
+                }
+            }
+            auto dg_col = [&](int st, int col) { return dg_lds ? s_dg[MASK ? st * P + col : 0] : dg[(size_t)st * P + col]; };
+            gather_tile_bits_rows<P, W>(tile_g, maskT, S, s, in_graph, dg_col, colidx, wagg, rb, re, kHubDegree, lane);
         } else {
             int b_next = __builtin_amdgcn_readlane(rb, 0), e_next = __builtin_amdgcn_readlane(re, 0);
             int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;

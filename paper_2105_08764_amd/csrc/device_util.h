@@ -1182,6 +1182,75 @@ __device__ __forceinline__ void gather_tile_mu1_grad_rows(float *tile_a, const f
     }
 }
 
+// Row mode of the mask-word gather for a whole tile, one LANE per stored entry (as gather_tile_mu1_grad_rows):
+// for each of the 16 rows (v_i, s_i), per column j = lane % P, the number of neighbours u whose relu-mask
+// word (u, s_i) has bit j set (W: the sum of their edge weights), times scale_i[j] when the row is inside its
+// state's graph (lane i (mod 16) holds in_graph for tile row i) and zero otherwise; written to tile[i][j].
+// scale(s, j): the per-state factor.  Rows longer than max_len are left to the caller.
+template <int P, bool W, class Scale>
+__device__ __forceinline__ void gather_tile_bits_rows(float *tile, const unsigned long long *__restrict__ mask, int S,
+                                                      int s, bool in_graph, const Scale &scale,
+                                                      const int *__restrict__ colidx, const float *__restrict__ wagg,
+                                                      int rb, int re, int max_len, int lane) {
+    constexpr int STRIDE = Geo<P>::STRIDE;
+    const int j = lane % P;
+    const bool hi_half = j >= 32;
+    const int sh = j & 31;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        float cnt[8];
+        int nlev = 0;   // chunk levels of the longest row of this half that is gathered here (wave-uniform)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            cnt[k] = 0.f;
+            const int n = __builtin_amdgcn_readlane(re, 8 * half + k) - __builtin_amdgcn_readlane(rb, 8 * half + k);
+            if (n <= max_len) nlev = max(nlev, (n + 63) >> 6);
+        }
+#pragma unroll 1
+        for (int lev = 0; lev < nlev; ++lev) {
+            int cols[8];
+            float wl[W ? 8 : 1];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int b = __builtin_amdgcn_readlane(rb, 8 * half + k), n = __builtin_amdgcn_readlane(re, 8 * half + k) - b;
+                const int i = 64 * lev + lane;
+                const bool ok = n <= max_len && i < n;
+                cols[k] = ok ? colidx[b + i] : -1;
+                if (W) wl[W ? k : 0] = ok ? wagg[b + i] : 0.f;
+            }
+            unsigned lo[8], hi[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int sk = __builtin_amdgcn_readlane(s, 8 * half + k);
+                const unsigned long long wd = cols[k] >= 0 ? mask[(size_t)cols[k] * S + sk] : 0ull;
+                lo[k] = (unsigned)wd;
+                hi[k] = (unsigned)(wd >> 32);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                unsigned long long todo = __ballot((lo[k] | hi[k]) != 0u);
+                while (todo != 0ull) {
+                    const int l = __ffsll((long long)todo) - 1;
+                    todo &= todo - 1ull;
+                    const unsigned wlo = (unsigned)__builtin_amdgcn_readlane((int)lo[k], l);
+                    const unsigned whi = (unsigned)__builtin_amdgcn_readlane((int)hi[k], l);
+                    const unsigned bit = ((hi_half ? whi : wlo) >> sh) & 1u;
+                    if (W) cnt[k] = fmaf((float)bit, readlane_f(wl[W ? k : 0], l), cnt[k]);
+                    else cnt[k] += (float)bit;
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = 8 * half + k;
+            if (__builtin_amdgcn_readlane(re, i) - __builtin_amdgcn_readlane(rb, i) > max_len) continue;   // wave-uniform
+            const bool ing = __builtin_amdgcn_readlane((int)in_graph, i) != 0;
+            const int si = __builtin_amdgcn_readlane(s, i);
+            if (lane < P) tile[i * STRIDE + lane] = ing ? cnt[k] * scale(si, j) : 0.f;
+        }
+    }
+}
+
 // Weighted form of gather_node_block_bits: per column, the sum of the weights of the neighbours whose
 // entry is positive (per-chunk accumulators folded into a running total, as in the other gathers).
 template <int P>
