@@ -656,38 +656,37 @@ __global__ __launch_bounds__(kThreads, (NODE && MASK) ? S2V_BWD_MASK_OCC : 2) vo
             auto dg_col = [&](int st, int col) { return dg_lds ? s_dg[MASK ? st * P + col : 0] : dg[(size_t)st * P + col]; };
             gather_tile_bits_rows<P, W>(tile_g, maskT, S, s, in_graph, dg_col, colidx, wagg, rb, re, kHubDegree, lane);
         } else {
-            int b_next = __builtin_amdgcn_readlane(rb, 0), e_next = __builtin_amdgcn_readlane(re, 0);
-            int cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+            // row mode, rows of dz^t in memory: the rows two at a time; two short rows share one trip to memory
+            auto first_cols = [&](int b, int e) {
+                return (e - b <= kHubDegree && lane < min(64, e - b)) ? colidx[b + lane] : 0;
+            };
+            int nb0 = __builtin_amdgcn_readlane(rb, 0), ne0 = __builtin_amdgcn_readlane(re, 0);
+            int nb1 = __builtin_amdgcn_readlane(rb, 1), ne1 = __builtin_amdgcn_readlane(re, 1);
+            int nc0 = first_cols(nb0, ne0), nc1 = first_cols(nb1, ne1);
 #pragma unroll 1
-            for (int i = 0; i < kTileRows; ++i) {
-                const int b = b_next, e = e_next;
-                const int cols = cols_next;
-                const int si = __builtin_amdgcn_readlane(s, i);   // (i is wave-uniform)
-                if (i + 1 < kTileRows) {
-                    b_next = __builtin_amdgcn_readlane(rb, i + 1);
-                    e_next = __builtin_amdgcn_readlane(re, i + 1);
-                    cols_next = (lane < min(64, e_next - b_next)) ? colidx[b_next + lane] : 0;
+            for (int i = 0; i < kTileRows; i += 2) {
+                const int b0 = nb0, e0 = ne0, c0 = nc0, b1 = nb1, e1 = ne1, c1 = nc1;
+                if (i + 2 < kTileRows) {
+                    nb0 = __builtin_amdgcn_readlane(rb, i + 2); ne0 = __builtin_amdgcn_readlane(re, i + 2);
+                    nb1 = __builtin_amdgcn_readlane(rb, i + 3); ne1 = __builtin_amdgcn_readlane(re, i + 3);
+                    nc0 = first_cols(nb0, ne0);
+                    nc1 = first_cols(nb1, ne1);
                 }
-                float4 a;
-                if (e - b > kHubDegree) {
-                    const int h = hub_index(ht, __builtin_amdgcn_readlane(v, i));
-                    a = ld4(hub_sum + ((size_t)h * S + si) * P + 4 * li);
-                } else if (MASK) {
-                    const BitsRow bits{maskT, S, si, 4 * li};
-                    a = gather_row_sum<P, W>(bits, colidx, wagg, b, e, cols, lane);
+                const int s0 = __builtin_amdgcn_readlane(s, i), s1 = __builtin_amdgcn_readlane(s, i + 1);
+                const MemRow mem0{dz_in, row_stride, (size_t)s0 * P + 4 * li}, mem1{dz_in, row_stride, (size_t)s1 * P + 4 * li};
+                float4 a0, a1;
+                if (e0 - b0 <= 4 * Ge::NPL && e1 - b1 <= 4 * Ge::NPL) {
+                    gather_row_sum_pair<P, W>(mem0, mem1, wagg, b0, e0, c0, b1, e1, c1, lane, a0, a1);
                 } else {
-                    const MemRow mem{dz_in, row_stride, (size_t)si * P + 4 * li};
-                    a = gather_row_sum<P, W>(mem, colidx, wagg, b, e, cols, lane);
+                    if (e0 - b0 > kHubDegree) a0 = ld4(hub_sum + ((size_t)hub_index(ht, __builtin_amdgcn_readlane(v, i)) * S + s0) * P + 4 * li);
+                    else a0 = gather_row_sum<P, W>(mem0, colidx, wagg, b0, e0, c0, lane);
+                    if (e1 - b1 > kHubDegree) a1 = ld4(hub_sum + ((size_t)hub_index(ht, __builtin_amdgcn_readlane(v, i + 1)) * S + s1) * P + 4 * li);
+                    else a1 = gather_row_sum<P, W>(mem1, colidx, wagg, b1, e1, c1, lane);
                 }
-                if (MASK) {
-                    const bool ing = __builtin_amdgcn_readlane((int)in_graph, i) != 0;
-                    const float4 d = dg_at(si, 4 * li);
-                    a.x = ing ? a.x * d.x : 0.f;
-                    a.y = ing ? a.y * d.y : 0.f;
-                    a.z = ing ? a.z * d.z : 0.f;
-                    a.w = ing ? a.w * d.w : 0.f;
+                if (lane < Ge::LPR) {
+                    st4(tile_g + i * STRIDE + 4 * lane, a0);
+                    st4(tile_g + (i + 1) * STRIDE + 4 * lane, a1);
                 }
-                if (lane < Ge::LPR) st4(tile_g + i * STRIDE + 4 * lane, a);
             }
         }
         __builtin_amdgcn_wave_barrier();

@@ -175,6 +175,51 @@ __device__ __forceinline__ float4 gather_row_sum(const Loader &row, const int *_
     return a0;
 }
 
+// Two short rows at once (each of at most 4 * NPL stored entries, possibly none): the loads of both rows are in
+// flight together, so the pair costs one trip to memory instead of two.  Each row's terms are added exactly as
+// gather_row_sum adds them for such a row: the same bits.  cols0 / cols1: colidx[b + lane] of the rows.
+template <int P, bool W = false, class Loader>
+__device__ __forceinline__ void gather_row_sum_pair(const Loader &row0, const Loader &row1,
+                                                    const float *__restrict__ wagg, int b0, int e0, int cols0, int b1,
+                                                    int e1, int cols1, int lane, float4 &out0, float4 &out1) {
+    constexpr int NPL = Geo<P>::NPL, LPR = Geo<P>::LPR;
+    const int gq = lane / LPR;
+    const int cnt0 = e0 - b0, cnt1 = e1 - b1;
+    float wv0 = 0.f, wv1 = 0.f;
+    if (W) {
+        wv0 = (lane < cnt0) ? wagg[b0 + lane] : 0.f;
+        wv1 = (lane < cnt1) ? wagg[b1 + lane] : 0.f;
+    }
+    const int last0 = max(cnt0 - 1, 0), last1 = max(cnt1 - 1, 0);   // (an empty row re-reads a valid row: dropped below)
+    int sl[4];
+    float4 v0[4], v1[4];
+    float wk0[4], wk1[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        sl[k] = gq + k * NPL;
+        v0[k] = row0(__shfl(cols0, min(sl[k], last0)));
+        v1[k] = row1(__shfl(cols1, min(sl[k], last1)));
+        wk0[k] = W ? __shfl(wv0, min(sl[k], last0)) : 1.f;
+        wk1[k] = W ? __shfl(wv1, min(sl[k], last1)) : 1.f;
+    }
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 a[4], c[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        a[k] = sl[k] < cnt0 ? acc4<W>(zero, v0[k], wk0[k]) : zero;
+        c[k] = sl[k] < cnt1 ? acc4<W>(zero, v1[k], wk1[k]) : zero;
+    }
+    float4 t0 = cnt0 > 0 ? add4(zero, add4(add4(a[0], a[1]), add4(a[2], a[3]))) : zero;
+    float4 t1 = cnt1 > 0 ? add4(zero, add4(add4(c[0], c[1]), add4(c[2], c[3]))) : zero;
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) {
+        t0.x += __shfl_xor(t0.x, m); t0.y += __shfl_xor(t0.y, m); t0.z += __shfl_xor(t0.z, m); t0.w += __shfl_xor(t0.w, m);
+        t1.x += __shfl_xor(t1.x, m); t1.y += __shfl_xor(t1.y, m); t1.z += __shfl_xor(t1.z, m); t1.w += __shfl_xor(t1.w, m);
+    }
+    out0 = t0;
+    out1 = t1;
+}
+
 // The round-2 neighbour sum for S = 1 (records {x, s+, s-, pad}, see Mu1RowSingle), with the cheap
 // case split off: for a neighbour with x = 0 and s- = 0 the recomputed row is
 // relu(s+ q+) = s+ relu(q+) (s+ >= 0), i.e. linear in one scalar, so such neighbours only add
