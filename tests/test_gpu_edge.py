@@ -37,6 +37,14 @@ def test_error_codes():
     with pytest.raises(s2v.S2VError) as e:
         ctx.s2v_embed_fwd(graph, bad, x, 3, 1, mu, None, gsum, ws)
     assert _status(e) == s2v.S2V_ERR_UNSUPPORTED
+    # more than 2^31 - 1 rows (nodes times states): refused before anything is touched
+    S_big = (1 << 31) // g.n + 1
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_embed_fwd(graph, prm, x, 3, S_big, mu, None, gsum, ws)
+    assert _status(e) == s2v.S2V_ERR_UNSUPPORTED
+    with pytest.raises(s2v.S2VError) as e:
+        ctx.s2v_policy_eval(graph, prm, x, 3, S_big, mu, gsum, q, ws)
+    assert _status(e) == s2v.S2V_ERR_UNSUPPORTED
     # T < 1, S < 1
     for T, S in ((0, 1), (3, 0)):
         with pytest.raises(s2v.S2VError) as e:
